@@ -1,0 +1,223 @@
+/*
+ * icq_oracle.c -- TEST INFRASTRUCTURE, not part of the product.
+ *
+ * A plain, slow, double-precision CPU statement of what the ICQ query-time
+ * path computes (arxiv 1912.08756): the per-query table of squared
+ * query-to-codeword distances, the crude sum over the fast codebooks
+ * (left side of Eq. 2), the threshold filter, the full K-term sum (left side
+ * of Eq. 1) for the survivors, and the nearest-neighbour list (Sec. 3.4).
+ *
+ * The method reaches a result that has a plain definition (sum table entries,
+ * filter, select), so every function below is that definition written out with
+ * no blocking, fusion or reordering.  Nothing here is shared with the GPU
+ * library: no headers, no helpers, no tables.  Only tests, the smoke check
+ * and the benchmark's cpu_baseline leg may call it.
+ *
+ * Pins (tests/test_oracle_pins.py): the composite-quantization distance
+ * identity on constant-inner-product codebooks, infinite threshold ==
+ * exhaustive ADC, brute-force k-NN over reconstructions on tiny inputs, the
+ * product-quantization special case, filter/select commutation, the
+ * lossless-pruning invariant on codebooks with the ICQ zero pattern, Kf == K,
+ * padding, and a hand-worked micro example.  No function here is unpinned.
+ *
+ * Conventions: codebooks [K][m][d] float; codes [K][N] uint8, codebook-major,
+ * rows 0..Kf-1 are the fast codebooks; T [Q][K][m] double; ids are uint32;
+ * an empty result slot is (0xFFFFFFFF, +inf).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+    double dist;
+    uint32_t id;
+} pair_t;
+
+/* Order of the nearest-neighbour list: ascending distance, ties by ascending
+ * id (the paper is silent on ties; Sec. 3.4 only keeps "the nearest"). */
+static int pair_cmp(const void *a, const void *b)
+{
+    const pair_t *x = (const pair_t *)a, *y = (const pair_t *)b;
+    if (x->dist < y->dist) return -1;
+    if (x->dist > y->dist) return 1;
+    if (x->id < y->id) return -1;
+    if (x->id > y->id) return 1;
+    return 0;
+}
+
+/* Table precompute (Sec. 1, paragraph after Eq. 1; the norm is squared as in
+ * Eq. 1 and Eq. 2):  T[q][k][j] = sum_e (q_e - c_{k,j,e})^2, direct form. */
+void icq_oracle_lut(const float *codebooks, int K, int m, int d,
+                    const float *queries, int Q, double *T)
+{
+#pragma omp parallel for schedule(static)
+    for (int q = 0; q < Q; ++q) {
+        const float *qv = queries + (size_t)q * d;
+        for (int k = 0; k < K; ++k) {
+            for (int j = 0; j < m; ++j) {
+                const float *c = codebooks + ((size_t)k * m + j) * d;
+                double s = 0.0;
+                for (int e = 0; e < d; ++e) {
+                    double diff = (double)qv[e] - (double)c[e];
+                    s += diff * diff;
+                }
+                T[((size_t)q * K + k) * m + j] = s;
+            }
+        }
+    }
+}
+
+/* Crude distance (left side of Eq. 2): P[q][i] = sum_{k in fast set} T[q][k][code_k(i)],
+ * fast set = codebooks 0..Kf-1, k ascending. */
+void icq_oracle_partial(const double *T, int K, int m, const uint8_t *codes,
+                        int64_t N, int Kf, int Q, double *P)
+{
+#pragma omp parallel for schedule(static)
+    for (int q = 0; q < Q; ++q) {
+        const double *Tq = T + (size_t)q * K * m;
+        for (int64_t i = 0; i < N; ++i) {
+            double s = 0.0;
+            for (int k = 0; k < Kf; ++k)
+                s += Tq[(size_t)k * m + codes[(size_t)k * N + i]];
+            P[(size_t)q * N + i] = s;
+        }
+    }
+}
+
+/* Two-step search (Sec. 1 after Eq. 2, Sec. 3.4) with a static per-query
+ * threshold in place of the running "furthest list element + sigma":
+ *   survivor  <=>  P[q][i] < t_q            (strict, as in Eq. 2)
+ *   D[q][i]   =    P[q][i] + sum_{k=Kf..K-1} T[q][k][code_k(i)]   (Eq. 1, left side)
+ *   result    =    the topk smallest (D, id) among survivors, ascending,
+ *                  padded with (0xFFFFFFFF, +inf).
+ * out_count[q] = number of survivors.  P_out / D_out (each [Q][N], may be
+ * NULL) receive every item's crude distance and the survivors' full distance
+ * (NaN for pruned items). */
+void icq_oracle_search(const double *T, int K, int m, const uint8_t *codes,
+                       int64_t N, int Kf, int Q, const float *thresholds,
+                       int topk, uint32_t *out_ids, double *out_dist,
+                       int64_t *out_count, double *P_out, double *D_out)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int q = 0; q < Q; ++q) {
+        const double *Tq = T + (size_t)q * K * m;
+        const double t = (double)thresholds[q];
+        pair_t *surv = (pair_t *)malloc(sizeof(pair_t) * (size_t)(N > 0 ? N : 1));
+        int64_t ns = 0;
+        for (int64_t i = 0; i < N; ++i) {
+            double p = 0.0;
+            for (int k = 0; k < Kf; ++k)
+                p += Tq[(size_t)k * m + codes[(size_t)k * N + i]];
+            if (P_out) P_out[(size_t)q * N + i] = p;
+            if (D_out) D_out[(size_t)q * N + i] = NAN;
+            if (p < t) {
+                double dfull = p;
+                for (int k = Kf; k < K; ++k)
+                    dfull += Tq[(size_t)k * m + codes[(size_t)k * N + i]];
+                if (D_out) D_out[(size_t)q * N + i] = dfull;
+                surv[ns].dist = dfull;
+                surv[ns].id = (uint32_t)i;
+                ++ns;
+            }
+        }
+        qsort(surv, (size_t)ns, sizeof(pair_t), pair_cmp);
+        for (int r = 0; r < topk; ++r) {
+            if (r < ns) {
+                out_ids[(size_t)q * topk + r] = surv[r].id;
+                out_dist[(size_t)q * topk + r] = surv[r].dist;
+            } else {
+                out_ids[(size_t)q * topk + r] = 0xFFFFFFFFu;
+                out_dist[(size_t)q * topk + r] = INFINITY;
+            }
+        }
+        out_count[q] = ns;
+        free(surv);
+    }
+}
+
+/* One-step exhaustive ADC (the conventional search of Sec. 3.4, first
+ * paragraph): every item gets all K table terms in a single loop and the
+ * whole list is sorted.  Written separately from icq_oracle_search on
+ * purpose; D_all ([Q][N], may be NULL) receives every distance. */
+void icq_oracle_adc_exhaustive(const double *T, int K, int m,
+                               const uint8_t *codes, int64_t N, int Q, int topk,
+                               uint32_t *out_ids, double *out_dist, double *D_all)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int q = 0; q < Q; ++q) {
+        pair_t *all = (pair_t *)malloc(sizeof(pair_t) * (size_t)(N > 0 ? N : 1));
+        for (int64_t i = 0; i < N; ++i) {
+            double s = 0.0;
+            for (int k = 0; k < K; ++k) {
+                int code = codes[(size_t)k * N + i];
+                s += T[((size_t)q * K + k) * m + code];
+            }
+            all[i].dist = s;
+            all[i].id = (uint32_t)i;
+            if (D_all) D_all[(size_t)q * N + i] = s;
+        }
+        qsort(all, (size_t)N, sizeof(pair_t), pair_cmp);
+        for (int r = 0; r < topk; ++r) {
+            int has = r < N;
+            out_ids[(size_t)q * topk + r] = has ? all[r].id : 0xFFFFFFFFu;
+            out_dist[(size_t)q * topk + r] = has ? all[r].dist : INFINITY;
+        }
+        free(all);
+    }
+}
+
+/* Reconstruction (Sec. 1): xbar_i = sum_k c_{k, code_k(i)} for the listed items. */
+void icq_oracle_reconstruct(const float *codebooks, int K, int m, int d,
+                            const uint8_t *codes, int64_t N, const int64_t *items,
+                            int64_t n_items, double *xbar)
+{
+    for (int64_t r = 0; r < n_items; ++r) {
+        int64_t i = items[r];
+        double *x = xbar + (size_t)r * d;
+        for (int e = 0; e < d; ++e) x[e] = 0.0;
+        for (int k = 0; k < K; ++k) {
+            const float *c = codebooks + ((size_t)k * m + codes[(size_t)k * N + i]) * d;
+            for (int e = 0; e < d; ++e) x[e] += (double)c[e];
+        }
+    }
+}
+
+/* Exact k-NN over the reconstructions: ||q - xbar_i||^2 by brute force
+ * (right side of Eq. 1), sorted by (distance, id). */
+void icq_oracle_bruteforce_knn(const float *codebooks, int K, int m, int d,
+                               const uint8_t *codes, int64_t N, const float *queries,
+                               int Q, int topk, uint32_t *out_ids, double *out_dist)
+{
+    double *x = (double *)malloc(sizeof(double) * (size_t)d);
+    pair_t *all = (pair_t *)malloc(sizeof(pair_t) * (size_t)(N > 0 ? N : 1));
+    for (int q = 0; q < Q; ++q) {
+        const float *qv = queries + (size_t)q * d;
+        for (int64_t i = 0; i < N; ++i) {
+            icq_oracle_reconstruct(codebooks, K, m, d, codes, N, &i, 1, x);
+            double s = 0.0;
+            for (int e = 0; e < d; ++e) {
+                double diff = (double)qv[e] - x[e];
+                s += diff * diff;
+            }
+            all[i].dist = s;
+            all[i].id = (uint32_t)i;
+        }
+        qsort(all, (size_t)N, sizeof(pair_t), pair_cmp);
+        for (int r = 0; r < topk; ++r) {
+            int has = r < N;
+            out_ids[(size_t)q * topk + r] = has ? all[r].id : 0xFFFFFFFFu;
+            out_dist[(size_t)q * topk + r] = has ? all[r].dist : INFINITY;
+        }
+    }
+    free(all);
+    free(x);
+}
+
+/* Number of OpenMP threads a parallel region here would use (for reporting). */
+#ifdef _OPENMP
+#include <omp.h>
+int icq_oracle_threads(void) { return omp_get_max_threads(); }
+#else
+int icq_oracle_threads(void) { return 1; }
+#endif

@@ -1,0 +1,158 @@
+"""ctypes loader for the CPU oracle (oracle/icq_oracle.c).
+
+TEST INFRASTRUCTURE: only tests, the smoke check and the benchmark's
+cpu_baseline leg may import this module.  It shares nothing with the GPU
+library and never falls back to it.  Argument marshalling only; every number is
+computed by the C file, whose functions cite the passages of arxiv 1912.08756
+they follow.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "icq_oracle.c")
+_LIB = os.path.join(_HERE, "libicq_oracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc (-O2, OpenMP over queries)."""
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+        return _LIB
+    tmp = _LIB + ".tmp.%d" % os.getpid()
+    subprocess.check_call(
+        ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+         "-o", tmp, _SRC, "-lm"])
+    os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+            build(force=True)
+        lib = ctypes.CDLL(_LIB)
+        c_f = ctypes.POINTER(ctypes.c_float)
+        c_d = ctypes.POINTER(ctypes.c_double)
+        c_u8 = ctypes.POINTER(ctypes.c_uint8)
+        c_u32 = ctypes.POINTER(ctypes.c_uint32)
+        c_i64 = ctypes.POINTER(ctypes.c_int64)
+        i, i64 = ctypes.c_int, ctypes.c_int64
+        lib.icq_oracle_lut.argtypes = [c_f, i, i, i, c_f, i, c_d]
+        lib.icq_oracle_partial.argtypes = [c_d, i, i, c_u8, i64, i, i, c_d]
+        lib.icq_oracle_search.argtypes = [c_d, i, i, c_u8, i64, i, i, c_f, i, c_u32, c_d, c_i64, c_d, c_d]
+        lib.icq_oracle_adc_exhaustive.argtypes = [c_d, i, i, c_u8, i64, i, i, c_u32, c_d, c_d]
+        lib.icq_oracle_reconstruct.argtypes = [c_f, i, i, i, c_u8, i64, c_i64, i64, c_d]
+        lib.icq_oracle_bruteforce_knn.argtypes = [c_f, i, i, i, c_u8, i64, c_f, i, i, c_u32, c_d]
+        lib.icq_oracle_threads.restype = i
+        for name in ("lut", "partial", "search", "adc_exhaustive", "reconstruct", "bruteforce_knn"):
+            getattr(lib, "icq_oracle_" + name).restype = None
+        _lib = lib
+    return _lib
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None else None
+
+
+def _chk(a, dtype, shape):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    assert a.shape == tuple(shape), (a.shape, shape)
+    return a
+
+
+def threads():
+    return int(_load().icq_oracle_threads())
+
+
+def lut(codebooks, queries):
+    """T[q][k][j] = ||q - c_{k,j}||^2 in double.  codebooks [K][m][d], queries [Q][d]."""
+    K, m, d = codebooks.shape
+    cb = _chk(codebooks, np.float32, (K, m, d))
+    Q = queries.shape[0]
+    qs = _chk(queries, np.float32, (Q, d))
+    T = np.empty((Q, K, m), dtype=np.float64)
+    _load().icq_oracle_lut(_p(cb, ctypes.c_float), K, m, d, _p(qs, ctypes.c_float), Q, _p(T, ctypes.c_double))
+    return T
+
+
+def partial(T, codes, Kf):
+    """P[q][i] = crude distance over the first Kf codebooks.  codes [K][N] uint8."""
+    Q, K, m = T.shape
+    N = codes.shape[1]
+    T = _chk(T, np.float64, (Q, K, m))
+    cd = _chk(codes, np.uint8, (K, N))
+    P = np.empty((Q, N), dtype=np.float64)
+    _load().icq_oracle_partial(_p(T, ctypes.c_double), K, m, _p(cd, ctypes.c_uint8), N, Kf, Q, _p(P, ctypes.c_double))
+    return P
+
+
+def search(T, codes, Kf, thresholds, topk, want_all=False):
+    """Two-step search.  Returns (ids [Q][topk] u32, dist [Q][topk] f64, count [Q] i64)
+    and, with want_all, also (P [Q][N], D [Q][N] with NaN for pruned items)."""
+    Q, K, m = T.shape
+    N = codes.shape[1]
+    T = _chk(T, np.float64, (Q, K, m))
+    cd = _chk(codes, np.uint8, (K, N))
+    th = _chk(thresholds, np.float32, (Q,))
+    ids = np.empty((Q, topk), dtype=np.uint32)
+    dist = np.empty((Q, topk), dtype=np.float64)
+    cnt = np.empty((Q,), dtype=np.int64)
+    P = np.empty((Q, N), dtype=np.float64) if want_all else None
+    D = np.empty((Q, N), dtype=np.float64) if want_all else None
+    _load().icq_oracle_search(_p(T, ctypes.c_double), K, m, _p(cd, ctypes.c_uint8), N, Kf, Q,
+                              _p(th, ctypes.c_float), topk, _p(ids, ctypes.c_uint32),
+                              _p(dist, ctypes.c_double), _p(cnt, ctypes.c_int64),
+                              _p(P, ctypes.c_double), _p(D, ctypes.c_double))
+    if want_all:
+        return ids, dist, cnt, P, D
+    return ids, dist, cnt
+
+
+def adc_exhaustive(T, codes, topk, want_all=False):
+    """One-step exhaustive ADC top-k (and every distance with want_all)."""
+    Q, K, m = T.shape
+    N = codes.shape[1]
+    T = _chk(T, np.float64, (Q, K, m))
+    cd = _chk(codes, np.uint8, (K, N))
+    ids = np.empty((Q, topk), dtype=np.uint32)
+    dist = np.empty((Q, topk), dtype=np.float64)
+    D = np.empty((Q, N), dtype=np.float64) if want_all else None
+    _load().icq_oracle_adc_exhaustive(_p(T, ctypes.c_double), K, m, _p(cd, ctypes.c_uint8), N, Q, topk,
+                                      _p(ids, ctypes.c_uint32), _p(dist, ctypes.c_double), _p(D, ctypes.c_double))
+    if want_all:
+        return ids, dist, D
+    return ids, dist
+
+
+def reconstruct(codebooks, codes, items):
+    """xbar_i = sum_k c_{k,code_k(i)} for i in items, double [len(items)][d]."""
+    K, m, d = codebooks.shape
+    N = codes.shape[1]
+    cb = _chk(codebooks, np.float32, (K, m, d))
+    cd = _chk(codes, np.uint8, (K, N))
+    it = np.ascontiguousarray(items, dtype=np.int64)
+    x = np.empty((it.shape[0], d), dtype=np.float64)
+    _load().icq_oracle_reconstruct(_p(cb, ctypes.c_float), K, m, d, _p(cd, ctypes.c_uint8), N,
+                                   _p(it, ctypes.c_int64), it.shape[0], _p(x, ctypes.c_double))
+    return x
+
+
+def bruteforce_knn(codebooks, codes, queries, topk):
+    """Exact k-NN of each query among the reconstructions, by brute force."""
+    K, m, d = codebooks.shape
+    N = codes.shape[1]
+    Q = queries.shape[0]
+    cb = _chk(codebooks, np.float32, (K, m, d))
+    cd = _chk(codes, np.uint8, (K, N))
+    qs = _chk(queries, np.float32, (Q, d))
+    ids = np.empty((Q, topk), dtype=np.uint32)
+    dist = np.empty((Q, topk), dtype=np.float64)
+    _load().icq_oracle_bruteforce_knn(_p(cb, ctypes.c_float), K, m, d, _p(cd, ctypes.c_uint8), N,
+                                      _p(qs, ctypes.c_float), Q, topk, _p(ids, ctypes.c_uint32),
+                                      _p(dist, ctypes.c_double))
+    return ids, dist

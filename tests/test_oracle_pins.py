@@ -1,0 +1,305 @@
+"""Pins for the CPU oracle: each test checks oracle/icq_oracle.c against something
+the paper or the mathematics fixes, computed here in numpy by a different route
+(reconstruction and brute force, sub-vector PQ tables, closed-form constants,
+hand-worked values).  A dropped term, a wrong index, a transposed operand or a
+wrong comparison sign in the oracle fails at least one of them."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import icq_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.Philox(key=[seed, 77]))
+
+
+def disjoint_support_codebooks(g, K, m, d, scale=None):
+    """Codebooks with pairwise-disjoint, interleaved coordinate supports (the ICQ
+    zero pattern of Sec. 3.1 taken to its limit): inter-codebook inner products
+    are all zero, so the constant cross term eps is 0."""
+    perm = g.permutation(d)
+    groups = np.array_split(perm, K)
+    cb = np.zeros((K, m, d), dtype=np.float32)
+    for k in range(K):
+        s = 1.0 if scale is None else scale[k]
+        cb[k][:, groups[k]] = (s * g.standard_normal((m, len(groups[k])))).astype(np.float32)
+    return cb, groups
+
+
+def constant_eps_codebooks(g, K, m, d_block):
+    """c_{k,j} = u_{k,j} + a_k: u_{k,.} lives in coordinate block k, the offsets a_k
+    all live in one extra block.  Then c_k^T c_l = a_k^T a_l for k != l whatever
+    the codewords: eps = sum_{k != l} a_k^T a_l, a non-zero constant (the
+    composite-quantization constraint of Sec. 2)."""
+    d = (K + 1) * d_block
+    cb = np.zeros((K, m, d), dtype=np.float32)
+    a = g.standard_normal((K, d_block)).astype(np.float32)
+    for k in range(K):
+        cb[k][:, k * d_block:(k + 1) * d_block] = g.standard_normal((m, d_block)).astype(np.float32)
+        cb[k][:, K * d_block:] = a[k]
+    a64 = a.astype(np.float64)
+    gram = a64 @ a64.T
+    eps = gram.sum() - np.trace(gram)
+    return cb, eps
+
+
+def np_reconstruct(cb, codes):
+    K = cb.shape[0]
+    x = np.zeros((codes.shape[1], cb.shape[2]), dtype=np.float64)
+    for k in range(K):
+        x += cb[k].astype(np.float64)[codes[k]]
+    return x
+
+
+def np_knn(x, queries, topk):
+    out = []
+    for q in queries.astype(np.float64):
+        dist = ((q[None, :] - x) ** 2).sum(axis=1)
+        order = np.lexsort((np.arange(x.shape[0]), dist))[:topk]
+        out.append((order, dist[order]))
+    return out
+
+
+# ---------------------------------------------------------------- P8: worked values
+def _golden():
+    vals = {}
+    with open(os.path.join(GOLDEN, "micro_example.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            key, *rest = line.split()
+            vals[key] = np.array([float(r) for r in rest])
+    return vals
+
+
+def test_micro_example_matches_hand_worked_values():
+    gold = _golden()
+    cb = np.array([[[1, 0], [-1, 0]], [[0, 1], [0, -1]]], dtype=np.float32)
+    q = np.array([[0.5, 0.25]], dtype=np.float32)
+    codes = np.array([[0, 0, 1, 1, 0], [0, 1, 0, 1, 0]], dtype=np.uint8)
+    T = orc.lut(cb, q)
+    assert np.array_equal(T[0, 0], gold["T0"]) and np.array_equal(T[0, 1], gold["T1"])
+    P = orc.partial(T, codes, 1)
+    assert np.array_equal(P[0], gold["P"])
+    ids, dist, D = orc.adc_exhaustive(T, codes, 5, want_all=True)
+    assert np.array_equal(D[0], gold["D"])
+    t = np.array([1.0], dtype=np.float32)
+    ids, dist, cnt, P2, D2 = orc.search(T, codes, 1, t, 2, want_all=True)
+    assert cnt[0] == 3
+    assert np.array_equal(np.nonzero(~np.isnan(D2[0]))[0], gold["survivors"].astype(int))
+    assert np.array_equal(ids[0], gold["top2_ids"].astype(np.uint32))
+    assert np.array_equal(dist[0], gold["top2_dist"])
+    ids4, dist4, cnt4 = orc.search(T, codes, 1, t, 4)
+    assert ids4[0, 3] == 0xFFFFFFFF and np.isposinf(dist4[0, 3]) and ids4[0, 2] == 1
+    # strictness of "<": an item whose crude distance equals t is pruned
+    t_eq = np.array([0.3125], dtype=np.float32)
+    assert orc.search(T, codes, 1, t_eq, 2)[2][0] == 0
+    # identity on item 0: D - (K-1)||q||^2 + eps == ||q - xbar||^2
+    assert D[0, 0] - 0.3125 == gold["true_dist_item0"][0]
+    x = orc.reconstruct(cb, codes, [0])
+    assert np.array_equal(x[0], [1.0, 1.0])
+
+
+# ---------------------------------------------------------------- P1: CQ distance identity
+@pytest.mark.parametrize("kind", ["disjoint", "const_eps"])
+def test_cq_distance_identity(kind):
+    g = _rng(1)
+    K, m, N, Q = 5, 16, 400, 7
+    if kind == "disjoint":
+        cb, _ = disjoint_support_codebooks(g, K, m, 23)
+        eps = 0.0
+    else:
+        cb, eps = constant_eps_codebooks(g, K, m, 3)
+        assert abs(eps) > 1e-3
+    d = cb.shape[2]
+    codes = g.integers(0, m, size=(K, N), dtype=np.uint8)
+    queries = g.standard_normal((Q, d)).astype(np.float32)
+    T = orc.lut(cb, queries)
+    _, _, D = orc.adc_exhaustive(T, codes, 1, want_all=True)
+    x = np_reconstruct(cb, codes)
+    q64 = queries.astype(np.float64)
+    true = ((q64[:, None, :] - x[None, :, :]) ** 2).sum(axis=2)
+    qn = (q64 ** 2).sum(axis=1)[:, None]
+    lhs = D - (K - 1) * qn + eps
+    np.testing.assert_allclose(lhs, true, rtol=1e-12, atol=1e-12)
+    # the same identity through the two-step search with nothing pruned
+    inf = np.full(Q, np.inf, dtype=np.float32)
+    _, _, cnt, P, D2 = orc.search(T, codes, 2, inf, 3, want_all=True)
+    assert (cnt == N).all()
+    np.testing.assert_allclose(D2 - (K - 1) * qn + eps, true, rtol=1e-12, atol=1e-12)
+    # the oracle's own reconstruction agrees with numpy's
+    np.testing.assert_allclose(orc.reconstruct(cb, codes, np.arange(N)), x, rtol=0, atol=1e-15)
+
+
+# ---------------------------------------------------------------- P2: t = +inf == exhaustive ADC
+def test_infinite_threshold_equals_exhaustive_adc():
+    g = _rng(2)
+    K, m, d, N, Q, topk = 6, 256, 20, 3000, 9, 25
+    cb = g.standard_normal((K, m, d)).astype(np.float32)   # dense: no CQ property needed
+    codes = g.integers(0, m, size=(K, N), dtype=np.uint8)
+    queries = g.standard_normal((Q, d)).astype(np.float32)
+    T = orc.lut(cb, queries)
+    e_ids, e_dist = orc.adc_exhaustive(T, codes, topk)
+    inf = np.full(Q, np.inf, dtype=np.float32)
+    for Kf in (1, 2, 5, 6):
+        ids, dist, cnt = orc.search(T, codes, Kf, inf, topk)
+        assert np.array_equal(ids, e_ids)
+        # K-term sums in the same (ascending k) order: bit-identical
+        assert np.array_equal(dist, e_dist)
+        assert (cnt == N).all()
+
+
+# ---------------------------------------------------------------- P3: ADC top-k == brute-force k-NN
+def test_adc_topk_equals_bruteforce_knn_on_cq_codebooks():
+    g = _rng(3)
+    K, m, N, Q, topk = 4, 32, 1500, 6, 12
+    cb, _ = disjoint_support_codebooks(g, K, m, 16)
+    codes = g.integers(0, m, size=(K, N), dtype=np.uint8)
+    src = g.integers(0, N, size=Q)
+    x = np_reconstruct(cb, codes)
+    queries = (x[src] + 0.1 * g.standard_normal((Q, 16))).astype(np.float32)
+    T = orc.lut(cb, queries)
+    a_ids, a_dist = orc.adc_exhaustive(T, codes, topk)
+    b_ids, b_dist = orc.bruteforce_knn(cb, codes, queries, topk)
+    ref = np_knn(x, queries, topk)
+    qn = (queries.astype(np.float64) ** 2).sum(axis=1)
+    for q in range(Q):
+        assert np.array_equal(b_ids[q], ref[q][0])            # oracle brute force vs numpy brute force
+        np.testing.assert_allclose(b_dist[q], ref[q][1], rtol=1e-13)
+        assert np.array_equal(a_ids[q], b_ids[q])             # Eq. 1: table sums rank like true distances
+        np.testing.assert_allclose(a_dist[q] - (K - 1) * qn[q], b_dist[q], rtol=1e-11, atol=1e-11)
+        assert a_ids[q][0] == src[q] or a_dist[q][0] <= a_dist[q][1]
+
+
+# ---------------------------------------------------------------- P4: PQ special case
+def test_pq_special_case_matches_subvector_tables():
+    g = _rng(4)
+    K, m, d, Q = 4, 64, 24, 5
+    sub = d // K
+    cb = np.zeros((K, m, d), dtype=np.float32)
+    for k in range(K):
+        cb[k][:, k * sub:(k + 1) * sub] = g.standard_normal((m, sub)).astype(np.float32)
+    queries = g.standard_normal((Q, d)).astype(np.float32)
+    T = orc.lut(cb, queries)
+    q64 = queries.astype(np.float64)
+    for k in range(K):
+        blk = slice(k * sub, (k + 1) * sub)
+        # textbook PQ asymmetric table: sub-query against sub-codewords
+        t_pq = ((q64[:, None, blk] - cb[k][None, :, blk].astype(np.float64)) ** 2).sum(axis=2)
+        rest = (q64 ** 2).sum(axis=1) - (q64[:, blk] ** 2).sum(axis=1)
+        np.testing.assert_allclose(T[:, k, :], t_pq + rest[:, None], rtol=1e-13, atol=1e-13)
+    # and the K-table sum is the PQ-ADC distance plus the constant (K-1)||q||^2
+    N = 300
+    codes = g.integers(0, m, size=(K, N), dtype=np.uint8)
+    _, _, D = orc.adc_exhaustive(T, codes, 1, want_all=True)
+    x = np_reconstruct(cb, codes)
+    pq = ((q64[:, None, :] - x[None]) ** 2).sum(axis=2)
+    np.testing.assert_allclose(D, pq + (K - 1) * (q64 ** 2).sum(axis=1)[:, None], rtol=1e-12)
+
+
+# ---------------------------------------------------------------- P5: filter / select commute
+def test_filter_and_select_commute_and_survivors_are_monotone():
+    g = _rng(5)
+    K, Kf, m, d, N, Q, topk = 5, 2, 256, 12, 4000, 8, 15
+    cb = (g.standard_normal((K, m, d)) * (0.6 ** np.arange(K))[:, None, None]).astype(np.float32)
+    codes = g.integers(0, m, size=(K, N), dtype=np.uint8)
+    queries = g.standard_normal((Q, d)).astype(np.float32)
+    T = orc.lut(cb, queries)
+    P = orc.partial(T, codes, Kf)
+    _, _, D_all = orc.adc_exhaustive(T, codes, 1, want_all=True)
+    prev = None
+    for frac in (0.002, 0.01, 0.2):
+        n = int(np.ceil(frac * N))
+        t = np.partition(P, n - 1, axis=1)[:, n - 1].astype(np.float32)
+        ids, dist, cnt, P2, D2 = orc.search(T, codes, Kf, t, topk, want_all=True)
+        assert np.array_equal(P2, P)
+        for q in range(Q):
+            keep = np.nonzero(P[q] < np.float64(t[q]))[0]
+            assert cnt[q] == keep.size
+            order = keep[np.lexsort((keep, D_all[q][keep]))][:topk]
+            exp_ids = np.full(topk, 0xFFFFFFFF, dtype=np.uint32)
+            exp_ids[:order.size] = order
+            assert np.array_equal(ids[q], exp_ids)
+            assert np.array_equal(dist[q][:order.size], D_all[q][order])
+            assert np.array_equal(np.nonzero(~np.isnan(D2[q]))[0], keep)
+        surv = ~np.isnan(D2)
+        if prev is not None:
+            assert (prev <= surv).all()          # S(t1) subset of S(t2) for t1 < t2
+        prev = surv
+
+
+# ---------------------------------------------------------------- P6: lossless pruning on ICQ-structured codebooks
+def test_lossless_pruning_invariant_on_icq_structure():
+    g = _rng(6)
+    K, Kf, m, d, N, Q, topk = 6, 2, 64, 30, 2000, 10, 8
+    # all supports disjoint; the two fast codebooks carry most of the variance
+    cb, groups = disjoint_support_codebooks(g, K, m, d, scale=[2.0, 2.0, 0.3, 0.3, 0.3, 0.3])
+    psi = np.concatenate(groups[:Kf])
+    psibar = np.concatenate(groups[Kf:])
+    codes = g.integers(0, m, size=(K, N), dtype=np.uint8)
+    x = np_reconstruct(cb, codes)
+    src = g.integers(0, N, size=Q)
+    queries = (x[src] + 0.05 * g.standard_normal((Q, d))).astype(np.float32)
+    q64 = queries.astype(np.float64)
+    T = orc.lut(cb, queries)
+    P = orc.partial(T, codes, Kf)
+    # closed form: P - const_q is the exact distance inside the fast subspace
+    const = (Kf - 1) * (q64[:, psi] ** 2).sum(axis=1) + Kf * (q64[:, psibar] ** 2).sum(axis=1)
+    d_psi = ((q64[:, None, psi] - x[None][:, :, psi]) ** 2).sum(axis=2)
+    np.testing.assert_allclose(P - const[:, None], d_psi, rtol=1e-11, atol=1e-11)
+    ref = np_knn(x, queries, topk)
+    t = np.array([ref[q][1][topk - 1] * (1 + 1e-6) + const[q] + 1e-6 for q in range(Q)], dtype=np.float32)
+    ids, dist, cnt = orc.search(T, codes, Kf, t, topk)
+    assert (cnt < N // 2).all(), "threshold should really prune"
+    for q in range(Q):
+        assert np.array_equal(ids[q], ref[q][0]), "a true nearest neighbour was pruned"
+
+
+# ---------------------------------------------------------------- P7: degenerate settings
+def test_kf_equals_k_and_padding():
+    g = _rng(7)
+    K, m, d, N, Q = 3, 256, 8, 500, 4
+    cb = g.standard_normal((K, m, d)).astype(np.float32)
+    codes = g.integers(0, m, size=(K, N), dtype=np.uint8)
+    queries = g.standard_normal((Q, d)).astype(np.float32)
+    T = orc.lut(cb, queries)
+    P = orc.partial(T, codes, K)
+    t = np.partition(P, 4, axis=1)[:, 4].astype(np.float32)      # 5th smallest, rounded to fp32: 4 or 5 strictly below
+    ids, dist, cnt, P2, D2 = orc.search(T, codes, K, t, 10, want_all=True)
+    for q in range(Q):
+        keep = ~np.isnan(D2[q])
+        assert np.array_equal(D2[q][keep], P[q][keep])           # stage 2 adds nothing
+        n = int(cnt[q])
+        assert n in (4, 5) and (ids[q][n:] == 0xFFFFFFFF).all() and np.isposinf(dist[q][n:]).all()
+        assert (np.diff(dist[q][:n]) >= 0).all()
+    # empty database
+    e = np.zeros((K, 0), dtype=np.uint8)
+    ids, dist, cnt = orc.search(T, e, 1, t, 3)
+    assert (cnt == 0).all() and (ids == 0xFFFFFFFF).all()
+
+
+def test_tie_break_is_by_id():
+    cb = np.zeros((1, 2, 1), dtype=np.float32)
+    cb[0, 1, 0] = 1.0
+    q = np.array([[0.0]], dtype=np.float32)
+    codes = np.array([[1, 0, 0, 1, 0]], dtype=np.uint8)
+    T = orc.lut(cb, q)
+    ids, dist = orc.adc_exhaustive(T, codes, 5)
+    assert ids[0].tolist() == [1, 2, 4, 0, 3]
+    assert dist[0].tolist() == [0, 0, 0, 1, 1]
+
+
+def test_lut_against_expanded_form_at_benchmark_shape():
+    """||q-c||^2 == ||q||^2 - 2<q,c> + ||c||^2 (a different route, via a matmul)."""
+    g = _rng(8)
+    K, m, d, Q = 3, 256, 96, 5
+    cb = g.standard_normal((K, m, d)).astype(np.float32)
+    queries = g.standard_normal((Q, d)).astype(np.float32)
+    T = orc.lut(cb, queries)
+    q64, c64 = queries.astype(np.float64), cb.astype(np.float64).reshape(K * m, d)
+    ref = (q64 ** 2).sum(1)[:, None] - 2 * q64 @ c64.T + (c64 ** 2).sum(1)[None]
+    np.testing.assert_allclose(T.reshape(Q, K * m), ref, rtol=1e-12)
