@@ -1,0 +1,141 @@
+/*
+ * icq.h -- C ABI of the MI355X (gfx950) query-time path of Interleaved
+ * Composite Quantization (arxiv 1912.08756).
+ *
+ * Notation follows the paper: K codebooks ("quantizers") C_k of m codewords in
+ * R^d; every database item i is stored as K one-byte sub-codes code_k(i); the
+ * first Kf codebooks are the fast set (script-K of Sec. 1 / Eq. 8; the caller
+ * orders the codebooks so that the fast ones come first).  N items, Q queries.
+ *
+ * General rules
+ *  - Every pointer is a DEVICE pointer owned by the caller unless marked
+ *    "host".  The library never frees or keeps caller memory beyond a call,
+ *    except that an index keeps private device copies it allocates itself.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Every call only enqueues work on `stream` and returns; results are valid
+ *    once the stream has been synchronised.  Calls on one index from several
+ *    host threads are safe as long as they do not share output or workspace
+ *    buffers.
+ *  - Return value: ICQ_OK (0) or a negative ICQ_ERR_* code.  Arguments are
+ *    checked on the host before anything is launched; on error nothing has
+ *    been enqueued.
+ *  - Layouts are row-major with the last index contiguous.
+ *  - Candidate lists: cand_ids / cand_partial are [Q][cap]; list q holds
+ *    min(cand_count[q], cap) valid entries in UNSPECIFIED order (compare as
+ *    sets).  cand_count[q] is the true number of survivors even when it
+ *    exceeds cap; in that case which survivors were kept is unspecified and
+ *    the caller must retry with a larger cap.
+ *  - Results: out_ids / out_dist are [Q][topk], ascending by (distance, id);
+ *    when fewer than topk items survive, the tail is (0xFFFFFFFF, +inf).
+ *  - The distance returned is the table sum on the left of Eq. 1,
+ *    sum_k ||q - c_{k,code_k(i)}||^2, not corrected by the constant
+ *    -(K-1)||q||^2 + eps that relates it to ||q - xbar_i||^2.
+ */
+#ifndef ICQ_H
+#define ICQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ICQ_OK 0
+#define ICQ_ERR_ARG (-1)       /* null pointer, or K/m/d/Kf/N/Q/topk/cap out of range   */
+#define ICQ_ERR_WORKSPACE (-2) /* workspace missing, misaligned (256 B) or too small    */
+#define ICQ_ERR_HIP (-3)       /* a HIP runtime call failed (allocation, launch)        */
+#define ICQ_ERR_CAPACITY (-4)  /* reserved for synchronous helpers; async calls report
+                                  overflow through cand_count / out_survivors            */
+
+#define ICQ_MAX_K 64      /* codebooks                         */
+#define ICQ_MAX_M 256     /* codewords per codebook (one byte) */
+#define ICQ_MAX_TOPK 1024 /* result list length                */
+#define ICQ_MAX_N 0xFFF00000ll /* items per index (ids are 32-bit) */
+#define ICQ_MAX_Q (1 << 22) /* queries per call                  */
+#define ICQ_PAD_ID 0xFFFFFFFFu
+
+typedef struct icq_index icq_index;
+
+/* Human-readable text for an ICQ_* code (host pointer to a static string). */
+const char *icq_strerror(int code);
+
+/*
+ * Build a search index from codebooks and codes (Sec. 1: x_i is quantised to
+ * xbar_i = sum_k c_{k,code_k(i)}; the codes are the K codeword indices).
+ *   codebooks [K][m][d] fp32;  codes [K][N] uint8, codebook-major, every value < m;
+ *   1 <= Kf <= K <= ICQ_MAX_K, 1 <= m <= 256, d >= 1, 0 <= N <= ICQ_MAX_N.
+ * The index copies what it needs into private device arrays laid out for the
+ * kernels (fast sub-codes [Kf][N] padded and 16-byte aligned per row, slow
+ * sub-codes item-major [N][stride], codewords padded in d, codeword norms), so
+ * the caller may release `codebooks` and `codes` once `stream` has been
+ * synchronised.  Sub-codes >= m are not detected; tables are always 256
+ * entries wide with +inf beyond m, so such an item simply gets distance +inf.  *out is set only on success.
+ */
+int icq_index_create(icq_index **out /*host*/, const float *codebooks, const uint8_t *codes,
+                     int K, int m, int d, int Kf, int64_t N, void *stream);
+
+/* Free the index and its private device arrays (host call; the caller makes
+ * sure no enqueued work still uses it).  NULL is ignored. */
+void icq_index_destroy(icq_index *index);
+
+/* Write the index's private copy of the codes back in the input layout
+ * [K][N] (bit-exact round trip of the storage layout; a debugging aid). */
+int icq_index_export_codes(const icq_index *index, uint8_t *codes_out, void *stream);
+
+/* Bytes of 256-byte-aligned device workspace that icq_scan_fast, icq_refine
+ * and icq_search need for up to Q queries per call, candidate capacity `cap`
+ * per query and result length `topk`.  *out is a host pointer. */
+int icq_workspace_bytes(const icq_index *index, int Q, int64_t cap, int topk, size_t *out /*host*/);
+
+/*
+ * Lookup-table precompute (Sec. 1, text after Eq. 1: all ||q - c_{k,j}||^2 are
+ * computed once per query so that a distance costs K additions):
+ *   lut[q][k][j] = ||q||^2 - 2<q, c_{k,j}> + ||c_{k,j}||^2,   fp32, [Q][K][256]
+ * (rows are always 256 wide; entries j >= m are +inf).  queries [Q][d] fp32.
+ * The inner products run on the fp32 matrix cores.  Q >= 0.
+ */
+int icq_build_lut(const icq_index *index, const float *queries, int Q, float *lut, void *stream);
+
+/*
+ * Stage 1, crude comparison (Eq. 2 with a static per-query threshold in place
+ * of "furthest list element + sigma"): for every item
+ *   P[q][i] = sum_{k<Kf} lut[q][k][code_k(i)]   (k ascending, fp32)
+ * and item i survives for query q iff P[q][i] < thresholds[q] (strict; +inf
+ * keeps every item, NaN keeps none).  Survivors are appended to query q's
+ * candidate list as (cand_ids, cand_partial = P).  cand_count [Q] is written
+ * (not accumulated).  lut is [Q][K][256] as written by icq_build_lut.
+ * 0 <= Q, 1 <= cap, Q*cap < 2^40.  Needs icq_workspace_bytes(index, Q, cap, 1).
+ */
+int icq_scan_fast(const icq_index *index, const float *lut, int Q, const float *thresholds,
+                  uint32_t *cand_ids, float *cand_partial, uint32_t *cand_count, int64_t cap,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Stage 2, exact comparison for the survivors only (Eq. 1, left side) and the
+ * nearest-neighbour list (Sec. 3.4):
+ *   D[q][i] = cand_partial + sum_{k=Kf..K-1} lut[q][k][code_k(i)]   (k ascending, fp32)
+ * then the topk smallest (D, id) per query.  Reads min(cand_count[q], cap)
+ * entries of each list.  1 <= topk <= ICQ_MAX_TOPK.
+ */
+int icq_refine(const icq_index *index, const float *lut, int Q, const uint32_t *cand_ids,
+               const float *cand_partial, const uint32_t *cand_count, int64_t cap, int topk,
+               uint32_t *out_ids, float *out_dist, void *workspace, size_t workspace_bytes,
+               void *stream);
+
+/*
+ * The whole path for a batch of queries: table precompute, stage 1, stage 2,
+ * nearest-neighbour list.  queries [Q][d], thresholds [Q]; `cap` is the
+ * per-query candidate capacity carved out of the workspace (needs
+ * icq_workspace_bytes(index, Q, cap, topk)).  out_survivors [Q] (may be NULL)
+ * receives the true survivor count of each query; a value above cap means
+ * that query's list overflowed and its result may miss neighbours.
+ */
+int icq_search(const icq_index *index, const float *queries, int Q, const float *thresholds,
+               int64_t cap, int topk, uint32_t *out_ids, float *out_dist, uint32_t *out_survivors,
+               void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ICQ_H */

@@ -1,0 +1,161 @@
+"""ctypes binding of libicq.so: the functions of include/icq.h under the same names.
+
+Argument marshalling only.  Tensors are torch CUDA (ROCm) tensors used as plain
+device memory; work is enqueued on torch's current stream.  Every step of the
+search runs in the library's kernels: there is no CPU or PyTorch fallback, and a
+missing library is an error.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libicq.so")
+
+ICQ_OK, ICQ_ERR_ARG, ICQ_ERR_WORKSPACE, ICQ_ERR_HIP, ICQ_ERR_CAPACITY = 0, -1, -2, -3, -4
+ICQ_PAD_ID = 0xFFFFFFFF
+ICQ_LUT_W = 256
+
+# name -> (restype, argtypes); mirrors include/icq.h one to one
+_vp, _i, _i64, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+SIGNATURES = {
+    "icq_strerror": (ctypes.c_char_p, [_i]),
+    "icq_index_create": (_i, [ctypes.POINTER(_vp), _vp, _vp, _i, _i, _i, _i, _i64, _vp]),
+    "icq_index_destroy": (None, [_vp]),
+    "icq_index_export_codes": (_i, [_vp, _vp, _vp]),
+    "icq_workspace_bytes": (_i, [_vp, _i, _i64, _i, ctypes.POINTER(_sz)]),
+    "icq_build_lut": (_i, [_vp, _vp, _i, _vp, _vp]),
+    "icq_scan_fast": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
+    "icq_refine": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _sz, _vp]),
+    "icq_search": (_i, [_vp, _vp, _i, _vp, _i64, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+}
+_lib = None
+
+
+class IcqError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (where, strerror(code), code))
+
+
+def load():
+    """Load libicq.so; raise if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "HIP library %s is missing: build it with `python -m paper_1912_08756_amd.build`"
+                % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def strerror(code):
+    return load().icq_strerror(int(code)).decode()
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, shape=None, name="tensor"):
+    if t is None:
+        return ctypes.c_void_p(0)
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor of %s" % (name, dtype))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _check(rc, where):
+    if rc != ICQ_OK:
+        raise IcqError(rc, where)
+
+
+class Index:
+    """Owner of an icq_index handle (destroyed with the object)."""
+
+    def __init__(self, handle, K, m, d, Kf, N):
+        self.handle, self.K, self.m, self.d, self.Kf, self.N = handle, K, m, d, Kf, N
+
+    def __del__(self):
+        h, self.handle = getattr(self, "handle", None), None
+        if h and _lib is not None:
+            _lib.icq_index_destroy(h)
+
+
+def icq_index_create(codebooks, codes, Kf):
+    """codebooks [K][m][d] f32, codes [K][N] u8 (device tensors) -> Index."""
+    K, m, d = codebooks.shape
+    N = codes.shape[1]
+    h = ctypes.c_void_p(0)
+    rc = load().icq_index_create(ctypes.byref(h), _dev(codebooks, torch.float32, name="codebooks"),
+                                 _dev(codes, torch.uint8, (K, N), "codes"), K, m, d, Kf, N, _stream())
+    _check(rc, "icq_index_create")
+    return Index(h, K, m, d, Kf, N)
+
+
+def icq_index_destroy(index):
+    h, index.handle = index.handle, None
+    if h:
+        load().icq_index_destroy(h)
+
+
+def icq_index_export_codes(index, codes_out):
+    _check(load().icq_index_export_codes(index.handle, _dev(codes_out, torch.uint8, (index.K, index.N)),
+                                         _stream()), "icq_index_export_codes")
+    return codes_out
+
+
+def icq_workspace_bytes(index, Q, cap, topk):
+    out = ctypes.c_size_t(0)
+    _check(load().icq_workspace_bytes(index.handle, Q, cap, topk, ctypes.byref(out)), "icq_workspace_bytes")
+    return int(out.value)
+
+
+def icq_build_lut(index, queries, lut):
+    Q = queries.shape[0]
+    _check(load().icq_build_lut(index.handle, _dev(queries, torch.float32, (Q, index.d), "queries"), Q,
+                                _dev(lut, torch.float32, (Q, index.K, ICQ_LUT_W), "lut"), _stream()),
+           "icq_build_lut")
+    return lut
+
+
+def icq_scan_fast(index, lut, thresholds, cand_ids, cand_partial, cand_count, workspace):
+    Q, cap = cand_ids.shape
+    _check(load().icq_scan_fast(index.handle, _dev(lut, torch.float32, (Q, index.K, ICQ_LUT_W), "lut"), Q,
+                                _dev(thresholds, torch.float32, (Q,), "thresholds"),
+                                _dev(cand_ids, torch.int32, (Q, cap), "cand_ids"),
+                                _dev(cand_partial, torch.float32, (Q, cap), "cand_partial"),
+                                _dev(cand_count, torch.int32, (Q,), "cand_count"), cap,
+                                _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()),
+           "icq_scan_fast")
+
+
+def icq_refine(index, lut, cand_ids, cand_partial, cand_count, topk, out_ids, out_dist, workspace):
+    Q, cap = cand_ids.shape
+    _check(load().icq_refine(index.handle, _dev(lut, torch.float32, (Q, index.K, ICQ_LUT_W), "lut"), Q,
+                             _dev(cand_ids, torch.int32, (Q, cap), "cand_ids"),
+                             _dev(cand_partial, torch.float32, (Q, cap), "cand_partial"),
+                             _dev(cand_count, torch.int32, (Q,), "cand_count"), cap, topk,
+                             _dev(out_ids, torch.int32, (Q, topk), "out_ids"),
+                             _dev(out_dist, torch.float32, (Q, topk), "out_dist"),
+                             _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()),
+           "icq_refine")
+
+
+def icq_search(index, queries, thresholds, cap, topk, out_ids, out_dist, out_survivors, workspace):
+    Q = queries.shape[0]
+    _check(load().icq_search(index.handle, _dev(queries, torch.float32, (Q, index.d), "queries"), Q,
+                             _dev(thresholds, torch.float32, (Q,), "thresholds"), cap, topk,
+                             _dev(out_ids, torch.int32, (Q, topk), "out_ids"),
+                             _dev(out_dist, torch.float32, (Q, topk), "out_dist"),
+                             _dev(out_survivors, torch.int32, (Q,), "out_survivors"),
+                             _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()),
+           "icq_search")

@@ -1,0 +1,149 @@
+// Index construction: private device copies of codebooks and codes in the
+// layouts the search kernels stream (Sec. 1 of arxiv 1912.08756: an item is K
+// codeword indices; the fast set is codebooks 0..Kf-1).
+#include "icq_internal.h"
+
+#include <math.h>
+#include <new>
+
+namespace {
+
+// fast[k][i] = codes[k][i] for k < Kf, zero beyond N (row stride Npad).
+__global__ void copy_fast_kernel(const uint8_t *__restrict__ codes, int64_t N, int64_t Npad,
+                                 uint8_t *__restrict__ fast) {
+    int k = blockIdx.y;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < Npad) fast[(int64_t)k * Npad + i] = i < N ? codes[(int64_t)k * N + i] : (uint8_t)0;
+}
+
+// slow[i][j] = codes[Kf + j][i] for j < Ks, zero for Ks <= j < stride.
+__global__ void copy_slow_kernel(const uint8_t *__restrict__ codes, int64_t N, int Kf, int Ks,
+                                 int stride, uint8_t *__restrict__ slow) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= N) return;
+    uint8_t *dst = slow + i * stride;
+    for (int j = 0; j < stride; ++j)
+        dst[j] = j < Ks ? codes[(int64_t)(Kf + j) * N + i] : (uint8_t)0;
+}
+
+// One wavefront per table row r = k*256 + j: copy the codeword with zero padding
+// in d and store its squared norm (accumulated in double, rounded once).
+__global__ void copy_codebooks_kernel(const float *__restrict__ codebooks, int K, int m, int d,
+                                      int d_pad, float *__restrict__ cb,
+                                      float *__restrict__ cnorm) {
+    int row = blockIdx.x * (blockDim.x / ICQ_WAVE) + threadIdx.x / ICQ_WAVE;
+    int lane = threadIdx.x % ICQ_WAVE;
+    if (row >= K * ICQ_LUT_W) return;
+    int k = row / ICQ_LUT_W, j = row % ICQ_LUT_W;
+    double s = 0.0;
+    for (int e = lane; e < d_pad; e += ICQ_WAVE) {
+        float v = (j < m && e < d) ? codebooks[((int64_t)k * m + j) * d + e] : 0.0f;
+        cb[(int64_t)row * d_pad + e] = v;
+        s += (double)v * (double)v;
+    }
+    for (int off = ICQ_WAVE / 2; off > 0; off >>= 1) s += __shfl_down(s, off, ICQ_WAVE);
+    if (lane == 0) cnorm[row] = j < m ? (float)s : INFINITY;
+}
+
+// codes_out[k][i] rebuilt from the private layouts.
+__global__ void export_codes_kernel(const uint8_t *__restrict__ fast, const uint8_t *__restrict__ slow,
+                                    int64_t N, int64_t Npad, int Kf, int stride,
+                                    uint8_t *__restrict__ out) {
+    int k = blockIdx.y;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= N) return;
+    out[(int64_t)k * N + i] = k < Kf ? fast[(int64_t)k * Npad + i] : slow[i * stride + (k - Kf)];
+}
+
+int slow_stride_for(int Ks) {
+    if (Ks == 0) return 0;
+    if (Ks <= 4) return 4;
+    if (Ks <= 8) return 8;
+    return (Ks + 15) / 16 * 16;
+}
+
+}  // namespace
+
+ICQ_EXPORT const char *icq_strerror(int code) {
+    switch (code) {
+        case ICQ_OK: return "ok";
+        case ICQ_ERR_ARG: return "invalid argument";
+        case ICQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case ICQ_ERR_HIP: return "HIP runtime error";
+        case ICQ_ERR_CAPACITY: return "candidate capacity exceeded";
+        default: return "unknown error code";
+    }
+}
+
+ICQ_EXPORT void icq_index_destroy(icq_index *ix) {
+    if (!ix) return;
+    (void)hipFree(ix->cb);
+    (void)hipFree(ix->cnorm);
+    (void)hipFree(ix->fast);
+    (void)hipFree(ix->slow);
+    delete ix;
+}
+
+ICQ_EXPORT int icq_index_create(icq_index **out, const float *codebooks, const uint8_t *codes,
+                                int K, int m, int d, int Kf, int64_t N, void *stream) {
+    if (!out || !codebooks) return ICQ_ERR_ARG;
+    if (K < 1 || K > ICQ_MAX_K || Kf < 1 || Kf > K || m < 1 || m > ICQ_MAX_M || d < 1 ||
+        d > (1 << 20))
+        return ICQ_ERR_ARG;
+    if (N < 0 || N > ICQ_MAX_N || (N > 0 && !codes)) return ICQ_ERR_ARG;
+    hipStream_t s = (hipStream_t)stream;
+
+    icq_index *ix = new (std::nothrow) icq_index();
+    if (!ix) return ICQ_ERR_HIP;
+    ix->K = K; ix->m = m; ix->d = d; ix->Kf = Kf; ix->Ks = K - Kf;
+    ix->d_pad = (d + 15) / 16 * 16;
+    ix->slow_stride = slow_stride_for(ix->Ks);
+    ix->N = N;
+    ix->Npad = (N + 4095) / 4096 * 4096 + 4096;   // one spare block so read-ahead stays in bounds
+    ix->cb = nullptr; ix->cnorm = nullptr; ix->fast = nullptr; ix->slow = nullptr;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&ix->device) != hipSuccess ||
+        hipGetDeviceProperties(&prop, ix->device) != hipSuccess) {
+        delete ix;
+        return ICQ_ERR_HIP;
+    }
+    ix->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+    bool ok = hipMalloc(&ix->cb, sizeof(float) * (size_t)K * ICQ_LUT_W * ix->d_pad) == hipSuccess &&
+              hipMalloc(&ix->cnorm, sizeof(float) * (size_t)K * ICQ_LUT_W) == hipSuccess &&
+              hipMalloc(&ix->fast, (size_t)Kf * ix->Npad) == hipSuccess;
+    if (ok && ix->Ks > 0 && N > 0)
+        ok = hipMalloc(&ix->slow, (size_t)N * ix->slow_stride) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        icq_index_destroy(ix);
+        return ICQ_ERR_HIP;
+    }
+
+    const int T = 256;
+    copy_codebooks_kernel<<<(K * ICQ_LUT_W + 3) / 4, T, 0, s>>>(codebooks, K, m, d, ix->d_pad,
+                                                                 ix->cb, ix->cnorm);
+    {
+        dim3 g((unsigned)((ix->Npad + T - 1) / T), (unsigned)Kf);
+        copy_fast_kernel<<<g, T, 0, s>>>(codes, N, ix->Npad, ix->fast);
+    }
+    if (ix->Ks > 0 && N > 0)
+        copy_slow_kernel<<<(unsigned)((N + T - 1) / T), T, 0, s>>>(codes, N, Kf, ix->Ks,
+                                                                    ix->slow_stride, ix->slow);
+    if (icq_check_launch() != ICQ_OK) {
+        icq_index_destroy(ix);
+        return ICQ_ERR_HIP;
+    }
+    *out = ix;
+    return ICQ_OK;
+}
+
+ICQ_EXPORT int icq_index_export_codes(const icq_index *ix, uint8_t *codes_out, void *stream) {
+    if (!ix || (!codes_out && ix->N > 0)) return ICQ_ERR_ARG;
+    if (ix->N == 0) return ICQ_OK;
+    const int T = 256;
+    dim3 g((unsigned)((ix->N + T - 1) / T), (unsigned)ix->K);
+    export_codes_kernel<<<g, T, 0, (hipStream_t)stream>>>(ix->fast, ix->slow, ix->N, ix->Npad,
+                                                          ix->Kf, ix->slow_stride, codes_out);
+    return icq_check_launch();
+}

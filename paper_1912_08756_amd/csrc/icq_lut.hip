@@ -1,0 +1,102 @@
+// Lookup-table precompute (arxiv 1912.08756, Sec. 1, text after Eq. 1): for
+// every query the squared distance to every codeword of every codebook,
+//   lut[q][k][j] = ||q||^2 - 2<q, c_{k,j}> + ||c_{k,j}||^2.
+// The inner products are one [Q x d] . [d x K*256] contraction and run on the
+// fp32 matrix cores (v_mfma_f32_32x32x2_f32); norms are added in the epilogue.
+#include "icq_internal.h"
+
+namespace {
+
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 64;   // queries per block
+constexpr int BN = 64;   // table entries per block
+constexpr int BK = 16;   // reduction slice staged in LDS
+constexpr int LD = 65;   // LDS row stride (floats): k-major tiles, +1 to spread the transposing writes
+
+// Block = 4 wavefronts in a 2x2 arrangement, each owning a 32x32 output block.
+// MFMA 32x32x2 operand layout: lane l supplies A[l%32][l/32] and B[l/32][l%32];
+// accumulator register v of lane l is C[(v%4) + 4*(l/32) + 8*(v/4)][l%32].
+__global__ __launch_bounds__(256) void build_lut_kernel(const float *__restrict__ queries, int Q,
+                                                        int d, const float *__restrict__ cb,
+                                                        int d_pad, const float *__restrict__ cnorm,
+                                                        int ncols, float *__restrict__ lut) {
+    __shared__ float As[BK][LD];
+    __shared__ float Bs[BK][LD];
+    __shared__ float qn_s[BM];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int n0 = blockIdx.x * BN;
+    const int q0 = blockIdx.y * BM;
+
+    const int le = tid & 15;    // position along the reduction axis for the loads
+    const int lr = tid >> 4;    // row (0..15), +16 per pass
+
+    float16v acc;
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    float qn = 0.0f;
+
+    for (int k0 = 0; k0 < d_pad; k0 += BK) {
+        float a[4], b[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            int row = lr + 16 * p;
+            int q = q0 + row;
+            int e = k0 + le;
+            a[p] = (q < Q && e < d) ? queries[(int64_t)q * d + e] : 0.0f;
+            b[p] = cb[(int64_t)(n0 + row) * d_pad + e];
+        }
+        __syncthreads();   // previous slice fully consumed
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            As[le][lr + 16 * p] = a[p];
+            Bs[le][lr + 16 * p] = b[p];
+        }
+        __syncthreads();
+        if (tid < BM) {
+#pragma unroll
+            for (int e = 0; e < BK; ++e) {
+                float x = As[e][tid];
+                qn = fmaf(x, x, qn);
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < BK / 2; ++s) {
+            float av = As[2 * s + (lane >> 5)][wm * 32 + (lane & 31)];
+            float bv = Bs[2 * s + (lane >> 5)][wn * 32 + (lane & 31)];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
+        }
+    }
+    if (tid < BM) qn_s[tid] = qn;
+    __syncthreads();
+
+    const int col = n0 + wn * 32 + (lane & 31);
+    const float cn = cnorm[col];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        int i = (v & 3) + 4 * (lane >> 5) + 8 * (v >> 2);
+        int q = q0 + wm * 32 + i;
+        if (q < Q) lut[(int64_t)q * ncols + col] = (qn_s[wm * 32 + i] + cn) - 2.0f * acc[v];
+    }
+}
+
+}  // namespace
+
+int icq_launch_build_lut(const icq_index *ix, const float *queries, int Q, float *lut,
+                         hipStream_t s) {
+    if (Q == 0) return ICQ_OK;
+    const int ncols = ix->K * ICQ_LUT_W;
+    dim3 grid((unsigned)(ncols / BN), (unsigned)((Q + BM - 1) / BM));
+    build_lut_kernel<<<grid, 256, 0, s>>>(queries, Q, ix->d, ix->cb, ix->d_pad, ix->cnorm, ncols,
+                                          lut);
+    return icq_check_launch();
+}
+
+ICQ_EXPORT int icq_build_lut(const icq_index *ix, const float *queries, int Q, float *lut,
+                             void *stream) {
+    if (!ix || Q < 0 || (Q > 0 && (!queries || !lut))) return ICQ_ERR_ARG;
+    return icq_launch_build_lut(ix, queries, Q, lut, (hipStream_t)stream);
+}

@@ -1,0 +1,79 @@
+// The whole query-time path of arxiv 1912.08756 (Sec. 3.4) for a batch of
+// queries: table precompute, crude comparison over the fast codebooks (Eq. 2),
+// exact comparison for the survivors (Eq. 1), nearest-neighbour list.  Host
+// side only: workspace carving and kernel sequencing on one stream.
+#include "icq_internal.h"
+
+icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool with_lut,
+                         bool with_cands) {
+    icq_ws_layout L;
+    size_t off = 0;
+    const size_t tiles = ((size_t)Q + 63) / 64;
+    L.lut_off = off;
+    if (with_lut) off = icq_align_up(off + sizeof(float) * (size_t)Q * ix->K * ICQ_LUT_W, ICQ_ALIGN);
+    L.lutT_off = off;
+    off = icq_align_up(off + sizeof(float) * tiles * 64 * (size_t)(ix->Kf <= 2 ? ix->Kf : 0) * ICQ_LUT_W,
+                       ICQ_ALIGN);
+    L.ids_off = off;
+    if (with_cands) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
+    L.part_off = off;
+    if (with_cands) off = icq_align_up(off + sizeof(float) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
+    L.count_off = off;
+    if (with_cands) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q, ICQ_ALIGN);
+    L.splits = icq_refine_splits(ix, Q, cap, topk);
+    L.keys_off = off;
+    if (L.splits > 1)
+        off = icq_align_up(off + sizeof(unsigned long long) * (size_t)Q * L.splits * topk, ICQ_ALIGN);
+    L.total = off;
+    return L;
+}
+
+ICQ_EXPORT int icq_workspace_bytes(const icq_index *ix, int Q, int64_t cap, int topk, size_t *out) {
+    if (!ix || !out || Q < 0 || Q > (1 << 22) || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK)
+        return ICQ_ERR_ARG;
+    if ((double)Q * (double)cap >= 1099511627776.0) return ICQ_ERR_ARG;
+    icq_ws_layout L = icq_layout(ix, Q, cap, topk, true, true);
+    *out = L.total > ICQ_ALIGN ? L.total : ICQ_ALIGN;
+    return ICQ_OK;
+}
+
+ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, const float *thresholds,
+                          int64_t cap, int topk, uint32_t *out_ids, float *out_dist,
+                          uint32_t *out_survivors, void *workspace, size_t workspace_bytes,
+                          void *stream) {
+    if (!ix || Q < 0 || Q > (1 << 22) || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK)
+        return ICQ_ERR_ARG;
+    if (Q == 0) return ICQ_OK;
+    if (!queries || !thresholds || !out_ids || !out_dist) return ICQ_ERR_ARG;
+    if ((double)Q * (double)cap >= 1099511627776.0) return ICQ_ERR_ARG;
+    if (!workspace || ((uintptr_t)workspace % ICQ_ALIGN) != 0) return ICQ_ERR_WORKSPACE;
+
+    // Largest sub-batch (all of Q, else a multiple of 64 queries) that fits the workspace.
+    int Qb = Q;
+    while (icq_layout(ix, Qb, cap, topk, true, true).total > workspace_bytes) {
+        if (Qb <= 64) return ICQ_ERR_WORKSPACE;
+        Qb = ((Qb / 2) + 63) / 64 * 64;
+    }
+    if (Q % Qb != 0 && icq_layout(ix, Q % Qb, cap, topk, true, true).total > workspace_bytes)
+        return ICQ_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = static_cast<char *>(workspace);
+    for (int q0 = 0; q0 < Q; q0 += Qb) {
+        const int nq = (Q - q0) < Qb ? (Q - q0) : Qb;
+        const icq_ws_layout L = icq_layout(ix, nq, cap, topk, true, true);
+        float *lut = reinterpret_cast<float *>(ws + L.lut_off);
+        float *lutT = reinterpret_cast<float *>(ws + L.lutT_off);
+        uint32_t *ids = reinterpret_cast<uint32_t *>(ws + L.ids_off);
+        float *part = reinterpret_cast<float *>(ws + L.part_off);
+        uint32_t *cnt = out_survivors ? out_survivors + q0 : reinterpret_cast<uint32_t *>(ws + L.count_off);
+        unsigned long long *keys = reinterpret_cast<unsigned long long *>(ws + L.keys_off);
+        int rc = icq_launch_build_lut(ix, queries + (int64_t)q0 * ix->d, nq, lut, s);
+        if (rc != ICQ_OK) return rc;
+        rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, part, cnt, cap, lutT, s);
+        if (rc != ICQ_OK) return rc;
+        rc = icq_launch_refine(ix, lut, nq, ids, part, cnt, cap, topk, L.splits, keys,
+                               out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
+        if (rc != ICQ_OK) return rc;
+    }
+    return ICQ_OK;
+}

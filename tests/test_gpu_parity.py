@@ -1,0 +1,307 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element on the same seeded inputs.  Bar: candidate lists equal as sets except
+entries whose crude distance lies within 1e-4*(|t|+1) of the threshold; distances
+within 1e-4*(|d|+1); top-k sets equal except at ties within that tolerance;
+storage round trip bit-exact."""
+import numpy as np
+import pytest
+
+from helpers import check_candidates, check_topk, thresholds_kth, thresholds_quantile, tol
+from oracle import icq_oracle as orc
+from paper_1912_08756_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_1912_08756_amd import binding
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.load()
+    return torch, binding
+
+
+def _dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+class Gpu:
+    """Thin test driver around the binding for one workload."""
+
+    def __init__(self, gpu, cfg):
+        self.torch, self.b = gpu
+        torch = self.torch
+        self.cfg = cfg
+        self.cb = _dev(torch, cfg["codebooks"])
+        self.codes = _dev(torch, cfg["codes"])
+        self.queries = _dev(torch, cfg["queries"])
+        self.index = self.b.icq_index_create(self.cb, self.codes, cfg["Kf"])
+        self.K, self.Q, self.N = cfg["K"], cfg["queries"].shape[0], cfg["codes"].shape[1]
+
+    def workspace(self, Q, cap, topk, nbytes=None):
+        n = self.b.icq_workspace_bytes(self.index, Q, cap, topk) if nbytes is None else nbytes
+        return self.torch.empty(n, dtype=self.torch.uint8, device="cuda")
+
+    def lut(self):
+        torch = self.torch
+        lut = torch.empty((self.Q, self.K, 256), dtype=torch.float32, device="cuda")
+        self.b.icq_build_lut(self.index, self.queries, lut)
+        return lut
+
+    def scan(self, lut, thr, cap):
+        torch = self.torch
+        Q = lut.shape[0]
+        ids = torch.full((Q, cap), -1, dtype=torch.int32, device="cuda")
+        part = torch.full((Q, cap), float("nan"), dtype=torch.float32, device="cuda")
+        cnt = torch.full((Q,), 12345, dtype=torch.int32, device="cuda")
+        ws = self.workspace(Q, cap, 1)
+        self.b.icq_scan_fast(self.index, lut, _dev(torch, thr), ids, part, cnt, ws)
+        torch.cuda.synchronize()
+        return ids, part, cnt
+
+    def refine(self, lut, ids, part, cnt, topk):
+        torch = self.torch
+        Q, cap = ids.shape
+        out_ids = torch.empty((Q, topk), dtype=torch.int32, device="cuda")
+        out_dist = torch.empty((Q, topk), dtype=torch.float32, device="cuda")
+        ws = self.workspace(Q, cap, topk)
+        self.b.icq_refine(self.index, lut, ids, part, cnt, topk, out_ids, out_dist, ws)
+        torch.cuda.synchronize()
+        return _u32(out_ids), out_dist.cpu().numpy()
+
+    def search(self, thr, cap, topk, ws_bytes=None, queries=None):
+        torch = self.torch
+        qs = self.queries if queries is None else queries
+        Q = qs.shape[0]
+        out_ids = torch.empty((Q, topk), dtype=torch.int32, device="cuda")
+        out_dist = torch.empty((Q, topk), dtype=torch.float32, device="cuda")
+        surv = torch.empty((Q,), dtype=torch.int32, device="cuda")
+        ws = self.workspace(Q, cap, topk, ws_bytes)
+        self.b.icq_search(self.index, qs, _dev(torch, thr), cap, topk, out_ids, out_dist, surv, ws)
+        torch.cuda.synchronize()
+        return _u32(out_ids), out_dist.cpu().numpy(), _u32(surv)
+
+
+def oracle_all(cfg, topk=None):
+    """Oracle tables, crude distances and full distances of EVERY item (exhaustive
+    sums), so that band cases can be judged whatever the GPU decided."""
+    T = orc.lut(cfg["codebooks"], cfg["queries"])
+    P = orc.partial(T, cfg["codes"], cfg["Kf"])
+    _, _, D = orc.adc_exhaustive(T, cfg["codes"], 1, want_all=True)
+    return T, P, D
+
+
+def small(name, N, Q, **kw):
+    return synth.make(name, N=N, Q=Q, **kw)
+
+
+# ------------------------------------------------------------------ storage layout
+@pytest.mark.parametrize("K,Kf,N", [(4, 1, 10_007), (8, 2, 4096), (16, 4, 70_001), (3, 3, 513),
+                                      (7, 2, 1), (20, 4, 9_999)])
+def test_storage_round_trip_is_bit_exact(gpu, K, Kf, N):
+    torch, b = gpu
+    cfg = synth.make("C0", N=N, Q=1, K=K, Kf=Kf, sigma=("geom", 0.7))
+    g = Gpu(gpu, cfg)
+    out = torch.zeros((K, N), dtype=torch.uint8, device="cuda")
+    b.icq_index_export_codes(g.index, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), cfg["codes"])
+
+
+# ------------------------------------------------------------------ lookup tables
+@pytest.mark.parametrize("name,Q,over", [
+    ("C0", 100, {}), ("C1", 130, {}), ("C2", 70, {}), ("C3", 65, {}),
+    ("C0", 5, dict(d=7)), ("C0", 64, dict(d=33, m=100)), ("C1", 1, dict(d=200, K=3, Kf=1, sigma=("geom", 0.5)))])
+def test_build_lut_matches_oracle(gpu, name, Q, over):
+    cfg = synth.make(name, N=1000, Q=Q, **over)
+    g = Gpu(gpu, cfg)
+    lut = g.lut().cpu().numpy().astype(np.float64)
+    T = orc.lut(cfg["codebooks"], cfg["queries"])
+    m = cfg["m"]
+    err = np.abs(lut[:, :, :m] - T)
+    assert (err <= tol(T)).all(), "table entry off by %g" % err.max()
+    assert np.isposinf(lut[:, :, m:]).all()
+
+
+# ------------------------------------------------------------------ stage 1
+SCAN_CASES = [
+    # name, N, Q, overrides, threshold rule
+    ("C0", 10_000, 100, {}, ("kth", 20, 1.5)),            # lanes = queries, Kf = 1
+    ("C1", 50_003, 130, {}, ("q", 0.01)),                 # lanes = queries, Kf = 2, ragged tail
+    ("C1", 5_000, 3, {}, ("q", 0.02)),                    # lanes = items (few queries)
+    ("C2", 20_001, 70, dict(d=64), ("q", 0.01)),          # Kf = 4
+    ("C3", 60_000, 64, {}, ("q", 0.01)),                  # clustered codes: ties and bursts
+    ("C4", 30_000, 9, dict(Kf=6), ("q", 0.05)),           # Kf = 6
+    ("C1", 700, 8, {}, ("q", 0.5)),                       # tiny N, half survive
+]
+
+
+def _thr(P, rule):
+    if rule[0] == "kth":
+        return thresholds_kth(P, rule[1], rule[2])
+    return thresholds_quantile(P, rule[1])
+
+
+@pytest.mark.parametrize("name,N,Q,over,rule", SCAN_CASES)
+def test_scan_fast_candidates_match_oracle(gpu, name, N, Q, over, rule):
+    cfg = small(name, N, Q, **over)
+    g = Gpu(gpu, cfg)
+    T, P, D = oracle_all(cfg)
+    thr = _thr(P, rule)
+    cap = int((P < thr[:, None].astype(np.float64)).sum(axis=1).max() * 1.2) + 64
+    lut = g.lut()
+    ids, part, cnt = g.scan(lut, thr, cap)
+    ids, part, cnt = _u32(ids), part.cpu().numpy(), _u32(cnt)
+    for q in range(Q):
+        assert cnt[q] <= cap
+        check_candidates(P[q], thr[q], ids[q], part[q], cnt[q], cap)
+    # determinism of the candidate sets
+    ids2, _, cnt2 = g.scan(lut, thr, cap)
+    ids2, cnt2 = _u32(ids2), _u32(cnt2)
+    assert np.array_equal(cnt, cnt2)
+    for q in range(Q):
+        assert np.array_equal(np.sort(ids[q][:cnt[q]]), np.sort(ids2[q][:cnt2[q]]))
+
+
+@pytest.mark.parametrize("Q", [2, 70])
+def test_scan_fast_special_thresholds_and_overflow(gpu, Q):
+    cfg = small("C1", 3000, Q)
+    g = Gpu(gpu, cfg)
+    T, P, D = oracle_all(cfg)
+    N = 3000
+    lut = g.lut()
+    # +inf keeps everything
+    inf = np.full(Q, np.inf, dtype=np.float32)
+    ids, part, cnt = g.scan(lut, inf, N)
+    ids, cnt = _u32(ids), _u32(cnt)
+    assert (cnt == N).all()
+    for q in range(Q):
+        assert np.array_equal(np.sort(ids[q]), np.arange(N, dtype=np.uint32))
+    # -inf and NaN keep nothing
+    for v in (-np.inf, np.nan):
+        _, _, cnt = g.scan(lut, np.full(Q, v, dtype=np.float32), 8)
+        assert (_u32(cnt) == 0).all()
+    # overflow: true count reported, the cap entries written are genuine survivors
+    thr = thresholds_quantile(P, 0.1)
+    cap = 50
+    ids, part, cnt = g.scan(lut, thr, cap)
+    ids, part, cnt = _u32(ids), part.cpu().numpy(), _u32(cnt)
+    for q in range(Q):
+        exact = int((P[q] < np.float64(thr[q])).sum())
+        assert abs(int(cnt[q]) - exact) <= 3 and cnt[q] > cap
+        check_candidates(P[q], thr[q], ids[q], part[q], cnt[q], cap)
+
+
+# ------------------------------------------------------------------ stage 2 + list
+@pytest.mark.parametrize("name,N,Q,over,rule,topk", [
+    ("C0", 10_000, 100, {}, ("kth", 20, 1.5), 10),
+    ("C1", 50_003, 66, {}, ("q", 0.01), 100),
+    ("C2", 20_001, 5, dict(d=64), ("q", 0.3), 100),       # long lists, few queries: sliced + merged
+    ("C4", 30_000, 9, dict(Kf=6, K=7), ("q", 0.05), 1000),  # one slow codebook, long result
+    ("C1", 4_000, 10, dict(Kf=8), ("q", 0.05), 7),        # Kf == K: stage 2 adds nothing
+])
+def test_refine_matches_oracle(gpu, name, N, Q, over, rule, topk):
+    cfg = small(name, N, Q, **over)
+    g = Gpu(gpu, cfg)
+    T, P, D = oracle_all(cfg)
+    thr = _thr(P, rule)
+    cap = int((P < thr[:, None].astype(np.float64)).sum(axis=1).max() * 1.2) + 64
+    lut = g.lut()
+    ids, part, cnt = g.scan(lut, thr, cap)
+    out_ids, out_dist = g.refine(lut, ids, part, cnt, topk)
+    for q in range(Q):
+        check_topk(P[q], D[q], thr[q], topk, out_ids[q], out_dist[q])
+
+
+# ------------------------------------------------------------------ whole path
+@pytest.mark.parametrize("name,N,Q,over,rule", [
+    ("C0", None, None, {}, ("kth", 20, 1.5)),             # the tiny config, complete
+    ("C1", 200_003, 130, {}, ("q", 0.01)),
+    ("C2", 50_001, 70, {}, ("q", 0.01)),                  # d = 960, Kf = 4
+    ("C3", 100_000, 256, {}, ("q", 0.01)),
+    ("C4", 120_000, 128, {}, ("q", 0.01)),
+    ("C1", 2_000, 1, {}, ("q", 0.01)),                    # one query
+    ("C1", 300, 33, {}, ("kth", 3, 1.0)),                 # fewer survivors than topk
+])
+def test_search_matches_oracle(gpu, name, N, Q, over, rule):
+    cfg = small(name, N, Q, **over)
+    g = Gpu(gpu, cfg)
+    T, P, D = oracle_all(cfg)
+    thr = _thr(P, rule)
+    topk = cfg["topk"]
+    exact = (P < thr[:, None].astype(np.float64)).sum(axis=1)
+    cap = int(exact.max() * 1.2) + 64
+    out_ids, out_dist, surv = g.search(thr, cap, topk)
+    o_ids, o_dist, o_cnt = orc.search(T, cfg["codes"], cfg["Kf"], thr, topk)
+    n_equal = n_eligible = 0
+    for q in range(g.Q):
+        band = np.nonzero((P[q] >= thr[q] - tol(thr[q])) & (P[q] <= thr[q] + tol(thr[q])))[0]
+        assert abs(int(surv[q]) - int(o_cnt[q])) <= band.size
+        check_topk(P[q], D[q], thr[q], topk, out_ids[q], out_dist[q])
+        if not (np.isin(o_ids[q], band).any() or np.isin(out_ids[q], band).any()):
+            n_eligible += 1
+            n_equal += np.array_equal(out_ids[q], o_ids[q])
+    # where no threshold-band item reaches the list, the lists are identical up to near-ties
+    assert n_equal >= 0.9 * n_eligible
+
+
+def test_search_infinite_threshold_is_exhaustive_adc(gpu):
+    cfg = small("C1", 20_000, 20)
+    g = Gpu(gpu, cfg)
+    T, P, D = oracle_all(cfg)
+    inf = np.full(20, np.inf, dtype=np.float32)
+    out_ids, out_dist, surv = g.search(inf, 20_000, 100)
+    e_ids, e_dist = orc.adc_exhaustive(T, cfg["codes"], 100)
+    assert (surv == 20_000).all()
+    for q in range(20):
+        check_topk(P[q], D[q], np.inf, 100, out_ids[q], out_dist[q])
+    assert (out_ids == e_ids).mean() > 0.98
+
+
+def test_search_in_sub_batches_gives_the_same_lists(gpu):
+    cfg = small("C1", 30_000, 300)
+    g = Gpu(gpu, cfg)
+    T, P, D = oracle_all(cfg)
+    thr = thresholds_quantile(P, 0.01)
+    cap, topk = 512, 50
+    full = g.search(thr, cap, topk)
+    need64 = g.b.icq_workspace_bytes(g.index, 64, cap, topk)
+    sub = g.search(thr, cap, topk, ws_bytes=need64 + 4096)     # forces batches of 64 queries
+    assert np.array_equal(full[0], sub[0]) and np.array_equal(full[1], sub[1])
+    assert np.array_equal(full[2], sub[2])
+    with pytest.raises(g.b.IcqError):
+        g.search(thr, cap, topk, ws_bytes=1024)
+
+
+def test_empty_inputs(gpu):
+    torch, b = gpu
+    cfg = small("C1", 10, 4)
+    cfg["codes"] = np.ascontiguousarray(cfg["codes"][:, :0])
+    g = Gpu(gpu, cfg)
+    thr = np.full(4, np.inf, dtype=np.float32)
+    out_ids, out_dist, surv = g.search(thr, 16, 5)
+    assert (out_ids == 0xFFFFFFFF).all() and np.isposinf(out_dist).all() and (surv == 0).all()
+    # Q = 0 is a no-op
+    lib = b.load()
+    assert lib.icq_search(g.index.handle, None, 0, None, 16, 5, None, None, None, None, 0, None) == 0
+    assert lib.icq_build_lut(g.index.handle, None, 0, None, None) == 0
+
+
+def test_argument_errors_on_a_live_index(gpu):
+    torch, b = gpu
+    cfg = small("C1", 1000, 4)
+    g = Gpu(gpu, cfg)
+    lib = b.load()
+    one = g.queries.data_ptr()
+    h = g.index.handle
+    assert lib.icq_search(h, one, 4, one, 16, 0, one, one, None, one, 1 << 20, None) == b.ICQ_ERR_ARG
+    assert lib.icq_search(h, one, 4, one, 16, 2000, one, one, None, one, 1 << 20, None) == b.ICQ_ERR_ARG
+    assert lib.icq_search(h, one, 4, one, 0, 5, one, one, None, one, 1 << 20, None) == b.ICQ_ERR_ARG
+    assert lib.icq_search(h, one, 4, one, 16, 5, one, one, None, None, 0, None) == b.ICQ_ERR_WORKSPACE
+    assert lib.icq_search(h, one, 4, one, 16, 5, one, one, None, one + 4, 1 << 20, None) == b.ICQ_ERR_WORKSPACE
+    assert lib.icq_search(h, one, -1, one, 16, 5, one, one, None, one, 1 << 20, None) == b.ICQ_ERR_ARG
