@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Throughput of the ICQ query-time path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one icq_search call over the whole query set of the workload (table
+build, stage-1 scan, stage-2 refine, top-k), inputs resident in HBM.  Prints ONE
+JSON line: queries/s, the roofline of the dominant kernel (the stage-1 scan;
+batch mode is bound by LDS gather bandwidth), the stage-1 scan on a 400 MB
+fast-code array with a single query (bound by HBM), and the CPU oracle timed on
+the host cores as a baseline.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E
+LDS_PEAK_GBS = 256 * 128 * 2.4              # 256 CUs x 128 B/clk x 2.4 GHz = 78643 GB/s
+SURVIVE_FRAC = 0.01
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def sampled_thresholds(torch, b, cb_dev, codes_dev, queries_dev, Kf, frac, n_sample, seed):
+    """Per-query threshold = the frac-quantile of the crude distance over a random
+    sample of items.  The crude distances come from the library itself (table
+    build + stage-1 scan with an infinite threshold on an index over the sample);
+    only the quantile pick is a torch op.  Input preparation, not timed."""
+    K, N = codes_dev.shape
+    Q = queries_dev.shape[0]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    pick = torch.randint(0, N, (n_sample,), device="cuda", generator=g)
+    sample_codes = codes_dev[:, pick].contiguous()
+    idx = b.icq_index_create(cb_dev, sample_codes, Kf)
+    kth = max(1, int(math.ceil(frac * n_sample)))
+    thr = torch.empty(Q, dtype=torch.float32, device="cuda")
+    step = 2048
+    for q0 in range(0, Q, step):
+        qs = queries_dev[q0:q0 + step].contiguous()
+        nq = qs.shape[0]
+        lut = torch.empty((nq, K, 256), dtype=torch.float32, device="cuda")
+        b.icq_build_lut(idx, qs, lut)
+        ids = torch.empty((nq, n_sample), dtype=torch.int32, device="cuda")
+        part = torch.empty((nq, n_sample), dtype=torch.float32, device="cuda")
+        cnt = torch.empty((nq,), dtype=torch.int32, device="cuda")
+        ws = torch.empty(b.icq_workspace_bytes(idx, nq, n_sample, 1), dtype=torch.uint8, device="cuda")
+        inf = torch.full((nq,), float("inf"), dtype=torch.float32, device="cuda")
+        b.icq_scan_fast(idx, lut, inf, ids, part, cnt, ws)
+        torch.cuda.synchronize()
+        assert int(cnt.min()) == n_sample and int(cnt.max()) == n_sample
+        thr[q0:q0 + nq] = torch.kthvalue(part, kth, dim=1).values
+    torch.cuda.synchronize()
+    del idx
+    return thr
+
+
+def event_time_ms(torch, fn, reps):
+    """Average duration of fn() over reps, by events on the launch stream."""
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(reps):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / reps
+
+
+def hbm_leg(torch, b, steps, warmup):
+    """Stage-1 scan of a 400 MB fast-code array (N = 1e8, Kf = 4) for a single
+    query: every code byte is read once per query, so the kernel is HBM-bound."""
+    N, Kf, d = 100_000_000, 4, 96
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4)
+    codes = torch.randint(0, 256, (Kf, N), dtype=torch.uint8, device="cuda", generator=g)
+    from paper_1912_08756_amd import synth
+    cb = torch.from_numpy(synth.make_codebooks(Kf, 256, d, synth.sigmas(("geom", 0.8), Kf), 4)).cuda()
+    src = codes[:, :1].long()
+    q = sum(cb[k, src[k, 0]] for k in range(Kf)).reshape(1, d).contiguous()
+    q = q + 0.05 * q.norm() / math.sqrt(d) * torch.randn((1, d), device="cuda", generator=g)
+    thr = sampled_thresholds(torch, b, cb, codes, q, Kf, SURVIVE_FRAC, 65536, 5)
+    idx = b.icq_index_create(cb, codes, Kf)
+    cap = int(N * SURVIVE_FRAC * 2)
+    lut = torch.empty((1, Kf, 256), dtype=torch.float32, device="cuda")
+    b.icq_build_lut(idx, q, lut)
+    ids = torch.empty((1, cap), dtype=torch.int32, device="cuda")
+    part = torch.empty((1, cap), dtype=torch.float32, device="cuda")
+    cnt = torch.empty((1,), dtype=torch.int32, device="cuda")
+    ws = torch.empty(b.icq_workspace_bytes(idx, 1, cap, 1), dtype=torch.uint8, device="cuda")
+
+    def run():
+        b.icq_scan_fast(idx, lut, thr, ids, part, cnt, ws)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    ms = event_time_ms(torch, run, steps)
+    surv = int(cnt.item())
+    alg_bytes = Kf * N + 4 * Kf * 256 + 8 * surv
+    achieved = alg_bytes / (ms * 1e-3) / 1e9
+    return {"bound": "hbm", "kernel": "scan_items_kernel", "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": None, "ms": round(ms, 4),
+            "workload": "fast codes [4][1e8] u8 (400 MB), 1 query, survivors %d" % surv}
+
+
+def cpu_baseline(cfg, thr_np, gpu_ids, gpu_dist, target_s=15.0):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the
+    same workload; its results double as the oracle-matched check of the GPU lists."""
+    from oracle import icq_oracle as orc
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import check_topk
+    codes, cb, queries = cfg["codes"], cfg["codebooks"], cfg["queries"]
+    Kf, topk = cfg["Kf"], cfg["topk"]
+    Q = queries.shape[0]
+    pilot = min(Q, 64)
+    t0 = time.perf_counter()
+    T = orc.lut(cb, queries[:pilot])
+    orc.search(T, codes, Kf, thr_np[:pilot], topk)
+    per_q = (time.perf_counter() - t0) / pilot
+    n = int(min(Q, max(pilot, target_s / max(per_q, 1e-9))))
+    t0 = time.perf_counter()
+    T = orc.lut(cb, queries[:n])
+    o_ids, o_dist, o_cnt = orc.search(T, codes, Kf, thr_np[:n], topk)
+    dt = time.perf_counter() - t0
+    # oracle-matched: full acceptance rule on a few queries, identical-list rate on all sampled
+    n_check = min(n, 16)
+    P = orc.partial(T[:n_check], codes, Kf)
+    _, _, D = orc.adc_exhaustive(T[:n_check], codes, 1, want_all=True)
+    for q in range(n_check):
+        check_topk(P[q], D[q], thr_np[q], topk, gpu_ids[q], gpu_dist[q])
+    same = float((gpu_ids[:n] == o_ids).all(axis=1).mean())
+    return ({"value": round(n / dt, 2), "unit": "queries/s", "cores": orc.threads(), "kind": "oracle",
+             "sample": "first %d of %d queries of the workload, full N, table build + two-step search, "
+                       "%.1f s wall" % (n, Q, dt)},
+            {"checked_queries": n_check, "identical_lists_frac": round(same, 4), "sampled_queries": n})
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-hbm-leg", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    from paper_1912_08756_amd import binding as b, synth
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    b.load()
+
+    log("[bench] drawing workload", args.workload)
+    cfg = synth.make(args.workload)
+    K, Kf, d, N, Q, topk = cfg["K"], cfg["Kf"], cfg["d"], cfg["N"], cfg["Q"], cfg["topk"]
+    cb = torch.from_numpy(cfg["codebooks"]).cuda()
+    codes = torch.from_numpy(cfg["codes"]).cuda()
+    queries = torch.from_numpy(cfg["queries"]).cuda()
+    index = b.icq_index_create(cb, codes, Kf)
+    thr = sampled_thresholds(torch, b, cb, codes, queries, Kf, SURVIVE_FRAC, 16384, cfg["seed"])
+    cap = 1 << int(math.ceil(math.log2(max(64, N * SURVIVE_FRAC * 1.5))))
+    out_ids = torch.empty((Q, topk), dtype=torch.int32, device="cuda")
+    out_dist = torch.empty((Q, topk), dtype=torch.float32, device="cuda")
+    surv = torch.empty((Q,), dtype=torch.int32, device="cuda")
+    ws_bytes = b.icq_workspace_bytes(index, Q, cap, topk)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    log("[bench] N=%d Q=%d K=%d Kf=%d d=%d topk=%d cap=%d workspace=%.2f GB" %
+        (N, Q, K, Kf, d, topk, cap, ws_bytes / 1e9))
+
+    def step():
+        b.icq_search(index, queries, thr, cap, topk, out_ids, out_dist, surv, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    surv_np = surv.cpu().numpy().view(np.uint32)
+    overflow = int((surv_np > cap).sum())
+    log("[bench] %.3f ms/step, survivors mean %.0f max %d, overflowed lists %d" %
+        (ms_per_step, surv_np.mean(), surv_np.max(), overflow))
+
+    # stage breakdown on the same inputs (same kernels as icq_search, called one by one)
+    lut = torch.empty((Q, K, 256), dtype=torch.float32, device="cuda")
+    c_ids = torch.empty((Q, cap), dtype=torch.int32, device="cuda")
+    c_part = torch.empty((Q, cap), dtype=torch.float32, device="cuda")
+    c_cnt = torch.empty((Q,), dtype=torch.int32, device="cuda")
+    reps = max(3, args.steps)
+    ms_lut = event_time_ms(torch, lambda: b.icq_build_lut(index, queries, lut), reps)
+    ms_scan = event_time_ms(torch, lambda: b.icq_scan_fast(index, lut, thr, c_ids, c_part, c_cnt, ws), reps)
+    ms_refine = event_time_ms(
+        torch, lambda: b.icq_refine(index, lut, c_ids, c_part, c_cnt, topk, out_ids, out_dist, ws), reps)
+    log("[bench] stages: lut %.3f ms, scan %.3f ms, refine %.3f ms" % (ms_lut, ms_scan, ms_refine))
+
+    lds_bytes = 4.0 * Kf * N * Q                     # one 4-byte table read per (query, item, fast codebook)
+    achieved = lds_bytes / (ms_scan * 1e-3) / 1e9
+    roofline = {"bound": "lds", "kernel": "scan_batch_kernel", "achieved": round(achieved, 1),
+                "peak": round(LDS_PEAK_GBS, 1), "unit": "GB/s", "frac": round(achieved / LDS_PEAK_GBS, 4),
+                "traffic": None, "ms": round(ms_scan, 4),
+                "note": "algorithmic LDS gather bytes 4*Kf*N*Q per launch; code bytes from HBM are Kf*N*ceil(Q/64)"}
+
+    result = {
+        "metric": "queries/sec at top-%d (oracle-matched)" % topk,
+        "value": round(Q / (ms_per_step * 1e-3), 1), "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: d=%d K=%d Kf=%d m=256 N=%d Q=%d top-%d, ~%.0f%% survive stage 1" %
+                   (args.workload, d, K, Kf, N, Q, topk, 100 * SURVIVE_FRAC),
+                   "cap": cap, "overflowed_lists": overflow,
+                   "survivors_mean": round(float(surv_np.mean()), 1)},
+        "stages_ms": {"build_lut": round(ms_lut, 4), "scan_fast": round(ms_scan, 4), "refine": round(ms_refine, 4)},
+        "roofline": roofline,
+    }
+    if not args.no_hbm_leg:
+        del c_ids, c_part, lut, ws
+        torch.cuda.empty_cache()
+        log("[bench] stage-1 scan on the 400 MB fast-code array, one query")
+        result["roofline_stage1_hbm"] = hbm_leg(torch, b, max(5, args.steps), args.warmup)
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle")
+        base, match = cpu_baseline(cfg, thr.cpu().numpy(), out_ids.cpu().numpy().view(np.uint32),
+                                   out_dist.cpu().numpy())
+        result["cpu_baseline"] = base
+        result["oracle_matched"] = match
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
