@@ -66,8 +66,9 @@ const char *icq_strerror(int code);
  *   codebooks [K][m][d] fp32;  codes [K][N] uint8, codebook-major, every value < m;
  *   1 <= Kf <= K <= ICQ_MAX_K, 1 <= m <= 256, d >= 1, 0 <= N <= ICQ_MAX_N.
  * The index copies what it needs into private device arrays laid out for the
- * kernels (fast sub-codes [Kf][N] padded and 16-byte aligned per row, slow
- * sub-codes item-major [N][stride], codewords padded in d, codeword norms), so
+ * kernels (fast sub-codes [Kf][N] padded and 16-byte aligned per row, all K
+ * sub-codes of an item as one item-major record [N][stride], codewords padded
+ * in d, codeword norms), so
  * the caller may release `codebooks` and `codes` once `stream` has been
  * synchronised.  Sub-codes >= m are not detected; tables are always 256
  * entries wide with +inf beyond m, so such an item simply gets distance +inf.  *out is set only on success.
@@ -80,8 +81,10 @@ int icq_index_create(icq_index **out /*host*/, const float *codebooks, const uin
 void icq_index_destroy(icq_index *index);
 
 /* Write the index's private copy of the codes back in the input layout
- * [K][N] (bit-exact round trip of the storage layout; a debugging aid). */
-int icq_index_export_codes(const icq_index *index, uint8_t *codes_out, void *stream);
+ * [K][N] (bit-exact round trip of the storage layout; a debugging aid).
+ * from_items == 0: fast rows from the stage-1 array, slow rows from the item
+ * records; from_items != 0: every row from the item records. */
+int icq_index_export_codes(const icq_index *index, int from_items, uint8_t *codes_out, void *stream);
 
 /* Bytes of 256-byte-aligned device workspace that icq_scan_fast, icq_refine
  * and icq_search need for up to Q queries per call, candidate capacity `cap`

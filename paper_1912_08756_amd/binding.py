@@ -23,7 +23,7 @@ SIGNATURES = {
     "icq_strerror": (ctypes.c_char_p, [_i]),
     "icq_index_create": (_i, [ctypes.POINTER(_vp), _vp, _vp, _i, _i, _i, _i, _i64, _vp]),
     "icq_index_destroy": (None, [_vp]),
-    "icq_index_export_codes": (_i, [_vp, _vp, _vp]),
+    "icq_index_export_codes": (_i, [_vp, _i, _vp, _vp]),
     "icq_workspace_bytes": (_i, [_vp, _i, _i64, _i, ctypes.POINTER(_sz)]),
     "icq_build_lut": (_i, [_vp, _vp, _i, _vp, _vp]),
     "icq_scan_fast": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
@@ -107,8 +107,9 @@ def icq_index_destroy(index):
         load().icq_index_destroy(h)
 
 
-def icq_index_export_codes(index, codes_out):
-    _check(load().icq_index_export_codes(index.handle, _dev(codes_out, torch.uint8, (index.K, index.N)),
+def icq_index_export_codes(index, from_items, codes_out):
+    _check(load().icq_index_export_codes(index.handle, int(from_items),
+                                         _dev(codes_out, torch.uint8, (index.K, index.N)),
                                          _stream()), "icq_index_export_codes")
     return codes_out
 

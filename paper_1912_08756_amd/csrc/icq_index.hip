@@ -16,14 +16,13 @@ __global__ void copy_fast_kernel(const uint8_t *__restrict__ codes, int64_t N, i
     if (i < Npad) fast[(int64_t)k * Npad + i] = i < N ? codes[(int64_t)k * N + i] : (uint8_t)0;
 }
 
-// slow[i][j] = codes[Kf + j][i] for j < Ks, zero for Ks <= j < stride.
-__global__ void copy_slow_kernel(const uint8_t *__restrict__ codes, int64_t N, int Kf, int Ks,
-                                 int stride, uint8_t *__restrict__ slow) {
+// items[i][k] = codes[k][i] for k < K, zero for K <= k < stride.
+__global__ void copy_items_kernel(const uint8_t *__restrict__ codes, int64_t N, int K, int stride,
+                                  uint8_t *__restrict__ items) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= N) return;
-    uint8_t *dst = slow + i * stride;
-    for (int j = 0; j < stride; ++j)
-        dst[j] = j < Ks ? codes[(int64_t)(Kf + j) * N + i] : (uint8_t)0;
+    uint8_t *dst = items + i * stride;
+    for (int k = 0; k < stride; ++k) dst[k] = k < K ? codes[(int64_t)k * N + i] : (uint8_t)0;
 }
 
 // One wavefront per table row r = k*256 + j: copy the codeword with zero padding
@@ -45,21 +44,21 @@ __global__ void copy_codebooks_kernel(const float *__restrict__ codebooks, int K
     if (lane == 0) cnorm[row] = j < m ? (float)s : INFINITY;
 }
 
-// codes_out[k][i] rebuilt from the private layouts.
-__global__ void export_codes_kernel(const uint8_t *__restrict__ fast, const uint8_t *__restrict__ slow,
-                                    int64_t N, int64_t Npad, int Kf, int stride,
+// codes_out[k][i] rebuilt from the private layouts: rows below `fast_rows` from
+// the codebook-major fast array, the others from the item records.
+__global__ void export_codes_kernel(const uint8_t *__restrict__ fast, const uint8_t *__restrict__ items,
+                                    int64_t N, int64_t Npad, int fast_rows, int stride,
                                     uint8_t *__restrict__ out) {
     int k = blockIdx.y;
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= N) return;
-    out[(int64_t)k * N + i] = k < Kf ? fast[(int64_t)k * Npad + i] : slow[i * stride + (k - Kf)];
+    out[(int64_t)k * N + i] = k < fast_rows ? fast[(int64_t)k * Npad + i] : items[i * stride + k];
 }
 
-int slow_stride_for(int Ks) {
-    if (Ks == 0) return 0;
-    if (Ks <= 4) return 4;
-    if (Ks <= 8) return 8;
-    return (Ks + 15) / 16 * 16;
+int item_stride_for(int K) {
+    if (K <= 4) return 4;
+    if (K <= 8) return 8;
+    return (K + 15) / 16 * 16;
 }
 
 }  // namespace
@@ -80,7 +79,7 @@ ICQ_EXPORT void icq_index_destroy(icq_index *ix) {
     (void)hipFree(ix->cb);
     (void)hipFree(ix->cnorm);
     (void)hipFree(ix->fast);
-    (void)hipFree(ix->slow);
+    (void)hipFree(ix->items);
     delete ix;
 }
 
@@ -97,10 +96,10 @@ ICQ_EXPORT int icq_index_create(icq_index **out, const float *codebooks, const u
     if (!ix) return ICQ_ERR_HIP;
     ix->K = K; ix->m = m; ix->d = d; ix->Kf = Kf; ix->Ks = K - Kf;
     ix->d_pad = (d + 15) / 16 * 16;
-    ix->slow_stride = slow_stride_for(ix->Ks);
+    ix->item_stride = item_stride_for(K);
     ix->N = N;
     ix->Npad = (N + 4095) / 4096 * 4096 + 4096;   // one spare block so read-ahead stays in bounds
-    ix->cb = nullptr; ix->cnorm = nullptr; ix->fast = nullptr; ix->slow = nullptr;
+    ix->cb = nullptr; ix->cnorm = nullptr; ix->fast = nullptr; ix->items = nullptr;
     hipDeviceProp_t prop;
     if (hipGetDevice(&ix->device) != hipSuccess ||
         hipGetDeviceProperties(&prop, ix->device) != hipSuccess) {
@@ -112,8 +111,7 @@ ICQ_EXPORT int icq_index_create(icq_index **out, const float *codebooks, const u
     bool ok = hipMalloc(&ix->cb, sizeof(float) * (size_t)K * ICQ_LUT_W * ix->d_pad) == hipSuccess &&
               hipMalloc(&ix->cnorm, sizeof(float) * (size_t)K * ICQ_LUT_W) == hipSuccess &&
               hipMalloc(&ix->fast, (size_t)Kf * ix->Npad) == hipSuccess;
-    if (ok && ix->Ks > 0 && N > 0)
-        ok = hipMalloc(&ix->slow, (size_t)N * ix->slow_stride) == hipSuccess;
+    if (ok && N > 0) ok = hipMalloc(&ix->items, (size_t)N * ix->item_stride) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
         icq_index_destroy(ix);
@@ -127,9 +125,9 @@ ICQ_EXPORT int icq_index_create(icq_index **out, const float *codebooks, const u
         dim3 g((unsigned)((ix->Npad + T - 1) / T), (unsigned)Kf);
         copy_fast_kernel<<<g, T, 0, s>>>(codes, N, ix->Npad, ix->fast);
     }
-    if (ix->Ks > 0 && N > 0)
-        copy_slow_kernel<<<(unsigned)((N + T - 1) / T), T, 0, s>>>(codes, N, Kf, ix->Ks,
-                                                                    ix->slow_stride, ix->slow);
+    if (N > 0)
+        copy_items_kernel<<<(unsigned)((N + T - 1) / T), T, 0, s>>>(codes, N, K, ix->item_stride,
+                                                                     ix->items);
     if (icq_check_launch() != ICQ_OK) {
         icq_index_destroy(ix);
         return ICQ_ERR_HIP;
@@ -138,12 +136,14 @@ ICQ_EXPORT int icq_index_create(icq_index **out, const float *codebooks, const u
     return ICQ_OK;
 }
 
-ICQ_EXPORT int icq_index_export_codes(const icq_index *ix, uint8_t *codes_out, void *stream) {
+ICQ_EXPORT int icq_index_export_codes(const icq_index *ix, int from_items, uint8_t *codes_out,
+                                      void *stream) {
     if (!ix || (!codes_out && ix->N > 0)) return ICQ_ERR_ARG;
     if (ix->N == 0) return ICQ_OK;
     const int T = 256;
     dim3 g((unsigned)((ix->N + T - 1) / T), (unsigned)ix->K);
-    export_codes_kernel<<<g, T, 0, (hipStream_t)stream>>>(ix->fast, ix->slow, ix->N, ix->Npad,
-                                                          ix->Kf, ix->slow_stride, codes_out);
+    export_codes_kernel<<<g, T, 0, (hipStream_t)stream>>>(ix->fast, ix->items, ix->N, ix->Npad,
+                                                          from_items ? 0 : ix->Kf, ix->item_stride,
+                                                          codes_out);
     return icq_check_launch();
 }

@@ -14,14 +14,14 @@
 struct icq_index {
     int K, m, d, Kf, Ks;       // Ks = K - Kf slow codebooks
     int d_pad;                 // d rounded up to a multiple of 16 (zero filled)
-    int slow_stride;           // bytes per item in `slow` (0 when Ks == 0)
+    int item_stride;           // bytes per item record in `items`
     int device;
     int num_cu;
     int64_t N, Npad;           // Npad: N rounded up to a multiple of 4096
     float *cb;                 // [K*256][d_pad] codewords, rows j >= m are zero
     float *cnorm;              // [K*256] squared codeword norms, +inf for j >= m
     uint8_t *fast;             // [Kf][Npad] fast sub-codes, zero padded
-    uint8_t *slow;             // [N][slow_stride] slow sub-codes, item-major
+    uint8_t *items;            // [N][item_stride] all K sub-codes of an item, item-major
 };
 
 // Sub-buffers carved out of the caller's workspace for one query batch.
@@ -42,9 +42,12 @@ int icq_refine_splits(const icq_index *ix, int Q, int64_t cap, int topk);
 // Kernel launchers (each checks nothing; the extern "C" entry points validate).
 int icq_launch_build_lut(const icq_index *ix, const float *queries, int Q, float *lut,
                          hipStream_t s);
+// cand_part == nullptr: the crude distances are not materialised (the fused path
+// recomputes the full sum in stage 2 from the item records).
 int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
                     uint32_t *cand_ids, float *cand_part, uint32_t *cand_count, int64_t cap,
                     float *lutT, hipStream_t s);
+// cand_part == nullptr: D is the full K-term sum; else D = cand_part + slow terms.
 int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32_t *cand_ids,
                       const float *cand_part, const uint32_t *cand_count, int64_t cap, int topk,
                       int splits, unsigned long long *keys, uint32_t *out_ids, float *out_dist,

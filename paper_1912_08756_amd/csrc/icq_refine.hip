@@ -3,9 +3,11 @@
 //   D[q][i] = P[q][i] + sum_{k=Kf..K-1} lut[q][k][code_k(i)]
 // and keep the per-query list of the topk nearest, ordered by (D, id).
 //
-// One block handles one slice of one query's candidate list.  The query's slow
-// tables sit in LDS; each thread gathers one survivor's slow sub-codes (stored
-// item-major, one aligned record per item) and forms D.  Selection keeps a
+// One block handles one slice of one query's candidate list.  The query's
+// tables sit in LDS; each thread gathers one survivor's sub-codes (stored
+// item-major, one aligned record per item) and forms D, either from the crude
+// distance handed over by stage 1 plus the slow terms, or -- when stage 1 listed
+// ids only -- as the whole K-term sum in the same order of additions.  Selection keeps a
 // running bound: a 64-bit key (order-preserving bits of D, id) enters an LDS
 // buffer only if it beats the current topk-th key; when the buffer fills it is
 // sorted (bitonic) and cut back to topk, which tightens the bound.
@@ -76,9 +78,10 @@ __device__ __forceinline__ void write_result(const u64 *keys, int kept, int topk
     }
 }
 
-// grid (Q * splits), block b = q * splits + slice.  LDS: keys[bufn] | slow tables [Ks][256].
+// grid (Q * splits), block b = q * splits + slice.  LDS: keys[bufn] | tables k0..K-1,
+// k0 = Kf when cand_part is given, else 0.
 __global__ __launch_bounds__(RF_THREADS) void refine_kernel(
-    const uint8_t *__restrict__ slow, int stride, int K, int Kf, const float *__restrict__ lut,
+    const uint8_t *__restrict__ items, int stride, int K, int Kf, const float *__restrict__ lut,
     const uint32_t *__restrict__ cand_ids, const float *__restrict__ cand_part,
     const uint32_t *__restrict__ cand_count, int64_t cap, int topk, int bufn, int splits,
     u64 *__restrict__ keys_out, uint32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
@@ -87,12 +90,12 @@ __global__ __launch_bounds__(RF_THREADS) void refine_kernel(
     __shared__ u64 s_bound;
     u64 *keys = smem64;
     float *T = reinterpret_cast<float *>(keys + bufn);
-    const int Ks = K - Kf;
+    const int k0 = cand_part ? Kf : 0;
     const int q = blockIdx.x / splits, sp = blockIdx.x % splits;
     const int tid = threadIdx.x;
 
-    for (int i = tid; i < Ks * ICQ_LUT_W; i += RF_THREADS)
-        T[i] = lut[((int64_t)q * K + Kf) * ICQ_LUT_W + i];
+    for (int i = tid; i < (K - k0) * ICQ_LUT_W; i += RF_THREADS)
+        T[i] = lut[((int64_t)q * K + k0) * ICQ_LUT_W + i];
     if (tid == 0) {
         s_cnt = 0;
         s_bound = KEY_PAD;
@@ -103,19 +106,25 @@ __global__ __launch_bounds__(RF_THREADS) void refine_kernel(
     if (n > (u64)cap) n = (u64)cap;
     const u64 lo = n * (u64)sp / (u64)splits, hi = n * (u64)(sp + 1) / (u64)splits;
     const uint32_t *ids = cand_ids + (int64_t)q * cap;
-    const float *part = cand_part + (int64_t)q * cap;
+    const float *part = cand_part ? cand_part + (int64_t)q * cap : nullptr;
+    const int w0 = k0 / 4;   // first record word that holds a needed sub-code
 
     for (u64 base = lo; base < hi; base += RF_THREADS) {
         const u64 idx = base + tid;
         if (idx < hi) {
             const uint32_t id = ids[idx];
-            float D = part[idx];
-            const uint32_t *rec = reinterpret_cast<const uint32_t *>(slow + (size_t)id * stride);
-            for (int w = 0; w * 4 < Ks; ++w) {
+            float D = part ? part[idx] : 0.0f;
+            const uint32_t *rec = reinterpret_cast<const uint32_t *>(items + (size_t)id * stride);
+            for (int w = w0; w * 4 < K; ++w) {
                 const uint32_t word = rec[w];
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (w * 4 + j < Ks) D += T[(w * 4 + j) * ICQ_LUT_W + ((word >> (8 * j)) & 0xffu)];
+                for (int j = 0; j < 4; ++j) {
+                    const int k = w * 4 + j;
+                    if (k >= k0 && k < K) {
+                        const float v = T[(k - k0) * ICQ_LUT_W + ((word >> (8 * j)) & 0xffu)];
+                        D = (k == 0) ? v : D + v;
+                    }
+                }
             }
             const u64 key = ((u64)order_bits(D) << 32) | id;
             if (key < s_bound) {
@@ -184,7 +193,7 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
                       int splits, u64 *keys, uint32_t *out_ids, float *out_dist, hipStream_t s) {
     if (Q == 0) return ICQ_OK;
     const int bufn = bufn_for(topk);
-    const size_t lds = sizeof(u64) * bufn + sizeof(float) * (size_t)ix->Ks * ICQ_LUT_W;
+    const size_t lds = sizeof(u64) * bufn + sizeof(float) * (size_t)(cand_part ? ix->Ks : ix->K) * ICQ_LUT_W;
     static bool attr_set = false;
     if (!attr_set) {
         ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&refine_kernel),
@@ -192,7 +201,7 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
         attr_set = true;
     }
     const unsigned grid = (unsigned)Q * (unsigned)splits;
-    refine_kernel<<<grid, RF_THREADS, lds, s>>>(ix->slow, ix->slow_stride, ix->K, ix->Kf, lut,
+    refine_kernel<<<grid, RF_THREADS, lds, s>>>(ix->items, ix->item_stride, ix->K, ix->Kf, lut,
                                                 cand_ids, cand_part, cand_count, cap, topk, bufn,
                                                 splits, keys, out_ids, out_dist);
     if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;

@@ -7,7 +7,9 @@
 //   scan_batch_kernel  - lanes = queries.  A tile of 64 queries keeps its fast
 //       tables in LDS as [k][code][query]; a wavefront walks the items, the
 //       sub-code is wave-uniform, so every table read is one conflict-free
-//       256-byte LDS row.  One pass over the codes serves 64 queries.
+//       256-byte LDS row.  One pass over the codes serves 64 queries.  It lists
+//       survivor ids only; crude distances are filled in afterwards for the
+//       listed ids when the caller wants them.
 //   scan_items_kernel  - lanes = items.  Any Kf; the tables of a few queries
 //       sit in LDS as [query][k][code], each lane gathers with its own
 //       sub-codes held in registers, survivors are compacted with a ballot.
@@ -50,17 +52,23 @@ __global__ __launch_bounds__(256) void transpose_fast_lut_kernel(const float *__
 }
 
 // ------------------------------------------------------------------ lanes = queries
-constexpr int SB_WAVES = 8;                 // wavefronts per block
+constexpr int SB_WAVES = 16;                // wavefronts per block (4 per SIMD: the loop is issue-bound)
 constexpr int SB_THREADS = SB_WAVES * 64;
-constexpr int SB_STAGE = 6;                 // staged survivors per lane before a flush
+constexpr int SB_SLOTS = 4;                 // staged survivor ids per lane and buffer (two buffers)
 constexpr int SB_GROUP = 256;               // items per wavefront step (one dword per lane and row)
+constexpr int SB_WORDS = 2;                 // lane-words (4 items each) looked up together
 
+// Survivor ids are staged per wavefront and lane in LDS ([buffer][slot][lane])
+// and moved to the query's global list in bulk: when some lane's buffer is full
+// the wavefront reserves list space for the whole buffer with ONE atomic per
+// lane, switches to the other buffer and keeps scanning; the reserved offset is
+// only needed when that buffer is written out at the next switch, so the
+// atomic's round trip overlaps the scan.
 template <int KF>
 __global__ __launch_bounds__(SB_THREADS, 1) void scan_batch_kernel(
     const uint8_t *__restrict__ fast, int64_t Npad, uint32_t N, const float *__restrict__ lutT,
     const float *__restrict__ thr, int Q, uint32_t *__restrict__ cand_ids,
-    float *__restrict__ cand_part, uint32_t *__restrict__ cand_count, int64_t cap,
-    uint32_t items_per_block) {
+    uint32_t *__restrict__ cand_count, int64_t cap, uint32_t items_per_block) {
     extern __shared__ float smem[];
     constexpr int LUT_FLOATS = KF * ICQ_LUT_W * 64;
     const int tid = threadIdx.x;
@@ -78,32 +86,42 @@ __global__ __launch_bounds__(SB_THREADS, 1) void scan_batch_kernel(
     const int q = tile * 64 + lane;
     const float t = q < Q ? thr[q] : -INFINITY;
     uint32_t *my_ids = cand_ids + (int64_t)q * cap;
-    float *my_part = cand_part + (int64_t)q * cap;
-    // per-wavefront staging area [slot][lane] of (id, P) pairs
-    uint2 *stage = reinterpret_cast<uint2 *>(smem + LUT_FLOATS) + wave * (64 * SB_STAGE);
-    int my_cnt = 0;
+    uint32_t *const st = reinterpret_cast<uint32_t *>(smem + LUT_FLOATS) + wave * (2 * SB_SLOTS * 64) + lane;
+    uint32_t *cur0 = st;                    // current buffer (this lane's column)
+    uint32_t *prev0 = st + SB_SLOTS * 64;   // buffer whose reservation is in flight
+    uint32_t *sp = cur0;                    // next free slot of the current buffer
+    uint32_t pend_cnt = 0, pend_base = 0;
 
-    auto flush = [&]() {
-        uint32_t base = 0;
-        if (my_cnt > 0) base = atomicAdd(&cand_count[q], (uint32_t)my_cnt);
+    auto retire = [&]() {   // write the previous buffer to the reserved list range
 #pragma unroll
-        for (int s = 0; s < SB_STAGE; ++s) {
-            if (s < my_cnt) {
-                uint64_t slot = (uint64_t)base + s;
-                if (slot < (uint64_t)cap) {
-                    uint2 e = stage[s * 64 + lane];
-                    my_ids[slot] = e.x;
-                    my_part[slot] = __uint_as_float(e.y);
-                }
+        for (int s = 0; s < SB_SLOTS; ++s) {
+            if ((uint32_t)s < pend_cnt) {
+                const uint64_t slot = (uint64_t)pend_base + s;
+                if (slot < (uint64_t)cap) my_ids[slot] = prev0[s * 64];
             }
         }
-        my_cnt = 0;
+    };
+    auto flush = [&]() {
+        retire();
+        pend_cnt = (uint32_t)(sp - cur0) >> 6;
+        pend_base = 0;
+        if (pend_cnt > 0) pend_base = atomicAdd(&cand_count[q], pend_cnt);
+        uint32_t *tmp = cur0;
+        cur0 = prev0;
+        prev0 = tmp;
+        sp = cur0;
     };
 
     const uint32_t begin = blockIdx.x * items_per_block;
     uint32_t end = begin + items_per_block;
     if (end > N || end < begin) end = N;
-    const float *lds = smem;
+    // one opaque base index per table so that no per-read offset arithmetic is left
+    int tab[KF];
+#pragma unroll
+    for (int k = 0; k < KF; ++k) {
+        tab[k] = k * ICQ_LUT_W * 64 + lane;
+        asm volatile("" : "+v"(tab[k]));
+    }
 
     uint32_t w[KF], wn[KF];
     uint32_t g = begin + wave * SB_GROUP;
@@ -119,39 +137,65 @@ __global__ __launch_bounds__(SB_THREADS, 1) void scan_batch_kernel(
             for (int k = 0; k < KF; ++k)
                 wn[k] = *reinterpret_cast<const uint32_t *>(fast + (int64_t)k * Npad + gn + lane * 4);
         }
+        // lane-words holding items below `end` (a word = 4 consecutive items)
         const int nl = (end - g + 3) / 4 < 64 ? (int)((end - g + 3) / 4) : 64;
-#pragma unroll 2
-        for (int l = 0; l < nl; ++l) {
-            uint32_t s[KF];
+        for (int l = 0; l < nl; l += SB_WORDS) {
+            uint32_t s[KF][SB_WORDS];
 #pragma unroll
-            for (int k = 0; k < KF; ++k) s[k] = __builtin_amdgcn_readlane(w[k], l);
+            for (int k = 0; k < KF; ++k)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                float P = lds[(0 * ICQ_LUT_W + ((s[0] >> (8 * j)) & 0xffu)) * 64 + lane];
+                for (int u = 0; u < SB_WORDS; ++u) s[k][u] = __builtin_amdgcn_readlane(w[k], l + u);
+            // all table reads of the step are issued before any result is used
+            float P[4 * SB_WORDS];
+#pragma unroll
+            for (int i = 0; i < 4 * SB_WORDS; ++i) {
+                P[i] = smem[tab[0] + (int)(((s[0][i >> 2] >> (8 * (i & 3))) & 0xffu) * 64)];
 #pragma unroll
                 for (int k = 1; k < KF; ++k)
-                    P += lds[(k * ICQ_LUT_W + ((s[k] >> (8 * j)) & 0xffu)) * 64 + lane];
-                const uint32_t id = g + l * 4 + j;
-                const bool hit = (P < t) && (id < end);
-                if (__builtin_amdgcn_ballot_w64(hit) != 0) {
-                    if (hit) {
-                        stage[my_cnt * 64 + lane] = make_uint2(id, __float_as_uint(P));
-                        ++my_cnt;
+                    P[i] += smem[tab[k] + (int)(((s[k][i >> 2] >> (8 * (i & 3))) & 0xffu) * 64)];
+            }
+#pragma unroll
+            for (int i = 0; i < 4 * SB_WORDS; ++i) {
+                if (__builtin_amdgcn_ballot_w64(P[i] < t) != 0) {
+                    const uint32_t id = g + l * 4 + i;
+                    if (P[i] < t && id < end) {
+                        *sp = id;
+                        sp += 64;
                     }
-                    if (__builtin_amdgcn_ballot_w64(my_cnt == SB_STAGE) != 0) flush();
+                    if (__builtin_amdgcn_ballot_w64(sp == cur0 + 64 * SB_SLOTS) != 0) flush();
                 }
             }
         }
 #pragma unroll
         for (int k = 0; k < KF; ++k) w[k] = wn[k];
     }
-    flush();
+    flush();    // reserve for the last buffer ...
+    retire();   // ... and write it out
+}
+
+// cand_part[q][s] = sum_{k<Kf} lut[q][k][code_k(id)] for the listed survivors, in
+// the same order of additions as the scan (so the value is the one it compared).
+__global__ __launch_bounds__(256) void fill_partials_kernel(
+    const uint8_t *__restrict__ fast, int64_t Npad, const float *__restrict__ lut, int K, int Kf,
+    const uint32_t *__restrict__ cand_ids, const uint32_t *__restrict__ cand_count, int64_t cap,
+    int blocks_per_query, float *__restrict__ cand_part) {
+    const int q = blockIdx.x / blocks_per_query, bq = blockIdx.x % blocks_per_query;
+    uint64_t n = cand_count[q];
+    if (n > (uint64_t)cap) n = (uint64_t)cap;
+    const float *T = lut + (int64_t)q * K * ICQ_LUT_W;
+    for (uint64_t s = (uint64_t)bq * blockDim.x + threadIdx.x; s < n;
+         s += (uint64_t)blocks_per_query * blockDim.x) {
+        const uint32_t id = cand_ids[(int64_t)q * cap + s];
+        float P = T[fast[id]];
+        for (int k = 1; k < Kf; ++k) P += T[k * ICQ_LUT_W + fast[(int64_t)k * Npad + id]];
+        cand_part[(int64_t)q * cap + s] = P;
+    }
 }
 
 // ------------------------------------------------------------------ lanes = items
 constexpr int SI_THREADS = 256;
 
-// Block (x = item chunk, y = query group of up to `nb` queries).  LDS holds
+// Block (x = query group of up to `nb` queries, y = item chunk).  LDS holds
 // lut[q][k][*] for the group's queries and k < Kf.  Each thread owns 4
 // consecutive items per step (one dword of sub-codes per fast row).
 template <int KF_MAX>
@@ -163,7 +207,7 @@ __global__ __launch_bounds__(SI_THREADS) void scan_items_kernel(
     extern __shared__ float smem[];
     const int tid = threadIdx.x;
     const uint32_t lane = lane_id();
-    const int qbase = blockIdx.y * nb;
+    const int qbase = blockIdx.x * nb;
     const int nq = (Q - qbase) < nb ? (Q - qbase) : nb;
 
     for (int i = tid; i < nq * Kf * ICQ_LUT_W; i += SI_THREADS) {
@@ -172,7 +216,7 @@ __global__ __launch_bounds__(SI_THREADS) void scan_items_kernel(
     }
     __syncthreads();
 
-    const uint32_t begin = blockIdx.x * items_per_block;
+    const uint32_t begin = blockIdx.y * items_per_block;
     uint32_t end = begin + items_per_block;
     if (end > N || end < begin) end = N;
 
@@ -204,7 +248,7 @@ __global__ __launch_bounds__(SI_THREADS) void scan_items_kernel(
                         uint64_t slot = (uint64_t)base + __builtin_popcountll(mask & ((1ull << lane) - 1));
                         if (slot < (uint64_t)cap) {
                             cand_ids[row + slot] = id;
-                            cand_part[row + slot] = P;
+                            if (cand_part) cand_part[row + slot] = P;
                         }
                     }
                 }
@@ -214,10 +258,10 @@ __global__ __launch_bounds__(SI_THREADS) void scan_items_kernel(
 }
 
 template <int KF>
-int launch_batch(const icq_index *ix, int Q, const float *thr, uint32_t *cand_ids, float *cand_part,
+int launch_batch(const icq_index *ix, int Q, const float *thr, uint32_t *cand_ids,
                  uint32_t *cand_count, int64_t cap, const float *lutT, hipStream_t s) {
     const int tiles = (Q + 63) / 64;
-    const size_t lds = sizeof(float) * KF * ICQ_LUT_W * 64 + sizeof(uint2) * SB_WAVES * 64 * SB_STAGE;
+    const size_t lds = sizeof(float) * KF * ICQ_LUT_W * 64 + sizeof(uint32_t) * SB_WAVES * 2 * SB_SLOTS * 64;
     static bool attr_set = false;   // idempotent; a race only repeats the call
     if (!attr_set) {
         ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_batch_kernel<KF>),
@@ -234,8 +278,7 @@ int launch_batch(const icq_index *ix, int Q, const float *thr, uint32_t *cand_id
     chunks = (ix->N + per - 1) / per;
     dim3 grid((unsigned)chunks, (unsigned)tiles);
     scan_batch_kernel<KF><<<grid, SB_THREADS, lds, s>>>(ix->fast, ix->Npad, (uint32_t)ix->N, lutT,
-                                                        thr, Q, cand_ids, cand_part, cand_count,
-                                                        cap, per);
+                                                        thr, Q, cand_ids, cand_count, cap, per);
     return icq_check_launch();
 }
 
@@ -252,9 +295,13 @@ int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *t
         const int tiles = (Q + 63) / 64;
         dim3 g((unsigned)tiles, (unsigned)ix->Kf);
         transpose_fast_lut_kernel<<<g, 256, 0, s>>>(lut, Q, ix->K, ix->Kf, lutT);
-        if (ix->Kf == 1)
-            return launch_batch<1>(ix, Q, thr, cand_ids, cand_part, cand_count, cap, lutT, s);
-        return launch_batch<2>(ix, Q, thr, cand_ids, cand_part, cand_count, cap, lutT, s);
+        int rc = ix->Kf == 1 ? launch_batch<1>(ix, Q, thr, cand_ids, cand_count, cap, lutT, s)
+                             : launch_batch<2>(ix, Q, thr, cand_ids, cand_count, cap, lutT, s);
+        if (rc != ICQ_OK || !cand_part) return rc;
+        const int bpq = (int)((cap + 255) / 256 < 32 ? (cap + 255) / 256 : 32);
+        fill_partials_kernel<<<(unsigned)Q * (unsigned)bpq, 256, 0, s>>>(
+            ix->fast, ix->Npad, lut, ix->K, ix->Kf, cand_ids, cand_count, cap, bpq, cand_part);
+        return icq_check_launch();
     }
 
     // lanes = items: group size limited by LDS (64 KB of tables per block)
@@ -271,7 +318,7 @@ int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *t
     if (chunks < 1) chunks = 1;
     uint32_t per = (uint32_t)(((ix->N + chunks - 1) / chunks + step - 1) / step * step);
     chunks = (ix->N + per - 1) / per;
-    dim3 grid((unsigned)chunks, (unsigned)groups);
+    dim3 grid((unsigned)groups, (unsigned)chunks);
 #define ICQ_SI_LAUNCH(KFM)                                                                          \
     do {                                                                                            \
         static bool attr_set = false;                                                               \

@@ -16,8 +16,7 @@ icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool
                        ICQ_ALIGN);
     L.ids_off = off;
     if (with_cands) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
-    L.part_off = off;
-    if (with_cands) off = icq_align_up(off + sizeof(float) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
+    L.part_off = off;   // the fused path keeps no crude distances
     L.count_off = off;
     if (with_cands) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q, ICQ_ALIGN);
     L.splits = icq_refine_splits(ix, Q, cap, topk);
@@ -64,14 +63,13 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
         float *lut = reinterpret_cast<float *>(ws + L.lut_off);
         float *lutT = reinterpret_cast<float *>(ws + L.lutT_off);
         uint32_t *ids = reinterpret_cast<uint32_t *>(ws + L.ids_off);
-        float *part = reinterpret_cast<float *>(ws + L.part_off);
         uint32_t *cnt = out_survivors ? out_survivors + q0 : reinterpret_cast<uint32_t *>(ws + L.count_off);
         unsigned long long *keys = reinterpret_cast<unsigned long long *>(ws + L.keys_off);
         int rc = icq_launch_build_lut(ix, queries + (int64_t)q0 * ix->d, nq, lut, s);
         if (rc != ICQ_OK) return rc;
-        rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, part, cnt, cap, lutT, s);
+        rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, nullptr, cnt, cap, lutT, s);
         if (rc != ICQ_OK) return rc;
-        rc = icq_launch_refine(ix, lut, nq, ids, part, cnt, cap, topk, L.splits, keys,
+        rc = icq_launch_refine(ix, lut, nq, ids, nullptr, cnt, cap, topk, L.splits, keys,
                                out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
         if (rc != ICQ_OK) return rc;
     }

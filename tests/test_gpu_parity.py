@@ -107,10 +107,11 @@ def test_storage_round_trip_is_bit_exact(gpu, K, Kf, N):
     torch, b = gpu
     cfg = synth.make("C0", N=N, Q=1, K=K, Kf=Kf, sigma=("geom", 0.7))
     g = Gpu(gpu, cfg)
-    out = torch.zeros((K, N), dtype=torch.uint8, device="cuda")
-    b.icq_index_export_codes(g.index, out)
-    torch.cuda.synchronize()
-    assert np.array_equal(out.cpu().numpy(), cfg["codes"])
+    for from_items in (0, 1):
+        out = torch.zeros((K, N), dtype=torch.uint8, device="cuda")
+        b.icq_index_export_codes(g.index, from_items, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), cfg["codes"])
 
 
 # ------------------------------------------------------------------ lookup tables
