@@ -106,7 +106,9 @@ int icq_build_lut(const icq_index *index, const float *queries, int Q, float *lu
  *   P[q][i] = sum_{k<Kf} lut[q][k][code_k(i)]   (k ascending, fp32)
  * and item i survives for query q iff P[q][i] < thresholds[q] (strict; +inf
  * keeps every item, NaN keeps none).  Survivors are appended to query q's
- * candidate list as (cand_ids, cand_partial = P).  cand_count [Q] is written
+ * candidate list as (cand_ids, cand_partial = P).  cand_partial may be NULL
+ * when the caller does not need the crude distances (the kernels list ids and
+ * fill in P afterwards, so this saves a pass).  cand_count [Q] is written
  * (not accumulated).  lut is [Q][K][256] as written by icq_build_lut.
  * 0 <= Q, 1 <= cap, Q*cap < 2^40.  Needs icq_workspace_bytes(index, Q, cap, 1).
  */
@@ -119,7 +121,9 @@ int icq_scan_fast(const icq_index *index, const float *lut, int Q, const float *
  * nearest-neighbour list (Sec. 3.4):
  *   D[q][i] = cand_partial + sum_{k=Kf..K-1} lut[q][k][code_k(i)]   (k ascending, fp32)
  * then the topk smallest (D, id) per query.  Reads min(cand_count[q], cap)
- * entries of each list.  1 <= topk <= ICQ_MAX_TOPK.
+ * entries of each list.  With cand_partial == NULL the same D is formed as the
+ * whole K-term sum (same order of additions, identical bits).
+ * 1 <= topk <= ICQ_MAX_TOPK.
  */
 int icq_refine(const icq_index *index, const float *lut, int Q, const uint32_t *cand_ids,
                const float *cand_partial, const uint32_t *cand_count, int64_t cap, int topk,

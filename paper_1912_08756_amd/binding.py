@@ -129,7 +129,7 @@ def icq_build_lut(index, queries, lut):
 
 
 def icq_scan_fast(index, lut, thresholds, cand_ids, cand_partial, cand_count, workspace):
-    Q, cap = cand_ids.shape
+    Q, cap = cand_ids.shape     # cand_partial may be None
     _check(load().icq_scan_fast(index.handle, _dev(lut, torch.float32, (Q, index.K, ICQ_LUT_W), "lut"), Q,
                                 _dev(thresholds, torch.float32, (Q,), "thresholds"),
                                 _dev(cand_ids, torch.int32, (Q, cap), "cand_ids"),

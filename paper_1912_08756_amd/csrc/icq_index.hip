@@ -98,7 +98,7 @@ ICQ_EXPORT int icq_index_create(icq_index **out, const float *codebooks, const u
     ix->d_pad = (d + 15) / 16 * 16;
     ix->item_stride = item_stride_for(K);
     ix->N = N;
-    ix->Npad = (N + 4095) / 4096 * 4096 + 4096;   // one spare block so read-ahead stays in bounds
+    ix->Npad = (N + 16383) / 16384 * 16384 + 16384;   // spare so that whole-step reads stay in bounds
     ix->cb = nullptr; ix->cnorm = nullptr; ix->fast = nullptr; ix->items = nullptr;
     hipDeviceProp_t prop;
     if (hipGetDevice(&ix->device) != hipSuccess ||

@@ -222,7 +222,7 @@ ICQ_EXPORT int icq_refine(const icq_index *ix, const float *lut, int Q, const ui
     if (!ix || Q < 0 || Q > (1 << 22) || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK)
         return ICQ_ERR_ARG;
     if (Q == 0) return ICQ_OK;
-    if (!lut || !cand_ids || !cand_part || !cand_count || !out_ids || !out_dist) return ICQ_ERR_ARG;
+    if (!lut || !cand_ids || !cand_count || !out_ids || !out_dist) return ICQ_ERR_ARG;
     if ((double)Q * (double)cap >= 1099511627776.0) return ICQ_ERR_ARG;
     icq_ws_layout L = icq_layout(ix, Q, cap, topk, false, false);
     if (L.total > 0 &&

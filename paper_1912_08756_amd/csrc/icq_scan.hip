@@ -192,6 +192,150 @@ __global__ __launch_bounds__(256) void fill_partials_kernel(
     }
 }
 
+// ------------------------------------------------------------------ lanes = items, few queries
+// Streaming form for one to a few queries per pass: every code byte is read
+// from HBM once per B queries, so the kernel is bound by the code stream.  Each
+// lane owns 16 consecutive items per step (one 128-bit load per fast row).  The
+// B queries' fast tables sit in LDS replicated 16 times, entry (k, c) copy r at
+// dword ((k*256 + c)*16 + r)*B: lane l reads copy l%16, and the 16 lanes the LDS
+// serves per clock then always fall into 16 different banks, whatever their
+// sub-codes.  The B values of an entry are adjacent, so one 32/64-bit read
+// serves all B queries.  Survivors are compacted per wavefront with a ballot
+// into an LDS staging row per query and flushed with one atomic per flush.
+constexpr int SS_SLOTS = 256;   // staged ids per wavefront and query
+
+template <int KF, int B>
+__global__ __launch_bounds__(1024) void scan_stream_kernel(
+    const uint8_t *__restrict__ fast, int64_t Npad, uint32_t N, const float *__restrict__ lut, int K,
+    const float *__restrict__ thr, int Q, uint32_t *__restrict__ cand_ids,
+    uint32_t *__restrict__ cand_count, int64_t cap, uint32_t items_per_block) {
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    constexpr int TAB_FLOATS = KF * ICQ_LUT_W * 16 * B;
+    const int tid = threadIdx.x;
+    const uint32_t lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nwaves = blockDim.x >> 6;
+    const int qbase = blockIdx.y * B;
+
+    for (int i = tid; i < KF * ICQ_LUT_W * B; i += blockDim.x) {
+        const int b = i / (KF * ICQ_LUT_W), e = i % (KF * ICQ_LUT_W);
+        const float v = (qbase + b) < Q ? lut[(int64_t)(qbase + b) * K * ICQ_LUT_W + e] : INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) smem[(e * 16 + r) * B + b] = v;
+    }
+    float t[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) t[b] = (qbase + b) < Q ? thr[qbase + b] : -INFINITY;
+    uint32_t *stage = reinterpret_cast<uint32_t *>(smem + TAB_FLOATS) + wave * (B * SS_SLOTS);
+    uint32_t cnt[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) cnt[b] = 0;
+    __syncthreads();
+
+    auto flush = [&](int b) {   // wave-uniform b and cnt[b]
+        const uint32_t n = cnt[b];
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(&cand_count[qbase + b], n);
+        base = __builtin_amdgcn_readfirstlane(base);
+        uint32_t *dst = cand_ids + (int64_t)(qbase + b) * cap;
+        for (uint32_t i = lane; i < n; i += 64) {
+            const uint64_t slot = (uint64_t)base + i;
+            if (slot < (uint64_t)cap) dst[slot] = stage[b * SS_SLOTS + i];
+        }
+        cnt[b] = 0;
+    };
+
+    const uint32_t begin = blockIdx.x * items_per_block;
+    uint32_t end = begin + items_per_block;
+    if (end > N || end < begin) end = N;
+    const float *tab = smem + (lane & 15) * B;
+    const uint32_t step = (uint32_t)nwaves * 1024u;
+
+    uint4 w[KF], wn[KF];
+    uint32_t g = begin + wave * 1024u;
+    if (g < end) {
+#pragma unroll
+        for (int k = 0; k < KF; ++k)
+            w[k] = *reinterpret_cast<const uint4 *>(fast + (int64_t)k * Npad + g + lane * 16);
+    }
+    for (; g < end; g += step) {
+        const uint32_t gn = g + step;
+        if (gn < end) {   // read ahead; rows are padded so a whole step is always addressable
+#pragma unroll
+            for (int k = 0; k < KF; ++k)
+                wn[k] = *reinterpret_cast<const uint4 *>(fast + (int64_t)k * Npad + gn + lane * 16);
+        }
+        const uint32_t id0 = g + lane * 16;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            float P[B];
+#pragma unroll
+            for (int k = 0; k < KF; ++k) {
+                const uint32_t word = j < 4 ? w[k].x : j < 8 ? w[k].y : j < 12 ? w[k].z : w[k].w;
+                const uint32_t c = (word >> (8 * (j & 3))) & 0xffu;
+                const float *e = tab + (k * ICQ_LUT_W + c) * 16 * B;
+                if (B == 1) {
+                    P[0] = k == 0 ? e[0] : P[0] + e[0];
+                } else if (B == 2) {
+                    const float2 v = *reinterpret_cast<const float2 *>(e);
+                    P[0] = k == 0 ? v.x : P[0] + v.x;
+                    P[1 % B] = k == 0 ? v.y : P[1 % B] + v.y;
+                } else {
+                    const float4 v = *reinterpret_cast<const float4 *>(e);
+                    P[0] = k == 0 ? v.x : P[0] + v.x;
+                    P[1 % B] = k == 0 ? v.y : P[1 % B] + v.y;
+                    P[2 % B] = k == 0 ? v.z : P[2 % B] + v.z;
+                    P[3 % B] = k == 0 ? v.w : P[3 % B] + v.w;
+                }
+            }
+            const uint32_t id = id0 + j;
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const bool hit = (P[b] < t[b]) && (id < end);
+                const uint64_t mask = __builtin_amdgcn_ballot_w64(hit);
+                if (mask != 0) {
+                    if (hit)
+                        stage[b * SS_SLOTS + cnt[b] + __builtin_popcountll(mask & ((1ull << lane) - 1))] = id;
+                    cnt[b] += (uint32_t)__builtin_popcountll(mask);
+                    if (cnt[b] > SS_SLOTS - 64) flush(b);
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < KF; ++k) w[k] = wn[k];
+    }
+#pragma unroll
+    for (int b = 0; b < B; ++b)
+        if (cnt[b] > 0) flush(b);
+}
+
+template <int KF, int B>
+int launch_stream(const icq_index *ix, const float *lut, int Q, const float *thr, uint32_t *cand_ids,
+                  uint32_t *cand_count, int64_t cap, hipStream_t s) {
+    const size_t tab = sizeof(float) * KF * ICQ_LUT_W * 16 * B;
+    const int threads = tab > 65536 ? 1024 : 512;         // two blocks per CU when the tables allow
+    const size_t lds = tab + sizeof(uint32_t) * (threads / 64) * B * SS_SLOTS;
+    static bool attr_set = false;
+    if (!attr_set) {
+        ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_stream_kernel<KF, B>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 163840));
+        attr_set = true;
+    }
+    const int groups = (Q + B - 1) / B;
+    const uint32_t step = (uint32_t)(threads / 64) * 1024u;
+    // one wave of equally loaded blocks: the chip is filled once and every block streams a long run
+    int64_t chunks = ((int64_t)ix->num_cu * (threads == 1024 ? 1 : 2) + groups - 1) / groups;
+    int64_t max_chunks = (ix->N + step - 1) / step;
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (chunks < 1) chunks = 1;
+    uint32_t per = (uint32_t)(((ix->N + chunks - 1) / chunks + step - 1) / step * step);
+    chunks = (ix->N + per - 1) / per;
+    dim3 grid((unsigned)chunks, (unsigned)groups);
+    scan_stream_kernel<KF, B><<<grid, threads, lds, s>>>(ix->fast, ix->Npad, (uint32_t)ix->N, lut,
+                                                         ix->K, thr, Q, cand_ids, cand_count, cap, per);
+    return icq_check_launch();
+}
+
 // ------------------------------------------------------------------ lanes = items
 constexpr int SI_THREADS = 256;
 
@@ -304,6 +448,25 @@ int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *t
         return icq_check_launch();
     }
 
+    if (ix->Kf <= 4 && Q <= 4) {
+        int rc;
+        switch (ix->Kf * 2 + (Q >= 2 ? 1 : 0)) {
+            case 2: rc = launch_stream<1, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 3: rc = launch_stream<1, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 4: rc = launch_stream<2, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 5: rc = launch_stream<2, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 6: rc = launch_stream<3, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 7: rc = launch_stream<3, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 8: rc = launch_stream<4, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            default: rc = launch_stream<4, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+        }
+        if (rc != ICQ_OK || !cand_part) return rc;
+        const int bpq = (int)((cap + 255) / 256 < 256 ? (cap + 255) / 256 : 256);
+        fill_partials_kernel<<<(unsigned)Q * (unsigned)bpq, 256, 0, s>>>(
+            ix->fast, ix->Npad, lut, ix->K, ix->Kf, cand_ids, cand_count, cap, bpq, cand_part);
+        return icq_check_launch();
+    }
+
     // lanes = items: group size limited by LDS (64 KB of tables per block)
     int nb = 64 / ix->Kf;
     if (nb < 1) nb = 1;
@@ -344,7 +507,7 @@ ICQ_EXPORT int icq_scan_fast(const icq_index *ix, const float *lut, int Q, const
                              int64_t cap, void *workspace, size_t workspace_bytes, void *stream) {
     if (!ix || Q < 0 || Q > (1 << 22) || cap < 1) return ICQ_ERR_ARG;
     if (Q == 0) return ICQ_OK;
-    if (!lut || !thresholds || !cand_ids || !cand_part || !cand_count) return ICQ_ERR_ARG;
+    if (!lut || !thresholds || !cand_ids || !cand_count) return ICQ_ERR_ARG;
     if ((double)Q * (double)cap >= 1099511627776.0) return ICQ_ERR_ARG;
     icq_ws_layout L = icq_layout(ix, Q, cap, 1, false, false);
     if (!workspace || ((uintptr_t)workspace % ICQ_ALIGN) != 0 || workspace_bytes < L.total)

@@ -53,18 +53,18 @@ class Gpu:
         self.b.icq_build_lut(self.index, self.queries, lut)
         return lut
 
-    def scan(self, lut, thr, cap):
+    def scan(self, lut, thr, cap, want_partial=True):
         torch = self.torch
         Q = lut.shape[0]
         ids = torch.full((Q, cap), -1, dtype=torch.int32, device="cuda")
-        part = torch.full((Q, cap), float("nan"), dtype=torch.float32, device="cuda")
+        part = torch.full((Q, cap), float("nan"), dtype=torch.float32, device="cuda") if want_partial else None
         cnt = torch.full((Q,), 12345, dtype=torch.int32, device="cuda")
         ws = self.workspace(Q, cap, 1)
         self.b.icq_scan_fast(self.index, lut, _dev(torch, thr), ids, part, cnt, ws)
         torch.cuda.synchronize()
         return ids, part, cnt
 
-    def refine(self, lut, ids, part, cnt, topk):
+    def refine(self, lut, ids, part, cnt, topk):   # part may be None: full K-term sum
         torch = self.torch
         Q, cap = ids.shape
         out_ids = torch.empty((Q, topk), dtype=torch.int32, device="cuda")
@@ -134,7 +134,12 @@ SCAN_CASES = [
     # name, N, Q, overrides, threshold rule
     ("C0", 10_000, 100, {}, ("kth", 20, 1.5)),            # lanes = queries, Kf = 1
     ("C1", 50_003, 130, {}, ("q", 0.01)),                 # lanes = queries, Kf = 2, ragged tail
-    ("C1", 5_000, 3, {}, ("q", 0.02)),                    # lanes = items (few queries)
+    ("C1", 5_000, 3, {}, ("q", 0.02)),                    # streaming kernel, two query groups
+    ("C1", 40_007, 1, {}, ("q", 0.01)),                   # streaming kernel, one query, Kf = 2
+    ("C4", 70_001, 2, dict(K=6), ("q", 0.01)),            # streaming kernel, Kf = 4, two queries
+    ("C4", 33_000, 1, dict(K=5), ("q", 0.3)),             # streaming kernel, many survivors: flushes
+    ("C0", 9_000, 4, {}, ("q", 0.01)),                    # streaming kernel, Kf = 1
+    ("C2", 9_000, 2, dict(d=32, Kf=3), ("q", 0.01)),      # streaming kernel, Kf = 3
     ("C2", 20_001, 70, dict(d=64), ("q", 0.01)),          # Kf = 4
     ("C3", 60_000, 64, {}, ("q", 0.01)),                  # clustered codes: ties and bursts
     ("C4", 30_000, 9, dict(Kf=6), ("q", 0.05)),           # Kf = 6
@@ -217,6 +222,11 @@ def test_refine_matches_oracle(gpu, name, N, Q, over, rule, topk):
     out_ids, out_dist = g.refine(lut, ids, part, cnt, topk)
     for q in range(Q):
         check_topk(P[q], D[q], thr[q], topk, out_ids[q], out_dist[q])
+    # without crude distances: ids only from stage 1, whole sum in stage 2, identical bits
+    ids2, none, cnt2 = g.scan(lut, thr, cap, want_partial=False)
+    assert none is None and np.array_equal(_u32(cnt2), _u32(cnt))
+    out_ids2, out_dist2 = g.refine(lut, ids2, None, cnt2, topk)
+    assert np.array_equal(out_ids2, out_ids) and np.array_equal(out_dist2, out_dist)
 
 
 # ------------------------------------------------------------------ whole path
