@@ -200,16 +200,24 @@ __global__ __launch_bounds__(256) void fill_partials_kernel(
 // dword ((k*256 + c)*16 + r)*B: lane l reads copy l%16, and the 16 lanes the LDS
 // serves per clock then always fall into 16 different banks, whatever their
 // sub-codes.  The B values of an entry are adjacent, so one 32/64-bit read
-// serves all B queries.  Survivors are compacted per wavefront with a ballot
-// into an LDS staging row per query and flushed with one atomic per flush.
-constexpr int SS_SLOTS = 256;   // staged ids per wavefront and query
+// serves all B queries.
+// Survivors: a lane collects the hit bits of its 16 items; a wavefront compacts
+// them with ballots into a block-wide LDS list (one LDS atomic per round), and
+// the block moves the list to the query's global list with ONE global atomic
+// per flush -- all blocks add to the same counter, and that address only takes
+// a few million atomics per second.  If a burst does not fit the LDS list the
+// wavefront writes straight to the global list instead.
+constexpr int SS_HALF = 8;        // items per lane whose table reads are issued together
+constexpr int SS_CHECK = 8;       // steps between block-wide flush checks
+constexpr uint32_t SS_NONE = 0xFFFFFFFFu;
 
 template <int KF, int B>
 __global__ __launch_bounds__(1024) void scan_stream_kernel(
     const uint8_t *__restrict__ fast, int64_t Npad, uint32_t N, const float *__restrict__ lut, int K,
     const float *__restrict__ thr, int Q, uint32_t *__restrict__ cand_ids,
-    uint32_t *__restrict__ cand_count, int64_t cap, uint32_t items_per_block) {
+    uint32_t *__restrict__ cand_count, int64_t cap, uint32_t items_per_block, uint32_t stage_cap) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
+    __shared__ uint32_t s_cnt[B], s_valid[B], s_base[B];
     constexpr int TAB_FLOATS = KF * ICQ_LUT_W * 16 * B;
     const int tid = threadIdx.x;
     const uint32_t lane = lane_id();
@@ -223,33 +231,25 @@ __global__ __launch_bounds__(1024) void scan_stream_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) smem[(e * 16 + r) * B + b] = v;
     }
+    if (tid < B) {
+        s_cnt[tid] = 0;
+        s_valid[tid] = SS_NONE;
+    }
     float t[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) t[b] = (qbase + b) < Q ? thr[qbase + b] : -INFINITY;
-    uint32_t *stage = reinterpret_cast<uint32_t *>(smem + TAB_FLOATS) + wave * (B * SS_SLOTS);
-    uint32_t cnt[B];
-#pragma unroll
-    for (int b = 0; b < B; ++b) cnt[b] = 0;
+    uint32_t *stage = reinterpret_cast<uint32_t *>(smem + TAB_FLOATS);   // [B][stage_cap]
     __syncthreads();
-
-    auto flush = [&](int b) {   // wave-uniform b and cnt[b]
-        const uint32_t n = cnt[b];
-        uint32_t base = 0;
-        if (lane == 0) base = atomicAdd(&cand_count[qbase + b], n);
-        base = __builtin_amdgcn_readfirstlane(base);
-        uint32_t *dst = cand_ids + (int64_t)(qbase + b) * cap;
-        for (uint32_t i = lane; i < n; i += 64) {
-            const uint64_t slot = (uint64_t)base + i;
-            if (slot < (uint64_t)cap) dst[slot] = stage[b * SS_SLOTS + i];
-        }
-        cnt[b] = 0;
-    };
 
     const uint32_t begin = blockIdx.x * items_per_block;
     uint32_t end = begin + items_per_block;
     if (end > N || end < begin) end = N;
-    const float *tab = smem + (lane & 15) * B;
+    // byte offset of this lane's copy inside an entry; an entry is 16 copies of B floats
+    constexpr int ENTRY_SHIFT = B == 1 ? 6 : B == 2 ? 7 : 8;
+    const uint32_t copy_off = (lane & 15) * (4 * B);
+    const char *tab_bytes = reinterpret_cast<const char *>(smem);
     const uint32_t step = (uint32_t)nwaves * 1024u;
+    const uint32_t nsteps = end > begin ? (end - begin + step - 1) / step : 0;   // same for every wavefront
 
     uint4 w[KF], wn[KF];
     uint32_t g = begin + wave * 1024u;
@@ -258,73 +258,157 @@ __global__ __launch_bounds__(1024) void scan_stream_kernel(
         for (int k = 0; k < KF; ++k)
             w[k] = *reinterpret_cast<const uint4 *>(fast + (int64_t)k * Npad + g + lane * 16);
     }
-    for (; g < end; g += step) {
-        const uint32_t gn = g + step;
-        if (gn < end) {   // read ahead; rows are padded so a whole step is always addressable
+    for (uint32_t it = 0; it < nsteps; ++it, g += step) {
+        if (g < end) {
+            const uint32_t gn = g + step;
+            if (gn < end) {   // read ahead; rows are padded so a whole step is always addressable
 #pragma unroll
-            for (int k = 0; k < KF; ++k)
-                wn[k] = *reinterpret_cast<const uint4 *>(fast + (int64_t)k * Npad + gn + lane * 16);
-        }
-        const uint32_t id0 = g + lane * 16;
+                for (int k = 0; k < KF; ++k)
+                    wn[k] = *reinterpret_cast<const uint4 *>(fast + (int64_t)k * Npad + gn + lane * 16);
+            }
+            const uint32_t id0 = g + lane * 16;
+            uint32_t hm[B];   // hit bits of this lane's 16 items, one mask per query
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            float P[B];
+            for (int b = 0; b < B; ++b) hm[b] = 0;
 #pragma unroll
-            for (int k = 0; k < KF; ++k) {
-                const uint32_t word = j < 4 ? w[k].x : j < 8 ? w[k].y : j < 12 ? w[k].z : w[k].w;
-                const uint32_t c = (word >> (8 * (j & 3))) & 0xffu;
-                const float *e = tab + (k * ICQ_LUT_W + c) * 16 * B;
-                if (B == 1) {
-                    P[0] = k == 0 ? e[0] : P[0] + e[0];
-                } else if (B == 2) {
-                    const float2 v = *reinterpret_cast<const float2 *>(e);
-                    P[0] = k == 0 ? v.x : P[0] + v.x;
-                    P[1 % B] = k == 0 ? v.y : P[1 % B] + v.y;
-                } else {
-                    const float4 v = *reinterpret_cast<const float4 *>(e);
-                    P[0] = k == 0 ? v.x : P[0] + v.x;
-                    P[1 % B] = k == 0 ? v.y : P[1 % B] + v.y;
-                    P[2 % B] = k == 0 ? v.z : P[2 % B] + v.z;
-                    P[3 % B] = k == 0 ? v.w : P[3 % B] + v.w;
+            for (int h = 0; h < 16; h += SS_HALF) {
+                // phase 1: every table address of the half step
+                uint32_t off[SS_HALF][KF];
+#pragma unroll
+                for (int jj = 0; jj < SS_HALF; ++jj) {
+                    const int j = h + jj;
+#pragma unroll
+                    for (int k = 0; k < KF; ++k) {
+                        const uint32_t word = j < 4 ? w[k].x : j < 8 ? w[k].y : j < 12 ? w[k].z : w[k].w;
+                        const int sh = 8 * (j & 3) - ENTRY_SHIFT;   // code byte -> entry offset
+                        const uint32_t pos = sh >= 0 ? (word >> (sh >= 0 ? sh : 0)) : (word << (sh < 0 ? -sh : 0));
+                        off[jj][k] = (pos & (0xffu << ENTRY_SHIFT)) | copy_off;
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // phase 2: all reads in flight together
+                float v[SS_HALF][KF][B];
+#pragma unroll
+                for (int jj = 0; jj < SS_HALF; ++jj) {
+#pragma unroll
+                    for (int k = 0; k < KF; ++k) {
+                        const char *e = tab_bytes + k * (ICQ_LUT_W * 64 * B) + off[jj][k];
+                        if (B == 1) {
+                            v[jj][k][0] = *reinterpret_cast<const float *>(e);
+                        } else if (B == 2) {
+                            const float2 x = *reinterpret_cast<const float2 *>(e);
+                            v[jj][k][0] = x.x;
+                            v[jj][k][1 % B] = x.y;
+                        } else {
+                            const float4 x = *reinterpret_cast<const float4 *>(e);
+                            v[jj][k][0] = x.x;
+                            v[jj][k][1 % B] = x.y;
+                            v[jj][k][2 % B] = x.z;
+                            v[jj][k][3 % B] = x.w;
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // phase 3: sums (k ascending) and hit bits
+#pragma unroll
+                for (int jj = 0; jj < SS_HALF; ++jj) {
+#pragma unroll
+                    for (int b = 0; b < B; ++b) {
+                        float P = v[jj][0][b];
+#pragma unroll
+                        for (int k = 1; k < KF; ++k) P += v[jj][k][b];
+                        hm[b] |= (P < t[b]) ? (1u << (h + jj)) : 0u;
+                    }
                 }
             }
-            const uint32_t id = id0 + j;
+            if (id0 + 16 > end) {   // ragged tail: drop bits of items at or beyond `end`
+                const uint32_t valid = id0 < end ? (1u << (end - id0)) - 1u : 0u;
+#pragma unroll
+                for (int b = 0; b < B; ++b) hm[b] &= valid;
+            }
+            // compaction: each round appends every lane's lowest remaining hit
 #pragma unroll
             for (int b = 0; b < B; ++b) {
-                const bool hit = (P[b] < t[b]) && (id < end);
-                const uint64_t mask = __builtin_amdgcn_ballot_w64(hit);
-                if (mask != 0) {
-                    if (hit)
-                        stage[b * SS_SLOTS + cnt[b] + __builtin_popcountll(mask & ((1ull << lane) - 1))] = id;
-                    cnt[b] += (uint32_t)__builtin_popcountll(mask);
-                    if (cnt[b] > SS_SLOTS - 64) flush(b);
+                uint64_t mask = __builtin_amdgcn_ballot_w64(hm[b] != 0);
+                while (mask != 0) {
+                    const uint32_t n = (uint32_t)__builtin_popcountll(mask);
+                    const int leader = __builtin_ctzll(mask);
+                    uint32_t old = 0;
+                    if ((int)lane == leader) old = atomicAdd(&s_cnt[b], n);
+                    old = __builtin_amdgcn_readlane(old, leader);
+                    const uint32_t mine = old + __builtin_popcountll(mask & ((1ull << lane) - 1));
+                    if (old + n <= stage_cap) {
+                        if (hm[b] != 0) stage[b * stage_cap + mine] = id0 + (uint32_t)__builtin_ctz(hm[b]);
+                    } else {   // burst: straight to the global list
+                        uint32_t gb = 0;
+                        if ((int)lane == leader) {
+                            atomicMin(&s_valid[b], old);
+                            gb = atomicAdd(&cand_count[qbase + b], n);
+                        }
+                        gb = __builtin_amdgcn_readlane(gb, leader);
+                        const uint64_t slot = (uint64_t)gb + (mine - old);
+                        if (hm[b] != 0 && slot < (uint64_t)cap)
+                            cand_ids[(int64_t)(qbase + b) * cap + slot] = id0 + (uint32_t)__builtin_ctz(hm[b]);
+                    }
+                    hm[b] &= hm[b] - 1;
+                    mask = __builtin_amdgcn_ballot_w64(hm[b] != 0);
                 }
             }
+#pragma unroll
+            for (int k = 0; k < KF; ++k) w[k] = wn[k];
         }
+        // block-wide flush check (every wavefront takes the same path: nsteps is block-uniform)
+        if ((it % SS_CHECK) == SS_CHECK - 1 || it == nsteps - 1) {
+            __syncthreads();
+            uint32_t nb[B];
+            bool any = false;
 #pragma unroll
-        for (int k = 0; k < KF; ++k) w[k] = wn[k];
+            for (int b = 0; b < B; ++b) {
+                const uint32_t c = s_cnt[b], vld = s_valid[b];
+                nb[b] = c < vld ? c : vld;      // entries below the first burst are staged
+                if (nb[b] > stage_cap) nb[b] = stage_cap;
+                any |= (c > stage_cap / 2) || (it == nsteps - 1 && c > 0);
+            }
+            __syncthreads();   // nobody appends again before every thread has read the counters
+            if (any) {   // uniform: everyone read the same counters between the two barriers
+                if (tid < B) s_base[tid] = nb[tid] ? atomicAdd(&cand_count[qbase + tid], nb[tid]) : 0;
+                __syncthreads();
+#pragma unroll
+                for (int b = 0; b < B; ++b) {
+                    const uint32_t base = s_base[b];
+                    uint32_t *dst = cand_ids + (int64_t)(qbase + b) * cap;
+                    for (uint32_t i = tid; i < nb[b]; i += blockDim.x) {
+                        const uint64_t slot = (uint64_t)base + i;
+                        if (slot < (uint64_t)cap) dst[slot] = stage[b * stage_cap + i];
+                    }
+                }
+                if (tid < B) {
+                    s_cnt[tid] = 0;
+                    s_valid[tid] = SS_NONE;
+                }
+                __syncthreads();
+            }
+        }
     }
-#pragma unroll
-    for (int b = 0; b < B; ++b)
-        if (cnt[b] > 0) flush(b);
 }
 
 template <int KF, int B>
 int launch_stream(const icq_index *ix, const float *lut, int Q, const float *thr, uint32_t *cand_ids,
                   uint32_t *cand_count, int64_t cap, hipStream_t s) {
     const size_t tab = sizeof(float) * KF * ICQ_LUT_W * 16 * B;
-    const int threads = tab > 65536 ? 1024 : 512;         // two blocks per CU when the tables allow
-    const size_t lds = tab + sizeof(uint32_t) * (threads / 64) * B * SS_SLOTS;
+    const int threads = 1024;
+    const uint32_t stage_cap = tab * 1 + 32768 * B <= 163840 - 64 ? 8192 : 4000;   // ids per query staged in LDS
+    const size_t lds = tab + sizeof(uint32_t) * B * stage_cap;
     static bool attr_set = false;
     if (!attr_set) {
         ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_stream_kernel<KF, B>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 163840));
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 163840 - 64));
         attr_set = true;
     }
     const int groups = (Q + B - 1) / B;
     const uint32_t step = (uint32_t)(threads / 64) * 1024u;
     // one wave of equally loaded blocks: the chip is filled once and every block streams a long run
-    int64_t chunks = ((int64_t)ix->num_cu * (threads == 1024 ? 1 : 2) + groups - 1) / groups;
+    int64_t chunks = ((int64_t)ix->num_cu + groups - 1) / groups;
     int64_t max_chunks = (ix->N + step - 1) / step;
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks < 1) chunks = 1;
@@ -332,7 +416,8 @@ int launch_stream(const icq_index *ix, const float *lut, int Q, const float *thr
     chunks = (ix->N + per - 1) / per;
     dim3 grid((unsigned)chunks, (unsigned)groups);
     scan_stream_kernel<KF, B><<<grid, threads, lds, s>>>(ix->fast, ix->Npad, (uint32_t)ix->N, lut,
-                                                         ix->K, thr, Q, cand_ids, cand_count, cap, per);
+                                                         ix->K, thr, Q, cand_ids, cand_count, cap, per,
+                                                         stage_cap);
     return icq_check_launch();
 }
 
