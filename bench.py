@@ -79,40 +79,44 @@ def event_time_ms(torch, fn, reps):
 
 
 def hbm_leg(torch, b, steps, warmup):
-    """Stage-1 scan of a 400 MB fast-code array (N = 1e8, Kf = 4) for a single
-    query: every code byte is read once per query, so the kernel is HBM-bound."""
+    """Stage-1 scan of a 400 MB fast-code array (N = 1e8, Kf = 4) for one and for two
+    queries per pass: every code byte is read from HBM once per pass, so the kernel
+    is bound by the code stream."""
+    from paper_1912_08756_amd import synth
     N, Kf, d = 100_000_000, 4, 96
     g = torch.Generator(device="cuda")
     g.manual_seed(4)
     codes = torch.randint(0, 256, (Kf, N), dtype=torch.uint8, device="cuda", generator=g)
-    from paper_1912_08756_amd import synth
     cb = torch.from_numpy(synth.make_codebooks(Kf, 256, d, synth.sigmas(("geom", 0.8), Kf), 4)).cuda()
-    src = codes[:, :1].long()
-    q = sum(cb[k, src[k, 0]] for k in range(Kf)).reshape(1, d).contiguous()
-    q = q + 0.05 * q.norm() / math.sqrt(d) * torch.randn((1, d), device="cuda", generator=g)
-    thr = sampled_thresholds(torch, b, cb, codes, q, Kf, SURVIVE_FRAC, 65536, 5)
     idx = b.icq_index_create(cb, codes, Kf)
-    cap = int(N * SURVIVE_FRAC * 2)
-    lut = torch.empty((1, Kf, 256), dtype=torch.float32, device="cuda")
-    b.icq_build_lut(idx, q, lut)
-    ids = torch.empty((1, cap), dtype=torch.int32, device="cuda")
-    part = torch.empty((1, cap), dtype=torch.float32, device="cuda")
-    cnt = torch.empty((1,), dtype=torch.int32, device="cuda")
-    ws = torch.empty(b.icq_workspace_bytes(idx, 1, cap, 1), dtype=torch.uint8, device="cuda")
+    out = {}
+    for Q in (1, 2):
+        src = codes[:, :Q].long()
+        q = torch.stack([sum(cb[k, src[k, i]] for k in range(Kf)) for i in range(Q)]).contiguous()
+        q = q + 0.05 * q.norm(dim=1, keepdim=True) / math.sqrt(d) * torch.randn((Q, d), device="cuda", generator=g)
+        thr = sampled_thresholds(torch, b, cb, codes, q, Kf, SURVIVE_FRAC, 65536, 5)
+        cap = int(N * SURVIVE_FRAC * 2)
+        lut = torch.empty((Q, Kf, 256), dtype=torch.float32, device="cuda")
+        b.icq_build_lut(idx, q, lut)
+        ids = torch.empty((Q, cap), dtype=torch.int32, device="cuda")
+        cnt = torch.empty((Q,), dtype=torch.int32, device="cuda")
+        ws = torch.empty(b.icq_workspace_bytes(idx, Q, cap, 1), dtype=torch.uint8, device="cuda")
 
-    def run():
-        b.icq_scan_fast(idx, lut, thr, ids, part, cnt, ws)
-    for _ in range(warmup):
-        run()
-    torch.cuda.synchronize()
-    ms = event_time_ms(torch, run, steps)
-    surv = int(cnt.item())
-    alg_bytes = Kf * N + 4 * Kf * 256 + 8 * surv
-    achieved = alg_bytes / (ms * 1e-3) / 1e9
-    return {"bound": "hbm", "kernel": "scan_items_kernel", "achieved": round(achieved, 1),
-            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": None, "ms": round(ms, 4),
-            "workload": "fast codes [4][1e8] u8 (400 MB), 1 query, survivors %d" % surv}
+        def run():
+            b.icq_scan_fast(idx, lut, thr, ids, None, cnt, ws)
+        for _ in range(warmup):
+            run()
+        torch.cuda.synchronize()
+        ms = event_time_ms(torch, run, steps)
+        surv = int(cnt.sum().item())
+        alg_bytes = Kf * N + 4 * Q * Kf * 256 + 4 * surv      # codes once, tables, survivor ids
+        achieved = alg_bytes / (ms * 1e-3) / 1e9
+        out["B%d" % Q] = {"bound": "hbm", "kernel": "scan_stream_kernel<4,%d>" % Q, "achieved": round(achieved, 1),
+                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                          "traffic": None, "ms": round(ms, 4),
+                          "workload": "fast codes [4][1e8] u8 (400 MB), %d quer%s per pass, %d survivors"
+                                      % (Q, "y" if Q == 1 else "ies", surv)}
+    return out
 
 
 def cpu_baseline(cfg, thr_np, gpu_ids, gpu_dist, target_s=15.0):

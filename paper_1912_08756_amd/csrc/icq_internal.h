@@ -26,7 +26,7 @@ struct icq_index {
 
 // Sub-buffers carved out of the caller's workspace for one query batch.
 struct icq_ws_layout {
-    size_t lut_off, lutT_off, ids_off, part_off, count_off, keys_off, total;
+    size_t lut_off, lutT_off, ids_off, rec_off, count_off, keys_off, total;
     int splits;                // stage-2 blocks per query
 };
 
@@ -44,14 +44,17 @@ int icq_launch_build_lut(const icq_index *ix, const float *queries, int Q, float
                          hipStream_t s);
 // cand_part == nullptr: the crude distances are not materialised (the fused path
 // recomputes the full sum in stage 2 from the item records).
+// cand_rec != nullptr: the scan may also write each survivor's item record next
+// to its id ([Q][cap][item_stride/4] words) and says so through *rec_written.
 int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
-                    uint32_t *cand_ids, float *cand_part, uint32_t *cand_count, int64_t cap,
-                    float *lutT, hipStream_t s);
+                    uint32_t *cand_ids, float *cand_part, uint32_t *cand_rec, bool *rec_written,
+                    uint32_t *cand_count, int64_t cap, float *lutT, hipStream_t s);
 // cand_part == nullptr: D is the full K-term sum; else D = cand_part + slow terms.
+// cand_rec != nullptr: item records come from the candidate list instead of a gather.
 int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32_t *cand_ids,
-                      const float *cand_part, const uint32_t *cand_count, int64_t cap, int topk,
-                      int splits, unsigned long long *keys, uint32_t *out_ids, float *out_dist,
-                      hipStream_t s);
+                      const float *cand_part, const uint32_t *cand_rec, const uint32_t *cand_count,
+                      int64_t cap, int topk, int splits, unsigned long long *keys, uint32_t *out_ids,
+                      float *out_dist, hipStream_t s);
 
 #define ICQ_HIP_TRY(expr)                      \
     do {                                       \

@@ -174,7 +174,242 @@ __global__ __launch_bounds__(RF_THREADS) void merge_kernel(const u64 *__restrict
 
 int bufn_for(int topk) { return topk <= 256 ? 2048 : 4096; }
 
+// ------------------------------------------------------------------ bounded stream + radix select
+// One block owns one slice of one query's candidate list, of any length, and
+// walks it in chunks of RS_FIRST candidates.  The distances of the first chunk
+// go to LDS as order-preserving bits; an exact radix select (8-bit digits over
+// the occupied range, LDS histograms) finds their topk-th value, which becomes
+// the bound: from then on only candidates at or below the bound are kept, in a
+// list of 64-bit keys (bits of D, id).  The list is sorted once at the end (a
+// few hundred keys for a 10^4-candidate list); should an adversarial order fill
+// it first, it is sorted, cut back to topk and the bound tightened.
+constexpr int RS_CHUNK = 8;                          // candidates per thread and chunk
+constexpr int RS_FIRST = RF_THREADS * RS_CHUNK;      // 2048
+constexpr int RS_LIST = 4096;                        // key list capacity (>= topk + RS_FIRST)
+
+struct SelectShared {
+    uint32_t hist[256];
+    uint32_t wsum[4];
+    uint32_t red[8];
+    uint32_t bin, below, ties, cnt;
+};
+
+// Locate the bin that holds the kr-th smallest element (1-based) of a complete
+// histogram; all threads call; results in sh->bin / below / ties.
+__device__ __forceinline__ void find_bin(SelectShared *sh, uint32_t kr) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t h = sh->hist[tid];
+    uint32_t incl = h;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) sh->wsum[wave] = incl;
+    __syncthreads();
+    uint32_t cum = incl;
+    for (int w = 0; w < wave; ++w) cum += sh->wsum[w];
+    if (cum >= kr && cum - h < kr) {
+        sh->bin = (uint32_t)tid;
+        sh->below = cum - h;
+        sh->ties = h;
+    }
+    __syncthreads();
+}
+
+// The kr-th smallest (1-based) of U[0..n), n >= kr >= 1; vmin/vmax bound the values.
+__device__ uint32_t block_radix_select(SelectShared *sh, const uint32_t *U, uint32_t n, uint32_t kr,
+                                       uint32_t vmin, uint32_t vmax) {
+    const int tid = threadIdx.x;
+    const uint32_t range = vmax - vmin;
+    const int bits = range == 0 ? 0 : 32 - __builtin_clz(range);
+    int shift = bits > 8 ? bits - 8 : 0;
+    int width = bits < 8 ? bits : 8;
+    uint32_t prefix = 0;       // chosen high digits of (value - vmin)
+    int fixed_from = bits;     // bits [fixed_from, 32) of (value - vmin) are decided
+    for (;;) {
+        sh->hist[tid] = 0;
+        __syncthreads();
+        const uint32_t dmask = (1u << width) - 1u;
+        for (uint32_t i = tid; i < n; i += RF_THREADS) {
+            const uint32_t y = U[i] - vmin;
+            const bool match = fixed_from >= 32 ? true : (y >> fixed_from) == prefix;
+            if (match) atomicAdd(&sh->hist[(y >> shift) & dmask], 1u);
+        }
+        __syncthreads();
+        find_bin(sh, kr);
+        kr -= sh->below;
+        prefix = (prefix << width) | sh->bin;
+        fixed_from = shift;
+        if (shift == 0) break;
+        const int ns = shift > 8 ? shift - 8 : 0;
+        width = shift - ns;
+        shift = ns;
+    }
+    return vmin + prefix;
+}
+
+// LDS: keys[RS_LIST] (u64) | U[RS_FIRST] (u32) | tables k0..K-1 (f32)
+template <int WORDS>
+__global__ __launch_bounds__(RF_THREADS) void refine_select_kernel(
+    const uint8_t *__restrict__ items, int K, int Kf, const float *__restrict__ lut,
+    const uint32_t *__restrict__ cand_ids, const float *__restrict__ cand_part,
+    const uint32_t *__restrict__ cand_rec, const uint32_t *__restrict__ cand_count, int64_t cap,
+    int topk, int splits, u64 *__restrict__ keys_out, uint32_t *__restrict__ out_ids,
+    float *__restrict__ out_dist) {
+    extern __shared__ u64 smem64[];
+    __shared__ SelectShared sh;
+    u64 *keys = smem64;
+    uint32_t *U = reinterpret_cast<uint32_t *>(keys + RS_LIST);
+    float *T = reinterpret_cast<float *>(U + RS_FIRST);
+    const int k0 = cand_part ? Kf : 0;
+    const int q = blockIdx.x / splits, sp = blockIdx.x % splits;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    for (int i = tid; i < (K - k0) * ICQ_LUT_W; i += RF_THREADS)
+        T[i] = lut[((int64_t)q * K + k0) * ICQ_LUT_W + i];
+    if (tid == 0) sh.cnt = 0;
+
+    u64 ntot = cand_count[q];
+    if (ntot > (u64)cap) ntot = (u64)cap;
+    const u64 lo = ntot * (u64)sp / (u64)splits, hi = ntot * (u64)(sp + 1) / (u64)splits;
+    const u64 n = hi - lo;
+    const uint32_t *ids = cand_ids + (int64_t)q * cap + lo;
+    const float *part = cand_part ? cand_part + (int64_t)q * cap + lo : nullptr;
+    // records either listed next to the ids by stage 1 or gathered here by id
+    const uint32_t *recs = cand_rec ? cand_rec + ((int64_t)q * cap + lo) * WORDS : nullptr;
+    __syncthreads();   // tables in LDS
+
+    uint32_t ubound = 0xFFFFFFFFu;   // keep u <= ubound
+    for (u64 c = 0; c < n; c += RS_FIRST) {
+        uint32_t id[RS_CHUNK], rec[RS_CHUNK][WORDS], u[RS_CHUNK];
+        float D[RS_CHUNK];
+#pragma unroll
+        for (int j = 0; j < RS_CHUNK; ++j) {
+            const u64 i = c + j * RF_THREADS + tid;
+            id[j] = i < n ? ids[i] : 0u;
+            D[j] = (part && i < n) ? part[i] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < RS_CHUNK; ++j) {
+            const u64 i = c + j * RF_THREADS + tid;
+            const uint32_t *p = recs ? recs + (size_t)i * WORDS
+                                     : reinterpret_cast<const uint32_t *>(items + (size_t)id[j] * (WORDS * 4));
+#pragma unroll
+            for (int w = 0; w < WORDS; ++w) rec[j][w] = 0u;
+            if (i < n) {
+                if (WORDS == 1) {
+                    rec[j][0] = p[0];
+                } else if (WORDS == 2) {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(p);
+                    rec[j][0] = v.x;
+                    rec[j][1 % WORDS] = v.y;
+                } else {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(p);
+                    rec[j][0] = v.x;
+                    rec[j][1 % WORDS] = v.y;
+                    rec[j][2 % WORDS] = v.z;
+                    rec[j][3 % WORDS] = v.w;
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < RS_CHUNK; ++j) {
+            float d = D[j];
+#pragma unroll
+            for (int w = 0; w < WORDS; ++w) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int k = w * 4 + b;
+                    if (k >= k0 && k < K) {
+                        const float v = T[(k - k0) * ICQ_LUT_W + ((rec[j][w] >> (8 * b)) & 0xffu)];
+                        d = (k == 0) ? v : d + v;
+                    }
+                }
+            }
+            u[j] = order_bits(d);
+        }
+
+        if (c == 0 && n > (u64)topk) {
+            // first chunk: its topk-th smallest distance bounds everything that follows
+            const uint32_t n1 = n < (u64)RS_FIRST ? (uint32_t)n : (uint32_t)RS_FIRST;
+            uint32_t umin = 0xFFFFFFFFu, umax = 0u;
+#pragma unroll
+            for (int j = 0; j < RS_CHUNK; ++j) {
+                const uint32_t i = j * RF_THREADS + tid;
+                if (i < n1) {
+                    U[i] = u[j];
+                    umin = u[j] < umin ? u[j] : umin;
+                    umax = u[j] > umax ? u[j] : umax;
+                }
+            }
+#pragma unroll
+            for (int d = 32; d > 0; d >>= 1) {
+                const uint32_t a = __shfl_xor(umin, d, 64), b = __shfl_xor(umax, d, 64);
+                umin = a < umin ? a : umin;
+                umax = b > umax ? b : umax;
+            }
+            if (lane == 0) {
+                sh.red[wave] = umin;
+                sh.red[4 + wave] = umax;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                umin = sh.red[w] < umin ? sh.red[w] : umin;
+                umax = sh.red[4 + w] > umax ? sh.red[4 + w] : umax;
+            }
+            if (n1 > (uint32_t)topk) ubound = block_radix_select(&sh, U, n1, (uint32_t)topk, umin, umax);
+        }
+
+        // keep what is at or below the bound (ties at the bound included; the final sort decides)
+#pragma unroll
+        for (int j = 0; j < RS_CHUNK; ++j) {
+            const u64 i = c + j * RF_THREADS + tid;
+            if (i < n && u[j] <= ubound) {
+                const uint32_t slot = atomicAdd(&sh.cnt, 1u);
+                if (slot < (uint32_t)RS_LIST) keys[slot] = ((u64)u[j] << 32) | id[j];
+            }
+        }
+        __syncthreads();
+        const uint32_t filled = sh.cnt;
+        __syncthreads();   // everyone has read the count before anyone appends again
+        if (filled > (uint32_t)(RS_LIST - RS_FIRST) && c + RS_FIRST < n) {
+            // the list could overflow in the next chunk: sort, cut back to topk, tighten the bound
+            const uint32_t m = filled < (uint32_t)RS_LIST ? filled : (uint32_t)RS_LIST;
+            int len = 2;
+            while (len < (int)m) len <<= 1;
+            for (int i = (int)m + tid; i < len; i += RF_THREADS) keys[i] = KEY_PAD;
+            __syncthreads();
+            block_sort(keys, len);
+            const uint32_t kept = m < (uint32_t)topk ? m : (uint32_t)topk;
+            if (m >= (uint32_t)topk) ubound = (uint32_t)(keys[topk - 1] >> 32);
+            if (tid == 0) sh.cnt = kept;
+            __syncthreads();
+        }
+    }
+
+    // ---- final order
+    const uint32_t m = sh.cnt < (uint32_t)RS_LIST ? sh.cnt : (uint32_t)RS_LIST;
+    int len = 2;
+    while (len < (int)m) len <<= 1;
+    for (int i = (int)m + tid; i < len; i += RF_THREADS) keys[i] = KEY_PAD;
+    __syncthreads();
+    block_sort(keys, len);
+    const int kept = (int)m < topk ? (int)m : topk;
+    if (splits == 1) {
+        write_result(keys, kept, topk, out_ids + (int64_t)q * topk, out_dist + (int64_t)q * topk);
+    } else {
+        u64 *dst = keys_out + ((int64_t)q * splits + sp) * topk;
+        for (int r = tid; r < topk; r += RF_THREADS) dst[r] = r < kept ? keys[r] : KEY_PAD;
+    }
+}
+
 }  // namespace
+
+// Item records of at most 16 bytes take the bounded-stream kernel; wider records
+// (K > 16) the generic streaming kernel.
+static bool use_select(const icq_index *ix) { return ix->item_stride <= 16; }
 
 int icq_refine_splits(const icq_index *ix, int Q, int64_t cap, int topk) {
     if (Q <= 0) return 1;
@@ -189,21 +424,54 @@ int icq_refine_splits(const icq_index *ix, int Q, int64_t cap, int topk) {
 }
 
 int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32_t *cand_ids,
-                      const float *cand_part, const uint32_t *cand_count, int64_t cap, int topk,
-                      int splits, u64 *keys, uint32_t *out_ids, float *out_dist, hipStream_t s) {
+                      const float *cand_part, const uint32_t *cand_rec, const uint32_t *cand_count,
+                      int64_t cap, int topk, int splits, u64 *keys, uint32_t *out_ids, float *out_dist,
+                      hipStream_t s) {
     if (Q == 0) return ICQ_OK;
-    const int bufn = bufn_for(topk);
-    const size_t lds = sizeof(u64) * bufn + sizeof(float) * (size_t)(cand_part ? ix->Ks : ix->K) * ICQ_LUT_W;
-    static bool attr_set = false;
-    if (!attr_set) {
-        ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&refine_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 98304));
-        attr_set = true;
-    }
     const unsigned grid = (unsigned)Q * (unsigned)splits;
-    refine_kernel<<<grid, RF_THREADS, lds, s>>>(ix->items, ix->item_stride, ix->K, ix->Kf, lut,
-                                                cand_ids, cand_part, cand_count, cap, topk, bufn,
-                                                splits, keys, out_ids, out_dist);
+    const size_t tab = sizeof(float) * (size_t)(cand_part ? ix->Ks : ix->K) * ICQ_LUT_W;
+    if (use_select(ix)) {
+        const size_t lds = sizeof(u64) * RS_LIST + sizeof(uint32_t) * RS_FIRST + tab;
+        static bool sel_attr_set = false;
+        if (!sel_attr_set) {
+            ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&refine_select_kernel<1>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 98304));
+            ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&refine_select_kernel<2>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 98304));
+            ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&refine_select_kernel<4>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 98304));
+            sel_attr_set = true;
+        }
+        switch (ix->item_stride) {
+            case 4:
+                refine_select_kernel<1><<<grid, RF_THREADS, lds, s>>>(
+                    ix->items, ix->K, ix->Kf, lut, cand_ids, cand_part, cand_rec, cand_count, cap, topk,
+                    splits, keys, out_ids, out_dist);
+                break;
+            case 8:
+                refine_select_kernel<2><<<grid, RF_THREADS, lds, s>>>(
+                    ix->items, ix->K, ix->Kf, lut, cand_ids, cand_part, cand_rec, cand_count, cap, topk,
+                    splits, keys, out_ids, out_dist);
+                break;
+            default:
+                refine_select_kernel<4><<<grid, RF_THREADS, lds, s>>>(
+                    ix->items, ix->K, ix->Kf, lut, cand_ids, cand_part, cand_rec, cand_count, cap, topk,
+                    splits, keys, out_ids, out_dist);
+                break;
+        }
+    } else {
+        const int bufn = bufn_for(topk);
+        const size_t lds = sizeof(u64) * bufn + tab;
+        static bool attr_set = false;
+        if (!attr_set) {
+            ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&refine_kernel),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 98304));
+            attr_set = true;
+        }
+        refine_kernel<<<grid, RF_THREADS, lds, s>>>(ix->items, ix->item_stride, ix->K, ix->Kf, lut,
+                                                    cand_ids, cand_part, cand_count, cap, topk, bufn,
+                                                    splits, keys, out_ids, out_dist);
+    }
     if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;
     if (splits > 1) {
         int len = 2;
@@ -229,6 +497,6 @@ ICQ_EXPORT int icq_refine(const icq_index *ix, const float *lut, int Q, const ui
         (!workspace || ((uintptr_t)workspace % ICQ_ALIGN) != 0 || workspace_bytes < L.total))
         return ICQ_ERR_WORKSPACE;
     u64 *keys = reinterpret_cast<u64 *>(static_cast<char *>(workspace) + L.keys_off);
-    return icq_launch_refine(ix, lut, Q, cand_ids, cand_part, cand_count, cap, topk, L.splits, keys,
-                             out_ids, out_dist, (hipStream_t)stream);
+    return icq_launch_refine(ix, lut, Q, cand_ids, cand_part, nullptr, cand_count, cap, topk, L.splits,
+                             keys, out_ids, out_dist, (hipStream_t)stream);
 }

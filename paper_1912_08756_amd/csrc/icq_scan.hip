@@ -54,23 +54,28 @@ __global__ __launch_bounds__(256) void transpose_fast_lut_kernel(const float *__
 // ------------------------------------------------------------------ lanes = queries
 constexpr int SB_WAVES = 16;                // wavefronts per block (4 per SIMD: the loop is issue-bound)
 constexpr int SB_THREADS = SB_WAVES * 64;
-constexpr int SB_SLOTS = 4;                 // staged survivor ids per lane and buffer (two buffers)
+constexpr int SB_SLOTS = 8;                 // staged survivor ids per lane
 constexpr int SB_GROUP = 256;               // items per wavefront step (one dword per lane and row)
 constexpr int SB_WORDS = 2;                 // lane-words (4 items each) looked up together
 
-// Survivor ids are staged per wavefront and lane in LDS ([buffer][slot][lane])
-// and moved to the query's global list in bulk: when some lane's buffer is full
-// the wavefront reserves list space for the whole buffer with ONE atomic per
-// lane, switches to the other buffer and keeps scanning; the reserved offset is
-// only needed when that buffer is written out at the next switch, so the
-// atomic's round trip overlaps the scan.
-template <int KF>
+// Survivor ids are staged per wavefront and lane in LDS ([slot][lane]) and moved
+// to the query's global list in bulk.  When some lane's column is full the
+// wavefront pulls the staged ids into registers, reserves list space for them
+// with ONE atomic per lane, (REC_WORDS > 0: also starts the gather of each
+// survivor's item record) and goes on scanning; offsets and records are only
+// consumed when that batch is written out at the next flush, so the round trips
+// of the atomic and of the gathers overlap the scan, which keeps the memory
+// pipeline idle otherwise.  REC_WORDS > 0 hands stage 2 a contiguous
+// (id, record) list, so it does not have to gather at random itself.
+template <int KF, int REC_WORDS>
 __global__ __launch_bounds__(SB_THREADS, 1) void scan_batch_kernel(
     const uint8_t *__restrict__ fast, int64_t Npad, uint32_t N, const float *__restrict__ lutT,
     const float *__restrict__ thr, int Q, uint32_t *__restrict__ cand_ids,
+    uint32_t *__restrict__ cand_rec, const uint8_t *__restrict__ items,
     uint32_t *__restrict__ cand_count, int64_t cap, uint32_t items_per_block) {
     extern __shared__ float smem[];
     constexpr int LUT_FLOATS = KF * ICQ_LUT_W * 64;
+    constexpr int RW = REC_WORDS > 0 ? REC_WORDS : 1;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -86,30 +91,57 @@ __global__ __launch_bounds__(SB_THREADS, 1) void scan_batch_kernel(
     const int q = tile * 64 + lane;
     const float t = q < Q ? thr[q] : -INFINITY;
     uint32_t *my_ids = cand_ids + (int64_t)q * cap;
-    uint32_t *const st = reinterpret_cast<uint32_t *>(smem + LUT_FLOATS) + wave * (2 * SB_SLOTS * 64) + lane;
-    uint32_t *cur0 = st;                    // current buffer (this lane's column)
-    uint32_t *prev0 = st + SB_SLOTS * 64;   // buffer whose reservation is in flight
-    uint32_t *sp = cur0;                    // next free slot of the current buffer
+    uint32_t *my_rec = REC_WORDS > 0 ? cand_rec + (int64_t)q * cap * RW : nullptr;
+    uint32_t *const st0 = reinterpret_cast<uint32_t *>(smem + LUT_FLOATS) + wave * (SB_SLOTS * 64) + lane;
+    uint32_t *sp = st0;                     // next free slot of this lane's column
+    uint32_t pid[SB_SLOTS], prec[SB_SLOTS][RW];   // batch in flight
     uint32_t pend_cnt = 0, pend_base = 0;
 
-    auto retire = [&]() {   // write the previous buffer to the reserved list range
+    auto retire = [&]() {   // write the batch in flight to its reserved list range
 #pragma unroll
         for (int s = 0; s < SB_SLOTS; ++s) {
             if ((uint32_t)s < pend_cnt) {
                 const uint64_t slot = (uint64_t)pend_base + s;
-                if (slot < (uint64_t)cap) my_ids[slot] = prev0[s * 64];
+                if (slot < (uint64_t)cap) {
+                    my_ids[slot] = pid[s];
+                    if (REC_WORDS == 1) {
+                        my_rec[slot] = prec[s][0];
+                    } else if (REC_WORDS == 2) {
+                        *reinterpret_cast<uint2 *>(my_rec + slot * 2) = make_uint2(prec[s][0], prec[s][1 % RW]);
+                    } else if (REC_WORDS == 4) {
+                        *reinterpret_cast<uint4 *>(my_rec + slot * 4) =
+                            make_uint4(prec[s][0], prec[s][1 % RW], prec[s][2 % RW], prec[s][3 % RW]);
+                    }
+                }
             }
         }
     };
     auto flush = [&]() {
         retire();
-        pend_cnt = (uint32_t)(sp - cur0) >> 6;
+        pend_cnt = (uint32_t)(sp - st0) >> 6;
+#pragma unroll
+        for (int s = 0; s < SB_SLOTS; ++s) {
+            if ((uint32_t)s < pend_cnt) {
+                pid[s] = st0[s * 64];
+                const uint8_t *r = items + (size_t)pid[s] * (RW * 4);
+                if (REC_WORDS == 1) {
+                    prec[s][0] = *reinterpret_cast<const uint32_t *>(r);
+                } else if (REC_WORDS == 2) {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(r);
+                    prec[s][0] = v.x;
+                    prec[s][1 % RW] = v.y;
+                } else if (REC_WORDS == 4) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(r);
+                    prec[s][0] = v.x;
+                    prec[s][1 % RW] = v.y;
+                    prec[s][2 % RW] = v.z;
+                    prec[s][3 % RW] = v.w;
+                }
+            }
+        }
         pend_base = 0;
         if (pend_cnt > 0) pend_base = atomicAdd(&cand_count[q], pend_cnt);
-        uint32_t *tmp = cur0;
-        cur0 = prev0;
-        prev0 = tmp;
-        sp = cur0;
+        sp = st0;
     };
 
     const uint32_t begin = blockIdx.x * items_per_block;
@@ -131,12 +163,18 @@ __global__ __launch_bounds__(SB_THREADS, 1) void scan_batch_kernel(
             w[k] = *reinterpret_cast<const uint32_t *>(fast + (int64_t)k * Npad + g + lane * 4);
     }
     for (; g < end; g += SB_WAVES * SB_GROUP) {
+        // Read ahead, unconditionally (rows are padded by more than one block step beyond
+        // N, so the group after the last one is still addressable): with a fixed number
+        // of loads in flight the wait below can leave exactly these outstanding.
         const uint32_t gn = g + SB_WAVES * SB_GROUP;
-        if (gn < end) {   // read ahead; rows are padded so a full group is always addressable
 #pragma unroll
-            for (int k = 0; k < KF; ++k)
-                wn[k] = *reinterpret_cast<const uint32_t *>(fast + (int64_t)k * Npad + gn + lane * 4);
-        }
+        for (int k = 0; k < KF; ++k)
+            wn[k] = *reinterpret_cast<const uint32_t *>(fast + (int64_t)k * Npad + gn + lane * 4);
+        // Touch this group's code words here, once: the wait for their load then sits in
+        // straight-line code instead of inside the loop below, where it would also wait
+        // for the atomics and gathers a flush has just started.
+#pragma unroll
+        for (int k = 0; k < KF; ++k) asm volatile("" ::"v"(w[k]));
         // lane-words holding items below `end` (a word = 4 consecutive items)
         const int nl = (end - g + 3) / 4 < 64 ? (int)((end - g + 3) / 4) : 64;
         for (int l = 0; l < nl; l += SB_WORDS) {
@@ -162,7 +200,7 @@ __global__ __launch_bounds__(SB_THREADS, 1) void scan_batch_kernel(
                         *sp = id;
                         sp += 64;
                     }
-                    if (__builtin_amdgcn_ballot_w64(sp == cur0 + 64 * SB_SLOTS) != 0) flush();
+                    if (__builtin_amdgcn_ballot_w64(sp == st0 + 64 * SB_SLOTS) != 0) flush();
                 }
             }
         }
@@ -486,14 +524,14 @@ __global__ __launch_bounds__(SI_THREADS) void scan_items_kernel(
     }
 }
 
-template <int KF>
-int launch_batch(const icq_index *ix, int Q, const float *thr, uint32_t *cand_ids,
+template <int KF, int REC_WORDS>
+int launch_batch(const icq_index *ix, int Q, const float *thr, uint32_t *cand_ids, uint32_t *cand_rec,
                  uint32_t *cand_count, int64_t cap, const float *lutT, hipStream_t s) {
     const int tiles = (Q + 63) / 64;
-    const size_t lds = sizeof(float) * KF * ICQ_LUT_W * 64 + sizeof(uint32_t) * SB_WAVES * 2 * SB_SLOTS * 64;
+    const size_t lds = sizeof(float) * KF * ICQ_LUT_W * 64 + sizeof(uint32_t) * SB_WAVES * SB_SLOTS * 64;
     static bool attr_set = false;   // idempotent; a race only repeats the call
     if (!attr_set) {
-        ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_batch_kernel<KF>),
+        ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_batch_kernel<KF, REC_WORDS>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
@@ -506,16 +544,30 @@ int launch_batch(const icq_index *ix, int Q, const float *thr, uint32_t *cand_id
     uint32_t per = (uint32_t)(((ix->N + chunks - 1) / chunks + step - 1) / step * step);
     chunks = (ix->N + per - 1) / per;
     dim3 grid((unsigned)chunks, (unsigned)tiles);
-    scan_batch_kernel<KF><<<grid, SB_THREADS, lds, s>>>(ix->fast, ix->Npad, (uint32_t)ix->N, lutT,
-                                                        thr, Q, cand_ids, cand_count, cap, per);
+    scan_batch_kernel<KF, REC_WORDS><<<grid, SB_THREADS, lds, s>>>(
+        ix->fast, ix->Npad, (uint32_t)ix->N, lutT, thr, Q, cand_ids, cand_rec, ix->items, cand_count,
+        cap, per);
     return icq_check_launch();
+}
+
+template <int KF>
+int launch_batch_rec(const icq_index *ix, int Q, const float *thr, uint32_t *cand_ids,
+                     uint32_t *cand_rec, uint32_t *cand_count, int64_t cap, const float *lutT,
+                     hipStream_t s) {
+    if (!cand_rec) return launch_batch<KF, 0>(ix, Q, thr, cand_ids, nullptr, cand_count, cap, lutT, s);
+    switch (ix->item_stride) {
+        case 4: return launch_batch<KF, 1>(ix, Q, thr, cand_ids, cand_rec, cand_count, cap, lutT, s);
+        case 8: return launch_batch<KF, 2>(ix, Q, thr, cand_ids, cand_rec, cand_count, cap, lutT, s);
+        default: return launch_batch<KF, 4>(ix, Q, thr, cand_ids, cand_rec, cand_count, cap, lutT, s);
+    }
 }
 
 }  // namespace
 
 int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
-                    uint32_t *cand_ids, float *cand_part, uint32_t *cand_count, int64_t cap,
-                    float *lutT, hipStream_t s) {
+                    uint32_t *cand_ids, float *cand_part, uint32_t *cand_rec, bool *rec_written,
+                    uint32_t *cand_count, int64_t cap, float *lutT, hipStream_t s) {
+    if (rec_written) *rec_written = false;
     if (Q == 0) return ICQ_OK;
     zero_counts_kernel<<<(Q + 255) / 256, 256, 0, s>>>(cand_count, Q);
     if (ix->N == 0) return icq_check_launch();
@@ -524,8 +576,10 @@ int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *t
         const int tiles = (Q + 63) / 64;
         dim3 g((unsigned)tiles, (unsigned)ix->Kf);
         transpose_fast_lut_kernel<<<g, 256, 0, s>>>(lut, Q, ix->K, ix->Kf, lutT);
-        int rc = ix->Kf == 1 ? launch_batch<1>(ix, Q, thr, cand_ids, cand_count, cap, lutT, s)
-                             : launch_batch<2>(ix, Q, thr, cand_ids, cand_count, cap, lutT, s);
+        if (ix->item_stride > 16) cand_rec = nullptr;   // wide records stay with stage 2
+        int rc = ix->Kf == 1 ? launch_batch_rec<1>(ix, Q, thr, cand_ids, cand_rec, cand_count, cap, lutT, s)
+                             : launch_batch_rec<2>(ix, Q, thr, cand_ids, cand_rec, cand_count, cap, lutT, s);
+        if (rec_written) *rec_written = cand_rec != nullptr;
         if (rc != ICQ_OK || !cand_part) return rc;
         const int bpq = (int)((cap + 255) / 256 < 32 ? (cap + 255) / 256 : 32);
         fill_partials_kernel<<<(unsigned)Q * (unsigned)bpq, 256, 0, s>>>(
@@ -598,6 +652,6 @@ ICQ_EXPORT int icq_scan_fast(const icq_index *ix, const float *lut, int Q, const
     if (!workspace || ((uintptr_t)workspace % ICQ_ALIGN) != 0 || workspace_bytes < L.total)
         return ICQ_ERR_WORKSPACE;
     float *lutT = reinterpret_cast<float *>(static_cast<char *>(workspace) + L.lutT_off);
-    return icq_launch_scan(ix, lut, Q, thresholds, cand_ids, cand_part, cand_count, cap, lutT,
-                           (hipStream_t)stream);
+    return icq_launch_scan(ix, lut, Q, thresholds, cand_ids, cand_part, nullptr, nullptr, cand_count,
+                           cap, lutT, (hipStream_t)stream);
 }
