@@ -316,3 +316,70 @@ def test_argument_errors_on_a_live_index(gpu):
     assert lib.icq_search(h, one, 4, one, 16, 5, one, one, None, None, 0, None) == b.ICQ_ERR_WORKSPACE
     assert lib.icq_search(h, one, 4, one, 16, 5, one, one, None, one + 4, 1 << 20, None) == b.ICQ_ERR_WORKSPACE
     assert lib.icq_search(h, one, -1, one, 16, 5, one, one, None, one, 1 << 20, None) == b.ICQ_ERR_ARG
+
+
+# ------------------------------------------------------------------ full size, as benchmarked
+def test_full_size_workload_sampled_against_oracle(gpu):
+    """The benchmark's workload (C1: N = 1e6, Q = 1e4, top-100) in the benchmark's launch
+    configuration (all queries in one icq_search call, same candidate capacity and the
+    same sampled-quantile thresholds).  A sample of queries is checked against the
+    oracle element by element; every query is checked for the properties that hold at
+    any size."""
+    import bench
+    torch, b = gpu
+    cfg = synth.make("C1")
+    N, Q, Kf, topk = cfg["N"], cfg["Q"], cfg["Kf"], cfg["topk"]
+    g = Gpu(gpu, cfg)
+    thr_dev = bench.sampled_thresholds(torch, b, g.cb, g.codes, g.queries, Kf, bench.SURVIVE_FRAC, 16384,
+                                       cfg["seed"])
+    thr = thr_dev.cpu().numpy()
+    cap = 16384
+    out_ids, out_dist, surv = g.search(thr, cap, topk)
+    # properties for every query
+    assert (surv <= cap).all(), "candidate capacity exceeded"
+    assert (surv >= topk).all()
+    assert (out_ids < N).all()
+    assert (np.diff(out_dist, axis=1) >= 0).all(), "distances not ascending"
+    srt = np.sort(out_ids, axis=1)
+    assert (np.diff(srt.astype(np.int64), axis=1) > 0).all(), "duplicate ids in a result"
+    assert 0.005 * N < surv.mean() < 0.02 * N
+    # element by element on a sample
+    sample = np.linspace(0, Q - 1, 12).astype(int)
+    T = orc.lut(cfg["codebooks"], cfg["queries"][sample])
+    P = orc.partial(T, cfg["codes"], Kf)
+    _, _, D = orc.adc_exhaustive(T, cfg["codes"], 1, want_all=True)
+    o_ids, o_dist, o_cnt = orc.search(T, cfg["codes"], Kf, thr[sample], topk)
+    same = 0
+    for r, q in enumerate(sample):
+        band = ((P[r] >= thr[q] - tol(thr[q])) & (P[r] <= thr[q] + tol(thr[q]))).sum()
+        assert abs(int(surv[q]) - int(o_cnt[r])) <= band
+        check_topk(P[r], D[r], thr[q], topk, out_ids[q], out_dist[q])
+        same += np.array_equal(out_ids[q], o_ids[r])
+    assert same >= 10
+    # the staged calls give the same lists as the fused call (same kernels, other plumbing)
+    lut = g.lut()
+    ids, part, cnt = g.scan(lut, thr, cap)
+    assert np.array_equal(_u32(cnt), surv)
+    r_ids, r_dist = g.refine(lut, ids, part, cnt, topk)
+    assert np.array_equal(r_ids, out_ids) and np.array_equal(r_dist, out_dist)
+    for r, q in enumerate(sample[:4]):
+        check_candidates(P[r], thr[q], _u32(ids[q]), part[q].cpu().numpy(), int(_u32(cnt)[q]), cap)
+
+
+def test_stream_scan_at_full_length_properties(gpu):
+    """Streaming stage-1 kernel on a long code array (N = 2e7, Kf = 4, one and two queries
+    per pass): survivor sets against the oracle's crude distances, element by element
+    (the oracle finishes 2e7 items in seconds)."""
+    torch, b = gpu
+    cfg = synth.make("C4", N=20_000_003, Q=2, K=4)
+    g = Gpu(gpu, cfg)
+    T = orc.lut(cfg["codebooks"], cfg["queries"])
+    P = orc.partial(T, cfg["codes"], 4)
+    thr = thresholds_quantile(P, 0.01)
+    cap = 400_000
+    lut = g.lut()
+    for nq in (1, 2):
+        ids, part, cnt = g.scan(lut[:nq].contiguous(), thr[:nq], cap)
+        ids, part, cnt = _u32(ids), part.cpu().numpy(), _u32(cnt)
+        for q in range(nq):
+            check_candidates(P[q], thr[q], ids[q], part[q], cnt[q], cap)
