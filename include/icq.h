@@ -83,8 +83,24 @@ void icq_index_destroy(icq_index *index);
 /* Write the index's private copy of the codes back in the input layout
  * [K][N] (bit-exact round trip of the storage layout; a debugging aid).
  * from_items == 0: fast rows from the stage-1 array, slow rows from the item
- * records; from_items != 0: every row from the item records. */
+ * records; 1: every row from the item records; 2: every row from the grouped
+ * item records through the position -> id map (ICQ_ERR_ARG if the index is not
+ * grouped, i.e. Kf > 2 or N == 0). */
 int icq_index_export_codes(const icq_index *index, int from_items, uint8_t *codes_out, void *stream);
+
+/*
+ * Stage-1 strategy for calls with more than 4 queries on an index with Kf <= 2.
+ * An item's crude distance (Eq. 2) depends only on its Kf fast sub-codes, so when
+ * N is much larger than 256^Kf the index also keeps the items grouped by that
+ * tuple and stage 1 evaluates each tuple once per query instead of each item
+ * (identical values and survivors).  ICQ_SCAN_AUTO picks the grouped form when
+ * it is available and cheaper, ICQ_SCAN_STREAMED always walks the fast
+ * sub-codes, ICQ_SCAN_GROUPED uses the grouped form whenever the index has it.
+ */
+#define ICQ_SCAN_AUTO 0
+#define ICQ_SCAN_STREAMED 1
+#define ICQ_SCAN_GROUPED 2
+int icq_index_set_scan_mode(icq_index *index, int mode);
 
 /* Bytes of 256-byte-aligned device workspace that icq_scan_fast, icq_refine
  * and icq_search need for up to Q queries per call, candidate capacity `cap`

@@ -24,6 +24,7 @@ SIGNATURES = {
     "icq_index_create": (_i, [ctypes.POINTER(_vp), _vp, _vp, _i, _i, _i, _i, _i64, _vp]),
     "icq_index_destroy": (None, [_vp]),
     "icq_index_export_codes": (_i, [_vp, _i, _vp, _vp]),
+    "icq_index_set_scan_mode": (_i, [_vp, _i]),
     "icq_workspace_bytes": (_i, [_vp, _i, _i64, _i, ctypes.POINTER(_sz)]),
     "icq_build_lut": (_i, [_vp, _vp, _i, _vp, _vp]),
     "icq_scan_fast": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
@@ -112,6 +113,13 @@ def icq_index_export_codes(index, from_items, codes_out):
                                          _dev(codes_out, torch.uint8, (index.K, index.N)),
                                          _stream()), "icq_index_export_codes")
     return codes_out
+
+
+ICQ_SCAN_AUTO, ICQ_SCAN_STREAMED, ICQ_SCAN_GROUPED = 0, 1, 2
+
+
+def icq_index_set_scan_mode(index, mode):
+    _check(load().icq_index_set_scan_mode(index.handle, int(mode)), "icq_index_set_scan_mode")
 
 
 def icq_workspace_bytes(index, Q, cap, topk):

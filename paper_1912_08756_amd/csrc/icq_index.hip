@@ -44,6 +44,16 @@ __global__ void copy_codebooks_kernel(const float *__restrict__ codebooks, int K
     if (lane == 0) cnorm[row] = j < m ? (float)s : INFINITY;
 }
 
+// codes_out[k][perm[pos]] = items_grouped[pos][k]: the grouped layout written back in item order.
+__global__ void export_grouped_kernel(const uint8_t *__restrict__ items_grouped,
+                                      const uint32_t *__restrict__ perm, int64_t N, int stride,
+                                      uint8_t *__restrict__ out) {
+    int k = blockIdx.y;
+    int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pos >= N) return;
+    out[(int64_t)k * N + perm[pos]] = items_grouped[pos * (2 * stride) + k];   // grouped records are 2*stride wide
+}
+
 // codes_out[k][i] rebuilt from the private layouts: rows below `fast_rows` from
 // the codebook-major fast array, the others from the item records.
 __global__ void export_codes_kernel(const uint8_t *__restrict__ fast, const uint8_t *__restrict__ items,
@@ -80,6 +90,10 @@ ICQ_EXPORT void icq_index_destroy(icq_index *ix) {
     (void)hipFree(ix->cnorm);
     (void)hipFree(ix->fast);
     (void)hipFree(ix->items);
+    (void)hipFree(ix->group_start);
+    (void)hipFree(ix->group_cursor);
+    (void)hipFree(ix->perm);
+    (void)hipFree(ix->items_grouped);
     delete ix;
 }
 
@@ -100,6 +114,8 @@ ICQ_EXPORT int icq_index_create(icq_index **out, const float *codebooks, const u
     ix->N = N;
     ix->Npad = (N + 16383) / 16384 * 16384 + 16384;   // spare so that whole-step reads stay in bounds
     ix->cb = nullptr; ix->cnorm = nullptr; ix->fast = nullptr; ix->items = nullptr;
+    ix->groups = 0; ix->scan_mode = ICQ_SCAN_AUTO;
+    ix->group_start = nullptr; ix->group_cursor = nullptr; ix->perm = nullptr; ix->items_grouped = nullptr;
     hipDeviceProp_t prop;
     if (hipGetDevice(&ix->device) != hipSuccess ||
         hipGetDeviceProperties(&prop, ix->device) != hipSuccess) {
@@ -128,7 +144,7 @@ ICQ_EXPORT int icq_index_create(icq_index **out, const float *codebooks, const u
     if (N > 0)
         copy_items_kernel<<<(unsigned)((N + T - 1) / T), T, 0, s>>>(codes, N, K, ix->item_stride,
                                                                      ix->items);
-    if (icq_check_launch() != ICQ_OK) {
+    if (icq_check_launch() != ICQ_OK || icq_group_build(ix, s) != ICQ_OK) {
         icq_index_destroy(ix);
         return ICQ_ERR_HIP;
     }
@@ -142,6 +158,12 @@ ICQ_EXPORT int icq_index_export_codes(const icq_index *ix, int from_items, uint8
     if (ix->N == 0) return ICQ_OK;
     const int T = 256;
     dim3 g((unsigned)((ix->N + T - 1) / T), (unsigned)ix->K);
+    if (from_items == 2) {
+        if (!ix->groups) return ICQ_ERR_ARG;
+        export_grouped_kernel<<<g, T, 0, (hipStream_t)stream>>>(ix->items_grouped, ix->perm, ix->N,
+                                                                ix->item_stride, codes_out);
+        return icq_check_launch();
+    }
     export_codes_kernel<<<g, T, 0, (hipStream_t)stream>>>(ix->fast, ix->items, ix->N, ix->Npad,
                                                           from_items ? 0 : ix->Kf, ix->item_stride,
                                                           codes_out);

@@ -22,6 +22,21 @@ struct icq_index {
     float *cnorm;              // [K*256] squared codeword norms, +inf for j >= m
     uint8_t *fast;             // [Kf][Npad] fast sub-codes, zero padded
     uint8_t *items;            // [N][item_stride] all K sub-codes of an item, item-major
+    // Grouping by fast-code tuple (Kf <= 2): items with the same fast sub-codes share their
+    // crude distance, so batch-mode stage 1 evaluates each tuple once.
+    int groups;                // 256^Kf, or 0 when the index is not grouped
+    int scan_mode;             // ICQ_SCAN_AUTO / ICQ_SCAN_STREAMED / ICQ_SCAN_GROUPED
+    uint32_t *group_start;     // [groups + 1] first grouped position of each tuple
+    uint32_t *group_cursor;    // [groups] scratch of the build
+    uint32_t *perm;            // [N] grouped position -> item id
+    uint8_t *items_grouped;    // [N][2*item_stride] grouped order: sub-codes, then the item id, zero padded
+};
+
+// What a candidate list holds.
+enum icq_list_kind {
+    ICQ_LIST_IDS = 0,          // item ids
+    ICQ_LIST_IDS_REC = 1,      // item ids, item records alongside in cand_rec
+    ICQ_LIST_POSITIONS = 2     // grouped positions (ids through perm, records from items_grouped)
 };
 
 // Sub-buffers carved out of the caller's workspace for one query batch.
@@ -44,17 +59,25 @@ int icq_launch_build_lut(const icq_index *ix, const float *queries, int Q, float
                          hipStream_t s);
 // cand_part == nullptr: the crude distances are not materialised (the fused path
 // recomputes the full sum in stage 2 from the item records).
-// cand_rec != nullptr: the scan may also write each survivor's item record next
-// to its id ([Q][cap][item_stride/4] words) and says so through *rec_written.
+// list_kind == nullptr: the list must hold item ids (public contract).  Otherwise the
+// scan picks the cheapest representation for stage 2 and reports it: grouped positions,
+// or ids with each survivor's item record written to cand_rec
+// ([Q][cap][item_stride/4] words; cand_rec may be nullptr).
 int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
-                    uint32_t *cand_ids, float *cand_part, uint32_t *cand_rec, bool *rec_written,
+                    uint32_t *cand_ids, float *cand_part, uint32_t *cand_rec, int *list_kind,
                     uint32_t *cand_count, int64_t cap, float *lutT, hipStream_t s);
+// Grouped stage 1 (icq_group.hip); as_positions: list grouped positions instead of ids.
+bool icq_group_usable(const icq_index *ix, int Q);
+int icq_launch_group_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
+                          uint32_t *cand_ids, bool as_positions, uint32_t *cand_count, int64_t cap,
+                          hipStream_t s);
+int icq_group_build(icq_index *ix, hipStream_t s);
 // cand_part == nullptr: D is the full K-term sum; else D = cand_part + slow terms.
-// cand_rec != nullptr: item records come from the candidate list instead of a gather.
+// list_kind says what cand_ids (and cand_rec) hold, see icq_list_kind.
 int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32_t *cand_ids,
-                      const float *cand_part, const uint32_t *cand_rec, const uint32_t *cand_count,
-                      int64_t cap, int topk, int splits, unsigned long long *keys, uint32_t *out_ids,
-                      float *out_dist, hipStream_t s);
+                      const float *cand_part, const uint32_t *cand_rec, int list_kind,
+                      const uint32_t *cand_count, int64_t cap, int topk, int splits,
+                      unsigned long long *keys, uint32_t *out_ids, float *out_dist, hipStream_t s);
 
 #define ICQ_HIP_TRY(expr)                      \
     do {                                       \

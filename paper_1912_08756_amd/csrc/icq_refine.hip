@@ -116,8 +116,9 @@ __device__ __forceinline__ void write_result(const u64 *keys, int kept, int topk
 __global__ __launch_bounds__(RF_THREADS) void refine_kernel(
     const uint8_t *__restrict__ items, int stride, int K, int Kf, const float *__restrict__ lut,
     const uint32_t *__restrict__ cand_ids, const float *__restrict__ cand_part,
-    const uint32_t *__restrict__ cand_count, int64_t cap, int topk, int bufn, int splits,
-    u64 *__restrict__ keys_out, uint32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
+    const uint32_t *__restrict__ perm, const uint32_t *__restrict__ cand_count, int64_t cap, int topk,
+    int bufn, int splits, u64 *__restrict__ keys_out, uint32_t *__restrict__ out_ids,
+    float *__restrict__ out_dist) {
     extern __shared__ u64 smem64[];
     __shared__ uint32_t s_cnt;
     __shared__ u64 s_bound;
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(RF_THREADS) void refine_kernel(
                     }
                 }
             }
-            const u64 key = ((u64)order_bits(D) << 32) | id;
+            const u64 key = ((u64)order_bits(D) << 32) | (perm ? perm[id] : id);
             if (key < s_bound) {
                 uint32_t slot = atomicAdd(&s_cnt, 1u);
                 keys[slot] = key;
@@ -283,7 +284,9 @@ __device__ uint32_t block_radix_select(SelectShared *sh, const uint32_t *U, uint
 }
 
 // LDS: keys[RS_LIST] (u64) | U[RS_FIRST] (u32) | tables k0..K-1 (f32)
-template <int WORDS>
+// GROUPED: the list holds grouped positions and `items` is the grouped record array,
+// whose records are 2*WORDS words: the sub-codes, then the item id in word WORDS.
+template <int WORDS, bool GROUPED>
 __global__ __launch_bounds__(RF_THREADS) void refine_select_kernel(
     const uint8_t *__restrict__ items, int K, int Kf, const float *__restrict__ lut,
     const uint32_t *__restrict__ cand_ids, const float *__restrict__ cand_part,
@@ -292,6 +295,7 @@ __global__ __launch_bounds__(RF_THREADS) void refine_select_kernel(
     float *__restrict__ out_dist) {
     extern __shared__ u64 smem64[];
     __shared__ SelectShared sh;
+    constexpr int RW = GROUPED ? 2 * WORDS : WORDS;   // words per record as stored
     u64 *keys = smem64;
     uint32_t *U = reinterpret_cast<uint32_t *>(keys + RS_LIST);
     float *T = reinterpret_cast<float *>(U + RS_FIRST);
@@ -299,22 +303,23 @@ __global__ __launch_bounds__(RF_THREADS) void refine_select_kernel(
     const int q = blockIdx.x / splits, sp = blockIdx.x % splits;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    {   // tables -> LDS: one 16-byte load per thread and table, all in flight together
-        const float4 *src = reinterpret_cast<const float4 *>(lut + ((int64_t)q * K + k0) * ICQ_LUT_W);
+    {   // tables -> LDS: 4*WORDS tables, one per sub-code byte of a record; tables that do
+        // not take part (k < k0: already in the crude distance; k >= K: padding bytes) are
+        // zero, so the sum below needs no conditions: adding +0 leaves it unchanged.
+        const float4 *src = reinterpret_cast<const float4 *>(lut + (int64_t)q * K * ICQ_LUT_W);
         float4 *dst = reinterpret_cast<float4 *>(T);
-        const int n4 = (K - k0) * (ICQ_LUT_W / 4);
-        for (int i0 = 0; i0 < n4; i0 += 4 * RF_THREADS) {
-            float4 v[4];
+        constexpr int N4 = 4 * WORDS * (ICQ_LUT_W / 4);
+        float4 v[(N4 + RF_THREADS - 1) / RF_THREADS];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int i = i0 + r * RF_THREADS + tid;
-                if (i < n4) v[r] = src[i];
-            }
+        for (int r = 0; r < (N4 + RF_THREADS - 1) / RF_THREADS; ++r) {
+            const int i = r * RF_THREADS + tid;
+            const int k = i / (ICQ_LUT_W / 4);
+            v[r] = (i < N4 && k >= k0 && k < K) ? src[i] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        }
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int i = i0 + r * RF_THREADS + tid;
-                if (i < n4) dst[i] = v[r];
-            }
+        for (int r = 0; r < (N4 + RF_THREADS - 1) / RF_THREADS; ++r) {
+            const int i = r * RF_THREADS + tid;
+            if (i < N4) dst[i] = v[r];
         }
     }
     if (tid == 0) sh.cnt = 0;
@@ -330,51 +335,65 @@ __global__ __launch_bounds__(RF_THREADS) void refine_select_kernel(
     __syncthreads();   // tables in LDS
 
     uint32_t ubound = 0xFFFFFFFFu;   // keep u <= ubound
-    for (u64 c = 0; c < n; c += RS_FIRST) {
-        uint32_t id[RS_CHUNK], rec[RS_CHUNK][WORDS], u[RS_CHUNK];
-        float D[RS_CHUNK];
+    // Software pipeline over the chunks: ids (and crude distances) are loaded two chunks
+    // ahead, records one chunk ahead, so their round trips overlap the table lookups and
+    // the barriers of the chunk being processed.
+    uint32_t idA[RS_CHUNK], idB[RS_CHUNK], idC[RS_CHUNK];
+    uint32_t recA[RS_CHUNK][RW], recB[RS_CHUNK][RW];
+    float DA[RS_CHUNK], DB[RS_CHUNK], DC[RS_CHUNK];
+    // Loads are unconditional with the index clamped to the last candidate (n > 0 here):
+    // without branches around them they all go out back to back and are waited for once.
+    auto load_ids = [&](u64 c, uint32_t(&id)[RS_CHUNK], float(&D)[RS_CHUNK]) {
 #pragma unroll
         for (int j = 0; j < RS_CHUNK; ++j) {
             const u64 i = c + j * RF_THREADS + tid;
-            id[j] = i < n ? ids[i] : 0u;
-            D[j] = (part && i < n) ? part[i] : 0.0f;
+            const u64 ic = i < n ? i : n - 1;
+            id[j] = ids[ic];
+            D[j] = part ? part[ic] : 0.0f;
         }
+    };
+    auto load_recs = [&](u64 c, const uint32_t(&id)[RS_CHUNK], uint32_t(&rec)[RS_CHUNK][RW]) {
 #pragma unroll
         for (int j = 0; j < RS_CHUNK; ++j) {
             const u64 i = c + j * RF_THREADS + tid;
-            const uint32_t *p = recs ? recs + (size_t)i * WORDS
-                                     : reinterpret_cast<const uint32_t *>(items + (size_t)id[j] * (WORDS * 4));
+            const u64 ic = i < n ? i : n - 1;
+            const uint32_t *p = recs ? recs + (size_t)ic * RW
+                                     : reinterpret_cast<const uint32_t *>(items + (size_t)id[j] * (RW * 4));
+            if (RW == 1) {
+                rec[j][0] = p[0];
+            } else if (RW == 2) {
+                const uint2 v = *reinterpret_cast<const uint2 *>(p);
+                rec[j][0] = v.x;
+                rec[j][1 % RW] = v.y;
+            } else {
 #pragma unroll
-            for (int w = 0; w < WORDS; ++w) rec[j][w] = 0u;
-            if (i < n) {
-                if (WORDS == 1) {
-                    rec[j][0] = p[0];
-                } else if (WORDS == 2) {
-                    const uint2 v = *reinterpret_cast<const uint2 *>(p);
-                    rec[j][0] = v.x;
-                    rec[j][1 % WORDS] = v.y;
-                } else {
-                    const uint4 v = *reinterpret_cast<const uint4 *>(p);
-                    rec[j][0] = v.x;
-                    rec[j][1 % WORDS] = v.y;
-                    rec[j][2 % WORDS] = v.z;
-                    rec[j][3 % WORDS] = v.w;
+                for (int w4 = 0; w4 < RW / 4; ++w4) {
+                    const uint4 v = reinterpret_cast<const uint4 *>(p)[w4];
+                    rec[j][(4 * w4) % RW] = v.x;
+                    rec[j][(4 * w4 + 1) % RW] = v.y;
+                    rec[j][(4 * w4 + 2) % RW] = v.z;
+                    rec[j][(4 * w4 + 3) % RW] = v.w;
                 }
             }
         }
+    };
+    if (n > 0) {
+    load_ids(0, idA, DA);
+    load_ids(RS_FIRST, idB, DB);
+    load_recs(0, idA, recA);
+    for (u64 c = 0; c < n; c += RS_FIRST) {
+        load_recs(c + RS_FIRST, idB, recB);
+        load_ids(c + 2 * (u64)RS_FIRST, idC, DC);
+        uint32_t u[RS_CHUNK], id[RS_CHUNK];
 #pragma unroll
         for (int j = 0; j < RS_CHUNK; ++j) {
-            float d = D[j];
+            id[j] = GROUPED ? recA[j][WORDS % RW] : idA[j];   // grouped records carry the item id
+            float d = DA[j];
 #pragma unroll
             for (int w = 0; w < WORDS; ++w) {
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const int k = w * 4 + b;
-                    if (k >= k0 && k < K) {
-                        const float v = T[(k - k0) * ICQ_LUT_W + ((rec[j][w] >> (8 * b)) & 0xffu)];
-                        d = (k == 0) ? v : d + v;
-                    }
-                }
+                for (int b = 0; b < 4; ++b)
+                    d += T[(w * 4 + b) * ICQ_LUT_W + ((recA[j][w] >> (8 * b)) & 0xffu)];
             }
             u[j] = order_bits(d);
         }
@@ -436,7 +455,17 @@ __global__ __launch_bounds__(RF_THREADS) void refine_select_kernel(
             if (tid == 0) sh.cnt = kept;
             __syncthreads();
         }
+#pragma unroll
+        for (int j = 0; j < RS_CHUNK; ++j) {
+            idA[j] = idB[j];
+            idB[j] = idC[j];
+            DA[j] = DB[j];
+            DB[j] = DC[j];
+#pragma unroll
+            for (int w = 0; w < RW; ++w) recA[j][w] = recB[j][w];
+        }
     }
+    }   // n > 0
 
     // ---- final order
     const uint32_t m = sh.cnt < (uint32_t)RS_LIST ? sh.cnt : (uint32_t)RS_LIST;
@@ -473,41 +502,43 @@ int icq_refine_splits(const icq_index *ix, int Q, int64_t cap, int topk) {
 }
 
 int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32_t *cand_ids,
-                      const float *cand_part, const uint32_t *cand_rec, const uint32_t *cand_count,
-                      int64_t cap, int topk, int splits, u64 *keys, uint32_t *out_ids, float *out_dist,
-                      hipStream_t s) {
+                      const float *cand_part, const uint32_t *cand_rec, int list_kind,
+                      const uint32_t *cand_count, int64_t cap, int topk, int splits, u64 *keys,
+                      uint32_t *out_ids, float *out_dist, hipStream_t s) {
     if (Q == 0) return ICQ_OK;
+    const uint8_t *items = list_kind == ICQ_LIST_POSITIONS ? ix->items_grouped : ix->items;
+    const uint32_t *perm = list_kind == ICQ_LIST_POSITIONS ? ix->perm : nullptr;
+    if (list_kind != ICQ_LIST_IDS_REC) cand_rec = nullptr;
     const unsigned grid = (unsigned)Q * (unsigned)splits;
     const size_t tab = sizeof(float) * (size_t)(cand_part ? ix->Ks : ix->K) * ICQ_LUT_W;
     if (use_select(ix)) {
-        const size_t lds = sizeof(u64) * RS_LIST + sizeof(uint32_t) * RS_FIRST + tab;
-        static bool sel_attr_set = false;
-        if (!sel_attr_set) {
-            ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&refine_select_kernel<1>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 98304));
-            ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&refine_select_kernel<2>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 98304));
-            ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&refine_select_kernel<4>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 98304));
-            sel_attr_set = true;
-        }
+        const size_t lds = sizeof(u64) * RS_LIST + sizeof(uint32_t) * RS_FIRST +
+                           sizeof(float) * (size_t)ix->item_stride * ICQ_LUT_W;   // one table per record byte
+#define ICQ_RS_LAUNCH(W, G)                                                                            \
+    do {                                                                                               \
+        static bool attr_set = false;                                                                  \
+        if (!attr_set) {                                                                               \
+            ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&refine_select_kernel<W, G>),\
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 98304));       \
+            attr_set = true;                                                                           \
+        }                                                                                              \
+        refine_select_kernel<W, G><<<grid, RF_THREADS, lds, s>>>(items, ix->K, ix->Kf, lut, cand_ids,  \
+                                                                 cand_part, cand_rec, cand_count, cap, \
+                                                                 topk, splits, keys, out_ids, out_dist);\
+    } while (0)
+        const bool grouped = list_kind == ICQ_LIST_POSITIONS;
         switch (ix->item_stride) {
             case 4:
-                refine_select_kernel<1><<<grid, RF_THREADS, lds, s>>>(
-                    ix->items, ix->K, ix->Kf, lut, cand_ids, cand_part, cand_rec, cand_count, cap, topk,
-                    splits, keys, out_ids, out_dist);
+                if (grouped) ICQ_RS_LAUNCH(1, true); else ICQ_RS_LAUNCH(1, false);
                 break;
             case 8:
-                refine_select_kernel<2><<<grid, RF_THREADS, lds, s>>>(
-                    ix->items, ix->K, ix->Kf, lut, cand_ids, cand_part, cand_rec, cand_count, cap, topk,
-                    splits, keys, out_ids, out_dist);
+                if (grouped) ICQ_RS_LAUNCH(2, true); else ICQ_RS_LAUNCH(2, false);
                 break;
             default:
-                refine_select_kernel<4><<<grid, RF_THREADS, lds, s>>>(
-                    ix->items, ix->K, ix->Kf, lut, cand_ids, cand_part, cand_rec, cand_count, cap, topk,
-                    splits, keys, out_ids, out_dist);
+                if (grouped) ICQ_RS_LAUNCH(4, true); else ICQ_RS_LAUNCH(4, false);
                 break;
         }
+#undef ICQ_RS_LAUNCH
     } else {
         const int bufn = bufn_for(topk);
         const size_t lds = sizeof(u64) * bufn + tab;
@@ -517,9 +548,10 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
                                             hipFuncAttributeMaxDynamicSharedMemorySize, 98304));
             attr_set = true;
         }
-        refine_kernel<<<grid, RF_THREADS, lds, s>>>(ix->items, ix->item_stride, ix->K, ix->Kf, lut,
-                                                    cand_ids, cand_part, cand_count, cap, topk, bufn,
-                                                    splits, keys, out_ids, out_dist);
+        const int rec_stride = list_kind == ICQ_LIST_POSITIONS ? 2 * ix->item_stride : ix->item_stride;
+        refine_kernel<<<grid, RF_THREADS, lds, s>>>(items, rec_stride, ix->K, ix->Kf, lut,
+                                                    cand_ids, cand_part, perm, cand_count, cap, topk,
+                                                    bufn, splits, keys, out_ids, out_dist);
     }
     if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;
     if (splits > 1) {
@@ -546,6 +578,6 @@ ICQ_EXPORT int icq_refine(const icq_index *ix, const float *lut, int Q, const ui
         (!workspace || ((uintptr_t)workspace % ICQ_ALIGN) != 0 || workspace_bytes < L.total))
         return ICQ_ERR_WORKSPACE;
     u64 *keys = reinterpret_cast<u64 *>(static_cast<char *>(workspace) + L.keys_off);
-    return icq_launch_refine(ix, lut, Q, cand_ids, cand_part, nullptr, cand_count, cap, topk, L.splits,
-                             keys, out_ids, out_dist, (hipStream_t)stream);
+    return icq_launch_refine(ix, lut, Q, cand_ids, cand_part, nullptr, ICQ_LIST_IDS, cand_count, cap, topk,
+                             L.splits, keys, out_ids, out_dist, (hipStream_t)stream);
 }

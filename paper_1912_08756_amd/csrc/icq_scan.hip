@@ -565,21 +565,34 @@ int launch_batch_rec(const icq_index *ix, int Q, const float *thr, uint32_t *can
 }  // namespace
 
 int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
-                    uint32_t *cand_ids, float *cand_part, uint32_t *cand_rec, bool *rec_written,
+                    uint32_t *cand_ids, float *cand_part, uint32_t *cand_rec, int *list_kind,
                     uint32_t *cand_count, int64_t cap, float *lutT, hipStream_t s) {
-    if (rec_written) *rec_written = false;
+    if (list_kind) *list_kind = ICQ_LIST_IDS;
     if (Q == 0) return ICQ_OK;
     zero_counts_kernel<<<(Q + 255) / 256, 256, 0, s>>>(cand_count, Q);
     if (ix->N == 0) return icq_check_launch();
+
+    const int bpq_fill = (int)((cap + 255) / 256 < 32 ? (cap + 255) / 256 : 32);
+    if (icq_group_usable(ix, Q)) {
+        // positions only when the caller can take them and needs no crude distances
+        const bool as_positions = list_kind != nullptr && cand_part == nullptr;
+        int rc = icq_launch_group_scan(ix, lut, Q, thr, cand_ids, as_positions, cand_count, cap, s);
+        if (rc != ICQ_OK) return rc;
+        if (as_positions) *list_kind = ICQ_LIST_POSITIONS;
+        if (!cand_part) return ICQ_OK;
+        fill_partials_kernel<<<(unsigned)Q * (unsigned)bpq_fill, 256, 0, s>>>(
+            ix->fast, ix->Npad, lut, ix->K, ix->Kf, cand_ids, cand_count, cap, bpq_fill, cand_part);
+        return icq_check_launch();
+    }
 
     if (ix->Kf <= 2 && Q >= 8) {
         const int tiles = (Q + 63) / 64;
         dim3 g((unsigned)tiles, (unsigned)ix->Kf);
         transpose_fast_lut_kernel<<<g, 256, 0, s>>>(lut, Q, ix->K, ix->Kf, lutT);
-        if (ix->item_stride > 16) cand_rec = nullptr;   // wide records stay with stage 2
+        if (ix->item_stride > 16 || !list_kind) cand_rec = nullptr;   // wide records stay with stage 2
         int rc = ix->Kf == 1 ? launch_batch_rec<1>(ix, Q, thr, cand_ids, cand_rec, cand_count, cap, lutT, s)
                              : launch_batch_rec<2>(ix, Q, thr, cand_ids, cand_rec, cand_count, cap, lutT, s);
-        if (rec_written) *rec_written = cand_rec != nullptr;
+        if (list_kind && cand_rec) *list_kind = ICQ_LIST_IDS_REC;
         if (rc != ICQ_OK || !cand_part) return rc;
         const int bpq = (int)((cap + 255) / 256 < 32 ? (cap + 255) / 256 : 32);
         fill_partials_kernel<<<(unsigned)Q * (unsigned)bpq, 256, 0, s>>>(

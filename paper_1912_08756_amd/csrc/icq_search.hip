@@ -17,7 +17,7 @@ icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool
     L.ids_off = off;
     if (with_cands) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
     L.rec_off = off;    // item records of the survivors (the fused path keeps no crude distances)
-    if (with_cands && ix->item_stride <= 16)
+    if (with_cands && ix->item_stride <= 16 && !icq_group_usable(ix, Q))
         off = icq_align_up(off + (size_t)ix->item_stride * (size_t)Q * (size_t)cap, ICQ_ALIGN);
     L.count_off = off;
     if (with_cands) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q, ICQ_ALIGN);
@@ -69,13 +69,13 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
         unsigned long long *keys = reinterpret_cast<unsigned long long *>(ws + L.keys_off);
         int rc = icq_launch_build_lut(ix, queries + (int64_t)q0 * ix->d, nq, lut, s);
         if (rc != ICQ_OK) return rc;
-        uint32_t *rec = ix->item_stride <= 16 ? reinterpret_cast<uint32_t *>(ws + L.rec_off) : nullptr;
-        bool rec_written = false;
-        rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, nullptr, rec, &rec_written, cnt, cap,
+        uint32_t *rec = (ix->item_stride <= 16 && !icq_group_usable(ix, nq))
+                            ? reinterpret_cast<uint32_t *>(ws + L.rec_off) : nullptr;
+        int list_kind = ICQ_LIST_IDS;
+        rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, nullptr, rec, &list_kind, cnt, cap,
                              lutT, s);
         if (rc != ICQ_OK) return rc;
-        rc = icq_launch_refine(ix, lut, nq, ids, nullptr, rec_written ? rec : nullptr, cnt, cap, topk,
-                               L.splits, keys,
+        rc = icq_launch_refine(ix, lut, nq, ids, nullptr, rec, list_kind, cnt, cap, topk, L.splits, keys,
                                out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
         if (rc != ICQ_OK) return rc;
     }

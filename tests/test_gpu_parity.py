@@ -33,7 +33,7 @@ def _u32(t):
 class Gpu:
     """Thin test driver around the binding for one workload."""
 
-    def __init__(self, gpu, cfg):
+    def __init__(self, gpu, cfg, mode=0):
         self.torch, self.b = gpu
         torch = self.torch
         self.cfg = cfg
@@ -41,6 +41,7 @@ class Gpu:
         self.codes = _dev(torch, cfg["codes"])
         self.queries = _dev(torch, cfg["queries"])
         self.index = self.b.icq_index_create(self.cb, self.codes, cfg["Kf"])
+        self.b.icq_index_set_scan_mode(self.index, mode)    # 0 auto, 1 streamed, 2 grouped
         self.K, self.Q, self.N = cfg["K"], cfg["queries"].shape[0], cfg["codes"].shape[1]
 
     def workspace(self, Q, cap, topk, nbytes=None):
@@ -107,7 +108,7 @@ def test_storage_round_trip_is_bit_exact(gpu, K, Kf, N):
     torch, b = gpu
     cfg = synth.make("C0", N=N, Q=1, K=K, Kf=Kf, sigma=("geom", 0.7))
     g = Gpu(gpu, cfg)
-    for from_items in (0, 1):
+    for from_items in (0, 1, 2) if Kf <= 2 else (0, 1):
         out = torch.zeros((K, N), dtype=torch.uint8, device="cuda")
         b.icq_index_export_codes(g.index, from_items, out)
         torch.cuda.synchronize()
@@ -153,10 +154,13 @@ def _thr(P, rule):
     return thresholds_quantile(P, rule[1])
 
 
+@pytest.mark.parametrize("mode", [1, 2], ids=["streamed", "grouped"])
 @pytest.mark.parametrize("name,N,Q,over,rule", SCAN_CASES)
-def test_scan_fast_candidates_match_oracle(gpu, name, N, Q, over, rule):
+def test_scan_fast_candidates_match_oracle(gpu, name, N, Q, over, rule, mode):
     cfg = small(name, N, Q, **over)
-    g = Gpu(gpu, cfg)
+    if mode == 2 and cfg["Kf"] > 2:
+        pytest.skip("grouping exists for Kf <= 2 only")
+    g = Gpu(gpu, cfg, mode)
     T, P, D = oracle_all(cfg)
     thr = _thr(P, rule)
     cap = int((P < thr[:, None].astype(np.float64)).sum(axis=1).max() * 1.2) + 64
@@ -174,10 +178,11 @@ def test_scan_fast_candidates_match_oracle(gpu, name, N, Q, over, rule):
         assert np.array_equal(np.sort(ids[q][:cnt[q]]), np.sort(ids2[q][:cnt2[q]]))
 
 
+@pytest.mark.parametrize("mode", [1, 2], ids=["streamed", "grouped"])
 @pytest.mark.parametrize("Q", [2, 70])
-def test_scan_fast_special_thresholds_and_overflow(gpu, Q):
+def test_scan_fast_special_thresholds_and_overflow(gpu, Q, mode):
     cfg = small("C1", 3000, Q)
-    g = Gpu(gpu, cfg)
+    g = Gpu(gpu, cfg, mode)
     T, P, D = oracle_all(cfg)
     N = 3000
     lut = g.lut()
@@ -213,7 +218,7 @@ def test_scan_fast_special_thresholds_and_overflow(gpu, Q):
 ])
 def test_refine_matches_oracle(gpu, name, N, Q, over, rule, topk):
     cfg = small(name, N, Q, **over)
-    g = Gpu(gpu, cfg)
+    g = Gpu(gpu, cfg, 1)
     T, P, D = oracle_all(cfg)
     thr = _thr(P, rule)
     cap = int((P < thr[:, None].astype(np.float64)).sum(axis=1).max() * 1.2) + 64
@@ -238,10 +243,14 @@ def test_refine_matches_oracle(gpu, name, N, Q, over, rule, topk):
     ("C4", 120_000, 128, {}, ("q", 0.01)),
     ("C1", 2_000, 1, {}, ("q", 0.01)),                    # one query
     ("C1", 300, 33, {}, ("kth", 3, 1.0)),                 # fewer survivors than topk
+    ("C0", 70_000, 40, {}, ("q", 0.02)),                  # Kf = 1: 256 groups of ~270 items
 ])
-def test_search_matches_oracle(gpu, name, N, Q, over, rule):
+@pytest.mark.parametrize("mode", [1, 2], ids=["streamed", "grouped"])
+def test_search_matches_oracle(gpu, name, N, Q, over, rule, mode):
     cfg = small(name, N, Q, **over)
-    g = Gpu(gpu, cfg)
+    if mode == 2 and cfg["Kf"] > 2:
+        pytest.skip("grouping exists for Kf <= 2 only")
+    g = Gpu(gpu, cfg, mode)
     T, P, D = oracle_all(cfg)
     thr = _thr(P, rule)
     topk = cfg["topk"]
@@ -319,7 +328,8 @@ def test_argument_errors_on_a_live_index(gpu):
 
 
 # ------------------------------------------------------------------ full size, as benchmarked
-def test_full_size_workload_sampled_against_oracle(gpu):
+@pytest.mark.parametrize("mode", [0, 1], ids=["auto", "streamed"])
+def test_full_size_workload_sampled_against_oracle(gpu, mode):
     """The benchmark's workload (C1: N = 1e6, Q = 1e4, top-100) in the benchmark's launch
     configuration (all queries in one icq_search call, same candidate capacity and the
     same sampled-quantile thresholds).  A sample of queries is checked against the
@@ -329,7 +339,7 @@ def test_full_size_workload_sampled_against_oracle(gpu):
     torch, b = gpu
     cfg = synth.make("C1")
     N, Q, Kf, topk = cfg["N"], cfg["Q"], cfg["Kf"], cfg["topk"]
-    g = Gpu(gpu, cfg)
+    g = Gpu(gpu, cfg, mode)
     thr_dev = bench.sampled_thresholds(torch, b, g.cb, g.codes, g.queries, Kf, bench.SURVIVE_FRAC, 16384,
                                        cfg["seed"])
     thr = thr_dev.cpu().numpy()
