@@ -208,104 +208,60 @@ __global__ __launch_bounds__(RF_THREADS) void merge_kernel(const u64 *__restrict
 
 int bufn_for(int topk) { return topk <= 256 ? 2048 : 4096; }
 
-// ------------------------------------------------------------------ bounded stream + radix select
-// One block owns one slice of one query's candidate list, of any length, and
-// walks it in chunks of RS_FIRST candidates.  The distances of the first chunk
-// go to LDS as order-preserving bits; an exact radix select (8-bit digits over
-// the occupied range, LDS histograms) finds their topk-th value, which becomes
-// the bound: from then on only candidates at or below the bound are kept, in a
-// list of 64-bit keys (bits of D, id).  The list is sorted once at the end (a
-// few hundred keys for a 10^4-candidate list); should an adversarial order fill
-// it first, it is sorted, cut back to topk and the bound tightened.
-constexpr int RS_CHUNK = 8;                          // candidates per thread and chunk
-constexpr int RS_FIRST = RF_THREADS * RS_CHUNK;      // 2048
-constexpr int RS_LIST = 4096;                        // key list capacity (>= topk + RS_FIRST)
+// ------------------------------------------------------------------ distances, then bounded select
+// Stage 2 runs as two kernels.
+//   refine_dist_kernel: flat over all candidates of all queries, many small blocks at
+//     full occupancy.  A block owns RD_BLOCK consecutive candidates of one query,
+//     keeps that query's tables in LDS (one table per record byte; tables that do not
+//     take part are zero, so the sum has no conditions) and writes one 64-bit key
+//     (order-preserving bits of D, item id) per candidate.
+//   select_keys_kernel: one wavefront per (query, slice) streams the keys.  An exact
+//     radix select (8-bit digits over the occupied range, LDS histogram) over the first
+//     512 keys gives their topk-th distance, the bound; afterwards only keys at or
+//     below the bound enter a key list (ballot compaction).  Whenever the list could
+//     overflow it is bitonic-sorted, cut to topk and the bound tightened; the final
+//     sort orders the result.
+constexpr int RD_PER = 8;                            // candidates per thread and step
+constexpr int RD_STEP = RF_THREADS * RD_PER;         // 2048
+constexpr int RD_BLOCK = 2 * RD_STEP;                // candidates per block
 
-struct SelectShared {
-    uint32_t hist[256];
-    uint32_t wsum[4];
-    uint32_t red[8];
-    uint32_t bin, below, ties, cnt;
-};
-
-// Locate the bin that holds the kr-th smallest element (1-based) of a complete
-// histogram; all threads call; results in sh->bin / below / ties.
-__device__ __forceinline__ void find_bin(SelectShared *sh, uint32_t kr) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t h = sh->hist[tid];
-    uint32_t incl = h;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(incl, d, 64);
-        if (lane >= d) incl += o;
-    }
-    if (lane == 63) sh->wsum[wave] = incl;
-    __syncthreads();
-    uint32_t cum = incl;
-    for (int w = 0; w < wave; ++w) cum += sh->wsum[w];
-    if (cum >= kr && cum - h < kr) {
-        sh->bin = (uint32_t)tid;
-        sh->below = cum - h;
-        sh->ties = h;
-    }
-    __syncthreads();
-}
-
-// The kr-th smallest (1-based) of U[0..n), n >= kr >= 1; vmin/vmax bound the values.
-__device__ uint32_t block_radix_select(SelectShared *sh, const uint32_t *U, uint32_t n, uint32_t kr,
-                                       uint32_t vmin, uint32_t vmax) {
-    const int tid = threadIdx.x;
-    const uint32_t range = vmax - vmin;
-    const int bits = range == 0 ? 0 : 32 - __builtin_clz(range);
-    int shift = bits > 8 ? bits - 8 : 0;
-    int width = bits < 8 ? bits : 8;
-    uint32_t prefix = 0;       // chosen high digits of (value - vmin)
-    int fixed_from = bits;     // bits [fixed_from, 32) of (value - vmin) are decided
-    for (;;) {
-        sh->hist[tid] = 0;
-        __syncthreads();
-        const uint32_t dmask = (1u << width) - 1u;
-        for (uint32_t i = tid; i < n; i += RF_THREADS) {
-            const uint32_t y = U[i] - vmin;
-            const bool match = fixed_from >= 32 ? true : (y >> fixed_from) == prefix;
-            if (match) atomicAdd(&sh->hist[(y >> shift) & dmask], 1u);
-        }
-        __syncthreads();
-        find_bin(sh, kr);
-        kr -= sh->below;
-        prefix = (prefix << width) | sh->bin;
-        fixed_from = shift;
-        if (shift == 0) break;
-        const int ns = shift > 8 ? shift - 8 : 0;
-        width = shift - ns;
-        shift = ns;
-    }
-    return vmin + prefix;
-}
-
-// LDS: keys[RS_LIST] (u64) | U[RS_FIRST] (u32) | tables k0..K-1 (f32)
 // GROUPED: the list holds grouped positions and `items` is the grouped record array,
 // whose records are 2*WORDS words: the sub-codes, then the item id in word WORDS.
 template <int WORDS, bool GROUPED>
-__global__ __launch_bounds__(RF_THREADS) void refine_select_kernel(
+__global__ __launch_bounds__(RF_THREADS) void refine_dist_kernel(
     const uint8_t *__restrict__ items, int K, int Kf, const float *__restrict__ lut,
     const uint32_t *__restrict__ cand_ids, const float *__restrict__ cand_part,
     const uint32_t *__restrict__ cand_rec, const uint32_t *__restrict__ cand_count, int64_t cap,
-    int topk, int splits, u64 *__restrict__ keys_out, uint32_t *__restrict__ out_ids,
-    float *__restrict__ out_dist) {
-    extern __shared__ u64 smem64[];
-    __shared__ SelectShared sh;
+    int blocks_per_query, u64 *__restrict__ keys) {
+    __shared__ float T[4 * WORDS * ICQ_LUT_W];
     constexpr int RW = GROUPED ? 2 * WORDS : WORDS;   // words per record as stored
-    u64 *keys = smem64;
-    uint32_t *U = reinterpret_cast<uint32_t *>(keys + RS_LIST);
-    float *T = reinterpret_cast<float *>(U + RS_FIRST);
+    const int q = blockIdx.x / blocks_per_query;
+    const u64 c0 = (u64)(blockIdx.x % blocks_per_query) * RD_BLOCK;
+    const int tid = threadIdx.x;
+    u64 n = cand_count[q];
+    if (n > (u64)cap) n = (u64)cap;
+    if (c0 >= n) return;                              // block-uniform
     const int k0 = cand_part ? Kf : 0;
-    const int q = blockIdx.x / splits, sp = blockIdx.x % splits;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t *ids = cand_ids + (int64_t)q * cap;
+    const float *part = cand_part ? cand_part + (int64_t)q * cap : nullptr;
+    const uint32_t *recs = cand_rec ? cand_rec + (int64_t)q * cap * RW : nullptr;
+    u64 *out = keys + (int64_t)q * cap;
 
-    {   // tables -> LDS: 4*WORDS tables, one per sub-code byte of a record; tables that do
-        // not take part (k < k0: already in the crude distance; k >= K: padding bytes) are
-        // zero, so the sum below needs no conditions: adding +0 leaves it unchanged.
+    // Loads are unconditional with the index clamped to the last candidate: without
+    // branches around them they all go out back to back and are waited for once.
+    uint32_t id[2][RD_PER], rec[2][RD_PER][RW];
+    float D[2][RD_PER];
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+#pragma unroll
+        for (int j = 0; j < RD_PER; ++j) {
+            const u64 i = c0 + (u64)st * RD_STEP + j * RF_THREADS + tid;
+            const u64 ic = i < n ? i : n - 1;
+            id[st][j] = ids[ic];
+            D[st][j] = part ? part[ic] : 0.0f;
+        }
+    }
+    {   // tables -> LDS
         const float4 *src = reinterpret_cast<const float4 *>(lut + (int64_t)q * K * ICQ_LUT_W);
         float4 *dst = reinterpret_cast<float4 *>(T);
         constexpr int N4 = 4 * WORDS * (ICQ_LUT_W / 4);
@@ -322,164 +278,262 @@ __global__ __launch_bounds__(RF_THREADS) void refine_select_kernel(
             if (i < N4) dst[i] = v[r];
         }
     }
-    if (tid == 0) sh.cnt = 0;
-
-    u64 ntot = cand_count[q];
-    if (ntot > (u64)cap) ntot = (u64)cap;
-    const u64 lo = ntot * (u64)sp / (u64)splits, hi = ntot * (u64)(sp + 1) / (u64)splits;
-    const u64 n = hi - lo;
-    const uint32_t *ids = cand_ids + (int64_t)q * cap + lo;
-    const float *part = cand_part ? cand_part + (int64_t)q * cap + lo : nullptr;
-    // records either listed next to the ids by stage 1 or gathered here by id
-    const uint32_t *recs = cand_rec ? cand_rec + ((int64_t)q * cap + lo) * WORDS : nullptr;
-    __syncthreads();   // tables in LDS
-
-    uint32_t ubound = 0xFFFFFFFFu;   // keep u <= ubound
-    // Software pipeline over the chunks: ids (and crude distances) are loaded two chunks
-    // ahead, records one chunk ahead, so their round trips overlap the table lookups and
-    // the barriers of the chunk being processed.
-    uint32_t idA[RS_CHUNK], idB[RS_CHUNK], idC[RS_CHUNK];
-    uint32_t recA[RS_CHUNK][RW], recB[RS_CHUNK][RW];
-    float DA[RS_CHUNK], DB[RS_CHUNK], DC[RS_CHUNK];
-    // Loads are unconditional with the index clamped to the last candidate (n > 0 here):
-    // without branches around them they all go out back to back and are waited for once.
-    auto load_ids = [&](u64 c, uint32_t(&id)[RS_CHUNK], float(&D)[RS_CHUNK]) {
 #pragma unroll
-        for (int j = 0; j < RS_CHUNK; ++j) {
-            const u64 i = c + j * RF_THREADS + tid;
-            const u64 ic = i < n ? i : n - 1;
-            id[j] = ids[ic];
-            D[j] = part ? part[ic] : 0.0f;
-        }
-    };
-    auto load_recs = [&](u64 c, const uint32_t(&id)[RS_CHUNK], uint32_t(&rec)[RS_CHUNK][RW]) {
+    for (int st = 0; st < 2; ++st) {
 #pragma unroll
-        for (int j = 0; j < RS_CHUNK; ++j) {
-            const u64 i = c + j * RF_THREADS + tid;
+        for (int j = 0; j < RD_PER; ++j) {
+            const u64 i = c0 + (u64)st * RD_STEP + j * RF_THREADS + tid;
             const u64 ic = i < n ? i : n - 1;
             const uint32_t *p = recs ? recs + (size_t)ic * RW
-                                     : reinterpret_cast<const uint32_t *>(items + (size_t)id[j] * (RW * 4));
+                                     : reinterpret_cast<const uint32_t *>(items + (size_t)id[st][j] * (RW * 4));
             if (RW == 1) {
-                rec[j][0] = p[0];
+                rec[st][j][0] = p[0];
             } else if (RW == 2) {
                 const uint2 v = *reinterpret_cast<const uint2 *>(p);
-                rec[j][0] = v.x;
-                rec[j][1 % RW] = v.y;
+                rec[st][j][0] = v.x;
+                rec[st][j][1 % RW] = v.y;
             } else {
 #pragma unroll
                 for (int w4 = 0; w4 < RW / 4; ++w4) {
                     const uint4 v = reinterpret_cast<const uint4 *>(p)[w4];
-                    rec[j][(4 * w4) % RW] = v.x;
-                    rec[j][(4 * w4 + 1) % RW] = v.y;
-                    rec[j][(4 * w4 + 2) % RW] = v.z;
-                    rec[j][(4 * w4 + 3) % RW] = v.w;
+                    rec[st][j][(4 * w4) % RW] = v.x;
+                    rec[st][j][(4 * w4 + 1) % RW] = v.y;
+                    rec[st][j][(4 * w4 + 2) % RW] = v.z;
+                    rec[st][j][(4 * w4 + 3) % RW] = v.w;
                 }
             }
         }
-    };
-    if (n > 0) {
-    load_ids(0, idA, DA);
-    load_ids(RS_FIRST, idB, DB);
-    load_recs(0, idA, recA);
-    for (u64 c = 0; c < n; c += RS_FIRST) {
-        load_recs(c + RS_FIRST, idB, recB);
-        load_ids(c + 2 * (u64)RS_FIRST, idC, DC);
-        uint32_t u[RS_CHUNK], id[RS_CHUNK];
+    }
+    __syncthreads();
 #pragma unroll
-        for (int j = 0; j < RS_CHUNK; ++j) {
-            id[j] = GROUPED ? recA[j][WORDS % RW] : idA[j];   // grouped records carry the item id
-            float d = DA[j];
+    for (int st = 0; st < 2; ++st) {
+#pragma unroll
+        for (int j = 0; j < RD_PER; ++j) {
+            float d = D[st][j];
 #pragma unroll
             for (int w = 0; w < WORDS; ++w) {
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
-                    d += T[(w * 4 + b) * ICQ_LUT_W + ((recA[j][w] >> (8 * b)) & 0xffu)];
+                    d += T[(w * 4 + b) * ICQ_LUT_W + ((rec[st][j][w] >> (8 * b)) & 0xffu)];
             }
-            u[j] = order_bits(d);
-        }
-
-        if (c == 0 && n > (u64)topk) {
-            // first chunk: its topk-th smallest distance bounds everything that follows
-            const uint32_t n1 = n < (u64)RS_FIRST ? (uint32_t)n : (uint32_t)RS_FIRST;
-            uint32_t umin = 0xFFFFFFFFu, umax = 0u;
-#pragma unroll
-            for (int j = 0; j < RS_CHUNK; ++j) {
-                const uint32_t i = j * RF_THREADS + tid;
-                if (i < n1) {
-                    U[i] = u[j];
-                    umin = u[j] < umin ? u[j] : umin;
-                    umax = u[j] > umax ? u[j] : umax;
-                }
-            }
-#pragma unroll
-            for (int d = 32; d > 0; d >>= 1) {
-                const uint32_t a = __shfl_xor(umin, d, 64), b = __shfl_xor(umax, d, 64);
-                umin = a < umin ? a : umin;
-                umax = b > umax ? b : umax;
-            }
-            if (lane == 0) {
-                sh.red[wave] = umin;
-                sh.red[4 + wave] = umax;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                umin = sh.red[w] < umin ? sh.red[w] : umin;
-                umax = sh.red[4 + w] > umax ? sh.red[4 + w] : umax;
-            }
-            if (n1 > (uint32_t)topk) ubound = block_radix_select(&sh, U, n1, (uint32_t)topk, umin, umax);
-        }
-
-        // keep what is at or below the bound (ties at the bound included; the final sort decides)
-#pragma unroll
-        for (int j = 0; j < RS_CHUNK; ++j) {
-            const u64 i = c + j * RF_THREADS + tid;
-            if (i < n && u[j] <= ubound) {
-                const uint32_t slot = atomicAdd(&sh.cnt, 1u);
-                if (slot < (uint32_t)RS_LIST) keys[slot] = ((u64)u[j] << 32) | id[j];
-            }
-        }
-        __syncthreads();
-        const uint32_t filled = sh.cnt;
-        __syncthreads();   // everyone has read the count before anyone appends again
-        if (filled > (uint32_t)(RS_LIST - RS_FIRST) && c + RS_FIRST < n) {
-            // the list could overflow in the next chunk: sort, cut back to topk, tighten the bound
-            const uint32_t m = filled < (uint32_t)RS_LIST ? filled : (uint32_t)RS_LIST;
-            int len = 2;
-            while (len < (int)m) len <<= 1;
-            for (int i = (int)m + tid; i < len; i += RF_THREADS) keys[i] = KEY_PAD;
-            __syncthreads();
-            block_sort(keys, len);
-            const uint32_t kept = m < (uint32_t)topk ? m : (uint32_t)topk;
-            if (m >= (uint32_t)topk) ubound = (uint32_t)(keys[topk - 1] >> 32);
-            if (tid == 0) sh.cnt = kept;
-            __syncthreads();
-        }
-#pragma unroll
-        for (int j = 0; j < RS_CHUNK; ++j) {
-            idA[j] = idB[j];
-            idB[j] = idC[j];
-            DA[j] = DB[j];
-            DB[j] = DC[j];
-#pragma unroll
-            for (int w = 0; w < RW; ++w) recA[j][w] = recB[j][w];
+            const u64 i = c0 + (u64)st * RD_STEP + j * RF_THREADS + tid;
+            const uint32_t item = GROUPED ? rec[st][j][WORDS % RW] : id[st][j];
+            if (i < n) out[i] = ((u64)order_bits(d) << 32) | item;
         }
     }
-    }   // n > 0
+}
+
+// One WAVEFRONT per (query, slice): nothing in the select needs more than 64 lanes,
+// and a one-wavefront block pays no barrier waits, so a CU keeps ~15 independent
+// selects in flight instead of 3 barrier-bound blocks.
+constexpr int SK_THREADS = 64;
+constexpr int SK_CHUNK = 8;                           // keys per lane and chunk
+constexpr int SK_FIRST = SK_THREADS * SK_CHUNK;       // 512
+
+struct SelectShared {
+    uint32_t hist[256];
+    uint32_t bin, below, cnt;
+};
+
+// Locate the bin that holds the kr-th smallest element (1-based) of a complete
+// 256-bin histogram with one wavefront (4 bins per lane).
+__device__ __forceinline__ void find_bin(SelectShared *sh, uint32_t kr) {
+    const int lane = threadIdx.x;
+    uint32_t h[4], mine = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        h[r] = sh->hist[lane * 4 + r];
+        mine += h[r];
+    }
+    uint32_t incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    uint32_t run = incl - mine;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        if (run < kr && run + h[r] >= kr) {
+            sh->bin = (uint32_t)(lane * 4 + r);
+            sh->below = run;
+        }
+        run += h[r];
+    }
+    __syncthreads();
+}
+
+// The kr-th smallest (1-based) of U[0..n), n >= kr >= 1; vmin/vmax bound the values.
+__device__ uint32_t wave_radix_select(SelectShared *sh, const uint32_t *U, uint32_t n, uint32_t kr,
+                                      uint32_t vmin, uint32_t vmax) {
+    const int tid = threadIdx.x;
+    const uint32_t range = vmax - vmin;
+    const int bits = range == 0 ? 0 : 32 - __builtin_clz(range);
+    int shift = bits > 8 ? bits - 8 : 0;
+    int width = bits < 8 ? bits : 8;
+    uint32_t prefix = 0;       // chosen high digits of (value - vmin)
+    int fixed_from = bits;     // bits [fixed_from, 32) of (value - vmin) are decided
+    for (;;) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sh->hist[tid * 4 + r] = 0;
+        __syncthreads();
+        const uint32_t dmask = (1u << width) - 1u;
+        for (uint32_t i = tid; i < n; i += SK_THREADS) {
+            const uint32_t y = U[i] - vmin;
+            const bool match = fixed_from >= 32 ? true : (y >> fixed_from) == prefix;
+            if (match) atomicAdd(&sh->hist[(y >> shift) & dmask], 1u);
+        }
+        __syncthreads();
+        find_bin(sh, kr);
+        kr -= sh->below;
+        prefix = (prefix << width) | sh->bin;
+        fixed_from = shift;
+        if (shift == 0) break;
+        const int ns = shift > 8 ? shift - 8 : 0;
+        width = shift - ns;
+        shift = ns;
+        __syncthreads();
+    }
+    return vmin + prefix;
+}
+
+// Ascending bitonic sort of keys[0..len) by ONE wavefront (len a power of two >= 2):
+// exchanges at distance < 64 by shuffles on the element a lane holds, the rest
+// through LDS; a single-wavefront block needs no waiting at the barriers.
+__device__ void wave_sort(u64 *keys, int len) {
+    const int lane = threadIdx.x;
+    for (int base = 0; base < len; base += 64) {
+        const int e = base + lane;
+        u64 x = e < len ? keys[e] : KEY_PAD;
+        for (int k = 2; k <= 64 && k <= len; k <<= 1) x = wave_bitonic_steps(x, e, k, k >> 1);
+        if (e < len) keys[e] = x;
+    }
+    __syncthreads();
+    for (int k = 128; k <= len; k <<= 1) {
+        for (int j = k >> 1; j >= 64; j >>= 1) {
+            for (int i = lane; i < len / 2; i += 64) {
+                const int a = ((i / j) * 2 * j) + (i % j);
+                const int b = a + j;
+                const bool up = (a & k) == 0;
+                const u64 x = keys[a], y = keys[b];
+                if ((x > y) == up) {
+                    keys[a] = y;
+                    keys[b] = x;
+                }
+            }
+            __syncthreads();
+        }
+        for (int base = 0; base < len; base += 64) {
+            const int e = base + lane;
+            keys[e] = wave_bitonic_steps(keys[e], e, k, 32);
+        }
+        __syncthreads();
+    }
+}
+
+// grid (Q * splits), block = one wavefront.  LDS: list[listcap] (u64) | U[SK_FIRST] (u32);
+// listcap is a power of two >= topk + SK_FIRST.
+__global__ __launch_bounds__(SK_THREADS) void select_keys_kernel(
+    const u64 *__restrict__ keys_in, const uint32_t *__restrict__ cand_count, int64_t cap, int topk,
+    int listcap, int splits, u64 *__restrict__ keys_out, uint32_t *__restrict__ out_ids,
+    float *__restrict__ out_dist) {
+    extern __shared__ u64 smem64[];
+    __shared__ SelectShared sh;
+    u64 *list = smem64;
+    uint32_t *U = reinterpret_cast<uint32_t *>(list + listcap);
+    const int q = blockIdx.x / splits, sp = blockIdx.x % splits;
+    const int tid = threadIdx.x;
+    u64 ntot = cand_count[q];
+    if (ntot > (u64)cap) ntot = (u64)cap;
+    const u64 lo = ntot * (u64)sp / (u64)splits, hi = ntot * (u64)(sp + 1) / (u64)splits;
+    const u64 n = hi - lo;
+    const u64 *in = keys_in + (int64_t)q * cap + lo;
+
+    uint32_t ubound = 0xFFFFFFFFu;   // keep keys whose distance bits are <= ubound
+    uint32_t cnt = 0;                // keys in the list (wave-uniform)
+    if (n > 0) {
+        u64 kA[SK_CHUNK], kB[SK_CHUNK];
+#pragma unroll
+        for (int j = 0; j < SK_CHUNK; ++j) {
+            const u64 i = (u64)j * SK_THREADS + tid;
+            kA[j] = in[i < n ? i : n - 1];
+        }
+        for (u64 c = 0; c < n; c += SK_FIRST) {
+#pragma unroll
+            for (int j = 0; j < SK_CHUNK; ++j) {   // one chunk ahead
+                const u64 i = c + SK_FIRST + (u64)j * SK_THREADS + tid;
+                kB[j] = in[i < n ? i : n - 1];
+            }
+            if (c == 0 && n > (u64)topk && (uint32_t)topk < (uint32_t)SK_FIRST) {
+                // first chunk: its topk-th smallest distance bounds everything that follows
+                const uint32_t n1 = n < (u64)SK_FIRST ? (uint32_t)n : (uint32_t)SK_FIRST;
+                uint32_t umin = 0xFFFFFFFFu, umax = 0u;
+#pragma unroll
+                for (int j = 0; j < SK_CHUNK; ++j) {
+                    const uint32_t i = j * SK_THREADS + tid;
+                    const uint32_t u = (uint32_t)(kA[j] >> 32);
+                    if (i < n1) {
+                        U[i] = u;
+                        umin = u < umin ? u : umin;
+                        umax = u > umax ? u : umax;
+                    }
+                }
+#pragma unroll
+                for (int d = 32; d > 0; d >>= 1) {
+                    const uint32_t a = __shfl_xor(umin, d, 64), b = __shfl_xor(umax, d, 64);
+                    umin = a < umin ? a : umin;
+                    umax = b > umax ? b : umax;
+                }
+                __syncthreads();
+                if (n1 > (uint32_t)topk) ubound = wave_radix_select(&sh, U, n1, (uint32_t)topk, umin, umax);
+            }
+            // keep what is at or below the bound (ties at the bound included; the final sort
+            // decides); ballot compaction, the list cursor is wave-uniform
+#pragma unroll
+            for (int j = 0; j < SK_CHUNK; ++j) {
+                const u64 i = c + (u64)j * SK_THREADS + tid;
+                const bool keep = i < n && (uint32_t)(kA[j] >> 32) <= ubound;
+                const uint64_t mask = __builtin_amdgcn_ballot_w64(keep);
+                if (keep) list[cnt + __builtin_popcountll(mask & ((1ull << tid) - 1))] = kA[j];
+                cnt += (uint32_t)__builtin_popcountll(mask);
+            }
+            if (cnt > (uint32_t)(listcap - SK_FIRST) && c + SK_FIRST < n) {
+                // the next chunk might not fit: sort, cut back to topk, tighten the bound
+                __syncthreads();
+                int len = 2;
+                while (len < (int)cnt) len <<= 1;
+                for (int i = (int)cnt + tid; i < len; i += SK_THREADS) list[i] = KEY_PAD;
+                __syncthreads();
+                wave_sort(list, len);
+                if (cnt >= (uint32_t)topk) {
+                    ubound = (uint32_t)(list[topk - 1] >> 32);
+                    cnt = (uint32_t)topk;
+                }
+                __syncthreads();
+            }
+#pragma unroll
+            for (int j = 0; j < SK_CHUNK; ++j) kA[j] = kB[j];
+        }
+    }
 
     // ---- final order
-    const uint32_t m = sh.cnt < (uint32_t)RS_LIST ? sh.cnt : (uint32_t)RS_LIST;
-    int len = 2;
-    while (len < (int)m) len <<= 1;
-    for (int i = (int)m + tid; i < len; i += RF_THREADS) keys[i] = KEY_PAD;
     __syncthreads();
-    block_sort(keys, len);
-    const int kept = (int)m < topk ? (int)m : topk;
-    if (splits == 1) {
-        write_result(keys, kept, topk, out_ids + (int64_t)q * topk, out_dist + (int64_t)q * topk);
-    } else {
-        u64 *dst = keys_out + ((int64_t)q * splits + sp) * topk;
-        for (int r = tid; r < topk; r += RF_THREADS) dst[r] = r < kept ? keys[r] : KEY_PAD;
+    int len = 2;
+    while (len < (int)cnt) len <<= 1;
+    for (int i = (int)cnt + tid; i < len; i += SK_THREADS) list[i] = KEY_PAD;
+    __syncthreads();
+    wave_sort(list, len);
+    const int kept = (int)cnt < topk ? (int)cnt : topk;
+    uint32_t *oi = out_ids + (int64_t)q * topk;
+    float *od = out_dist + (int64_t)q * topk;
+    u64 *dst = keys_out + ((int64_t)q * splits + sp) * topk;
+    for (int r = tid; r < topk; r += SK_THREADS) {
+        if (splits == 1) {
+            oi[r] = r < kept ? (uint32_t)list[r] : ICQ_PAD_ID;
+            od[r] = r < kept ? unorder_bits((uint32_t)(list[r] >> 32)) : INFINITY;
+        } else {
+            dst[r] = r < kept ? list[r] : KEY_PAD;
+        }
     }
 }
 
@@ -512,33 +566,33 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
     const unsigned grid = (unsigned)Q * (unsigned)splits;
     const size_t tab = sizeof(float) * (size_t)(cand_part ? ix->Ks : ix->K) * ICQ_LUT_W;
     if (use_select(ix)) {
-        const size_t lds = sizeof(u64) * RS_LIST + sizeof(uint32_t) * RS_FIRST +
-                           sizeof(float) * (size_t)ix->item_stride * ICQ_LUT_W;   // one table per record byte
-#define ICQ_RS_LAUNCH(W, G)                                                                            \
-    do {                                                                                               \
-        static bool attr_set = false;                                                                  \
-        if (!attr_set) {                                                                               \
-            ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&refine_select_kernel<W, G>),\
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 98304));       \
-            attr_set = true;                                                                           \
-        }                                                                                              \
-        refine_select_kernel<W, G><<<grid, RF_THREADS, lds, s>>>(items, ix->K, ix->Kf, lut, cand_ids,  \
-                                                                 cand_part, cand_rec, cand_count, cap, \
-                                                                 topk, splits, keys, out_ids, out_dist);\
-    } while (0)
+        // distances for every candidate (flat), then the per-query select over the keys
+        u64 *cand_keys = keys + (splits > 1 ? (size_t)Q * splits * topk : 0);   // [Q][cap], behind the slice lists
+        int64_t len = cap < ix->N ? cap : ix->N;
+        const int bpq = len > 0 ? (int)((len + RD_BLOCK - 1) / RD_BLOCK) : 1;
+        const unsigned dgrid = (unsigned)Q * (unsigned)bpq;
         const bool grouped = list_kind == ICQ_LIST_POSITIONS;
+#define ICQ_RD_LAUNCH(W, G)                                                                          \
+    refine_dist_kernel<W, G><<<dgrid, RF_THREADS, 0, s>>>(items, ix->K, ix->Kf, lut, cand_ids,       \
+                                                          cand_part, cand_rec, cand_count, cap, bpq, \
+                                                          cand_keys)
         switch (ix->item_stride) {
             case 4:
-                if (grouped) ICQ_RS_LAUNCH(1, true); else ICQ_RS_LAUNCH(1, false);
+                if (grouped) ICQ_RD_LAUNCH(1, true); else ICQ_RD_LAUNCH(1, false);
                 break;
             case 8:
-                if (grouped) ICQ_RS_LAUNCH(2, true); else ICQ_RS_LAUNCH(2, false);
+                if (grouped) ICQ_RD_LAUNCH(2, true); else ICQ_RD_LAUNCH(2, false);
                 break;
             default:
-                if (grouped) ICQ_RS_LAUNCH(4, true); else ICQ_RS_LAUNCH(4, false);
+                if (grouped) ICQ_RD_LAUNCH(4, true); else ICQ_RD_LAUNCH(4, false);
                 break;
         }
-#undef ICQ_RS_LAUNCH
+#undef ICQ_RD_LAUNCH
+        if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;
+        int listcap = 1024;
+        while (listcap < topk + SK_FIRST) listcap <<= 1;
+        select_keys_kernel<<<grid, SK_THREADS, sizeof(u64) * listcap + sizeof(uint32_t) * SK_FIRST, s>>>(
+            cand_keys, cand_count, cap, topk, listcap, splits, keys, out_ids, out_dist);
     } else {
         const int bufn = bufn_for(topk);
         const size_t lds = sizeof(u64) * bufn + tab;

@@ -23,8 +23,11 @@ icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool
     if (with_cands) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q, ICQ_ALIGN);
     L.splits = icq_refine_splits(ix, Q, cap, topk);
     L.keys_off = off;
+    // slice lists [Q][splits][topk] (when sliced), then one 64-bit key per candidate [Q][cap]
     if (L.splits > 1)
-        off = icq_align_up(off + sizeof(unsigned long long) * (size_t)Q * L.splits * topk, ICQ_ALIGN);
+        off = icq_align_up(off + sizeof(unsigned long long) * (size_t)Q * L.splits * topk, 8);
+    if (ix->item_stride <= 16)
+        off = icq_align_up(off + sizeof(unsigned long long) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
     L.total = off;
     return L;
 }
