@@ -397,43 +397,106 @@ __device__ uint32_t wave_radix_select(SelectShared *sh, const uint32_t *U, uint3
     return vmin + prefix;
 }
 
-// Ascending bitonic sort of keys[0..len) by ONE wavefront (len a power of two >= 2):
-// exchanges at distance < 64 by shuffles on the element a lane holds, the rest
-// through LDS; a single-wavefront block needs no waiting at the barriers.
-__device__ void wave_sort(u64 *keys, int len) {
-    const int lane = threadIdx.x;
-    for (int base = 0; base < len; base += 64) {
-        const int e = base + lane;
-        u64 x = e < len ? keys[e] : KEY_PAD;
-        for (int k = 2; k <= 64 && k <= len; k <<= 1) x = wave_bitonic_steps(x, e, k, k >> 1);
-        if (e < len) keys[e] = x;
-    }
-    __syncthreads();
-    for (int k = 128; k <= len; k <<= 1) {
-        for (int j = k >> 1; j >= 64; j >>= 1) {
-            for (int i = lane; i < len / 2; i += 64) {
-                const int a = ((i / j) * 2 * j) + (i % j);
-                const int b = a + j;
-                const bool up = (a & k) == 0;
-                const u64 x = keys[a], y = keys[b];
-                if ((x > y) == up) {
-                    keys[a] = y;
-                    keys[b] = x;
-                }
-            }
-            __syncthreads();
+// Compare-exchange of the register pairs (r, r | M) of a lane: elements 64*M apart.
+template <int M>
+__device__ __forceinline__ void reg_exchange(u64 (&x)[16], int E, int k, int lane) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if ((r & M) == 0 && (r | M) < E) {
+            const bool up = (((r * 64 + lane) & k) == 0);
+            const u64 a = x[r], b = x[r | M];
+            const bool sw = (a > b) == up;
+            x[r] = sw ? b : a;
+            x[r | M] = sw ? a : b;
         }
-        for (int base = 0; base < len; base += 64) {
-            const int e = base + lane;
-            keys[e] = wave_bitonic_steps(keys[e], e, k, 32);
-        }
-        __syncthreads();
     }
 }
 
-// grid (Q * splits), block = one wavefront.  LDS: list[listcap] (u64) | U[SK_FIRST] (u32);
-// listcap is a power of two >= topk + SK_FIRST.
-__global__ __launch_bounds__(SK_THREADS) void select_keys_kernel(
+// Ascending bitonic sort of keys[0..len) by ONE wavefront, len a power of two, 64 <= len
+// <= 1024, entirely in registers: element e sits in register e/64 of lane e%64, so an
+// exchange at distance >= 64 pairs two registers of a lane and one at distance < 64 is
+// a shuffle; the len/64 elements of a lane are independent, which keeps the shuffles
+// pipelined.  keys[len..) is not touched; keys must hold len valid or padding entries.
+__device__ void wave_sort(u64 *keys, int len) {
+    const int lane = threadIdx.x;
+    const int E = len >> 6;
+    u64 x[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) x[r] = r < E ? keys[r * 64 + lane] : KEY_PAD;
+    for (int k = 2; k <= len; k <<= 1) {
+        for (int j = k >> 1; j >= 64; j >>= 1) {
+            switch (j >> 6) {
+                case 1: reg_exchange<1>(x, E, k, lane); break;
+                case 2: reg_exchange<2>(x, E, k, lane); break;
+                case 4: reg_exchange<4>(x, E, k, lane); break;
+                default: reg_exchange<8>(x, E, k, lane); break;
+            }
+        }
+        for (int j = (k >> 1) < 32 ? (k >> 1) : 32; j > 0; j >>= 1) {
+            const bool low = (lane & j) == 0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                if (r < E) {
+                    const u64 y = __shfl_xor(x[r], j, 64);
+                    const bool up = (((r * 64 + lane) & k) == 0);
+                    const bool take_min = up == low;
+                    x[r] = take_min ? (x[r] < y ? x[r] : y) : (x[r] > y ? x[r] : y);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        if (r < E) keys[r * 64 + lane] = x[r];
+    __syncthreads();
+}
+
+// Cut the list back to its topk smallest distances (ties at the cut kept): exact radix
+// select of the topk-th distance, then an in-place ballot compaction.  One wavefront,
+// cnt <= 1024 (wave-uniform), cnt > topk.  Returns the new count; *ubound = the cut.
+__device__ uint32_t wave_cut_list(SelectShared *sh, u64 *list, uint32_t *U, uint32_t cnt, int topk,
+                                  uint32_t *ubound) {
+    const int lane = threadIdx.x;
+    u64 x[16];
+    uint32_t umin = 0xFFFFFFFFu, umax = 0u;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const uint32_t i = r * 64 + lane;
+        x[r] = i < cnt ? list[i] : KEY_PAD;
+        if (i < cnt) {
+            const uint32_t u = (uint32_t)(x[r] >> 32);
+            U[i] = u;
+            umin = u < umin ? u : umin;
+            umax = u > umax ? u : umax;
+        }
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+        const uint32_t a = __shfl_xor(umin, d, 64), b = __shfl_xor(umax, d, 64);
+        umin = a < umin ? a : umin;
+        umax = b > umax ? b : umax;
+    }
+    __syncthreads();
+    const uint32_t cut = wave_radix_select(sh, U, cnt, (uint32_t)topk, umin, umax);
+    __syncthreads();
+    uint32_t kept = 0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if ((uint32_t)(r * 64) < cnt) {   // wave-uniform
+            const bool keep = (uint32_t)(r * 64 + lane) < cnt && (uint32_t)(x[r] >> 32) <= cut;
+            const uint64_t mask = __builtin_amdgcn_ballot_w64(keep);
+            if (keep) list[kept + __builtin_popcountll(mask & ((1ull << lane) - 1))] = x[r];
+            kept += (uint32_t)__builtin_popcountll(mask);
+        }
+    }
+    __syncthreads();
+    *ubound = cut;
+    return kept;
+}
+
+// grid (Q * splits), block = one wavefront.  LDS: list[listcap] (u64) | U[listcap] (u32);
+// listcap is a power of two, topk + SK_FIRST <= listcap <= 1024... 2048 (see launcher).
+__global__ __launch_bounds__(SK_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8))) void select_keys_kernel(
     const u64 *__restrict__ keys_in, const uint32_t *__restrict__ cand_count, int64_t cap, int topk,
     int listcap, int splits, u64 *__restrict__ keys_out, uint32_t *__restrict__ out_ids,
     float *__restrict__ out_dist) {
@@ -451,74 +514,77 @@ __global__ __launch_bounds__(SK_THREADS) void select_keys_kernel(
 
     uint32_t ubound = 0xFFFFFFFFu;   // keep keys whose distance bits are <= ubound
     uint32_t cnt = 0;                // keys in the list (wave-uniform)
-    if (n > 0) {
-        u64 kA[SK_CHUNK], kB[SK_CHUNK];
+    // Keys are loaded one chunk ahead, unconditionally with the index clamped.
+    auto load_chunk = [&](u64 c, u64(&k)[SK_CHUNK]) {
 #pragma unroll
         for (int j = 0; j < SK_CHUNK; ++j) {
-            const u64 i = (u64)j * SK_THREADS + tid;
-            kA[j] = in[i < n ? i : n - 1];
+            const u64 i = c + (u64)j * SK_THREADS + tid;
+            k[j] = in[i < n ? i : n - 1];
         }
-        for (u64 c = 0; c < n; c += SK_FIRST) {
-#pragma unroll
-            for (int j = 0; j < SK_CHUNK; ++j) {   // one chunk ahead
-                const u64 i = c + SK_FIRST + (u64)j * SK_THREADS + tid;
-                kB[j] = in[i < n ? i : n - 1];
-            }
-            if (c == 0 && n > (u64)topk && (uint32_t)topk < (uint32_t)SK_FIRST) {
-                // first chunk: its topk-th smallest distance bounds everything that follows
-                const uint32_t n1 = n < (u64)SK_FIRST ? (uint32_t)n : (uint32_t)SK_FIRST;
-                uint32_t umin = 0xFFFFFFFFu, umax = 0u;
-#pragma unroll
-                for (int j = 0; j < SK_CHUNK; ++j) {
-                    const uint32_t i = j * SK_THREADS + tid;
-                    const uint32_t u = (uint32_t)(kA[j] >> 32);
-                    if (i < n1) {
-                        U[i] = u;
-                        umin = u < umin ? u : umin;
-                        umax = u > umax ? u : umax;
-                    }
-                }
-#pragma unroll
-                for (int d = 32; d > 0; d >>= 1) {
-                    const uint32_t a = __shfl_xor(umin, d, 64), b = __shfl_xor(umax, d, 64);
-                    umin = a < umin ? a : umin;
-                    umax = b > umax ? b : umax;
-                }
-                __syncthreads();
-                if (n1 > (uint32_t)topk) ubound = wave_radix_select(&sh, U, n1, (uint32_t)topk, umin, umax);
-            }
-            // keep what is at or below the bound (ties at the bound included; the final sort
-            // decides); ballot compaction, the list cursor is wave-uniform
+    };
+    auto step = [&](u64 c, u64(&kA)[SK_CHUNK], u64(&kNext)[SK_CHUNK]) {   // wave-uniform c < n
+        load_chunk(c + (u64)SK_FIRST, kNext);   // one chunk ahead
+        if (c == 0 && n > (u64)topk && (uint32_t)topk < (uint32_t)SK_FIRST) {
+            // first chunk: its topk-th smallest distance bounds everything that follows
+            const uint32_t n1 = n < (u64)SK_FIRST ? (uint32_t)n : (uint32_t)SK_FIRST;
+            uint32_t umin = 0xFFFFFFFFu, umax = 0u;
 #pragma unroll
             for (int j = 0; j < SK_CHUNK; ++j) {
-                const u64 i = c + (u64)j * SK_THREADS + tid;
-                const bool keep = i < n && (uint32_t)(kA[j] >> 32) <= ubound;
-                const uint64_t mask = __builtin_amdgcn_ballot_w64(keep);
-                if (keep) list[cnt + __builtin_popcountll(mask & ((1ull << tid) - 1))] = kA[j];
-                cnt += (uint32_t)__builtin_popcountll(mask);
-            }
-            if (cnt > (uint32_t)(listcap - SK_FIRST) && c + SK_FIRST < n) {
-                // the next chunk might not fit: sort, cut back to topk, tighten the bound
-                __syncthreads();
-                int len = 2;
-                while (len < (int)cnt) len <<= 1;
-                for (int i = (int)cnt + tid; i < len; i += SK_THREADS) list[i] = KEY_PAD;
-                __syncthreads();
-                wave_sort(list, len);
-                if (cnt >= (uint32_t)topk) {
-                    ubound = (uint32_t)(list[topk - 1] >> 32);
-                    cnt = (uint32_t)topk;
+                const uint32_t i = j * SK_THREADS + tid;
+                const uint32_t u = (uint32_t)(kA[j] >> 32);
+                if (i < n1) {
+                    U[i] = u;
+                    umin = u < umin ? u : umin;
+                    umax = u > umax ? u : umax;
                 }
-                __syncthreads();
             }
 #pragma unroll
-            for (int j = 0; j < SK_CHUNK; ++j) kA[j] = kB[j];
+            for (int d = 32; d > 0; d >>= 1) {
+                const uint32_t a = __shfl_xor(umin, d, 64), b = __shfl_xor(umax, d, 64);
+                umin = a < umin ? a : umin;
+                umax = b > umax ? b : umax;
+            }
+            __syncthreads();
+            if (n1 > (uint32_t)topk) ubound = wave_radix_select(&sh, U, n1, (uint32_t)topk, umin, umax);
+        }
+        // keep what is at or below the bound (ties at the bound included; the final sort
+        // decides); ballot compaction, the list cursor is wave-uniform
+#pragma unroll
+        for (int j = 0; j < SK_CHUNK; ++j) {
+            const u64 i = c + (u64)j * SK_THREADS + tid;
+            const bool keep = i < n && (uint32_t)(kA[j] >> 32) <= ubound;
+            const uint64_t mask = __builtin_amdgcn_ballot_w64(keep);
+            if (keep) list[cnt + __builtin_popcountll(mask & ((1ull << tid) - 1))] = kA[j];
+            cnt += (uint32_t)__builtin_popcountll(mask);
+        }
+        if (cnt > (uint32_t)(listcap - SK_FIRST) && c + SK_FIRST < n) {
+            // the next chunk might not fit: cut the list back to topk, tighten the bound
+            __syncthreads();
+            cnt = wave_cut_list(&sh, list, U, cnt, topk, &ubound);
+            if (cnt > (uint32_t)(listcap - SK_FIRST)) {
+                // so many ties at the cut that the list is still too full: order by the
+                // whole key and keep exactly topk (the ids decide among equal distances)
+                for (int i = (int)cnt + tid; i < listcap; i += SK_THREADS) list[i] = KEY_PAD;
+                __syncthreads();
+                wave_sort(list, listcap);
+                cnt = (uint32_t)topk;
+                ubound = (uint32_t)(list[topk - 1] >> 32);
+            }
+        }
+    };
+    if (n > 0) {
+        u64 k0[SK_CHUNK], k1[SK_CHUNK];
+        load_chunk(0, k0);
+        for (u64 c = 0; c < n; c += 2 * (u64)SK_FIRST) {
+            step(c, k0, k1);
+            if (c + SK_FIRST < n) step(c + SK_FIRST, k1, k0);
         }
     }
 
-    // ---- final order
+    // ---- final order: cut to the topk smallest distances, then sort what is left
     __syncthreads();
-    int len = 2;
+    if (cnt > (uint32_t)topk) cnt = wave_cut_list(&sh, list, U, cnt, topk, &ubound);
+    int len = 64;
     while (len < (int)cnt) len <<= 1;
     for (int i = (int)cnt + tid; i < len; i += SK_THREADS) list[i] = KEY_PAD;
     __syncthreads();
@@ -541,7 +607,7 @@ __global__ __launch_bounds__(SK_THREADS) void select_keys_kernel(
 
 // Item records of at most 16 bytes take the bounded-stream kernel; wider records
 // (K > 16) the generic streaming kernel.
-static bool use_select(const icq_index *ix) { return ix->item_stride <= 16; }
+static bool use_select(const icq_index *ix, int topk) { return ix->item_stride <= 16 && topk <= 512; }
 
 int icq_refine_splits(const icq_index *ix, int Q, int64_t cap, int topk) {
     if (Q <= 0) return 1;
@@ -565,7 +631,7 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
     if (list_kind != ICQ_LIST_IDS_REC) cand_rec = nullptr;
     const unsigned grid = (unsigned)Q * (unsigned)splits;
     const size_t tab = sizeof(float) * (size_t)(cand_part ? ix->Ks : ix->K) * ICQ_LUT_W;
-    if (use_select(ix)) {
+    if (use_select(ix, topk)) {
         // distances for every candidate (flat), then the per-query select over the keys
         u64 *cand_keys = keys + (splits > 1 ? (size_t)Q * splits * topk : 0);   // [Q][cap], behind the slice lists
         int64_t len = cap < ix->N ? cap : ix->N;
@@ -589,9 +655,8 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
         }
 #undef ICQ_RD_LAUNCH
         if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;
-        int listcap = 1024;
-        while (listcap < topk + SK_FIRST) listcap <<= 1;
-        select_keys_kernel<<<grid, SK_THREADS, sizeof(u64) * listcap + sizeof(uint32_t) * SK_FIRST, s>>>(
+        const int listcap = 1024;   // register sort and cut handle up to 1024 keys: topk <= 512 here
+        select_keys_kernel<<<grid, SK_THREADS, (sizeof(u64) + sizeof(uint32_t)) * listcap, s>>>(
             cand_keys, cand_count, cap, topk, listcap, splits, keys, out_ids, out_dist);
     } else {
         const int bufn = bufn_for(topk);
