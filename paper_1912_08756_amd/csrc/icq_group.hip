@@ -189,6 +189,160 @@ __global__ __launch_bounds__(GS_THREADS) void group_scan_kernel(
     expand(s_nh);
 }
 
+// ---- grouped stage 1 fused with the stage-2 distances
+constexpr int GD_HITS = 2048;     // tuples below the threshold buffered per block
+constexpr int GD_POS = 1024;      // survivor positions buffered per wavefront
+
+// grid (parts, Q) like group_scan_kernel, but instead of listing the survivors the
+// block finishes them: a wavefront expands 64 surviving tuples into a flat buffer of
+// grouped positions in LDS, then all 64 lanes walk that buffer -- grouped records are
+// contiguous per tuple, so the 16/32-byte record reads coalesce -- add up the K table
+// entries (all K tables of the query in LDS, k ascending, one table per record byte,
+// zero tables beyond K) and write the 64-bit key (order-preserving bits of D, item id)
+// to the query's key list.  No position list is written or read back.
+template <int KF, int WORDS>
+__global__ __launch_bounds__(GS_THREADS) void group_keys_kernel(
+    const float *__restrict__ lut, int K, const float *__restrict__ thr,
+    const uint32_t *__restrict__ start, const uint8_t *__restrict__ items_grouped,
+    unsigned long long *__restrict__ keys_out, uint32_t *__restrict__ count, int64_t cap,
+    int rows_per_block) {
+    __shared__ float t0[ICQ_LUT_W];
+    __shared__ float T[4 * WORDS * ICQ_LUT_W];
+    __shared__ uint32_t hits[GD_HITS];
+    __shared__ uint32_t posbuf[GS_THREADS / 64][GD_POS];
+    __shared__ uint32_t s_nh;
+    constexpr int RW = 2 * WORDS;
+    const int tid = threadIdx.x;
+    const uint32_t lane = lane_id();
+    const int wave = tid >> 6;
+    const int q = blockIdx.y;
+    const float *Tq = lut + (int64_t)q * K * ICQ_LUT_W;
+    const float t = thr[q];
+    unsigned long long *my_out = keys_out + (int64_t)q * cap;
+
+    t0[tid] = Tq[tid];
+    const float t1 = KF == 2 ? Tq[ICQ_LUT_W + tid] : 0.0f;
+    for (int i = tid; i < 4 * WORDS * ICQ_LUT_W; i += GS_THREADS) T[i] = i < K * ICQ_LUT_W ? Tq[i] : 0.0f;
+    if (tid == 0) s_nh = 0;
+    __syncthreads();
+
+    auto finish = [&](uint32_t nh) {   // every thread calls; nh is block-uniform
+        uint32_t *pb = posbuf[wave];
+        for (uint32_t h0 = wave * 64; h0 < nh; h0 += (GS_THREADS / 64) * 64) {
+            const uint32_t h = h0 + lane;
+            uint32_t s = 0, n = 0;
+            if (h < nh) {
+                const uint32_t g = hits[h];
+                s = start[g];
+                n = start[g + 1] - s;
+            }
+            uint32_t incl = n;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t o = __shfl_up(incl, d, 64);
+                if ((int)lane >= d) incl += o;
+            }
+            const uint32_t tot = __builtin_amdgcn_readlane(incl, 63);
+            if (tot == 0) continue;
+            uint32_t base = 0;
+            if (lane == 0) base = atomicAdd(&count[q], tot);
+            base = __builtin_amdgcn_readfirstlane(base);
+            const uint32_t excl = incl - n;
+            for (uint32_t c0 = 0; c0 < tot; c0 += GD_POS) {
+                // positions [c0, c0 + GD_POS) of this batch -> LDS
+                uint64_t live = __builtin_amdgcn_ballot_w64(n != 0 && excl < c0 + GD_POS && excl + n > c0);
+                while (live != 0) {
+                    const int l = __builtin_ctzll(live);
+                    live &= live - 1;
+                    const uint32_t sl = __builtin_amdgcn_readlane(s, l);
+                    const uint32_t nl = __builtin_amdgcn_readlane(n, l);
+                    const uint32_t ol = __builtin_amdgcn_readlane(excl, l);
+                    const uint32_t lo = ol > c0 ? ol : c0;
+                    const uint32_t hi = ol + nl < c0 + GD_POS ? ol + nl : c0 + GD_POS;
+                    for (uint32_t j = lo + lane; j < hi; j += 64) pb[j - c0] = sl + (j - ol);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const uint32_t clen = tot - c0 < (uint32_t)GD_POS ? tot - c0 : (uint32_t)GD_POS;
+                for (uint32_t i0 = 0; i0 < clen; i0 += 64 * 4) {
+                    uint32_t rec[4][RW];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const uint32_t idx = i0 + u * 64 + lane;
+                        const uint32_t pos = pb[idx < clen ? idx : clen - 1];
+                        const uint32_t *p = reinterpret_cast<const uint32_t *>(items_grouped + (size_t)pos * (RW * 4));
+                        if (RW == 2) {
+                            const uint2 v = *reinterpret_cast<const uint2 *>(p);
+                            rec[u][0] = v.x;
+                            rec[u][1 % RW] = v.y;
+                        } else {
+#pragma unroll
+                            for (int w4 = 0; w4 < RW / 4; ++w4) {
+                                const uint4 v = reinterpret_cast<const uint4 *>(p)[w4];
+                                rec[u][(4 * w4) % RW] = v.x;
+                                rec[u][(4 * w4 + 1) % RW] = v.y;
+                                rec[u][(4 * w4 + 2) % RW] = v.z;
+                                rec[u][(4 * w4 + 3) % RW] = v.w;
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        float d = 0.0f;
+#pragma unroll
+                        for (int w = 0; w < WORDS; ++w) {
+#pragma unroll
+                            for (int b = 0; b < 4; ++b)
+                                d += T[(w * 4 + b) * ICQ_LUT_W + ((rec[u][w] >> (8 * b)) & 0xffu)];
+                        }
+                        const uint32_t idx = i0 + u * 64 + lane;
+                        const uint64_t slot = (uint64_t)base + c0 + idx;
+                        if (idx < clen && slot < (uint64_t)cap)
+                            my_out[slot] = ((unsigned long long)icq_order_bits(d) << 32) | rec[u][WORDS % RW];
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    };
+
+    const int row_begin = KF == 2 ? blockIdx.x * rows_per_block : 0;
+    const int row_end = KF == 2 ? (row_begin + rows_per_block < 256 ? row_begin + rows_per_block : 256) : 1;
+    constexpr int ROWS = GD_HITS / 256 / 2;   // rows between two looks at the buffer (half of it)
+    for (int r0 = row_begin; r0 < row_end; r0 += ROWS) {
+        const int r1 = r0 + ROWS < row_end ? r0 + ROWS : row_end;
+        for (int c0 = r0; c0 < r1; ++c0) {
+            // same additions as the item-by-item scan: lut[0][c0] (+ lut[1][c1])
+            const float P = KF == 2 ? t0[c0] + t1 : t0[tid];
+            const bool hit = P < t;
+            const uint64_t mask = __builtin_amdgcn_ballot_w64(hit);
+            if (mask != 0) {
+                uint32_t base = 0;
+                const int leader = __builtin_ctzll(mask);
+                if ((int)lane == leader) base = atomicAdd(&s_nh, (uint32_t)__builtin_popcountll(mask));
+                base = __builtin_amdgcn_readlane(base, leader);
+                if (hit)
+                    hits[base + __builtin_popcountll(mask & ((1ull << lane) - 1))] =
+                        KF == 2 ? (uint32_t)c0 * 256u + (uint32_t)tid : (uint32_t)tid;
+            }
+        }
+        if (r1 < row_end) {
+            __syncthreads();
+            const uint32_t nh = s_nh;
+            __syncthreads();
+            if (nh > (uint32_t)(GD_HITS - ROWS * 256)) {
+                finish(nh);
+                __syncthreads();
+                if (tid == 0) s_nh = 0;
+                __syncthreads();
+            }
+        }
+    }
+    __syncthreads();
+    finish(s_nh);
+}
+
 }  // namespace
 
 int icq_group_build(icq_index *ix, hipStream_t s) {
@@ -248,6 +402,37 @@ int icq_launch_group_scan(const icq_index *ix, const float *lut, int Q, const fl
             group_scan_kernel<2><<<grid, GS_THREADS, 0, s>>>(
                 lut + (int64_t)q0 * ix->K * ICQ_LUT_W, ix->K, thr + q0, ix->group_start,
                 as_positions ? nullptr : ix->perm, cand_ids + (int64_t)q0 * cap, cand_count + q0, cap, rows);
+    }
+    return icq_check_launch();
+}
+
+int icq_launch_group_keys(const icq_index *ix, const float *lut, int Q, const float *thr,
+                          unsigned long long *cand_keys, uint32_t *cand_count, int64_t cap,
+                          hipStream_t s) {
+    // cand_count has been zeroed by the caller (icq_launch_scan); item_stride <= 16 here
+    int parts = 1;
+    if (ix->Kf == 2) {
+        parts = (2 * ix->num_cu + Q - 1) / Q;
+        if (parts > 16) parts = 16;
+        if (parts < 1) parts = 1;
+    }
+    const int rows = (256 + parts - 1) / parts;
+    for (int q0 = 0; q0 < Q; q0 += 65535) {
+        const int nq = Q - q0 < 65535 ? Q - q0 : 65535;
+        dim3 grid((unsigned)parts, (unsigned)nq);
+        const float *l = lut + (int64_t)q0 * ix->K * ICQ_LUT_W;
+        unsigned long long *ko = cand_keys + (int64_t)q0 * cap;
+#define ICQ_GK(KF, W)                                                                                \
+    group_keys_kernel<KF, W><<<grid, GS_THREADS, 0, s>>>(l, ix->K, thr + q0, ix->group_start,         \
+                                                         ix->items_grouped, ko, cand_count + q0, cap, \
+                                                         rows)
+        const int W = ix->item_stride / 4;
+        if (ix->Kf == 1) {
+            if (W == 1) ICQ_GK(1, 1); else if (W == 2) ICQ_GK(1, 2); else ICQ_GK(1, 4);
+        } else {
+            if (W == 1) ICQ_GK(2, 1); else if (W == 2) ICQ_GK(2, 2); else ICQ_GK(2, 4);
+        }
+#undef ICQ_GK
     }
     return icq_check_launch();
 }

@@ -36,8 +36,15 @@ struct icq_index {
 enum icq_list_kind {
     ICQ_LIST_IDS = 0,          // item ids
     ICQ_LIST_IDS_REC = 1,      // item ids, item records alongside in cand_rec
-    ICQ_LIST_POSITIONS = 2     // grouped positions (ids through perm, records from items_grouped)
+    ICQ_LIST_POSITIONS = 2,    // grouped positions (ids through perm, records from items_grouped)
+    ICQ_LIST_KEYS = 3          // stage 1 already wrote one 64-bit key (bits of D, id) per survivor
 };
+
+// Order-preserving bits of a float: u(a) < u(b) <=> a < b.
+__device__ __forceinline__ uint32_t icq_order_bits(float x) {
+    uint32_t b = __float_as_uint(x);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
 
 // Sub-buffers carved out of the caller's workspace for one query batch.
 struct icq_ws_layout {
@@ -60,12 +67,21 @@ int icq_launch_build_lut(const icq_index *ix, const float *queries, int Q, float
 // cand_part == nullptr: the crude distances are not materialised (the fused path
 // recomputes the full sum in stage 2 from the item records).
 // list_kind == nullptr: the list must hold item ids (public contract).  Otherwise the
-// scan picks the cheapest representation for stage 2 and reports it: grouped positions,
-// or ids with each survivor's item record written to cand_rec
-// ([Q][cap][item_stride/4] words; cand_rec may be nullptr).
+// scan picks the cheapest representation for stage 2 and reports it: finished keys in
+// cand_keys ([Q][cap], may be nullptr), grouped positions, or ids with each survivor's
+// item record written to cand_rec ([Q][cap][item_stride/4] words; may be nullptr).
 int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
-                    uint32_t *cand_ids, float *cand_part, uint32_t *cand_rec, int *list_kind,
-                    uint32_t *cand_count, int64_t cap, float *lutT, hipStream_t s);
+                    uint32_t *cand_ids, float *cand_part, uint32_t *cand_rec,
+                    unsigned long long *cand_keys, int *list_kind, uint32_t *cand_count, int64_t cap,
+                    float *lutT, hipStream_t s);
+// Grouped stage 1 fused with the stage-2 distances: one 64-bit key per survivor.
+int icq_launch_group_keys(const icq_index *ix, const float *lut, int Q, const float *thr,
+                          unsigned long long *cand_keys, uint32_t *cand_count, int64_t cap,
+                          hipStream_t s);
+// Where the per-candidate keys live inside the key area of the workspace.
+static inline unsigned long long *icq_cand_keys(unsigned long long *keys, int Q, int splits, int topk) {
+    return keys + (splits > 1 ? (size_t)Q * splits * topk : 0);
+}
 // Grouped stage 1 (icq_group.hip); as_positions: list grouped positions instead of ids.
 bool icq_group_usable(const icq_index *ix, int Q);
 int icq_launch_group_scan(const icq_index *ix, const float *lut, int Q, const float *thr,

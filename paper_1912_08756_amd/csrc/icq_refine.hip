@@ -633,11 +633,12 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
     const size_t tab = sizeof(float) * (size_t)(cand_part ? ix->Ks : ix->K) * ICQ_LUT_W;
     if (use_select(ix, topk)) {
         // distances for every candidate (flat), then the per-query select over the keys
-        u64 *cand_keys = keys + (splits > 1 ? (size_t)Q * splits * topk : 0);   // [Q][cap], behind the slice lists
+        u64 *cand_keys = icq_cand_keys(keys, Q, splits, topk);   // [Q][cap], behind the slice lists
         int64_t len = cap < ix->N ? cap : ix->N;
         const int bpq = len > 0 ? (int)((len + RD_BLOCK - 1) / RD_BLOCK) : 1;
         const unsigned dgrid = (unsigned)Q * (unsigned)bpq;
         const bool grouped = list_kind == ICQ_LIST_POSITIONS;
+        if (list_kind != ICQ_LIST_KEYS) {
 #define ICQ_RD_LAUNCH(W, G)                                                                          \
     refine_dist_kernel<W, G><<<dgrid, RF_THREADS, 0, s>>>(items, ix->K, ix->Kf, lut, cand_ids,       \
                                                           cand_part, cand_rec, cand_count, cap, bpq, \
@@ -655,6 +656,7 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
         }
 #undef ICQ_RD_LAUNCH
         if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;
+        }
         const int listcap = 1024;   // register sort and cut handle up to 1024 keys: topk <= 512 here
         select_keys_kernel<<<grid, SK_THREADS, (sizeof(u64) + sizeof(uint32_t)) * listcap, s>>>(
             cand_keys, cand_count, cap, topk, listcap, splits, keys, out_ids, out_dist);

@@ -75,8 +75,10 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
         uint32_t *rec = (ix->item_stride <= 16 && !icq_group_usable(ix, nq))
                             ? reinterpret_cast<uint32_t *>(ws + L.rec_off) : nullptr;
         int list_kind = ICQ_LIST_IDS;
-        rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, nullptr, rec, &list_kind, cnt, cap,
-                             lutT, s);
+        unsigned long long *cand_keys =
+            (ix->item_stride <= 16 && topk <= 512) ? icq_cand_keys(keys, nq, L.splits, topk) : nullptr;
+        rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, nullptr, rec, cand_keys, &list_kind, cnt,
+                             cap, lutT, s);
         if (rc != ICQ_OK) return rc;
         rc = icq_launch_refine(ix, lut, nq, ids, nullptr, rec, list_kind, cnt, cap, topk, L.splits, keys,
                                out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
