@@ -102,6 +102,23 @@ int icq_index_export_codes(const icq_index *index, int from_items, uint8_t *code
 #define ICQ_SCAN_GROUPED 2
 int icq_index_set_scan_mode(icq_index *index, int mode);
 
+/*
+ * Stage timing, a measurement aid for icq_search (for profiling only: it adds
+ * four event records per call and is not thread-safe).  With enable != 0 every
+ * later icq_search on this index records events on its stream around the
+ * kernels of its FIRST query sub-batch: before the table build, after it, after
+ * stage 1 (scan, plus the survivors' distances where the scan is fused with
+ * them) and after the nearest-neighbour lists are written.  enable == 0 stops
+ * that and releases the events.
+ * icq_index_stage_times waits for the last recorded call to finish and writes
+ * ms[0..2] (host) = milliseconds of table build, stage 1, stage 2 + list;
+ * *batches (host, may be NULL) = the number of sub-batches that call was split
+ * into (the times cover the whole call only when it is 1).  ICQ_ERR_ARG when
+ * timing is off or no search has run since it was switched on.
+ */
+int icq_index_set_stage_timing(icq_index *index, int enable);
+int icq_index_stage_times(const icq_index *index, float *ms /*host [3]*/, int *batches /*host*/);
+
 /* Bytes of 256-byte-aligned device workspace that icq_scan_fast, icq_refine
  * and icq_search need for up to Q queries per call, candidate capacity `cap`
  * per query and result length `topk`.  *out is a host pointer. */

@@ -25,6 +25,8 @@ SIGNATURES = {
     "icq_index_destroy": (None, [_vp]),
     "icq_index_export_codes": (_i, [_vp, _i, _vp, _vp]),
     "icq_index_set_scan_mode": (_i, [_vp, _i]),
+    "icq_index_set_stage_timing": (_i, [_vp, _i]),
+    "icq_index_stage_times": (_i, [_vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(_i)]),
     "icq_workspace_bytes": (_i, [_vp, _i, _i64, _i, ctypes.POINTER(_sz)]),
     "icq_build_lut": (_i, [_vp, _vp, _i, _vp, _vp]),
     "icq_scan_fast": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
@@ -120,6 +122,18 @@ ICQ_SCAN_AUTO, ICQ_SCAN_STREAMED, ICQ_SCAN_GROUPED = 0, 1, 2
 
 def icq_index_set_scan_mode(index, mode):
     _check(load().icq_index_set_scan_mode(index.handle, int(mode)), "icq_index_set_scan_mode")
+
+
+def icq_index_set_stage_timing(index, enable):
+    _check(load().icq_index_set_stage_timing(index.handle, int(bool(enable))), "icq_index_set_stage_timing")
+
+
+def icq_index_stage_times(index):
+    """(ms of table build, stage 1, stage 2 + list), sub-batches of the latest timed icq_search."""
+    ms = (ctypes.c_float * 3)()
+    batches = _i(0)
+    _check(load().icq_index_stage_times(index.handle, ms, ctypes.byref(batches)), "icq_index_stage_times")
+    return [float(x) for x in ms], int(batches.value)
 
 
 def icq_workspace_bytes(index, Q, cap, topk):

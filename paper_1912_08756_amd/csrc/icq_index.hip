@@ -94,6 +94,10 @@ ICQ_EXPORT void icq_index_destroy(icq_index *ix) {
     (void)hipFree(ix->group_cursor);
     (void)hipFree(ix->perm);
     (void)hipFree(ix->items_grouped);
+    if (ix->timer) {
+        for (int i = 0; i < 4; ++i) (void)hipEventDestroy(ix->timer->ev[i]);
+        delete ix->timer;
+    }
     delete ix;
 }
 
@@ -114,7 +118,7 @@ ICQ_EXPORT int icq_index_create(icq_index **out, const float *codebooks, const u
     ix->N = N;
     ix->Npad = (N + 16383) / 16384 * 16384 + 16384;   // spare so that whole-step reads stay in bounds
     ix->cb = nullptr; ix->cnorm = nullptr; ix->fast = nullptr; ix->items = nullptr;
-    ix->groups = 0; ix->scan_mode = ICQ_SCAN_AUTO;
+    ix->groups = 0; ix->scan_mode = ICQ_SCAN_AUTO; ix->timer = nullptr;
     ix->group_start = nullptr; ix->group_cursor = nullptr; ix->perm = nullptr; ix->items_grouped = nullptr;
     hipDeviceProp_t prop;
     if (hipGetDevice(&ix->device) != hipSuccess ||
@@ -168,4 +172,37 @@ ICQ_EXPORT int icq_index_export_codes(const icq_index *ix, int from_items, uint8
                                                           from_items ? 0 : ix->Kf, ix->item_stride,
                                                           codes_out);
     return icq_check_launch();
+}
+
+ICQ_EXPORT int icq_index_set_stage_timing(icq_index *ix, int enable) {
+    if (!ix) return ICQ_ERR_ARG;
+    if (!enable) {
+        if (ix->timer) {
+            for (int i = 0; i < 4; ++i) (void)hipEventDestroy(ix->timer->ev[i]);
+            delete ix->timer;
+            ix->timer = nullptr;
+        }
+        return ICQ_OK;
+    }
+    if (ix->timer) return ICQ_OK;
+    icq_stage_timer *t = new (std::nothrow) icq_stage_timer();
+    if (!t) return ICQ_ERR_HIP;
+    t->batches = 0;
+    for (int i = 0; i < 4; ++i) {
+        if (hipEventCreate(&t->ev[i]) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(t->ev[j]);
+            delete t;
+            return ICQ_ERR_HIP;
+        }
+    }
+    ix->timer = t;
+    return ICQ_OK;
+}
+
+ICQ_EXPORT int icq_index_stage_times(const icq_index *ix, float *ms, int *batches) {
+    if (!ix || !ms || !ix->timer || ix->timer->batches == 0) return ICQ_ERR_ARG;
+    ICQ_HIP_TRY(hipEventSynchronize(ix->timer->ev[3]));
+    for (int i = 0; i < 3; ++i) ICQ_HIP_TRY(hipEventElapsedTime(&ms[i], ix->timer->ev[i], ix->timer->ev[i + 1]));
+    if (batches) *batches = ix->timer->batches;
+    return ICQ_OK;
 }

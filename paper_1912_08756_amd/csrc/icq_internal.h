@@ -11,6 +11,12 @@
 #define ICQ_WAVE 64            // gfx950 wavefront
 #define ICQ_ALIGN 256          // workspace sub-buffer alignment
 
+// Events around the stages of the latest icq_search (icq_index_set_stage_timing).
+struct icq_stage_timer {
+    hipEvent_t ev[4];
+    int batches;               // sub-batches of the latest call, 0 = nothing recorded yet
+};
+
 struct icq_index {
     int K, m, d, Kf, Ks;       // Ks = K - Kf slow codebooks
     int d_pad;                 // d rounded up to a multiple of 16 (zero filled)
@@ -30,6 +36,7 @@ struct icq_index {
     uint32_t *group_cursor;    // [groups] scratch of the build
     uint32_t *perm;            // [N] grouped position -> item id
     uint8_t *items_grouped;    // [N][2*item_stride] grouped order: sub-codes, then the item id, zero padded
+    icq_stage_timer *timer;    // nullptr unless stage timing is on
 };
 
 // What a candidate list holds.
