@@ -5,10 +5,11 @@
 
 A step is one icq_search call over the whole query set of the workload (table
 build, stage-1 scan, stage-2 refine, top-k), inputs resident in HBM.  Prints ONE
-JSON line: queries/s, the roofline of the dominant kernel (the stage-1 scan;
-batch mode is bound by LDS gather bandwidth), the stage-1 scan on a 400 MB
-fast-code array with a single query (bound by HBM), and the CPU oracle timed on
-the host cores as a baseline.
+JSON line: queries/s; the roofline of the dominant kernel of that step (stage 1
+over the items grouped by fast-code tuple, fused with the survivors' distances);
+the same step with the item-by-item stage 1 (bound by LDS table reads); the
+stage-1 scan on a 400 MB fast-code array with one and two queries (bound by
+HBM); and the CPU oracle timed on the host cores as a baseline.
 """
 import argparse
 import json
@@ -151,14 +152,34 @@ def cpu_baseline(cfg, thr_np, gpu_ids, gpu_dist, target_s=15.0):
             {"checked_queries": n_check, "identical_lists_frac": round(same, 4), "sampled_queries": n})
 
 
+def pmc_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed counter summary (two rocprofv3
+    --pmc runs of this program, scaled by what the counters read for a copy of known
+    size), or None when the summary has no line for it.  Line format:
+    `traffic <kernel> <workload> <fetch_bytes> <write_bytes>`."""
+    path = os.path.join(ROOT, "profiles", "pmc_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 5 and f[0] == "traffic" and f[1] == kernel:
+            return {"workload": f[2], "fetch_bytes": float(f[3]), "write_bytes": float(f[4]),
+                    "bytes": float(f[3]) + float(f[4]), "source": "profiles/pmc_traffic.txt"}
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hbm-leg", action="store_true")
+    ap.add_argument("--no-streamed-leg", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB): the scale for "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
@@ -168,6 +189,14 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     b.load()
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.mul(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     log("[bench] drawing workload", args.workload)
     cfg = synth.make(args.workload)
@@ -189,40 +218,49 @@ def main():
     def step():
         b.icq_search(index, queries, thr, cap, topk, out_ids, out_dist, surv, ws)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    def timed(steps, warmup):
+        """ms per step by the host clock around `steps` calls, and the stage times the
+        library's own events (on the launch stream) recorded inside those same calls."""
+        b.icq_index_set_stage_timing(index, False)
+        for _ in range(warmup):
+            step()
+        b.icq_index_set_stage_timing(index, True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        stage, calls, batches = b.icq_index_stage_times(index)
+        b.icq_index_set_stage_timing(index, False)
+        assert batches == 1, "the workspace must hold the whole query set"
+        return ms, stage, calls
+
+    ms_per_step, stage, calls = timed(args.steps, args.warmup)
     surv_np = surv.cpu().numpy().view(np.uint32)
     overflow = int((surv_np > cap).sum())
-    log("[bench] %.3f ms/step, survivors mean %.0f max %d, overflowed lists %d" %
-        (ms_per_step, surv_np.mean(), surv_np.max(), overflow))
+    n_surv = float(np.minimum(surv_np, cap).sum())
+    log("[bench] %.3f ms/step; stages (events, mean of %d steps): lut %.3f, stage 1 %.3f, stage 2 %.3f ms; "
+        "survivors mean %.0f max %d, overflowed lists %d" %
+        (ms_per_step, calls, stage[0], stage[1], stage[2], surv_np.mean(), surv_np.max(), overflow))
+    gpu_ids = out_ids.cpu().numpy().view(np.uint32)
+    gpu_dist = out_dist.cpu().numpy()
 
-    # stage breakdown on the same inputs (same kernels as icq_search, called one by one)
-    lut = torch.empty((Q, K, 256), dtype=torch.float32, device="cuda")
-    c_ids = torch.empty((Q, cap), dtype=torch.int32, device="cuda")
-    c_cnt = torch.empty((Q,), dtype=torch.int32, device="cuda")
-    reps = max(3, args.steps)
-    ms_lut = event_time_ms(torch, lambda: b.icq_build_lut(index, queries, lut), reps)
-    # ids only, as the fused path runs the scan (no crude-distance pass); stage 2 then forms the whole sum
-    ms_scan = event_time_ms(torch, lambda: b.icq_scan_fast(index, lut, thr, c_ids, None, c_cnt, ws), reps)
-    ms_refine = event_time_ms(
-        torch, lambda: b.icq_refine(index, lut, c_ids, None, c_cnt, topk, out_ids, out_dist, ws), reps)
-    log("[bench] stages: lut %.3f ms, scan %.3f ms, refine %.3f ms" % (ms_lut, ms_scan, ms_refine))
-
-    lds_bytes = 4.0 * Kf * N * Q                     # one 4-byte table read per (query, item, fast codebook)
-    achieved = lds_bytes / (ms_scan * 1e-3) / 1e9
-    roofline = {"bound": "lds", "kernel": "scan_batch_kernel", "achieved": round(achieved, 1),
-                "peak": round(LDS_PEAK_GBS, 1), "unit": "GB/s", "frac": round(achieved / LDS_PEAK_GBS, 4),
-                "traffic": None, "ms": round(ms_scan, 4),
-                "peak_measured_b32": round(LDS_PEAK_GBS / 2, 1),
-                "note": "algorithmic LDS gather bytes 4*Kf*N*Q per launch over the duration of one icq_scan_fast call "
-                        "(scan kernel + 2 small kernels); peak = 256 CU x 128 B/clk x 2.4 GHz; a 4-byte ds_read "
-                        "measures 64 B/clk/CU on this chip (peak_measured_b32); HBM code bytes are Kf*N*ceil(Q/64)"}
+    # Dominant kernel of the step: stage 1 of the grouped form, fused with the survivors'
+    # distances (group_keys_kernel; the stage-1 event pair also spans the 4 us counter fill).
+    # Algorithmic bytes per launch: per survivor K code bytes + 4 id bytes read and one
+    # 8-byte key written; per query its K tables (4*K*256 bytes) read.
+    alg_bytes = n_surv * (K + 4 + 8) + 4.0 * Q * K * 256
+    achieved = alg_bytes / (stage[1] * 1e-3) / 1e9
+    traffic = pmc_traffic("group_keys_kernel")
+    roofline = {"bound": "hbm", "kernel": "group_keys_kernel<%d,%d>" % (Kf, index_words(K)),
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": traffic["bytes"] if traffic else None, "traffic_detail": traffic,
+                "ms": round(stage[1], 4), "algorithmic_bytes": alg_bytes,
+                "note": "bytes per launch = survivors*(K code bytes + 4 id bytes + 8 key bytes) + Q*4*K*256 table "
+                        "bytes; duration = stage-1 event pair inside the timed icq_search calls; the grouped item "
+                        "records (16 MB here) stay in the last-level cache, so HBM sees mostly the key writes"}
 
     result = {
         "metric": "queries/sec at top-%d (oracle-matched)" % topk,
@@ -232,22 +270,54 @@ def main():
         "config": {"workload": "%s: d=%d K=%d Kf=%d m=256 N=%d Q=%d top-%d, ~%.0f%% survive stage 1" %
                    (args.workload, d, K, Kf, N, Q, topk, 100 * SURVIVE_FRAC),
                    "cap": cap, "overflowed_lists": overflow,
-                   "survivors_mean": round(float(surv_np.mean()), 1)},
-        "stages_ms": {"build_lut": round(ms_lut, 4), "scan_fast": round(ms_scan, 4), "refine": round(ms_refine, 4)},
+                   "survivors_mean": round(float(surv_np.mean()), 1), "stage1": "grouped by fast-code tuple"},
+        "stages_ms": {"build_lut": round(stage[0], 4), "stage1_scan_and_distances": round(stage[1], 4),
+                      "stage2_select": round(stage[2], 4)},
         "roofline": roofline,
     }
+
+    if not args.no_streamed_leg and index.Kf <= 2:
+        # The same step with stage 1 walking the fast sub-codes item by item (what an index
+        # without the grouping, or with N below 256^Kf, runs): bound by LDS table reads.
+        b.icq_index_set_scan_mode(index, b.ICQ_SCAN_STREAMED)
+        ws2 = torch.empty(b.icq_workspace_bytes(index, Q, cap, topk), dtype=torch.uint8, device="cuda")
+        ws_keep, ws = ws, ws2
+        ms_s, stage_s, _ = timed(max(3, args.steps // 4), 1)
+        same = bool((out_ids.cpu().numpy().view(np.uint32) == gpu_ids).all())
+        ws = ws_keep
+        del ws2
+        b.icq_index_set_scan_mode(index, b.ICQ_SCAN_AUTO)
+        lds_bytes = 4.0 * Kf * N * Q                 # one 4-byte table read per (query, item, fast codebook)
+        ach = lds_bytes / (stage_s[1] * 1e-3) / 1e9
+        result["roofline_streamed"] = {
+            "bound": "lds", "kernel": "scan_batch_kernel<%d,%d>" % (Kf, index_words(K)), "achieved": round(ach, 1),
+            "peak": round(LDS_PEAK_GBS, 1), "unit": "GB/s", "frac": round(ach / LDS_PEAK_GBS, 4), "traffic": None,
+            "ms": round(stage_s[1], 4), "ms_per_step": round(ms_s, 4),
+            "queries_per_s": round(Q / (ms_s * 1e-3), 1), "peak_measured_b32": round(LDS_PEAK_GBS / 2, 1),
+            "same_ids_as_grouped": same,
+            "stages_ms": {"build_lut": round(stage_s[0], 4), "stage1": round(stage_s[1], 4),
+                          "stage2": round(stage_s[2], 4)},
+            "note": "item-by-item stage 1: algorithmic LDS gather bytes 4*Kf*N*Q over the stage-1 event pair (scan "
+                    "kernel + 2 small kernels); peak = 256 CU x 128 B/clk x 2.4 GHz; a 4-byte ds_read measures "
+                    "64 B/clk/CU on this chip (peak_measured_b32); HBM code bytes are Kf*N*ceil(Q/64)"}
+        log("[bench] streamed stage 1: %.3f ms/step (stage 1 %.3f ms), same ids as grouped: %s" %
+            (ms_s, stage_s[1], same))
+
     if not args.no_hbm_leg:
-        del c_ids, lut, ws
+        del ws
         torch.cuda.empty_cache()
         log("[bench] stage-1 scan on the 400 MB fast-code array, one query")
         result["roofline_stage1_hbm"] = hbm_leg(torch, b, max(5, args.steps), args.warmup)
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle")
-        base, match = cpu_baseline(cfg, thr.cpu().numpy(), out_ids.cpu().numpy().view(np.uint32),
-                                   out_dist.cpu().numpy())
+        base, match = cpu_baseline(cfg, thr.cpu().numpy(), gpu_ids, gpu_dist)
         result["cpu_baseline"] = base
         result["oracle_matched"] = match
     print(json.dumps(result), flush=True)
+
+
+def index_words(K):
+    return 1 if K <= 4 else 2 if K <= 8 else 4
 
 
 if __name__ == "__main__":

@@ -108,16 +108,21 @@ int icq_index_set_scan_mode(icq_index *index, int mode);
  * later icq_search on this index records events on its stream around the
  * kernels of its FIRST query sub-batch: before the table build, after it, after
  * stage 1 (scan, plus the survivors' distances where the scan is fused with
- * them) and after the nearest-neighbour lists are written.  enable == 0 stops
- * that and releases the events.
+ * them) and after the nearest-neighbour lists are written.  The latest
+ * ICQ_TIMED_CALLS calls are kept.  enable == 0 stops that and releases the
+ * events.
  * icq_index_stage_times waits for the last recorded call to finish and writes
- * ms[0..2] (host) = milliseconds of table build, stage 1, stage 2 + list;
- * *batches (host, may be NULL) = the number of sub-batches that call was split
- * into (the times cover the whole call only when it is 1).  ICQ_ERR_ARG when
- * timing is off or no search has run since it was switched on.
+ * ms[0..2] (host) = milliseconds of table build, stage 1, stage 2 + list,
+ * averaged over the calls recorded since timing was switched on or last read
+ * (*calls, host, may be NULL); *batches (host, may be NULL) = the largest number
+ * of sub-batches one of those calls was split into (the times cover whole calls
+ * only when it is 1).  Reading resets the record.  ICQ_ERR_ARG when timing is
+ * off or no search has run since it was switched on or last read.
  */
+#define ICQ_TIMED_CALLS 64
 int icq_index_set_stage_timing(icq_index *index, int enable);
-int icq_index_stage_times(const icq_index *index, float *ms /*host [3]*/, int *batches /*host*/);
+int icq_index_stage_times(const icq_index *index, float *ms /*host [3]*/, int *calls /*host*/,
+                          int *batches /*host*/);
 
 /* Bytes of 256-byte-aligned device workspace that icq_scan_fast, icq_refine
  * and icq_search need for up to Q queries per call, candidate capacity `cap`

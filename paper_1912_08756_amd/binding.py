@@ -26,7 +26,7 @@ SIGNATURES = {
     "icq_index_export_codes": (_i, [_vp, _i, _vp, _vp]),
     "icq_index_set_scan_mode": (_i, [_vp, _i]),
     "icq_index_set_stage_timing": (_i, [_vp, _i]),
-    "icq_index_stage_times": (_i, [_vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(_i)]),
+    "icq_index_stage_times": (_i, [_vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(_i), ctypes.POINTER(_i)]),
     "icq_workspace_bytes": (_i, [_vp, _i, _i64, _i, ctypes.POINTER(_sz)]),
     "icq_build_lut": (_i, [_vp, _vp, _i, _vp, _vp]),
     "icq_scan_fast": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
@@ -129,11 +129,13 @@ def icq_index_set_stage_timing(index, enable):
 
 
 def icq_index_stage_times(index):
-    """(ms of table build, stage 1, stage 2 + list), sub-batches of the latest timed icq_search."""
+    """((ms of table build, stage 1, stage 2 + list) averaged over the recorded icq_search calls,
+    number of calls, most sub-batches in one of them); resets the record."""
     ms = (ctypes.c_float * 3)()
-    batches = _i(0)
-    _check(load().icq_index_stage_times(index.handle, ms, ctypes.byref(batches)), "icq_index_stage_times")
-    return [float(x) for x in ms], int(batches.value)
+    calls, batches = _i(0), _i(0)
+    _check(load().icq_index_stage_times(index.handle, ms, ctypes.byref(calls), ctypes.byref(batches)),
+           "icq_index_stage_times")
+    return [float(x) for x in ms], int(calls.value), int(batches.value)
 
 
 def icq_workspace_bytes(index, Q, cap, topk):

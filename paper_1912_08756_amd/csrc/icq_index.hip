@@ -95,7 +95,7 @@ ICQ_EXPORT void icq_index_destroy(icq_index *ix) {
     (void)hipFree(ix->perm);
     (void)hipFree(ix->items_grouped);
     if (ix->timer) {
-        for (int i = 0; i < 4; ++i) (void)hipEventDestroy(ix->timer->ev[i]);
+        for (int i = 0; i < ICQ_TIMED_CALLS * 4; ++i) (void)hipEventDestroy(ix->timer->ev[i / 4][i % 4]);
         delete ix->timer;
     }
     delete ix;
@@ -174,24 +174,27 @@ ICQ_EXPORT int icq_index_export_codes(const icq_index *ix, int from_items, uint8
     return icq_check_launch();
 }
 
+static void timer_free(icq_stage_timer *t, int created) {
+    for (int i = 0; i < created; ++i) (void)hipEventDestroy(t->ev[i / 4][i % 4]);
+    delete t;
+}
+
 ICQ_EXPORT int icq_index_set_stage_timing(icq_index *ix, int enable) {
     if (!ix) return ICQ_ERR_ARG;
     if (!enable) {
-        if (ix->timer) {
-            for (int i = 0; i < 4; ++i) (void)hipEventDestroy(ix->timer->ev[i]);
-            delete ix->timer;
-            ix->timer = nullptr;
-        }
+        if (ix->timer) timer_free(ix->timer, ICQ_TIMED_CALLS * 4);
+        ix->timer = nullptr;
         return ICQ_OK;
     }
     if (ix->timer) return ICQ_OK;
     icq_stage_timer *t = new (std::nothrow) icq_stage_timer();
     if (!t) return ICQ_ERR_HIP;
+    t->calls = 0;
     t->batches = 0;
-    for (int i = 0; i < 4; ++i) {
-        if (hipEventCreate(&t->ev[i]) != hipSuccess) {
-            for (int j = 0; j < i; ++j) (void)hipEventDestroy(t->ev[j]);
-            delete t;
+    for (int i = 0; i < ICQ_TIMED_CALLS * 4; ++i) {
+        if (hipEventCreate(&t->ev[i / 4][i % 4]) != hipSuccess) {
+            (void)hipGetLastError();
+            timer_free(t, i);
             return ICQ_ERR_HIP;
         }
     }
@@ -199,10 +202,25 @@ ICQ_EXPORT int icq_index_set_stage_timing(icq_index *ix, int enable) {
     return ICQ_OK;
 }
 
-ICQ_EXPORT int icq_index_stage_times(const icq_index *ix, float *ms, int *batches) {
-    if (!ix || !ms || !ix->timer || ix->timer->batches == 0) return ICQ_ERR_ARG;
-    ICQ_HIP_TRY(hipEventSynchronize(ix->timer->ev[3]));
-    for (int i = 0; i < 3; ++i) ICQ_HIP_TRY(hipEventElapsedTime(&ms[i], ix->timer->ev[i], ix->timer->ev[i + 1]));
-    if (batches) *batches = ix->timer->batches;
+ICQ_EXPORT int icq_index_stage_times(const icq_index *ix, float *ms, int *calls, int *batches) {
+    if (!ix || !ms || !ix->timer || ix->timer->calls == 0) return ICQ_ERR_ARG;
+    icq_stage_timer *t = ix->timer;
+    const long long last = t->calls - 1;
+    const int n = t->calls < ICQ_TIMED_CALLS ? (int)t->calls : ICQ_TIMED_CALLS;
+    ICQ_HIP_TRY(hipEventSynchronize(t->ev[last % ICQ_TIMED_CALLS][3]));
+    double sum[3] = {0.0, 0.0, 0.0};
+    for (int c = 0; c < n; ++c) {
+        const int slot = (int)((last - c) % ICQ_TIMED_CALLS);
+        for (int i = 0; i < 3; ++i) {
+            float v = 0.0f;
+            ICQ_HIP_TRY(hipEventElapsedTime(&v, t->ev[slot][i], t->ev[slot][i + 1]));
+            sum[i] += v;
+        }
+    }
+    for (int i = 0; i < 3; ++i) ms[i] = (float)(sum[i] / n);
+    if (calls) *calls = n;
+    if (batches) *batches = t->batches;
+    t->calls = 0;
+    t->batches = 0;
     return ICQ_OK;
 }

@@ -13,8 +13,9 @@
 
 // Events around the stages of the latest icq_search (icq_index_set_stage_timing).
 struct icq_stage_timer {
-    hipEvent_t ev[4];
-    int batches;               // sub-batches of the latest call, 0 = nothing recorded yet
+    hipEvent_t ev[ICQ_TIMED_CALLS][4];
+    long long calls;           // searches recorded since the last read (slot = call % ICQ_TIMED_CALLS)
+    int batches;               // most sub-batches among them
 };
 
 struct icq_index {

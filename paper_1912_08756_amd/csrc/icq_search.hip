@@ -63,7 +63,13 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
     hipStream_t s = (hipStream_t)stream;
     char *ws = static_cast<char *>(workspace);
     icq_stage_timer *tm = ix->timer;
-    if (tm) tm->batches = (Q + Qb - 1) / Qb;
+    hipEvent_t *ev = nullptr;
+    if (tm) {
+        const int nb = (Q + Qb - 1) / Qb;
+        if (nb > tm->batches) tm->batches = nb;
+        ev = tm->ev[tm->calls % ICQ_TIMED_CALLS];
+        tm->calls += 1;
+    }
     for (int q0 = 0; q0 < Q; q0 += Qb) {
         const bool timed = tm && q0 == 0;
         const int nq = (Q - q0) < Qb ? (Q - q0) : Qb;
@@ -73,10 +79,10 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
         uint32_t *ids = reinterpret_cast<uint32_t *>(ws + L.ids_off);
         uint32_t *cnt = out_survivors ? out_survivors + q0 : reinterpret_cast<uint32_t *>(ws + L.count_off);
         unsigned long long *keys = reinterpret_cast<unsigned long long *>(ws + L.keys_off);
-        if (timed) ICQ_HIP_TRY(hipEventRecord(tm->ev[0], s));
+        if (timed) ICQ_HIP_TRY(hipEventRecord(ev[0], s));
         int rc = icq_launch_build_lut(ix, queries + (int64_t)q0 * ix->d, nq, lut, s);
         if (rc != ICQ_OK) return rc;
-        if (timed) ICQ_HIP_TRY(hipEventRecord(tm->ev[1], s));
+        if (timed) ICQ_HIP_TRY(hipEventRecord(ev[1], s));
         uint32_t *rec = (ix->item_stride <= 16 && !icq_group_usable(ix, nq))
                             ? reinterpret_cast<uint32_t *>(ws + L.rec_off) : nullptr;
         int list_kind = ICQ_LIST_IDS;
@@ -85,11 +91,11 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
         rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, nullptr, rec, cand_keys, &list_kind, cnt,
                              cap, lutT, s);
         if (rc != ICQ_OK) return rc;
-        if (timed) ICQ_HIP_TRY(hipEventRecord(tm->ev[2], s));
+        if (timed) ICQ_HIP_TRY(hipEventRecord(ev[2], s));
         rc = icq_launch_refine(ix, lut, nq, ids, nullptr, rec, list_kind, cnt, cap, topk, L.splits, keys,
                                out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
         if (rc != ICQ_OK) return rc;
-        if (timed) ICQ_HIP_TRY(hipEventRecord(tm->ev[3], s));
+        if (timed) ICQ_HIP_TRY(hipEventRecord(ev[3], s));
     }
     return ICQ_OK;
 }

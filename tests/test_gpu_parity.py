@@ -283,6 +283,54 @@ def test_search_infinite_threshold_is_exhaustive_adc(gpu):
     assert (out_ids == e_ids).mean() > 0.98
 
 
+def test_search_grouped_with_many_surviving_tuples(gpu):
+    """Thresholds that let far more fast-code tuples through than the grouped kernel buffers
+    at once (several passes per query), an infinite and a NaN threshold among them."""
+    cfg = small("C1", 150_000, 12)
+    g = Gpu(gpu, cfg, 2)
+    T, P, D = oracle_all(cfg)
+    thr = thresholds_quantile(P, 0.2)
+    thr[3] = np.inf
+    thr[7] = np.nan
+    thr[9] = np.float32(np.sort(P[9])[5000])
+    N, topk = 150_000, 100
+    out_ids, out_dist, surv = g.search(thr, N, topk)
+    for q in range(12):
+        if q == 7:
+            assert surv[q] == 0 and (out_ids[q] == 0xFFFFFFFF).all() and np.isinf(out_dist[q]).all()
+            continue
+        band = np.count_nonzero((P[q] >= thr[q] - tol(thr[q])) & (P[q] <= thr[q] + tol(thr[q]))) if np.isfinite(thr[q]) else 0
+        exact = int((P[q] < np.float64(thr[q])).sum())
+        assert abs(int(surv[q]) - exact) <= band
+        check_topk(P[q], D[q], thr[q], topk, out_ids[q], out_dist[q])
+    # same lists from the item-by-item form
+    g1 = Gpu(gpu, cfg, 1)
+    ids1, dist1, surv1 = g1.search(thr, N, topk)
+    assert np.array_equal(surv, surv1) and np.array_equal(out_ids, ids1) and np.array_equal(out_dist, dist1)
+
+
+def test_stage_timing_records_the_search_calls(gpu):
+    cfg = small("C1", 40_000, 64)
+    g = Gpu(gpu, cfg)
+    T, P, D = oracle_all(cfg)
+    thr = thresholds_quantile(P, 0.01)
+    with pytest.raises(g.b.IcqError):
+        g.b.icq_index_stage_times(g.index)              # timing is off
+    g.b.icq_index_set_stage_timing(g.index, True)
+    with pytest.raises(g.b.IcqError):
+        g.b.icq_index_stage_times(g.index)              # nothing recorded yet
+    ref = g.search(thr, 1024, 100)
+    for _ in range(2):
+        again = g.search(thr, 1024, 100)
+        assert np.array_equal(ref[0], again[0])
+    ms, calls, batches = g.b.icq_index_stage_times(g.index)
+    assert calls == 3 and batches == 1 and all(0.0 < x < 1e3 for x in ms)
+    with pytest.raises(g.b.IcqError):
+        g.b.icq_index_stage_times(g.index)              # reading resets the record
+    g.b.icq_index_set_stage_timing(g.index, False)
+    assert np.array_equal(ref[0], g.search(thr, 1024, 100)[0])
+
+
 def test_search_in_sub_batches_gives_the_same_lists(gpu):
     cfg = small("C1", 30_000, 300)
     g = Gpu(gpu, cfg)
