@@ -7,6 +7,7 @@
 // item of a tuple below the threshold survives.  Values and survivor sets are
 // the ones the item-by-item scan produces.
 #include "icq_internal.h"
+#include "icq_sort.h"
 
 #include <math.h>
 
@@ -71,13 +72,11 @@ __global__ void group_scatter_kernel(const uint8_t *__restrict__ fast, int64_t N
     if (i >= N) return;
     const uint32_t pos = atomicAdd(&cursor[group_of(fast, Npad, Kf, i)], 1u);
     perm[pos] = (uint32_t)i;
-    // grouped record: the item's sub-codes, then its id, padded to twice the record size
+    // the item's record, moved to its grouped position
     const int W = stride / 4;
     const uint32_t *src = reinterpret_cast<const uint32_t *>(items + (size_t)i * stride);
-    uint32_t *dst = reinterpret_cast<uint32_t *>(items_grouped + (size_t)pos * (2 * stride));
+    uint32_t *dst = reinterpret_cast<uint32_t *>(items_grouped + (size_t)pos * stride);
     for (int w = 0; w < W; ++w) dst[w] = src[w];
-    dst[W] = (uint32_t)i;
-    for (int w = W + 1; w < 2 * W; ++w) dst[w] = 0u;
 }
 
 __global__ void group_zero_kernel(uint32_t *__restrict__ p, int n) {
@@ -189,11 +188,26 @@ __global__ __launch_bounds__(GS_THREADS) void group_scan_kernel(
     expand(s_nh);
 }
 
-// ---- grouped stage 1 fused with the stage-2 distances
-constexpr int GD_HITS = 2048;     // tuples below the threshold handled per pass
+// ---- grouped stage 1 fused with stage 2
+constexpr int GD_HITS = 1024;     // tuples below the threshold handled per pass
 constexpr int GD_PER = GD_HITS / GS_THREADS;
 constexpr int GD_LINEAR = 12;     // up to this many tuple boundaries in a row of 64 survivors: count them one by one
+constexpr int GD_ROWS = 4;        // rows of 64 survivors per wavefront and step
+constexpr int GD_STEP = GD_ROWS * GS_THREADS;            // most keys one step can add to the list
+constexpr int GD_LIST = 2048;     // keys of the block's nearest-neighbour list
+constexpr int GD_LPT = GD_LIST / GS_THREADS;             // list entries per thread in a cut
+constexpr int GD_SORT = 1024;     // most keys the final register sort takes
 static_assert(GD_HITS <= 2048 && GD_HITS % GS_THREADS == 0, "tuple search covers 64 x 32 entries");
+static_assert(GS_THREADS == 256, "one histogram bin per thread");
+static_assert(GD_LIST - GD_STEP >= 2 * 512, "room for topk <= 512 plus ties between two cuts");
+
+struct GdShared {
+    uint32_t hist[256];
+    uint32_t wred[GS_THREADS / 64][2];
+    uint32_t wtot[2][GS_THREADS / 64];
+    uint32_t wsum[GS_THREADS / 64][2];
+    uint32_t base;
+};
 
 // Inclusive scan of two counters over the block (GS_THREADS threads); returns the
 // exclusive prefixes through ex_a / ex_b and the block totals through tot_a / tot_b.
@@ -221,41 +235,203 @@ __device__ __forceinline__ void block_scan2(uint32_t a, uint32_t b, uint32_t (*w
     tot_a = ta; tot_b = tb;
 }
 
+// The kr-th smallest (1-based) of the values v[u] whose bit u is set in `ok`, taken over
+// the whole block; at least kr values are flagged.  EXACT: that value (radix select, 8-bit
+// digits over the occupied range).  Otherwise a single counting pass over the top 8 bits
+// of the occupied range; the result is the largest value of the bin that holds the kr-th
+// smallest, i.e. an upper bound that keeps the bin whole.  Every thread calls (barriers).
+__device__ __forceinline__ uint32_t block_kth(GdShared &sh, const uint32_t (&v)[GD_LPT], uint32_t ok, uint32_t kr,
+                                              bool EXACT, int tid, uint32_t lane, int wave) {
+    uint32_t vmin = 0xFFFFFFFFu, vmax = 0u;
+#pragma unroll
+    for (int u = 0; u < GD_LPT; ++u) {
+        if ((ok >> u) & 1u) {
+            vmin = v[u] < vmin ? v[u] : vmin;
+            vmax = v[u] > vmax ? v[u] : vmax;
+        }
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+        const uint32_t a = __shfl_xor(vmin, d, 64), b = __shfl_xor(vmax, d, 64);
+        vmin = a < vmin ? a : vmin;
+        vmax = b > vmax ? b : vmax;
+    }
+    __syncthreads();                       // earlier readers of wred / hist are done
+    if (lane == 0) { sh.wred[wave][0] = vmin; sh.wred[wave][1] = vmax; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < GS_THREADS / 64; ++w) {
+        const uint32_t a = sh.wred[w][0], b = sh.wred[w][1];
+        vmin = a < vmin ? a : vmin;
+        vmax = b > vmax ? b : vmax;
+    }
+    const uint32_t range = vmax - vmin;
+    const int bits = range == 0 ? 0 : 32 - __builtin_clz(range);
+    if (bits == 0) return vmin;
+    int shift = bits > 8 ? bits - 8 : 0;
+    int width = bits < 8 ? bits : 8;
+    uint32_t prefix = 0;       // chosen high digits of (value - vmin)
+    int fixed_from = 32;       // bits [fixed_from, 32) of (value - vmin) are decided
+    for (;;) {
+        sh.hist[tid] = 0;
+        __syncthreads();
+        const uint32_t dmask = (1u << width) - 1u;
+#pragma unroll
+        for (int u = 0; u < GD_LPT; ++u) {
+            if ((ok >> u) & 1u) {
+                const uint32_t y = v[u] - vmin;
+                const bool match = fixed_from >= 32 ? true : (y >> fixed_from) == prefix;
+                if (match) atomicAdd(&sh.hist[(y >> shift) & dmask], 1u);
+            }
+        }
+        __syncthreads();
+        // every wavefront locates the bin by itself (4 bins per lane)
+        uint32_t h[4], mine = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            h[r] = sh.hist[lane * 4 + r];
+            mine += h[r];
+        }
+        uint32_t incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(incl, d, 64);
+            if ((int)lane >= d) incl += o;
+        }
+        const int L = __builtin_ctzll(__builtin_amdgcn_ballot_w64(incl >= kr));
+        uint32_t run = incl - mine, my_bin = 0, my_below = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if (run < kr && run + h[r] >= kr) {
+                my_bin = lane * 4 + r;
+                my_below = run;
+            }
+            run += h[r];
+        }
+        const uint32_t bin = (uint32_t)__builtin_amdgcn_readlane((int)my_bin, L);
+        const uint32_t below = (uint32_t)__builtin_amdgcn_readlane((int)my_below, L);
+        kr -= below;
+        prefix = (prefix << width) | bin;
+        fixed_from = shift;
+        if (!EXACT || shift == 0) break;
+        const int ns = shift > 8 ? shift - 8 : 0;
+        width = shift - ns;
+        shift = ns;
+        __syncthreads();                   // every wavefront has read the histogram
+    }
+    if (shift == 0) return vmin + prefix;
+    const unsigned long long top = (unsigned long long)vmin + ((((unsigned long long)prefix + 1ull) << shift) - 1ull);
+    return top < (unsigned long long)vmax ? (uint32_t)top : vmax;
+}
+
+// Cut list[0..cnt) (cnt block-uniform, > topk) back to the keys whose distance word is at
+// or below a bound that keeps the topk smallest distances (ties at the bound kept; with
+// !EXACT the bound is the top of a histogram bin, see block_kth).  Returns the new count,
+// *bound = the bound.  Every thread calls.
+__device__ __forceinline__ uint32_t block_cut(GdShared &sh, unsigned long long *list, uint32_t cnt, uint32_t topk,
+                                              uint32_t *bound, bool EXACT, int tid, uint32_t lane, int wave) {
+    unsigned long long e[GD_LPT];
+    uint32_t v[GD_LPT], ok = 0;
+    __syncthreads();                       // the list is complete
+#pragma unroll
+    for (int u = 0; u < GD_LPT; ++u) {
+        const uint32_t i = (uint32_t)u * GS_THREADS + tid;
+        if (i < cnt) ok |= 1u << u;
+        e[u] = list[i < cnt ? i : 0];
+        v[u] = (uint32_t)(e[u] >> 32);
+    }
+    const uint32_t cut = block_kth(sh, v, ok, topk, EXACT, tid, lane, wave);
+    uint32_t c = 0;
+#pragma unroll
+    for (int u = 0; u < GD_LPT; ++u) c += ((ok >> u) & 1u) && v[u] <= cut ? 1u : 0u;
+    uint32_t off, d0, tot, d1;
+    block_scan2(c, 0u, sh.wsum, lane, wave, off, d0, tot, d1);
+#pragma unroll
+    for (int u = 0; u < GD_LPT; ++u)
+        if (((ok >> u) & 1u) && v[u] <= cut) list[off++] = e[u];
+    __syncthreads();
+    *bound = cut;
+    return tot;
+}
+
+// After an exact cut that left more than topk keys because many share the distance
+// `cut`: keep the keys below it and, of those at it, the ones with the smallest item ids
+// (the low word of a key is a grouped position; perm maps it to the id), exactly topk in
+// all -- the order (distance, id) decides, as in the final list.  Every thread calls.
+__device__ __forceinline__ uint32_t block_tie_cut(GdShared &sh, unsigned long long *list, uint32_t cnt, uint32_t topk, uint32_t cut,
+                                  const uint32_t *__restrict__ perm, int tid, uint32_t lane, int wave) {
+    unsigned long long e[GD_LPT];
+    uint32_t w[GD_LPT], lt = 0, eq = 0;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < GD_LPT; ++u) {
+        const uint32_t i = (uint32_t)u * GS_THREADS + tid;
+        e[u] = list[i < cnt ? i : 0];
+        const uint32_t d = (uint32_t)(e[u] >> 32);
+        if (i < cnt && d < cut) lt |= 1u << u;
+        if (i < cnt && d == cut) eq |= 1u << u;
+        w[u] = perm[(uint32_t)e[u]];       // a valid position even where the entry is unused
+    }
+    uint32_t x0, x1, n_lt, n_eq;
+    block_scan2((uint32_t)__builtin_popcount(lt), (uint32_t)__builtin_popcount(eq), sh.wsum, lane, wave, x0, x1,
+                n_lt, n_eq);
+    const uint32_t need = topk - n_lt;     // >= 1: the topk-th smallest distance is `cut`
+    const uint32_t idcut = block_kth(sh, w, eq, need, true, tid, lane, wave);
+    uint32_t keep = lt;
+#pragma unroll
+    for (int u = 0; u < GD_LPT; ++u)
+        if (((eq >> u) & 1u) && w[u] <= idcut) keep |= 1u << u;
+    uint32_t off, d0, tot, d1;
+    block_scan2((uint32_t)__builtin_popcount(keep), 0u, sh.wsum, lane, wave, off, d0, tot, d1);
+#pragma unroll
+    for (int u = 0; u < GD_LPT; ++u)
+        if ((keep >> u) & 1u) list[off++] = e[u];
+    __syncthreads();
+    return tot;
+}
+
 // grid (parts, Q): a block evaluates the tuples (c0, c1) with c0 in its part's row
 // range for one query; thread t owns column c1 = t (Kf == 2) or tuple c0 = t (Kf == 1)
 // and keeps one bit per row: crude distance below the threshold or not.  The
-// surviving tuples are compacted into LDS together with their first grouped
-// position and an exclusive prefix of their sizes (empty tuples dropped), which
-// turns "all items of all surviving tuples" into a flat range of survivor numbers
-// 0 .. tot-1.  The wavefronts then walk that range 64 survivors at a time: a lane
-// finds its tuple by counting the tuple boundaries at or below its number, reads
-// the item's grouped record (records of one tuple are contiguous, so the loads
-// coalesce), adds up the K table entries (all K tables of the query in LDS, k
-// ascending, one table per record byte, zero tables beyond K) and writes the
-// 64-bit key (order-preserving bits of D, item id) to slot base + number of the
-// query's key list.  No list of positions or ids is written or read back.  A block
-// that owns its query alone (parts == 1) counts the survivors locally and writes the
-// count once; otherwise every pass reserves its slots with one atomic.
-template <int KF, int WORDS>
-__global__ __launch_bounds__(GS_THREADS) void group_keys_kernel(
+// surviving tuples are compacted into LDS (GD_HITS at a time) together with their
+// first grouped position and an exclusive prefix of their sizes (empty tuples
+// dropped), which turns "all items of all surviving tuples" into a flat range of
+// survivor numbers 0 .. tot-1.  The wavefronts walk that range 64 survivors at a
+// time: a lane finds its tuple by counting the tuple boundaries at or below its
+// number, reads the item's record in grouped order (records of one tuple are
+// contiguous, so the loads coalesce) and adds up the K table entries (all K tables
+// of the query in LDS, k ascending, one table per record byte, zero tables beyond K).
+//
+// FUSED (the block owns its query: parts == 1): the nearest-neighbour list of Sec. 3.4
+// is kept right here.  A key (order-preserving bits of D, grouped position) enters the
+// block's list in LDS only if D is at or below the running bound; when the list could
+// overflow it is cut back to the topk smallest distances, which tightens the bound (one
+// histogram pass, see block_cut).  At the end the list is cut exactly, positions become
+// item ids, one wavefront sorts by (D, id) in registers and the result rows are written.
+// No candidate list ever reaches memory.
+//
+// !FUSED (several blocks share a query): every survivor's key (bits of D, item id) is
+// written to slot base + number of the query's key list for the select kernel; each
+// pass reserves its slots with one atomic on the query's counter.
+template <int KF, int WORDS, bool FUSED>
+__global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8))) void group_keys_kernel(
     const float *__restrict__ lut, int K, const float *__restrict__ thr,
     const uint32_t *__restrict__ start, const uint8_t *__restrict__ items_grouped,
-    unsigned long long *__restrict__ keys_out, uint32_t *__restrict__ count, int64_t cap,
-    int rows_per_block) {
+    const uint32_t *__restrict__ perm, unsigned long long *__restrict__ keys_out,
+    uint32_t *__restrict__ count, int64_t cap, int rows_per_block, int topk,
+    uint32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
     __shared__ float T[4 * WORDS * ICQ_LUT_W];
     __shared__ uint32_t hbuf[GD_HITS];        // tuple ids while compacting, then first positions
     __shared__ uint32_t hx[GD_HITS + 1];      // exclusive prefix of the tuple sizes, hx[nhc] = tot
-    __shared__ uint32_t wsum[GS_THREADS / 64][2];
-    __shared__ uint32_t s_base;
-    constexpr int RW = 2 * WORDS;
+    __shared__ unsigned long long list[FUSED ? GD_LIST : 1];
+    __shared__ GdShared sh;
     const int tid = threadIdx.x;
     const uint32_t lane = lane_id();
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wavefront-uniform, and known to be
     const int q = blockIdx.y;
     const float *Tq = lut + (int64_t)q * K * ICQ_LUT_W;
     const float t = thr[q];
-    unsigned long long *my_out = keys_out + (int64_t)q * cap;
-    const bool own_query = gridDim.x == 1;
+    unsigned long long *my_out = FUSED ? nullptr : keys_out + (int64_t)q * cap;
 
     for (int i = tid; i < 4 * WORDS * ICQ_LUT_W; i += GS_THREADS) T[i] = i < K * ICQ_LUT_W ? Tq[i] : 0.0f;
 
@@ -285,47 +461,28 @@ __global__ __launch_bounds__(GS_THREADS) void group_keys_kernel(
         m[0] = Tq[tid] < t ? 1u : 0u;
         mine = m[0];
     }
+    // this thread's surviving tuples are numbers [off_all, off_all + mine) of the block's total_hits
     uint32_t off_all, dummy0, total_hits, dummy1;
-    block_scan2(mine, 0u, wsum, lane, wave, off_all, dummy0, total_hits, dummy1);
-    // every surviving tuple at once if they fit, else eight rows (at most GD_HITS tuples) per pass
-    const bool single = total_hits <= (uint32_t)GD_HITS;
-    const int pass_rows = single ? 256 : GD_HITS / 256;
-    uint32_t run = 0;                          // survivors so far (block-uniform)
+    block_scan2(mine, 0u, sh.wsum, lane, wave, off_all, dummy0, total_hits, dummy1);
 
-    for (int ra = row_begin; ra < row_end; ra += pass_rows) {
-        const int rb = ra + pass_rows < row_end ? ra + pass_rows : row_end;
-        // ---- compact the tuples of rows [ra, rb) into hbuf
-        uint32_t off, nh;
-        if (single) {
-            off = off_all;
-            nh = total_hits;
-        } else {
-            uint32_t c = 0;
+    uint32_t run = 0;                          // survivors so far (block-uniform)
+    uint32_t cnt = 0;                          // FUSED: keys in the list (block-uniform)
+    uint32_t bound = 0xFFFFFFFFu;              // FUSED: keys with distance bits above it cannot reach the result
+
+    for (uint32_t pass_lo = 0; pass_lo < total_hits; pass_lo += GD_HITS) {
+        const uint32_t nh = total_hits - pass_lo < (uint32_t)GD_HITS ? total_hits - pass_lo : (uint32_t)GD_HITS;
+        // ---- tuples number pass_lo .. pass_lo + nh - 1 -> hbuf
+        {
+            uint32_t idx = off_all;
 #pragma unroll
             for (int w = 0; w < 8; ++w) {
-                const int lo = ra - w * 32, hi = rb - w * 32;
-                if (hi > 0 && lo < 32) {
-                    uint32_t bits = m[w];
-                    if (lo > 0) bits &= ~0u << lo;
-                    if (hi < 32) bits &= ~(~0u << hi);
-                    c += __builtin_popcount(bits);
-                }
-            }
-            uint32_t d0, d1;
-            block_scan2(c, 0u, wsum, lane, wave, off, d0, nh, d1);
-        }
-        if (nh == 0) continue;                 // block-uniform
-#pragma unroll
-        for (int w = 0; w < 8; ++w) {
-            const int lo = ra - w * 32, hi = rb - w * 32;
-            if (hi > 0 && lo < 32) {
                 uint32_t bits = m[w];
-                if (lo > 0) bits &= ~0u << lo;
-                if (hi < 32) bits &= ~(~0u << hi);
                 while (bits != 0) {
                     const int b = __builtin_ctz(bits);
                     bits &= bits - 1;
-                    hbuf[off++] = KF == 2 ? (uint32_t)(w * 32 + b) * 256u + (uint32_t)tid : (uint32_t)tid;
+                    const uint32_t rel = idx - pass_lo;             // wraps below the pass: fails the test
+                    if (rel < nh) hbuf[rel] = KF == 2 ? (uint32_t)(w * 32 + b) * 256u + (uint32_t)tid : (uint32_t)tid;
+                    ++idx;
                 }
             }
         }
@@ -349,7 +506,7 @@ __global__ __launch_bounds__(GS_THREADS) void group_keys_kernel(
             tc += n[u] != 0 ? 1u : 0u;
         }
         uint32_t x, c, tot, nhc;
-        block_scan2(tn, tc, wsum, lane, wave, x, c, tot, nhc);   // its barriers also order the hbuf reads above
+        block_scan2(tn, tc, sh.wsum, lane, wave, x, c, tot, nhc);   // its barriers also order the hbuf reads above
         if (tot == 0) continue;                // block-uniform
 #pragma unroll
         for (int u = 0; u < GD_PER; ++u) {
@@ -362,106 +519,175 @@ __global__ __launch_bounds__(GS_THREADS) void group_keys_kernel(
         }
         if (tid == 0) {
             hx[nhc] = tot;
-            if (!own_query) s_base = atomicAdd(&count[q], tot);
+            if (!FUSED) sh.base = atomicAdd(&count[q], tot);
         }
         __syncthreads();
-        const uint32_t base = own_query ? run : s_base;
+        const uint32_t base = FUSED ? 0u : sh.base;
         run += tot;
 
         // ---- the survivors, 64 per row; the rows are dealt to the wavefronts in contiguous runs
         const uint32_t nrows = (tot + 63) >> 6;
         const uint32_t rpw = (nrows + GS_THREADS / 64 - 1) / (GS_THREADS / 64);
-        uint32_t r = (uint32_t)wave * rpw;
-        const uint32_t rend = r + rpw < nrows ? r + rpw : nrows;
-        if (r < rend) {
-            // tuple holding survivor r * 64: the last one whose prefix is <= it (two 64-way probes)
-            uint32_t ha;
-            {
-                const uint32_t p = r * 64;
-                const uint32_t i1 = lane * 32;
-                const uint32_t v1 = hx[i1 < nhc ? i1 : nhc];
-                const uint32_t c1 = __builtin_popcountll(__builtin_amdgcn_ballot_w64(i1 < nhc && v1 <= p));
-                const uint32_t b0 = (c1 - 1) * 32;
-                const uint32_t i2 = b0 + lane;
-                const uint32_t v2 = hx[i2 < nhc ? i2 : nhc];
-                const uint32_t c2 = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lane < 32 && i2 < nhc && v2 <= p));
-                ha = b0 + c2 - 1;
+        const uint32_t r0 = (uint32_t)wave * rpw;
+        const uint32_t rend = r0 + rpw < nrows ? r0 + rpw : nrows;        // <= r0: nothing for this wavefront
+        const uint32_t steps = (rpw + GD_ROWS - 1) / GD_ROWS;              // block-uniform
+        uint32_t ha = 0;
+        if (r0 < rend) {
+            // tuple holding survivor r0 * 64: the last one whose prefix is <= it (two 64-way probes)
+            const uint32_t p = r0 * 64;
+            const uint32_t i1 = lane * 32;
+            const uint32_t v1 = hx[i1 < nhc ? i1 : nhc];
+            const uint32_t c1 = __builtin_popcountll(__builtin_amdgcn_ballot_w64(i1 < nhc && v1 <= p));
+            const uint32_t b0 = (c1 - 1) * 32;
+            const uint32_t i2 = b0 + lane;
+            const uint32_t v2 = hx[i2 < nhc ? i2 : nhc];
+            const uint32_t c2 = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lane < 32 && i2 < nhc && v2 <= p));
+            ha = b0 + c2 - 1;
+        }
+        // grouped position of this lane's survivor in row `row` (< rend); moves ha to the tuple of the next row
+        auto locate = [&](uint32_t row) -> uint32_t {
+            const uint32_t pl = row * 64 + 63 < tot ? row * 64 + 63 : tot - 1;
+            uint32_t p = row * 64 + lane;
+            p = p < pl ? p : pl;
+            const uint32_t bi = ha + 1 + lane;
+            const uint32_t bnd = hx[bi < nhc ? bi : nhc];      // prefixes of the tuples after ha
+            const uint32_t nb = __builtin_popcountll(__builtin_amdgcn_ballot_w64(bnd <= pl));
+            uint32_t h = ha;
+            if (nb <= (uint32_t)GD_LINEAR) {
+                for (uint32_t j = 0; j < nb; ++j)
+                    h += p >= (uint32_t)__builtin_amdgcn_readlane((int)bnd, (int)j) ? 1u : 0u;
+            } else {
+                uint32_t lo = ha, hi = ha + nb;                 // hx[lo] <= p, answer in [lo, hi]
+                while (__builtin_amdgcn_ballot_w64(lo < hi) != 0) {
+                    const uint32_t mid = (lo + hi + 1) >> 1;
+                    const bool le = hx[mid] <= p;
+                    if (lo < hi) {
+                        if (le) lo = mid; else hi = mid - 1;
+                    }
+                }
+                h = lo;
             }
-            // grouped position of this lane's survivor in row `row`; moves ha to the tuple of the next row
-            auto locate = [&](uint32_t row) -> uint32_t {
-                const uint32_t pl = row * 64 + 63 < tot ? row * 64 + 63 : tot - 1;
-                uint32_t p = row * 64 + lane;
-                p = p < pl ? p : pl;
-                const uint32_t bi = ha + 1 + lane;
-                const uint32_t bnd = hx[bi < nhc ? bi : nhc];      // prefixes of the tuples after ha
-                const uint32_t nb = __builtin_popcountll(__builtin_amdgcn_ballot_w64(bnd <= pl));
-                uint32_t h = ha;
-                if (nb <= (uint32_t)GD_LINEAR) {
-                    for (uint32_t j = 0; j < nb; ++j) h += p >= (uint32_t)__builtin_amdgcn_readlane((int)bnd, (int)j) ? 1u : 0u;
+            const uint32_t pos = hbuf[h] + (p - hx[h]);
+            ha += __builtin_popcountll(__builtin_amdgcn_ballot_w64(bnd <= pl + 1 && bi < nhc));
+            return pos;
+        };
+        // records (and, for the key list, ids) of rows r .. r + GD_ROWS - 1; rows past rend read record 0, unused
+        auto fetch = [&](uint32_t r, uint32_t (*rec)[WORDS], uint32_t *low) {
+#pragma unroll
+            for (int u = 0; u < GD_ROWS; ++u) {
+                uint32_t pos = 0;
+                if (r + u < rend) pos = locate(r + u);          // wavefront-uniform
+                const uint32_t *p = reinterpret_cast<const uint32_t *>(items_grouped + (size_t)pos * (WORDS * 4));
+                if (WORDS == 1) {
+                    rec[u][0] = p[0];
+                } else if (WORDS == 2) {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(p);
+                    rec[u][0] = v.x;
+                    rec[u][1 % WORDS] = v.y;
                 } else {
-                    uint32_t lo = ha, hi = ha + nb;                 // hx[lo] <= p, answer in [lo, hi]
-                    while (__builtin_amdgcn_ballot_w64(lo < hi) != 0) {
-                        const uint32_t mid = (lo + hi + 1) >> 1;
-                        const bool le = hx[mid] <= p;
-                        if (lo < hi) {
-                            if (le) lo = mid; else hi = mid - 1;
-                        }
-                    }
-                    h = lo;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(p);
+                    rec[u][0] = v.x;
+                    rec[u][1 % WORDS] = v.y;
+                    rec[u][2 % WORDS] = v.z;
+                    rec[u][3 % WORDS] = v.w;
                 }
-                const uint32_t pos = hbuf[h] + (p - hx[h]);
-                ha += __builtin_popcountll(__builtin_amdgcn_ballot_w64(bnd <= pl + 1 && bi < nhc));
-                return pos;
-            };
-            auto fetch = [&](uint32_t r0, uint32_t (*rec)[RW]) {
+                low[u] = FUSED ? pos : perm[pos];
+            }
+        };
+        uint32_t cur[GD_ROWS][WORDS], nxt[GD_ROWS][WORDS], cur_low[GD_ROWS], nxt_low[GD_ROWS];
+        fetch(r0, cur, cur_low);
+        for (uint32_t it = 0; it < steps; ++it) {
+            const uint32_t r = r0 + it * GD_ROWS;
+            fetch(r + GD_ROWS, nxt, nxt_low);
+            unsigned long long key[GD_ROWS];
+            bool take[GD_ROWS];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    uint32_t pos = 0;
-                    if (r0 + u < rend) pos = locate(r0 + u);        // wavefront-uniform
-                    const uint32_t *p = reinterpret_cast<const uint32_t *>(items_grouped + (size_t)pos * (RW * 4));
-                    if (RW == 2) {
-                        const uint2 v = *reinterpret_cast<const uint2 *>(p);
-                        rec[u][0] = v.x;
-                        rec[u][1 % RW] = v.y;
-                    } else {
+            for (int u = 0; u < GD_ROWS; ++u) {
+                float d = 0.0f;
 #pragma unroll
-                        for (int w4 = 0; w4 < RW / 4; ++w4) {
-                            const uint4 v = reinterpret_cast<const uint4 *>(p)[w4];
-                            rec[u][(4 * w4) % RW] = v.x;
-                            rec[u][(4 * w4 + 1) % RW] = v.y;
-                            rec[u][(4 * w4 + 2) % RW] = v.z;
-                            rec[u][(4 * w4 + 3) % RW] = v.w;
-                        }
-                    }
+                for (int w = 0; w < WORDS; ++w) {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        d += T[(w * 4 + b) * ICQ_LUT_W + ((cur[u][w] >> (8 * b)) & 0xffu)];
                 }
-            };
-            uint32_t cur[4][RW], nxt[4][RW];
-            fetch(r, cur);
-            for (; r < rend; r += 4) {
-                fetch(r + 4, nxt);                                   // rows past rend read record 0, unused
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    float d = 0.0f;
-#pragma unroll
-                    for (int w = 0; w < WORDS; ++w) {
-#pragma unroll
-                        for (int b = 0; b < 4; ++b)
-                            d += T[(w * 4 + b) * ICQ_LUT_W + ((cur[u][w] >> (8 * b)) & 0xffu)];
-                    }
-                    const uint32_t num = (r + u) * 64 + lane;
+                const uint32_t ob = icq_order_bits(d);
+                const uint32_t num = (r + u) * 64 + lane;
+                key[u] = ((unsigned long long)ob << 32) | cur_low[u];
+                take[u] = r + u < rend && num < tot;
+                if (FUSED) {
+                    take[u] = take[u] && ob <= bound;
+                } else {
                     const uint64_t slot = (uint64_t)base + num;
-                    if (r + u < rend && num < tot && slot < (uint64_t)cap)
-                        my_out[slot] = ((unsigned long long)icq_order_bits(d) << 32) | cur[u][WORDS % RW];
+                    if (take[u] && slot < (uint64_t)cap) my_out[slot] = key[u];
+                }
+            }
+            if (FUSED) {
+                uint64_t mk[GD_ROWS];
+                uint32_t pre[GD_ROWS], mycnt = 0;
+#pragma unroll
+                for (int u = 0; u < GD_ROWS; ++u) {
+                    mk[u] = __builtin_amdgcn_ballot_w64(take[u]);
+                    pre[u] = mycnt;
+                    mycnt += (uint32_t)__builtin_popcountll(mk[u]);
+                }
+                if (lane == 0) sh.wtot[it & 1][wave] = mycnt;
+                __syncthreads();
+                uint32_t mybase = cnt, all = 0;
+#pragma unroll
+                for (int w = 0; w < GS_THREADS / 64; ++w) {
+                    const uint32_t tw = sh.wtot[it & 1][w];
+                    if (w < wave) mybase += tw;
+                    all += tw;
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < GD_ROWS; ++u)
+                    if (take[u]) list[mybase + pre[u] + (uint32_t)__builtin_popcountll(mk[u] & ((1ull << lane) - 1))] = key[u];
+                cnt += all;
+                // block-uniform: cut while the next step might not fit -- one counting pass, then
+                // (fat bin) exactly, then (many equal distances) by id
+                for (int lvl = 0; lvl < 3 && cnt > (uint32_t)(GD_LIST - GD_STEP); ++lvl) {
+                    if (lvl < 2) cnt = block_cut(sh, list, cnt, (uint32_t)topk, &bound, lvl == 1, tid, lane, wave);
+                    else cnt = block_tie_cut(sh, list, cnt, (uint32_t)topk, bound, perm, tid, lane, wave);
+                }
+            }
 #pragma unroll
-                    for (int w = 0; w < RW; ++w) cur[u][w] = nxt[u][w];
+            for (int u = 0; u < GD_ROWS; ++u) {
+#pragma unroll
+                for (int w = 0; w < WORDS; ++w) cur[u][w] = nxt[u][w];
+                cur_low[u] = nxt_low[u];
             }
         }
         __syncthreads();                       // hbuf / hx are rewritten by the next pass
     }
-    if (own_query && tid == 0) count[q] = run;
+
+    if (!FUSED) return;                        // the atomics have counted the survivors
+    if (tid == 0) count[q] = run;
+    // ---- final list: exact cut, positions -> ids, order by (D, id)
+    if (cnt > (uint32_t)topk) {
+        cnt = block_cut(sh, list, cnt, (uint32_t)topk, &bound, true, tid, lane, wave);
+        if (cnt > (uint32_t)GD_SORT) cnt = block_tie_cut(sh, list, cnt, (uint32_t)topk, bound, perm, tid, lane, wave);
+    }
+    __syncthreads();
+    int len = 64;
+    while (len < (int)cnt) len <<= 1;
+    for (int i = tid; i < len; i += GS_THREADS) {
+        unsigned long long k = KEY_PAD;
+        if (i < (int)cnt) {
+            k = list[i];
+            k = (k & 0xFFFFFFFF00000000ull) | perm[(uint32_t)k];
+        }
+        list[i] = k;
+    }
+    __syncthreads();
+    if (wave == 0) wave_sort(list, len, (int)lane);
+    __syncthreads();
+    const int kept = (int)cnt < topk ? (int)cnt : topk;
+    uint32_t *oi = out_ids + (int64_t)q * topk;
+    float *od = out_dist + (int64_t)q * topk;
+    for (int r = tid; r < topk; r += GS_THREADS) {
+        oi[r] = r < kept ? (uint32_t)list[r] : ICQ_PAD_ID;
+        od[r] = r < kept ? icq_unorder_bits((uint32_t)(list[r] >> 32)) : INFINITY;
+    }
 }
 
 }  // namespace
@@ -477,7 +703,7 @@ int icq_group_build(icq_index *ix, hipStream_t s) {
     bool ok = hipMalloc(&ix->group_start, sizeof(uint32_t) * (G + 1)) == hipSuccess &&
               hipMalloc(&ix->group_cursor, sizeof(uint32_t) * G) == hipSuccess &&
               hipMalloc(&ix->perm, sizeof(uint32_t) * (size_t)ix->N) == hipSuccess &&
-              hipMalloc(&ix->items_grouped, (size_t)ix->N * ix->item_stride * 2) == hipSuccess;
+              hipMalloc(&ix->items_grouped, (size_t)ix->N * ix->item_stride) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
         return ICQ_ERR_HIP;   // the caller destroys the index, which frees whatever was allocated
@@ -501,16 +727,21 @@ bool icq_group_usable(const icq_index *ix, int Q) {
     return Q > 4 && ix->N >= (int64_t)ix->groups / 2;
 }
 
+// Blocks that share one query's tuple rows in the grouped kernels: enough to fill the chip
+// when there are few queries.
+static int group_parts(const icq_index *ix, int Q) {
+    if (ix->Kf != 2) return 1;
+    int parts = (2 * ix->num_cu + Q - 1) / Q;
+    if (parts > 16) parts = 16;
+    if (parts < 1) parts = 1;
+    return parts;
+}
+
 int icq_launch_group_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
                           uint32_t *cand_ids, bool as_positions, uint32_t *cand_count, int64_t cap,
                           hipStream_t s) {
     // cand_count has been zeroed by the caller (icq_launch_scan)
-    int parts = 1;
-    if (ix->Kf == 2) {
-        parts = (2 * ix->num_cu + Q - 1) / Q;
-        if (parts > 16) parts = 16;
-        if (parts < 1) parts = 1;
-    }
+    const int parts = group_parts(ix, Q);
     const int rows = (256 + parts - 1) / parts;
     for (int q0 = 0; q0 < Q; q0 += 65535) {
         const int nq = Q - q0 < 65535 ? Q - q0 : 65535;
@@ -527,26 +758,36 @@ int icq_launch_group_scan(const icq_index *ix, const float *lut, int Q, const fl
     return icq_check_launch();
 }
 
+bool icq_group_fused(const icq_index *ix, int Q, int topk) {
+    return icq_group_usable(ix, Q) && ix->item_stride <= 16 && topk <= 512 && group_parts(ix, Q) == 1;
+}
+
 int icq_launch_group_keys(const icq_index *ix, const float *lut, int Q, const float *thr,
-                          unsigned long long *cand_keys, uint32_t *cand_count, int64_t cap,
-                          hipStream_t s) {
+                          unsigned long long *cand_keys, uint32_t *cand_count, int64_t cap, int topk,
+                          uint32_t *out_ids, float *out_dist, hipStream_t s) {
     // cand_count has been zeroed by the caller (icq_launch_scan); item_stride <= 16 here
-    int parts = 1;
-    if (ix->Kf == 2) {
-        parts = (2 * ix->num_cu + Q - 1) / Q;
-        if (parts > 16) parts = 16;
-        if (parts < 1) parts = 1;
-    }
+    const bool fused = out_ids != nullptr && icq_group_fused(ix, Q, topk);
+    if (!fused && !cand_keys) return ICQ_ERR_ARG;
+    const int parts = group_parts(ix, Q);
     const int rows = (256 + parts - 1) / parts;
     for (int q0 = 0; q0 < Q; q0 += 65535) {
         const int nq = Q - q0 < 65535 ? Q - q0 : 65535;
         dim3 grid((unsigned)parts, (unsigned)nq);
         const float *l = lut + (int64_t)q0 * ix->K * ICQ_LUT_W;
-        unsigned long long *ko = cand_keys + (int64_t)q0 * cap;
-#define ICQ_GK(KF, W)                                                                                \
-    group_keys_kernel<KF, W><<<grid, GS_THREADS, 0, s>>>(l, ix->K, thr + q0, ix->group_start,         \
-                                                         ix->items_grouped, ko, cand_count + q0, cap, \
-                                                         rows)
+        unsigned long long *ko = cand_keys ? cand_keys + (int64_t)q0 * cap : nullptr;
+        uint32_t *oi = fused ? out_ids + (int64_t)q0 * topk : nullptr;
+        float *od = fused ? out_dist + (int64_t)q0 * topk : nullptr;
+#define ICQ_GK(KF, W)                                                                                         \
+    do {                                                                                                      \
+        if (fused)                                                                                            \
+            group_keys_kernel<KF, W, true><<<grid, GS_THREADS, 0, s>>>(                                        \
+                l, ix->K, thr + q0, ix->group_start, ix->items_grouped, ix->perm, ko, cand_count + q0, cap,    \
+                rows, topk, oi, od);                                                                          \
+        else                                                                                                  \
+            group_keys_kernel<KF, W, false><<<grid, GS_THREADS, 0, s>>>(                                       \
+                l, ix->K, thr + q0, ix->group_start, ix->items_grouped, ix->perm, ko, cand_count + q0, cap,    \
+                rows, topk, oi, od);                                                                          \
+    } while (0)
         const int W = ix->item_stride / 4;
         if (ix->Kf == 1) {
             if (W == 1) ICQ_GK(1, 1); else if (W == 2) ICQ_GK(1, 2); else ICQ_GK(1, 4);

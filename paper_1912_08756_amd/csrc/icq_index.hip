@@ -51,7 +51,7 @@ __global__ void export_grouped_kernel(const uint8_t *__restrict__ items_grouped,
     int k = blockIdx.y;
     int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (pos >= N) return;
-    out[(int64_t)k * N + perm[pos]] = items_grouped[pos * (2 * stride) + k];   // grouped records are 2*stride wide
+    out[(int64_t)k * N + perm[pos]] = items_grouped[pos * stride + k];
 }
 
 // codes_out[k][i] rebuilt from the private layouts: rows below `fast_rows` from

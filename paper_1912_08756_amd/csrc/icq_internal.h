@@ -36,7 +36,7 @@ struct icq_index {
     uint32_t *group_start;     // [groups + 1] first grouped position of each tuple
     uint32_t *group_cursor;    // [groups] scratch of the build
     uint32_t *perm;            // [N] grouped position -> item id
-    uint8_t *items_grouped;    // [N][2*item_stride] grouped order: sub-codes, then the item id, zero padded
+    uint8_t *items_grouped;    // [N][item_stride] the item records in grouped order
     icq_stage_timer *timer;    // nullptr unless stage timing is on
 };
 
@@ -45,7 +45,8 @@ enum icq_list_kind {
     ICQ_LIST_IDS = 0,          // item ids
     ICQ_LIST_IDS_REC = 1,      // item ids, item records alongside in cand_rec
     ICQ_LIST_POSITIONS = 2,    // grouped positions (ids through perm, records from items_grouped)
-    ICQ_LIST_KEYS = 3          // stage 1 already wrote one 64-bit key (bits of D, id) per survivor
+    ICQ_LIST_KEYS = 3,         // stage 1 already wrote one 64-bit key (bits of D, id) per survivor
+    ICQ_LIST_DONE = 4          // stage 1 kept the nearest-neighbour lists itself and wrote the results
 };
 
 // Order-preserving bits of a float: u(a) < u(b) <=> a < b.
@@ -78,14 +79,18 @@ int icq_launch_build_lut(const icq_index *ix, const float *queries, int Q, float
 // scan picks the cheapest representation for stage 2 and reports it: finished keys in
 // cand_keys ([Q][cap], may be nullptr), grouped positions, or ids with each survivor's
 // item record written to cand_rec ([Q][cap][item_stride/4] words; may be nullptr).
+// topk / out_ids / out_dist (may be nullptr): where the scan may write the final lists
+// itself (ICQ_LIST_DONE) when its grouped form covers stage 2 as well.
 int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
                     uint32_t *cand_ids, float *cand_part, uint32_t *cand_rec,
                     unsigned long long *cand_keys, int *list_kind, uint32_t *cand_count, int64_t cap,
-                    float *lutT, hipStream_t s);
-// Grouped stage 1 fused with the stage-2 distances: one 64-bit key per survivor.
+                    float *lutT, int topk, uint32_t *out_ids, float *out_dist, hipStream_t s);
+// Grouped stage 1 fused with stage 2: the final lists when icq_group_fused() holds and
+// out_ids is given, else one 64-bit key per survivor in cand_keys.
+bool icq_group_fused(const icq_index *ix, int Q, int topk);
 int icq_launch_group_keys(const icq_index *ix, const float *lut, int Q, const float *thr,
-                          unsigned long long *cand_keys, uint32_t *cand_count, int64_t cap,
-                          hipStream_t s);
+                          unsigned long long *cand_keys, uint32_t *cand_count, int64_t cap, int topk,
+                          uint32_t *out_ids, float *out_dist, hipStream_t s);
 // Where the per-candidate keys live inside the key area of the workspace.
 static inline unsigned long long *icq_cand_keys(unsigned long long *keys, int Q, int splits, int topk) {
     return keys + (splits > 1 ? (size_t)Q * splits * topk : 0);

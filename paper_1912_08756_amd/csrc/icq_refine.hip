@@ -12,20 +12,14 @@
 // buffer only if it beats the current topk-th key; when the buffer fills it is
 // sorted (bitonic) and cut back to topk, which tightens the bound.
 #include "icq_internal.h"
+#include "icq_sort.h"
 
 namespace {
 
-typedef unsigned long long u64;
 constexpr int RF_THREADS = 256;
-constexpr u64 KEY_PAD = ~0ull;
 
-__device__ __forceinline__ uint32_t order_bits(float x) {
-    uint32_t b = __float_as_uint(x);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
-__device__ __forceinline__ float unorder_bits(uint32_t u) {
-    return __uint_as_float((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
-}
+__device__ __forceinline__ uint32_t order_bits(float x) { return icq_order_bits(x); }
+__device__ __forceinline__ float unorder_bits(uint32_t u) { return icq_unorder_bits(u); }
 
 // Compare-exchange steps j = jmax, jmax/2, .., 1 of bitonic stage k on the element
 // a lane holds, against lanes lane^j of its own wavefront (no LDS, no barrier).
@@ -225,16 +219,14 @@ constexpr int RD_PER = 8;                            // candidates per thread an
 constexpr int RD_STEP = RF_THREADS * RD_PER;         // 2048
 constexpr int RD_BLOCK = 2 * RD_STEP;                // candidates per block
 
-// GROUPED: the list holds grouped positions and `items` is the grouped record array,
-// whose records are 2*WORDS words: the sub-codes, then the item id in word WORDS.
-template <int WORDS, bool GROUPED>
+template <int WORDS>
 __global__ __launch_bounds__(RF_THREADS) void refine_dist_kernel(
     const uint8_t *__restrict__ items, int K, int Kf, const float *__restrict__ lut,
     const uint32_t *__restrict__ cand_ids, const float *__restrict__ cand_part,
     const uint32_t *__restrict__ cand_rec, const uint32_t *__restrict__ cand_count, int64_t cap,
     int blocks_per_query, u64 *__restrict__ keys) {
     __shared__ float T[4 * WORDS * ICQ_LUT_W];
-    constexpr int RW = GROUPED ? 2 * WORDS : WORDS;   // words per record as stored
+    constexpr int RW = WORDS;                         // words per item record
     const int q = blockIdx.x / blocks_per_query;
     const u64 c0 = (u64)(blockIdx.x % blocks_per_query) * RD_BLOCK;
     const int tid = threadIdx.x;
@@ -317,8 +309,7 @@ __global__ __launch_bounds__(RF_THREADS) void refine_dist_kernel(
                     d += T[(w * 4 + b) * ICQ_LUT_W + ((rec[st][j][w] >> (8 * b)) & 0xffu)];
             }
             const u64 i = c0 + (u64)st * RD_STEP + j * RF_THREADS + tid;
-            const uint32_t item = GROUPED ? rec[st][j][WORDS % RW] : id[st][j];
-            if (i < n) out[i] = ((u64)order_bits(d) << 32) | item;
+            if (i < n) out[i] = ((u64)order_bits(d) << 32) | id[st][j];
         }
     }
 }
@@ -395,60 +386,6 @@ __device__ uint32_t wave_radix_select(SelectShared *sh, const uint32_t *U, uint3
         __syncthreads();
     }
     return vmin + prefix;
-}
-
-// Compare-exchange of the register pairs (r, r | M) of a lane: elements 64*M apart.
-template <int M>
-__device__ __forceinline__ void reg_exchange(u64 (&x)[16], int E, int k, int lane) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        if ((r & M) == 0 && (r | M) < E) {
-            const bool up = (((r * 64 + lane) & k) == 0);
-            const u64 a = x[r], b = x[r | M];
-            const bool sw = (a > b) == up;
-            x[r] = sw ? b : a;
-            x[r | M] = sw ? a : b;
-        }
-    }
-}
-
-// Ascending bitonic sort of keys[0..len) by ONE wavefront, len a power of two, 64 <= len
-// <= 1024, entirely in registers: element e sits in register e/64 of lane e%64, so an
-// exchange at distance >= 64 pairs two registers of a lane and one at distance < 64 is
-// a shuffle; the len/64 elements of a lane are independent, which keeps the shuffles
-// pipelined.  keys[len..) is not touched; keys must hold len valid or padding entries.
-__device__ void wave_sort(u64 *keys, int len) {
-    const int lane = threadIdx.x;
-    const int E = len >> 6;
-    u64 x[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) x[r] = r < E ? keys[r * 64 + lane] : KEY_PAD;
-    for (int k = 2; k <= len; k <<= 1) {
-        for (int j = k >> 1; j >= 64; j >>= 1) {
-            switch (j >> 6) {
-                case 1: reg_exchange<1>(x, E, k, lane); break;
-                case 2: reg_exchange<2>(x, E, k, lane); break;
-                case 4: reg_exchange<4>(x, E, k, lane); break;
-                default: reg_exchange<8>(x, E, k, lane); break;
-            }
-        }
-        for (int j = (k >> 1) < 32 ? (k >> 1) : 32; j > 0; j >>= 1) {
-            const bool low = (lane & j) == 0;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                if (r < E) {
-                    const u64 y = __shfl_xor(x[r], j, 64);
-                    const bool up = (((r * 64 + lane) & k) == 0);
-                    const bool take_min = up == low;
-                    x[r] = take_min ? (x[r] < y ? x[r] : y) : (x[r] > y ? x[r] : y);
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < 16; ++r)
-        if (r < E) keys[r * 64 + lane] = x[r];
-    __syncthreads();
 }
 
 // Cut the list back to its topk smallest distances (ties at the cut kept): exact radix
@@ -566,7 +503,8 @@ __global__ __launch_bounds__(SK_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8
                 // whole key and keep exactly topk (the ids decide among equal distances)
                 for (int i = (int)cnt + tid; i < listcap; i += SK_THREADS) list[i] = KEY_PAD;
                 __syncthreads();
-                wave_sort(list, listcap);
+                wave_sort(list, listcap, threadIdx.x);
+                __syncthreads();
                 cnt = (uint32_t)topk;
                 ubound = (uint32_t)(list[topk - 1] >> 32);
             }
@@ -588,7 +526,8 @@ __global__ __launch_bounds__(SK_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8
     while (len < (int)cnt) len <<= 1;
     for (int i = (int)cnt + tid; i < len; i += SK_THREADS) list[i] = KEY_PAD;
     __syncthreads();
-    wave_sort(list, len);
+    wave_sort(list, len, threadIdx.x);
+    __syncthreads();
     const int kept = (int)cnt < topk ? (int)cnt : topk;
     uint32_t *oi = out_ids + (int64_t)q * topk;
     float *od = out_dist + (int64_t)q * topk;
@@ -625,7 +564,7 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
                       const float *cand_part, const uint32_t *cand_rec, int list_kind,
                       const uint32_t *cand_count, int64_t cap, int topk, int splits, u64 *keys,
                       uint32_t *out_ids, float *out_dist, hipStream_t s) {
-    if (Q == 0) return ICQ_OK;
+    if (Q == 0 || list_kind == ICQ_LIST_DONE) return ICQ_OK;
     const uint8_t *items = list_kind == ICQ_LIST_POSITIONS ? ix->items_grouped : ix->items;
     const uint32_t *perm = list_kind == ICQ_LIST_POSITIONS ? ix->perm : nullptr;
     if (list_kind != ICQ_LIST_IDS_REC) cand_rec = nullptr;
@@ -637,22 +576,15 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
         int64_t len = cap < ix->N ? cap : ix->N;
         const int bpq = len > 0 ? (int)((len + RD_BLOCK - 1) / RD_BLOCK) : 1;
         const unsigned dgrid = (unsigned)Q * (unsigned)bpq;
-        const bool grouped = list_kind == ICQ_LIST_POSITIONS;
         if (list_kind != ICQ_LIST_KEYS) {
-#define ICQ_RD_LAUNCH(W, G)                                                                          \
-    refine_dist_kernel<W, G><<<dgrid, RF_THREADS, 0, s>>>(items, ix->K, ix->Kf, lut, cand_ids,       \
-                                                          cand_part, cand_rec, cand_count, cap, bpq, \
-                                                          cand_keys)
+#define ICQ_RD_LAUNCH(W)                                                                          \
+    refine_dist_kernel<W><<<dgrid, RF_THREADS, 0, s>>>(items, ix->K, ix->Kf, lut, cand_ids,       \
+                                                       cand_part, cand_rec, cand_count, cap, bpq, \
+                                                       cand_keys)
         switch (ix->item_stride) {
-            case 4:
-                if (grouped) ICQ_RD_LAUNCH(1, true); else ICQ_RD_LAUNCH(1, false);
-                break;
-            case 8:
-                if (grouped) ICQ_RD_LAUNCH(2, true); else ICQ_RD_LAUNCH(2, false);
-                break;
-            default:
-                if (grouped) ICQ_RD_LAUNCH(4, true); else ICQ_RD_LAUNCH(4, false);
-                break;
+            case 4: ICQ_RD_LAUNCH(1); break;
+            case 8: ICQ_RD_LAUNCH(2); break;
+            default: ICQ_RD_LAUNCH(4); break;
         }
 #undef ICQ_RD_LAUNCH
         if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;
@@ -669,8 +601,7 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
                                             hipFuncAttributeMaxDynamicSharedMemorySize, 98304));
             attr_set = true;
         }
-        const int rec_stride = list_kind == ICQ_LIST_POSITIONS ? 2 * ix->item_stride : ix->item_stride;
-        refine_kernel<<<grid, RF_THREADS, lds, s>>>(items, rec_stride, ix->K, ix->Kf, lut,
+        refine_kernel<<<grid, RF_THREADS, lds, s>>>(items, ix->item_stride, ix->K, ix->Kf, lut,
                                                     cand_ids, cand_part, perm, cand_count, cap, topk,
                                                     bufn, splits, keys, out_ids, out_dist);
     }

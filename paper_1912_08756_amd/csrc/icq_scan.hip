@@ -567,17 +567,19 @@ int launch_batch_rec(const icq_index *ix, int Q, const float *thr, uint32_t *can
 int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
                     uint32_t *cand_ids, float *cand_part, uint32_t *cand_rec,
                     unsigned long long *cand_keys, int *list_kind, uint32_t *cand_count, int64_t cap,
-                    float *lutT, hipStream_t s) {
+                    float *lutT, int topk, uint32_t *out_ids, float *out_dist, hipStream_t s) {
     if (list_kind) *list_kind = ICQ_LIST_IDS;
     if (Q == 0) return ICQ_OK;
     zero_counts_kernel<<<(Q + 255) / 256, 256, 0, s>>>(cand_count, Q);
     if (ix->N == 0) return icq_check_launch();
 
     const int bpq_fill = (int)((cap + 255) / 256 < 32 ? (cap + 255) / 256 : 32);
-    if (icq_group_usable(ix, Q) && list_kind && cand_keys && !cand_part && ix->item_stride <= 16) {
-        // the caller only wants the final lists: finish the distances right here
-        *list_kind = ICQ_LIST_KEYS;
-        return icq_launch_group_keys(ix, lut, Q, thr, cand_keys, cand_count, cap, s);
+    if (icq_group_usable(ix, Q) && list_kind && !cand_part && ix->item_stride <= 16 &&
+        (cand_keys || (out_ids && icq_group_fused(ix, Q, topk)))) {
+        // the caller only wants the final lists: finish the distances (and, where one block
+        // owns a query, the lists) right here
+        *list_kind = out_ids && icq_group_fused(ix, Q, topk) ? ICQ_LIST_DONE : ICQ_LIST_KEYS;
+        return icq_launch_group_keys(ix, lut, Q, thr, cand_keys, cand_count, cap, topk, out_ids, out_dist, s);
     }
     if (icq_group_usable(ix, Q)) {
         // positions only when the caller can take them and needs no crude distances
@@ -672,5 +674,5 @@ ICQ_EXPORT int icq_scan_fast(const icq_index *ix, const float *lut, int Q, const
         return ICQ_ERR_WORKSPACE;
     float *lutT = reinterpret_cast<float *>(static_cast<char *>(workspace) + L.lutT_off);
     return icq_launch_scan(ix, lut, Q, thresholds, cand_ids, cand_part, nullptr, nullptr, nullptr,
-                           cand_count, cap, lutT, (hipStream_t)stream);
+                           cand_count, cap, lutT, 0, nullptr, nullptr, (hipStream_t)stream);
 }

@@ -14,8 +14,11 @@ icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool
     L.lutT_off = off;
     off = icq_align_up(off + sizeof(float) * tiles * 64 * (size_t)(ix->Kf <= 2 ? ix->Kf : 0) * ICQ_LUT_W,
                        ICQ_ALIGN);
+    // icq_search with the grouped stage 1 owning whole queries keeps the candidates on chip:
+    // no lists in the workspace at all
+    const bool on_chip = with_cands && icq_group_fused(ix, Q, topk);
     L.ids_off = off;
-    if (with_cands) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
+    if (with_cands && !on_chip) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
     L.rec_off = off;    // item records of the survivors (the fused path keeps no crude distances)
     if (with_cands && ix->item_stride <= 16 && !icq_group_usable(ix, Q))
         off = icq_align_up(off + (size_t)ix->item_stride * (size_t)Q * (size_t)cap, ICQ_ALIGN);
@@ -24,10 +27,12 @@ icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool
     L.splits = icq_refine_splits(ix, Q, cap, topk);
     L.keys_off = off;
     // slice lists [Q][splits][topk] (when sliced), then one 64-bit key per candidate [Q][cap]
-    if (L.splits > 1)
-        off = icq_align_up(off + sizeof(unsigned long long) * (size_t)Q * L.splits * topk, 8);
-    if (ix->item_stride <= 16)
-        off = icq_align_up(off + sizeof(unsigned long long) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
+    if (!on_chip) {
+        if (L.splits > 1)
+            off = icq_align_up(off + sizeof(unsigned long long) * (size_t)Q * L.splits * topk, 8);
+        if (ix->item_stride <= 16)
+            off = icq_align_up(off + sizeof(unsigned long long) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
+    }
     L.total = off;
     return L;
 }
@@ -36,8 +41,11 @@ ICQ_EXPORT int icq_workspace_bytes(const icq_index *ix, int Q, int64_t cap, int 
     if (!ix || !out || Q < 0 || Q > (1 << 22) || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK)
         return ICQ_ERR_ARG;
     if ((double)Q * (double)cap >= 1099511627776.0) return ICQ_ERR_ARG;
-    icq_ws_layout L = icq_layout(ix, Q, cap, topk, true, true);
-    *out = L.total > ICQ_ALIGN ? L.total : ICQ_ALIGN;
+    // the largest of what icq_search and the staged calls (which take lists from the caller) carve out
+    const size_t a = icq_layout(ix, Q, cap, topk, true, true).total;
+    const size_t b = icq_layout(ix, Q, cap, topk, false, false).total;
+    const size_t need = a > b ? a : b;
+    *out = need > ICQ_ALIGN ? need : ICQ_ALIGN;
     return ICQ_OK;
 }
 
@@ -86,10 +94,10 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
         uint32_t *rec = (ix->item_stride <= 16 && !icq_group_usable(ix, nq))
                             ? reinterpret_cast<uint32_t *>(ws + L.rec_off) : nullptr;
         int list_kind = ICQ_LIST_IDS;
-        unsigned long long *cand_keys =
-            (ix->item_stride <= 16 && topk <= 512) ? icq_cand_keys(keys, nq, L.splits, topk) : nullptr;
+        unsigned long long *cand_keys = (ix->item_stride <= 16 && topk <= 512 && !icq_group_fused(ix, nq, topk))
+                                            ? icq_cand_keys(keys, nq, L.splits, topk) : nullptr;
         rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, nullptr, rec, cand_keys, &list_kind, cnt,
-                             cap, lutT, s);
+                             cap, lutT, topk, out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
         if (rc != ICQ_OK) return rc;
         if (timed) ICQ_HIP_TRY(hipEventRecord(ev[2], s));
         rc = icq_launch_refine(ix, lut, nq, ids, nullptr, rec, list_kind, cnt, cap, topk, L.splits, keys,

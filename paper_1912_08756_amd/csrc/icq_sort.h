@@ -1,0 +1,68 @@
+// Register-resident sort of up to 1024 64-bit keys by one wavefront, and the key
+// helpers shared by the kernels that keep nearest-neighbour lists (Sec. 3.4 of
+// arxiv 1912.08756: the list of the nearest neighbours found so far).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef unsigned long long u64;
+constexpr u64 KEY_PAD = ~0ull;     // sorts behind every real key
+
+// Inverse of icq_order_bits.
+__device__ __forceinline__ float icq_unorder_bits(uint32_t u) {
+    return __uint_as_float((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
+}
+
+// Compare-exchange of the register pairs (r, r | M) of a lane: elements 64*M apart.
+template <int M>
+__device__ __forceinline__ void reg_exchange(u64 (&x)[16], int E, int k, int lane) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if ((r & M) == 0 && (r | M) < E) {
+            const bool up = (((r * 64 + lane) & k) == 0);
+            const u64 a = x[r], b = x[r | M];
+            const bool sw = (a > b) == up;
+            x[r] = sw ? b : a;
+            x[r | M] = sw ? a : b;
+        }
+    }
+}
+
+// Ascending bitonic sort of keys[0..len) by ONE wavefront, len a power of two, 64 <= len
+// <= 1024, entirely in registers: element e sits in register e/64 of lane e%64, so an
+// exchange at distance >= 64 pairs two registers of a lane and one at distance < 64 is
+// a shuffle; the len/64 elements of a lane are independent, which keeps the shuffles
+// pipelined.  keys[len..) is not touched; keys must hold len valid or padding entries.
+// No barrier inside: the caller orders the LDS traffic around the call.
+__device__ inline void wave_sort(u64 *keys, int len, int lane) {
+    const int E = len >> 6;
+    u64 x[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) x[r] = r < E ? keys[r * 64 + lane] : KEY_PAD;
+    for (int k = 2; k <= len; k <<= 1) {
+        for (int j = k >> 1; j >= 64; j >>= 1) {
+            switch (j >> 6) {
+                case 1: reg_exchange<1>(x, E, k, lane); break;
+                case 2: reg_exchange<2>(x, E, k, lane); break;
+                case 4: reg_exchange<4>(x, E, k, lane); break;
+                default: reg_exchange<8>(x, E, k, lane); break;
+            }
+        }
+        for (int j = (k >> 1) < 32 ? (k >> 1) : 32; j > 0; j >>= 1) {
+            const bool low = (lane & j) == 0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                if (r < E) {
+                    const u64 y = __shfl_xor(x[r], j, 64);
+                    const bool up = (((r * 64 + lane) & k) == 0);
+                    const bool take_min = up == low;
+                    x[r] = take_min ? (x[r] < y ? x[r] : y) : (x[r] > y ? x[r] : y);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        if (r < E) keys[r * 64 + lane] = x[r];
+}
+
