@@ -191,7 +191,6 @@ __global__ __launch_bounds__(GS_THREADS) void group_scan_kernel(
 // ---- grouped stage 1 fused with stage 2
 constexpr int GD_HITS = 1024;     // tuples below the threshold handled per pass
 constexpr int GD_PER = GD_HITS / GS_THREADS;
-constexpr int GD_LINEAR = 12;     // up to this many tuple boundaries in a row of 64 survivors: count them one by one
 constexpr int GD_ROWS = 4;        // rows of 64 survivors per wavefront and step
 constexpr int GD_STEP = GD_ROWS * GS_THREADS;            // most keys one step can add to the list
 constexpr int GD_LIST = 2048;     // keys of the block's nearest-neighbour list
@@ -206,6 +205,7 @@ struct GdShared {
     uint32_t wred[GS_THREADS / 64][2];
     uint32_t wtot[2][GS_THREADS / 64];
     uint32_t wsum[GS_THREADS / 64][2];
+    uint32_t flag[GS_THREADS / 64][64];    // locate(): stamps of the tuple starts inside a row of survivors
     uint32_t base;
 };
 
@@ -434,6 +434,9 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8
     unsigned long long *my_out = FUSED ? nullptr : keys_out + (int64_t)q * cap;
 
     for (int i = tid; i < 4 * WORDS * ICQ_LUT_W; i += GS_THREADS) T[i] = i < K * ICQ_LUT_W ? Tq[i] : 0.0f;
+    uint32_t *flag = sh.flag[wave];
+    flag[lane] = 0;
+    uint32_t stamp = 0;                        // wavefront-uniform, never 0 when compared
 
     // ---- one bit per (row, column): same additions as the item-by-item scan, lut[0][c0] (+ lut[1][c1])
     const int row_begin = KF == 2 ? blockIdx.x * rows_per_block : 0;
@@ -544,31 +547,24 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8
             const uint32_t c2 = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lane < 32 && i2 < nhc && v2 <= p));
             ha = b0 + c2 - 1;
         }
-        // grouped position of this lane's survivor in row `row` (< rend); moves ha to the tuple of the next row
+        // Grouped position of this lane's survivor in row `row` (< rend); moves ha to the tuple of
+        // the next row.  Tuple ha holds the row's first survivor; every later tuple that starts
+        // inside the row raises a flag at the lane of its first survivor (a stamp in the
+        // wavefront's 64 LDS words, unique per call, so nothing has to be cleared), and a lane's
+        // tuple is ha + the number of flags at or below it.
         auto locate = [&](uint32_t row) -> uint32_t {
-            const uint32_t pl = row * 64 + 63 < tot ? row * 64 + 63 : tot - 1;
-            uint32_t p = row * 64 + lane;
-            p = p < pl ? p : pl;
+            const uint32_t pf = row * 64;
+            const uint32_t pl = pf + 63 < tot ? pf + 63 : tot - 1;
+            const uint32_t p = pf + lane < pl ? pf + lane : pl;
             const uint32_t bi = ha + 1 + lane;
-            const uint32_t bnd = hx[bi < nhc ? bi : nhc];      // prefixes of the tuples after ha
-            const uint32_t nb = __builtin_popcountll(__builtin_amdgcn_ballot_w64(bnd <= pl));
-            uint32_t h = ha;
-            if (nb <= (uint32_t)GD_LINEAR) {
-                for (uint32_t j = 0; j < nb; ++j)
-                    h += p >= (uint32_t)__builtin_amdgcn_readlane((int)bnd, (int)j) ? 1u : 0u;
-            } else {
-                uint32_t lo = ha, hi = ha + nb;                 // hx[lo] <= p, answer in [lo, hi]
-                while (__builtin_amdgcn_ballot_w64(lo < hi) != 0) {
-                    const uint32_t mid = (lo + hi + 1) >> 1;
-                    const bool le = hx[mid] <= p;
-                    if (lo < hi) {
-                        if (le) lo = mid; else hi = mid - 1;
-                    }
-                }
-                h = lo;
-            }
+            const uint32_t bnd = hx[bi < nhc ? bi : nhc];      // prefixes of the tuples after ha (hx[nhc] = tot > pl)
+            ++stamp;
+            if (bnd <= pl) flag[bnd - pf] = stamp;              // pf < bnd: tuple ha holds pf
+            __builtin_amdgcn_wave_barrier();                    // LDS runs a wavefront's accesses in order
+            const uint64_t marks = __builtin_amdgcn_ballot_w64(flag[lane] == stamp);
+            const uint32_t h = ha + (uint32_t)__builtin_popcountll(marks & ((2ull << lane) - 1ull));
             const uint32_t pos = hbuf[h] + (p - hx[h]);
-            ha += __builtin_popcountll(__builtin_amdgcn_ballot_w64(bnd <= pl + 1 && bi < nhc));
+            ha += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(bnd <= pl + 1 && bi < nhc));
             return pos;
         };
         // records (and, for the key list, ids) of rows r .. r + GD_ROWS - 1; rows past rend read record 0, unused
@@ -603,11 +599,12 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8
             bool take[GD_ROWS];
 #pragma unroll
             for (int u = 0; u < GD_ROWS; ++u) {
-                float d = 0.0f;
+                // k ascending like every other kernel; the first term stands for 0 + itself (no table holds -0)
+                float d = T[cur[u][0] & 0xffu];
 #pragma unroll
                 for (int w = 0; w < WORDS; ++w) {
 #pragma unroll
-                    for (int b = 0; b < 4; ++b)
+                    for (int b = w == 0 ? 1 : 0; b < 4; ++b)
                         d += T[(w * 4 + b) * ICQ_LUT_W + ((cur[u][w] >> (8 * b)) & 0xffu)];
                 }
                 const uint32_t ob = icq_order_bits(d);
