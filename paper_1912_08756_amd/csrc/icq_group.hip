@@ -198,6 +198,7 @@ constexpr int GD_LPT = GD_LIST / GS_THREADS;             // list entries per thr
 constexpr int GD_SORT = 1024;     // most keys the final register sort takes
 static_assert(GD_HITS <= 2048 && GD_HITS % GS_THREADS == 0, "tuple search covers 64 x 32 entries");
 static_assert(GS_THREADS == 256, "one histogram bin per thread");
+static_assert(GD_ROWS % 2 == 0, "a step is two half steps");
 static_assert(GD_LIST - GD_STEP >= 2 * 512, "room for topk <= 512 plus ties between two cuts");
 
 struct GdShared {
@@ -567,10 +568,11 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8
             ha += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(bnd <= pl + 1 && bi < nhc));
             return pos;
         };
-        // records (and, for the key list, ids) of rows r .. r + GD_ROWS - 1; rows past rend read record 0, unused
+        // records (and, for the key list, ids) of rows r, r + 1; rows past rend read record 0, unused
+        constexpr int HALF = GD_ROWS / 2;
         auto fetch = [&](uint32_t r, uint32_t (*rec)[WORDS], uint32_t *low) {
 #pragma unroll
-            for (int u = 0; u < GD_ROWS; ++u) {
+            for (int u = 0; u < HALF; ++u) {
                 uint32_t pos = 0;
                 if (r + u < rend) pos = locate(r + u);          // wavefront-uniform
                 const uint32_t *p = reinterpret_cast<const uint32_t *>(items_grouped + (size_t)pos * (WORDS * 4));
@@ -590,34 +592,43 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8
                 low[u] = FUSED ? pos : perm[pos];
             }
         };
-        uint32_t cur[GD_ROWS][WORDS], nxt[GD_ROWS][WORDS], cur_low[GD_ROWS], nxt_low[GD_ROWS];
-        fetch(r0, cur, cur_low);
-        for (uint32_t it = 0; it < steps; ++it) {
-            const uint32_t r = r0 + it * GD_ROWS;
-            fetch(r + GD_ROWS, nxt, nxt_low);
-            unsigned long long key[GD_ROWS];
-            bool take[GD_ROWS];
+        unsigned long long key[GD_ROWS];
+        bool take[GD_ROWS];
+        // distances and keys of rows r, r + 1 from their records
+        auto finish = [&](uint32_t r, const uint32_t (*rec)[WORDS], const uint32_t *low, int slot0) {
 #pragma unroll
-            for (int u = 0; u < GD_ROWS; ++u) {
+            for (int u = 0; u < HALF; ++u) {
                 // k ascending like every other kernel; the first term stands for 0 + itself (no table holds -0)
-                float d = T[cur[u][0] & 0xffu];
+                float d = T[rec[u][0] & 0xffu];
 #pragma unroll
                 for (int w = 0; w < WORDS; ++w) {
 #pragma unroll
                     for (int b = w == 0 ? 1 : 0; b < 4; ++b)
-                        d += T[(w * 4 + b) * ICQ_LUT_W + ((cur[u][w] >> (8 * b)) & 0xffu)];
+                        d += T[(w * 4 + b) * ICQ_LUT_W + ((rec[u][w] >> (8 * b)) & 0xffu)];
                 }
                 const uint32_t ob = icq_order_bits(d);
                 const uint32_t num = (r + u) * 64 + lane;
-                key[u] = ((unsigned long long)ob << 32) | cur_low[u];
-                take[u] = r + u < rend && num < tot;
+                key[slot0 + u] = ((unsigned long long)ob << 32) | low[u];
+                take[slot0 + u] = r + u < rend && num < tot;
                 if (FUSED) {
-                    take[u] = take[u] && ob <= bound;
+                    take[slot0 + u] = take[slot0 + u] && ob <= bound;
                 } else {
                     const uint64_t slot = (uint64_t)base + num;
-                    if (take[u] && slot < (uint64_t)cap) my_out[slot] = key[u];
+                    if (take[slot0 + u] && slot < (uint64_t)cap) my_out[slot] = key[slot0 + u];
                 }
             }
+        };
+        // Two half steps in flight: the records of one half are fetched while the other half's
+        // distances are formed, each into registers of its own (no copies, so no wait on the
+        // loads that were just sent).
+        uint32_t recA[HALF][WORDS], recB[HALF][WORDS], lowA[HALF], lowB[HALF];
+        fetch(r0, recA, lowA);
+        for (uint32_t it = 0; it < steps; ++it) {
+            const uint32_t r = r0 + it * GD_ROWS;
+            fetch(r + HALF, recB, lowB);
+            finish(r, recA, lowA, 0);
+            fetch(r + GD_ROWS, recA, lowA);
+            finish(r + HALF, recB, lowB, HALF);
             if (FUSED) {
                 uint64_t mk[GD_ROWS];
                 uint32_t pre[GD_ROWS], mycnt = 0;
@@ -647,12 +658,6 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8
                     else cnt = block_tie_cut(sh, list, cnt, (uint32_t)topk, bound, perm, tid, lane, wave);
                 }
             }
-#pragma unroll
-            for (int u = 0; u < GD_ROWS; ++u) {
-#pragma unroll
-                for (int w = 0; w < WORDS; ++w) cur[u][w] = nxt[u][w];
-                cur_low[u] = nxt_low[u];
-            }
         }
         __syncthreads();                       // hbuf / hx are rewritten by the next pass
     }
@@ -665,6 +670,32 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8
         if (cnt > (uint32_t)GD_SORT) cnt = block_tie_cut(sh, list, cnt, (uint32_t)topk, bound, perm, tid, lane, wave);
     }
     __syncthreads();
+    uint32_t *oi = out_ids + (int64_t)q * topk;
+    float *od = out_dist + (int64_t)q * topk;
+    const int kept = (int)cnt < topk ? (int)cnt : topk;
+    if (cnt <= (uint32_t)GS_THREADS) {
+        // one key per thread: its rank among the (distinct) keys is its row
+        unsigned long long mine_k = KEY_PAD;
+        if (tid < (int)cnt) {
+            const unsigned long long k = list[tid];
+            mine_k = (k & 0xFFFFFFFF00000000ull) | perm[(uint32_t)k];
+        }
+        __syncthreads();
+        if (tid < (int)cnt) list[tid] = mine_k;
+        __syncthreads();
+        uint32_t rank = 0;
+        for (uint32_t j = 0; j < cnt; ++j) rank += list[j] < mine_k ? 1u : 0u;
+        if (tid < (int)cnt && rank < (uint32_t)topk) {
+            oi[rank] = (uint32_t)mine_k;
+            od[rank] = icq_unorder_bits((uint32_t)(mine_k >> 32));
+        }
+        for (int r = kept + tid; r < topk; r += GS_THREADS) {
+            oi[r] = ICQ_PAD_ID;
+            od[r] = INFINITY;
+        }
+        return;
+    }
+    // many equal distances at the cut: bitonic sort of up to GD_SORT keys by one wavefront
     int len = 64;
     while (len < (int)cnt) len <<= 1;
     for (int i = tid; i < len; i += GS_THREADS) {
@@ -678,9 +709,6 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8
     __syncthreads();
     if (wave == 0) wave_sort(list, len, (int)lane);
     __syncthreads();
-    const int kept = (int)cnt < topk ? (int)cnt : topk;
-    uint32_t *oi = out_ids + (int64_t)q * topk;
-    float *od = out_dist + (int64_t)q * topk;
     for (int r = tid; r < topk; r += GS_THREADS) {
         oi[r] = r < kept ? (uint32_t)list[r] : ICQ_PAD_ID;
         od[r] = r < kept ? icq_unorder_bits((uint32_t)(list[r] >> 32)) : INFINITY;
