@@ -70,11 +70,16 @@ def check_topk(P_q, D_q, t, topk, out_ids, out_dist):
     assert nv >= min(topk, sure.size), "too few results"
     assert nv <= min(topk, maybe.size)
     if sure.size >= topk:
-        Dk = np.partition(D_q[sure], topk - 1)[topk - 1]   # k-th distance among sure survivors
-        need = sure[D_q[sure] < Dk - tol(Dk)]
+        # Items in the threshold band may or may not survive, and one that does can push a
+        # certain survivor out of the list.  So: nothing returned may be farther than the
+        # k-th distance with no band item surviving, and every certain survivor closer than
+        # the k-th distance with ALL band items surviving must be there.
+        Dk = np.partition(D_q[sure], topk - 1)[topk - 1]
+        assert (D_q[ids] <= Dk + tol(Dk)).all(), "returned id farther than the k-th distance"
+        Dk_all = np.partition(D_q[maybe], topk - 1)[topk - 1]
+        need = sure[D_q[sure] < Dk_all - tol(Dk_all)]
         missing = np.setdiff1d(need, ids)
         assert missing.size == 0, "clearly-closer survivor missing: %s" % missing[:8]
-        assert (D_q[ids] <= Dk + tol(Dk)).all(), "returned id farther than the k-th distance"
     else:
         missing = np.setdiff1d(sure, ids)
         assert missing.size == 0, "survivor missing from a short result"

@@ -235,6 +235,26 @@ def test_refine_matches_oracle(gpu, name, N, Q, over, rule, topk):
 
 
 # ------------------------------------------------------------------ whole path
+def _check_search(g, cfg, T, P, D, thr, topk, cap):
+    out_ids, out_dist, surv = g.search(thr, cap, topk)
+    o_ids, o_dist, o_cnt = orc.search(T, cfg["codes"], cfg["Kf"], thr, topk)
+    n_equal = n_eligible = 0
+    for q in range(g.Q):
+        if np.isnan(thr[q]):
+            assert surv[q] == 0 and (out_ids[q] == 0xFFFFFFFF).all() and np.isinf(out_dist[q]).all()
+            continue
+        band = np.nonzero((P[q] >= thr[q] - tol(thr[q])) & (P[q] <= thr[q] + tol(thr[q])))[0] \
+            if np.isfinite(thr[q]) else np.zeros(0, dtype=np.int64)
+        assert abs(int(surv[q]) - int(o_cnt[q])) <= band.size
+        check_topk(P[q], D[q], thr[q], topk, out_ids[q], out_dist[q])
+        if not (np.isin(o_ids[q], band).any() or np.isin(out_ids[q], band).any()):
+            n_eligible += 1
+            n_equal += np.array_equal(out_ids[q], o_ids[q])
+    # where no threshold-band item reaches the list, the lists are identical up to near-ties
+    assert n_equal >= 0.9 * n_eligible
+    return out_ids, out_dist, surv
+
+
 @pytest.mark.parametrize("name,N,Q,over,rule", [
     ("C0", None, None, {}, ("kth", 20, 1.5)),             # the tiny config, complete
     ("C1", 200_003, 130, {}, ("q", 0.01)),
@@ -253,21 +273,36 @@ def test_search_matches_oracle(gpu, name, N, Q, over, rule, mode):
     g = Gpu(gpu, cfg, mode)
     T, P, D = oracle_all(cfg)
     thr = _thr(P, rule)
-    topk = cfg["topk"]
     exact = (P < thr[:, None].astype(np.float64)).sum(axis=1)
-    cap = int(exact.max() * 1.2) + 64
-    out_ids, out_dist, surv = g.search(thr, cap, topk)
-    o_ids, o_dist, o_cnt = orc.search(T, cfg["codes"], cfg["Kf"], thr, topk)
-    n_equal = n_eligible = 0
-    for q in range(g.Q):
-        band = np.nonzero((P[q] >= thr[q] - tol(thr[q])) & (P[q] <= thr[q] + tol(thr[q])))[0]
-        assert abs(int(surv[q]) - int(o_cnt[q])) <= band.size
-        check_topk(P[q], D[q], thr[q], topk, out_ids[q], out_dist[q])
-        if not (np.isin(o_ids[q], band).any() or np.isin(out_ids[q], band).any()):
-            n_eligible += 1
-            n_equal += np.array_equal(out_ids[q], o_ids[q])
-    # where no threshold-band item reaches the list, the lists are identical up to near-ties
-    assert n_equal >= 0.9 * n_eligible
+    _check_search(g, cfg, T, P, D, thr, cfg["topk"], int(exact.max() * 1.2) + 64)
+
+
+# With 512 queries or more a block of the grouped kernel owns its query and keeps the
+# nearest-neighbour list on chip (no candidate list in memory): the cases below run that form.
+@pytest.mark.parametrize("name,N,Q,over,rule,topk", [
+    ("C1", 70_000, 600, {}, ("q", 0.01), 100),              # about one item per fast-code tuple
+    ("C1", 40_000, 512, {}, ("q", 0.02), 128),              # fewer items than tuples; longest on-chip list
+    ("C0", 70_000, 520, {}, ("q", 0.02), 10),               # Kf = 1: 256 tuples of ~270 items, 4-byte records
+    ("C3", 150_000, 512, {}, ("q", 0.01), 100),             # clustered codes: a few huge tuples, bursts
+    ("C2", 60_000, 512, dict(d=32, Kf=2), ("q", 0.01), 100),  # K = 16: 16-byte records
+    ("C1", 60_000, 512, {}, ("q", 0.25), 100),              # many surviving tuples: several passes per query
+    ("C1", 3_000, 512, {}, ("kth", 3, 1.0), 100),           # fewer survivors than topk
+])
+def test_search_with_lists_kept_on_chip(gpu, name, N, Q, over, rule, topk):
+    cfg = small(name, N, Q, **over)
+    g = Gpu(gpu, cfg, 2)
+    T, P, D = oracle_all(cfg)
+    thr = _thr(P, rule)
+    thr[5] = np.inf
+    thr[11] = np.nan
+    ids2, dist2, surv2 = _check_search(g, cfg, T, P, D, thr, topk, N)
+    # the item-by-item form and the form that writes the candidates' keys out (one more result
+    # than the on-chip lists serve) agree to the bit
+    ids1, dist1, surv1 = Gpu(gpu, cfg, 1).search(thr, N, topk)
+    assert np.array_equal(surv2, surv1) and np.array_equal(ids2, ids1) and np.array_equal(dist2, dist1)
+    ids3, dist3, surv3 = g.search(thr, N, 129)
+    short = (ids3[:, :topk] != ids2).any(axis=1)
+    assert np.array_equal(surv3, surv2) and not short.any()
 
 
 def test_search_infinite_threshold_is_exhaustive_adc(gpu):
@@ -307,6 +342,30 @@ def test_search_grouped_with_many_surviving_tuples(gpu):
     g1 = Gpu(gpu, cfg, 1)
     ids1, dist1, surv1 = g1.search(thr, N, topk)
     assert np.array_equal(surv, surv1) and np.array_equal(out_ids, ids1) and np.array_equal(out_dist, dist1)
+
+
+@pytest.mark.parametrize("mode", [1, 2], ids=["streamed", "grouped"])
+def test_search_with_masses_of_equal_distances(gpu, mode):
+    """Items drawn from 8 code patterns only: thousands of exactly equal distances, so the
+    lists are decided by the item ids alone (order (distance, id)) and every cut of a
+    running list meets far more ties than it can hold."""
+    Q = 12 if mode == 1 else 520                            # 520: the grouped kernel keeps the lists on chip
+    cfg = small("C1", 40_000, Q)
+    rng = np.random.default_rng(5)
+    patterns = rng.integers(0, 256, size=(cfg["K"], 8), dtype=np.uint8)
+    cfg["codes"] = np.ascontiguousarray(patterns[:, rng.integers(0, 8, size=40_000)])
+    g = Gpu(gpu, cfg, mode)
+    T, P, D = oracle_all(cfg)
+    thr = np.full(Q, np.inf, dtype=np.float32)
+    for q in range(6, Q):                                   # let the 5 nearest patterns (by crude distance) through
+        u = np.unique(P[q])
+        thr[q] = np.float32(0.5 * (u[4] + u[5])) if u.size > 5 else np.inf
+    topk = 100
+    out_ids, out_dist, surv = g.search(thr, 40_000, topk)
+    o_ids, o_dist, o_cnt = orc.search(T, cfg["codes"], cfg["Kf"], thr, topk)
+    assert np.array_equal(surv, o_cnt)
+    assert np.array_equal(out_ids, o_ids)
+    assert np.allclose(out_dist, o_dist, rtol=1e-4, atol=1e-4)
 
 
 def test_stage_timing_records_the_search_calls(gpu):
