@@ -240,43 +240,49 @@ __global__ __launch_bounds__(256) void fill_partials_kernel(
 // sub-codes.  The B values of an entry are adjacent, so one 32/64-bit read
 // serves all B queries.
 // Survivors: a lane collects the hit bits of its 16 items; a wavefront compacts
-// them with ballots into a block-wide LDS list (one LDS atomic per round), and
-// the block moves the list to the query's global list with ONE global atomic
-// per flush -- all blocks add to the same counter, and that address only takes
-// a few million atomics per second.  If a burst does not fit the LDS list the
-// wavefront writes straight to the global list instead.
+// them with ballots into its OWN slice of an LDS staging list (its count lives in
+// a scalar register: no atomics, nothing to wait for), and every SS_CHECK steps
+// the block looks at the 16 counts; when a slice is half full the block moves all
+// slices to the query's global list with ONE global atomic -- all blocks add to
+// the same counter, and that address only takes ~10^8 atomics per second.  A
+// slice that fills up between two checks is moved out by its wavefront alone.
+// The code stream is read one step ahead into a second set of registers (two
+// copies of the step body, no register moves), with loads that are never
+// conditional: the rows are padded by more than one block step, so reading past
+// the block's range is harmless, and the compiler can leave the newer loads in
+// flight while the older ones are consumed.
 constexpr int SS_HALF = 8;        // items per lane whose table reads are issued together
 constexpr int SS_CHECK = 8;       // steps between block-wide flush checks
-constexpr uint32_t SS_NONE = 0xFFFFFFFFu;
+constexpr int SS_THREADS = 1024;
+constexpr int SS_WAVES = SS_THREADS / 64;
 
 template <int KF, int B>
-__global__ __launch_bounds__(1024) void scan_stream_kernel(
+__global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     const uint8_t *__restrict__ fast, int64_t Npad, uint32_t N, const float *__restrict__ lut, int K,
     const float *__restrict__ thr, int Q, uint32_t *__restrict__ cand_ids,
-    uint32_t *__restrict__ cand_count, int64_t cap, uint32_t items_per_block, uint32_t stage_cap) {
+    uint32_t *__restrict__ cand_count, int64_t cap, uint32_t items_per_block, uint32_t wave_cap) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
-    __shared__ uint32_t s_cnt[B], s_valid[B], s_base[B];
+    __shared__ uint32_t s_wcnt[B][SS_WAVES], s_base[B];
     constexpr int TAB_FLOATS = KF * ICQ_LUT_W * 16 * B;
     const int tid = threadIdx.x;
     const uint32_t lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nwaves = blockDim.x >> 6;
     const int qbase = blockIdx.y * B;
 
-    for (int i = tid; i < KF * ICQ_LUT_W * B; i += blockDim.x) {
+    for (int i = tid; i < KF * ICQ_LUT_W * B; i += SS_THREADS) {
         const int b = i / (KF * ICQ_LUT_W), e = i % (KF * ICQ_LUT_W);
         const float v = (qbase + b) < Q ? lut[(int64_t)(qbase + b) * K * ICQ_LUT_W + e] : INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) smem[(e * 16 + r) * B + b] = v;
     }
-    if (tid < B) {
-        s_cnt[tid] = 0;
-        s_valid[tid] = SS_NONE;
-    }
     float t[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) t[b] = (qbase + b) < Q ? thr[qbase + b] : -INFINITY;
-    uint32_t *stage = reinterpret_cast<uint32_t *>(smem + TAB_FLOATS);   // [B][stage_cap]
+    // staging: [B][SS_WAVES][wave_cap] ids
+    uint32_t *stage = reinterpret_cast<uint32_t *>(smem + TAB_FLOATS);
+    uint32_t wc[B];               // ids staged by this wavefront (wavefront-uniform)
+#pragma unroll
+    for (int b = 0; b < B; ++b) wc[b] = 0;
     __syncthreads();
 
     const uint32_t begin = blockIdx.x * items_per_block;
@@ -286,146 +292,157 @@ __global__ __launch_bounds__(1024) void scan_stream_kernel(
     constexpr int ENTRY_SHIFT = B == 1 ? 6 : B == 2 ? 7 : 8;
     const uint32_t copy_off = (lane & 15) * (4 * B);
     const char *tab_bytes = reinterpret_cast<const char *>(smem);
-    const uint32_t step = (uint32_t)nwaves * 1024u;
+    constexpr uint32_t step = (uint32_t)SS_WAVES * 1024u;
     const uint32_t nsteps = end > begin ? (end - begin + step - 1) / step : 0;   // same for every wavefront
 
-    uint4 w[KF], wn[KF];
-    uint32_t g = begin + wave * 1024u;
-    if (g < end) {
+    // 1024 items at g into w; past the block's range the block's first items are read instead
+    // (unused, but in bounds: g < end <= N and the rows are padded by more than 1024 bytes)
+    auto load = [&](uint32_t g, uint4 (&w)[KF]) {
+        const uint32_t gs = (g < end && g >= begin) ? g : begin;
 #pragma unroll
         for (int k = 0; k < KF; ++k)
-            w[k] = *reinterpret_cast<const uint4 *>(fast + (int64_t)k * Npad + g + lane * 16);
-    }
-    for (uint32_t it = 0; it < nsteps; ++it, g += step) {
-        if (g < end) {
-            const uint32_t gn = g + step;
-            if (gn < end) {   // read ahead; rows are padded so a whole step is always addressable
+            w[k] = *reinterpret_cast<const uint4 *>(fast + (int64_t)k * Npad + gs + lane * 16);
+    };
+    // the 1024 items at g held in w: table sums, hit bits, staging
+    auto process = [&](uint32_t g, const uint4 (&w)[KF]) {
+        const uint32_t id0 = g + lane * 16;
+        uint32_t hm[B];   // hit bits of this lane's 16 items, one mask per query
 #pragma unroll
-                for (int k = 0; k < KF; ++k)
-                    wn[k] = *reinterpret_cast<const uint4 *>(fast + (int64_t)k * Npad + gn + lane * 16);
+        for (int b = 0; b < B; ++b) hm[b] = 0;
+#pragma unroll
+        for (int h = 0; h < 16; h += SS_HALF) {
+            // phase 1: every table address of the half step
+            uint32_t off[SS_HALF][KF];
+#pragma unroll
+            for (int jj = 0; jj < SS_HALF; ++jj) {
+                const int j = h + jj;
+#pragma unroll
+                for (int k = 0; k < KF; ++k) {
+                    const uint32_t word = j < 4 ? w[k].x : j < 8 ? w[k].y : j < 12 ? w[k].z : w[k].w;
+                    const int sh = 8 * (j & 3) - ENTRY_SHIFT;   // code byte -> entry offset
+                    const uint32_t pos = sh >= 0 ? (word >> (sh >= 0 ? sh : 0)) : (word << (sh < 0 ? -sh : 0));
+                    off[jj][k] = (pos & (0xffu << ENTRY_SHIFT)) | copy_off;
+                }
             }
-            const uint32_t id0 = g + lane * 16;
-            uint32_t hm[B];   // hit bits of this lane's 16 items, one mask per query
+            __builtin_amdgcn_sched_barrier(0);
+            // phase 2: all reads in flight together
+            float v[SS_HALF][KF][B];
 #pragma unroll
-            for (int b = 0; b < B; ++b) hm[b] = 0;
+            for (int jj = 0; jj < SS_HALF; ++jj) {
 #pragma unroll
-            for (int h = 0; h < 16; h += SS_HALF) {
-                // phase 1: every table address of the half step
-                uint32_t off[SS_HALF][KF];
-#pragma unroll
-                for (int jj = 0; jj < SS_HALF; ++jj) {
-                    const int j = h + jj;
-#pragma unroll
-                    for (int k = 0; k < KF; ++k) {
-                        const uint32_t word = j < 4 ? w[k].x : j < 8 ? w[k].y : j < 12 ? w[k].z : w[k].w;
-                        const int sh = 8 * (j & 3) - ENTRY_SHIFT;   // code byte -> entry offset
-                        const uint32_t pos = sh >= 0 ? (word >> (sh >= 0 ? sh : 0)) : (word << (sh < 0 ? -sh : 0));
-                        off[jj][k] = (pos & (0xffu << ENTRY_SHIFT)) | copy_off;
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                // phase 2: all reads in flight together
-                float v[SS_HALF][KF][B];
-#pragma unroll
-                for (int jj = 0; jj < SS_HALF; ++jj) {
-#pragma unroll
-                    for (int k = 0; k < KF; ++k) {
-                        const char *e = tab_bytes + k * (ICQ_LUT_W * 64 * B) + off[jj][k];
-                        if (B == 1) {
-                            v[jj][k][0] = *reinterpret_cast<const float *>(e);
-                        } else if (B == 2) {
-                            const float2 x = *reinterpret_cast<const float2 *>(e);
-                            v[jj][k][0] = x.x;
-                            v[jj][k][1 % B] = x.y;
-                        } else {
-                            const float4 x = *reinterpret_cast<const float4 *>(e);
-                            v[jj][k][0] = x.x;
-                            v[jj][k][1 % B] = x.y;
-                            v[jj][k][2 % B] = x.z;
-                            v[jj][k][3 % B] = x.w;
-                        }
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                // phase 3: sums (k ascending) and hit bits
-#pragma unroll
-                for (int jj = 0; jj < SS_HALF; ++jj) {
-#pragma unroll
-                    for (int b = 0; b < B; ++b) {
-                        float P = v[jj][0][b];
-#pragma unroll
-                        for (int k = 1; k < KF; ++k) P += v[jj][k][b];
-                        hm[b] |= (P < t[b]) ? (1u << (h + jj)) : 0u;
+                for (int k = 0; k < KF; ++k) {
+                    const char *e = tab_bytes + k * (ICQ_LUT_W * 64 * B) + off[jj][k];
+                    if (B == 1) {
+                        v[jj][k][0] = *reinterpret_cast<const float *>(e);
+                    } else if (B == 2) {
+                        const float2 x = *reinterpret_cast<const float2 *>(e);
+                        v[jj][k][0] = x.x;
+                        v[jj][k][1 % B] = x.y;
+                    } else {
+                        const float4 x = *reinterpret_cast<const float4 *>(e);
+                        v[jj][k][0] = x.x;
+                        v[jj][k][1 % B] = x.y;
+                        v[jj][k][2 % B] = x.z;
+                        v[jj][k][3 % B] = x.w;
                     }
                 }
             }
-            if (id0 + 16 > end) {   // ragged tail: drop bits of items at or beyond `end`
-                const uint32_t valid = id0 < end ? (1u << (end - id0)) - 1u : 0u;
+            __builtin_amdgcn_sched_barrier(0);
+            // phase 3: sums (k ascending) and hit bits
 #pragma unroll
-                for (int b = 0; b < B; ++b) hm[b] &= valid;
-            }
-            // compaction: each round appends every lane's lowest remaining hit
-#pragma unroll
-            for (int b = 0; b < B; ++b) {
-                uint64_t mask = __builtin_amdgcn_ballot_w64(hm[b] != 0);
-                while (mask != 0) {
-                    const uint32_t n = (uint32_t)__builtin_popcountll(mask);
-                    const int leader = __builtin_ctzll(mask);
-                    uint32_t old = 0;
-                    if ((int)lane == leader) old = atomicAdd(&s_cnt[b], n);
-                    old = __builtin_amdgcn_readlane(old, leader);
-                    const uint32_t mine = old + __builtin_popcountll(mask & ((1ull << lane) - 1));
-                    if (old + n <= stage_cap) {
-                        if (hm[b] != 0) stage[b * stage_cap + mine] = id0 + (uint32_t)__builtin_ctz(hm[b]);
-                    } else {   // burst: straight to the global list
-                        uint32_t gb = 0;
-                        if ((int)lane == leader) {
-                            atomicMin(&s_valid[b], old);
-                            gb = atomicAdd(&cand_count[qbase + b], n);
-                        }
-                        gb = __builtin_amdgcn_readlane(gb, leader);
-                        const uint64_t slot = (uint64_t)gb + (mine - old);
-                        if (hm[b] != 0 && slot < (uint64_t)cap)
-                            cand_ids[(int64_t)(qbase + b) * cap + slot] = id0 + (uint32_t)__builtin_ctz(hm[b]);
-                    }
-                    hm[b] &= hm[b] - 1;
-                    mask = __builtin_amdgcn_ballot_w64(hm[b] != 0);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < KF; ++k) w[k] = wn[k];
-        }
-        // block-wide flush check (every wavefront takes the same path: nsteps is block-uniform)
-        if ((it % SS_CHECK) == SS_CHECK - 1 || it == nsteps - 1) {
-            __syncthreads();
-            uint32_t nb[B];
-            bool any = false;
-#pragma unroll
-            for (int b = 0; b < B; ++b) {
-                const uint32_t c = s_cnt[b], vld = s_valid[b];
-                nb[b] = c < vld ? c : vld;      // entries below the first burst are staged
-                if (nb[b] > stage_cap) nb[b] = stage_cap;
-                any |= (c > stage_cap / 2) || (it == nsteps - 1 && c > 0);
-            }
-            __syncthreads();   // nobody appends again before every thread has read the counters
-            if (any) {   // uniform: everyone read the same counters between the two barriers
-                if (tid < B) s_base[tid] = nb[tid] ? atomicAdd(&cand_count[qbase + tid], nb[tid]) : 0;
-                __syncthreads();
+            for (int jj = 0; jj < SS_HALF; ++jj) {
 #pragma unroll
                 for (int b = 0; b < B; ++b) {
-                    const uint32_t base = s_base[b];
-                    uint32_t *dst = cand_ids + (int64_t)(qbase + b) * cap;
-                    for (uint32_t i = tid; i < nb[b]; i += blockDim.x) {
-                        const uint64_t slot = (uint64_t)base + i;
-                        if (slot < (uint64_t)cap) dst[slot] = stage[b * stage_cap + i];
-                    }
+                    float P = v[jj][0][b];
+#pragma unroll
+                    for (int k = 1; k < KF; ++k) P += v[jj][k][b];
+                    hm[b] |= (P < t[b]) ? (1u << (h + jj)) : 0u;
                 }
-                if (tid < B) {
-                    s_cnt[tid] = 0;
-                    s_valid[tid] = SS_NONE;
-                }
-                __syncthreads();
             }
+        }
+        if (id0 + 16 > end || id0 + 16 < id0) {   // ragged tail: drop bits of items at or beyond `end`
+            const uint32_t valid = id0 < end ? (1u << (end - id0)) - 1u : 0u;
+#pragma unroll
+            for (int b = 0; b < B; ++b) hm[b] &= valid;
+        }
+        // compaction: each round appends every lane's lowest remaining hit
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            uint32_t *mine_stage = stage + ((uint32_t)b * SS_WAVES + wave) * wave_cap;
+            uint64_t mask = __builtin_amdgcn_ballot_w64(hm[b] != 0);
+            while (mask != 0) {
+                const uint32_t n = (uint32_t)__builtin_popcountll(mask);
+                const uint32_t rank = (uint32_t)__builtin_popcountll(mask & ((1ull << lane) - 1));
+                if (wc[b] + n > wave_cap) {   // slice full between two checks: the wavefront moves it out itself
+                    uint32_t gb = 0;
+                    if (lane == 0) gb = atomicAdd(&cand_count[qbase + b], wc[b]);
+                    gb = (uint32_t)__builtin_amdgcn_readfirstlane((int)gb);
+                    uint32_t *dst = cand_ids + (int64_t)(qbase + b) * cap;
+                    for (uint32_t i = lane; i < wc[b]; i += 64) {
+                        const uint64_t slot = (uint64_t)gb + i;
+                        if (slot < (uint64_t)cap) dst[slot] = mine_stage[i];
+                    }
+                    wc[b] = 0;
+                }
+                if (hm[b] != 0) mine_stage[wc[b] + rank] = id0 + (uint32_t)__builtin_ctz(hm[b]);
+                wc[b] += n;
+                hm[b] &= hm[b] - 1;
+                mask = __builtin_amdgcn_ballot_w64(hm[b] != 0);
+            }
+        }
+    };
+    // block-wide look at the slices; moves them out when one is half full (or at the end)
+    auto flush_check = [&](bool last) {
+        if (lane == 0) {
+#pragma unroll
+            for (int b = 0; b < B; ++b) s_wcnt[b][wave] = wc[b];
+        }
+        __syncthreads();
+        uint32_t pre[B], tot[B];
+        bool any = false;
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            pre[b] = 0;
+            tot[b] = 0;
+#pragma unroll
+            for (int w = 0; w < SS_WAVES; ++w) {
+                const uint32_t c = s_wcnt[b][w];
+                if (w < wave) pre[b] += c;
+                tot[b] += c;
+                any |= c > wave_cap / 2;
+            }
+            any |= last && tot[b] > 0;
+        }
+        __syncthreads();   // nobody publishes again before every thread has read the counts
+        if (!any) return;  // block-uniform
+        if (tid < B) s_base[tid] = tot[tid] ? atomicAdd(&cand_count[qbase + tid], tot[tid]) : 0;
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const uint32_t *src = stage + ((uint32_t)b * SS_WAVES + wave) * wave_cap;
+            uint32_t *dst = cand_ids + (int64_t)(qbase + b) * cap;
+            const uint64_t base = (uint64_t)s_base[b] + pre[b];
+            for (uint32_t i = lane; i < wc[b]; i += 64) {
+                const uint64_t slot = base + i;
+                if (slot < (uint64_t)cap) dst[slot] = src[i];
+            }
+            wc[b] = 0;
+        }
+        // the next publish of s_wcnt / s_base comes after at least one more barrier pair
+    };
+
+    uint4 wa[KF], wb[KF];
+    uint32_t g = begin + wave * 1024u;
+    load(g, wa);
+    for (uint32_t it = 0; it < nsteps; it += 2, g += 2 * step) {
+        load(g + step, wb);
+        if (g < end && g >= begin) process(g, wa);
+        if ((it % SS_CHECK) == SS_CHECK - 1 || it == nsteps - 1) flush_check(it == nsteps - 1);
+        if (it + 1 < nsteps) {     // block-uniform
+            load(g + 2 * step, wa);
+            const uint32_t g1 = g + step;
+            if (g1 < end && g1 >= begin) process(g1, wb);
+            if (((it + 1) % SS_CHECK) == SS_CHECK - 1 || it + 1 == nsteps - 1) flush_check(it + 1 == nsteps - 1);
         }
     }
 }
@@ -434,13 +451,14 @@ template <int KF, int B>
 int launch_stream(const icq_index *ix, const float *lut, int Q, const float *thr, uint32_t *cand_ids,
                   uint32_t *cand_count, int64_t cap, hipStream_t s) {
     const size_t tab = sizeof(float) * KF * ICQ_LUT_W * 16 * B;
-    const int threads = 1024;
-    const uint32_t stage_cap = tab * 1 + 32768 * B <= 163840 - 64 ? 8192 : 4000;   // ids per query staged in LDS
-    const size_t lds = tab + sizeof(uint32_t) * B * stage_cap;
+    const int threads = SS_THREADS;
+    // ids one wavefront stages per query: 512 (32 KB per query) when the tables leave that much LDS
+    const uint32_t wave_cap = tab + 32768 * B <= 163840 - 256 ? 512 : 248;
+    const size_t lds = tab + sizeof(uint32_t) * B * SS_WAVES * wave_cap;
     static bool attr_set = false;
     if (!attr_set) {
         ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_stream_kernel<KF, B>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 163840 - 64));
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 163840 - 256));
         attr_set = true;
     }
     const int groups = (Q + B - 1) / B;
@@ -455,7 +473,7 @@ int launch_stream(const icq_index *ix, const float *lut, int Q, const float *thr
     dim3 grid((unsigned)chunks, (unsigned)groups);
     scan_stream_kernel<KF, B><<<grid, threads, lds, s>>>(ix->fast, ix->Npad, (uint32_t)ix->N, lut,
                                                          ix->K, thr, Q, cand_ids, cand_count, cap, per,
-                                                         stage_cap);
+                                                         wave_cap);
     return icq_check_launch();
 }
 
