@@ -246,11 +246,11 @@ __global__ __launch_bounds__(256) void fill_partials_kernel(
 // slices to the query's global list with ONE global atomic -- all blocks add to
 // the same counter, and that address only takes ~10^8 atomics per second.  A
 // slice that fills up between two checks is moved out by its wavefront alone.
-// The code stream is read one step ahead into a second set of registers (two
+// The code stream is read R - 1 steps ahead into register sets of their own (R
 // copies of the step body, no register moves), with loads that are never
-// conditional: the rows are padded by more than one block step, so reading past
-// the block's range is harmless, and the compiler can leave the newer loads in
-// flight while the older ones are consumed.
+// conditional (past the block's range they re-read its first items), so the
+// compiler can leave the newer loads in flight while the oldest are consumed;
+// the first of them are sent before the tables are even written to LDS.
 constexpr int SS_HALF = 8;        // items per lane whose table reads are issued together
 constexpr int SS_CHECK = 8;       // steps between block-wide flush checks
 constexpr int SS_THREADS = 1024;
@@ -269,12 +269,16 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qbase = blockIdx.y * B;
 
-    for (int i = tid; i < KF * ICQ_LUT_W * B; i += SS_THREADS) {
-        const int b = i / (KF * ICQ_LUT_W), e = i % (KF * ICQ_LUT_W);
-        const float v = (qbase + b) < Q ? lut[(int64_t)(qbase + b) * K * ICQ_LUT_W + e] : INFINITY;
+    // the tables go to LDS after the first code loads have been sent (see the end of the kernel)
+    auto fill_tables = [&]() {
+        for (int i = tid; i < KF * ICQ_LUT_W * B; i += SS_THREADS) {
+            const int b = i / (KF * ICQ_LUT_W), e = i % (KF * ICQ_LUT_W);
+            const float v = (qbase + b) < Q ? lut[(int64_t)(qbase + b) * K * ICQ_LUT_W + e] : INFINITY;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) smem[(e * 16 + r) * B + b] = v;
-    }
+            for (int r = 0; r < 16; ++r) smem[(e * 16 + r) * B + b] = v;
+        }
+        __syncthreads();
+    };
     float t[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) t[b] = (qbase + b) < Q ? thr[qbase + b] : -INFINITY;
@@ -283,7 +287,6 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     uint32_t wc[B];               // ids staged by this wavefront (wavefront-uniform)
 #pragma unroll
     for (int b = 0; b < B; ++b) wc[b] = 0;
-    __syncthreads();
 
     const uint32_t begin = blockIdx.x * items_per_block;
     uint32_t end = begin + items_per_block;
@@ -297,6 +300,8 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
 
     // 1024 items at g into w; past the block's range the block's first items are read instead
     // (unused, but in bounds: g < end <= N and the rows are padded by more than 1024 bytes)
+    constexpr int R = B == 1 ? 3 : 2;
+    uint4 w[R][KF];
     auto load = [&](uint32_t g, uint4 (&w)[KF]) {
         const uint32_t gs = (g < end && g >= begin) ? g : begin;
 #pragma unroll
@@ -431,18 +436,19 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
         // the next publish of s_wcnt / s_base comes after at least one more barrier pair
     };
 
-    uint4 wa[KF], wb[KF];
+    // R register sets of 1024 items per wavefront: R - 1 steps are always in flight
     uint32_t g = begin + wave * 1024u;
-    load(g, wa);
-    for (uint32_t it = 0; it < nsteps; it += 2, g += 2 * step) {
-        load(g + step, wb);
-        if (g < end && g >= begin) process(g, wa);
-        if ((it % SS_CHECK) == SS_CHECK - 1 || it == nsteps - 1) flush_check(it == nsteps - 1);
-        if (it + 1 < nsteps) {     // block-uniform
-            load(g + 2 * step, wa);
-            const uint32_t g1 = g + step;
-            if (g1 < end && g1 >= begin) process(g1, wb);
-            if (((it + 1) % SS_CHECK) == SS_CHECK - 1 || it + 1 == nsteps - 1) flush_check(it + 1 == nsteps - 1);
+#pragma unroll
+    for (int r = 0; r < R - 1; ++r) load(g + (uint32_t)r * step, w[r]);
+    fill_tables();
+    for (uint32_t it = 0; it < nsteps; it += R, g += R * step) {
+#pragma unroll
+        for (int u = 0; u < R; ++u) {
+            load(g + (uint32_t)(u + R - 1) * step, w[(u + R - 1) % R]);     // never conditional
+            const uint32_t gu = g + (uint32_t)u * step, itu = it + u;
+            if (gu < end && gu >= begin) process(gu, w[u]);
+            if (itu < nsteps && ((itu % SS_CHECK) == SS_CHECK - 1 || itu == nsteps - 1))   // block-uniform
+                flush_check(itu == nsteps - 1);
         }
     }
 }
