@@ -18,7 +18,12 @@
  * exhaustive ADC, brute-force k-NN over reconstructions on tiny inputs, the
  * product-quantization special case, filter/select commutation, the
  * lossless-pruning invariant on codebooks with the ICQ zero pattern, Kf == K,
- * padding, and a hand-worked micro example.  No function here is unpinned.
+ * padding, and a hand-worked micro example; for the paper's serial loop:
+ * infinite margin == exhaustive ADC, a margin above the spread of the slow
+ * terms loses nothing, a margin of -inf keeps the first topk items, closed
+ * forms on items visited in ascending order of distance, and a hand-worked
+ * trace; for the sample threshold and the operation counts: closed forms.  No
+ * function here is unpinned.
  *
  * Conventions: codebooks [K][m][d] float; codes [K][N] uint8, codebook-major,
  * rows 0..Kf-1 are the fast codebooks; T [Q][K][m] double; ids are uint32;
@@ -165,6 +170,120 @@ void icq_oracle_adc_exhaustive(const double *T, int K, int m,
         }
         free(all);
     }
+}
+
+/* The search operation as the paper states it (Sec. 3.4), a serial loop over
+ * the items in index order with a list of the topk nearest found so far:
+ *   - while the list is not full, an item gets the exact comparison at once
+ *     (the paper does not say what "the furthest element" is before the list
+ *     is full; this is the reading taken here);
+ *   - afterwards let f be the furthest element of the list (largest (D, id)).
+ *     Crude comparison (Eq. 2):  P(i) < P(f) + sigma_q.  Only if it holds, the
+ *     exact comparison (Eq. 1, left sides): D(i) < D(f); if that holds too,
+ *     i replaces f.
+ * P is the sum over the fast codebooks 0..Kf-1, D adds the other K-Kf terms.
+ * sigma [Q] is the margin of Eq. 2 / Eq. 11, supplied by the caller (double;
+ * +inf makes the crude comparison always hold).  Output: the list ascending by
+ * (D, id), padded with (0xFFFFFFFF, +inf); out_refined[q] = how many items got
+ * the exact comparison (the quantity behind the paper's "average ops"). */
+void icq_oracle_running_search(const double *T, int K, int m, const uint8_t *codes,
+                               int64_t N, int Kf, int Q, const double *sigma, int topk,
+                               uint32_t *out_ids, double *out_dist, int64_t *out_refined)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int q = 0; q < Q; ++q) {
+        const double *Tq = T + (size_t)q * K * m;
+        pair_t *list = (pair_t *)malloc(sizeof(pair_t) * (size_t)topk);   /* (D, id) */
+        double *listP = (double *)malloc(sizeof(double) * (size_t)topk);  /* P of the same entries */
+        int len = 0;
+        int64_t refined = 0;
+        for (int64_t i = 0; i < N; ++i) {
+            double p = 0.0;
+            for (int k = 0; k < Kf; ++k)
+                p += Tq[(size_t)k * m + codes[(size_t)k * N + i]];
+            int f = -1;                       /* slot of the furthest element */
+            if (len == topk) {
+                f = 0;
+                for (int r = 1; r < len; ++r)
+                    if (pair_cmp(&list[r], &list[f]) > 0) f = r;
+                if (!(p < listP[f] + sigma[q])) continue;      /* pruned by the crude comparison */
+            }
+            double dfull = p;
+            for (int k = Kf; k < K; ++k)
+                dfull += Tq[(size_t)k * m + codes[(size_t)k * N + i]];
+            ++refined;
+            if (f < 0) {                      /* list not full yet */
+                list[len].dist = dfull; list[len].id = (uint32_t)i; listP[len] = p;
+                ++len;
+            } else if (dfull < list[f].dist) {
+                list[f].dist = dfull; list[f].id = (uint32_t)i; listP[f] = p;
+            }
+        }
+        qsort(list, (size_t)len, sizeof(pair_t), pair_cmp);
+        for (int r = 0; r < topk; ++r) {
+            out_ids[(size_t)q * topk + r] = r < len ? list[r].id : 0xFFFFFFFFu;
+            out_dist[(size_t)q * topk + r] = r < len ? list[r].dist : INFINITY;
+        }
+        out_refined[q] = refined;
+        free(list);
+        free(listP);
+    }
+}
+
+/* A static threshold with the meaning of Sec. 3.4's running one: look at the
+ * first M items only, give every one of them the exact comparison, let f be
+ * the topk-th nearest of them by (D, id), and set
+ *     t_q = P(f) + sigma_q
+ * -- the right side of Eq. 2 as the paper's loop would hold it after its first
+ * M items had none of them been pruned.  Fewer than topk items in the sample:
+ * t_q = +inf (the list would not be full).  thr_out [Q] double. */
+void icq_oracle_sample_thresholds(const double *T, int K, int m, const uint8_t *codes,
+                                  int64_t N, int Kf, int Q, const double *sigma, int topk,
+                                  int64_t M, double *thr_out)
+{
+    const int64_t n = M < N ? M : N;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int q = 0; q < Q; ++q) {
+        if (n < topk) { thr_out[q] = INFINITY; continue; }
+        const double *Tq = T + (size_t)q * K * m;
+        pair_t *all = (pair_t *)malloc(sizeof(pair_t) * (size_t)n);
+        for (int64_t i = 0; i < n; ++i) {
+            double s = 0.0;
+            for (int k = 0; k < K; ++k)
+                s += Tq[(size_t)k * m + codes[(size_t)k * N + i]];
+            all[i].dist = s;
+            all[i].id = (uint32_t)i;
+        }
+        qsort(all, (size_t)n, sizeof(pair_t), pair_cmp);
+        const int64_t f = all[topk - 1].id;
+        double p = 0.0;
+        for (int k = 0; k < Kf; ++k)
+            p += Tq[(size_t)k * m + codes[(size_t)k * N + f]];
+        thr_out[q] = p + sigma[q];
+        free(all);
+    }
+}
+
+/* Operation counts behind the paper's speed axis (Sec. 1, last sentences before
+ * the contributions; Sec. 4.2, effective code length): a two-step search spends
+ * Kf table additions on every item and K-Kf more on each item that gets the
+ * exact comparison, the one-step search spends K on every item:
+ *     ops_icq[q] = N*Kf + refined[q]*(K-Kf),      ops_adc = N*K.
+ * summary[0] = mean_q ops_icq, [1] = ops_adc, [2] = their ratio,
+ * [3] = effective code length  code_bits * ratio  (Sec. 4.2's l-hat with the
+ * one-step search at the same code length as the reference). */
+void icq_oracle_op_counts(int64_t N, int K, int Kf, int Q, const int64_t *refined,
+                          double code_bits, double *ops_icq, double *summary)
+{
+    double sum = 0.0;
+    for (int q = 0; q < Q; ++q) {
+        ops_icq[q] = (double)N * (double)Kf + (double)refined[q] * (double)(K - Kf);
+        sum += ops_icq[q];
+    }
+    summary[0] = Q > 0 ? sum / Q : 0.0;
+    summary[1] = (double)N * (double)K;
+    summary[2] = summary[1] > 0.0 ? summary[0] / summary[1] : 0.0;
+    summary[3] = code_bits * summary[2];
 }
 
 /* Reconstruction (Sec. 1): xbar_i = sum_k c_{k, code_k(i)} for the listed items. */

@@ -48,8 +48,12 @@ def _load():
         lib.icq_oracle_adc_exhaustive.argtypes = [c_d, i, i, c_u8, i64, i, i, c_u32, c_d, c_d]
         lib.icq_oracle_reconstruct.argtypes = [c_f, i, i, i, c_u8, i64, c_i64, i64, c_d]
         lib.icq_oracle_bruteforce_knn.argtypes = [c_f, i, i, i, c_u8, i64, c_f, i, i, c_u32, c_d]
+        lib.icq_oracle_running_search.argtypes = [c_d, i, i, c_u8, i64, i, i, c_d, i, c_u32, c_d, c_i64]
+        lib.icq_oracle_sample_thresholds.argtypes = [c_d, i, i, c_u8, i64, i, i, c_d, i, i64, c_d]
+        lib.icq_oracle_op_counts.argtypes = [i64, i, i, i, c_i64, ctypes.c_double, c_d, c_d]
         lib.icq_oracle_threads.restype = i
-        for name in ("lut", "partial", "search", "adc_exhaustive", "reconstruct", "bruteforce_knn"):
+        for name in ("lut", "partial", "search", "adc_exhaustive", "reconstruct", "bruteforce_knn",
+                     "running_search", "sample_thresholds", "op_counts"):
             getattr(lib, "icq_oracle_" + name).restype = None
         _lib = lib
     return _lib
@@ -127,6 +131,47 @@ def adc_exhaustive(T, codes, topk, want_all=False):
     if want_all:
         return ids, dist, D
     return ids, dist
+
+
+def running_search(T, codes, Kf, sigma, topk):
+    """The paper's serial search loop with margin sigma [Q].  Returns (ids [Q][topk] u32,
+    dist [Q][topk] f64, refined [Q] i64 = items that got the exact comparison)."""
+    Q, K, m = T.shape
+    N = codes.shape[1]
+    T = _chk(T, np.float64, (Q, K, m))
+    cd = _chk(codes, np.uint8, (K, N))
+    sg = _chk(sigma, np.float64, (Q,))
+    ids = np.empty((Q, topk), dtype=np.uint32)
+    dist = np.empty((Q, topk), dtype=np.float64)
+    refined = np.empty((Q,), dtype=np.int64)
+    _load().icq_oracle_running_search(_p(T, ctypes.c_double), K, m, _p(cd, ctypes.c_uint8), N, Kf, Q,
+                                      _p(sg, ctypes.c_double), topk, _p(ids, ctypes.c_uint32),
+                                      _p(dist, ctypes.c_double), _p(refined, ctypes.c_int64))
+    return ids, dist, refined
+
+
+def sample_thresholds(T, codes, Kf, sigma, topk, M):
+    """t_q = P(topk-th nearest of the first M items) + sigma_q, double [Q]."""
+    Q, K, m = T.shape
+    N = codes.shape[1]
+    T = _chk(T, np.float64, (Q, K, m))
+    cd = _chk(codes, np.uint8, (K, N))
+    sg = _chk(sigma, np.float64, (Q,))
+    thr = np.empty((Q,), dtype=np.float64)
+    _load().icq_oracle_sample_thresholds(_p(T, ctypes.c_double), K, m, _p(cd, ctypes.c_uint8), N, Kf, Q,
+                                         _p(sg, ctypes.c_double), topk, M, _p(thr, ctypes.c_double))
+    return thr
+
+
+def op_counts(N, K, Kf, refined, code_bits):
+    """(ops_icq [Q] f64, summary [4] f64 = mean ops_icq, ops_adc, ratio, effective code length)."""
+    rf = np.ascontiguousarray(refined, dtype=np.int64)
+    Q = rf.shape[0]
+    ops = np.empty((Q,), dtype=np.float64)
+    summary = np.empty((4,), dtype=np.float64)
+    _load().icq_oracle_op_counts(N, K, Kf, Q, _p(rf, ctypes.c_int64), float(code_bits),
+                                 _p(ops, ctypes.c_double), _p(summary, ctypes.c_double))
+    return ops, summary
 
 
 def reconstruct(codebooks, codes, items):

@@ -303,3 +303,137 @@ def test_lut_against_expanded_form_at_benchmark_shape():
     q64, c64 = queries.astype(np.float64), cb.astype(np.float64).reshape(K * m, d)
     ref = (q64 ** 2).sum(1)[:, None] - 2 * q64 @ c64.T + (c64 ** 2).sum(1)[None]
     np.testing.assert_allclose(T.reshape(Q, K * m), ref, rtol=1e-12)
+
+
+# ================================================================ the paper's serial loop (Sec. 3.4),
+# the sample threshold derived from it, and the operation counts
+def _golden_file(name):
+    vals = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            key, *rest = line.split()
+            vals[key] = np.array([float(r) for r in rest])
+    return vals
+
+
+def _micro_tables():
+    cb = np.array([[[1, 0], [-1, 0]], [[0, 1], [0, -1]]], dtype=np.float32)
+    q = np.array([[0.5, 0.25]], dtype=np.float32)
+    return orc.lut(cb, q)
+
+
+def test_running_search_matches_hand_worked_trace():
+    gold = _golden_file("running_example.txt")
+    T = _micro_tables()
+    codes = np.stack([gold["codes0"], gold["codes1"]]).astype(np.uint8)
+    topk = int(gold["topk"][0])
+    sigma = np.array([gold["sigma"][0]])
+    ids, dist, refined = orc.running_search(T, codes, 1, sigma, topk)
+    assert np.array_equal(ids[0], gold["ids"].astype(np.uint32))
+    assert np.array_equal(dist[0], gold["dist"])
+    assert refined[0] == int(gold["refined"][0])
+    assert orc.sample_thresholds(T, codes, 1, sigma, topk, 4)[0] == gold["thr_M4"][0]
+    assert orc.sample_thresholds(T, codes, 1, sigma, topk, 7)[0] == gold["thr_M7"][0]
+    assert orc.sample_thresholds(T, codes, 1, sigma, topk, 100)[0] == gold["thr_M7"][0]   # M beyond N
+    assert np.isposinf(orc.sample_thresholds(T, codes, 1, sigma, 8, 7)[0])                 # fewer items than topk
+    ops, summary = orc.op_counts(7, 2, 1, refined, 2.0)
+    assert ops[0] == gold["ops_icq"][0] and summary[1] == gold["ops_adc"][0]
+    assert summary[0] == gold["ops_icq"][0] and summary[2] == gold["ops_icq"][0] / gold["ops_adc"][0]
+    assert abs(summary[3] - gold["effective_bits"][0]) < 1e-15
+    # a longer list than items: everything is refined, padding follows
+    ids9, dist9, ref9 = orc.running_search(T, codes, 1, sigma, 9)
+    assert ref9[0] == 7 and ids9[0, 7] == 0xFFFFFFFF and np.isposinf(dist9[0, 8])
+    assert np.array_equal(ids9[0, :7], [4, 2, 6, 1, 3, 5, 0])
+
+
+def _random_case(seed, K=6, Kf=2, N=4000, Q=7, d=12):
+    g = _rng(seed)
+    cb = (g.standard_normal((K, 256, d)) * (0.7 ** np.arange(K))[:, None, None]).astype(np.float32)
+    codes = g.integers(0, 256, size=(K, N), dtype=np.uint8)
+    queries = g.standard_normal((Q, d)).astype(np.float32)
+    T = orc.lut(cb, queries)
+    return T, codes
+
+
+def test_running_search_with_infinite_margin_is_exhaustive_adc():
+    T, codes = _random_case(21)
+    Q, N, topk = T.shape[0], codes.shape[1], 30
+    e_ids, e_dist = orc.adc_exhaustive(T, codes, topk)
+    ids, dist, refined = orc.running_search(T, codes, 2, np.full(Q, np.inf), topk)
+    assert np.array_equal(ids, e_ids) and np.array_equal(dist, e_dist)
+    assert (refined == N).all()
+
+
+def test_running_search_loses_nothing_when_the_margin_exceeds_the_spread_of_the_slow_terms():
+    """D = P + S with S the sum over the slow codebooks.  An item i of the true top-k has
+    D(i) <= D(f) for the furthest list element f, hence P(i) <= P(f) + S(f) - S(i)
+    <= P(f) + (max S - min S): with a margin above that spread the crude comparison never
+    prunes a true neighbour, whatever the codebooks, and the list stays exact."""
+    T, codes = _random_case(22)
+    Q, N, topk, Kf = T.shape[0], codes.shape[1], 20, 2
+    P = orc.partial(T, codes, Kf)
+    _, _, D = orc.adc_exhaustive(T, codes, 1, want_all=True)
+    S = D - P
+    spread = S.max(axis=1) - S.min(axis=1)
+    e_ids, e_dist = orc.adc_exhaustive(T, codes, topk)
+    ids, dist, refined = orc.running_search(T, codes, Kf, spread * 1.0001, topk)
+    assert np.array_equal(ids, e_ids) and np.array_equal(dist, e_dist)
+    assert (refined < N).all()          # and it still prunes
+    # a much smaller margin prunes more and (on these dense codebooks) loses neighbours
+    ids0, _, refined0 = orc.running_search(T, codes, Kf, np.zeros(Q), topk)
+    assert (refined0 < refined).all()
+    assert (ids0 != e_ids).any()
+
+
+def test_running_search_with_margin_minus_infinity_keeps_the_first_items():
+    T, codes = _random_case(23)
+    Q, topk = T.shape[0], 15
+    ids, dist, refined = orc.running_search(T, codes, 2, np.full(Q, -np.inf), topk)
+    assert (refined == topk).all()
+    e_ids, e_dist = orc.adc_exhaustive(T, codes[:, :topk], topk)     # the first topk items, ordered
+    assert np.array_equal(ids, e_ids) and np.array_equal(dist, e_dist)
+
+
+def test_running_search_on_items_in_ascending_order_of_distance():
+    """Visited nearest first, the list is final after topk items: nothing ever replaces an
+    element, the furthest element stays item topk-1, so an item i >= topk gets the exact
+    comparison iff P(i) < P(topk-1) + sigma -- a closed form for the refined count."""
+    T, codes = _random_case(24, Q=1)
+    Kf, topk = 2, 12
+    _, _, D = orc.adc_exhaustive(T, codes, 1, want_all=True)
+    order = np.argsort(D[0], kind="stable")
+    codes_sorted = np.ascontiguousarray(codes[:, order])
+    P = orc.partial(T, codes_sorted, Kf)[0]
+    for sigma in (0.0, 0.3, 2.0):
+        ids, dist, refined = orc.running_search(T, codes_sorted, Kf, np.array([sigma]), topk)
+        assert np.array_equal(ids[0], np.arange(topk))
+        expect = topk + int((P[topk:] < P[topk - 1] + sigma).sum())
+        assert refined[0] == expect
+
+
+def test_sample_threshold_is_the_crude_distance_of_the_kth_neighbour_plus_margin():
+    T, codes = _random_case(25)
+    Q, N, Kf, topk = T.shape[0], codes.shape[1], 2, 10
+    sigma = np.linspace(0.0, 1.5, Q)
+    P = orc.partial(T, codes, Kf)
+    for M in (N, 500):
+        e_ids, _ = orc.adc_exhaustive(T, codes[:, :M], topk)
+        thr = orc.sample_thresholds(T, codes, Kf, sigma, topk, M)
+        assert np.array_equal(thr, P[np.arange(Q), e_ids[:, topk - 1]] + sigma)
+    # searching with that threshold keeps every item the serial loop could ever list once its
+    # first M items are in: the k-th neighbour of the sample itself survives (P(f) < P(f) + sigma)
+    thr = orc.sample_thresholds(T, codes, Kf, sigma + 0.5, topk, 500).astype(np.float32)
+    ids, _, cnt = orc.search(T, codes, Kf, thr, topk)
+    assert (cnt >= topk).all()
+
+
+def test_op_counts_closed_forms():
+    N, K, Kf = 1000, 8, 2
+    ops, s = orc.op_counts(N, K, Kf, np.full(5, N), 64.0)      # everything refined: the one-step search
+    assert (ops == N * K).all() and s[2] == 1.0 and s[3] == 64.0
+    ops, s = orc.op_counts(N, K, Kf, np.zeros(5, dtype=np.int64), 64.0)   # nothing refined
+    assert (ops == N * Kf).all() and s[2] == Kf / K and s[3] == 64.0 * Kf / K
+    ops, s = orc.op_counts(N, K, Kf, np.array([10, 30]), 64.0)
+    assert np.array_equal(ops, [N * Kf + 60, N * Kf + 180]) and s[0] == N * Kf + 120
