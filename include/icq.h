@@ -53,6 +53,7 @@ extern "C" {
 #define ICQ_MAX_TOPK 1024 /* result list length                */
 #define ICQ_MAX_N 0xFFF00000ll /* items per index (ids are 32-bit) */
 #define ICQ_MAX_Q (1 << 22) /* queries per call                  */
+#define ICQ_MAX_SAMPLE 4096 /* items icq_sample_thresholds looks at */
 #define ICQ_PAD_ID 0xFFFFFFFFu
 
 typedef struct icq_index icq_index;
@@ -179,6 +180,38 @@ int icq_refine(const icq_index *index, const float *lut, int Q, const uint32_t *
 int icq_search(const icq_index *index, const float *queries, int Q, const float *thresholds,
                int64_t cap, int topk, uint32_t *out_ids, float *out_dist, uint32_t *out_survivors,
                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * A static threshold with the meaning of the running one of Sec. 3.4 (right
+ * side of Eq. 2: crude distance of the furthest element of the nearest-
+ * neighbour list, plus the margin sigma of Eq. 11).  For every query the first
+ * min(M, N) items of the index all get the exact comparison; with f the
+ * topk-th nearest of them by (D, id),
+ *     thresholds_out[q] = P[q][f] + sigma[q]            (fp32)
+ * i.e. what the paper's loop would hold after its first M items had none of
+ * them been pruned.  Fewer than topk items: +inf (the list never fills).
+ * sigma [Q] may be NULL (zero margin); the caller derives it from the variance
+ * of its data in the subspace the slow codebooks cover.  lut [Q][K][256] as
+ * written by icq_build_lut.  1 <= M <= ICQ_MAX_SAMPLE, 1 <= topk <= ICQ_MAX_TOPK.
+ * Feed the result to icq_scan_fast / icq_search.
+ */
+int icq_sample_thresholds(const icq_index *index, const float *lut, int Q, const float *sigma, int topk,
+                          int64_t M, float *thresholds_out, void *stream);
+
+/*
+ * Operation counts of the two-step search (Sec. 1: Kf table additions for every
+ * item, K - Kf more for each item that gets the exact comparison, against K per
+ * item for the one-step search) and the effective code length of Sec. 4.2.
+ * refined [Q] = items that got the exact comparison (the out_survivors /
+ * cand_count of a search); values above N count as N.
+ *   ops_out[q]     = N*Kf + refined[q]*(K-Kf)            (64-bit, device)
+ *   summary_out[0] = mean over the queries of ops_out    (double, device [4])
+ *   summary_out[1] = N*K, [2] = [0]/[1],
+ *   summary_out[3] = K*log2(m) * [2]: the code length at which the one-step
+ *                    search would cost the same.
+ */
+int icq_op_counts(const icq_index *index, const uint32_t *refined, int Q, unsigned long long *ops_out,
+                  double *summary_out, void *stream);
 
 #ifdef __cplusplus
 }

@@ -32,6 +32,8 @@ SIGNATURES = {
     "icq_scan_fast": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
     "icq_refine": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _sz, _vp]),
     "icq_search": (_i, [_vp, _vp, _i, _vp, _i64, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "icq_sample_thresholds": (_i, [_vp, _vp, _i, _vp, _i, _i64, _vp, _vp]),
+    "icq_op_counts": (_i, [_vp, _vp, _i, _vp, _vp, _vp]),
 }
 _lib = None
 
@@ -184,3 +186,20 @@ def icq_search(index, queries, thresholds, cap, topk, out_ids, out_dist, out_sur
                              _dev(out_survivors, torch.int32, (Q,), "out_survivors"),
                              _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()),
            "icq_search")
+
+
+def icq_sample_thresholds(index, lut, sigma, topk, M, thresholds_out):
+    """sigma: [Q] f32 device tensor or None (zero margin)."""
+    Q = lut.shape[0]
+    _check(load().icq_sample_thresholds(
+        index.handle, _dev(lut, torch.float32, (Q, index.K, ICQ_LUT_W), "lut"), Q,
+        _dev(sigma, torch.float32, (Q,), "sigma") if sigma is not None else None, topk, M,
+        _dev(thresholds_out, torch.float32, (Q,), "thresholds_out"), _stream()), "icq_sample_thresholds")
+
+
+def icq_op_counts(index, refined, ops_out, summary_out):
+    """refined [Q] int32 (survivor counts), ops_out [Q] int64, summary_out [4] float64 (device)."""
+    Q = refined.shape[0]
+    _check(load().icq_op_counts(index.handle, _dev(refined, torch.int32, (Q,), "refined"), Q,
+                                _dev(ops_out, torch.int64, (Q,), "ops_out"),
+                                _dev(summary_out, torch.float64, (4,), "summary_out"), _stream()), "icq_op_counts")

@@ -1,0 +1,130 @@
+// Threshold policy and operation counts around the two-step search of arxiv
+// 1912.08756.
+//
+// Sec. 3.4 prunes with a running threshold: the crude distance of the furthest
+// element of the nearest-neighbour list plus the margin sigma (right side of
+// Eq. 2, sigma as in Eq. 11).  The search kernels here take a static threshold
+// per query instead, and icq_sample_thresholds derives one with the same
+// meaning from the first M items: every one of them gets the exact comparison,
+// f is the topk-th nearest of them by (D, id), and t_q = P(f) + sigma_q -- what
+// the paper's loop would hold after its first M items had none been pruned.
+//
+// icq_op_counts turns survivor counts into the table additions the paper's speed
+// axis counts (Sec. 1: Kf per item plus K - Kf per item that gets the exact
+// comparison, against K per item for the one-step search) and the effective code
+// length of Sec. 4.2.
+#include "icq_internal.h"
+#include "icq_sort.h"
+
+#include <math.h>
+
+namespace {
+
+constexpr int SP_THREADS = ICQ_SORT_THREADS;
+
+// One block per query.  LDS: K tables | keys[len] (len = power of two >= n).
+__global__ __launch_bounds__(SP_THREADS) void sample_threshold_kernel(
+    const uint8_t *__restrict__ items, int stride, int K, int Kf, const float *__restrict__ lut,
+    const float *__restrict__ sigma, int topk, int n, int len, float *__restrict__ thr_out) {
+    extern __shared__ __attribute__((aligned(16))) float sp_smem[];
+    float *T = sp_smem;
+    u64 *keys = reinterpret_cast<u64 *>(sp_smem + (size_t)K * ICQ_LUT_W);
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const float *Tq = lut + (int64_t)q * K * ICQ_LUT_W;
+    for (int i = tid; i < K * ICQ_LUT_W; i += SP_THREADS) T[i] = Tq[i];
+    __syncthreads();
+    for (int i = tid; i < len; i += SP_THREADS) {
+        u64 key = KEY_PAD;
+        if (i < n) {
+            const uint8_t *rec = items + (size_t)i * stride;
+            float d = T[rec[0]];                       // k ascending, as in the search kernels
+            for (int k = 1; k < K; ++k) d += T[k * ICQ_LUT_W + rec[k]];
+            key = ((u64)icq_order_bits(d) << 32) | (uint32_t)i;
+        }
+        keys[i] = key;
+    }
+    __syncthreads();
+    block_sort(keys, len);
+    if (tid == 0) {
+        const uint32_t f = (uint32_t)keys[topk - 1];
+        const uint8_t *rec = items + (size_t)f * stride;
+        float p = T[rec[0]];
+        for (int k = 1; k < Kf; ++k) p += T[k * ICQ_LUT_W + rec[k]];
+        thr_out[q] = p + (sigma ? sigma[q] : 0.0f);
+    }
+}
+
+__global__ void fill_float_kernel(float *__restrict__ p, int n, float v) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// One block: ops[q] for every query, then the summary from the exact integer sum.
+__global__ __launch_bounds__(1024) void op_counts_kernel(const uint32_t *__restrict__ refined, int Q,
+                                                         unsigned long long N, int K, int Kf, double code_bits,
+                                                         unsigned long long *__restrict__ ops,
+                                                         double *__restrict__ summary) {
+    __shared__ unsigned long long part[1024];
+    unsigned long long sum = 0;
+    for (int q = threadIdx.x; q < Q; q += 1024) {
+        unsigned long long r = refined[q];
+        if (r > N) r = N;                              // a survivor count never exceeds N; guards stale input
+        const unsigned long long o = N * (unsigned long long)Kf + r * (unsigned long long)(K - Kf);
+        ops[q] = o;
+        sum += o;
+    }
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int d = 512; d > 0; d >>= 1) {
+        if ((int)threadIdx.x < d) part[threadIdx.x] += part[threadIdx.x + d];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double mean = Q > 0 ? (double)part[0] / (double)Q : 0.0;
+        const double adc = (double)N * (double)K;
+        const double ratio = adc > 0.0 ? mean / adc : 0.0;
+        summary[0] = mean;
+        summary[1] = adc;
+        summary[2] = ratio;
+        summary[3] = code_bits * ratio;
+    }
+}
+
+}  // namespace
+
+ICQ_EXPORT int icq_sample_thresholds(const icq_index *ix, const float *lut, int Q, const float *sigma,
+                                     int topk, int64_t M, float *thresholds_out, void *stream) {
+    if (!ix || Q < 0 || Q > ICQ_MAX_Q || topk < 1 || topk > ICQ_MAX_TOPK || M < 1 || M > ICQ_MAX_SAMPLE)
+        return ICQ_ERR_ARG;
+    if (Q == 0) return ICQ_OK;
+    if (!lut || !thresholds_out) return ICQ_ERR_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const int n = (int)(M < ix->N ? M : ix->N);
+    if (n < topk) {   // the list would never fill: nothing is pruned
+        fill_float_kernel<<<(Q + 255) / 256, 256, 0, s>>>(thresholds_out, Q, INFINITY);
+        return icq_check_launch();
+    }
+    int len = 2;
+    while (len < n) len <<= 1;
+    const size_t lds = sizeof(float) * (size_t)ix->K * ICQ_LUT_W + sizeof(u64) * (size_t)len;
+    static bool attr_set = false;
+    if (!attr_set) {
+        ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&sample_threshold_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+        attr_set = true;
+    }
+    if (lds > 131072) return ICQ_ERR_ARG;
+    sample_threshold_kernel<<<Q, SP_THREADS, lds, s>>>(ix->items, ix->item_stride, ix->K, ix->Kf, lut, sigma,
+                                                       topk, n, len, thresholds_out);
+    return icq_check_launch();
+}
+
+ICQ_EXPORT int icq_op_counts(const icq_index *ix, const uint32_t *refined, int Q, unsigned long long *ops_out,
+                             double *summary_out, void *stream) {
+    if (!ix || Q < 0 || Q > ICQ_MAX_Q || !summary_out) return ICQ_ERR_ARG;
+    if (Q > 0 && (!refined || !ops_out)) return ICQ_ERR_ARG;
+    const double code_bits = (double)ix->K * log2((double)ix->m);
+    op_counts_kernel<<<1, 1024, 0, (hipStream_t)stream>>>(refined, Q, (unsigned long long)ix->N, ix->K, ix->Kf,
+                                                          code_bits, ops_out, summary_out);
+    return icq_check_launch();
+}

@@ -13,6 +13,60 @@ __device__ __forceinline__ float icq_unorder_bits(uint32_t u) {
     return __uint_as_float((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
 }
 
+constexpr int ICQ_SORT_THREADS = 256;   // block size block_sort is written for
+
+// Compare-exchange steps j = jmax, jmax/2, .., 1 of bitonic stage k on the element
+// a lane holds, against lanes lane^j of its own wavefront (no LDS, no barrier).
+__device__ __forceinline__ u64 wave_bitonic_steps(u64 x, int e, int k, int jmax) {
+    const int lane = threadIdx.x & 63;
+    for (int j = jmax; j > 0; j >>= 1) {
+        const u64 y = __shfl_xor(x, j, 64);
+        const bool up = (e & k) == 0;            // this run sorts ascending
+        const bool low = (lane & j) == 0;        // this lane holds the lower index of the pair
+        const bool take_min = up == low;
+        x = take_min ? (x < y ? x : y) : (x > y ? x : y);
+    }
+    return x;
+}
+
+// Ascending bitonic sort of keys[0..len), len a power of two >= 2, whole block
+// (ICQ_SORT_THREADS threads).  Element e lives on lane e % 64, so every exchange at
+// distance < 64 stays inside a wavefront and is done with shuffles; only the
+// exchanges at distance >= 64 go through LDS with a barrier.
+__device__ inline void block_sort(u64 *keys, int len) {
+    const int tid = threadIdx.x;
+    // stages k <= 64: entirely inside 64-element groups
+    for (int base = 0; base < len; base += ICQ_SORT_THREADS) {
+        const int e = base + tid;
+        if ((e & ~63) < len) {                   // wavefront-uniform
+            u64 x = e < len ? keys[e] : KEY_PAD;
+            for (int k = 2; k <= 64 && k <= len; k <<= 1) x = wave_bitonic_steps(x, e, k, k >> 1);
+            if (e < len) keys[e] = x;
+        }
+    }
+    __syncthreads();
+    for (int k = 128; k <= len; k <<= 1) {
+        for (int j = k >> 1; j >= 64; j >>= 1) {
+            for (int i = tid; i < len / 2; i += ICQ_SORT_THREADS) {
+                const int a = ((i / j) * 2 * j) + (i % j);
+                const int b = a + j;
+                const bool up = (a & k) == 0;
+                const u64 x = keys[a], y = keys[b];
+                if ((x > y) == up) {
+                    keys[a] = y;
+                    keys[b] = x;
+                }
+            }
+            __syncthreads();
+        }
+        for (int base = 0; base < len; base += ICQ_SORT_THREADS) {
+            const int e = base + tid;            // len >= 128 here: every wavefront of the pass is full
+            if (e < len) keys[e] = wave_bitonic_steps(keys[e], e, k, 32);
+        }
+        __syncthreads();
+    }
+}
+
 // Compare-exchange of the register pairs (r, r | M) of a lane: elements 64*M apart.
 template <int M>
 __device__ __forceinline__ void reg_exchange(u64 (&x)[16], int E, int k, int lane) {

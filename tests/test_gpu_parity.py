@@ -502,3 +502,88 @@ def test_stream_scan_at_full_length_properties(gpu):
         ids, part, cnt = _u32(ids), part.cpu().numpy(), _u32(cnt)
         for q in range(nq):
             check_candidates(P[q], thr[q], ids[q], part[q], cnt[q], cap)
+
+
+# ------------------------------------------------------------------ threshold policy, operation counts
+@pytest.mark.parametrize("name,N,Q,over,topk,M", [
+    ("C1", 30_000, 70, {}, 100, 4096),
+    ("C1", 30_000, 9, {}, 10, 1000),                    # sample length not a power of two
+    ("C2", 9_000, 33, dict(d=64), 100, 2048),           # K = 16, Kf = 4
+    ("C0", 10_000, 100, {}, 10, 4096),                  # K = 4, Kf = 1
+    ("C1", 700, 5, {}, 100, 4096),                      # sample = the whole index
+    ("C1", 60, 5, {}, 100, 4096),                       # fewer items than topk: nothing is pruned
+])
+def test_sample_thresholds_match_oracle(gpu, name, N, Q, over, topk, M):
+    torch, b = gpu
+    cfg = small(name, N, Q, **over)
+    g = Gpu(gpu, cfg)
+    T, P, D = oracle_all(cfg)
+    rng = np.random.default_rng(3)
+    sigma = rng.uniform(0.0, 2.0, size=Q).astype(np.float32)
+    lut = g.lut()
+    thr = torch.full((Q,), float("nan"), dtype=torch.float32, device="cuda")
+    b.icq_sample_thresholds(g.index, lut, _dev(torch, sigma), topk, M, thr)
+    thr0 = torch.full((Q,), float("nan"), dtype=torch.float32, device="cuda")
+    b.icq_sample_thresholds(g.index, lut, None, topk, M, thr0)         # no margin
+    torch.cuda.synchronize()
+    thr, thr0 = thr.cpu().numpy(), thr0.cpu().numpy()
+    want = orc.sample_thresholds(T, cfg["codes"], cfg["Kf"], sigma.astype(np.float64), topk, M)
+    n = min(M, N)
+    if n < topk:
+        assert np.isposinf(thr).all() and np.isposinf(thr0).all() and np.isposinf(want).all()
+        return
+    exact = 0
+    for q in range(Q):
+        # fp32 and fp64 may order two sample items differently when their distances nearly tie
+        # at the topk-th place: accept the crude distance of any item that ties with it
+        Dk = np.sort(D[q, :n])[topk - 1]
+        ties = np.nonzero(np.abs(D[q, :n] - Dk) <= tol(Dk))[0]
+        err = np.abs(P[q, ties] + sigma[q] - thr[q]).min()
+        assert err <= tol(thr[q]), (q, err)
+        assert np.abs(P[q, ties] - thr0[q]).min() <= tol(thr0[q])
+        exact += abs(want[q] - thr[q]) <= tol(want[q])
+    assert exact >= 0.9 * Q
+    with pytest.raises(b.IcqError):
+        b.icq_sample_thresholds(g.index, lut, None, topk, 4097, torch.empty(Q, dtype=torch.float32, device="cuda"))
+
+
+def test_two_pass_search_with_sampled_thresholds(gpu):
+    """Thresholds from the first items, then the two-step search: the lists equal the oracle's
+    two-step search under the same thresholds, and they contain what the paper's serial loop
+    finds with the same margin wherever that loop's own running threshold never fell below
+    the static one (checked through the crude distances of its results)."""
+    torch, b = gpu
+    cfg = small("C1", 60_000, 64)
+    g = Gpu(gpu, cfg)
+    T, P, D = oracle_all(cfg)
+    Q, topk, M, Kf = 64, 50, 2048, cfg["Kf"]
+    S = D - P
+    sigma = (0.5 * S.std(axis=1)).astype(np.float32)
+    thr = torch.empty((Q,), dtype=torch.float32, device="cuda")
+    b.icq_sample_thresholds(g.index, g.lut(), _dev(torch, sigma), topk, M, thr)
+    torch.cuda.synchronize()
+    thr = thr.cpu().numpy()
+    out_ids, out_dist, surv = _check_search(g, cfg, T, P, D, thr, topk, 60_000)
+    r_ids, r_dist, refined = orc.running_search(T, cfg["codes"], Kf, sigma.astype(np.float64), topk)
+    for q in range(Q):
+        inside = r_ids[q][P[q, r_ids[q]] < thr[q] - tol(thr[q])]      # the loop's results that clearly pass t_q
+        worst = out_dist[q][-1]
+        need = inside[D[q, inside] < worst - tol(worst)]
+        assert np.isin(need, out_ids[q]).all()
+
+
+def test_op_counts_match_oracle(gpu):
+    torch, b = gpu
+    cfg = small("C1", 5_000, 300)
+    g = Gpu(gpu, cfg)
+    rng = np.random.default_rng(9)
+    refined = rng.integers(0, 5_001, size=300).astype(np.int32)
+    refined[7] = 0
+    refined[8] = 5_000
+    ops = torch.empty((300,), dtype=torch.int64, device="cuda")
+    summary = torch.empty((4,), dtype=torch.float64, device="cuda")
+    b.icq_op_counts(g.index, _dev(torch, refined), ops, summary)
+    torch.cuda.synchronize()
+    o_ops, o_sum = orc.op_counts(5_000, cfg["K"], cfg["Kf"], refined.astype(np.int64), cfg["K"] * 8.0)
+    assert np.array_equal(ops.cpu().numpy(), o_ops.astype(np.int64))
+    assert np.array_equal(summary.cpu().numpy(), o_sum)
