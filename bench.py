@@ -153,6 +153,68 @@ def cpu_baseline(cfg, thr_np, gpu_ids, gpu_dist, target_s=15.0):
             {"checked_queries": n_check, "identical_lists_frac": round(same, 4), "sampled_queries": n})
 
 
+def policy_leg(torch, b, cfg, index, queries, step_args, steps, with_cpu):
+    """The paper's threshold policy on the same workload: thresholds from the first M items
+    with the margin of Eq. 11 (icq_sample_thresholds), then the two-step search, then the
+    operation counts of the paper's speed axis; on a few queries the result is compared with
+    the paper's serial loop (oracle) run with the same margin."""
+    K, Kf, N, Q, topk = cfg["K"], cfg["Kf"], cfg["N"], cfg["Q"], cfg["topk"]
+    M = 4096
+    # margin: variance of the data in the part of space the slow codebooks cover, summed over
+    # the dimensions -- for sub-codes drawn uniformly that is the codeword variance of the slow
+    # codebooks (input preparation, from the codebooks alone)
+    cbk = cfg["codebooks"].astype(np.float64)
+    sigma_val = float(sum(cbk[k].var(axis=0).sum() for k in range(Kf, K)))
+    sigma = torch.full((Q,), sigma_val, dtype=torch.float32, device="cuda")
+    cap, out_ids, out_dist, surv, ws = step_args
+    lut = torch.empty((Q, K, 256), dtype=torch.float32, device="cuda")
+    thr = torch.empty((Q,), dtype=torch.float32, device="cuda")
+    b.icq_build_lut(index, queries, lut)
+
+    def sample():
+        b.icq_sample_thresholds(index, lut, sigma, topk, M, thr)
+
+    def whole():   # what a caller runs per batch: tables for the policy, policy, search (which builds its own tables)
+        b.icq_build_lut(index, queries, lut)
+        b.icq_sample_thresholds(index, lut, sigma, topk, M, thr)
+        b.icq_search(index, queries, thr, cap, topk, out_ids, out_dist, surv, ws)
+    sample()
+    whole()
+    torch.cuda.synchronize()
+    ms_sample = event_time_ms(torch, sample, max(3, steps))
+    ms_whole = event_time_ms(torch, whole, max(3, steps))
+    ops = torch.empty((Q,), dtype=torch.int64, device="cuda")
+    summary = torch.empty((4,), dtype=torch.float64, device="cuda")
+    b.icq_op_counts(index, surv, ops, summary)
+    torch.cuda.synchronize()
+    sm = summary.cpu().numpy()
+    surv_np = surv.cpu().numpy().view(np.uint32)
+    out = {"policy": "t_q = crude distance of the top-%d-th nearest of the first %d items + sigma" % (topk, M),
+           "sigma": round(sigma_val, 4), "ms_sample_thresholds": round(ms_sample, 4),
+           "ms_tables_policy_search": round(ms_whole, 4), "queries_per_s": round(Q / (ms_whole * 1e-3), 1),
+           "survivors_mean": round(float(surv_np.mean()), 1), "survivors_frac": round(float(surv_np.mean()) / N, 5),
+           "ops_two_step_mean": float(sm[0]), "ops_one_step": float(sm[1]), "ops_ratio": round(float(sm[2]), 5),
+           "code_bits": K * 8, "effective_code_bits": round(float(sm[3]), 3)}
+    if with_cpu:
+        from oracle import icq_oracle as orc
+        nq = 16
+        T = orc.lut(cfg["codebooks"], cfg["queries"][:nq])
+        t0 = time.perf_counter()
+        r_ids, _, refined = orc.running_search(T, cfg["codes"], Kf, np.full(nq, sigma_val), topk)
+        dt = time.perf_counter() - t0
+        e_ids, _ = orc.adc_exhaustive(T, cfg["codes"], topk)
+        g_ids = out_ids[:nq].cpu().numpy().view(np.uint32)
+        inter = lambda a, c: float(np.mean([np.intersect1d(a[q], c[q]).size / topk for q in range(nq)]))
+        out["vs_serial_loop"] = {
+            "queries": nq, "recall_of_serial_loop_lists": round(inter(g_ids, r_ids), 4),
+            "recall_of_exhaustive_lists": round(inter(g_ids, e_ids), 4),
+            "serial_loop_recall_of_exhaustive": round(inter(r_ids, e_ids), 4),
+            "serial_loop_refined_mean": float(refined.mean()),
+            "two_pass_refined_mean": float(surv_np[:nq].mean()),
+            "serial_loop_queries_per_s_cpu": round(nq / dt, 2)}
+    return out
+
+
 def pmc_traffic(kernel):
     """HBM bytes per launch of `kernel` from the committed counter summary (two rocprofv3
     --pmc runs of this program, scaled by what the counters read for a copy of known
@@ -178,6 +240,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hbm-leg", action="store_true")
     ap.add_argument("--no-streamed-leg", action="store_true")
+    ap.add_argument("--no-policy-leg", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB): the scale for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
@@ -305,6 +368,14 @@ def main():
                     "64 B/clk/CU on this chip (peak_measured_b32); HBM code bytes are Kf*N*ceil(Q/64)"}
         log("[bench] streamed stage 1: %.3f ms/step (stage 1 %.3f ms), same ids as grouped: %s" %
             (ms_s, stage_s[1], same))
+
+    if not args.no_policy_leg:
+        log("[bench] threshold policy of the paper: sampled thresholds with margin, search, operation counts")
+        result["threshold_policy"] = policy_leg(torch, b, cfg, index, queries, (cap, out_ids, out_dist, surv, ws),
+                                                max(3, args.steps // 2), not args.no_cpu_baseline)
+        p = result["threshold_policy"]
+        log("[bench] policy: thresholds %.3f ms, tables + policy + search %.3f ms, %.2f %% survive, ops ratio %.4f"
+            % (p["ms_sample_thresholds"], p["ms_tables_policy_search"], 100 * p["survivors_frac"], p["ops_ratio"]))
 
     if not args.no_hbm_leg:
         del ws

@@ -202,8 +202,7 @@ static_assert(GD_ROWS % 2 == 0, "a step is two half steps");
 static_assert(GD_LIST - GD_STEP >= 2 * 512, "room for topk <= 512 plus ties between two cuts");
 
 struct GdShared {
-    uint32_t hist[256];
-    uint32_t wred[GS_THREADS / 64][2];
+    IcqKthShared kth;
     uint32_t wtot[2][GS_THREADS / 64];
     uint32_t wsum[GS_THREADS / 64][2];
     uint32_t flag[GS_THREADS / 64][64];    // locate(): stamps of the tuple starts inside a row of survivors
@@ -236,95 +235,6 @@ __device__ __forceinline__ void block_scan2(uint32_t a, uint32_t b, uint32_t (*w
     tot_a = ta; tot_b = tb;
 }
 
-// The kr-th smallest (1-based) of the values v[u] whose bit u is set in `ok`, taken over
-// the whole block; at least kr values are flagged.  EXACT: that value (radix select, 8-bit
-// digits over the occupied range).  Otherwise a single counting pass over the top 8 bits
-// of the occupied range; the result is the largest value of the bin that holds the kr-th
-// smallest, i.e. an upper bound that keeps the bin whole.  Every thread calls (barriers).
-__device__ __forceinline__ uint32_t block_kth(GdShared &sh, const uint32_t (&v)[GD_LPT], uint32_t ok, uint32_t kr,
-                                              bool EXACT, int tid, uint32_t lane, int wave) {
-    uint32_t vmin = 0xFFFFFFFFu, vmax = 0u;
-#pragma unroll
-    for (int u = 0; u < GD_LPT; ++u) {
-        if ((ok >> u) & 1u) {
-            vmin = v[u] < vmin ? v[u] : vmin;
-            vmax = v[u] > vmax ? v[u] : vmax;
-        }
-    }
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) {
-        const uint32_t a = __shfl_xor(vmin, d, 64), b = __shfl_xor(vmax, d, 64);
-        vmin = a < vmin ? a : vmin;
-        vmax = b > vmax ? b : vmax;
-    }
-    __syncthreads();                       // earlier readers of wred / hist are done
-    if (lane == 0) { sh.wred[wave][0] = vmin; sh.wred[wave][1] = vmax; }
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < GS_THREADS / 64; ++w) {
-        const uint32_t a = sh.wred[w][0], b = sh.wred[w][1];
-        vmin = a < vmin ? a : vmin;
-        vmax = b > vmax ? b : vmax;
-    }
-    const uint32_t range = vmax - vmin;
-    const int bits = range == 0 ? 0 : 32 - __builtin_clz(range);
-    if (bits == 0) return vmin;
-    int shift = bits > 8 ? bits - 8 : 0;
-    int width = bits < 8 ? bits : 8;
-    uint32_t prefix = 0;       // chosen high digits of (value - vmin)
-    int fixed_from = 32;       // bits [fixed_from, 32) of (value - vmin) are decided
-    for (;;) {
-        sh.hist[tid] = 0;
-        __syncthreads();
-        const uint32_t dmask = (1u << width) - 1u;
-#pragma unroll
-        for (int u = 0; u < GD_LPT; ++u) {
-            if ((ok >> u) & 1u) {
-                const uint32_t y = v[u] - vmin;
-                const bool match = fixed_from >= 32 ? true : (y >> fixed_from) == prefix;
-                if (match) atomicAdd(&sh.hist[(y >> shift) & dmask], 1u);
-            }
-        }
-        __syncthreads();
-        // every wavefront locates the bin by itself (4 bins per lane)
-        uint32_t h[4], mine = 0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            h[r] = sh.hist[lane * 4 + r];
-            mine += h[r];
-        }
-        uint32_t incl = mine;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t o = __shfl_up(incl, d, 64);
-            if ((int)lane >= d) incl += o;
-        }
-        const int L = __builtin_ctzll(__builtin_amdgcn_ballot_w64(incl >= kr));
-        uint32_t run = incl - mine, my_bin = 0, my_below = 0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            if (run < kr && run + h[r] >= kr) {
-                my_bin = lane * 4 + r;
-                my_below = run;
-            }
-            run += h[r];
-        }
-        const uint32_t bin = (uint32_t)__builtin_amdgcn_readlane((int)my_bin, L);
-        const uint32_t below = (uint32_t)__builtin_amdgcn_readlane((int)my_below, L);
-        kr -= below;
-        prefix = (prefix << width) | bin;
-        fixed_from = shift;
-        if (!EXACT || shift == 0) break;
-        const int ns = shift > 8 ? shift - 8 : 0;
-        width = shift - ns;
-        shift = ns;
-        __syncthreads();                   // every wavefront has read the histogram
-    }
-    if (shift == 0) return vmin + prefix;
-    const unsigned long long top = (unsigned long long)vmin + ((((unsigned long long)prefix + 1ull) << shift) - 1ull);
-    return top < (unsigned long long)vmax ? (uint32_t)top : vmax;
-}
-
 // Cut list[0..cnt) (cnt block-uniform, > topk) back to the keys whose distance word is at
 // or below a bound that keeps the topk smallest distances (ties at the bound kept; with
 // !EXACT the bound is the top of a histogram bin, see block_kth).  Returns the new count,
@@ -341,7 +251,7 @@ __device__ __forceinline__ uint32_t block_cut(GdShared &sh, unsigned long long *
         e[u] = list[i < cnt ? i : 0];
         v[u] = (uint32_t)(e[u] >> 32);
     }
-    const uint32_t cut = block_kth(sh, v, ok, topk, EXACT, tid, lane, wave);
+    const uint32_t cut = block_kth<GD_LPT>(sh.kth, v, ok, topk, EXACT, tid, lane, wave);
     uint32_t c = 0;
 #pragma unroll
     for (int u = 0; u < GD_LPT; ++u) c += ((ok >> u) & 1u) && v[u] <= cut ? 1u : 0u;
@@ -377,7 +287,7 @@ __device__ __forceinline__ uint32_t block_tie_cut(GdShared &sh, unsigned long lo
     block_scan2((uint32_t)__builtin_popcount(lt), (uint32_t)__builtin_popcount(eq), sh.wsum, lane, wave, x0, x1,
                 n_lt, n_eq);
     const uint32_t need = topk - n_lt;     // >= 1: the topk-th smallest distance is `cut`
-    const uint32_t idcut = block_kth(sh, w, eq, need, true, tid, lane, wave);
+    const uint32_t idcut = block_kth<GD_LPT>(sh.kth, w, eq, need, true, tid, lane, wave);
     uint32_t keep = lt;
 #pragma unroll
     for (int u = 0; u < GD_LPT; ++u)

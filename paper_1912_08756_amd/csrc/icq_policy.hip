@@ -22,31 +22,69 @@ namespace {
 
 constexpr int SP_THREADS = ICQ_SORT_THREADS;
 
-// One block per query.  LDS: K tables | keys[len] (len = power of two >= n).
+constexpr int SP_LPT = ICQ_MAX_SAMPLE / SP_THREADS;    // sample items per thread
+static_assert(ICQ_MAX_SAMPLE % SP_THREADS == 0 && SP_LPT <= 32, "one flag bit per item of a thread");
+
+// One block per query; thread t owns sample items u * SP_THREADS + t.  LDS: the K tables.
+// The topk-th nearest by (D, id) comes from two exact radix selects: the topk-th smallest
+// distance word, then -- among the items at exactly that distance -- the id that completes
+// the count (usually the only one).
 __global__ __launch_bounds__(SP_THREADS) void sample_threshold_kernel(
     const uint8_t *__restrict__ items, int stride, int K, int Kf, const float *__restrict__ lut,
-    const float *__restrict__ sigma, int topk, int n, int len, float *__restrict__ thr_out) {
+    const float *__restrict__ sigma, int topk, int n, float *__restrict__ thr_out) {
     extern __shared__ __attribute__((aligned(16))) float sp_smem[];
+    __shared__ IcqKthShared kth;
+    __shared__ uint32_t s_below[SP_THREADS / 64];
     float *T = sp_smem;
-    u64 *keys = reinterpret_cast<u64 *>(sp_smem + (size_t)K * ICQ_LUT_W);
     const int q = blockIdx.x, tid = threadIdx.x;
+    const uint32_t lane = (uint32_t)tid & 63u;
+    const int wave = tid >> 6;
     const float *Tq = lut + (int64_t)q * K * ICQ_LUT_W;
     for (int i = tid; i < K * ICQ_LUT_W; i += SP_THREADS) T[i] = Tq[i];
     __syncthreads();
-    for (int i = tid; i < len; i += SP_THREADS) {
-        u64 key = KEY_PAD;
+    uint32_t v[SP_LPT], ok = 0;
+#pragma unroll
+    for (int u = 0; u < SP_LPT; ++u) {
+        const int i = u * SP_THREADS + tid;
+        v[u] = 0;
         if (i < n) {
-            const uint8_t *rec = items + (size_t)i * stride;
-            float d = T[rec[0]];                       // k ascending, as in the search kernels
-            for (int k = 1; k < K; ++k) d += T[k * ICQ_LUT_W + rec[k]];
-            key = ((u64)icq_order_bits(d) << 32) | (uint32_t)i;
+            // the record word by word (records are 4-byte aligned); k ascending, as in the search kernels
+            const uint32_t *rec = reinterpret_cast<const uint32_t *>(items + (size_t)i * stride);
+            float d = 0.0f;
+            for (int w = 0; w * 4 < K; ++w) {
+                const uint32_t word = rec[w];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int k = w * 4 + b;
+                    if (k < K) {
+                        const float e = T[k * ICQ_LUT_W + ((word >> (8 * b)) & 0xffu)];
+                        d = k == 0 ? e : d + e;
+                    }
+                }
+            }
+            v[u] = icq_order_bits(d);
+            ok |= 1u << u;
         }
-        keys[i] = key;
     }
+    const uint32_t cut = block_kth<SP_LPT>(kth, v, ok, (uint32_t)topk, true, tid, lane, wave);
+    // items nearer than the cut, and the ids of those at it
+    uint32_t below = 0, eq = 0, ids[SP_LPT];
+#pragma unroll
+    for (int u = 0; u < SP_LPT; ++u) {
+        ids[u] = (uint32_t)(u * SP_THREADS + tid);
+        if (((ok >> u) & 1u) && v[u] < cut) ++below;
+        if (((ok >> u) & 1u) && v[u] == cut) eq |= 1u << u;
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) below += __shfl_xor(below, d, 64);
     __syncthreads();
-    block_sort(keys, len);
+    if (lane == 0) s_below[wave] = below;
+    __syncthreads();
+    uint32_t total_below = 0;
+#pragma unroll
+    for (int w = 0; w < SP_THREADS / 64; ++w) total_below += s_below[w];
+    const uint32_t f = block_kth<SP_LPT>(kth, ids, eq, (uint32_t)topk - total_below, true, tid, lane, wave);
     if (tid == 0) {
-        const uint32_t f = (uint32_t)keys[topk - 1];
         const uint8_t *rec = items + (size_t)f * stride;
         float p = T[rec[0]];
         for (int k = 1; k < Kf; ++k) p += T[k * ICQ_LUT_W + rec[k]];
@@ -104,18 +142,15 @@ ICQ_EXPORT int icq_sample_thresholds(const icq_index *ix, const float *lut, int 
         fill_float_kernel<<<(Q + 255) / 256, 256, 0, s>>>(thresholds_out, Q, INFINITY);
         return icq_check_launch();
     }
-    int len = 2;
-    while (len < n) len <<= 1;
-    const size_t lds = sizeof(float) * (size_t)ix->K * ICQ_LUT_W + sizeof(u64) * (size_t)len;
+    const size_t lds = sizeof(float) * (size_t)ix->K * ICQ_LUT_W;
     static bool attr_set = false;
     if (!attr_set) {
         ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&sample_threshold_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 65536));
         attr_set = true;
     }
-    if (lds > 131072) return ICQ_ERR_ARG;
     sample_threshold_kernel<<<Q, SP_THREADS, lds, s>>>(ix->items, ix->item_stride, ix->K, ix->Kf, lut, sigma,
-                                                       topk, n, len, thresholds_out);
+                                                       topk, n, thresholds_out);
     return icq_check_launch();
 }
 

@@ -120,3 +120,99 @@ __device__ inline void wave_sort(u64 *keys, int len, int lane) {
         if (r < E) keys[r * 64 + lane] = x[r];
 }
 
+// LDS scratch of block_kth.
+struct IcqKthShared {
+    uint32_t hist[256];
+    uint32_t wred[ICQ_SORT_THREADS / 64][2];
+};
+
+// The kr-th smallest (1-based) of the values v[u] whose bit u is set in `ok`, taken over
+// the whole block of ICQ_SORT_THREADS threads (LPT <= 32 values per thread); at least kr values are flagged.  EXACT: that value (radix select, 8-bit
+// digits over the occupied range).  Otherwise a single counting pass over the top 8 bits
+// of the occupied range; the result is the largest value of the bin that holds the kr-th
+// smallest, i.e. an upper bound that keeps the bin whole.  Every thread calls (barriers).
+template <int LPT>
+__device__ __forceinline__ uint32_t block_kth(IcqKthShared &sh, const uint32_t (&v)[LPT], uint32_t ok, uint32_t kr,
+                                              bool EXACT, int tid, uint32_t lane, int wave) {
+    uint32_t vmin = 0xFFFFFFFFu, vmax = 0u;
+#pragma unroll
+    for (int u = 0; u < LPT; ++u) {
+        if ((ok >> u) & 1u) {
+            vmin = v[u] < vmin ? v[u] : vmin;
+            vmax = v[u] > vmax ? v[u] : vmax;
+        }
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+        const uint32_t a = __shfl_xor(vmin, d, 64), b = __shfl_xor(vmax, d, 64);
+        vmin = a < vmin ? a : vmin;
+        vmax = b > vmax ? b : vmax;
+    }
+    __syncthreads();                       // earlier readers of wred / hist are done
+    if (lane == 0) { sh.wred[wave][0] = vmin; sh.wred[wave][1] = vmax; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < ICQ_SORT_THREADS / 64; ++w) {
+        const uint32_t a = sh.wred[w][0], b = sh.wred[w][1];
+        vmin = a < vmin ? a : vmin;
+        vmax = b > vmax ? b : vmax;
+    }
+    const uint32_t range = vmax - vmin;
+    const int bits = range == 0 ? 0 : 32 - __builtin_clz(range);
+    if (bits == 0) return vmin;
+    int shift = bits > 8 ? bits - 8 : 0;
+    int width = bits < 8 ? bits : 8;
+    uint32_t prefix = 0;       // chosen high digits of (value - vmin)
+    int fixed_from = 32;       // bits [fixed_from, 32) of (value - vmin) are decided
+    for (;;) {
+        sh.hist[tid] = 0;
+        __syncthreads();
+        const uint32_t dmask = (1u << width) - 1u;
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) {
+            if ((ok >> u) & 1u) {
+                const uint32_t y = v[u] - vmin;
+                const bool match = fixed_from >= 32 ? true : (y >> fixed_from) == prefix;
+                if (match) atomicAdd(&sh.hist[(y >> shift) & dmask], 1u);
+            }
+        }
+        __syncthreads();
+        // every wavefront locates the bin by itself (4 bins per lane)
+        uint32_t h[4], mine = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            h[r] = sh.hist[lane * 4 + r];
+            mine += h[r];
+        }
+        uint32_t incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(incl, d, 64);
+            if ((int)lane >= d) incl += o;
+        }
+        const int L = __builtin_ctzll(__builtin_amdgcn_ballot_w64(incl >= kr));
+        uint32_t run = incl - mine, my_bin = 0, my_below = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if (run < kr && run + h[r] >= kr) {
+                my_bin = lane * 4 + r;
+                my_below = run;
+            }
+            run += h[r];
+        }
+        const uint32_t bin = (uint32_t)__builtin_amdgcn_readlane((int)my_bin, L);
+        const uint32_t below = (uint32_t)__builtin_amdgcn_readlane((int)my_below, L);
+        kr -= below;
+        prefix = (prefix << width) | bin;
+        fixed_from = shift;
+        if (!EXACT || shift == 0) break;
+        const int ns = shift > 8 ? shift - 8 : 0;
+        width = shift - ns;
+        shift = ns;
+        __syncthreads();                   // every wavefront has read the histogram
+    }
+    if (shift == 0) return vmin + prefix;
+    const unsigned long long top = (unsigned long long)vmin + ((((unsigned long long)prefix + 1ull) << shift) - 1ull);
+    return top < (unsigned long long)vmax ? (uint32_t)top : vmax;
+}
+
