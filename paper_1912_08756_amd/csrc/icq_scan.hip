@@ -234,11 +234,16 @@ __global__ __launch_bounds__(256) void fill_partials_kernel(
 // Streaming form for one to a few queries per pass: every code byte is read
 // from HBM once per B queries, so the kernel is bound by the code stream.  Each
 // lane owns 16 consecutive items per step (one 128-bit load per fast row).  The
-// B queries' fast tables sit in LDS replicated 16 times, entry (k, c) copy r at
-// dword ((k*256 + c)*16 + r)*B: lane l reads copy l%16, and the 16 lanes the LDS
+// B queries' fast tables sit in LDS replicated C = 16 times, entry (k, c) copy r
+// at dword ((k*256 + c)*C + r)*B: lane l reads copy l%C, and the 16 lanes the LDS
 // serves per clock then always fall into 16 different banks, whatever their
-// sub-codes.  The B values of an entry are adjacent, so one 32/64-bit read
-// serves all B queries.
+// sub-codes.  The B values of an entry are adjacent, so one 32/64/128-bit read
+// serves all B queries -- the LDS takes 16 addresses per clock whatever the
+// width, so B = 4 moves three times the table entries per clock of B = 1.  With
+// B = 4 and Kf > 2 only C = 8 copies fit (128 KB): two lanes of a 16-lane group
+// then share a copy and collide when their sub-codes have the same parity.
+// Calls with many queries and Kf = 3, 4 (no grouping, no transposed tables) run
+// this form with B = 4, one block column per group of four queries.
 // Survivors: a lane collects the hit bits of its 16 items; a wavefront compacts
 // them with ballots into its OWN slice of an LDS staging list (its count lives in
 // a scalar register: no atomics, nothing to wait for), and every SS_CHECK steps
@@ -251,7 +256,8 @@ __global__ __launch_bounds__(256) void fill_partials_kernel(
 // conditional (past the block's range they re-read its first items), so the
 // compiler can leave the newer loads in flight while the oldest are consumed;
 // the first of them are sent before the tables are even written to LDS.
-constexpr int SS_HALF = 8;        // items per lane whose table reads are issued together
+constexpr int ss_copies(int KF, int B) { return KF * ICQ_LUT_W * 16 * 4 * B <= 131072 ? 16 : 8; }
+constexpr int ss_half(int B) { return B == 4 ? 2 : 8; }   // items per lane whose table reads are issued together
 constexpr int SS_CHECK = 8;       // steps between block-wide flush checks
 constexpr int SS_THREADS = 1024;
 constexpr int SS_WAVES = SS_THREADS / 64;
@@ -263,7 +269,9 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     uint32_t *__restrict__ cand_count, int64_t cap, uint32_t items_per_block, uint32_t wave_cap) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     __shared__ uint32_t s_wcnt[B][SS_WAVES], s_base[B];
-    constexpr int TAB_FLOATS = KF * ICQ_LUT_W * 16 * B;
+    constexpr int C = ss_copies(KF, B);
+    constexpr int SS_HALF = ss_half(B);
+    constexpr int TAB_FLOATS = KF * ICQ_LUT_W * C * B;
     const int tid = threadIdx.x;
     const uint32_t lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -275,7 +283,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
             const int b = i / (KF * ICQ_LUT_W), e = i % (KF * ICQ_LUT_W);
             const float v = (qbase + b) < Q ? lut[(int64_t)(qbase + b) * K * ICQ_LUT_W + e] : INFINITY;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) smem[(e * 16 + r) * B + b] = v;
+            for (int r = 0; r < C; ++r) smem[(e * C + r) * B + b] = v;
         }
         __syncthreads();
     };
@@ -291,9 +299,11 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     const uint32_t begin = blockIdx.x * items_per_block;
     uint32_t end = begin + items_per_block;
     if (end > N || end < begin) end = N;
-    // byte offset of this lane's copy inside an entry; an entry is 16 copies of B floats
-    constexpr int ENTRY_SHIFT = B == 1 ? 6 : B == 2 ? 7 : 8;
-    const uint32_t copy_off = (lane & 15) * (4 * B);
+    // byte offset of this lane's copy inside an entry; an entry is C copies of B floats
+    constexpr int ENTRY_BYTES = C * 4 * B;
+    constexpr int ENTRY_SHIFT = ENTRY_BYTES == 64 ? 6 : ENTRY_BYTES == 128 ? 7 : 8;
+    static_assert((1 << ENTRY_SHIFT) == ENTRY_BYTES, "entry size is 64, 128 or 256 bytes");
+    const uint32_t copy_off = (lane & (C - 1)) * (4 * B);
     const char *tab_bytes = reinterpret_cast<const char *>(smem);
     constexpr uint32_t step = (uint32_t)SS_WAVES * 1024u;
     const uint32_t nsteps = end > begin ? (end - begin + step - 1) / step : 0;   // same for every wavefront
@@ -301,6 +311,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     // 1024 items at g into w; past the block's range the block's first items are read instead
     // (unused, but in bounds: g < end <= N and the rows are padded by more than 1024 bytes)
     constexpr int R = B == 1 ? 3 : 2;
+    static_assert(B == 1 || B == 2 || B == 4, "one 32/64/128-bit table read per lookup");
     uint4 w[R][KF];
     auto load = [&](uint32_t g, uint4 (&w)[KF]) {
         const uint32_t gs = (g < end && g >= begin) ? g : begin;
@@ -336,7 +347,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
             for (int jj = 0; jj < SS_HALF; ++jj) {
 #pragma unroll
                 for (int k = 0; k < KF; ++k) {
-                    const char *e = tab_bytes + k * (ICQ_LUT_W * 64 * B) + off[jj][k];
+                    const char *e = tab_bytes + k * (ICQ_LUT_W * ENTRY_BYTES) + off[jj][k];
                     if (B == 1) {
                         v[jj][k][0] = *reinterpret_cast<const float *>(e);
                     } else if (B == 2) {
@@ -407,15 +418,17 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
         bool any = false;
 #pragma unroll
         for (int b = 0; b < B; ++b) {
-            pre[b] = 0;
-            tot[b] = 0;
+            // lane w < 16 takes wavefront w's count; prefix over the 16 lanes
+            const uint32_t c = lane < SS_WAVES ? s_wcnt[b][lane] : 0u;
+            uint32_t incl = c;
 #pragma unroll
-            for (int w = 0; w < SS_WAVES; ++w) {
-                const uint32_t c = s_wcnt[b][w];
-                if (w < wave) pre[b] += c;
-                tot[b] += c;
-                any |= c > wave_cap / 2;
+            for (int d = 1; d < SS_WAVES; d <<= 1) {
+                const uint32_t o = __shfl_up(incl, d, 64);
+                if ((int)lane >= d) incl += o;
             }
+            pre[b] = (uint32_t)__builtin_amdgcn_readlane((int)(incl - c), wave);
+            tot[b] = (uint32_t)__builtin_amdgcn_readlane((int)incl, SS_WAVES - 1);
+            any |= __builtin_amdgcn_ballot_w64(c > wave_cap / 2) != 0;
             any |= last && tot[b] > 0;
         }
         __syncthreads();   // nobody publishes again before every thread has read the counts
@@ -456,15 +469,16 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
 template <int KF, int B>
 int launch_stream(const icq_index *ix, const float *lut, int Q, const float *thr, uint32_t *cand_ids,
                   uint32_t *cand_count, int64_t cap, hipStream_t s) {
-    const size_t tab = sizeof(float) * KF * ICQ_LUT_W * 16 * B;
+    const size_t tab = sizeof(float) * KF * ICQ_LUT_W * ss_copies(KF, B) * B;
     const int threads = SS_THREADS;
     // ids one wavefront stages per query: 512 (32 KB per query) when the tables leave that much LDS
-    const uint32_t wave_cap = tab + 32768 * B <= 163840 - 256 ? 512 : 248;
+    uint32_t wave_cap = 512;
+    while (tab + sizeof(uint32_t) * B * SS_WAVES * wave_cap > 163840 - 512) wave_cap -= 8;   // 512: the static arrays
     const size_t lds = tab + sizeof(uint32_t) * B * SS_WAVES * wave_cap;
     static bool attr_set = false;
     if (!attr_set) {
         ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_stream_kernel<KF, B>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 163840 - 256));
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 163840 - 512));
         attr_set = true;
     }
     const int groups = (Q + B - 1) / B;
@@ -632,17 +646,23 @@ int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *t
         return icq_check_launch();
     }
 
-    if (ix->Kf <= 4 && Q <= 4) {
+    if (ix->Kf <= 4) {
+        // lanes = items, one pass over the fast sub-codes per group of B queries: B = 1 or 2 for one or
+        // two queries, B = 4 for every larger call that has neither grouping nor transposed tables
         int rc;
-        switch (ix->Kf * 2 + (Q >= 2 ? 1 : 0)) {
-            case 2: rc = launch_stream<1, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 3: rc = launch_stream<1, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 4: rc = launch_stream<2, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 5: rc = launch_stream<2, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 6: rc = launch_stream<3, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 7: rc = launch_stream<3, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 8: rc = launch_stream<4, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            default: rc = launch_stream<4, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+        switch (ix->Kf * 3 + (Q >= 3 ? 2 : Q >= 2 ? 1 : 0)) {
+            case 3: rc = launch_stream<1, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 4: rc = launch_stream<1, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 5: rc = launch_stream<1, 4>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 6: rc = launch_stream<2, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 7: rc = launch_stream<2, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 8: rc = launch_stream<2, 4>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 9: rc = launch_stream<3, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 10: rc = launch_stream<3, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 11: rc = launch_stream<3, 4>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 12: rc = launch_stream<4, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            case 13: rc = launch_stream<4, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
+            default: rc = launch_stream<4, 4>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
         }
         if (rc != ICQ_OK || !cand_part) return rc;
         const int bpq = (int)((cap + 255) / 256 < 256 ? (cap + 255) / 256 : 256);
