@@ -43,10 +43,9 @@ struct icq_index {
 // What a candidate list holds.
 enum icq_list_kind {
     ICQ_LIST_IDS = 0,          // item ids
-    ICQ_LIST_IDS_REC = 1,      // item ids, item records alongside in cand_rec
-    ICQ_LIST_POSITIONS = 2,    // grouped positions (ids through perm, records from items_grouped)
-    ICQ_LIST_KEYS = 3,         // stage 1 already wrote one 64-bit key (bits of D, id) per survivor
-    ICQ_LIST_DONE = 4          // stage 1 kept the nearest-neighbour lists itself and wrote the results
+    ICQ_LIST_POSITIONS = 1,    // grouped positions (ids through perm, records from items_grouped)
+    ICQ_LIST_KEYS = 2,         // stage 1 already wrote one 64-bit key (bits of D, id) per survivor
+    ICQ_LIST_DONE = 3          // stage 1 kept the nearest-neighbour lists itself and wrote the results
 };
 
 // Order-preserving bits of a float: u(a) < u(b) <=> a < b.
@@ -57,7 +56,7 @@ __device__ __forceinline__ uint32_t icq_order_bits(float x) {
 
 // Sub-buffers carved out of the caller's workspace for one query batch.
 struct icq_ws_layout {
-    size_t lut_off, lutT_off, ids_off, rec_off, count_off, keys_off, total;
+    size_t lut_off, ids_off, count_off, keys_off, total;
     int splits;                // stage-2 blocks per query
 };
 
@@ -77,14 +76,12 @@ int icq_launch_build_lut(const icq_index *ix, const float *queries, int Q, float
 // recomputes the full sum in stage 2 from the item records).
 // list_kind == nullptr: the list must hold item ids (public contract).  Otherwise the
 // scan picks the cheapest representation for stage 2 and reports it: finished keys in
-// cand_keys ([Q][cap], may be nullptr), grouped positions, or ids with each survivor's
-// item record written to cand_rec ([Q][cap][item_stride/4] words; may be nullptr).
+// cand_keys ([Q][cap], may be nullptr), grouped positions, or plain ids.
 // topk / out_ids / out_dist (may be nullptr): where the scan may write the final lists
 // itself (ICQ_LIST_DONE) when its grouped form covers stage 2 as well.
 int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
-                    uint32_t *cand_ids, float *cand_part, uint32_t *cand_rec,
-                    unsigned long long *cand_keys, int *list_kind, uint32_t *cand_count, int64_t cap,
-                    float *lutT, int topk, uint32_t *out_ids, float *out_dist, hipStream_t s);
+                    uint32_t *cand_ids, float *cand_part, unsigned long long *cand_keys, int *list_kind,
+                    uint32_t *cand_count, int64_t cap, int topk, uint32_t *out_ids, float *out_dist, hipStream_t s);
 // Grouped stage 1 fused with stage 2: the final lists when icq_group_fused() holds and
 // out_ids is given, else one 64-bit key per survivor in cand_keys.
 bool icq_group_fused(const icq_index *ix, int Q, int topk);
@@ -102,9 +99,9 @@ int icq_launch_group_scan(const icq_index *ix, const float *lut, int Q, const fl
                           hipStream_t s);
 int icq_group_build(icq_index *ix, hipStream_t s);
 // cand_part == nullptr: D is the full K-term sum; else D = cand_part + slow terms.
-// list_kind says what cand_ids (and cand_rec) hold, see icq_list_kind.
+// list_kind says what cand_ids holds, see icq_list_kind.
 int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32_t *cand_ids,
-                      const float *cand_part, const uint32_t *cand_rec, int list_kind,
+                      const float *cand_part, int list_kind,
                       const uint32_t *cand_count, int64_t cap, int topk, int splits,
                       unsigned long long *keys, uint32_t *out_ids, float *out_dist, hipStream_t s);
 

@@ -171,8 +171,7 @@ template <int WORDS>
 __global__ __launch_bounds__(RF_THREADS) void refine_dist_kernel(
     const uint8_t *__restrict__ items, int K, int Kf, const float *__restrict__ lut,
     const uint32_t *__restrict__ cand_ids, const float *__restrict__ cand_part,
-    const uint32_t *__restrict__ cand_rec, const uint32_t *__restrict__ cand_count, int64_t cap,
-    int blocks_per_query, u64 *__restrict__ keys) {
+    const uint32_t *__restrict__ cand_count, int64_t cap, int blocks_per_query, u64 *__restrict__ keys) {
     __shared__ float T[4 * WORDS * ICQ_LUT_W];
     constexpr int RW = WORDS;                         // words per item record
     const int q = blockIdx.x / blocks_per_query;
@@ -184,7 +183,6 @@ __global__ __launch_bounds__(RF_THREADS) void refine_dist_kernel(
     const int k0 = cand_part ? Kf : 0;
     const uint32_t *ids = cand_ids + (int64_t)q * cap;
     const float *part = cand_part ? cand_part + (int64_t)q * cap : nullptr;
-    const uint32_t *recs = cand_rec ? cand_rec + (int64_t)q * cap * RW : nullptr;
     u64 *out = keys + (int64_t)q * cap;
 
     // Loads are unconditional with the index clamped to the last candidate: without
@@ -222,10 +220,7 @@ __global__ __launch_bounds__(RF_THREADS) void refine_dist_kernel(
     for (int st = 0; st < 2; ++st) {
 #pragma unroll
         for (int j = 0; j < RD_PER; ++j) {
-            const u64 i = c0 + (u64)st * RD_STEP + j * RF_THREADS + tid;
-            const u64 ic = i < n ? i : n - 1;
-            const uint32_t *p = recs ? recs + (size_t)ic * RW
-                                     : reinterpret_cast<const uint32_t *>(items + (size_t)id[st][j] * (RW * 4));
+            const uint32_t *p = reinterpret_cast<const uint32_t *>(items + (size_t)id[st][j] * (RW * 4));
             if (RW == 1) {
                 rec[st][j][0] = p[0];
             } else if (RW == 2) {
@@ -509,13 +504,12 @@ int icq_refine_splits(const icq_index *ix, int Q, int64_t cap, int topk) {
 }
 
 int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32_t *cand_ids,
-                      const float *cand_part, const uint32_t *cand_rec, int list_kind,
+                      const float *cand_part, int list_kind,
                       const uint32_t *cand_count, int64_t cap, int topk, int splits, u64 *keys,
                       uint32_t *out_ids, float *out_dist, hipStream_t s) {
     if (Q == 0 || list_kind == ICQ_LIST_DONE) return ICQ_OK;
     const uint8_t *items = list_kind == ICQ_LIST_POSITIONS ? ix->items_grouped : ix->items;
     const uint32_t *perm = list_kind == ICQ_LIST_POSITIONS ? ix->perm : nullptr;
-    if (list_kind != ICQ_LIST_IDS_REC) cand_rec = nullptr;
     const unsigned grid = (unsigned)Q * (unsigned)splits;
     const size_t tab = sizeof(float) * (size_t)(cand_part ? ix->Ks : ix->K) * ICQ_LUT_W;
     if (use_select(ix, topk)) {
@@ -527,8 +521,7 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
         if (list_kind != ICQ_LIST_KEYS) {
 #define ICQ_RD_LAUNCH(W)                                                                          \
     refine_dist_kernel<W><<<dgrid, RF_THREADS, 0, s>>>(items, ix->K, ix->Kf, lut, cand_ids,       \
-                                                       cand_part, cand_rec, cand_count, cap, bpq, \
-                                                       cand_keys)
+                                                       cand_part, cand_count, cap, bpq, cand_keys)
         switch (ix->item_stride) {
             case 4: ICQ_RD_LAUNCH(1); break;
             case 8: ICQ_RD_LAUNCH(2); break;
@@ -578,6 +571,6 @@ ICQ_EXPORT int icq_refine(const icq_index *ix, const float *lut, int Q, const ui
         (!workspace || ((uintptr_t)workspace % ICQ_ALIGN) != 0 || workspace_bytes < L.total))
         return ICQ_ERR_WORKSPACE;
     u64 *keys = reinterpret_cast<u64 *>(static_cast<char *>(workspace) + L.keys_off);
-    return icq_launch_refine(ix, lut, Q, cand_ids, cand_part, nullptr, ICQ_LIST_IDS, cand_count, cap, topk,
+    return icq_launch_refine(ix, lut, Q, cand_ids, cand_part, ICQ_LIST_IDS, cand_count, cap, topk,
                              L.splits, keys, out_ids, out_dist, (hipStream_t)stream);
 }

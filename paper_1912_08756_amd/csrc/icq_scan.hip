@@ -3,16 +3,15 @@
 // codebooks only, compared with a per-query threshold; survivors are appended
 // to per-query candidate lists for stage 2.
 //
-// Two kernels share the contract:
-//   scan_batch_kernel  - lanes = queries.  A tile of 64 queries keeps its fast
-//       tables in LDS as [k][code][query]; a wavefront walks the items, the
-//       sub-code is wave-uniform, so every table read is one conflict-free
-//       256-byte LDS row.  One pass over the codes serves 64 queries.  It lists
-//       survivor ids only; crude distances are filled in afterwards for the
-//       listed ids when the caller wants them.
+// Item-by-item kernels (the form grouped by fast-code tuple lives in icq_group.hip):
+//   scan_stream_kernel - lanes = items, up to Kf = 4.  The tables of B = 1, 2 or 4
+//       queries sit in LDS replicated so that the lanes the LDS serves in one clock
+//       never share a bank; one pass over the fast sub-codes serves B queries.
 //   scan_items_kernel  - lanes = items.  Any Kf; the tables of a few queries
 //       sit in LDS as [query][k][code], each lane gathers with its own
 //       sub-codes held in registers, survivors are compacted with a ballot.
+// Both list survivor ids only; crude distances are filled in afterwards for the
+// listed ids when the caller wants them.
 #include "icq_internal.h"
 
 #include <math.h>
@@ -29,186 +28,6 @@ __device__ __forceinline__ uint32_t lane_id() {
 __global__ void zero_counts_kernel(uint32_t *__restrict__ cnt, int Q) {
     int q = blockIdx.x * blockDim.x + threadIdx.x;
     if (q < Q) cnt[q] = 0u;
-}
-
-// lutT[tile][k][code][lane] = lut[tile*64 + lane][k][code] for k < Kf; queries
-// beyond Q get +inf (never below any threshold).  Block = (tile, k), 256 threads.
-__global__ __launch_bounds__(256) void transpose_fast_lut_kernel(const float *__restrict__ lut,
-                                                                 int Q, int K, int Kf,
-                                                                 float *__restrict__ lutT) {
-    __shared__ float tile[64][65];
-    const int t = blockIdx.x, k = blockIdx.y;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int c0 = 0; c0 < ICQ_LUT_W; c0 += 64) {
-        for (int r = ty; r < 64; r += 4) {
-            int q = t * 64 + r;
-            tile[r][tx] = q < Q ? lut[((int64_t)q * K + k) * ICQ_LUT_W + c0 + tx] : INFINITY;
-        }
-        __syncthreads();
-        for (int c = ty; c < 64; c += 4)
-            lutT[(((int64_t)t * Kf + k) * ICQ_LUT_W + c0 + c) * 64 + tx] = tile[tx][c];
-        __syncthreads();
-    }
-}
-
-// ------------------------------------------------------------------ lanes = queries
-constexpr int SB_WAVES = 16;                // wavefronts per block (4 per SIMD: the loop is issue-bound)
-constexpr int SB_THREADS = SB_WAVES * 64;
-constexpr int SB_SLOTS = 8;                 // staged survivor ids per lane
-constexpr int SB_GROUP = 256;               // items per wavefront step (one dword per lane and row)
-constexpr int SB_WORDS = 2;                 // lane-words (4 items each) looked up together
-
-// Survivor ids are staged per wavefront and lane in LDS ([slot][lane]) and moved
-// to the query's global list in bulk.  When some lane's column is full the
-// wavefront pulls the staged ids into registers, reserves list space for them
-// with ONE atomic per lane, (REC_WORDS > 0: also starts the gather of each
-// survivor's item record) and goes on scanning; offsets and records are only
-// consumed when that batch is written out at the next flush, so the round trips
-// of the atomic and of the gathers overlap the scan, which keeps the memory
-// pipeline idle otherwise.  REC_WORDS > 0 hands stage 2 a contiguous
-// (id, record) list, so it does not have to gather at random itself.
-template <int KF, int REC_WORDS>
-__global__ __launch_bounds__(SB_THREADS, 1) void scan_batch_kernel(
-    const uint8_t *__restrict__ fast, int64_t Npad, uint32_t N, const float *__restrict__ lutT,
-    const float *__restrict__ thr, int Q, uint32_t *__restrict__ cand_ids,
-    uint32_t *__restrict__ cand_rec, const uint8_t *__restrict__ items,
-    uint32_t *__restrict__ cand_count, int64_t cap, uint32_t items_per_block) {
-    extern __shared__ float smem[];
-    constexpr int LUT_FLOATS = KF * ICQ_LUT_W * 64;
-    constexpr int RW = REC_WORDS > 0 ? REC_WORDS : 1;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tile = blockIdx.y;
-
-    {   // tile's tables -> LDS, straight copy
-        const float4 *src = reinterpret_cast<const float4 *>(lutT + (int64_t)tile * LUT_FLOATS);
-        float4 *dst = reinterpret_cast<float4 *>(smem);
-        for (int i = tid; i < LUT_FLOATS / 4; i += SB_THREADS) dst[i] = src[i];
-    }
-    __syncthreads();
-
-    const int q = tile * 64 + lane;
-    const float t = q < Q ? thr[q] : -INFINITY;
-    uint32_t *my_ids = cand_ids + (int64_t)q * cap;
-    uint32_t *my_rec = REC_WORDS > 0 ? cand_rec + (int64_t)q * cap * RW : nullptr;
-    uint32_t *const st0 = reinterpret_cast<uint32_t *>(smem + LUT_FLOATS) + wave * (SB_SLOTS * 64) + lane;
-    uint32_t *sp = st0;                     // next free slot of this lane's column
-    uint32_t pid[SB_SLOTS], prec[SB_SLOTS][RW];   // batch in flight
-    uint32_t pend_cnt = 0, pend_base = 0;
-
-    auto retire = [&]() {   // write the batch in flight to its reserved list range
-#pragma unroll
-        for (int s = 0; s < SB_SLOTS; ++s) {
-            if ((uint32_t)s < pend_cnt) {
-                const uint64_t slot = (uint64_t)pend_base + s;
-                if (slot < (uint64_t)cap) {
-                    my_ids[slot] = pid[s];
-                    if (REC_WORDS == 1) {
-                        my_rec[slot] = prec[s][0];
-                    } else if (REC_WORDS == 2) {
-                        *reinterpret_cast<uint2 *>(my_rec + slot * 2) = make_uint2(prec[s][0], prec[s][1 % RW]);
-                    } else if (REC_WORDS == 4) {
-                        *reinterpret_cast<uint4 *>(my_rec + slot * 4) =
-                            make_uint4(prec[s][0], prec[s][1 % RW], prec[s][2 % RW], prec[s][3 % RW]);
-                    }
-                }
-            }
-        }
-    };
-    auto flush = [&]() {
-        retire();
-        pend_cnt = (uint32_t)(sp - st0) >> 6;
-#pragma unroll
-        for (int s = 0; s < SB_SLOTS; ++s) {
-            if ((uint32_t)s < pend_cnt) {
-                pid[s] = st0[s * 64];
-                const uint8_t *r = items + (size_t)pid[s] * (RW * 4);
-                if (REC_WORDS == 1) {
-                    prec[s][0] = *reinterpret_cast<const uint32_t *>(r);
-                } else if (REC_WORDS == 2) {
-                    const uint2 v = *reinterpret_cast<const uint2 *>(r);
-                    prec[s][0] = v.x;
-                    prec[s][1 % RW] = v.y;
-                } else if (REC_WORDS == 4) {
-                    const uint4 v = *reinterpret_cast<const uint4 *>(r);
-                    prec[s][0] = v.x;
-                    prec[s][1 % RW] = v.y;
-                    prec[s][2 % RW] = v.z;
-                    prec[s][3 % RW] = v.w;
-                }
-            }
-        }
-        pend_base = 0;
-        if (pend_cnt > 0) pend_base = atomicAdd(&cand_count[q], pend_cnt);
-        sp = st0;
-    };
-
-    const uint32_t begin = blockIdx.x * items_per_block;
-    uint32_t end = begin + items_per_block;
-    if (end > N || end < begin) end = N;
-    // one opaque base index per table so that no per-read offset arithmetic is left
-    int tab[KF];
-#pragma unroll
-    for (int k = 0; k < KF; ++k) {
-        tab[k] = k * ICQ_LUT_W * 64 + lane;
-        asm volatile("" : "+v"(tab[k]));
-    }
-
-    uint32_t w[KF], wn[KF];
-    uint32_t g = begin + wave * SB_GROUP;
-    if (g < end) {
-#pragma unroll
-        for (int k = 0; k < KF; ++k)
-            w[k] = *reinterpret_cast<const uint32_t *>(fast + (int64_t)k * Npad + g + lane * 4);
-    }
-    for (; g < end; g += SB_WAVES * SB_GROUP) {
-        // Read ahead, unconditionally (rows are padded by more than one block step beyond
-        // N, so the group after the last one is still addressable): with a fixed number
-        // of loads in flight the wait below can leave exactly these outstanding.
-        const uint32_t gn = g + SB_WAVES * SB_GROUP;
-#pragma unroll
-        for (int k = 0; k < KF; ++k)
-            wn[k] = *reinterpret_cast<const uint32_t *>(fast + (int64_t)k * Npad + gn + lane * 4);
-        // Touch this group's code words here, once: the wait for their load then sits in
-        // straight-line code instead of inside the loop below, where it would also wait
-        // for the atomics and gathers a flush has just started.
-#pragma unroll
-        for (int k = 0; k < KF; ++k) asm volatile("" ::"v"(w[k]));
-        // lane-words holding items below `end` (a word = 4 consecutive items)
-        const int nl = (end - g + 3) / 4 < 64 ? (int)((end - g + 3) / 4) : 64;
-        for (int l = 0; l < nl; l += SB_WORDS) {
-            uint32_t s[KF][SB_WORDS];
-#pragma unroll
-            for (int k = 0; k < KF; ++k)
-#pragma unroll
-                for (int u = 0; u < SB_WORDS; ++u) s[k][u] = __builtin_amdgcn_readlane(w[k], l + u);
-            // all table reads of the step are issued before any result is used
-            float P[4 * SB_WORDS];
-#pragma unroll
-            for (int i = 0; i < 4 * SB_WORDS; ++i) {
-                P[i] = smem[tab[0] + (int)(((s[0][i >> 2] >> (8 * (i & 3))) & 0xffu) * 64)];
-#pragma unroll
-                for (int k = 1; k < KF; ++k)
-                    P[i] += smem[tab[k] + (int)(((s[k][i >> 2] >> (8 * (i & 3))) & 0xffu) * 64)];
-            }
-#pragma unroll
-            for (int i = 0; i < 4 * SB_WORDS; ++i) {
-                if (__builtin_amdgcn_ballot_w64(P[i] < t) != 0) {
-                    const uint32_t id = g + l * 4 + i;
-                    if (P[i] < t && id < end) {
-                        *sp = id;
-                        sp += 64;
-                    }
-                    if (__builtin_amdgcn_ballot_w64(sp == st0 + 64 * SB_SLOTS) != 0) flush();
-                }
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < KF; ++k) w[k] = wn[k];
-    }
-    flush();    // reserve for the last buffer ...
-    retire();   // ... and write it out
 }
 
 // cand_part[q][s] = sum_{k<Kf} lut[q][k][code_k(id)] for the listed survivors, in
@@ -319,6 +138,14 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
         for (int k = 0; k < KF; ++k)
             w[k] = *reinterpret_cast<const uint4 *>(fast + (int64_t)k * Npad + gs + lane * 16);
     };
+    // n staged ids of query b -> the query's list from slot `first` on
+    auto move_out = [&](int b, const uint32_t *src, uint32_t n, uint64_t first) {
+        uint32_t *dst = cand_ids + (int64_t)(qbase + b) * cap;
+        for (uint32_t i = lane; i < n; i += 64) {
+            const uint64_t slot = first + i;
+            if (slot < (uint64_t)cap) dst[slot] = src[i];
+        }
+    };
     // the 1024 items at g held in w: table sums, hit bits, staging
     auto process = [&](uint32_t g, const uint4 (&w)[KF]) {
         const uint32_t id0 = g + lane * 16;
@@ -393,11 +220,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
                     uint32_t gb = 0;
                     if (lane == 0) gb = atomicAdd(&cand_count[qbase + b], wc[b]);
                     gb = (uint32_t)__builtin_amdgcn_readfirstlane((int)gb);
-                    uint32_t *dst = cand_ids + (int64_t)(qbase + b) * cap;
-                    for (uint32_t i = lane; i < wc[b]; i += 64) {
-                        const uint64_t slot = (uint64_t)gb + i;
-                        if (slot < (uint64_t)cap) dst[slot] = mine_stage[i];
-                    }
+                    move_out(b, mine_stage, wc[b], gb);
                     wc[b] = 0;
                 }
                 if (hm[b] != 0) mine_stage[wc[b] + rank] = id0 + (uint32_t)__builtin_ctz(hm[b]);
@@ -437,13 +260,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
         __syncthreads();
 #pragma unroll
         for (int b = 0; b < B; ++b) {
-            const uint32_t *src = stage + ((uint32_t)b * SS_WAVES + wave) * wave_cap;
-            uint32_t *dst = cand_ids + (int64_t)(qbase + b) * cap;
-            const uint64_t base = (uint64_t)s_base[b] + pre[b];
-            for (uint32_t i = lane; i < wc[b]; i += 64) {
-                const uint64_t slot = base + i;
-                if (slot < (uint64_t)cap) dst[slot] = src[i];
-            }
+            move_out(b, stage + ((uint32_t)b * SS_WAVES + wave) * wave_cap, wc[b], (uint64_t)s_base[b] + pre[b]);
             wc[b] = 0;
         }
         // the next publish of s_wcnt / s_base comes after at least one more barrier pair
@@ -562,50 +379,11 @@ __global__ __launch_bounds__(SI_THREADS) void scan_items_kernel(
     }
 }
 
-template <int KF, int REC_WORDS>
-int launch_batch(const icq_index *ix, int Q, const float *thr, uint32_t *cand_ids, uint32_t *cand_rec,
-                 uint32_t *cand_count, int64_t cap, const float *lutT, hipStream_t s) {
-    const int tiles = (Q + 63) / 64;
-    const size_t lds = sizeof(float) * KF * ICQ_LUT_W * 64 + sizeof(uint32_t) * SB_WAVES * SB_SLOTS * 64;
-    static bool attr_set = false;   // idempotent; a race only repeats the call
-    if (!attr_set) {
-        ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_batch_kernel<KF, REC_WORDS>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
-    // enough blocks to fill the chip ~8 times over, chunk a multiple of one block step
-    const uint32_t step = SB_WAVES * SB_GROUP;
-    int64_t chunks = (8LL * ix->num_cu + tiles - 1) / tiles;
-    int64_t max_chunks = (ix->N + step - 1) / step;
-    if (chunks > max_chunks) chunks = max_chunks;
-    if (chunks < 1) chunks = 1;
-    uint32_t per = (uint32_t)(((ix->N + chunks - 1) / chunks + step - 1) / step * step);
-    chunks = (ix->N + per - 1) / per;
-    dim3 grid((unsigned)chunks, (unsigned)tiles);
-    scan_batch_kernel<KF, REC_WORDS><<<grid, SB_THREADS, lds, s>>>(
-        ix->fast, ix->Npad, (uint32_t)ix->N, lutT, thr, Q, cand_ids, cand_rec, ix->items, cand_count,
-        cap, per);
-    return icq_check_launch();
-}
-
-template <int KF>
-int launch_batch_rec(const icq_index *ix, int Q, const float *thr, uint32_t *cand_ids,
-                     uint32_t *cand_rec, uint32_t *cand_count, int64_t cap, const float *lutT,
-                     hipStream_t s) {
-    if (!cand_rec) return launch_batch<KF, 0>(ix, Q, thr, cand_ids, nullptr, cand_count, cap, lutT, s);
-    switch (ix->item_stride) {
-        case 4: return launch_batch<KF, 1>(ix, Q, thr, cand_ids, cand_rec, cand_count, cap, lutT, s);
-        case 8: return launch_batch<KF, 2>(ix, Q, thr, cand_ids, cand_rec, cand_count, cap, lutT, s);
-        default: return launch_batch<KF, 4>(ix, Q, thr, cand_ids, cand_rec, cand_count, cap, lutT, s);
-    }
-}
-
 }  // namespace
 
 int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
-                    uint32_t *cand_ids, float *cand_part, uint32_t *cand_rec,
-                    unsigned long long *cand_keys, int *list_kind, uint32_t *cand_count, int64_t cap,
-                    float *lutT, int topk, uint32_t *out_ids, float *out_dist, hipStream_t s) {
+                    uint32_t *cand_ids, float *cand_part, unsigned long long *cand_keys, int *list_kind, uint32_t *cand_count, int64_t cap,
+                    int topk, uint32_t *out_ids, float *out_dist, hipStream_t s) {
     if (list_kind) *list_kind = ICQ_LIST_IDS;
     if (Q == 0) return ICQ_OK;
     zero_counts_kernel<<<(Q + 255) / 256, 256, 0, s>>>(cand_count, Q);
@@ -628,21 +406,6 @@ int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *t
         if (!cand_part) return ICQ_OK;
         fill_partials_kernel<<<(unsigned)Q * (unsigned)bpq_fill, 256, 0, s>>>(
             ix->fast, ix->Npad, lut, ix->K, ix->Kf, cand_ids, cand_count, cap, bpq_fill, cand_part);
-        return icq_check_launch();
-    }
-
-    if (ix->Kf <= 2 && Q >= 8) {
-        const int tiles = (Q + 63) / 64;
-        dim3 g((unsigned)tiles, (unsigned)ix->Kf);
-        transpose_fast_lut_kernel<<<g, 256, 0, s>>>(lut, Q, ix->K, ix->Kf, lutT);
-        if (ix->item_stride > 16 || !list_kind) cand_rec = nullptr;   // wide records stay with stage 2
-        int rc = ix->Kf == 1 ? launch_batch_rec<1>(ix, Q, thr, cand_ids, cand_rec, cand_count, cap, lutT, s)
-                             : launch_batch_rec<2>(ix, Q, thr, cand_ids, cand_rec, cand_count, cap, lutT, s);
-        if (list_kind && cand_rec) *list_kind = ICQ_LIST_IDS_REC;
-        if (rc != ICQ_OK || !cand_part) return rc;
-        const int bpq = (int)((cap + 255) / 256 < 32 ? (cap + 255) / 256 : 32);
-        fill_partials_kernel<<<(unsigned)Q * (unsigned)bpq, 256, 0, s>>>(
-            ix->fast, ix->Npad, lut, ix->K, ix->Kf, cand_ids, cand_count, cap, bpq, cand_part);
         return icq_check_launch();
     }
 
@@ -716,7 +479,6 @@ ICQ_EXPORT int icq_scan_fast(const icq_index *ix, const float *lut, int Q, const
     icq_ws_layout L = icq_layout(ix, Q, cap, 1, false, false);
     if (!workspace || ((uintptr_t)workspace % ICQ_ALIGN) != 0 || workspace_bytes < L.total)
         return ICQ_ERR_WORKSPACE;
-    float *lutT = reinterpret_cast<float *>(static_cast<char *>(workspace) + L.lutT_off);
-    return icq_launch_scan(ix, lut, Q, thresholds, cand_ids, cand_part, nullptr, nullptr, nullptr,
-                           cand_count, cap, lutT, 0, nullptr, nullptr, (hipStream_t)stream);
+    return icq_launch_scan(ix, lut, Q, thresholds, cand_ids, cand_part, nullptr, nullptr,
+                           cand_count, cap, 0, nullptr, nullptr, (hipStream_t)stream);
 }

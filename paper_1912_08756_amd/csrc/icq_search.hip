@@ -8,20 +8,13 @@ icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool
                          bool with_cands) {
     icq_ws_layout L;
     size_t off = 0;
-    const size_t tiles = ((size_t)Q + 63) / 64;
     L.lut_off = off;
     if (with_lut) off = icq_align_up(off + sizeof(float) * (size_t)Q * ix->K * ICQ_LUT_W, ICQ_ALIGN);
-    L.lutT_off = off;
-    off = icq_align_up(off + sizeof(float) * tiles * 64 * (size_t)(ix->Kf <= 2 ? ix->Kf : 0) * ICQ_LUT_W,
-                       ICQ_ALIGN);
     // icq_search with the grouped stage 1 owning whole queries keeps the candidates on chip:
     // no lists in the workspace at all
     const bool on_chip = with_cands && icq_group_fused(ix, Q, topk);
     L.ids_off = off;
     if (with_cands && !on_chip) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
-    L.rec_off = off;    // item records of the survivors (the fused path keeps no crude distances)
-    if (with_cands && ix->item_stride <= 16 && !icq_group_usable(ix, Q))
-        off = icq_align_up(off + (size_t)ix->item_stride * (size_t)Q * (size_t)cap, ICQ_ALIGN);
     L.count_off = off;
     if (with_cands) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q, ICQ_ALIGN);
     L.splits = icq_refine_splits(ix, Q, cap, topk);
@@ -83,7 +76,6 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
         const int nq = (Q - q0) < Qb ? (Q - q0) : Qb;
         const icq_ws_layout L = icq_layout(ix, nq, cap, topk, true, true);
         float *lut = reinterpret_cast<float *>(ws + L.lut_off);
-        float *lutT = reinterpret_cast<float *>(ws + L.lutT_off);
         uint32_t *ids = reinterpret_cast<uint32_t *>(ws + L.ids_off);
         uint32_t *cnt = out_survivors ? out_survivors + q0 : reinterpret_cast<uint32_t *>(ws + L.count_off);
         unsigned long long *keys = reinterpret_cast<unsigned long long *>(ws + L.keys_off);
@@ -91,16 +83,14 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
         int rc = icq_launch_build_lut(ix, queries + (int64_t)q0 * ix->d, nq, lut, s);
         if (rc != ICQ_OK) return rc;
         if (timed) ICQ_HIP_TRY(hipEventRecord(ev[1], s));
-        uint32_t *rec = (ix->item_stride <= 16 && !icq_group_usable(ix, nq))
-                            ? reinterpret_cast<uint32_t *>(ws + L.rec_off) : nullptr;
         int list_kind = ICQ_LIST_IDS;
         unsigned long long *cand_keys = (ix->item_stride <= 16 && topk <= 512 && !icq_group_fused(ix, nq, topk))
                                             ? icq_cand_keys(keys, nq, L.splits, topk) : nullptr;
-        rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, nullptr, rec, cand_keys, &list_kind, cnt,
-                             cap, lutT, topk, out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
+        rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, nullptr, cand_keys, &list_kind, cnt,
+                             cap, topk, out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
         if (rc != ICQ_OK) return rc;
         if (timed) ICQ_HIP_TRY(hipEventRecord(ev[2], s));
-        rc = icq_launch_refine(ix, lut, nq, ids, nullptr, rec, list_kind, cnt, cap, topk, L.splits, keys,
+        rc = icq_launch_refine(ix, lut, nq, ids, nullptr, list_kind, cnt, cap, topk, L.splits, keys,
                                out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
         if (rc != ICQ_OK) return rc;
         if (timed) ICQ_HIP_TRY(hipEventRecord(ev[3], s));
