@@ -486,18 +486,19 @@ def test_full_size_workload_sampled_against_oracle(gpu, mode):
 
 
 def test_stream_scan_at_full_length_properties(gpu):
-    """Streaming stage-1 kernel on a long code array (N = 2e7, Kf = 4, one and two queries
-    per pass): survivor sets against the oracle's crude distances, element by element
-    (the oracle finishes 2e7 items in seconds)."""
+    """Streaming stage-1 kernel on a long code array (N = 2e7, Kf = 4; one, two and four
+    queries per pass, the last with a ragged query group): survivor sets against the oracle's
+    crude distances, element by element (the oracle finishes 2e7 items in seconds)."""
     torch, b = gpu
-    cfg = synth.make("C4", N=20_000_003, Q=2, K=4)
+    cfg = synth.make("C4", N=20_000_003, Q=6, K=4)
     g = Gpu(gpu, cfg)
     T = orc.lut(cfg["codebooks"], cfg["queries"])
     P = orc.partial(T, cfg["codes"], 4)
     thr = thresholds_quantile(P, 0.01)
-    cap = 400_000
+    thr[4] = np.float32(np.quantile(P[4], 0.04))       # a denser list next to sparse ones
+    cap = 900_000
     lut = g.lut()
-    for nq in (1, 2):
+    for nq in (1, 2, 6):
         ids, part, cnt = g.scan(lut[:nq].contiguous(), thr[:nq], cap)
         ids, part, cnt = _u32(ids), part.cpu().numpy(), _u32(cnt)
         for q in range(nq):
