@@ -81,9 +81,9 @@ def event_time_ms(torch, fn, reps):
 
 
 def hbm_leg(torch, b, steps, warmup):
-    """Stage-1 scan of a 400 MB fast-code array (N = 1e8, Kf = 4) for one and for two
+    """Stage-1 scan of a 400 MB fast-code array (N = 1e8, Kf = 4) for one, two and four
     queries per pass: every code byte is read from HBM once per pass, so the kernel
-    is bound by the code stream."""
+    is bound by the code stream (with four queries the table reads weigh as much)."""
     from paper_1912_08756_amd import synth
     N, Kf, d = 100_000_000, 4, 96
     g = torch.Generator(device="cuda")
@@ -92,7 +92,7 @@ def hbm_leg(torch, b, steps, warmup):
     cb = torch.from_numpy(synth.make_codebooks(Kf, 256, d, synth.sigmas(("geom", 0.8), Kf), 4)).cuda()
     idx = b.icq_index_create(cb, codes, Kf)
     out = {}
-    for Q in (1, 2):
+    for Q in (1, 2, 4):
         src = codes[:, :Q].long()
         q = torch.stack([sum(cb[k, src[k, i]] for k in range(Kf)) for i in range(Q)]).contiguous()
         q = q + 0.05 * q.norm(dim=1, keepdim=True) / math.sqrt(d) * torch.randn((Q, d), device="cuda", generator=g)
@@ -115,7 +115,8 @@ def hbm_leg(torch, b, steps, warmup):
         achieved = alg_bytes / (ms * 1e-3) / 1e9
         out["B%d" % Q] = {"bound": "hbm", "kernel": "scan_stream_kernel<4,%d>" % Q, "achieved": round(achieved, 1),
                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                          "traffic": None, "ms": round(ms, 4),
+                          "traffic": (pmc_traffic("scan_stream_kernel_B%d" % Q) or {}).get("bytes"),
+                          "ms": round(ms, 4),
                           "workload": "fast codes [4][1e8] u8 (400 MB), %d quer%s per pass, %d survivors"
                                       % (Q, "y" if Q == 1 else "ies", surv)}
     return out
