@@ -191,15 +191,17 @@ __global__ __launch_bounds__(GS_THREADS) void group_scan_kernel(
 // ---- grouped stage 1 fused with stage 2
 constexpr int GD_HITS = 1024;     // tuples below the threshold handled per pass
 constexpr int GD_PER = GD_HITS / GS_THREADS;
-constexpr int GD_ROWS = 4;        // rows of 64 survivors per wavefront and step
+constexpr int GD_ROWS = 2;        // rows of 64 survivors per wavefront and step
 constexpr int GD_STEP = GD_ROWS * GS_THREADS;            // most keys one step can add to the list
-constexpr int GD_LIST = 2048;     // keys of the block's nearest-neighbour list
+constexpr int GD_LIST = 1024;     // keys of the block's nearest-neighbour list
 constexpr int GD_LPT = GD_LIST / GS_THREADS;             // list entries per thread in a cut
 constexpr int GD_SORT = 1024;     // most keys the final register sort takes
+constexpr int GD_TOPK = 256;      // longest result the on-chip list serves
 static_assert(GD_HITS <= 2048 && GD_HITS % GS_THREADS == 0, "tuple search covers 64 x 32 entries");
 static_assert(GS_THREADS == 256, "one histogram bin per thread");
 static_assert(GD_ROWS % 2 == 0, "a step is two half steps");
-static_assert(GD_LIST - GD_STEP >= 2 * 512, "room for topk <= 512 plus ties between two cuts");
+static_assert(GD_LIST - GD_STEP >= 2 * GD_TOPK, "room for the longest result plus as many ties between two cuts");
+static_assert(GD_LIST <= GD_SORT, "the final list fits the register sort");
 
 struct GdShared {
     IcqKthShared kth;
@@ -313,7 +315,7 @@ __device__ __forceinline__ uint32_t block_tie_cut(GdShared &sh, unsigned long lo
 // contiguous, so the loads coalesce) and adds up the K table entries (all K tables
 // of the query in LDS, k ascending, one table per record byte, zero tables beyond K).
 //
-// FUSED (the block owns its query: parts == 1): the nearest-neighbour list of Sec. 3.4
+// FUSED (the block owns its query: parts == 1, topk <= GD_TOPK): the nearest-neighbour list of Sec. 3.4
 // is kept right here.  A key (order-preserving bits of D, grouped position) enters the
 // block's list in LDS only if D is at or below the running bound; when the list could
 // overflow it is cut back to the topk smallest distances, which tightens the bound (one
@@ -325,7 +327,7 @@ __device__ __forceinline__ uint32_t block_tie_cut(GdShared &sh, unsigned long lo
 // written to slot base + number of the query's key list for the select kernel; each
 // pass reserves its slots with one atomic on the query's counter.
 template <int KF, int WORDS, bool FUSED>
-__global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8))) void group_keys_kernel(
+__global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(6, 8))) void group_keys_kernel(
     const float *__restrict__ lut, int K, const float *__restrict__ thr,
     const uint32_t *__restrict__ start, const uint8_t *__restrict__ items_grouped,
     const uint32_t *__restrict__ perm, unsigned long long *__restrict__ keys_out,
@@ -694,7 +696,7 @@ int icq_launch_group_scan(const icq_index *ix, const float *lut, int Q, const fl
 }
 
 bool icq_group_fused(const icq_index *ix, int Q, int topk) {
-    return icq_group_usable(ix, Q) && ix->item_stride <= 16 && topk <= 512 && group_parts(ix, Q) == 1;
+    return icq_group_usable(ix, Q) && ix->item_stride <= 16 && topk <= GD_TOPK && group_parts(ix, Q) == 1;
 }
 
 int icq_launch_group_keys(const icq_index *ix, const float *lut, int Q, const float *thr,

@@ -281,12 +281,13 @@ def test_search_matches_oracle(gpu, name, N, Q, over, rule, mode):
 # nearest-neighbour list on chip (no candidate list in memory): the cases below run that form.
 @pytest.mark.parametrize("name,N,Q,over,rule,topk", [
     ("C1", 70_000, 600, {}, ("q", 0.01), 100),              # about one item per fast-code tuple
-    ("C1", 40_000, 512, {}, ("q", 0.02), 128),              # fewer items than tuples; longest on-chip list
+    ("C1", 40_000, 512, {}, ("q", 0.02), 128),              # fewer items than tuples
     ("C0", 70_000, 520, {}, ("q", 0.02), 10),               # Kf = 1: 256 tuples of ~270 items, 4-byte records
     ("C3", 150_000, 512, {}, ("q", 0.01), 100),             # clustered codes: a few huge tuples, bursts
     ("C2", 60_000, 512, dict(d=32, Kf=2), ("q", 0.01), 100),  # K = 16: 16-byte records
     ("C1", 60_000, 512, {}, ("q", 0.25), 100),              # many surviving tuples: several passes per query
     ("C1", 3_000, 512, {}, ("kth", 3, 1.0), 100),           # fewer survivors than topk
+    ("C1", 50_000, 512, {}, ("q", 0.03), 256),              # longest on-chip list: final order by the register sort
 ])
 def test_search_with_lists_kept_on_chip(gpu, name, N, Q, over, rule, topk):
     cfg = small(name, N, Q, **over)
@@ -296,9 +297,9 @@ def test_search_with_lists_kept_on_chip(gpu, name, N, Q, over, rule, topk):
     thr[5] = np.inf
     thr[11] = np.nan
     ids2, dist2, surv2 = _check_search(g, cfg, T, P, D, thr, topk, N)
-    # the item-by-item form agrees to the bit, and so do the leading rows of a longer on-chip list
-    # (300: ordered by the register sort) and of one too long to keep on chip (513: position lists
-    # and the generic stage-2 kernel)
+    # the item-by-item form agrees to the bit, and so do the leading rows of lists too long to keep
+    # on chip (300: one key per survivor to the select kernel; 513: position lists and the generic
+    # stage-2 kernel)
     ids1, dist1, surv1 = Gpu(gpu, cfg, 1).search(thr, N, topk)
     assert np.array_equal(surv2, surv1) and np.array_equal(ids2, ids1) and np.array_equal(dist2, dist1)
     for longer in (300, 513):
