@@ -486,6 +486,40 @@ def test_full_size_workload_sampled_against_oracle(gpu, mode):
         check_candidates(P[r], thr[q], _u32(ids[q]), part[q].cpu().numpy(), int(_u32(cnt)[q]), cap)
 
 
+@pytest.mark.parametrize("name,Q,n_check", [
+    ("C2", None, 8),       # d = 960, K = 16, Kf = 4, N = 1e6, all 1000 queries in one call
+    ("C3", 256, 6),        # N = 1e7 clustered codes, one batch of 256 queries (grouped, several blocks per query)
+    ("C4", 128, 3),        # N = 1e8 (1.6 GB of codes), K = 16, Kf = 4, one batch of 128 queries
+])
+def test_other_configs_at_full_size_sampled_against_oracle(gpu, name, Q, n_check):
+    """The remaining benchmark shapes at their full N, one icq_search call per query batch with
+    thresholds from the library's own sampled quantile (1 %): properties for every query, the
+    oracle element by element on a few queries."""
+    import bench
+    torch, b = gpu
+    cfg = synth.make(name, Q=Q)
+    N, Q, Kf, topk = cfg["N"], cfg["queries"].shape[0], cfg["Kf"], cfg["topk"]
+    g = Gpu(gpu, cfg)
+    thr = bench.sampled_thresholds(torch, b, g.cb, g.codes, g.queries, Kf, 0.01, 16384, cfg["seed"]).cpu().numpy()
+    cap = int(N * 0.02)
+    out_ids, out_dist, surv = g.search(thr, cap, topk)
+    assert (surv <= cap).all() and (surv >= topk).all()
+    assert (out_ids < N).all()
+    assert (np.diff(out_dist, axis=1) >= 0).all(), "distances not ascending"
+    srt = np.sort(out_ids, axis=1)
+    assert (np.diff(srt.astype(np.int64), axis=1) > 0).all(), "duplicate ids in a result"
+    assert 0.005 * N < surv.mean() < 0.02 * N
+    sample = np.linspace(0, Q - 1, n_check).astype(int)
+    T = orc.lut(cfg["codebooks"], cfg["queries"][sample])
+    for r, q in enumerate(sample):          # one query at a time: P and D are N doubles each
+        P = orc.partial(T[r:r + 1], cfg["codes"], Kf)[0]
+        D = orc.partial(T[r:r + 1], cfg["codes"], cfg["K"])[0]    # all K terms, k ascending: the full distance
+        band = ((P >= thr[q] - tol(thr[q])) & (P <= thr[q] + tol(thr[q]))).sum()
+        exact = int((P < np.float64(thr[q])).sum())
+        assert abs(int(surv[q]) - exact) <= band
+        check_topk(P, D, thr[q], topk, out_ids[q], out_dist[q])
+
+
 def test_stream_scan_at_full_length_properties(gpu):
     """Streaming stage-1 kernel on a long code array (N = 2e7, Kf = 4; one, two and four
     queries per pass, the last with a ragged query group): survivor sets against the oracle's
