@@ -22,8 +22,11 @@
  * infinite margin == exhaustive ADC, a margin above the spread of the slow
  * terms loses nothing, a margin of -inf keeps the first topk items, closed
  * forms on items visited in ascending order of distance, and a hand-worked
- * trace; for the sample threshold and the operation counts: closed forms.  No
- * function here is unpinned.
+ * trace; for the sample threshold and the operation counts: closed forms; for
+ * the greedy encoding: K = 1 is the plain nearest codeword, disjoint supports
+ * give the sub-vector assignment and the brute-force optimum over all code
+ * combinations, reconstructions encode back to their own codes.  No function
+ * here is unpinned.
  *
  * Conventions: codebooks [K][m][d] float; codes [K][N] uint8, codebook-major,
  * rows 0..Kf-1 are the fast codebooks; T [Q][K][m] double; ids are uint32;
@@ -284,6 +287,52 @@ void icq_oracle_op_counts(int64_t N, int K, int Kf, int Q, const int64_t *refine
     summary[1] = (double)N * (double)K;
     summary[2] = summary[1] > 0.0 ? summary[0] / summary[1] : 0.0;
     summary[3] = code_bits * summary[2];
+}
+
+/* Encoding (the step before the search path, Sec. 1: an item is stored as one
+ * codeword index per codebook so that xbar_i = sum_k c_{k,code_k(i)}).  The
+ * paper gives no assignment algorithm; this build takes the greedy residual
+ * assignment in codebook order:
+ *     r_0 = x_i;   code_k(i) = argmin_j || r_k - c_{k,j} ||^2  (ties: smallest j);
+ *     r_{k+1} = r_k - c_{k,code_k(i)}.
+ * On codebooks with pairwise-disjoint supports (the ICQ zero pattern taken to
+ * its limit) a codeword only touches its own coordinates, so every step is the
+ * exact nearest codeword in its subspace and the result minimises
+ * ||x_i - xbar_i||^2 over all code combinations.  x [N][d] float;
+ * codes_out [K][N]; err_out [N] (may be NULL) = ||r_K||^2 = ||x_i - xbar_i||^2. */
+void icq_oracle_encode(const float *codebooks, int K, int m, int d, const float *x,
+                       int64_t N, uint8_t *codes_out, double *err_out)
+{
+#pragma omp parallel
+    {
+        double *r = (double *)malloc(sizeof(double) * (size_t)d);
+#pragma omp for schedule(static)
+        for (int64_t i = 0; i < N; ++i) {
+            for (int e = 0; e < d; ++e) r[e] = (double)x[(size_t)i * d + e];
+            for (int k = 0; k < K; ++k) {
+                int best = 0;
+                double best_s = INFINITY;
+                for (int j = 0; j < m; ++j) {
+                    const float *c = codebooks + ((size_t)k * m + j) * d;
+                    double s = 0.0;
+                    for (int e = 0; e < d; ++e) {
+                        double diff = r[e] - (double)c[e];
+                        s += diff * diff;
+                    }
+                    if (s < best_s) { best_s = s; best = j; }
+                }
+                codes_out[(size_t)k * N + i] = (uint8_t)best;
+                const float *c = codebooks + ((size_t)k * m + best) * d;
+                for (int e = 0; e < d; ++e) r[e] -= (double)c[e];
+            }
+            if (err_out) {
+                double s = 0.0;
+                for (int e = 0; e < d; ++e) s += r[e] * r[e];
+                err_out[i] = s;
+            }
+        }
+        free(r);
+    }
 }
 
 /* Reconstruction (Sec. 1): xbar_i = sum_k c_{k, code_k(i)} for the listed items. */

@@ -51,9 +51,10 @@ def _load():
         lib.icq_oracle_running_search.argtypes = [c_d, i, i, c_u8, i64, i, i, c_d, i, c_u32, c_d, c_i64]
         lib.icq_oracle_sample_thresholds.argtypes = [c_d, i, i, c_u8, i64, i, i, c_d, i, i64, c_d]
         lib.icq_oracle_op_counts.argtypes = [i64, i, i, i, c_i64, ctypes.c_double, c_d, c_d]
+        lib.icq_oracle_encode.argtypes = [c_f, i, i, i, c_f, i64, c_u8, c_d]
         lib.icq_oracle_threads.restype = i
         for name in ("lut", "partial", "search", "adc_exhaustive", "reconstruct", "bruteforce_knn",
-                     "running_search", "sample_thresholds", "op_counts"):
+                     "running_search", "sample_thresholds", "op_counts", "encode"):
             getattr(lib, "icq_oracle_" + name).restype = None
         _lib = lib
     return _lib
@@ -172,6 +173,19 @@ def op_counts(N, K, Kf, refined, code_bits):
     _load().icq_oracle_op_counts(N, K, Kf, Q, _p(rf, ctypes.c_int64), float(code_bits),
                                  _p(ops, ctypes.c_double), _p(summary, ctypes.c_double))
     return ops, summary
+
+
+def encode(codebooks, x, want_err=False):
+    """Greedy residual encoding in codebook order.  x [N][d] -> codes [K][N] u8 (and ||x - xbar||^2 [N])."""
+    K, m, d = codebooks.shape
+    cb = _chk(codebooks, np.float32, (K, m, d))
+    N = x.shape[0]
+    xs = _chk(x, np.float32, (N, d))
+    codes = np.empty((K, N), dtype=np.uint8)
+    err = np.empty((N,), dtype=np.float64) if want_err else None
+    _load().icq_oracle_encode(_p(cb, ctypes.c_float), K, m, d, _p(xs, ctypes.c_float), N,
+                              _p(codes, ctypes.c_uint8), _p(err, ctypes.c_double))
+    return (codes, err) if want_err else codes
 
 
 def reconstruct(codebooks, codes, items):

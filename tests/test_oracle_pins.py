@@ -437,3 +437,50 @@ def test_op_counts_closed_forms():
     assert (ops == N * Kf).all() and s[2] == Kf / K and s[3] == 64.0 * Kf / K
     ops, s = orc.op_counts(N, K, Kf, np.array([10, 30]), 64.0)
     assert np.array_equal(ops, [N * Kf + 60, N * Kf + 180]) and s[0] == N * Kf + 120
+
+
+# ================================================================ greedy encoding
+def test_encode_with_one_codebook_is_the_nearest_codeword():
+    g = _rng(31)
+    cb = g.standard_normal((1, 200, 9)).astype(np.float32)
+    x = g.standard_normal((500, 9)).astype(np.float32)
+    codes, err = orc.encode(cb, x, want_err=True)
+    d2 = ((x.astype(np.float64)[:, None, :] - cb[0].astype(np.float64)[None, :, :]) ** 2).sum(axis=2)
+    assert np.array_equal(codes[0], d2.argmin(axis=1))
+    assert np.allclose(err, d2.min(axis=1), rtol=1e-12, atol=0)
+
+
+def test_encode_on_disjoint_supports_is_the_subvector_assignment_and_the_global_optimum():
+    g = _rng(32)
+    K, m, d, N = 3, 4, 7, 40
+    cb, groups = disjoint_support_codebooks(g, K, m, d)
+    x = g.standard_normal((N, d)).astype(np.float32)
+    codes, err = orc.encode(cb, x, want_err=True)
+    # (a) per codebook: nearest codeword within its own coordinates (product-quantization assignment)
+    for k in range(K):
+        sub = x.astype(np.float64)[:, groups[k]]
+        cw = cb[k].astype(np.float64)[:, groups[k]]
+        assert np.array_equal(codes[k], ((sub[:, None, :] - cw[None, :, :]) ** 2).sum(axis=2).argmin(axis=1))
+    # (b) brute force over all m^K code combinations: nothing reconstructs x better
+    best = np.full(N, np.inf)
+    cb64 = cb.astype(np.float64)
+    for j0 in range(m):
+        for j1 in range(m):
+            for j2 in range(m):
+                rec = cb64[0, j0] + cb64[1, j1] + cb64[2, j2]
+                best = np.minimum(best, ((x.astype(np.float64) - rec) ** 2).sum(axis=1))
+    assert np.allclose(err, best, rtol=1e-12, atol=1e-15)
+    # (c) the error it reports is ||x - reconstruction||^2
+    rec = orc.reconstruct(cb, codes, np.arange(N))
+    assert np.allclose(err, ((x.astype(np.float64) - rec) ** 2).sum(axis=1), rtol=1e-12, atol=1e-15)
+
+
+def test_encode_returns_the_codes_of_a_reconstruction():
+    g = _rng(33)
+    K, m, d, N = 5, 256, 40, 300
+    cb, _ = disjoint_support_codebooks(g, K, m, d)
+    codes = g.integers(0, m, size=(K, N), dtype=np.uint8)
+    x = orc.reconstruct(cb, codes, np.arange(N)).astype(np.float32)    # exact: supports are disjoint
+    again, err = orc.encode(cb, x, want_err=True)
+    assert np.array_equal(again, codes)
+    assert (err == 0).all()
