@@ -213,6 +213,22 @@ int icq_sample_thresholds(const icq_index *index, const float *lut, int Q, const
 int icq_op_counts(const icq_index *index, const uint32_t *refined, int Q, unsigned long long *ops_out,
                   double *summary_out, void *stream);
 
+/*
+ * Encoding, the step before the search path (Sec. 1: an item is stored as one
+ * codeword index per codebook, xbar_i = sum_k c_{k,code_k(i)}).  The paper
+ * gives no assignment algorithm; this is the greedy residual assignment in
+ * codebook order:  r_0 = x_i;  code_k(i) = argmin_j ||r_k - c_{k,j}||^2
+ * (ties: smallest j);  r_{k+1} = r_k - c_{k,code_k(i)}.  On codebooks with
+ * pairwise-disjoint supports every step is the exact nearest codeword in its
+ * subspace.  Scores are formed in fp32 on the matrix cores.
+ * index: any index over the codebooks (it may hold no items: N = 0 at create).
+ * x [N][d] fp32, codes_out [K][N] (the layout icq_index_create takes),
+ * workspace of icq_encode_workspace_bytes(index, N) bytes (the residuals).
+ */
+int icq_encode_workspace_bytes(const icq_index *index, int64_t N, size_t *out /*host*/);
+int icq_encode(const icq_index *index, const float *x, int64_t N, uint8_t *codes_out, void *workspace,
+               size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

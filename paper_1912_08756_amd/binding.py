@@ -34,6 +34,8 @@ SIGNATURES = {
     "icq_search": (_i, [_vp, _vp, _i, _vp, _i64, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "icq_sample_thresholds": (_i, [_vp, _vp, _i, _vp, _i, _i64, _vp, _vp]),
     "icq_op_counts": (_i, [_vp, _vp, _i, _vp, _vp, _vp]),
+    "icq_encode_workspace_bytes": (_i, [_vp, _i64, ctypes.POINTER(_sz)]),
+    "icq_encode": (_i, [_vp, _vp, _i64, _vp, _vp, _sz, _vp]),
 }
 _lib = None
 
@@ -203,3 +205,18 @@ def icq_op_counts(index, refined, ops_out, summary_out):
     _check(load().icq_op_counts(index.handle, _dev(refined, torch.int32, (Q,), "refined"), Q,
                                 _dev(ops_out, torch.int64, (Q,), "ops_out"),
                                 _dev(summary_out, torch.float64, (4,), "summary_out"), _stream()), "icq_op_counts")
+
+
+def icq_encode_workspace_bytes(index, N):
+    out = ctypes.c_size_t(0)
+    _check(load().icq_encode_workspace_bytes(index.handle, N, ctypes.byref(out)), "icq_encode_workspace_bytes")
+    return int(out.value)
+
+
+def icq_encode(index, x, codes_out, workspace):
+    """x [N][d] f32, codes_out [K][N] u8 (device tensors)."""
+    N = x.shape[0]
+    _check(load().icq_encode(index.handle, _dev(x, torch.float32, (N, index.d), "x"), N,
+                             _dev(codes_out, torch.uint8, (index.K, N), "codes_out"),
+                             _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()),
+           "icq_encode")

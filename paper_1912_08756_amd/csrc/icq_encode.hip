@@ -1,0 +1,153 @@
+// Encoding, the step before the search path (arxiv 1912.08756, Sec. 1: an item is
+// stored as one codeword index per codebook, xbar_i = sum_k c_{k,code_k(i)}).  The
+// paper gives no assignment algorithm; this is the greedy residual assignment in
+// codebook order:
+//     r_0 = x_i;  code_k(i) = argmin_j ||r_k - c_{k,j}||^2 (ties: smallest j);
+//     r_{k+1} = r_k - c_{k,code_k(i)}.
+// ||r - c||^2 = ||r||^2 - 2<r,c> + ||c||^2 and ||r||^2 does not depend on j, so a level
+// is one [N x d].[d x 256] contraction on the fp32 matrix cores with the epilogue
+// argmin_j (||c_j||^2 - 2<r,c_j>), followed by the residual update of the block's own
+// rows.
+#include "icq_internal.h"
+
+#include <math.h>
+
+namespace {
+
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef unsigned long long u64;
+
+constexpr int EM = 64;            // items per block
+constexpr int EN = ICQ_LUT_W;     // codewords per level: the whole codebook (rows j >= m have norm +inf)
+constexpr int EK = 16;            // reduction slice staged in LDS
+constexpr int E_THREADS = 256;
+
+// One level for 64 items.  4 wavefronts, wavefront w owns codewords [64w, 64w + 64) as
+// 2x2 accumulators of 32x32 (MFMA 32x32x2 layout: lane l supplies A[l%32][l/32] and
+// B[l/32][l%32]; accumulator register v of lane l is C[(v%4) + 4*(l/32) + 8*(v/4)][l%32]).
+// src: x (row stride d, level 0) or the residuals (row stride d_pad); dst: residuals.
+__global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
+    const float *src, int src_stride, int d, const float *__restrict__ cb_k, int d_pad,
+    const float *__restrict__ cnorm_k, int64_t N, uint8_t *__restrict__ codes_k, float *res) {
+    __shared__ float As[EK][EM + 1];
+    __shared__ float Bs[EK][EN + 1];
+    __shared__ u64 best[E_THREADS / 64][EM];
+    __shared__ uint32_t s_code[EM];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t i0 = (int64_t)blockIdx.x * EM;
+    const int le = tid & 15, lr = tid >> 4;       // reduction position and row (+16 per pass) of the staging loads
+
+    float16v acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    for (int k0 = 0; k0 < d_pad; k0 += EK) {
+        float a[EM / 16], b[EN / 16];
+        const int e = k0 + le;
+#pragma unroll
+        for (int p = 0; p < EM / 16; ++p) {
+            const int64_t row = i0 + lr + 16 * p;
+            a[p] = (row < N && e < d) ? src[row * src_stride + e] : 0.0f;
+        }
+#pragma unroll
+        for (int p = 0; p < EN / 16; ++p) b[p] = cb_k[(int64_t)(lr + 16 * p) * d_pad + e];
+        __syncthreads();   // previous slice fully consumed
+#pragma unroll
+        for (int p = 0; p < EM / 16; ++p) As[le][lr + 16 * p] = a[p];
+#pragma unroll
+        for (int p = 0; p < EN / 16; ++p) Bs[le][lr + 16 * p] = b[p];
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < EK / 2; ++s) {
+            float av[2], bv[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                av[i] = As[2 * s + (lane >> 5)][i * 32 + (lane & 31)];
+                bv[i] = Bs[2 * s + (lane >> 5)][wave * 64 + i * 32 + (lane & 31)];
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    // argmin over the wavefront's 64 codewords for each of the 64 rows: key = (order-preserving bits
+    // of ||c||^2 - 2<r,c>, codeword index), the smaller key wins, so equal scores go to the smaller index
+    float cn[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) cn[j] = cnorm_k[wave * 64 + j * 32 + (lane & 31)];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            u64 key = ~0ull;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float score = cn[j] - 2.0f * acc[i][j][v];
+                const u64 kj = ((u64)icq_order_bits(score) << 32) | (uint32_t)(wave * 64 + j * 32 + (lane & 31));
+                key = kj < key ? kj : key;
+            }
+#pragma unroll
+            for (int dlt = 1; dlt < 32; dlt <<= 1) {
+                const u64 o = __shfl_xor(key, dlt, 64);
+                key = o < key ? o : key;
+            }
+            if ((lane & 31) == 0) best[wave][i * 32 + (v & 3) + 4 * (lane >> 5) + 8 * (v >> 2)] = key;
+        }
+    }
+    __syncthreads();
+    if (tid < EM) {
+        u64 key = best[0][tid];
+#pragma unroll
+        for (int w = 1; w < E_THREADS / 64; ++w) key = best[w][tid] < key ? best[w][tid] : key;
+        const uint32_t code = (uint32_t)key;
+        s_code[tid] = code;
+        if (i0 + tid < N) codes_k[i0 + tid] = (uint8_t)code;
+    }
+    __syncthreads();
+    // residual update of the block's rows (zero beyond d, so later levels can read whole slices)
+    for (int idx = tid; idx < EM * d_pad; idx += E_THREADS) {
+        const int r = idx / d_pad, e = idx % d_pad;
+        const int64_t row = i0 + r;
+        if (row < N) {
+            const float xv = e < d ? src[row * src_stride + e] : 0.0f;
+            res[row * d_pad + e] = xv - cb_k[(int64_t)s_code[r] * d_pad + e];
+        }
+    }
+}
+
+}  // namespace
+
+ICQ_EXPORT int icq_encode_workspace_bytes(const icq_index *ix, int64_t N, size_t *out) {
+    if (!ix || !out || N < 0 || N > ICQ_MAX_N) return ICQ_ERR_ARG;
+    const size_t need = sizeof(float) * (size_t)N * (size_t)ix->d_pad;
+    *out = need > ICQ_ALIGN ? icq_align_up(need, ICQ_ALIGN) : ICQ_ALIGN;
+    return ICQ_OK;
+}
+
+ICQ_EXPORT int icq_encode(const icq_index *ix, const float *x, int64_t N, uint8_t *codes_out, void *workspace,
+                          size_t workspace_bytes, void *stream) {
+    if (!ix || N < 0 || N > ICQ_MAX_N) return ICQ_ERR_ARG;
+    if (N == 0) return ICQ_OK;
+    if (!x || !codes_out) return ICQ_ERR_ARG;
+    size_t need = 0;
+    (void)icq_encode_workspace_bytes(ix, N, &need);
+    if (!workspace || ((uintptr_t)workspace % ICQ_ALIGN) != 0 || workspace_bytes < need) return ICQ_ERR_WORKSPACE;
+    float *res = static_cast<float *>(workspace);
+    hipStream_t s = (hipStream_t)stream;
+    const unsigned blocks = (unsigned)((N + EM - 1) / EM);
+    for (int k = 0; k < ix->K; ++k) {
+        const float *src = k == 0 ? x : res;
+        const int stride = k == 0 ? ix->d : ix->d_pad;
+        // in place for k > 0: a block reads and writes only its own rows, and every read of a row
+        // (slices, then the update) precedes its write in program order behind a barrier
+        encode_level_kernel<<<blocks, E_THREADS, 0, s>>>(src, stride, ix->d, ix->cb + (size_t)k * ICQ_LUT_W * ix->d_pad,
+                                                         ix->d_pad, ix->cnorm + (size_t)k * ICQ_LUT_W, N,
+                                                         codes_out + (size_t)k * N, res);
+    }
+    return icq_check_launch();
+}

@@ -623,3 +623,67 @@ def test_op_counts_match_oracle(gpu):
     o_ops, o_sum = orc.op_counts(5_000, cfg["K"], cfg["Kf"], refined.astype(np.int64), cfg["K"] * 8.0)
     assert np.array_equal(ops.cpu().numpy(), o_ops.astype(np.int64))
     assert np.array_equal(summary.cpu().numpy(), o_sum)
+
+
+# ------------------------------------------------------------------ encoding
+def _check_encoding(cb, x, codes_gpu, codes_orc):
+    """Greedy choices level by level, given the GPU's own earlier choices: the chosen codeword must
+    be a nearest one of the residual up to the tolerance (fp32 scores may order near-ties differently)."""
+    K, m, d = cb.shape
+    cb64, r = cb.astype(np.float64), x.astype(np.float64).copy()
+    n = np.arange(x.shape[0])
+    for k in range(K):
+        d2 = (r * r).sum(axis=1)[:, None] - 2.0 * r @ cb64[k].T + (cb64[k] ** 2).sum(axis=1)[None, :]
+        chosen = d2[n, codes_gpu[k]]
+        best = d2.min(axis=1)
+        assert (chosen <= best + tol(best)).all(), "level %d: a clearly nearer codeword exists" % k
+        r -= cb64[k][codes_gpu[k]]
+    same = (codes_gpu == codes_orc).all(axis=0).mean()
+    assert same >= 0.98, same
+
+
+@pytest.mark.parametrize("K,m,d,N", [(8, 256, 128, 5_000), (4, 256, 32, 1_000), (16, 256, 96, 777),
+                                      (3, 100, 17, 130), (1, 256, 8, 64), (2, 7, 5, 1)])
+def test_encode_matches_oracle(gpu, K, m, d, N):
+    torch, b = gpu
+    rng = np.random.default_rng(K * 1000 + d)
+    cb = (rng.standard_normal((K, m, d)) * (0.6 ** np.arange(K))[:, None, None]).astype(np.float32)
+    src = rng.integers(0, m, size=(K, N))
+    x = sum(cb[k][src[k]] for k in range(K)) + 0.05 * rng.standard_normal((N, d)).astype(np.float32)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    index = b.icq_index_create(_dev(torch, cb), torch.empty((K, 0), dtype=torch.uint8, device="cuda"), min(2, K))
+    codes = torch.full((K, N), 255, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(b.icq_encode_workspace_bytes(index, N), dtype=torch.uint8, device="cuda")
+    b.icq_encode(index, _dev(torch, x), codes, ws)
+    torch.cuda.synchronize()
+    codes = codes.cpu().numpy()
+    assert (codes < m).all()
+    _check_encoding(cb, x, codes, orc.encode(cb, x))
+    with pytest.raises(b.IcqError):
+        b.icq_encode(index, _dev(torch, x), torch.empty((K, N), dtype=torch.uint8, device="cuda"), ws[:128])
+
+
+def test_encode_on_disjoint_supports_recovers_the_codes(gpu):
+    """Codebooks with pairwise-disjoint supports, vectors that are exact reconstructions: every
+    greedy step has a codeword at distance zero, so the codes come back bit for bit; an index
+    over the encoded items then reproduces them through the storage round trip."""
+    torch, b = gpu
+    rng = np.random.default_rng(77)
+    K, m, d, N = 8, 256, 64, 20_000
+    cb = np.zeros((K, m, d), dtype=np.float32)
+    groups = np.array_split(rng.permutation(d), K)
+    for k in range(K):
+        cb[k][:, groups[k]] = rng.standard_normal((m, len(groups[k]))).astype(np.float32)
+    codes = rng.integers(0, m, size=(K, N)).astype(np.uint8)
+    x = orc.reconstruct(cb, codes, np.arange(N)).astype(np.float32)
+    index = b.icq_index_create(_dev(torch, cb), torch.empty((K, 0), dtype=torch.uint8, device="cuda"), 2)
+    out = torch.empty((K, N), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(b.icq_encode_workspace_bytes(index, N), dtype=torch.uint8, device="cuda")
+    b.icq_encode(index, _dev(torch, x), out, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), codes)
+    full = b.icq_index_create(_dev(torch, cb), out, 2)
+    back = torch.empty((K, N), dtype=torch.uint8, device="cuda")
+    b.icq_index_export_codes(full, 2, back)
+    torch.cuda.synchronize()
+    assert np.array_equal(back.cpu().numpy(), codes)
