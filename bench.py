@@ -216,6 +216,40 @@ def policy_leg(torch, b, cfg, index, queries, step_args, steps, with_cpu):
     return out
 
 
+def encode_leg(torch, b, cfg, steps):
+    """Greedy residual encoding of N vectors of the workload's shape (reconstructions of random
+    codes plus 5 % noise, drawn on the GPU: input preparation).  One contraction [N x d].[d x 256]
+    per codebook on the fp32 matrix cores."""
+    K, d = cfg["K"], cfg["d"]
+    N = min(cfg["N"], 1 << 20)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    cb = torch.from_numpy(cfg["codebooks"]).cuda()
+    src = torch.randint(0, 256, (K, N), device="cuda", generator=g)
+    x = torch.zeros((N, d), dtype=torch.float32, device="cuda")
+    for k in range(K):
+        x += cb[k][src[k]]
+    x += 0.05 * x.norm(dim=1, keepdim=True) / math.sqrt(d) * torch.randn((N, d), device="cuda", generator=g)
+    index = b.icq_index_create(cb, torch.empty((K, 0), dtype=torch.uint8, device="cuda"), cfg["Kf"])
+    codes = torch.empty((K, N), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(b.icq_encode_workspace_bytes(index, N), dtype=torch.uint8, device="cuda")
+
+    def run():
+        b.icq_encode(index, x, codes, ws)
+    run()
+    torch.cuda.synchronize()
+    ms = event_time_ms(torch, run, max(3, steps))
+    same = float((codes == src.to(torch.uint8)).all(dim=0).float().mean().item())
+    d_pad = (d + 15) // 16 * 16
+    flops = 2.0 * N * K * 256 * d_pad
+    ach = flops / (ms * 1e-3) / 1e12
+    return {"bound": "mfma", "kernel": "encode_level_kernel", "achieved": round(ach, 2), "peak": 157.3,
+            "unit": "TFLOP/s", "frac": round(ach / 157.3, 4), "traffic": None, "ms": round(ms, 4),
+            "items_per_s": round(N / (ms * 1e-3), 1), "N": N, "codes_recovered_frac": round(same, 4),
+            "note": "%d launches (one per codebook); flops = 2*N*K*256*d_pad; fp32 inputs on "
+                    "v_mfma_f32_32x32x2_f32; each level also rewrites the N x d residuals" % K}
+
+
 def pmc_traffic(kernel):
     """HBM bytes per launch of `kernel` from the committed counter summary (two rocprofv3
     --pmc runs of this program, scaled by what the counters read for a copy of known
@@ -242,6 +276,7 @@ def main():
     ap.add_argument("--no-hbm-leg", action="store_true")
     ap.add_argument("--no-streamed-leg", action="store_true")
     ap.add_argument("--no-policy-leg", action="store_true")
+    ap.add_argument("--no-encode-leg", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB): the scale for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
@@ -379,6 +414,12 @@ def main():
         p = result["threshold_policy"]
         log("[bench] policy: thresholds %.3f ms, tables + policy + search %.3f ms, %.2f %% survive, ops ratio %.4f"
             % (p["ms_sample_thresholds"], p["ms_tables_policy_search"], 100 * p["survivors_frac"], p["ops_ratio"]))
+
+    if not args.no_encode_leg:
+        log("[bench] greedy encoding of vectors of the workload's shape")
+        result["encode"] = encode_leg(torch, b, cfg, max(3, args.steps // 4))
+        log("[bench] encode: %.3f ms for %d items, %.1f TFLOP/s" %
+            (result["encode"]["ms"], result["encode"]["N"], result["encode"]["achieved"]))
 
     if not args.no_hbm_leg:
         del ws
