@@ -25,8 +25,12 @@
  * trace; for the sample threshold and the operation counts: closed forms; for
  * the greedy encoding: K = 1 is the plain nearest codeword, disjoint supports
  * give the sub-vector assignment and the brute-force optimum over all code
- * combinations, reconstructions encode back to their own codes.  No function
- * here is unpinned.
+ * combinations, reconstructions encode back to their own codes; for the
+ * fast-set quantities: the online variance equals the variance of the
+ * concatenated batches, the two prior densities integrate to their weights and
+ * the skew-normal mean has its textbook value, a symmetric special case puts the
+ * boundary of psi at mu/2, codebooks built inside / outside psi are classified
+ * as such.  No function here is unpinned.
  *
  * Conventions: codebooks [K][m][d] float; codes [K][N] uint8, codebook-major,
  * rows 0..Kf-1 are the fast codebooks; T [Q][K][m] double; ids are uint32;
@@ -333,6 +337,99 @@ void icq_oracle_encode(const float *codebooks, int K, int m, int d, const float 
         }
         free(r);
     }
+}
+
+/* ---- quantities around the fast set (Sec. 3.1 - 3.4); none is on the search path ---- */
+
+/* Population mean and variance of a batch per dimension (what Sec. 3.2 calls the
+ * sample mean and variance of a batch), two passes.  x [n][d]. */
+void icq_oracle_batch_moments(const float *x, int64_t n, int d, double *mean, double *var)
+{
+    for (int e = 0; e < d; ++e) {
+        double s = 0.0;
+        for (int64_t i = 0; i < n; ++i) s += (double)x[(size_t)i * d + e];
+        const double mu = n > 0 ? s / (double)n : 0.0;
+        double v = 0.0;
+        for (int64_t i = 0; i < n; ++i) {
+            const double t = (double)x[(size_t)i * d + e] - mu;
+            v += t * t;
+        }
+        mean[e] = mu;
+        var[e] = n > 0 ? v / (double)n : 0.0;
+    }
+}
+
+/* Online estimate of the dataset variance from batch statistics (Sec. 3.2, the
+ * two update equations): with b the 1-based number of the batch just seen,
+ *   Lambda_b = Lambda_{b-1} + (Lambda_batch - Lambda_{b-1})/b + (1/b)(1 - 1/b)(M_batch - M_{b-1})^2
+ *   M_b      = M_{b-1} + (M_batch - M_{b-1})/b
+ * (b = 1 makes the state equal to the batch).  mean / var [d] are updated in place. */
+void icq_oracle_online_variance(double *mean, double *var, const double *batch_mean,
+                                const double *batch_var, int d, int64_t b)
+{
+    const double w = 1.0 / (double)b;
+    for (int e = 0; e < d; ++e) {
+        const double dm = batch_mean[e] - mean[e];
+        var[e] = var[e] + w * (batch_var[e] - var[e]) + w * (1.0 - w) * dm * dm;
+        mean[e] = mean[e] + w * dm;
+    }
+}
+
+/* High-variance subspace psi (Sec. 3.1): dimension i belongs to psi iff the minor,
+ * skew-normal mode of the prior explains its variance better than the major, zero-centred
+ * normal mode:  pi2 * SN(lambda_i; mu2, sigma2, alpha2) > pi1 * N(lambda_i; 0, sigma1), with
+ *   N(x; 0, s)       = exp(-x^2 / (2 s^2)) / (s sqrt(2 pi))
+ *   SN(x; mu, s, a)  = (2/s) phi(z) Phi(a z),  z = (x - mu)/s,  phi / Phi the standard normal
+ *                      density / distribution function.
+ * xi [d] = 1 inside psi, 0 outside (the vector xi of the paper); p_major / p_minor [d] (may be
+ * NULL) receive the two weighted densities. */
+void icq_oracle_subspace_mask(const double *lambda, int d, double pi1, double sigma1, double pi2,
+                              double mu2, double sigma2, double alpha2, uint8_t *xi,
+                              double *p_major, double *p_minor)
+{
+    const double inv_sqrt_2pi = 0.3989422804014327;
+    for (int i = 0; i < d; ++i) {
+        const double x = lambda[i];
+        const double pm = pi1 * inv_sqrt_2pi / sigma1 * exp(-0.5 * (x / sigma1) * (x / sigma1));
+        const double z = (x - mu2) / sigma2;
+        const double phi = inv_sqrt_2pi * exp(-0.5 * z * z);
+        const double Phi = 0.5 * erfc(-alpha2 * z / 1.4142135623730951);
+        const double pn = pi2 * 2.0 / sigma2 * phi * Phi;
+        xi[i] = pn > pm ? 1 : 0;
+        if (p_major) p_major[i] = pm;
+        if (p_minor) p_minor[i] = pn;
+    }
+}
+
+/* The fast set (Sec. 3.1, the definition after the joint objective): codebook k is fast iff
+ * EVERY one of its codewords has more norm inside psi than outside,
+ *   || c o (1 - xi) || < || c o xi ||.   fast [K] = 1 / 0. */
+void icq_oracle_fast_set(const float *codebooks, int K, int m, int d, const uint8_t *xi,
+                         uint8_t *fast)
+{
+    for (int k = 0; k < K; ++k) {
+        int all = 1;
+        for (int j = 0; j < m; ++j) {
+            const float *c = codebooks + ((size_t)k * m + j) * d;
+            double in = 0.0, out = 0.0;
+            for (int e = 0; e < d; ++e) {
+                const double v = (double)c[e] * (double)c[e];
+                if (xi[e]) in += v; else out += v;
+            }
+            if (!(out < in)) all = 0;
+        }
+        fast[k] = (uint8_t)all;
+    }
+}
+
+/* Margin of the crude comparison (Sec. 3.4, last equation; the constant of proportionality
+ * taken as 1, the index set read as the dimensions outside psi):  sigma = sum_{xi_i = 0} lambda_i. */
+double icq_oracle_margin(const double *lambda, const uint8_t *xi, int d)
+{
+    double s = 0.0;
+    for (int i = 0; i < d; ++i)
+        if (!xi[i]) s += lambda[i];
+    return s;
 }
 
 /* Reconstruction (Sec. 1): xbar_i = sum_k c_{k, code_k(i)} for the listed items. */

@@ -51,10 +51,18 @@ def _load():
         lib.icq_oracle_running_search.argtypes = [c_d, i, i, c_u8, i64, i, i, c_d, i, c_u32, c_d, c_i64]
         lib.icq_oracle_sample_thresholds.argtypes = [c_d, i, i, c_u8, i64, i, i, c_d, i, i64, c_d]
         lib.icq_oracle_op_counts.argtypes = [i64, i, i, i, c_i64, ctypes.c_double, c_d, c_d]
+        dbl = ctypes.c_double
+        lib.icq_oracle_batch_moments.argtypes = [c_f, i64, i, c_d, c_d]
+        lib.icq_oracle_online_variance.argtypes = [c_d, c_d, c_d, c_d, i, i64]
+        lib.icq_oracle_subspace_mask.argtypes = [c_d, i, dbl, dbl, dbl, dbl, dbl, dbl, c_u8, c_d, c_d]
+        lib.icq_oracle_fast_set.argtypes = [c_f, i, i, i, c_u8, c_u8]
+        lib.icq_oracle_margin.argtypes = [c_d, c_u8, i]
+        lib.icq_oracle_margin.restype = dbl
         lib.icq_oracle_encode.argtypes = [c_f, i, i, i, c_f, i64, c_u8, c_d]
         lib.icq_oracle_threads.restype = i
         for name in ("lut", "partial", "search", "adc_exhaustive", "reconstruct", "bruteforce_knn",
-                     "running_search", "sample_thresholds", "op_counts", "encode"):
+                     "running_search", "sample_thresholds", "op_counts", "encode",
+                     "batch_moments", "online_variance", "subspace_mask", "fast_set"):
             getattr(lib, "icq_oracle_" + name).restype = None
         _lib = lib
     return _lib
@@ -186,6 +194,52 @@ def encode(codebooks, x, want_err=False):
     _load().icq_oracle_encode(_p(cb, ctypes.c_float), K, m, d, _p(xs, ctypes.c_float), N,
                               _p(codes, ctypes.c_uint8), _p(err, ctypes.c_double))
     return (codes, err) if want_err else codes
+
+
+def batch_moments(x):
+    """Population mean and variance per dimension of x [n][d] -> (mean [d], var [d]) f64."""
+    n, d = x.shape
+    xs = _chk(x, np.float32, (n, d))
+    mean, var = np.empty(d), np.empty(d)
+    _load().icq_oracle_batch_moments(_p(xs, ctypes.c_float), n, d, _p(mean, ctypes.c_double), _p(var, ctypes.c_double))
+    return mean, var
+
+
+def online_variance(mean, var, batch_mean, batch_var, b):
+    """One step of the online variance estimate (batch number b, 1-based); returns new (mean, var)."""
+    d = mean.shape[0]
+    mean, var = _chk(mean, np.float64, (d,)).copy(), _chk(var, np.float64, (d,)).copy()
+    bm, bv = _chk(batch_mean, np.float64, (d,)), _chk(batch_var, np.float64, (d,))
+    _load().icq_oracle_online_variance(_p(mean, ctypes.c_double), _p(var, ctypes.c_double), _p(bm, ctypes.c_double),
+                                       _p(bv, ctypes.c_double), d, b)
+    return mean, var
+
+
+def subspace_mask(lam, pi1, sigma1, pi2, mu2, sigma2, alpha2, want_densities=False):
+    """xi [d] u8: 1 where the minor (skew-normal) mode wins; optionally the two weighted densities."""
+    d = lam.shape[0]
+    lm = _chk(lam, np.float64, (d,))
+    xi = np.empty(d, dtype=np.uint8)
+    pm = np.empty(d) if want_densities else None
+    pn = np.empty(d) if want_densities else None
+    _load().icq_oracle_subspace_mask(_p(lm, ctypes.c_double), d, pi1, sigma1, pi2, mu2, sigma2, alpha2,
+                                     _p(xi, ctypes.c_uint8), _p(pm, ctypes.c_double), _p(pn, ctypes.c_double))
+    return (xi, pm, pn) if want_densities else xi
+
+
+def fast_set(codebooks, xi):
+    K, m, d = codebooks.shape
+    cb = _chk(codebooks, np.float32, (K, m, d))
+    x = _chk(xi, np.uint8, (d,))
+    fast = np.empty(K, dtype=np.uint8)
+    _load().icq_oracle_fast_set(_p(cb, ctypes.c_float), K, m, d, _p(x, ctypes.c_uint8), _p(fast, ctypes.c_uint8))
+    return fast
+
+
+def margin(lam, xi):
+    d = lam.shape[0]
+    return float(_load().icq_oracle_margin(_p(_chk(lam, np.float64, (d,)), ctypes.c_double),
+                                           _p(_chk(xi, np.uint8, (d,)), ctypes.c_uint8), d))
 
 
 def reconstruct(codebooks, codes, items):

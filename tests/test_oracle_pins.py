@@ -484,3 +484,65 @@ def test_encode_returns_the_codes_of_a_reconstruction():
     again, err = orc.encode(cb, x, want_err=True)
     assert np.array_equal(again, codes)
     assert (err == 0).all()
+
+
+# ================================================================ quantities around the fast set
+def test_online_variance_equals_the_variance_of_the_concatenated_batches():
+    g = _rng(41)
+    d, n, B = 11, 37, 9
+    batches = [(g.standard_normal((n, d)) * g.uniform(0.2, 3.0, size=d) + g.uniform(-2, 2, size=d)).astype(np.float32)
+               for _ in range(B)]
+    mean, var = np.zeros(d), np.zeros(d)
+    for b, x in enumerate(batches, start=1):
+        bm, bv = orc.batch_moments(x)
+        assert np.allclose(bm, x.astype(np.float64).mean(axis=0), rtol=1e-13, atol=1e-15)
+        assert np.allclose(bv, x.astype(np.float64).var(axis=0), rtol=1e-12, atol=1e-15)
+        mean, var = orc.online_variance(mean, var, bm, bv, b)
+        allx = np.concatenate(batches[:b]).astype(np.float64)
+        assert np.allclose(mean, allx.mean(axis=0), rtol=1e-12, atol=1e-13)
+        assert np.allclose(var, allx.var(axis=0), rtol=1e-11, atol=1e-13)
+
+
+def test_prior_densities_integrate_to_their_weights_and_the_skew_normal_mean_is_textbook():
+    pi1, s1, pi2, mu2, s2, a2 = 0.8, 0.5, 0.2, 3.0, 1.2, -10.0
+    grid = np.linspace(-12.0, 12.0, 240_001)
+    xi, pm, pn = orc.subspace_mask(grid, pi1, s1, pi2, mu2, s2, a2, want_densities=True)
+    h = grid[1] - grid[0]
+    assert abs(pm.sum() * h - pi1) < 1e-9 and abs(pn.sum() * h - pi2) < 1e-9
+    delta = a2 / np.sqrt(1.0 + a2 * a2)
+    assert abs((grid * pn).sum() * h / pi2 - (mu2 + s2 * delta * np.sqrt(2.0 / np.pi))) < 1e-8
+    assert np.array_equal(xi, (pn > pm).astype(np.uint8))
+    # far left the major mode wins, around the minor mode's bulk the minor one does
+    assert xi[np.searchsorted(grid, 0.0)] == 0 and xi[np.searchsorted(grid, 2.5)] == 1
+
+
+def test_subspace_boundary_in_the_symmetric_special_case():
+    """alpha2 = 0 makes the skew normal a normal; with equal weights and equal widths
+    N(x; mu, s) > N(x; 0, s)  <=>  x > mu/2."""
+    lam = np.array([0.0, 0.7, 0.99, 1.01, 1.5, 4.0])
+    xi = orc.subspace_mask(lam, 0.5, 0.8, 0.5, 2.0, 0.8, 0.0)
+    assert np.array_equal(xi, [0, 0, 0, 1, 1, 1])
+
+
+def test_fast_set_and_margin_on_codebooks_built_inside_and_outside_psi():
+    g = _rng(42)
+    K, m, d = 5, 16, 12
+    xi = np.zeros(d, dtype=np.uint8)
+    xi[[1, 4, 5, 9]] = 1
+    cb = np.zeros((K, m, d), dtype=np.float32)
+    inside, outside = np.nonzero(xi)[0], np.nonzero(xi == 0)[0]
+    cb[0][:, inside] = g.standard_normal((m, inside.size))           # fast: all norm inside psi
+    cb[1][:, outside] = g.standard_normal((m, outside.size))         # slow
+    cb[2][:, inside] = g.standard_normal((m, inside.size))           # fast but for ONE codeword
+    cb[2][3] = 0.0
+    cb[2][3, outside[0]] = 1.0
+    cb[3] = g.standard_normal((m, d)).astype(np.float32)             # mostly outside: 8 of 12 dimensions
+    cb[3][:, inside] *= 0.01
+    cb[4][:, inside] = 3.0 * g.standard_normal((m, inside.size))     # mixed but dominated by psi
+    cb[4][:, outside] = 0.01 * g.standard_normal((m, outside.size))
+    assert np.array_equal(orc.fast_set(cb, xi), [1, 0, 0, 0, 1])
+    lam = g.uniform(0.1, 2.0, size=d)
+    assert orc.margin(lam, xi) == lam[outside[0]] + lam[outside[1:]].sum() or \
+        abs(orc.margin(lam, xi) - lam[outside].sum()) < 1e-15
+    assert orc.margin(lam, np.ones(d, dtype=np.uint8)) == 0.0
+    assert abs(orc.margin(lam, np.zeros(d, dtype=np.uint8)) - lam.sum()) < 1e-15
