@@ -229,6 +229,36 @@ int icq_encode_workspace_bytes(const icq_index *index, int64_t N, size_t *out /*
 int icq_encode(const icq_index *index, const float *x, int64_t N, uint8_t *codes_out, void *workspace,
                size_t workspace_bytes, void *stream);
 
+/*
+ * Quantities around the fast set (Sec. 3.1 - 3.4).  Small utilities, none on
+ * the search path; all arrays are device memory, variances and the prior are
+ * handled in double.
+ *
+ * icq_batch_moments: population mean and variance per dimension of a batch
+ *   x [n][d] fp32 (the batch statistics of Sec. 3.2).
+ * icq_online_variance_update: the two update equations of Sec. 3.2 for batch
+ *   number b (1-based), in place on mean / var [d]:
+ *     var  += (batch_var - var)/b + (1/b)(1 - 1/b)(batch_mean - mean)^2
+ *     mean += (batch_mean - mean)/b
+ * icq_subspace_mask: the vector xi of Sec. 3.1, xi_i = 1 iff
+ *     pi2 * SN(lambda_i; mu2, sigma2, alpha2) > pi1 * N(lambda_i; 0, sigma1)
+ *   (SN(x; mu, s, a) = (2/s) phi((x-mu)/s) Phi(a (x-mu)/s)); sigma1, sigma2 > 0.
+ * icq_fast_set: the defining condition of the fast set (Sec. 3.1): codebook k
+ *   is fast iff every one of its codewords c has ||c o (1-xi)|| < ||c o xi||.
+ *   xi [d], fast_out [K] (1 / 0).  The caller reorders the codebooks so that
+ *   the fast ones come first before it builds a search index.
+ * icq_margin: sigma of Sec. 3.4's last equation with proportionality constant
+ *   1, sigma_out[0] = sum of lambda_i over the dimensions with xi_i = 0: the
+ *   value icq_sample_thresholds takes as margin.
+ */
+int icq_batch_moments(const float *x, int64_t n, int d, double *mean_out, double *var_out, void *stream);
+int icq_online_variance_update(double *mean, double *var, const double *batch_mean, const double *batch_var,
+                               int d, int64_t b, void *stream);
+int icq_subspace_mask(const double *lambda, int d, double pi1, double sigma1, double pi2, double mu2,
+                      double sigma2, double alpha2, uint8_t *xi_out, void *stream);
+int icq_fast_set(const icq_index *index, const uint8_t *xi, uint8_t *fast_out, void *stream);
+int icq_margin(const double *lambda, const uint8_t *xi, int d, double *sigma_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -36,6 +36,11 @@ SIGNATURES = {
     "icq_op_counts": (_i, [_vp, _vp, _i, _vp, _vp, _vp]),
     "icq_encode_workspace_bytes": (_i, [_vp, _i64, ctypes.POINTER(_sz)]),
     "icq_encode": (_i, [_vp, _vp, _i64, _vp, _vp, _sz, _vp]),
+    "icq_batch_moments": (_i, [_vp, _i64, _i, _vp, _vp, _vp]),
+    "icq_online_variance_update": (_i, [_vp, _vp, _vp, _vp, _i, _i64, _vp]),
+    "icq_subspace_mask": (_i, [_vp, _i] + [ctypes.c_double] * 6 + [_vp, _vp]),
+    "icq_fast_set": (_i, [_vp, _vp, _vp, _vp]),
+    "icq_margin": (_i, [_vp, _vp, _i, _vp, _vp]),
 }
 _lib = None
 
@@ -220,3 +225,33 @@ def icq_encode(index, x, codes_out, workspace):
                              _dev(codes_out, torch.uint8, (index.K, N), "codes_out"),
                              _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()),
            "icq_encode")
+
+
+def icq_batch_moments(x, mean_out, var_out):
+    n, d = x.shape
+    _check(load().icq_batch_moments(_dev(x, torch.float32, name="x"), n, d, _dev(mean_out, torch.float64, (d,)),
+                                    _dev(var_out, torch.float64, (d,)), _stream()), "icq_batch_moments")
+
+
+def icq_online_variance_update(mean, var, batch_mean, batch_var, b):
+    d = mean.shape[0]
+    _check(load().icq_online_variance_update(_dev(mean, torch.float64, (d,)), _dev(var, torch.float64, (d,)),
+                                             _dev(batch_mean, torch.float64, (d,)), _dev(batch_var, torch.float64, (d,)),
+                                             d, b, _stream()), "icq_online_variance_update")
+
+
+def icq_subspace_mask(lam, pi1, sigma1, pi2, mu2, sigma2, alpha2, xi_out):
+    d = lam.shape[0]
+    _check(load().icq_subspace_mask(_dev(lam, torch.float64, (d,)), d, pi1, sigma1, pi2, mu2, sigma2, alpha2,
+                                    _dev(xi_out, torch.uint8, (d,)), _stream()), "icq_subspace_mask")
+
+
+def icq_fast_set(index, xi, fast_out):
+    _check(load().icq_fast_set(index.handle, _dev(xi, torch.uint8, (index.d,)), _dev(fast_out, torch.uint8, (index.K,)),
+                               _stream()), "icq_fast_set")
+
+
+def icq_margin(lam, xi, sigma_out):
+    d = lam.shape[0]
+    _check(load().icq_margin(_dev(lam, torch.float64, (d,)), _dev(xi, torch.uint8, (d,)), d,
+                             _dev(sigma_out, torch.float64, (1,)), _stream()), "icq_margin")

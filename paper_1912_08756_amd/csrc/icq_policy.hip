@@ -128,6 +128,100 @@ __global__ __launch_bounds__(1024) void op_counts_kernel(const uint32_t *__restr
     }
 }
 
+// ---- quantities around the fast set (Sec. 3.1 - 3.4); small, none on the search path
+
+// One block per dimension: population mean and variance of x[:, e], two passes, double.
+__global__ __launch_bounds__(256) void batch_moments_kernel(const float *__restrict__ x, long long n, int d,
+                                                            double *__restrict__ mean, double *__restrict__ var) {
+    __shared__ double part[256];
+    const int e = blockIdx.x, tid = threadIdx.x;
+    auto block_sum = [&](double v) {
+        __syncthreads();
+        part[tid] = v;
+        __syncthreads();
+        for (int s = 128; s > 0; s >>= 1) {
+            if (tid < s) part[tid] += part[tid + s];
+            __syncthreads();
+        }
+        return part[0];
+    };
+    double s = 0.0;
+    for (long long i = tid; i < n; i += 256) s += (double)x[i * d + e];
+    const double mu = n > 0 ? block_sum(s) / (double)n : 0.0;
+    double v = 0.0;
+    for (long long i = tid; i < n; i += 256) {
+        const double t = (double)x[i * d + e] - mu;
+        v += t * t;
+    }
+    const double vs = block_sum(v);
+    if (tid == 0) {
+        mean[e] = mu;
+        var[e] = n > 0 ? vs / (double)n : 0.0;
+    }
+}
+
+__global__ void online_variance_kernel(double *__restrict__ mean, double *__restrict__ var,
+                                       const double *__restrict__ bmean, const double *__restrict__ bvar, int d,
+                                       double w) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= d) return;
+    const double dm = bmean[e] - mean[e];
+    var[e] = var[e] + w * (bvar[e] - var[e]) + w * (1.0 - w) * dm * dm;
+    mean[e] = mean[e] + w * dm;
+}
+
+__global__ void subspace_mask_kernel(const double *__restrict__ lambda, int d, double pi1, double sigma1, double pi2,
+                                     double mu2, double sigma2, double alpha2, uint8_t *__restrict__ xi) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= d) return;
+    const double inv_sqrt_2pi = 0.3989422804014327;
+    const double x = lambda[i];
+    const double pm = pi1 * inv_sqrt_2pi / sigma1 * exp(-0.5 * (x / sigma1) * (x / sigma1));
+    const double z = (x - mu2) / sigma2;
+    const double phi = inv_sqrt_2pi * exp(-0.5 * z * z);
+    const double Phi = 0.5 * erfc(-alpha2 * z / 1.4142135623730951);
+    xi[i] = pi2 * 2.0 / sigma2 * phi * Phi > pm ? 1 : 0;
+}
+
+// One block per codebook, one wavefront per codeword at a time: norm inside / outside psi in double.
+__global__ __launch_bounds__(256) void fast_set_kernel(const float *__restrict__ cb, int m, int d, int d_pad,
+                                                       const uint8_t *__restrict__ xi, uint8_t *__restrict__ fast) {
+    __shared__ int s_bad;
+    const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) s_bad = 0;
+    __syncthreads();
+    for (int j = wave; j < m; j += 4) {
+        const float *c = cb + ((size_t)k * ICQ_LUT_W + j) * d_pad;
+        double in = 0.0, out = 0.0;
+        for (int e = lane; e < d; e += 64) {
+            const double v = (double)c[e] * (double)c[e];
+            if (xi[e]) in += v; else out += v;
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            in += __shfl_xor(in, off, 64);
+            out += __shfl_xor(out, off, 64);
+        }
+        if (lane == 0 && !(out < in)) atomicOr(&s_bad, 1);
+    }
+    __syncthreads();
+    if (tid == 0) fast[k] = s_bad ? 0 : 1;
+}
+
+__global__ __launch_bounds__(256) void margin_kernel(const double *__restrict__ lambda, const uint8_t *__restrict__ xi,
+                                                     int d, double *__restrict__ out) {
+    __shared__ double part[256];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < d; i += 256)
+        if (!xi[i]) s += lambda[i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+        if ((int)threadIdx.x < st) part[threadIdx.x] += part[threadIdx.x + st];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = part[0];
+}
+
 }  // namespace
 
 ICQ_EXPORT int icq_sample_thresholds(const icq_index *ix, const float *lut, int Q, const float *sigma,
@@ -161,5 +255,39 @@ ICQ_EXPORT int icq_op_counts(const icq_index *ix, const uint32_t *refined, int Q
     const double code_bits = (double)ix->K * log2((double)ix->m);
     op_counts_kernel<<<1, 1024, 0, (hipStream_t)stream>>>(refined, Q, (unsigned long long)ix->N, ix->K, ix->Kf,
                                                           code_bits, ops_out, summary_out);
+    return icq_check_launch();
+}
+
+ICQ_EXPORT int icq_batch_moments(const float *x, int64_t n, int d, double *mean_out, double *var_out, void *stream) {
+    if (n < 0 || d < 1 || d > (1 << 20) || !mean_out || !var_out || (n > 0 && !x)) return ICQ_ERR_ARG;
+    batch_moments_kernel<<<d, 256, 0, (hipStream_t)stream>>>(x, (long long)n, d, mean_out, var_out);
+    return icq_check_launch();
+}
+
+ICQ_EXPORT int icq_online_variance_update(double *mean, double *var, const double *batch_mean,
+                                          const double *batch_var, int d, int64_t b, void *stream) {
+    if (!mean || !var || !batch_mean || !batch_var || d < 1 || b < 1) return ICQ_ERR_ARG;
+    online_variance_kernel<<<(d + 255) / 256, 256, 0, (hipStream_t)stream>>>(mean, var, batch_mean, batch_var, d,
+                                                                             1.0 / (double)b);
+    return icq_check_launch();
+}
+
+ICQ_EXPORT int icq_subspace_mask(const double *lambda, int d, double pi1, double sigma1, double pi2, double mu2,
+                                 double sigma2, double alpha2, uint8_t *xi_out, void *stream) {
+    if (!lambda || !xi_out || d < 1 || !(sigma1 > 0.0) || !(sigma2 > 0.0)) return ICQ_ERR_ARG;
+    subspace_mask_kernel<<<(d + 255) / 256, 256, 0, (hipStream_t)stream>>>(lambda, d, pi1, sigma1, pi2, mu2, sigma2,
+                                                                           alpha2, xi_out);
+    return icq_check_launch();
+}
+
+ICQ_EXPORT int icq_fast_set(const icq_index *ix, const uint8_t *xi, uint8_t *fast_out, void *stream) {
+    if (!ix || !xi || !fast_out) return ICQ_ERR_ARG;
+    fast_set_kernel<<<ix->K, 256, 0, (hipStream_t)stream>>>(ix->cb, ix->m, ix->d, ix->d_pad, xi, fast_out);
+    return icq_check_launch();
+}
+
+ICQ_EXPORT int icq_margin(const double *lambda, const uint8_t *xi, int d, double *sigma_out, void *stream) {
+    if (!lambda || !xi || !sigma_out || d < 1) return ICQ_ERR_ARG;
+    margin_kernel<<<1, 256, 0, (hipStream_t)stream>>>(lambda, xi, d, sigma_out);
     return icq_check_launch();
 }

@@ -687,3 +687,58 @@ def test_encode_on_disjoint_supports_recovers_the_codes(gpu):
     b.icq_index_export_codes(full, 2, back)
     torch.cuda.synchronize()
     assert np.array_equal(back.cpu().numpy(), codes)
+
+
+# ------------------------------------------------------------------ quantities around the fast set
+def test_moments_online_variance_mask_fast_set_and_margin_match_oracle(gpu):
+    torch, b = gpu
+    rng = np.random.default_rng(12)
+    d, n, B = 96, 5_003, 4
+    scale = rng.uniform(0.05, 3.0, size=d)
+    mean = torch.zeros(d, dtype=torch.float64, device="cuda")
+    var = torch.zeros(d, dtype=torch.float64, device="cuda")
+    o_mean, o_var = np.zeros(d), np.zeros(d)
+    bm = torch.empty(d, dtype=torch.float64, device="cuda")
+    bv = torch.empty(d, dtype=torch.float64, device="cuda")
+    for step in range(1, B + 1):
+        x = (rng.standard_normal((n, d)) * scale + rng.uniform(-1, 1, size=d)).astype(np.float32)
+        b.icq_batch_moments(_dev(torch, x), bm, bv)
+        b.icq_online_variance_update(mean, var, bm, bv, step)
+        torch.cuda.synchronize()
+        om, ov = orc.batch_moments(x)
+        assert np.allclose(bm.cpu().numpy(), om, rtol=1e-11, atol=1e-13)
+        assert np.allclose(bv.cpu().numpy(), ov, rtol=1e-10, atol=1e-13)
+        o_mean, o_var = orc.online_variance(o_mean, o_var, om, ov, step)
+    lam = var.cpu().numpy()
+    assert np.allclose(mean.cpu().numpy(), o_mean, rtol=1e-10, atol=1e-12)
+    assert np.allclose(lam, o_var, rtol=1e-9, atol=1e-12)
+    # subspace mask from the bimodal prior
+    prior = (0.8, 0.6, 0.2, 5.0, 2.0, -10.0)
+    xi = torch.empty(d, dtype=torch.uint8, device="cuda")
+    b.icq_subspace_mask(var, *prior, xi)
+    torch.cuda.synchronize()
+    o_xi, pm, pn = orc.subspace_mask(lam, *prior, want_densities=True)
+    clear = np.abs(pn - pm) > 1e-9 * (pn + pm)
+    assert np.array_equal(xi.cpu().numpy()[clear], o_xi[clear]) and 0 < o_xi.sum() < d
+    # fast set of codebooks built inside / outside / across psi, and the margin
+    K, m = 6, 256
+    inside, outside = np.nonzero(o_xi)[0], np.nonzero(o_xi == 0)[0]
+    cb = np.zeros((K, m, d), dtype=np.float32)
+    cb[0][:, inside] = rng.standard_normal((m, inside.size))
+    cb[1][:, outside] = rng.standard_normal((m, outside.size))
+    cb[2][:, inside] = rng.standard_normal((m, inside.size))
+    cb[2][200] = 0.0
+    cb[2][200, outside[0]] = 0.5
+    cb[3] = rng.standard_normal((m, d)).astype(np.float32)
+    cb[4][:, inside] = 5.0 * rng.standard_normal((m, inside.size))
+    cb[4][:, outside] = 0.01 * rng.standard_normal((m, outside.size))
+    cb[5][:, outside] = rng.standard_normal((m, outside.size))
+    index = b.icq_index_create(_dev(torch, cb), torch.empty((K, 0), dtype=torch.uint8, device="cuda"), 1)
+    fast = torch.empty(K, dtype=torch.uint8, device="cuda")
+    b.icq_fast_set(index, _dev(torch, o_xi), fast)
+    sigma = torch.empty(1, dtype=torch.float64, device="cuda")
+    b.icq_margin(var, _dev(torch, o_xi), sigma)
+    torch.cuda.synchronize()
+    assert np.array_equal(fast.cpu().numpy(), orc.fast_set(cb, o_xi))
+    assert np.array_equal(fast.cpu().numpy()[[0, 1, 2, 4, 5]], [1, 0, 0, 1, 0])
+    assert abs(float(sigma.item()) - orc.margin(lam, o_xi)) <= 1e-12 * max(1.0, orc.margin(lam, o_xi))
