@@ -61,3 +61,31 @@ def test_host_side_argument_checks():
     assert lib.icq_refine(None, one, 1, one, one, one, 1, 1, one, one, one, 0, None) == binding.ICQ_ERR_ARG
     assert lib.icq_search(None, one, 1, one, 1, 1, one, one, None, one, 0, None) == binding.ICQ_ERR_ARG
     lib.icq_index_destroy(None)
+
+
+def test_host_side_argument_checks_of_the_policy_encoding_and_utility_calls():
+    from paper_1912_08756_amd import binding
+    lib = binding.load()
+    E = binding.ICQ_ERR_ARG
+    one = ctypes.c_void_p(1)
+    out = ctypes.c_size_t(0)
+    assert lib.icq_index_set_scan_mode(None, 0) == E
+    assert lib.icq_index_set_stage_timing(None, 1) == E
+    assert lib.icq_index_stage_times(None, None, None, None) == E
+    assert lib.icq_index_export_codes(None, 0, one, None) == E
+    assert lib.icq_sample_thresholds(None, one, 1, None, 10, 100, one, None) == E
+    assert lib.icq_op_counts(None, one, 1, one, one, None) == E
+    assert lib.icq_encode_workspace_bytes(None, 10, ctypes.byref(out)) == E
+    assert lib.icq_encode(None, one, 10, one, one, 1 << 20, None) == E
+    # the utilities take no index: bad sizes and null pointers
+    assert lib.icq_batch_moments(one, -1, 4, one, one, None) == E
+    assert lib.icq_batch_moments(one, 10, 0, one, one, None) == E
+    assert lib.icq_batch_moments(None, 10, 4, one, one, None) == E
+    assert lib.icq_online_variance_update(one, one, one, one, 4, 0, None) == E
+    assert lib.icq_online_variance_update(None, one, one, one, 4, 1, None) == E
+    assert lib.icq_subspace_mask(one, 4, 0.8, 0.0, 0.2, 1.0, 1.0, -10.0, one, None) == E      # sigma1 must be > 0
+    assert lib.icq_subspace_mask(one, 4, 0.8, 1.0, 0.2, 1.0, float("nan"), -10.0, one, None) == E
+    assert lib.icq_subspace_mask(None, 4, 0.8, 1.0, 0.2, 1.0, 1.0, -10.0, one, None) == E
+    assert lib.icq_fast_set(None, one, one, None) == E
+    assert lib.icq_margin(one, one, 0, one, None) == E
+    assert lib.icq_margin(one, None, 4, one, None) == E
