@@ -333,7 +333,7 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(6, 8
     const uint32_t *__restrict__ perm, unsigned long long *__restrict__ keys_out,
     uint32_t *__restrict__ count, int64_t cap, int rows_per_block, int topk,
     uint32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
-    __shared__ float T[4 * WORDS * ICQ_LUT_W];
+    __shared__ __attribute__((aligned(16))) float T[4 * WORDS * ICQ_LUT_W];
     __shared__ uint32_t hbuf[GD_HITS];        // tuple ids while compacting, then first positions
     __shared__ uint32_t hx[GD_HITS + 1];      // exclusive prefix of the tuple sizes, hx[nhc] = tot
     __shared__ unsigned long long list[FUSED ? GD_LIST : 1];
@@ -346,7 +346,14 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(6, 8
     const float t = thr[q];
     unsigned long long *my_out = FUSED ? nullptr : keys_out + (int64_t)q * cap;
 
-    for (int i = tid; i < 4 * WORDS * ICQ_LUT_W; i += GS_THREADS) T[i] = i < K * ICQ_LUT_W ? Tq[i] : 0.0f;
+    // the query's tables: loads now, LDS writes after the tuple evaluation below, which hides their latency
+    constexpr int T_PER = 4 * WORDS * ICQ_LUT_W / GS_THREADS / 4;
+    float4 tv[T_PER];
+#pragma unroll
+    for (int r = 0; r < T_PER; ++r) {
+        const int i4 = r * GS_THREADS + tid;            // float4 index; a table row is 64 of them
+        tv[r] = i4 * 4 < K * ICQ_LUT_W ? reinterpret_cast<const float4 *>(Tq)[i4] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    }
     uint32_t *flag = sh.flag[wave];
     flag[lane] = 0;
     uint32_t stamp = 0;                        // wavefront-uniform, never 0 when compared
@@ -377,6 +384,8 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(6, 8
         m[0] = Tq[tid] < t ? 1u : 0u;
         mine = m[0];
     }
+#pragma unroll
+    for (int r = 0; r < T_PER; ++r) reinterpret_cast<float4 *>(T)[r * GS_THREADS + tid] = tv[r];
     // this thread's surviving tuples are numbers [off_all, off_all + mine) of the block's total_hits
     uint32_t off_all, dummy0, total_hits, dummy1;
     block_scan2(mine, 0u, sh.wsum, lane, wave, off_all, dummy0, total_hits, dummy1);
