@@ -742,3 +742,44 @@ def test_moments_online_variance_mask_fast_set_and_margin_match_oracle(gpu):
     assert np.array_equal(fast.cpu().numpy(), orc.fast_set(cb, o_xi))
     assert np.array_equal(fast.cpu().numpy()[[0, 1, 2, 4, 5]], [1, 0, 0, 1, 0])
     assert abs(float(sigma.item()) - orc.margin(lam, o_xi)) <= 1e-12 * max(1.0, orc.margin(lam, o_xi))
+
+
+# ------------------------------------------------------------------ seeded sweep over shapes
+def _sweep_cases():
+    rng = np.random.default_rng(20240)
+    cases = []
+    for i in range(36):
+        K = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16, 17]))
+        Kf = int(rng.integers(1, min(K, 5) + 1))
+        m = int(rng.choice([256, 256, 256, 100, 17]))
+        d = int(rng.choice([8, 24, 33, 64]))
+        N = int(rng.choice([1, 63, 64, 65, 1_000, 4_097, 16_384, 40_000, 70_001]))
+        Q = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 63, 64, 65, 130, 515]))
+        topk = int(rng.choice([1, 10, 100, 129, 257]))
+        frac = float(rng.choice([0.002, 0.01, 0.05, 0.3, 1.0]))
+        mode = int(rng.choice([0, 0, 1, 2]))
+        cases.append((i, K, Kf, m, d, N, Q, topk, frac, mode))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases(), ids=lambda c: "s%02d-K%d-Kf%d-m%d-N%d-Q%d-k%d-f%g-mode%d" % (
+    c[0], c[1], c[2], c[3], c[5], c[6], c[7], c[8], c[9]))
+def test_search_sweep_against_oracle(gpu, case):
+    """Shapes drawn from a fixed seed: codebook counts around the record widths (4 / 8 / 16 / wider),
+    every Kf up to 5, short codebooks, ragged N and Q around the tile sizes, lists from 1 to 257,
+    survivor fractions from 0.2 % to all, every stage-1 form."""
+    i, K, Kf, m, d, N, Q, topk, frac, mode = case
+    rng = np.random.default_rng(1000 + i)
+    cb = (rng.standard_normal((K, m, d)) * (0.7 ** np.arange(K))[:, None, None]).astype(np.float32)
+    codes = rng.integers(0, m, size=(K, N), dtype=np.uint8)
+    src = rng.integers(0, N, size=Q)
+    queries = sum(cb[k][codes[k, src]] for k in range(K)) + 0.1 * rng.standard_normal((Q, d))
+    cfg = dict(codebooks=cb, codes=codes, queries=np.ascontiguousarray(queries, dtype=np.float32),
+               K=K, Kf=Kf, d=d, N=N, Q=Q, topk=topk)
+    g = Gpu(gpu, cfg, mode if Kf <= 2 else (0 if mode == 2 else mode))
+    T, P, D = oracle_all(cfg)
+    if frac >= 1.0:
+        thr = np.full(Q, np.inf, dtype=np.float32)
+    else:
+        thr = np.quantile(P, frac, axis=1).astype(np.float32)
+    _check_search(g, cfg, T, P, D, thr, topk, N + 1)
