@@ -327,7 +327,7 @@ __device__ __forceinline__ uint32_t block_tie_cut(GdShared &sh, unsigned long lo
 // written to slot base + number of the query's key list for the select kernel; each
 // pass reserves its slots with one atomic on the query's counter.
 template <int KF, int WORDS, bool FUSED>
-__global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(6, 8))) void group_keys_kernel(
+__global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORDS == 4 ? 3 : 6, 8))) void group_keys_kernel(
     const float *__restrict__ lut, int K, const float *__restrict__ thr,
     const uint32_t *__restrict__ start, const uint8_t *__restrict__ items_grouped,
     const uint32_t *__restrict__ perm, unsigned long long *__restrict__ keys_out,
