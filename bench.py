@@ -109,7 +109,14 @@ def hbm_leg(torch, b, steps, warmup):
         for _ in range(warmup):
             run()
         torch.cuda.synchronize()
-        ms = event_time_ms(torch, run, steps)
+        # the library's own events on the launch stream: after the counter fill .. after the scan kernel
+        b.icq_index_set_stage_timing(idx, True)
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        stage, calls, _ = b.icq_index_stage_times(idx)
+        b.icq_index_set_stage_timing(idx, False)
+        ms = stage[1]
         surv = int(cnt.sum().item())
         alg_bytes = Kf * N + 4 * Q * Kf * 256 + 4 * surv      # codes once, tables, survivor ids
         achieved = alg_bytes / (ms * 1e-3) / 1e9

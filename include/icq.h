@@ -109,8 +109,10 @@ int icq_index_set_scan_mode(icq_index *index, int mode);
  * later icq_search on this index records events on its stream around the
  * kernels of its FIRST query sub-batch: before the table build, after it, after
  * stage 1 (scan, plus the survivors' distances where the scan is fused with
- * them) and after the nearest-neighbour lists are written.  The latest
- * ICQ_TIMED_CALLS calls are kept.  enable == 0 stops that and releases the
+ * them; the interval starts once the survivor counters are zeroed) and after
+ * the nearest-neighbour lists are written.  icq_scan_fast records the same
+ * events (its stage-1 interval is its scan kernel, stage 2 is empty).  The
+ * latest ICQ_TIMED_CALLS calls are kept.  enable == 0 stops that and releases the
  * events.
  * icq_index_stage_times waits for the last recorded call to finish and writes
  * ms[0..2] (host) = milliseconds of table build, stage 1, stage 2 + list,

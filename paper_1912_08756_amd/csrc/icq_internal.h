@@ -79,9 +79,11 @@ int icq_launch_build_lut(const icq_index *ix, const float *queries, int Q, float
 // cand_keys ([Q][cap], may be nullptr), grouped positions, or plain ids.
 // topk / out_ids / out_dist (may be nullptr): where the scan may write the final lists
 // itself (ICQ_LIST_DONE) when its grouped form covers stage 2 as well.
+// after_fill (may be nullptr): event recorded once the survivor counters are zeroed.
 int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
                     uint32_t *cand_ids, float *cand_part, unsigned long long *cand_keys, int *list_kind,
-                    uint32_t *cand_count, int64_t cap, int topk, uint32_t *out_ids, float *out_dist, hipStream_t s);
+                    uint32_t *cand_count, int64_t cap, int topk, uint32_t *out_ids, float *out_dist,
+                    hipEvent_t after_fill, hipStream_t s);
 // Grouped stage 1 fused with stage 2: the final lists when icq_group_fused() holds and
 // out_ids is given, else one 64-bit key per survivor in cand_keys.
 bool icq_group_fused(const icq_index *ix, int Q, int topk);

@@ -383,10 +383,11 @@ __global__ __launch_bounds__(SI_THREADS) void scan_items_kernel(
 
 int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
                     uint32_t *cand_ids, float *cand_part, unsigned long long *cand_keys, int *list_kind, uint32_t *cand_count, int64_t cap,
-                    int topk, uint32_t *out_ids, float *out_dist, hipStream_t s) {
+                    int topk, uint32_t *out_ids, float *out_dist, hipEvent_t after_fill, hipStream_t s) {
     if (list_kind) *list_kind = ICQ_LIST_IDS;
     if (Q == 0) return ICQ_OK;
     zero_counts_kernel<<<(Q + 255) / 256, 256, 0, s>>>(cand_count, Q);
+    if (after_fill) ICQ_HIP_TRY(hipEventRecord(after_fill, s));
     if (ix->N == 0) return icq_check_launch();
 
     const int bpq_fill = (int)((cap + 255) / 256 < 32 ? (cap + 255) / 256 : 32);
@@ -479,6 +480,22 @@ ICQ_EXPORT int icq_scan_fast(const icq_index *ix, const float *lut, int Q, const
     icq_ws_layout L = icq_layout(ix, Q, cap, 1, false, false);
     if (!workspace || ((uintptr_t)workspace % ICQ_ALIGN) != 0 || workspace_bytes < L.total)
         return ICQ_ERR_WORKSPACE;
-    return icq_launch_scan(ix, lut, Q, thresholds, cand_ids, cand_part, nullptr, nullptr,
-                           cand_count, cap, 0, nullptr, nullptr, (hipStream_t)stream);
+    // stage timing: [0] entry .. [1] after the counter fill .. [2] after the scan (.. [3] = [2])
+    icq_stage_timer *tm = ix->timer;
+    hipEvent_t *ev = nullptr;
+    hipStream_t s = (hipStream_t)stream;
+    if (tm) {
+        if (tm->batches < 1) tm->batches = 1;
+        ev = tm->ev[tm->calls % ICQ_TIMED_CALLS];
+        tm->calls += 1;
+        ICQ_HIP_TRY(hipEventRecord(ev[0], s));
+    }
+    const int rc = icq_launch_scan(ix, lut, Q, thresholds, cand_ids, cand_part, nullptr, nullptr, cand_count, cap,
+                                   0, nullptr, nullptr, ev ? ev[1] : nullptr, s);
+    if (rc != ICQ_OK) return rc;
+    if (ev) {
+        ICQ_HIP_TRY(hipEventRecord(ev[2], s));
+        ICQ_HIP_TRY(hipEventRecord(ev[3], s));
+    }
+    return ICQ_OK;
 }

@@ -82,12 +82,12 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
         if (timed) ICQ_HIP_TRY(hipEventRecord(ev[0], s));
         int rc = icq_launch_build_lut(ix, queries + (int64_t)q0 * ix->d, nq, lut, s);
         if (rc != ICQ_OK) return rc;
-        if (timed) ICQ_HIP_TRY(hipEventRecord(ev[1], s));
         int list_kind = ICQ_LIST_IDS;
         unsigned long long *cand_keys = (ix->item_stride <= 16 && topk <= 512 && !icq_group_fused(ix, nq, topk))
                                             ? icq_cand_keys(keys, nq, L.splits, topk) : nullptr;
         rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, nullptr, cand_keys, &list_kind, cnt,
-                             cap, topk, out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
+                             cap, topk, out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk,
+                             timed ? ev[1] : nullptr, s);
         if (rc != ICQ_OK) return rc;
         if (timed) ICQ_HIP_TRY(hipEventRecord(ev[2], s));
         rc = icq_launch_refine(ix, lut, nq, ids, nullptr, list_kind, cnt, cap, topk, L.splits, keys,
