@@ -96,13 +96,37 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qbase = blockIdx.y * B;
 
-    // the tables go to LDS after the first code loads have been sent (see the end of the kernel)
+    // The tables go to LDS after the first code loads have been sent (see the end of the kernel).
+    // Consecutive threads write consecutive 16-byte pieces (conflict-free; writing an entry's C
+    // copies from one thread instead puts 16 lanes on the same banks and took 7 us per block);
+    // a piece holds 4 / B copies of the entry's B values.  All loads go out before the writes.
     auto fill_tables = [&]() {
-        for (int i = tid; i < KF * ICQ_LUT_W * B; i += SS_THREADS) {
-            const int b = i / (KF * ICQ_LUT_W), e = i % (KF * ICQ_LUT_W);
-            const float v = (qbase + b) < Q ? lut[(int64_t)(qbase + b) * K * ICQ_LUT_W + e] : INFINITY;
+        constexpr int NV = TAB_FLOATS / 4 / SS_THREADS;              // 16-byte pieces per thread
+        static_assert(TAB_FLOATS % (4 * SS_THREADS) == 0 && C % 4 == 0, "whole pieces, inside one entry");
+        const float *row[B];
 #pragma unroll
-            for (int r = 0; r < C; ++r) smem[(e * C + r) * B + b] = v;
+        for (int b = 0; b < B; ++b) {
+            const int qb = (qbase + b) < Q ? qbase + b : Q - 1;       // clamped; replaced by +inf below
+            row[b] = lut + (int64_t)qb * K * ICQ_LUT_W;
+        }
+        float x[NV][B];
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int e = ((j * SS_THREADS + tid) * 4 / B) / C;
+#pragma unroll
+            for (int b = 0; b < B; ++b) x[j][b] = row[b][e];
+        }
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+#pragma unroll
+            for (int b = 0; b < B; ++b)
+                if ((qbase + b) >= Q) x[j][b] = INFINITY;            // block-uniform
+            float4 v;
+            v.x = x[j][0];
+            v.y = x[j][1 % B];
+            v.z = x[j][2 % B];
+            v.w = x[j][3 % B];
+            reinterpret_cast<float4 *>(smem)[j * SS_THREADS + tid] = v;
         }
         __syncthreads();
     };
