@@ -273,6 +273,85 @@ def pmc_traffic(kernel):
     return None
 
 
+def configs_leg(torch, b, synth, skip, with_cpu, target_s=4.0):
+    """Queries/s of the whole path at every other workload shape (full N, the batch size the
+    shape names), with the oracle timed beside it on a bounded sample of the same queries.
+    Thresholds: the shape's own rule for C0 (1.5 x the 20th-smallest crude distance), else
+    the sampled 1 % quantile.  Input preparation is not timed."""
+    from oracle import icq_oracle as orc
+    out = {}
+    for name, batch in (("C0", None), ("C1", None), ("C2", None), ("C3", 256), ("C4", 128)):
+        if name == skip:
+            continue
+        t_prep = time.perf_counter()
+        cfg = synth.make(name)
+        K, Kf, d, N, Q, topk = cfg["K"], cfg["Kf"], cfg["d"], cfg["N"], cfg["Q"], cfg["topk"]
+        batch = batch or Q
+        cb = torch.from_numpy(cfg["codebooks"]).cuda()
+        codes = torch.from_numpy(cfg["codes"]).cuda()
+        queries = torch.from_numpy(cfg["queries"]).cuda()
+        index = b.icq_index_create(cb, codes, Kf)
+        if name == "C0":
+            lut = torch.empty((Q, K, 256), dtype=torch.float32, device="cuda")
+            b.icq_build_lut(index, queries, lut)
+            ids = torch.empty((Q, N), dtype=torch.int32, device="cuda")
+            part = torch.empty((Q, N), dtype=torch.float32, device="cuda")
+            cnt = torch.empty((Q,), dtype=torch.int32, device="cuda")
+            ws0 = torch.empty(b.icq_workspace_bytes(index, Q, N, 1), dtype=torch.uint8, device="cuda")
+            b.icq_scan_fast(index, lut, torch.full((Q,), float("inf"), device="cuda"), ids, part, cnt, ws0)
+            thr = (torch.kthvalue(part, 20, dim=1).values * 1.5).contiguous()
+            cap = N
+            del lut, ids, part, cnt, ws0
+        else:
+            thr = sampled_thresholds(torch, b, cb, codes, queries, Kf, SURVIVE_FRAC, 16384, cfg["seed"])
+            cap = int(N * SURVIVE_FRAC * 2)
+        out_ids = torch.empty((Q, topk), dtype=torch.int32, device="cuda")
+        out_dist = torch.empty((Q, topk), dtype=torch.float32, device="cuda")
+        surv = torch.empty((Q,), dtype=torch.int32, device="cuda")
+        ws = torch.empty(b.icq_workspace_bytes(index, batch, cap, topk), dtype=torch.uint8, device="cuda")
+
+        def run():
+            for q0 in range(0, Q, batch):
+                b.icq_search(index, queries[q0:q0 + batch], thr[q0:q0 + batch], cap, topk, out_ids[q0:q0 + batch],
+                             out_dist[q0:q0 + batch], surv[q0:q0 + batch], ws)
+        run()
+        torch.cuda.synchronize()
+        reps = 3
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            run()
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / reps
+        surv_np = surv.cpu().numpy().view(np.uint32)
+        entry = {"workload": "%s: d=%d K=%d Kf=%d N=%d Q=%d top-%d, batches of %d" % (name, d, K, Kf, N, Q, topk, batch),
+                 "queries_per_s": round(Q / sec, 1), "ms_per_batch": round(sec * 1e3 / math.ceil(Q / batch), 4),
+                 "survivors_mean": round(float(surv_np.mean()), 1), "overflowed_lists": int((surv_np > cap).sum())}
+        if with_cpu:
+            thr_np = thr.cpu().numpy()
+            n = min(Q, orc.threads())
+            t0 = time.perf_counter()
+            o_ids = orc.search(orc.lut(cfg["codebooks"], cfg["queries"][:n]), cfg["codes"], Kf, thr_np[:n], topk)[0]
+            dt = time.perf_counter() - t0
+            more = int(min(Q, n * target_s / max(dt, 1e-9))) // n * n
+            if more > n and dt < target_s / 2:
+                n = more
+                t0 = time.perf_counter()
+                o_ids = orc.search(orc.lut(cfg["codebooks"], cfg["queries"][:n]), cfg["codes"], Kf, thr_np[:n], topk)[0]
+                dt = time.perf_counter() - t0
+            g_ids = out_ids[:n].cpu().numpy().view(np.uint32)
+            entry["oracle"] = {"queries_per_s": round(n / dt, 2), "cores": orc.threads(),
+                               "sample": "first %d queries, full N, %.1f s wall" % (n, dt),
+                               "identical_lists_frac": round(float((g_ids == o_ids).all(axis=1).mean()), 4)}
+            entry["gpu_over_oracle"] = round(Q / sec / (n / dt), 1)
+        out[name] = entry
+        log("[bench] %s: %.0f queries/s (%.3f ms per batch of %d)%s, prepared in %.0f s" %
+            (name, Q / sec, entry["ms_per_batch"], batch,
+             "; oracle %.1f queries/s" % entry["oracle"]["queries_per_s"] if with_cpu else "", time.perf_counter() - t_prep))
+        del index, cb, codes, queries, ws, out_ids, out_dist, surv, thr
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -284,6 +363,7 @@ def main():
     ap.add_argument("--no-streamed-leg", action="store_true")
     ap.add_argument("--no-policy-leg", action="store_true")
     ap.add_argument("--no-encode-leg", action="store_true")
+    ap.add_argument("--no-configs-leg", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB): the scale for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
@@ -355,7 +435,7 @@ def main():
 
     # Dominant kernel of the step: stage 1 over the items grouped by fast-code tuple, fused with
     # the survivors' distances and the nearest-neighbour lists (group_keys_kernel<Kf,W,true>;
-    # the stage-1 event pair also spans the 4 us counter fill).  What the method itself must
+    # the stage-1 event pair starts after the counter fill).  What the method itself must
     # move per launch: per survivor its K code bytes, per query its K tables (4*K*256 bytes)
     # and its result rows (8 bytes per entry).  Candidates never leave the chip.
     alg_bytes = n_surv * K + 4.0 * Q * K * 256 + 8.0 * Q * topk
@@ -407,8 +487,8 @@ def main():
             "same_ids_as_grouped": same,
             "stages_ms": {"build_lut": round(stage_s[0], 4), "stage1": round(stage_s[1], 4),
                           "stage2": round(stage_s[2], 4)},
-            "note": "item-by-item stage 1: algorithmic LDS gather bytes 4*Kf*N*Q over the stage-1 event pair (scan "
-                    "kernel + the counter fill); peak = 256 CU x 128 B/clk x 2.4 GHz; the LDS takes 16 addresses per "
+            "note": "item-by-item stage 1: algorithmic LDS gather bytes 4*Kf*N*Q over the stage-1 event pair (the scan "
+                    "kernel); peak = 256 CU x 128 B/clk x 2.4 GHz; the LDS takes 16 addresses per "
                     "clock and CU, so the kernel reads the entries of 4 queries with one 128-bit access; code bytes "
                     "read are Kf*N*ceil(Q/4), from the last-level cache at this N"}
         log("[bench] streamed stage 1: %.3f ms/step (stage 1 %.3f ms), same ids as grouped: %s" %
@@ -438,6 +518,11 @@ def main():
         base, match = cpu_baseline(cfg, thr.cpu().numpy(), gpu_ids, gpu_dist)
         result["cpu_baseline"] = base
         result["oracle_matched"] = match
+    if not args.no_configs_leg:
+        del index, cb, codes, queries
+        torch.cuda.empty_cache()
+        log("[bench] the other workload shapes, each against the oracle")
+        result["configs"] = configs_leg(torch, b, synth, args.workload, not args.no_cpu_baseline)
     print(json.dumps(result), flush=True)
 
 

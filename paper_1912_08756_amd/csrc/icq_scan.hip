@@ -83,7 +83,7 @@ constexpr int SS_WAVES = SS_THREADS / 64;
 
 template <int KF, int B>
 __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
-    const uint8_t *__restrict__ fast, int64_t Npad, uint32_t N, const float *__restrict__ lut, int K,
+    const uint8_t *fast, int64_t Npad, uint32_t N, const float *__restrict__ lut, int K,
     const float *__restrict__ thr, int Q, uint32_t *__restrict__ cand_ids,
     uint32_t *__restrict__ cand_count, int64_t cap, uint32_t items_per_block, uint32_t wave_cap) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
