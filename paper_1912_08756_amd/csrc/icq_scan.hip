@@ -81,6 +81,12 @@ constexpr int SS_CHECK = 8;       // steps between block-wide flush checks
 constexpr int SS_THREADS = 1024;
 constexpr int SS_WAVES = SS_THREADS / 64;
 
+// hm = 2 * hm + (P < t): the comparison's carry shifted in with one add (the compiler's own
+// form is a select and an or per item).  Item j of 16 ends up in bit 15 - j.
+__device__ __forceinline__ void hit_shift_in(uint32_t &hm, float P, float t) {
+    asm("v_cmp_gt_f32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(hm) : "v"(P), "v"(t) : "vcc");
+}
+
 template <int KF, int B>
 __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     const uint8_t *fast, int64_t Npad, uint32_t N, const float *__restrict__ lut, int K,
@@ -173,7 +179,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     // the 1024 items at g held in w: table sums, hit bits, staging
     auto process = [&](uint32_t g, const uint4 (&w)[KF]) {
         const uint32_t id0 = g + lane * 16;
-        uint32_t hm[B];   // hit bits of this lane's 16 items, one mask per query
+        uint32_t hm[B];   // hit bits of this lane's 16 items (item j in bit 15 - j), one mask per query
 #pragma unroll
         for (int b = 0; b < B; ++b) hm[b] = 0;
 #pragma unroll
@@ -223,12 +229,12 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
                     float P = v[jj][0][b];
 #pragma unroll
                     for (int k = 1; k < KF; ++k) P += v[jj][k][b];
-                    hm[b] |= (P < t[b]) ? (1u << (h + jj)) : 0u;
+                    hit_shift_in(hm[b], P, t[b]);
                 }
             }
         }
         if (id0 + 16 > end || id0 + 16 < id0) {   // ragged tail: drop bits of items at or beyond `end`
-            const uint32_t valid = id0 < end ? (1u << (end - id0)) - 1u : 0u;
+            const uint32_t valid = id0 < end ? 0xFFFFu & ~((1u << (16 - (end - id0))) - 1u) : 0u;
 #pragma unroll
             for (int b = 0; b < B; ++b) hm[b] &= valid;
         }
@@ -247,7 +253,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
                     move_out(b, mine_stage, wc[b], gb);
                     wc[b] = 0;
                 }
-                if (hm[b] != 0) mine_stage[wc[b] + rank] = id0 + (uint32_t)__builtin_ctz(hm[b]);
+                if (hm[b] != 0) mine_stage[wc[b] + rank] = id0 + 15u - (uint32_t)__builtin_ctz(hm[b]);
                 wc[b] += n;
                 hm[b] &= hm[b] - 1;
                 mask = __builtin_amdgcn_ballot_w64(hm[b] != 0);
