@@ -436,7 +436,7 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
 #pragma unroll
         for (int u = 0; u < GD_PER; ++u) {
             if (n[u] != 0) {
-                hbuf[c] = s[u];
+                hbuf[c] = s[u] - x;            // first position minus prefix (mod 2^32): position = this + survivor number
                 hx[c] = x;
                 ++c;
                 x += n[u];
@@ -456,6 +456,8 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
         const uint32_t r0 = (uint32_t)wave * rpw;
         const uint32_t rend = r0 + rpw < nrows ? r0 + rpw : nrows;        // <= r0: nothing for this wavefront
         const uint32_t steps = (rpw + GD_ROWS - 1) / GD_ROWS;              // block-uniform
+        const uint32_t lane4 = (lane + 1) * 4, nhc4 = nhc * 4;
+        const uint32_t lim = rend * 64 < tot ? rend * 64 : tot;            // end of this wavefront's survivors
         uint32_t ha = 0;
         if (r0 < rend) {
             // tuple holding survivor r0 * 64: the last one whose prefix is <= it (two 64-way probes)
@@ -478,15 +480,18 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
             const uint32_t pf = row * 64;
             const uint32_t pl = pf + 63 < tot ? pf + 63 : tot - 1;
             const uint32_t p = pf + lane < pl ? pf + lane : pl;
-            const uint32_t bi = ha + 1 + lane;
-            const uint32_t bnd = hx[bi < nhc ? bi : nhc];      // prefixes of the tuples after ha (hx[nhc] = tot > pl)
+            // prefixes of the tuples after ha (hx[nhc] = tot > pl), addressed in bytes: add, min, read
+            const uint32_t bi4 = ha * 4 + lane4;
+            const uint32_t bnd = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(hx) + (bi4 < nhc4 ? bi4 : nhc4));
             ++stamp;
             if (bnd <= pl) flag[bnd - pf] = stamp;              // pf < bnd: tuple ha holds pf
             __builtin_amdgcn_wave_barrier();                    // LDS runs a wavefront's accesses in order
             const uint64_t marks = __builtin_amdgcn_ballot_w64(flag[lane] == stamp);
             const uint32_t h = ha + (uint32_t)__builtin_popcountll(marks & ((2ull << lane) - 1ull));
-            const uint32_t pos = hbuf[h] + (p - hx[h]);
-            ha += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(bnd <= pl + 1 && bi < nhc));
+            const uint32_t pos = hbuf[h] + p;
+            // Tuples that start at or before the next row's first survivor.  The clamped lanes read tot,
+            // which passes only in the pass's last row -- after which ha is not used again.
+            ha += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(bnd <= pl + 1));
             return pos;
         };
         // records (and, for the key list, ids) of rows r, r + 1; rows past rend read record 0, unused
@@ -515,6 +520,7 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
         };
         unsigned long long key[GD_ROWS];
         bool take[GD_ROWS];
+        uint64_t mk[GD_ROWS];                  // FUSED: ballot of take (wavefront-uniform)
         // distances and keys of rows r, r + 1 from their records
         auto finish = [&](uint32_t r, const uint32_t (*rec)[WORDS], const uint32_t *low, int slot0) {
 #pragma unroll
@@ -528,14 +534,20 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
                         d += T[(w * 4 + b) * ICQ_LUT_W + ((rec[u][w] >> (8 * b)) & 0xffu)];
                 }
                 const uint32_t ob = icq_order_bits(d);
-                const uint32_t num = (r + u) * 64 + lane;
                 key[slot0 + u] = ((unsigned long long)ob << 32) | low[u];
-                take[slot0 + u] = r + u < rend && num < tot;
+                // survivors of this row that exist (wavefront-uniform count: the last row of a pass is ragged)
+                // (one signed comparison against a wavefront-uniform bound: rows at or past `lim` give <= 0)
+                const uint32_t first = (r + u) * 64;
+                const bool exists = (int)lane < (int)(lim - first);
                 if (FUSED) {
-                    take[slot0 + u] = take[slot0 + u] && ob <= bound;
+                    // the comparisons feed the ballots directly (one instruction each, no select)
+                    const bool near = ob <= bound;
+                    mk[slot0 + u] = __builtin_amdgcn_ballot_w64(near) & __builtin_amdgcn_ballot_w64(exists);
+                    take[slot0 + u] = near && exists;
                 } else {
-                    const uint64_t slot = (uint64_t)base + num;
-                    if (take[slot0 + u] && slot < (uint64_t)cap) my_out[slot] = key[slot0 + u];
+                    take[slot0 + u] = exists;
+                    const uint64_t slot = (uint64_t)base + first + lane;
+                    if (exists && slot < (uint64_t)cap) my_out[slot] = key[slot0 + u];
                 }
             }
         };
@@ -551,11 +563,9 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
             fetch(r + GD_ROWS, recA, lowA);
             finish(r + HALF, recB, lowB, HALF);
             if (FUSED) {
-                uint64_t mk[GD_ROWS];
                 uint32_t pre[GD_ROWS], mycnt = 0;
 #pragma unroll
                 for (int u = 0; u < GD_ROWS; ++u) {
-                    mk[u] = __builtin_amdgcn_ballot_w64(take[u]);
                     pre[u] = mycnt;
                     mycnt += (uint32_t)__builtin_popcountll(mk[u]);
                 }

@@ -48,6 +48,14 @@ enum icq_list_kind {
     ICQ_LIST_DONE = 3          // stage 1 kept the nearest-neighbour lists itself and wrote the results
 };
 
+// hm = 2 * hm + (P < t): the comparison's carry shifted in with one add (the compiler's own
+// form is a select and an or per item).  After n calls the first comparison sits in bit n - 1, the last in bit 0.
+__device__ __forceinline__ void icq_hit_shift_in(uint32_t &hm, float P, float t) {
+    // the two wait states are the ones the compiler itself puts between a vector instruction that
+    // writes VCC and one that reads it (it does not look inside an asm statement)
+    asm("v_cmp_gt_f32 vcc, %2, %1\n\ts_nop 1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(hm) : "v"(P), "v"(t) : "vcc");
+}
+
 // Order-preserving bits of a float: u(a) < u(b) <=> a < b.
 __device__ __forceinline__ uint32_t icq_order_bits(float x) {
     uint32_t b = __float_as_uint(x);

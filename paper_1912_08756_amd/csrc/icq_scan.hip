@@ -81,12 +81,6 @@ constexpr int SS_CHECK = 8;       // steps between block-wide flush checks
 constexpr int SS_THREADS = 1024;
 constexpr int SS_WAVES = SS_THREADS / 64;
 
-// hm = 2 * hm + (P < t): the comparison's carry shifted in with one add (the compiler's own
-// form is a select and an or per item).  Item j of 16 ends up in bit 15 - j.
-__device__ __forceinline__ void hit_shift_in(uint32_t &hm, float P, float t) {
-    asm("v_cmp_gt_f32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(hm) : "v"(P), "v"(t) : "vcc");
-}
-
 template <int KF, int B>
 __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     const uint8_t *fast, int64_t Npad, uint32_t N, const float *__restrict__ lut, int K,
@@ -192,9 +186,8 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
 #pragma unroll
                 for (int k = 0; k < KF; ++k) {
                     const uint32_t word = j < 4 ? w[k].x : j < 8 ? w[k].y : j < 12 ? w[k].z : w[k].w;
-                    const int sh = 8 * (j & 3) - ENTRY_SHIFT;   // code byte -> entry offset
-                    const uint32_t pos = sh >= 0 ? (word >> (sh >= 0 ? sh : 0)) : (word << (sh < 0 ? -sh : 0));
-                    off[jj][k] = (pos & (0xffu << ENTRY_SHIFT)) | copy_off;
+                    const uint32_t code = (word >> (8 * (j & 3))) & 0xffu;     // byte extract + shift-add: two instructions
+                    off[jj][k] = (code << ENTRY_SHIFT) + copy_off;
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -229,7 +222,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
                     float P = v[jj][0][b];
 #pragma unroll
                     for (int k = 1; k < KF; ++k) P += v[jj][k][b];
-                    hit_shift_in(hm[b], P, t[b]);
+                    icq_hit_shift_in(hm[b], P, t[b]);
                 }
             }
         }
