@@ -487,7 +487,10 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
             if (bnd <= pl) flag[bnd - pf] = stamp;              // pf < bnd: tuple ha holds pf
             __builtin_amdgcn_wave_barrier();                    // LDS runs a wavefront's accesses in order
             const uint64_t marks = __builtin_amdgcn_ballot_w64(flag[lane] == stamp);
-            const uint32_t h = ha + (uint32_t)__builtin_popcountll(marks & ((2ull << lane) - 1ull));
+            // flags at or below this lane: lane 0 never holds one (a flagged tuple starts after pf), so
+            // that is the count below the lane in the flags moved down by one -- two mbcnt, ha added in
+            const uint64_t m1 = marks >> 1;
+            const uint32_t h = __builtin_amdgcn_mbcnt_hi((uint32_t)(m1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m1, ha));
             const uint32_t pos = hbuf[h] + p;
             // Tuples that start at or before the next row's first survivor.  The clamped lanes read tot,
             // which passes only in the pass's last row -- after which ha is not used again.
@@ -571,16 +574,18 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
                 }
                 if (lane == 0) sh.wtot[it & 1][wave] = mycnt;
                 __syncthreads();
-                uint32_t mybase = cnt, all = 0;
+                uint32_t mybase = cnt, all = 0;              // scalar registers: the counts are read once per wavefront
 #pragma unroll
                 for (int w = 0; w < GS_THREADS / 64; ++w) {
-                    const uint32_t tw = sh.wtot[it & 1][w];
+                    const uint32_t tw = (uint32_t)__builtin_amdgcn_readfirstlane((int)sh.wtot[it & 1][w]);
                     if (w < wave) mybase += tw;
                     all += tw;
                 }
 #pragma unroll
                 for (int u = 0; u < GD_ROWS; ++u)
-                    if (take[u]) list[mybase + pre[u] + (uint32_t)__builtin_popcountll(mk[u] & ((1ull << lane) - 1))] = key[u];
+                    if (take[u])
+                        list[__builtin_amdgcn_mbcnt_hi((uint32_t)(mk[u] >> 32),
+                                                       __builtin_amdgcn_mbcnt_lo((uint32_t)mk[u], mybase + pre[u]))] = key[u];
                 cnt += all;
                 // block-uniform: cut while the next step might not fit -- one counting pass, then
                 // (fat bin) exactly, then (many equal distances) by id
