@@ -58,8 +58,9 @@ __device__ __forceinline__ void icq_hit_shift_in(uint32_t &hm, float P, float t)
 
 // Order-preserving bits of a float: u(a) < u(b) <=> a < b.
 __device__ __forceinline__ uint32_t icq_order_bits(float x) {
-    uint32_t b = __float_as_uint(x);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    // negative: all bits flipped; else the sign bit set -- as an arithmetic shift and one xor-or
+    const uint32_t b = __float_as_uint(x);
+    return b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);
 }
 
 // Sub-buffers carved out of the caller's workspace for one query batch.
