@@ -359,8 +359,11 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     uint32_t stamp = 0;                        // wavefront-uniform, never 0 when compared
 
     // ---- one bit per (row, column): same additions as the item-by-item scan, lut[0][c0] (+ lut[1][c1])
-    const int row_begin = KF == 2 ? blockIdx.x * rows_per_block : 0;
-    const int row_end = KF == 2 ? (row_begin + rows_per_block < 256 ? row_begin + rows_per_block : 256) : 1;
+    // Several blocks per query: the key-list form splits the tuple rows; the form that keeps the
+    // lists on chip evaluates every tuple in every block and splits the surviving tuples evenly
+    // (a query's survivors sit in the few rows of its nearest first-codebook codewords).
+    const int row_begin = KF == 2 && !FUSED ? blockIdx.x * rows_per_block : 0;
+    const int row_end = KF == 2 ? (row_begin + rows_per_block < 256 && !FUSED ? row_begin + rows_per_block : 256) : 1;
     uint32_t m[8];
     uint32_t mine = 0;
     if (KF == 2) {
@@ -394,8 +397,11 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     uint32_t cnt = 0;                          // FUSED: keys in the list (block-uniform)
     uint32_t bound = 0xFFFFFFFFu;              // FUSED: keys with distance bits above it cannot reach the result
 
-    for (uint32_t pass_lo = 0; pass_lo < total_hits; pass_lo += GD_HITS) {
-        const uint32_t nh = total_hits - pass_lo < (uint32_t)GD_HITS ? total_hits - pass_lo : (uint32_t)GD_HITS;
+    // this block's share of the surviving tuples (all of them unless the lists stay on chip)
+    const uint32_t hit_lo = FUSED ? (uint32_t)((uint64_t)total_hits * blockIdx.x / gridDim.x) : 0u;
+    const uint32_t hit_hi = FUSED ? (uint32_t)((uint64_t)total_hits * (blockIdx.x + 1) / gridDim.x) : total_hits;
+    for (uint32_t pass_lo = hit_lo; pass_lo < hit_hi; pass_lo += GD_HITS) {
+        const uint32_t nh = hit_hi - pass_lo < (uint32_t)GD_HITS ? hit_hi - pass_lo : (uint32_t)GD_HITS;
         // ---- tuples number pass_lo .. pass_lo + nh - 1 -> hbuf
         {
             uint32_t idx = off_all;
@@ -599,7 +605,13 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     }
 
     if (!FUSED) return;                        // the atomics have counted the survivors
-    if (tid == 0) count[q] = run;
+    // Several blocks per query (few queries): each keeps the list of its share of the tuple rows
+    // and leaves its topk best as keys (bits of D, id) for the merge kernel.
+    unsigned long long *part = keys_out ? keys_out + ((int64_t)q * gridDim.x + blockIdx.x) * topk : nullptr;
+    if (tid == 0) {
+        if (part) atomicAdd(&count[q], run);
+        else count[q] = run;
+    }
     // ---- final list: exact cut, positions -> ids, order by (D, id)
     if (cnt > (uint32_t)topk) {
         cnt = block_cut(sh, list, cnt, (uint32_t)topk, &bound, true, tid, lane, wave);
@@ -622,12 +634,20 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
         uint32_t rank = 0;
         for (uint32_t j = 0; j < cnt; ++j) rank += list[j] < mine_k ? 1u : 0u;
         if (tid < (int)cnt && rank < (uint32_t)topk) {
-            oi[rank] = (uint32_t)mine_k;
-            od[rank] = icq_unorder_bits((uint32_t)(mine_k >> 32));
+            if (part) {
+                part[rank] = mine_k;
+            } else {
+                oi[rank] = (uint32_t)mine_k;
+                od[rank] = icq_unorder_bits((uint32_t)(mine_k >> 32));
+            }
         }
         for (int r = kept + tid; r < topk; r += GS_THREADS) {
-            oi[r] = ICQ_PAD_ID;
-            od[r] = INFINITY;
+            if (part) {
+                part[r] = KEY_PAD;
+            } else {
+                oi[r] = ICQ_PAD_ID;
+                od[r] = INFINITY;
+            }
         }
         return;
     }
@@ -646,8 +666,12 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     if (wave == 0) wave_sort(list, len, (int)lane);
     __syncthreads();
     for (int r = tid; r < topk; r += GS_THREADS) {
-        oi[r] = r < kept ? (uint32_t)list[r] : ICQ_PAD_ID;
-        od[r] = r < kept ? icq_unorder_bits((uint32_t)(list[r] >> 32)) : INFINITY;
+        if (part) {
+            part[r] = r < kept ? list[r] : KEY_PAD;
+        } else {
+            oi[r] = r < kept ? (uint32_t)list[r] : ICQ_PAD_ID;
+            od[r] = r < kept ? icq_unorder_bits((uint32_t)(list[r] >> 32)) : INFINITY;
+        }
     }
 }
 
@@ -720,7 +744,19 @@ int icq_launch_group_scan(const icq_index *ix, const float *lut, int Q, const fl
 }
 
 bool icq_group_fused(const icq_index *ix, int Q, int topk) {
-    return icq_group_usable(ix, Q) && ix->item_stride <= 16 && topk <= GD_TOPK && group_parts(ix, Q) == 1;
+    return icq_group_usable(ix, Q) && ix->item_stride <= 16 && topk <= GD_TOPK;
+}
+
+// Blocks per query in the fused form: one when the queries alone fill the chip; else each block
+// takes an equal share of the surviving tuples and a merge kernel joins the parts' lists (at most
+// 8 parts of at most 256 keys; more parts measured slower: every block evaluates all tuples and
+// starts with an open bound).
+int icq_group_fused_parts(const icq_index *ix, int Q) {
+    if (ix->Kf != 2 || Q <= 0) return 1;
+    int parts = (4 * ix->num_cu + Q - 1) / Q;
+    if (parts > 8) parts = 8;
+    if (parts < 1) parts = 1;
+    return parts;
 }
 
 int icq_launch_group_keys(const icq_index *ix, const float *lut, int Q, const float *thr,
@@ -728,14 +764,16 @@ int icq_launch_group_keys(const icq_index *ix, const float *lut, int Q, const fl
                           uint32_t *out_ids, float *out_dist, hipStream_t s) {
     // cand_count has been zeroed by the caller (icq_launch_scan); item_stride <= 16 here
     const bool fused = out_ids != nullptr && icq_group_fused(ix, Q, topk);
-    if (!fused && !cand_keys) return ICQ_ERR_ARG;
-    const int parts = group_parts(ix, Q);
+    const int parts = fused ? icq_group_fused_parts(ix, Q) : group_parts(ix, Q);
+    // cand_keys: [Q][cap] keys of the survivors, or (fused, several parts) [Q][parts][topk] part lists
+    if ((!fused || parts > 1) && !cand_keys) return ICQ_ERR_ARG;
     const int rows = (256 + parts - 1) / parts;
     for (int q0 = 0; q0 < Q; q0 += 65535) {
         const int nq = Q - q0 < 65535 ? Q - q0 : 65535;
         dim3 grid((unsigned)parts, (unsigned)nq);
         const float *l = lut + (int64_t)q0 * ix->K * ICQ_LUT_W;
-        unsigned long long *ko = cand_keys ? cand_keys + (int64_t)q0 * cap : nullptr;
+        unsigned long long *ko = fused ? (parts > 1 ? cand_keys + (int64_t)q0 * parts * topk : nullptr)
+                                       : cand_keys + (int64_t)q0 * cap;
         uint32_t *oi = fused ? out_ids + (int64_t)q0 * topk : nullptr;
         float *od = fused ? out_dist + (int64_t)q0 * topk : nullptr;
 #define ICQ_GK(KF, W)                                                                                         \
@@ -757,7 +795,9 @@ int icq_launch_group_keys(const icq_index *ix, const float *lut, int Q, const fl
         }
 #undef ICQ_GK
     }
-    return icq_check_launch();
+    if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;
+    if (fused && parts > 1) return icq_launch_merge(cand_keys, Q, parts, topk, true, out_ids, out_dist, s);
+    return ICQ_OK;
 }
 
 ICQ_EXPORT int icq_index_set_scan_mode(icq_index *ix, int mode) {

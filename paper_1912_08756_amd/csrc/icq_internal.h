@@ -105,6 +105,9 @@ static inline unsigned long long *icq_cand_keys(unsigned long long *keys, int Q,
 }
 // Grouped stage 1 (icq_group.hip); as_positions: list grouped positions instead of ids.
 bool icq_group_usable(const icq_index *ix, int Q);
+int icq_group_fused_parts(const icq_index *ix, int Q);
+int icq_launch_merge(const unsigned long long *keys, int Q, int splits, int topk, bool ascending,
+                     uint32_t *out_ids, float *out_dist, hipStream_t s);
 int icq_launch_group_scan(const icq_index *ix, const float *lut, int Q, const float *thr,
                           uint32_t *cand_ids, bool as_positions, uint32_t *cand_count, int64_t cap,
                           hipStream_t s);

@@ -148,6 +148,47 @@ __global__ __launch_bounds__(RF_THREADS) void merge_kernel(const u64 *__restrict
     }
 }
 
+// grid (Q): join the lists of one query when every list is already ascending (pads last) and all
+// keys differ: a key's row is the number of keys below it, one binary search per list, no sort.
+// LDS: keys[parts * topk].
+__global__ __launch_bounds__(RF_THREADS) void merge_sorted_kernel(const u64 *__restrict__ keys_in, int parts,
+                                                                  int topk, uint32_t *__restrict__ out_ids,
+                                                                  float *__restrict__ out_dist) {
+    extern __shared__ u64 smem64[];
+    u64 *keys = smem64;
+    __shared__ int s_real;
+    const int q = blockIdx.x;
+    const int n = parts * topk;
+    if (threadIdx.x == 0) s_real = 0;
+    for (int i = threadIdx.x; i < n; i += RF_THREADS) keys[i] = keys_in[(int64_t)q * n + i];
+    __syncthreads();
+    auto below = [&](const u64 *list, u64 k) -> int {      // keys of an ascending list that are < k
+        int lo = 0, hi = topk;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (list[mid] < k) lo = mid + 1;
+            else hi = mid;
+        }
+        return lo;
+    };
+    if ((int)threadIdx.x < parts) atomicAdd(&s_real, below(keys + threadIdx.x * topk, KEY_PAD));
+    for (int i = threadIdx.x; i < n; i += RF_THREADS) {
+        const u64 k = keys[i];
+        if (k == KEY_PAD) continue;
+        int rank = 0;
+        for (int p = 0; p < parts && rank < topk; ++p) rank += below(keys + p * topk, k);
+        if (rank < topk) {
+            out_ids[(int64_t)q * topk + rank] = (uint32_t)k;
+            out_dist[(int64_t)q * topk + rank] = unorder_bits((uint32_t)(k >> 32));
+        }
+    }
+    __syncthreads();
+    for (int r = s_real + (int)threadIdx.x; r < topk; r += RF_THREADS) {
+        out_ids[(int64_t)q * topk + r] = ICQ_PAD_ID;
+        out_dist[(int64_t)q * topk + r] = INFINITY;
+    }
+}
+
 int bufn_for(int topk) { return topk <= 256 ? 2048 : 4096; }
 
 // ------------------------------------------------------------------ distances, then bounded select
@@ -491,6 +532,20 @@ __global__ __launch_bounds__(SK_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8
 // (K > 16) the generic streaming kernel.
 static bool use_select(const icq_index *ix, int topk) { return ix->item_stride <= 16 && topk <= 512; }
 
+// keys: [Q][splits][topk] keys (bits of D, id), KEY_PAD where a list is short; splits * topk <= 4096.
+// ascending: every list is sorted (pads last) and no key occurs twice.
+int icq_launch_merge(const unsigned long long *keys, int Q, int splits, int topk, bool ascending,
+                     uint32_t *out_ids, float *out_dist, hipStream_t s) {
+    if (ascending) {
+        merge_sorted_kernel<<<Q, RF_THREADS, sizeof(u64) * splits * topk, s>>>(keys, splits, topk, out_ids, out_dist);
+        return icq_check_launch();
+    }
+    int len = 2;
+    while (len < splits * topk) len <<= 1;
+    merge_kernel<<<Q, RF_THREADS, sizeof(u64) * len, s>>>(keys, splits, topk, len, out_ids, out_dist);
+    return icq_check_launch();
+}
+
 int icq_refine_splits(const icq_index *ix, int Q, int64_t cap, int topk) {
     if (Q <= 0) return 1;
     int64_t s = (4LL * ix->num_cu + Q - 1) / Q;
@@ -547,13 +602,7 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
                                                     bufn, splits, keys, out_ids, out_dist);
     }
     if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;
-    if (splits > 1) {
-        int len = 2;
-        while (len < splits * topk) len <<= 1;
-        merge_kernel<<<Q, RF_THREADS, sizeof(u64) * len, s>>>(keys, splits, topk, len, out_ids,
-                                                              out_dist);
-        return icq_check_launch();
-    }
+    if (splits > 1) return icq_launch_merge(keys, Q, splits, topk, false, out_ids, out_dist, s);
     return ICQ_OK;
 }
 

@@ -10,8 +10,8 @@ icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool
     size_t off = 0;
     L.lut_off = off;
     if (with_lut) off = icq_align_up(off + sizeof(float) * (size_t)Q * ix->K * ICQ_LUT_W, ICQ_ALIGN);
-    // icq_search with the grouped stage 1 owning whole queries keeps the candidates on chip:
-    // no lists in the workspace at all
+    // icq_search with the grouped stage 1 keeping the lists on chip: no candidate lists in the
+    // workspace, only (few queries, several blocks per query) the parts' lists for the merge
     const bool on_chip = with_cands && icq_group_fused(ix, Q, topk);
     L.ids_off = off;
     if (with_cands && !on_chip) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
@@ -20,7 +20,10 @@ icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool
     L.splits = icq_refine_splits(ix, Q, cap, topk);
     L.keys_off = off;
     // slice lists [Q][splits][topk] (when sliced), then one 64-bit key per candidate [Q][cap]
-    if (!on_chip) {
+    if (on_chip) {
+        const int parts = icq_group_fused_parts(ix, Q);
+        if (parts > 1) off = icq_align_up(off + sizeof(unsigned long long) * (size_t)Q * parts * topk, ICQ_ALIGN);
+    } else {
         if (L.splits > 1)
             off = icq_align_up(off + sizeof(unsigned long long) * (size_t)Q * L.splits * topk, 8);
         if (ix->item_stride <= 16)
@@ -83,8 +86,10 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
         int rc = icq_launch_build_lut(ix, queries + (int64_t)q0 * ix->d, nq, lut, s);
         if (rc != ICQ_OK) return rc;
         int list_kind = ICQ_LIST_IDS;
-        unsigned long long *cand_keys = (ix->item_stride <= 16 && topk <= 512 && !icq_group_fused(ix, nq, topk))
-                                            ? icq_cand_keys(keys, nq, L.splits, topk) : nullptr;
+        // keys of the survivors behind the slice lists, or (on-chip lists) the parts' lists
+        unsigned long long *cand_keys = icq_group_fused(ix, nq, topk) ? keys
+                                        : (ix->item_stride <= 16 && topk <= 512) ? icq_cand_keys(keys, nq, L.splits, topk)
+                                                                                 : nullptr;
         rc = icq_launch_scan(ix, lut, nq, thresholds + q0, ids, nullptr, cand_keys, &list_kind, cnt,
                              cap, topk, out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk,
                              timed ? ev[1] : nullptr, s);

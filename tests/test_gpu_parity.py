@@ -277,8 +277,10 @@ def test_search_matches_oracle(gpu, name, N, Q, over, rule, mode):
     _check_search(g, cfg, T, P, D, thr, cfg["topk"], int(exact.max() * 1.2) + 64)
 
 
-# With 512 queries or more a block of the grouped kernel owns its query and keeps the
-# nearest-neighbour list on chip (no candidate list in memory): the cases below run that form.
+# With grouping, record width <= 16 bytes and topk <= 256 the grouped kernel keeps the
+# nearest-neighbour lists on chip (no candidate list in memory).  From 1024 queries on a block
+# owns its query; with fewer, up to 8 blocks share a query's surviving tuples and a merge kernel
+# joins their lists.  The cases below run both forms.
 @pytest.mark.parametrize("name,N,Q,over,rule,topk", [
     ("C1", 70_000, 600, {}, ("q", 0.01), 100),              # about one item per fast-code tuple
     ("C1", 40_000, 512, {}, ("q", 0.02), 128),              # fewer items than tuples
@@ -288,6 +290,13 @@ def test_search_matches_oracle(gpu, name, N, Q, over, rule, mode):
     ("C1", 60_000, 512, {}, ("q", 0.25), 100),              # many surviving tuples: several passes per query
     ("C1", 3_000, 512, {}, ("kth", 3, 1.0), 100),           # fewer survivors than topk
     ("C1", 50_000, 512, {}, ("q", 0.03), 256),              # longest on-chip list: final order by the register sort
+    ("C1", 70_000, 1100, {}, ("q", 0.01), 100),             # one block per query
+    ("C1", 70_000, 24, {}, ("q", 0.01), 100),               # 8 blocks per query
+    ("C3", 150_000, 150, {}, ("q", 0.01), 100),             # 7 blocks per query, clustered codes
+    ("C1", 60_000, 300, {}, ("q", 0.25), 100),              # 4 blocks per query, several passes each
+    ("C1", 3_000, 40, {}, ("kth", 3, 1.0), 100),            # 8 blocks, fewer survivors than topk, some blocks with none
+    ("C1", 50_000, 130, {}, ("q", 0.03), 256),              # 8 blocks, 256 keys each into the merge
+    ("C2", 60_000, 90, dict(d=32, Kf=2), ("q", 0.01), 100), # 8 blocks, 16-byte records
 ])
 def test_search_with_lists_kept_on_chip(gpu, name, N, Q, over, rule, topk):
     cfg = small(name, N, Q, **over)
@@ -347,12 +356,13 @@ def test_search_grouped_with_many_surviving_tuples(gpu):
     assert np.array_equal(surv, surv1) and np.array_equal(out_ids, ids1) and np.array_equal(out_dist, dist1)
 
 
-@pytest.mark.parametrize("mode", [1, 2], ids=["streamed", "grouped"])
-def test_search_with_masses_of_equal_distances(gpu, mode):
+@pytest.mark.parametrize("mode,Q", [(1, 12), (2, 1100), (2, 520), (2, 40)],
+                         ids=["streamed", "grouped-1-block", "grouped-2-blocks", "grouped-8-blocks"])
+def test_search_with_masses_of_equal_distances(gpu, mode, Q):
     """Items drawn from 8 code patterns only: thousands of exactly equal distances, so the
     lists are decided by the item ids alone (order (distance, id)) and every cut of a
-    running list meets far more ties than it can hold."""
-    Q = 12 if mode == 1 else 520                            # 520: the grouped kernel keeps the lists on chip
+    running list meets far more ties than it can hold.  Grouped: the lists stay on chip, with
+    one, two or eight blocks per query."""
     cfg = small("C1", 40_000, Q)
     rng = np.random.default_rng(5)
     patterns = rng.integers(0, 256, size=(cfg["K"], 8), dtype=np.uint8)
