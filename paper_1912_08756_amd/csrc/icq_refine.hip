@@ -215,8 +215,13 @@ __global__ __launch_bounds__(RF_THREADS) void refine_dist_kernel(
     const uint32_t *__restrict__ cand_count, int64_t cap, int blocks_per_query, u64 *__restrict__ keys) {
     __shared__ float T[4 * WORDS * ICQ_LUT_W];
     constexpr int RW = WORDS;                         // words per item record
-    const int q = blockIdx.x / blocks_per_query;
-    const u64 c0 = (u64)(blockIdx.x % blocks_per_query) * RD_BLOCK;
+    // Blocks are numbered piece-major: blocks that run together take the same stretch of every
+    // query's list.  The lists follow the scan order, so those stretches hold ids from the same
+    // regions of the item records, and a record line fetched for one query is still cached when
+    // the other queries' candidates in it are gathered.
+    const int nq = gridDim.x / blocks_per_query;
+    const int q = blockIdx.x % nq;
+    const u64 c0 = (u64)(blockIdx.x / nq) * RD_BLOCK;
     const int tid = threadIdx.x;
     u64 n = cand_count[q];
     if (n > (u64)cap) n = (u64)cap;
