@@ -316,7 +316,10 @@ def configs_leg(torch, b, synth, skip, with_cpu, target_s=4.0):
                              out_dist[q0:q0 + batch], surv[q0:q0 + batch], ws)
         run()
         torch.cuda.synchronize()
-        reps = 3
+        t0 = time.perf_counter()
+        run()
+        torch.cuda.synchronize()
+        reps = int(min(200, max(3, 0.3 / max(time.perf_counter() - t0, 1e-6))))   # about 0.3 s of timed work
         t0 = time.perf_counter()
         for _ in range(reps):
             run()
