@@ -303,29 +303,29 @@ __device__ __forceinline__ uint32_t block_tie_cut(GdShared &sh, unsigned long lo
     return tot;
 }
 
-// grid (parts, Q): a block evaluates the tuples (c0, c1) with c0 in its part's row
-// range for one query; thread t owns column c1 = t (Kf == 2) or tuple c0 = t (Kf == 1)
-// and keeps one bit per row: crude distance below the threshold or not.  The
-// surviving tuples are compacted into LDS (GD_HITS at a time) together with their
-// first grouped position and an exclusive prefix of their sizes (empty tuples
-// dropped), which turns "all items of all surviving tuples" into a flat range of
-// survivor numbers 0 .. tot-1.  The wavefronts walk that range 64 survivors at a
-// time: a lane finds its tuple by counting the tuple boundaries at or below its
-// number, reads the item's record in grouped order (records of one tuple are
-// contiguous, so the loads coalesce) and adds up the K table entries (all K tables
-// of the query in LDS, k ascending, one table per record byte, zero tables beyond K).
+// grid (parts, Q): a block evaluates tuples (c0, c1) for one query; thread t owns column
+// c1 = t (Kf == 2) or tuple c0 = t (Kf == 1) and keeps one bit per row: crude distance below
+// the threshold or not.  The surviving tuples are compacted into LDS (GD_HITS at a time)
+// together with their first grouped position and an exclusive prefix of their sizes (empty
+// tuples dropped), which turns "all items of all surviving tuples" into a flat range of
+// survivor numbers 0 .. tot-1.  The wavefronts walk that range 64 survivors at a time: a lane
+// finds its tuple by counting the tuple boundaries at or below its number, reads the item's
+// record in grouped order (records of one tuple are contiguous, so the loads coalesce) and adds
+// up the K table entries (all K tables of the query in LDS, k ascending, one table per record
+// byte, zero tables beyond K).
 //
-// FUSED (the block owns its query: parts == 1, topk <= GD_TOPK): the nearest-neighbour list of Sec. 3.4
-// is kept right here.  A key (order-preserving bits of D, grouped position) enters the
-// block's list in LDS only if D is at or below the running bound; when the list could
-// overflow it is cut back to the topk smallest distances, which tightens the bound (one
-// histogram pass, see block_cut).  At the end the list is cut exactly, positions become
-// item ids, one wavefront sorts by (D, id) in registers and the result rows are written.
-// No candidate list ever reaches memory.
+// FUSED (topk <= GD_TOPK): the nearest-neighbour list of Sec. 3.4 is kept right here.  A key
+// (order-preserving bits of D, grouped position) enters the block's list in LDS only if D is at
+// or below the running bound; when the list could overflow it is cut back to the topk smallest
+// distances, which tightens the bound (one histogram pass, see block_cut).  At the end the
+// list is cut exactly, positions become item ids and the keys are ranked by (D, id).  No
+// candidate list ever reaches memory.  One block per query writes the result rows; with
+// several (few queries) every block evaluates all tuples, takes an equal share of the surviving
+// ones and leaves its topk best as ascending keys in keys_out[q][part][topk] for the merge.
 //
-// !FUSED (several blocks share a query): every survivor's key (bits of D, item id) is
-// written to slot base + number of the query's key list for the select kernel; each
-// pass reserves its slots with one atomic on the query's counter.
+// !FUSED (topk above GD_TOPK): the blocks of a query split the tuple rows; every survivor's key
+// (bits of D, item id) is written to slot base + number of the query's key list for the select
+// kernel; each pass reserves its slots with one atomic on the query's counter.
 template <int KF, int WORDS, bool FUSED>
 __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORDS == 4 ? 3 : 6, 8))) void group_keys_kernel(
     const float *__restrict__ lut, int K, const float *__restrict__ thr,
