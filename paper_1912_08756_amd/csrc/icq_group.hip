@@ -197,6 +197,7 @@ constexpr int GD_LIST = 1024;     // keys of the block's nearest-neighbour list
 constexpr int GD_LPT = GD_LIST / GS_THREADS;             // list entries per thread in a cut
 constexpr int GD_SORT = 1024;     // most keys the final register sort takes
 constexpr int GD_TOPK = 256;      // longest result the on-chip list serves
+constexpr int GD_OWN = 12;        // surviving tuples a thread lists by itself; more are listed by its wavefront together
 static_assert(GD_HITS <= 2048 && GD_HITS % GS_THREADS == 0, "tuple search covers 64 x 32 entries");
 static_assert(GS_THREADS == 256, "one histogram bin per thread");
 static_assert(GD_ROWS % 2 == 0, "a step is two half steps");
@@ -403,17 +404,40 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     for (uint32_t pass_lo = hit_lo; pass_lo < hit_hi; pass_lo += GD_HITS) {
         const uint32_t nh = hit_hi - pass_lo < (uint32_t)GD_HITS ? hit_hi - pass_lo : (uint32_t)GD_HITS;
         // ---- tuples number pass_lo .. pass_lo + nh - 1 -> hbuf
+        // A thread lists its own hits one by one -- unless it has many: the column of the query's
+        // nearest second-codebook codeword can hold a hundred, and one lane walking them alone
+        // kept its whole block waiting.  Such columns are listed by the wavefront together, 64
+        // rows at a time (same numbering: rows ascending).
         {
-            uint32_t idx = off_all;
+            const bool heavy = mine > (uint32_t)GD_OWN;
+            if (!heavy) {
+                uint32_t idx = off_all;
 #pragma unroll
-            for (int w = 0; w < 8; ++w) {
-                uint32_t bits = m[w];
-                while (bits != 0) {
-                    const int b = __builtin_ctz(bits);
-                    bits &= bits - 1;
-                    const uint32_t rel = idx - pass_lo;             // wraps below the pass: fails the test
-                    if (rel < nh) hbuf[rel] = KF == 2 ? (uint32_t)(w * 32 + b) * 256u + (uint32_t)tid : (uint32_t)tid;
-                    ++idx;
+                for (int w = 0; w < 8; ++w) {
+                    uint32_t bits = m[w];
+                    while (bits != 0) {
+                        const int b = __builtin_ctz(bits);
+                        bits &= bits - 1;
+                        const uint32_t rel = idx - pass_lo;         // wraps below the pass: fails the test
+                        if (rel < nh) hbuf[rel] = KF == 2 ? (uint32_t)(w * 32 + b) * 256u + (uint32_t)tid : (uint32_t)tid;
+                        ++idx;
+                    }
+                }
+            }
+            uint64_t hv = __builtin_amdgcn_ballot_w64(heavy);       // wavefront-uniform
+            while (hv != 0) {
+                const int src = __builtin_ctzll(hv);
+                hv &= hv - 1;
+                uint32_t idx = (uint32_t)__builtin_amdgcn_readlane((int)off_all, src);
+                const uint32_t col = (uint32_t)wave * 64u + (uint32_t)src;
+#pragma unroll
+                for (int wp = 0; wp < 4; ++wp) {
+                    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)m[2 * wp], src);
+                    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)m[2 * wp + 1], src);
+                    const uint32_t mybit = ((lane < 32 ? lo : hi) >> (lane & 31)) & 1u;
+                    const uint32_t rel = __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, idx)) - pass_lo;
+                    if (mybit != 0 && rel < nh) hbuf[rel] = (uint32_t)(wp * 64 + (int)lane) * 256u + col;
+                    idx += (uint32_t)__builtin_popcount(lo) + (uint32_t)__builtin_popcount(hi);
                 }
             }
         }
