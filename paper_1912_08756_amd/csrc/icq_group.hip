@@ -197,7 +197,7 @@ constexpr int GD_LIST = 1024;     // keys of the block's nearest-neighbour list
 constexpr int GD_LPT = GD_LIST / GS_THREADS;             // list entries per thread in a cut
 constexpr int GD_SORT = 1024;     // most keys the final register sort takes
 constexpr int GD_TOPK = 256;      // longest result the on-chip list serves
-constexpr int GD_OWN = 12;        // surviving tuples a thread lists by itself; more are listed by its wavefront together
+constexpr int GD_OWN = 12;        // surviving tuples a thread lists by itself (or four times the average): more are listed by its wavefront together
 static_assert(GD_HITS <= 2048 && GD_HITS % GS_THREADS == 0, "tuple search covers 64 x 32 entries");
 static_assert(GS_THREADS == 256, "one histogram bin per thread");
 static_assert(GD_ROWS % 2 == 0, "a step is two half steps");
@@ -409,7 +409,10 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
         // kept its whole block waiting.  Such columns are listed by the wavefront together, 64
         // rows at a time (same numbering: rows ascending).
         {
-            const bool heavy = mine > (uint32_t)GD_OWN;
+            // many = far above the average of the block's threads: the walk by one lane costs as many
+            // rounds as its wavefront's longest list, the joint listing a fixed amount per column
+            const uint32_t own = total_hits / 64 > (uint32_t)GD_OWN ? total_hits / 64 : (uint32_t)GD_OWN;
+            const bool heavy = mine > own;
             if (!heavy) {
                 uint32_t idx = off_all;
 #pragma unroll
