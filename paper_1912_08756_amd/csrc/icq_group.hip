@@ -217,13 +217,7 @@ struct GdShared {
 // Contains two barriers; every thread calls it.
 __device__ __forceinline__ void block_scan2(uint32_t a, uint32_t b, uint32_t (*wsum)[2], uint32_t lane, int wave,
                                             uint32_t &ex_a, uint32_t &ex_b, uint32_t &tot_a, uint32_t &tot_b) {
-    uint32_t ia = a, ib = b;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t oa = __shfl_up(ia, d, 64);
-        const uint32_t ob = __shfl_up(ib, d, 64);
-        if ((int)lane >= d) { ia += oa; ib += ob; }
-    }
+    const uint32_t ia = wave_scan_add(a), ib = wave_scan_add(b);
     __syncthreads();                       // earlier readers of wsum are done
     if (lane == 63) { wsum[wave][0] = ia; wsum[wave][1] = ib; }
     __syncthreads();

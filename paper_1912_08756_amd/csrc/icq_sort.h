@@ -15,6 +15,47 @@ __device__ __forceinline__ float icq_unorder_bits(uint32_t u) {
 
 constexpr int ICQ_SORT_THREADS = 256;   // block size block_sort is written for
 
+// Wavefront scans and reductions on the data-parallel-primitive path of the vector unit: a lane
+// reads its neighbour's register directly (row shifts inside the rows of 16 lanes, then lane 15 and
+// lane 31 broadcast to the rows after them), so a step is two vector instructions and nothing goes
+// through the LDS crossbar -- a shuffle there is a round trip that a dependent chain of six waits
+// for six times.  FILL is what a lane without a source adds (the identity of the operation).
+template <int CTRL, int ROW_MASK, uint32_t FILL>
+__device__ __forceinline__ uint32_t icq_dpp(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)FILL, (int)x, CTRL, ROW_MASK, 0xf, false);
+}
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ uint32_t wave_scan_add(uint32_t x) {
+    x += icq_dpp<0x111, 0xf, 0u>(x);       // row_shr:1
+    x += icq_dpp<0x112, 0xf, 0u>(x);       // row_shr:2
+    x += icq_dpp<0x114, 0xf, 0u>(x);       // row_shr:4
+    x += icq_dpp<0x118, 0xf, 0u>(x);       // row_shr:8
+    x += icq_dpp<0x142, 0xa, 0u>(x);       // row_bcast:15 into rows 1 and 3
+    x += icq_dpp<0x143, 0xc, 0u>(x);       // row_bcast:31 into rows 2 and 3
+    return x;
+}
+// minimum / maximum over the 64 lanes, in every lane
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
+    uint32_t y;
+    y = icq_dpp<0x111, 0xf, 0xFFFFFFFFu>(x); x = y < x ? y : x;
+    y = icq_dpp<0x112, 0xf, 0xFFFFFFFFu>(x); x = y < x ? y : x;
+    y = icq_dpp<0x114, 0xf, 0xFFFFFFFFu>(x); x = y < x ? y : x;
+    y = icq_dpp<0x118, 0xf, 0xFFFFFFFFu>(x); x = y < x ? y : x;
+    y = icq_dpp<0x142, 0xa, 0xFFFFFFFFu>(x); x = y < x ? y : x;
+    y = icq_dpp<0x143, 0xc, 0xFFFFFFFFu>(x); x = y < x ? y : x;
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
+    uint32_t y;
+    y = icq_dpp<0x111, 0xf, 0u>(x); x = y > x ? y : x;
+    y = icq_dpp<0x112, 0xf, 0u>(x); x = y > x ? y : x;
+    y = icq_dpp<0x114, 0xf, 0u>(x); x = y > x ? y : x;
+    y = icq_dpp<0x118, 0xf, 0u>(x); x = y > x ? y : x;
+    y = icq_dpp<0x142, 0xa, 0u>(x); x = y > x ? y : x;
+    y = icq_dpp<0x143, 0xc, 0u>(x); x = y > x ? y : x;
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+
 // Compare-exchange steps j = jmax, jmax/2, .., 1 of bitonic stage k on the element
 // a lane holds, against lanes lane^j of its own wavefront (no LDS, no barrier).
 __device__ __forceinline__ u64 wave_bitonic_steps(u64 x, int e, int k, int jmax) {
@@ -142,12 +183,8 @@ __device__ __forceinline__ uint32_t block_kth(IcqKthShared &sh, const uint32_t (
             vmax = v[u] > vmax ? v[u] : vmax;
         }
     }
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) {
-        const uint32_t a = __shfl_xor(vmin, d, 64), b = __shfl_xor(vmax, d, 64);
-        vmin = a < vmin ? a : vmin;
-        vmax = b > vmax ? b : vmax;
-    }
+    vmin = wave_min_u32(vmin);
+    vmax = wave_max_u32(vmax);
     __syncthreads();                       // earlier readers of wred / hist are done
     if (lane == 0) { sh.wred[wave][0] = vmin; sh.wred[wave][1] = vmax; }
     __syncthreads();
@@ -184,12 +221,7 @@ __device__ __forceinline__ uint32_t block_kth(IcqKthShared &sh, const uint32_t (
             h[r] = sh.hist[lane * 4 + r];
             mine += h[r];
         }
-        uint32_t incl = mine;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t o = __shfl_up(incl, d, 64);
-            if ((int)lane >= d) incl += o;
-        }
+        const uint32_t incl = wave_scan_add(mine);
         const int L = __builtin_ctzll(__builtin_amdgcn_ballot_w64(incl >= kr));
         uint32_t run = incl - mine, my_bin = 0, my_below = 0;
 #pragma unroll
