@@ -125,12 +125,7 @@ __global__ __launch_bounds__(GS_THREADS) void group_scan_kernel(
                 s = start[g];
                 n = start[g + 1] - s;
             }
-            uint32_t incl = n;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const uint32_t o = __shfl_up(incl, d, 64);
-                if ((int)lane >= d) incl += o;
-            }
+            const uint32_t incl = wave_scan_add(n);
             const uint32_t tot = __builtin_amdgcn_readlane(incl, 63);
             if (tot == 0) continue;
             uint32_t base = 0;

@@ -325,12 +325,7 @@ __device__ __forceinline__ void find_bin(SelectShared *sh, uint32_t kr) {
         h[r] = sh->hist[lane * 4 + r];
         mine += h[r];
     }
-    uint32_t incl = mine;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(incl, d, 64);
-        if (lane >= d) incl += o;
-    }
+    const uint32_t incl = wave_scan_add(mine);
     uint32_t run = incl - mine;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -396,12 +391,8 @@ __device__ uint32_t wave_cut_list(SelectShared *sh, u64 *list, uint32_t *U, uint
             umax = u > umax ? u : umax;
         }
     }
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) {
-        const uint32_t a = __shfl_xor(umin, d, 64), b = __shfl_xor(umax, d, 64);
-        umin = a < umin ? a : umin;
-        umax = b > umax ? b : umax;
-    }
+    umin = wave_min_u32(umin);
+    umax = wave_max_u32(umax);
     __syncthreads();
     const uint32_t cut = wave_radix_select(sh, U, cnt, (uint32_t)topk, umin, umax);
     __syncthreads();
@@ -464,12 +455,8 @@ __global__ __launch_bounds__(SK_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8
                     umax = u > umax ? u : umax;
                 }
             }
-#pragma unroll
-            for (int d = 32; d > 0; d >>= 1) {
-                const uint32_t a = __shfl_xor(umin, d, 64), b = __shfl_xor(umax, d, 64);
-                umin = a < umin ? a : umin;
-                umax = b > umax ? b : umax;
-            }
+            umin = wave_min_u32(umin);
+            umax = wave_max_u32(umax);
             __syncthreads();
             if (n1 > (uint32_t)topk) ubound = wave_radix_select(&sh, U, n1, (uint32_t)topk, umin, umax);
         }

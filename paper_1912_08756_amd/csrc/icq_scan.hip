@@ -13,6 +13,7 @@
 // Both list survivor ids only; crude distances are filled in afterwards for the
 // listed ids when the caller wants them.
 #include "icq_internal.h"
+#include "icq_sort.h"
 
 #include <math.h>
 
@@ -266,12 +267,12 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
         for (int b = 0; b < B; ++b) {
             // lane w < 16 takes wavefront w's count; prefix over the 16 lanes
             const uint32_t c = lane < SS_WAVES ? s_wcnt[b][lane] : 0u;
+            static_assert(SS_WAVES == 16, "the prefix below covers one DPP row of 16 lanes");
             uint32_t incl = c;
-#pragma unroll
-            for (int d = 1; d < SS_WAVES; d <<= 1) {
-                const uint32_t o = __shfl_up(incl, d, 64);
-                if ((int)lane >= d) incl += o;
-            }
+            incl += icq_dpp<0x111, 0xf, 0u>(incl);
+            incl += icq_dpp<0x112, 0xf, 0u>(incl);
+            incl += icq_dpp<0x114, 0xf, 0u>(incl);
+            incl += icq_dpp<0x118, 0xf, 0u>(incl);
             pre[b] = (uint32_t)__builtin_amdgcn_readlane((int)(incl - c), wave);
             tot[b] = (uint32_t)__builtin_amdgcn_readlane((int)incl, SS_WAVES - 1);
             any |= __builtin_amdgcn_ballot_w64(c > wave_cap / 2) != 0;
