@@ -178,7 +178,7 @@ int icq_refine(const icq_index *index, const float *lut, int Q, const uint32_t *
  * icq_workspace_bytes(index, Q, cap, topk)).  out_survivors [Q] (may be NULL)
  * receives the true survivor count of each query; a value above cap means
  * that query's list overflowed and its result may miss neighbours (when the
- * index is grouped, the call has 512 queries or more and topk <= 256, the
+ * grouped stage 1 runs, records are at most 16 bytes and topk <= 256, the
  * candidates never leave the chip and the result is complete whatever cap is).
  */
 int icq_search(const icq_index *index, const float *queries, int Q, const float *thresholds,
