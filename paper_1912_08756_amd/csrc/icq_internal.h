@@ -53,7 +53,8 @@ enum icq_list_kind {
 __device__ __forceinline__ void icq_hit_shift_in(uint32_t &hm, float P, float t) {
     // the two wait states are the ones the compiler itself puts between a vector instruction that
     // writes VCC and one that reads it (it does not look inside an asm statement)
-    asm("v_cmp_gt_f32 vcc, %2, %1\n\ts_nop 1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(hm) : "v"(P), "v"(t) : "vcc");
+    // (t is wavefront-uniform where this is used and may stay in a scalar register: first source of the compare)
+    asm("v_cmp_gt_f32 vcc, %2, %1\n\ts_nop 1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(hm) : "v"(P), "s"(t) : "vcc");
 }
 
 // Order-preserving bits of a float: u(a) < u(b) <=> a < b.

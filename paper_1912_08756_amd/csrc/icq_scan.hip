@@ -187,7 +187,9 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
 #pragma unroll
                 for (int k = 0; k < KF; ++k) {
                     const uint32_t word = j < 4 ? w[k].x : j < 8 ? w[k].y : j < 12 ? w[k].z : w[k].w;
-                    const uint32_t code = (word >> (8 * (j & 3))) & 0xffu;     // byte extract + shift-add: two instructions
+                    // bit-field extract as a builtin, so that the shift is not pulled in front of the mask:
+                    // extract + shift-add, two instructions for every byte
+                    const uint32_t code = __builtin_amdgcn_ubfe(word, 8 * (j & 3), 8);
                     off[jj][k] = (code << ENTRY_SHIFT) + copy_off;
                 }
             }
