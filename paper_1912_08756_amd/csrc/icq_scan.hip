@@ -187,9 +187,11 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
 #pragma unroll
                 for (int k = 0; k < KF; ++k) {
                     const uint32_t word = j < 4 ? w[k].x : j < 8 ? w[k].y : j < 12 ? w[k].z : w[k].w;
-                    // bit-field extract as a builtin, so that the shift is not pulled in front of the mask:
-                    // extract + shift-add, two instructions for every byte
-                    const uint32_t code = __builtin_amdgcn_ubfe(word, 8 * (j & 3), 8);
+                    // extract + shift-add: two instructions per byte.  For the lowest byte the compiler
+                    // pulls the shift in front of the mask and needs three, hence the opaque extract.
+                    uint32_t code;
+                    if ((j & 3) == 0) asm("v_bfe_u32 %0, %1, 0, 8" : "=v"(code) : "v"(word));
+                    else code = (word >> (8 * (j & 3))) & 0xffu;
                     off[jj][k] = (code << ENTRY_SHIFT) + copy_off;
                 }
             }
