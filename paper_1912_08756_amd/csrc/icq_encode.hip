@@ -9,14 +9,22 @@
 // argmin_j (||c_j||^2 - 2<r,c_j>), followed by the residual update of the block's own
 // rows.
 #include "icq_internal.h"
+#include "icq_sort.h"
 
 #include <math.h>
 
 namespace {
 
-typedef float float16v __attribute__((ext_vector_type(16)));
-typedef unsigned long long u64;
+// the smaller of a lane's key and its DPP neighbour's (a lane without a source keeps its own)
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ u64 dpp_min64(u64 key) {
+    const uint32_t lo = icq_dpp<CTRL, ROW_MASK, 0xFFFFFFFFu>((uint32_t)key);
+    const uint32_t hi = icq_dpp<CTRL, ROW_MASK, 0xFFFFFFFFu>((uint32_t)(key >> 32));
+    const u64 o = ((u64)hi << 32) | lo;
+    return o < key ? o : key;
+}
 
+typedef float float16v __attribute__((ext_vector_type(16)));
 constexpr int EM = 64;            // items per block
 constexpr int EN = ICQ_LUT_W;     // codewords per level: the whole codebook (rows j >= m have norm +inf)
 constexpr int EK = 16;            // reduction slice staged in LDS
@@ -91,12 +99,14 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
                 const u64 kj = ((u64)icq_order_bits(score) << 32) | (uint32_t)(wave * 64 + j * 32 + (lane & 31));
                 key = kj < key ? kj : key;
             }
-#pragma unroll
-            for (int dlt = 1; dlt < 32; dlt <<= 1) {
-                const u64 o = __shfl_xor(key, dlt, 64);
-                key = o < key ? o : key;
-            }
-            if ((lane & 31) == 0) best[wave][i * 32 + (v & 3) + 4 * (lane >> 5) + 8 * (v >> 2)] = key;
+            // minimum over each half of 32 lanes on the DPP path (row shifts, then lane 15 of rows 0 and 2
+            // into rows 1 and 3): lanes 31 and 63 end up with their half's smallest key
+            key = dpp_min64<0x111, 0xf>(key);
+            key = dpp_min64<0x112, 0xf>(key);
+            key = dpp_min64<0x114, 0xf>(key);
+            key = dpp_min64<0x118, 0xf>(key);
+            key = dpp_min64<0x142, 0xa>(key);
+            if ((lane & 31) == 31) best[wave][i * 32 + (v & 3) + 4 * (lane >> 5) + 8 * (v >> 2)] = key;
         }
     }
     __syncthreads();
