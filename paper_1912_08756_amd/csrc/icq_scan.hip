@@ -171,12 +171,10 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
             if (slot < (uint64_t)cap) dst[slot] = src[i];
         }
     };
-    // the 1024 items at g held in w: table sums, hit bits, staging
-    auto process = [&](uint32_t g, const uint4 (&w)[KF]) {
+    // the 1024 items at g held in w: table sums and hit bits.  hm[b] (zero on entry) receives the hit
+    // bits of this lane's 16 items for query b, item j in bit 15 - j.
+    auto hits = [&](uint32_t g, const uint4 (&w)[KF], uint32_t (&hm)[B]) {
         const uint32_t id0 = g + lane * 16;
-        uint32_t hm[B];   // hit bits of this lane's 16 items (item j in bit 15 - j), one mask per query
-#pragma unroll
-        for (int b = 0; b < B; ++b) hm[b] = 0;
 #pragma unroll
         for (int h = 0; h < 16; h += SS_HALF) {
             // phase 1: every table address of the half step
@@ -236,7 +234,13 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
 #pragma unroll
             for (int b = 0; b < B; ++b) hm[b] &= valid;
         }
-        // compaction: each round appends every lane's lowest remaining hit
+    };
+    // With two register sets the hit bits of two consecutive steps share one compaction: the earlier
+    // step's bits sit in the upper half of the mask, so one round of ballots serves 2048 items.
+    constexpr bool PAIR = R == 2;
+    // compaction: each round appends every lane's lowest remaining hit.  Bit p of hm[b] names item
+    // id_lo + 15 - p (p < 16) or id_hi + 31 - p.
+    auto compact = [&](uint32_t (&hm)[B], uint32_t id_hi, uint32_t id_lo) {
 #pragma unroll
         for (int b = 0; b < B; ++b) {
             uint32_t *mine_stage = stage + ((uint32_t)b * SS_WAVES + wave) * wave_cap;
@@ -251,7 +255,10 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
                     move_out(b, mine_stage, wc[b], gb);
                     wc[b] = 0;
                 }
-                if (hm[b] != 0) mine_stage[wc[b] + rank] = id0 + 15u - (uint32_t)__builtin_ctz(hm[b]);
+                if (hm[b] != 0) {
+                    const uint32_t p = (uint32_t)__builtin_ctz(hm[b]);
+                    mine_stage[wc[b] + rank] = (PAIR && p >= 16 ? id_hi + 31u : id_lo + 15u) - p;
+                }
                 wc[b] += n;
                 hm[b] &= hm[b] - 1;
                 mask = __builtin_amdgcn_ballot_w64(hm[b] != 0);
@@ -299,14 +306,35 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
 #pragma unroll
     for (int r = 0; r < R - 1; ++r) load(g + (uint32_t)r * step, w[r]);
     fill_tables();
+    static_assert(SS_CHECK % 2 == 0, "a pair of steps never straddles a periodic check");
+    uint32_t held[B];        // PAIR: the even step's hit bits, waiting for the odd step's
+    uint32_t id_held = 0;
+#pragma unroll
+    for (int b = 0; b < B; ++b) held[b] = 0;
     for (uint32_t it = 0; it < nsteps; it += R, g += R * step) {
 #pragma unroll
         for (int u = 0; u < R; ++u) {
             load(g + (uint32_t)(u + R - 1) * step, w[(u + R - 1) % R]);     // never conditional
             const uint32_t gu = g + (uint32_t)u * step, itu = it + u;
-            if (gu < end && gu >= begin) process(gu, w[u]);
-            if (itu < nsteps && ((itu % SS_CHECK) == SS_CHECK - 1 || itu == nsteps - 1))   // block-uniform
-                flush_check(itu == nsteps - 1);
+            const uint32_t idu = gu + lane * 16;
+            const bool check = itu < nsteps && ((itu % SS_CHECK) == SS_CHECK - 1 || itu == nsteps - 1);   // block-uniform
+            uint32_t hm[B];
+#pragma unroll
+            for (int b = 0; b < B; ++b) hm[b] = 0;
+            if (gu < end && gu >= begin) hits(gu, w[u], hm);
+            if (PAIR && u % 2 == 0) {
+#pragma unroll
+                for (int b = 0; b < B; ++b) held[b] = hm[b] << 16;
+                id_held = idu;
+                if (check) compact(held, id_held, id_held);   // the last step of the range (leaves held zero)
+            } else if (PAIR) {
+#pragma unroll
+                for (int b = 0; b < B; ++b) held[b] |= hm[b];
+                compact(held, id_held, idu);
+            } else {
+                compact(hm, idu, idu);
+            }
+            if (check) flush_check(itu == nsteps - 1);
         }
     }
 }
