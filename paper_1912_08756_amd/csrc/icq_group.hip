@@ -186,6 +186,7 @@ __global__ __launch_bounds__(GS_THREADS) void group_scan_kernel(
 // ---- grouped stage 1 fused with stage 2
 constexpr int GD_HITS = 1024;     // tuples below the threshold handled per pass
 constexpr int GD_PER = GD_HITS / GS_THREADS;
+constexpr int GD_SEED = 4;         // survivors of a pass's first part, in result lengths
 constexpr int GD_ROWS = 2;        // rows of 64 survivors per wavefront and step
 constexpr int GD_STEP = GD_ROWS * GS_THREADS;            // most keys one step can add to the list
 constexpr int GD_LIST = 1024;     // keys of the block's nearest-neighbour list
@@ -205,6 +206,7 @@ struct GdShared {
     uint32_t wsum[GS_THREADS / 64][2];
     uint32_t flag[GS_THREADS / 64][64];    // locate(): stamps of the tuple starts inside a row of survivors
     uint32_t base;
+    float tmin[16];                        // smallest entry of each of the query's tables
 };
 
 // Inclusive scan of two counters over the block (GS_THREADS threads); returns the
@@ -293,6 +295,20 @@ __device__ __forceinline__ uint32_t block_tie_cut(GdShared &sh, unsigned long lo
     return tot;
 }
 
+// Tuples whose crude distance P has order bits above the returned value cannot hold an item
+// that reaches the result: every item's distance is P plus one entry of each remaining table,
+// so D >= P + smin (smin = the sum of those tables' smallest entries), and with P above
+// dk * (1 + 1e-5) - smin that exceeds dk, the distance behind `bound`.  All tables are
+// non-negative where this is used; the 1e-5 covers the roundings of the fp32 sums on both
+// sides (7 additions of non-negative terms lose less than 8 * 2^-24 of the sum, the sum of
+// the minima and the two operations here as much again: under 3e-6 in all).
+__device__ __forceinline__ uint32_t prune_above(uint32_t bound, float smin) {
+    if (bound >= 0xFF800000u) return 0xFFFFFFFFu;     // open, infinite or not a number: nothing is pruned
+    float tb = icq_unorder_bits(bound) * (1.0f + 1e-5f) - smin;
+    if (!(tb > 0.0f)) tb = 0.0f;                      // P >= 0: a tuple at 0 is never pruned
+    return icq_order_bits(tb);
+}
+
 // grid (parts, Q): a block evaluates tuples (c0, c1) for one query; thread t owns column
 // c1 = t (Kf == 2) or tuple c0 = t (Kf == 1) and keeps one bit per row: crude distance below
 // the threshold or not.  The surviving tuples are compacted into LDS (GD_HITS at a time)
@@ -379,10 +395,31 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     }
 #pragma unroll
     for (int r = 0; r < T_PER; ++r) reinterpret_cast<float4 *>(T)[r * GS_THREADS + tid] = tv[r];
+    if (FUSED) {
+        // load r of wavefront w is table 4 r + w, whole: its smallest entry (tables beyond K hold zeros)
+#pragma unroll
+        for (int r = 0; r < T_PER; ++r) {
+            const float v = wave_min_f32(fminf(fminf(tv[r].x, tv[r].y), fminf(tv[r].z, tv[r].w)));
+            if (lane == 0) sh.tmin[r * 4 + wave] = v;
+        }
+    }
     // this thread's surviving tuples are numbers [off_all, off_all + mine) of the block's total_hits
     uint32_t off_all, dummy0, total_hits, dummy1;
     block_scan2(mine, 0u, sh.wsum, lane, wave, off_all, dummy0, total_hits, dummy1);
 
+    // FUSED: the bound of the list also prunes whole tuples (prune_above) -- if no table entry is negative
+    float smin = 0.0f;
+    bool prune_ok = false;
+    if (FUSED) {
+        float all = INFINITY;
+#pragma unroll
+        for (int k = 0; k < 4 * WORDS; ++k) {
+            const float v = sh.tmin[k];            // written before the barriers of the scan above
+            all = fminf(all, v);
+            if (k >= KF) smin += v;
+        }
+        prune_ok = all >= 0.0f;
+    }
     uint32_t run = 0;                          // survivors so far (block-uniform)
     uint32_t cnt = 0;                          // FUSED: keys in the list (block-uniform)
     uint32_t bound = 0xFFFFFFFFu;              // FUSED: keys with distance bits above it cannot reach the result
@@ -437,27 +474,68 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
 
         // ---- first position and size of every buffered tuple
         uint32_t s[GD_PER], n[GD_PER];
-        uint32_t tn = 0, tc = 0;
+        uint32_t pb[GD_PER];                   // FUSED: order bits of the tuple's crude distance
 #pragma unroll
         for (int u = 0; u < GD_PER; ++u) {
             const uint32_t h = (uint32_t)u * GS_THREADS + tid;
             const uint32_t g = hbuf[h < nh ? h : 0];
             s[u] = start[g];
             n[u] = start[g + 1];
+            // the same sum as in the evaluation above, from the tables in LDS
+            if (FUSED) pb[u] = icq_order_bits(KF == 2 ? T[g >> 8] + T[ICQ_LUT_W + (g & 255u)] : T[g]);
         }
 #pragma unroll
         for (int u = 0; u < GD_PER; ++u) {
             const uint32_t h = (uint32_t)u * GS_THREADS + tid;
             n[u] = h < nh ? n[u] - s[u] : 0u;
-            tn += n[u];
-            tc += n[u] != 0 ? 1u : 0u;
+        }
+        // FUSED: the pass runs in two parts while the list has no bound yet -- first the tuples
+        // with the smallest crude distances, about GD_SEED * topk survivors, whose topk-th distance
+        // then bounds the list and, through prune_above, the tuples of the second part.  Later
+        // passes start with the bound of the earlier ones.
+        int nsp = 1;
+        uint32_t pivot = 0xFFFFFFFFu;
+        if (FUSED) {
+            uint32_t tn_all = 0, tc_all = 0, okm = 0;
+#pragma unroll
+            for (int u = 0; u < GD_PER; ++u) {
+                tn_all += n[u];
+                tc_all += n[u] != 0 ? 1u : 0u;
+                okm |= n[u] != 0 ? 1u << u : 0u;
+            }
+            uint32_t d0, d1, tot_all, nhc_all;
+            block_scan2(tn_all, tc_all, sh.wsum, lane, wave, d0, d1, tot_all, nhc_all);   // its barriers also order the hbuf reads above
+            run += tot_all;
+            if (tot_all == 0) continue;        // block-uniform
+            if (prune_ok && bound == 0xFFFFFFFFu && tot_all > (uint32_t)(4 * GD_SEED * topk)) {
+                // so many tuples, smallest crude distances first, that they hold about GD_SEED * topk survivors
+                uint32_t kt = (uint32_t)(((uint64_t)GD_SEED * topk * nhc_all + tot_all - 1) / tot_all);
+                kt = kt < 1 ? 1 : kt > nhc_all ? nhc_all : kt;
+                pivot = block_kth<GD_PER>(sh.kth, pb, okm, kt, false, tid, lane, wave);
+                nsp = 2;
+            }
+        }
+#pragma nounroll
+        for (int sp = 0; sp < nsp; ++sp) {
+        uint32_t sel = 0;                      // this part's tuples among the thread's GD_PER
+        uint32_t tn = 0, tc = 0;
+        {
+            const uint32_t above = FUSED && prune_ok ? prune_above(bound, smin) : 0xFFFFFFFFu;
+#pragma unroll
+            for (int u = 0; u < GD_PER; ++u) {
+                bool in = n[u] != 0;
+                if (FUSED) in = in && pb[u] <= above && (nsp == 1 || (pb[u] <= pivot) == (sp == 0));
+                sel |= in ? 1u << u : 0u;
+                tn += in ? n[u] : 0u;
+                tc += in ? 1u : 0u;
+            }
         }
         uint32_t x, c, tot, nhc;
         block_scan2(tn, tc, sh.wsum, lane, wave, x, c, tot, nhc);   // its barriers also order the hbuf reads above
         if (tot == 0) continue;                // block-uniform
 #pragma unroll
         for (int u = 0; u < GD_PER; ++u) {
-            if (n[u] != 0) {
+            if ((sel >> u) & 1u) {
                 hbuf[c] = s[u] - x;            // first position minus prefix (mod 2^32): position = this + survivor number
                 hx[c] = x;
                 ++c;
@@ -470,7 +548,7 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
         }
         __syncthreads();
         const uint32_t base = FUSED ? 0u : sh.base;
-        run += tot;
+        if (!FUSED) run += tot;
 
         // ---- the survivors, 64 per row; the rows are dealt to the wavefronts in contiguous runs
         const uint32_t nrows = (tot + 63) >> 6;
@@ -617,7 +695,11 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
                 }
             }
         }
-        __syncthreads();                       // hbuf / hx are rewritten by the next pass
+        __syncthreads();                       // hbuf / hx are rewritten by the next part or pass
+        // the first part's topk-th distance (upper end of its histogram bin) becomes the bound
+        if (FUSED && nsp == 2 && sp == 0 && cnt > (uint32_t)topk)
+            cnt = block_cut(sh, list, cnt, (uint32_t)topk, &bound, false, tid, lane, wave);
+        }
     }
 
     if (!FUSED) return;                        // the atomics have counted the survivors

@@ -34,6 +34,17 @@ __device__ __forceinline__ uint32_t wave_scan_add(uint32_t x) {
     x += icq_dpp<0x143, 0xc, 0u>(x);       // row_bcast:31 into rows 2 and 3
     return x;
 }
+// minimum over the 64 lanes (wavefront-uniform result); a NaN loses against any number
+__device__ __forceinline__ float wave_min_f32(float x) {
+    constexpr uint32_t INF = 0x7F800000u;
+    x = fminf(x, __uint_as_float(icq_dpp<0x111, 0xf, INF>(__float_as_uint(x))));
+    x = fminf(x, __uint_as_float(icq_dpp<0x112, 0xf, INF>(__float_as_uint(x))));
+    x = fminf(x, __uint_as_float(icq_dpp<0x114, 0xf, INF>(__float_as_uint(x))));
+    x = fminf(x, __uint_as_float(icq_dpp<0x118, 0xf, INF>(__float_as_uint(x))));
+    x = fminf(x, __uint_as_float(icq_dpp<0x142, 0xa, INF>(__float_as_uint(x))));
+    x = fminf(x, __uint_as_float(icq_dpp<0x143, 0xc, INF>(__float_as_uint(x))));
+    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(x), 63));
+}
 // minimum / maximum over the 64 lanes, in every lane
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
     uint32_t y;
