@@ -186,7 +186,10 @@ __global__ __launch_bounds__(GS_THREADS) void group_scan_kernel(
 // ---- grouped stage 1 fused with stage 2
 constexpr int GD_HITS = 1024;     // tuples below the threshold handled per pass
 constexpr int GD_PER = GD_HITS / GS_THREADS;
-constexpr int GD_SEED = 4;         // survivors of a pass's first part, in result lengths
+#ifndef GD_SEED_V
+#define GD_SEED_V 4
+#endif
+constexpr int GD_SEED = GD_SEED_V;         // survivors of a pass's first part, in result lengths
 constexpr int GD_ROWS = 2;        // rows of 64 survivors per wavefront and step
 constexpr int GD_STEP = GD_ROWS * GS_THREADS;            // most keys one step can add to the list
 constexpr int GD_LIST = 1024;     // keys of the block's nearest-neighbour list
@@ -508,10 +511,8 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
             run += tot_all;
             if (tot_all == 0) continue;        // block-uniform
             if (prune_ok && bound == 0xFFFFFFFFu && tot_all > (uint32_t)(4 * GD_SEED * topk)) {
-                // so many tuples, smallest crude distances first, that they hold about GD_SEED * topk survivors
-                uint32_t kt = (uint32_t)(((uint64_t)GD_SEED * topk * nhc_all + tot_all - 1) / tot_all);
-                kt = kt < 1 ? 1 : kt > nhc_all ? nhc_all : kt;
-                pivot = block_kth<GD_PER>(sh.kth, pb, okm, kt, false, tid, lane, wave);
+                // tuples up to the crude distance below which GD_SEED * topk survivors lie (tuple sizes as weights)
+                pivot = block_kth_weighted<GD_PER>(sh.kth, pb, n, okm, (uint32_t)(GD_SEED * topk), tid, lane, wave);
                 nsp = 2;
             }
         }

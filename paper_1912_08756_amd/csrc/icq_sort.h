@@ -183,9 +183,10 @@ struct IcqKthShared {
 // digits over the occupied range).  Otherwise a single counting pass over the top 8 bits
 // of the occupied range; the result is the largest value of the bin that holds the kr-th
 // smallest, i.e. an upper bound that keeps the bin whole.  Every thread calls (barriers).
-template <int LPT>
-__device__ __forceinline__ uint32_t block_kth(IcqKthShared &sh, const uint32_t (&v)[LPT], uint32_t ok, uint32_t kr,
-                                              bool EXACT, int tid, uint32_t lane, int wave) {
+// WEIGHTED: value v[u] counts wgt[u] times (kr at most the flagged weights' sum, which fits 32 bits).
+template <int LPT, bool WEIGHTED>
+__device__ __forceinline__ uint32_t block_kth_impl(IcqKthShared &sh, const uint32_t (&v)[LPT], const uint32_t (&wgt)[LPT],
+                                                   uint32_t ok, uint32_t kr, bool EXACT, int tid, uint32_t lane, int wave) {
     uint32_t vmin = 0xFFFFFFFFu, vmax = 0u;
 #pragma unroll
     for (int u = 0; u < LPT; ++u) {
@@ -221,7 +222,7 @@ __device__ __forceinline__ uint32_t block_kth(IcqKthShared &sh, const uint32_t (
             if ((ok >> u) & 1u) {
                 const uint32_t y = v[u] - vmin;
                 const bool match = fixed_from >= 32 ? true : (y >> fixed_from) == prefix;
-                if (match) atomicAdd(&sh.hist[(y >> shift) & dmask], 1u);
+                if (match) atomicAdd(&sh.hist[(y >> shift) & dmask], WEIGHTED ? wgt[u] : 1u);
             }
         }
         __syncthreads();
@@ -257,5 +258,17 @@ __device__ __forceinline__ uint32_t block_kth(IcqKthShared &sh, const uint32_t (
     if (shift == 0) return vmin + prefix;
     const unsigned long long top = (unsigned long long)vmin + ((((unsigned long long)prefix + 1ull) << shift) - 1ull);
     return top < (unsigned long long)vmax ? (uint32_t)top : vmax;
+}
+template <int LPT>
+__device__ __forceinline__ uint32_t block_kth(IcqKthShared &sh, const uint32_t (&v)[LPT], uint32_t ok, uint32_t kr,
+                                              bool EXACT, int tid, uint32_t lane, int wave) {
+    return block_kth_impl<LPT, false>(sh, v, v, ok, kr, EXACT, tid, lane, wave);
+}
+// One counting pass with weights: the top of the first bin at which the weights of the flagged
+// values at or below it add up to kr or more.
+template <int LPT>
+__device__ __forceinline__ uint32_t block_kth_weighted(IcqKthShared &sh, const uint32_t (&v)[LPT], const uint32_t (&wgt)[LPT],
+                                                       uint32_t ok, uint32_t kr, int tid, uint32_t lane, int wave) {
+    return block_kth_impl<LPT, true>(sh, v, wgt, ok, kr, false, tid, lane, wave);
 }
 
