@@ -377,16 +377,30 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     uint32_t mine = 0;
     if (KF == 2) {
         const float t1 = Tq[ICQ_LUT_W + tid];
+        // The 256 row values come through scalar registers, 32 in use and 32 on their way: left to
+        // itself the compiler may start all 256 loads first, and then they overflow the scalar
+        // registers and travel through vector lanes (one more instruction per row, twice).
+        float rowv[2][32];
+#pragma unroll
+        for (int b = 0; b < 32; ++b) rowv[0][b] = Tq[b];
 #pragma unroll
         for (int w = 0; w < 8; ++w) {
             uint32_t bits = 0;
+            if (w < 7) {
+                // an offset the compiler cannot see through: these loads start here, not earlier
+                int nxt = (w + 1) * 32;
+                asm volatile("" : "+s"(nxt));
+#pragma unroll
+                for (int b = 0; b < 32; ++b) rowv[(w + 1) & 1][b] = Tq[nxt + b];
+            }
             if (w * 32 + 32 > row_begin && w * 32 < row_end) {       // block-uniform
 #pragma unroll
-                for (int b = 0; b < 32; ++b) bits |= (Tq[w * 32 + b] + t1 < t ? 1u : 0u) << b;
+                for (int b = 0; b < 32; ++b) bits |= (rowv[w & 1][b] + t1 < t ? 1u : 0u) << b;
                 const int lo = row_begin - w * 32, hi = row_end - w * 32;
                 if (lo > 0) bits &= ~0u << lo;
                 if (hi < 32) bits &= ~(~0u << hi);
             }
+            asm volatile("" : "+v"(bits));                           // ... and this word is done before the next but one loads
             m[w] = bits;
             mine += __builtin_popcount(bits);
         }
