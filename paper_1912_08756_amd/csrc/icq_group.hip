@@ -184,7 +184,7 @@ __global__ __launch_bounds__(GS_THREADS) void group_scan_kernel(
 }
 
 // ---- grouped stage 1 fused with stage 2
-constexpr int GD_HITS = 1024;     // tuples below the threshold handled per pass
+constexpr int GD_HITS = 768;      // tuples below the threshold handled per pass
 constexpr int GD_PER = GD_HITS / GS_THREADS;
 #ifndef GD_SEED_V
 #define GD_SEED_V 4
@@ -210,6 +210,8 @@ struct GdShared {
     uint32_t flag[GS_THREADS / 64][64];    // locate(): stamps of the tuple starts inside a row of survivors
     uint32_t base;
     float tmin[16];                        // smallest entry of each of the query's tables
+    float colmin[GS_THREADS / 64];         // smallest second-codebook entry of each wavefront's columns
+    uint32_t nlive[GS_THREADS / 64];       // rows that can hold a hit, per wavefront of rows
 };
 
 // Inclusive scan of two counters over the block (GS_THREADS threads); returns the
@@ -344,7 +346,8 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     uint32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
     __shared__ __attribute__((aligned(16))) float T[4 * WORDS * ICQ_LUT_W];
     __shared__ uint32_t hbuf[GD_HITS];        // tuple ids while compacting, then first positions
-    __shared__ uint32_t hx[GD_HITS + 1];      // exclusive prefix of the tuple sizes, hx[nhc] = tot
+    __shared__ __attribute__((aligned(16))) uint32_t hx[GD_HITS + 1];      // exclusive prefix of the tuple sizes, hx[nhc] = tot
+    __shared__ uint8_t rowid[256];            // KF == 2: the rows that can hold a hit, ascending
     __shared__ unsigned long long list[FUSED ? GD_LIST : 1];
     __shared__ GdShared sh;
     const int tid = threadIdx.x;
@@ -373,37 +376,60 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     // (a query's survivors sit in the few rows of its nearest first-codebook codewords).
     const int row_begin = KF == 2 && !FUSED ? blockIdx.x * rows_per_block : 0;
     const int row_end = KF == 2 ? (row_begin + rows_per_block < 256 && !FUSED ? row_begin + rows_per_block : 256) : 1;
+    // m: one bit per live row (KF == 2: bit i stands for row rowid[i], see below) or the tuple's own bit (KF == 1)
     uint32_t m[8];
     uint32_t mine = 0;
     if (KF == 2) {
+        // Rows that can hold a hit at all: lut[0][row] + (the smallest lut[1][.]) < t.  Rounding is
+        // monotone, so a row that fails this fails with every column.  A query's hits sit in the
+        // rows of its few nearest first-codebook codewords: the live rows are numbered 0 .. nlive - 1
+        // in row order, their values go to LDS (hx is free until the first pass) and the
+        // evaluation walks those only, 32 at a time (padded with +inf).
         const float t1 = Tq[ICQ_LUT_W + tid];
-        // The 256 row values come through scalar registers, 32 in use and 32 on their way: left to
-        // itself the compiler may start all 256 loads first, and then they overflow the scalar
-        // registers and travel through vector lanes (one more instruction per row, twice).
-        float rowv[2][32];
+        const float r0v = Tq[tid];                                   // this thread's row, for the liveness test
+        const float wmin = wave_min_f32(t1);
+        if (lane == 0) sh.colmin[wave] = wmin;
+        __syncthreads();
+        float cmin = sh.colmin[0];
 #pragma unroll
-        for (int b = 0; b < 32; ++b) rowv[0][b] = Tq[b];
+        for (int w = 1; w < GS_THREADS / 64; ++w) cmin = fminf(cmin, sh.colmin[w]);
+        const bool live = tid >= row_begin && tid < row_end && r0v + cmin < t;
+        const uint64_t lv = __builtin_amdgcn_ballot_w64(live);
+        if (lane == 0) sh.nlive[wave] = (uint32_t)__builtin_popcountll(lv);
+        __syncthreads();
+        uint32_t before = 0, nlive = 0;
+#pragma unroll
+        for (int w = 0; w < GS_THREADS / 64; ++w) {
+            const uint32_t c = (uint32_t)__builtin_amdgcn_readfirstlane((int)sh.nlive[w]);
+            if (w < wave) before += c;
+            nlive += c;
+        }
+        float *rowT = reinterpret_cast<float *>(hx);
+        if (live) {
+            const uint32_t slot = __builtin_amdgcn_mbcnt_hi((uint32_t)(lv >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)lv, before));
+            rowT[slot] = r0v;
+            rowid[slot] = (uint8_t)tid;
+        }
+        const uint32_t nlive_pad = (nlive + 31u) & ~31u;
+        if ((uint32_t)tid >= nlive && (uint32_t)tid < nlive_pad) rowT[tid] = INFINITY;
+        __syncthreads();
 #pragma unroll
         for (int w = 0; w < 8; ++w) {
             uint32_t bits = 0;
-            if (w < 7) {
-                // an offset the compiler cannot see through: these loads start here, not earlier
-                int nxt = (w + 1) * 32;
-                asm volatile("" : "+s"(nxt));
+            if ((uint32_t)(w * 32) < nlive) {                        // block-uniform
 #pragma unroll
-                for (int b = 0; b < 32; ++b) rowv[(w + 1) & 1][b] = Tq[nxt + b];
+                for (int b4 = 0; b4 < 8; ++b4) {
+                    const float4 v = reinterpret_cast<const float4 *>(rowT)[w * 8 + b4];   // one address for all lanes
+                    bits |= (v.x + t1 < t ? 1u : 0u) << (b4 * 4);
+                    bits |= (v.y + t1 < t ? 1u : 0u) << (b4 * 4 + 1);
+                    bits |= (v.z + t1 < t ? 1u : 0u) << (b4 * 4 + 2);
+                    bits |= (v.w + t1 < t ? 1u : 0u) << (b4 * 4 + 3);
+                }
             }
-            if (w * 32 + 32 > row_begin && w * 32 < row_end) {       // block-uniform
-#pragma unroll
-                for (int b = 0; b < 32; ++b) bits |= (rowv[w & 1][b] + t1 < t ? 1u : 0u) << b;
-                const int lo = row_begin - w * 32, hi = row_end - w * 32;
-                if (lo > 0) bits &= ~0u << lo;
-                if (hi < 32) bits &= ~(~0u << hi);
-            }
-            asm volatile("" : "+v"(bits));                           // ... and this word is done before the next but one loads
             m[w] = bits;
             mine += __builtin_popcount(bits);
         }
+        // (hx is next written in the first pass, behind the barriers of the scan below)
     } else {
 #pragma unroll
         for (int w = 0; w < 8; ++w) m[w] = 0;
@@ -465,7 +491,7 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
                         const int b = __builtin_ctz(bits);
                         bits &= bits - 1;
                         const uint32_t rel = idx - pass_lo;         // wraps below the pass: fails the test
-                        if (rel < nh) hbuf[rel] = KF == 2 ? (uint32_t)(w * 32 + b) * 256u + (uint32_t)tid : (uint32_t)tid;
+                        if (rel < nh) hbuf[rel] = KF == 2 ? (uint32_t)rowid[w * 32 + b] * 256u + (uint32_t)tid : (uint32_t)tid;
                         ++idx;
                     }
                 }
@@ -482,7 +508,7 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
                     const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)m[2 * wp + 1], src);
                     const uint32_t mybit = ((lane < 32 ? lo : hi) >> (lane & 31)) & 1u;
                     const uint32_t rel = __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, idx)) - pass_lo;
-                    if (mybit != 0 && rel < nh) hbuf[rel] = (uint32_t)(wp * 64 + (int)lane) * 256u + col;
+                    if (mybit != 0 && rel < nh) hbuf[rel] = (uint32_t)rowid[wp * 64 + (int)lane] * 256u + col;
                     idx += (uint32_t)__builtin_popcount(lo) + (uint32_t)__builtin_popcount(hi);
                 }
             }
