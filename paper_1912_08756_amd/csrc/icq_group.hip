@@ -379,6 +379,7 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     // m: one bit per live row (KF == 2: bit i stands for row rowid[i], see below) or the tuple's own bit (KF == 1)
     uint32_t m[8];
     uint32_t mine = 0;
+    uint32_t live_words = 1;                   // words of m that can hold a bit (block-uniform)
     if (KF == 2) {
         // Rows that can hold a hit at all: lut[0][row] + (the smallest lut[1][.]) < t.  Rounding is
         // monotone, so a row that fails this fails with every column.  A query's hits sit in the
@@ -411,6 +412,7 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
             rowid[slot] = (uint8_t)tid;
         }
         const uint32_t nlive_pad = (nlive + 31u) & ~31u;
+        live_words = nlive_pad >> 5;
         if ((uint32_t)tid >= nlive && (uint32_t)tid < nlive_pad) rowT[tid] = INFINITY;
         __syncthreads();
 #pragma unroll
@@ -486,7 +488,7 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
                 uint32_t idx = off_all;
 #pragma unroll
                 for (int w = 0; w < 8; ++w) {
-                    uint32_t bits = m[w];
+                    uint32_t bits = (uint32_t)w < live_words ? m[w] : 0u;
                     while (bits != 0) {
                         const int b = __builtin_ctz(bits);
                         bits &= bits - 1;
@@ -504,6 +506,7 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
                 const uint32_t col = (uint32_t)wave * 64u + (uint32_t)src;
 #pragma unroll
                 for (int wp = 0; wp < 4; ++wp) {
+                    if ((uint32_t)(2 * wp) >= live_words) break;    // block-uniform
                     const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)m[2 * wp], src);
                     const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)m[2 * wp + 1], src);
                     const uint32_t mybit = ((lane < 32 ? lo : hi) >> (lane & 31)) & 1u;
@@ -752,7 +755,10 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
         else count[q] = run;
     }
     // ---- final list: exact cut, positions -> ids, order by (D, id)
-    if (cnt > (uint32_t)topk) {
+    // (the ranking below drops what a counting cut leaves beyond topk; the exact cut is for the
+    // lists that one counting pass leaves longer than a block's worth of keys)
+    if (cnt > (uint32_t)GS_THREADS) cnt = block_cut(sh, list, cnt, (uint32_t)topk, &bound, false, tid, lane, wave);
+    if (cnt > (uint32_t)GS_THREADS) {
         cnt = block_cut(sh, list, cnt, (uint32_t)topk, &bound, true, tid, lane, wave);
         if (cnt > (uint32_t)GD_SORT) cnt = block_tie_cut(sh, list, cnt, (uint32_t)topk, bound, perm, tid, lane, wave);
     }
