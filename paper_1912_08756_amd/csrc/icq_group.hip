@@ -348,7 +348,7 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     __shared__ uint32_t hbuf[GD_HITS];        // tuple ids while compacting, then first positions
     __shared__ __attribute__((aligned(16))) uint32_t hx[GD_HITS + 1];      // exclusive prefix of the tuple sizes, hx[nhc] = tot
     __shared__ uint8_t rowid[256];            // KF == 2: the rows that can hold a hit, ascending
-    __shared__ unsigned long long list[FUSED ? GD_LIST : 1];
+    __shared__ __attribute__((aligned(16))) unsigned long long list[FUSED ? GD_LIST : 2];
     __shared__ GdShared sh;
     const int tid = threadIdx.x;
     const uint32_t lane = lane_id();
@@ -774,10 +774,14 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
             mine_k = (k & 0xFFFFFFFF00000000ull) | perm[(uint32_t)k];
         }
         __syncthreads();
-        if (tid < (int)cnt) list[tid] = mine_k;
+        if (tid <= (int)cnt) list[tid] = mine_k;       // list[cnt] = KEY_PAD: the keys are read in pairs
         __syncthreads();
         uint32_t rank = 0;
-        for (uint32_t j = 0; j < cnt; ++j) rank += list[j] < mine_k ? 1u : 0u;
+        for (uint32_t j = 0; j < cnt; j += 2) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(&list[j]);   // one address for all lanes
+            rank += (((unsigned long long)v.y << 32) | v.x) < mine_k ? 1u : 0u;
+            rank += (((unsigned long long)v.w << 32) | v.z) < mine_k ? 1u : 0u;
+        }
         if (tid < (int)cnt && rank < (uint32_t)topk) {
             if (part) {
                 part[rank] = mine_k;
