@@ -450,9 +450,11 @@ def main():
                 "traffic": traffic["bytes"] if traffic else None, "traffic_detail": traffic,
                 "ms": round(stage[1], 4), "algorithmic_bytes": alg_bytes,
                 "note": "bytes per launch = survivors*K code bytes + Q*4*K*256 table bytes + Q*topk*8 result bytes; "
-                        "duration = stage-1 event pair inside the timed icq_search calls.  The kernel is bound by "
-                        "instruction issue, not by memory: about 85 instructions per 64 survivors (record gather, 8 "
-                        "table reads from LDS, position bookkeeping) plus 65536 tuple evaluations per query"}
+                        "duration = stage-1 event pair inside the timed icq_search calls.  The algorithmic bytes are "
+                        "the method's (every survivor refined); the kernel skips the tuples that its list's bound "
+                        "excludes (crude distance + smallest possible remainder above the topk-th distance, same "
+                        "result), so it visits about a third of the survivors and 'traffic' is well below them.  It "
+                        "is bound by instruction issue (92 % of the vector issue slots), not by memory"}
 
     result = {
         "metric": "queries/sec at top-%d (oracle-matched)" % topk,
