@@ -902,7 +902,7 @@ bool icq_group_fused(const icq_index *ix, int Q, int topk) {
 // starts with an open bound).
 int icq_group_fused_parts(const icq_index *ix, int Q) {
     if (ix->Kf != 2 || Q <= 0) return 1;
-    int parts = (4 * ix->num_cu + Q - 1) / Q;
+    int parts = (2 * ix->num_cu + Q - 1) / Q;
     if (parts > 8) parts = 8;
     if (parts < 1) parts = 1;
     return parts;

@@ -292,11 +292,12 @@ def test_search_matches_oracle(gpu, name, N, Q, over, rule, mode):
     ("C1", 50_000, 512, {}, ("q", 0.03), 256),              # longest on-chip list: final order by the register sort
     ("C1", 70_000, 1100, {}, ("q", 0.01), 100),             # one block per query
     ("C1", 70_000, 24, {}, ("q", 0.01), 100),               # 8 blocks per query
-    ("C3", 150_000, 150, {}, ("q", 0.01), 100),             # 7 blocks per query, clustered codes
-    ("C1", 60_000, 300, {}, ("q", 0.25), 100),              # 4 blocks per query, several passes each
+    ("C3", 150_000, 150, {}, ("q", 0.01), 100),             # 4 blocks per query, clustered codes
+    ("C3", 150_000, 75, {}, ("q", 0.01), 100),              # 7 blocks per query, clustered codes
+    ("C1", 60_000, 300, {}, ("q", 0.25), 100),              # 2 blocks per query, several passes each
     ("C1", 3_000, 40, {}, ("kth", 3, 1.0), 100),            # 8 blocks, fewer survivors than topk, some blocks with none
-    ("C1", 50_000, 130, {}, ("q", 0.03), 256),              # 8 blocks, 256 keys each into the merge
-    ("C2", 60_000, 90, dict(d=32, Kf=2), ("q", 0.01), 100), # 8 blocks, 16-byte records
+    ("C1", 50_000, 130, {}, ("q", 0.03), 256),              # 4 blocks, 256 keys each into the merge
+    ("C2", 60_000, 90, dict(d=32, Kf=2), ("q", 0.01), 100), # 6 blocks, 16-byte records
 ])
 def test_search_with_lists_kept_on_chip(gpu, name, N, Q, over, rule, topk):
     cfg = small(name, N, Q, **over)
@@ -356,7 +357,7 @@ def test_search_grouped_with_many_surviving_tuples(gpu):
     assert np.array_equal(surv, surv1) and np.array_equal(out_ids, ids1) and np.array_equal(out_dist, dist1)
 
 
-@pytest.mark.parametrize("mode,Q", [(1, 12), (2, 1100), (2, 520), (2, 40)],
+@pytest.mark.parametrize("mode,Q", [(1, 12), (2, 1100), (2, 300), (2, 40)],
                          ids=["streamed", "grouped-1-block", "grouped-2-blocks", "grouped-8-blocks"])
 def test_search_with_masses_of_equal_distances(gpu, mode, Q):
     """Items drawn from 8 code patterns only: thousands of exactly equal distances, so the
