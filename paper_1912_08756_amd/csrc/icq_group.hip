@@ -315,8 +315,8 @@ __device__ __forceinline__ uint32_t prune_above(uint32_t bound, float smin) {
 }
 
 // grid (parts, Q): a block evaluates tuples (c0, c1) for one query; thread t owns column
-// c1 = t (Kf == 2) or tuple c0 = t (Kf == 1) and keeps one bit per row: crude distance below
-// the threshold or not.  The surviving tuples are compacted into LDS (GD_HITS at a time)
+// c1 = t (Kf == 2) or tuple c0 = t (Kf == 1) and keeps one bit per row that can hold a hit (see
+// the evaluation): crude distance below the threshold or not.  The surviving tuples are compacted into LDS (GD_HITS at a time)
 // together with their first grouped position and an exclusive prefix of their sizes (empty
 // tuples dropped), which turns "all items of all surviving tuples" into a flat range of
 // survivor numbers 0 .. tot-1.  The wavefronts walk that range 64 survivors at a time: a lane
@@ -328,9 +328,13 @@ __device__ __forceinline__ uint32_t prune_above(uint32_t bound, float smin) {
 // FUSED (topk <= GD_TOPK): the nearest-neighbour list of Sec. 3.4 is kept right here.  A key
 // (order-preserving bits of D, grouped position) enters the block's list in LDS only if D is at
 // or below the running bound; when the list could overflow it is cut back to the topk smallest
-// distances, which tightens the bound (one histogram pass, see block_cut).  At the end the
-// list is cut exactly, positions become item ids and the keys are ranked by (D, id).  No
-// candidate list ever reaches memory.  One block per query writes the result rows; with
+// distances, which tightens the bound (one histogram pass, see block_cut).  The bound also
+// prunes whole tuples (prune_above: crude distance + the smallest the other tables can add is
+// beyond it), and to have one early a pass whose list is still open first takes the tuples with
+// the smallest crude distances, a few topk survivors' worth, and then the rest, pruned; the
+// result and the survivor count (tuple sizes) are those of visiting everything.  At the end
+// positions become item ids and the keys are ranked by (D, id) -- after one counting cut if the
+// list is longer than a block's worth of keys.  No candidate list ever reaches memory.  One block per query writes the result rows; with
 // several (few queries) every block evaluates all tuples, takes an equal share of the surviving
 // ones and leaves its topk best as ascending keys in keys_out[q][part][topk] for the merge.
 //
