@@ -4,6 +4,7 @@
 // The inner products are one [Q x d] . [d x K*256] contraction and run on the
 // fp32 matrix cores (v_mfma_f32_32x32x2_f32); norms are added in the epilogue.
 #include "icq_internal.h"
+#include "icq_sort.h"
 
 namespace {
 
@@ -37,7 +38,7 @@ __global__ __launch_bounds__(256) void build_lut_kernel(const float *__restrict_
 
     float16v acc;
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-    float qn = 0.0f;
+    float qn[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // this thread's share of ||q||^2 of its four staged rows
 
     for (int k0 = 0; k0 < d_pad; k0 += BK) {
         float a[4], b[4];
@@ -49,6 +50,8 @@ __global__ __launch_bounds__(256) void build_lut_kernel(const float *__restrict_
             a[p] = (q < Q && e < d) ? queries[(int64_t)q * d + e] : 0.0f;
             b[p] = cb[(int64_t)(n0 + row) * d_pad + e];
         }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) qn[p] = fmaf(a[p], a[p], qn[p]);
         __syncthreads();   // previous slice fully consumed
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
@@ -56,13 +59,6 @@ __global__ __launch_bounds__(256) void build_lut_kernel(const float *__restrict_
             Bs[le][lr + 16 * p] = b[p];
         }
         __syncthreads();
-        if (tid < BM) {
-#pragma unroll
-            for (int e = 0; e < BK; ++e) {
-                float x = As[e][tid];
-                qn = fmaf(x, x, qn);
-            }
-        }
 #pragma unroll
         for (int s = 0; s < BK / 2; ++s) {
             float av = As[2 * s + (lane >> 5)][wm * 32 + (lane & 31)];
@@ -70,7 +66,16 @@ __global__ __launch_bounds__(256) void build_lut_kernel(const float *__restrict_
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
         }
     }
-    if (tid < BM) qn_s[tid] = qn;
+    // the 16 threads of a staged row are 16 consecutive lanes: sum their shares (lane 15 of the row ends with the total)
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        float x = qn[p];
+        x += __uint_as_float(icq_dpp<0x111, 0xf, 0u>(__float_as_uint(x)));
+        x += __uint_as_float(icq_dpp<0x112, 0xf, 0u>(__float_as_uint(x)));
+        x += __uint_as_float(icq_dpp<0x114, 0xf, 0u>(__float_as_uint(x)));
+        x += __uint_as_float(icq_dpp<0x118, 0xf, 0u>(__float_as_uint(x)));
+        if (le == 15) qn_s[lr + 16 * p] = x;
+    }
     __syncthreads();
 
     const int col = n0 + wn * 32 + (lane & 31);
