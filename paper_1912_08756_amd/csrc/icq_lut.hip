@@ -40,18 +40,28 @@ __global__ __launch_bounds__(256) void build_lut_kernel(const float *__restrict_
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
     float qn[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // this thread's share of ||q||^2 of its four staged rows
 
+    // Rows past Q read the last query instead (their results are never stored) and columns past d
+    // read column d - 1 (the codebook copy is zero there, so the product vanishes): no load
+    // depends on a condition, so all eight of a slice are in flight together.
+    const float *qrow[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int q = q0 + lr + 16 * p;
+        qrow[p] = queries + (int64_t)(q < Q ? q : Q - 1) * d;
+    }
     for (int k0 = 0; k0 < d_pad; k0 += BK) {
         float a[4], b[4];
+        const int e = k0 + le;
+        const int ec = e < d ? e : d - 1;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-            int row = lr + 16 * p;
-            int q = q0 + row;
-            int e = k0 + le;
-            a[p] = (q < Q && e < d) ? queries[(int64_t)q * d + e] : 0.0f;
-            b[p] = cb[(int64_t)(n0 + row) * d_pad + e];
+            a[p] = qrow[p][ec];
+            b[p] = cb[(int64_t)(n0 + lr + 16 * p) * d_pad + e];
         }
+        if (e < d) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) qn[p] = fmaf(a[p], a[p], qn[p]);
+            for (int p = 0; p < 4; ++p) qn[p] = fmaf(a[p], a[p], qn[p]);
+        }
         __syncthreads();   // previous slice fully consumed
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
@@ -80,11 +90,24 @@ __global__ __launch_bounds__(256) void build_lut_kernel(const float *__restrict_
 
     const int col = n0 + wn * 32 + (lane & 31);
     const float cn = cnorm[col];
+    // all 16 values first, then the stores back to back: a store inside a branch of its own is
+    // followed by a wait for everything outstanding, the previous store included
+    float r[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-        int i = (v & 3) + 4 * (lane >> 5) + 8 * (v >> 2);
-        int q = q0 + wm * 32 + i;
-        if (q < Q) lut[(int64_t)q * ncols + col] = (qn_s[wm * 32 + i] + cn) - 2.0f * acc[v];
+        const int i = (v & 3) + 4 * (lane >> 5) + 8 * (v >> 2);
+        r[v] = (qn_s[wm * 32 + i] + cn) - 2.0f * acc[v];
+    }
+    float *out = lut + (int64_t)(q0 + wm * 32 + 4 * (lane >> 5)) * ncols + col;
+    if (q0 + wm * 32 + 32 <= Q) {            // wavefront-uniform: every row of the 32 exists
+#pragma unroll
+        for (int v = 0; v < 16; ++v) out[(int64_t)((v & 3) + 8 * (v >> 2)) * ncols] = r[v];
+    } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = (v & 3) + 4 * (lane >> 5) + 8 * (v >> 2);
+            if (q0 + wm * 32 + i < Q) out[(int64_t)((v & 3) + 8 * (v >> 2)) * ncols] = r[v];
+        }
     }
 }
 
