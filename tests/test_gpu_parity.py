@@ -551,6 +551,26 @@ def test_stream_scan_at_full_length_properties(gpu):
             check_candidates(P[q], thr[q], ids[q], part[q], cnt[q], cap)
 
 
+@pytest.mark.gpu
+def test_stream_scan_of_an_array_beyond_the_last_level_cache(gpu):
+    """Fast codes of more than 256 MB (Kf = 4, N = 6.72e7): with one or two queries per pass the
+    streaming kernel then reads them with the non-temporal hint.  Survivor sets against the
+    oracle's crude distances, element by element."""
+    torch, b = gpu
+    cfg = synth.make("C4", N=67_200_003, Q=2, K=4)
+    g = Gpu(gpu, cfg)
+    T = orc.lut(cfg["codebooks"], cfg["queries"])
+    P = orc.partial(T, cfg["codes"], 4)
+    thr = thresholds_quantile(P, 0.005)
+    cap = 500_000
+    lut = g.lut()
+    for nq in (1, 2):
+        ids, part, cnt = g.scan(lut[:nq].contiguous(), thr[:nq], cap)
+        ids, part, cnt = _u32(ids), part.cpu().numpy(), _u32(cnt)
+        for q in range(nq):
+            check_candidates(P[q], thr[q], ids[q], part[q], cnt[q], cap)
+
+
 # ------------------------------------------------------------------ threshold policy, operation counts
 @pytest.mark.parametrize("name,N,Q,over,topk,M", [
     ("C1", 30_000, 70, {}, 100, 4096),
