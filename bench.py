@@ -120,7 +120,7 @@ def hbm_leg(torch, b, steps, warmup):
         surv = int(cnt.sum().item())
         alg_bytes = Kf * N + 4 * Q * Kf * 256 + 4 * surv      # codes once, tables, survivor ids
         achieved = alg_bytes / (ms * 1e-3) / 1e9
-        out["B%d" % Q] = {"bound": "hbm", "kernel": "scan_stream_kernel<4,%d>" % Q, "achieved": round(achieved, 1),
+        out["B%d" % Q] = {"bound": "hbm", "kernel": "scan_stream_kernel<4,%d,%s>" % (Q, "true" if Q <= 2 else "false"), "achieved": round(achieved, 1),
                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                           "traffic": (pmc_traffic("scan_stream_kernel_B%d" % Q) or {}).get("bytes"),
                           "ms": round(ms, 4),
@@ -485,7 +485,7 @@ def main():
         lds_bytes = 4.0 * Kf * N * Q                 # one 4-byte table read per (query, item, fast codebook)
         ach = lds_bytes / (stage_s[1] * 1e-3) / 1e9
         result["roofline_streamed"] = {
-            "bound": "lds", "kernel": "scan_stream_kernel<%d,4>" % Kf, "achieved": round(ach, 1),
+            "bound": "lds", "kernel": "scan_stream_kernel<%d,4,false>" % Kf, "achieved": round(ach, 1),
             "peak": round(LDS_PEAK_GBS, 1), "unit": "GB/s", "frac": round(ach / LDS_PEAK_GBS, 4), "traffic": None,
             "ms": round(stage_s[1], 4), "ms_per_step": round(ms_s, 4),
             "queries_per_s": round(Q / (ms_s * 1e-3), 1),
