@@ -553,8 +553,9 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
                 tc_all += n[u] != 0 ? 1u : 0u;
                 okm |= n[u] != 0 ? 1u << u : 0u;
             }
-            uint32_t d0, d1, tot_all, nhc_all;
-            block_scan2(tn_all, tc_all, sh.wsum, lane, wave, d0, d1, tot_all, nhc_all);   // its barriers also order the hbuf reads above
+            uint32_t d0, d1, tot_all, nonempty;
+            block_scan2(tn_all, tc_all, sh.wsum, lane, wave, d0, d1, tot_all, nonempty);  // its barriers also order the hbuf reads above
+            (void)nonempty;
             run += tot_all;
             if (tot_all == 0) continue;        // block-uniform
             if (prune_ok && bound == 0xFFFFFFFFu && tot_all > (uint32_t)(4 * GD_SEED * topk)) {
@@ -565,188 +566,188 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
         }
 #pragma nounroll
         for (int sp = 0; sp < nsp; ++sp) {
-        uint32_t sel = 0;                      // this part's tuples among the thread's GD_PER
-        uint32_t tn = 0, tc = 0;
-        {
-            const uint32_t above = FUSED && prune_ok ? prune_above(bound, smin) : 0xFFFFFFFFu;
+            uint32_t sel = 0;                      // this part's tuples among the thread's GD_PER
+            uint32_t tn = 0, tc = 0;
+            {
+                const uint32_t above = FUSED && prune_ok ? prune_above(bound, smin) : 0xFFFFFFFFu;
+#pragma unroll
+                for (int u = 0; u < GD_PER; ++u) {
+                    bool in = n[u] != 0;
+                    if (FUSED) in = in && pb[u] <= above && (nsp == 1 || (pb[u] <= pivot) == (sp == 0));
+                    sel |= in ? 1u << u : 0u;
+                    tn += in ? n[u] : 0u;
+                    tc += in ? 1u : 0u;
+                }
+            }
+            uint32_t x, c, tot, nhc;
+            block_scan2(tn, tc, sh.wsum, lane, wave, x, c, tot, nhc);   // its barriers also order the hbuf reads above
+            if (tot == 0) continue;                // block-uniform
 #pragma unroll
             for (int u = 0; u < GD_PER; ++u) {
-                bool in = n[u] != 0;
-                if (FUSED) in = in && pb[u] <= above && (nsp == 1 || (pb[u] <= pivot) == (sp == 0));
-                sel |= in ? 1u << u : 0u;
-                tn += in ? n[u] : 0u;
-                tc += in ? 1u : 0u;
+                if ((sel >> u) & 1u) {
+                    hbuf[c] = s[u] - x;            // first position minus prefix (mod 2^32): position = this + survivor number
+                    hx[c] = x;
+                    ++c;
+                    x += n[u];
+                }
             }
-        }
-        uint32_t x, c, tot, nhc;
-        block_scan2(tn, tc, sh.wsum, lane, wave, x, c, tot, nhc);   // its barriers also order the hbuf reads above
-        if (tot == 0) continue;                // block-uniform
-#pragma unroll
-        for (int u = 0; u < GD_PER; ++u) {
-            if ((sel >> u) & 1u) {
-                hbuf[c] = s[u] - x;            // first position minus prefix (mod 2^32): position = this + survivor number
-                hx[c] = x;
-                ++c;
-                x += n[u];
+            if (tid == 0) {
+                hx[nhc] = tot;
+                if (!FUSED) sh.base = atomicAdd(&count[q], tot);
             }
-        }
-        if (tid == 0) {
-            hx[nhc] = tot;
-            if (!FUSED) sh.base = atomicAdd(&count[q], tot);
-        }
-        __syncthreads();
-        const uint32_t base = FUSED ? 0u : sh.base;
-        if (!FUSED) run += tot;
+            __syncthreads();
+            const uint32_t base = FUSED ? 0u : sh.base;
+            if (!FUSED) run += tot;
 
-        // ---- the survivors, 64 per row; the rows are dealt to the wavefronts in contiguous runs
-        const uint32_t nrows = (tot + 63) >> 6;
-        const uint32_t rpw = (nrows + GS_THREADS / 64 - 1) / (GS_THREADS / 64);
-        const uint32_t r0 = (uint32_t)wave * rpw;
-        const uint32_t rend = r0 + rpw < nrows ? r0 + rpw : nrows;        // <= r0: nothing for this wavefront
-        const uint32_t steps = (rpw + GD_ROWS - 1) / GD_ROWS;              // block-uniform
-        const uint32_t lane4 = (lane + 1) * 4, nhc4 = nhc * 4;
-        const uint32_t lim = rend * 64 < tot ? rend * 64 : tot;            // end of this wavefront's survivors
-        uint32_t ha = 0;
-        if (r0 < rend) {
-            // tuple holding survivor r0 * 64: the last one whose prefix is <= it (two 64-way probes)
-            const uint32_t p = r0 * 64;
-            const uint32_t i1 = lane * 32;
-            const uint32_t v1 = hx[i1 < nhc ? i1 : nhc];
-            const uint32_t c1 = __builtin_popcountll(__builtin_amdgcn_ballot_w64(i1 < nhc && v1 <= p));
-            const uint32_t b0 = (c1 - 1) * 32;
-            const uint32_t i2 = b0 + lane;
-            const uint32_t v2 = hx[i2 < nhc ? i2 : nhc];
-            const uint32_t c2 = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lane < 32 && i2 < nhc && v2 <= p));
-            ha = b0 + c2 - 1;
-        }
-        // Grouped position of this lane's survivor in row `row` (< rend); moves ha to the tuple of
-        // the next row.  Tuple ha holds the row's first survivor; every later tuple that starts
-        // inside the row raises a flag at the lane of its first survivor (a stamp in the
-        // wavefront's 64 LDS words, unique per call, so nothing has to be cleared), and a lane's
-        // tuple is ha + the number of flags at or below it.
-        auto locate = [&](uint32_t row) -> uint32_t {
-            const uint32_t pf = row * 64;
-            const uint32_t pl = pf + 63 < tot ? pf + 63 : tot - 1;
-            const uint32_t p = pf + lane < pl ? pf + lane : pl;
-            // prefixes of the tuples after ha (hx[nhc] = tot > pl), addressed in bytes: add, min, read
-            const uint32_t bi4 = ha * 4 + lane4;
-            const uint32_t bnd = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(hx) + (bi4 < nhc4 ? bi4 : nhc4));
-            ++stamp;
-            if (bnd <= pl) flag[bnd - pf] = stamp;              // pf < bnd: tuple ha holds pf
-            __builtin_amdgcn_wave_barrier();                    // LDS runs a wavefront's accesses in order
-            const uint64_t marks = __builtin_amdgcn_ballot_w64(flag[lane] == stamp);
-            // flags at or below this lane: lane 0 never holds one (a flagged tuple starts after pf), so
-            // that is the count below the lane in the flags moved down by one -- two mbcnt, ha added in
-            const uint64_t m1 = marks >> 1;
-            const uint32_t h = __builtin_amdgcn_mbcnt_hi((uint32_t)(m1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m1, ha));
-            const uint32_t pos = hbuf[h] + p;
-            // Tuples that start at or before the next row's first survivor.  The clamped lanes read tot,
-            // which passes only in the pass's last row -- after which ha is not used again.
-            ha += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(bnd <= pl + 1));
-            return pos;
-        };
-        // records (and, for the key list, ids) of rows r, r + 1; rows past rend read record 0, unused
-        constexpr int HALF = GD_ROWS / 2;
-        auto fetch = [&](uint32_t r, uint32_t (*rec)[WORDS], uint32_t *low) {
-#pragma unroll
-            for (int u = 0; u < HALF; ++u) {
-                uint32_t pos = 0;
-                if (r + u < rend) pos = locate(r + u);          // wavefront-uniform
-                const uint32_t *p = reinterpret_cast<const uint32_t *>(items_grouped + (size_t)pos * (WORDS * 4));
-                if (WORDS == 1) {
-                    rec[u][0] = p[0];
-                } else if (WORDS == 2) {
-                    const uint2 v = *reinterpret_cast<const uint2 *>(p);
-                    rec[u][0] = v.x;
-                    rec[u][1 % WORDS] = v.y;
-                } else {
-                    const uint4 v = *reinterpret_cast<const uint4 *>(p);
-                    rec[u][0] = v.x;
-                    rec[u][1 % WORDS] = v.y;
-                    rec[u][2 % WORDS] = v.z;
-                    rec[u][3 % WORDS] = v.w;
-                }
-                low[u] = FUSED ? pos : perm[pos];
+            // ---- the survivors, 64 per row; the rows are dealt to the wavefronts in contiguous runs
+            const uint32_t nrows = (tot + 63) >> 6;
+            const uint32_t rpw = (nrows + GS_THREADS / 64 - 1) / (GS_THREADS / 64);
+            const uint32_t r0 = (uint32_t)wave * rpw;
+            const uint32_t rend = r0 + rpw < nrows ? r0 + rpw : nrows;        // <= r0: nothing for this wavefront
+            const uint32_t steps = (rpw + GD_ROWS - 1) / GD_ROWS;              // block-uniform
+            const uint32_t lane4 = (lane + 1) * 4, nhc4 = nhc * 4;
+            const uint32_t lim = rend * 64 < tot ? rend * 64 : tot;            // end of this wavefront's survivors
+            uint32_t ha = 0;
+            if (r0 < rend) {
+                // tuple holding survivor r0 * 64: the last one whose prefix is <= it (two 64-way probes)
+                const uint32_t p = r0 * 64;
+                const uint32_t i1 = lane * 32;
+                const uint32_t v1 = hx[i1 < nhc ? i1 : nhc];
+                const uint32_t c1 = __builtin_popcountll(__builtin_amdgcn_ballot_w64(i1 < nhc && v1 <= p));
+                const uint32_t b0 = (c1 - 1) * 32;
+                const uint32_t i2 = b0 + lane;
+                const uint32_t v2 = hx[i2 < nhc ? i2 : nhc];
+                const uint32_t c2 = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lane < 32 && i2 < nhc && v2 <= p));
+                ha = b0 + c2 - 1;
             }
-        };
-        unsigned long long key[GD_ROWS];
-        bool take[GD_ROWS];
-        uint64_t mk[GD_ROWS];                  // FUSED: ballot of take (wavefront-uniform)
-        // distances and keys of rows r, r + 1 from their records
-        auto finish = [&](uint32_t r, const uint32_t (*rec)[WORDS], const uint32_t *low, int slot0) {
+            // Grouped position of this lane's survivor in row `row` (< rend); moves ha to the tuple of
+            // the next row.  Tuple ha holds the row's first survivor; every later tuple that starts
+            // inside the row raises a flag at the lane of its first survivor (a stamp in the
+            // wavefront's 64 LDS words, unique per call, so nothing has to be cleared), and a lane's
+            // tuple is ha + the number of flags at or below it.
+            auto locate = [&](uint32_t row) -> uint32_t {
+                const uint32_t pf = row * 64;
+                const uint32_t pl = pf + 63 < tot ? pf + 63 : tot - 1;
+                const uint32_t p = pf + lane < pl ? pf + lane : pl;
+                // prefixes of the tuples after ha (hx[nhc] = tot > pl), addressed in bytes: add, min, read
+                const uint32_t bi4 = ha * 4 + lane4;
+                const uint32_t bnd = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(hx) + (bi4 < nhc4 ? bi4 : nhc4));
+                ++stamp;
+                if (bnd <= pl) flag[bnd - pf] = stamp;              // pf < bnd: tuple ha holds pf
+                __builtin_amdgcn_wave_barrier();                    // LDS runs a wavefront's accesses in order
+                const uint64_t marks = __builtin_amdgcn_ballot_w64(flag[lane] == stamp);
+                // flags at or below this lane: lane 0 never holds one (a flagged tuple starts after pf), so
+                // that is the count below the lane in the flags moved down by one -- two mbcnt, ha added in
+                const uint64_t m1 = marks >> 1;
+                const uint32_t h = __builtin_amdgcn_mbcnt_hi((uint32_t)(m1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m1, ha));
+                const uint32_t pos = hbuf[h] + p;
+                // Tuples that start at or before the next row's first survivor.  The clamped lanes read tot,
+                // which passes only in the pass's last row -- after which ha is not used again.
+                ha += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(bnd <= pl + 1));
+                return pos;
+            };
+            // records (and, for the key list, ids) of rows r, r + 1; rows past rend read record 0, unused
+            constexpr int HALF = GD_ROWS / 2;
+            auto fetch = [&](uint32_t r, uint32_t (*rec)[WORDS], uint32_t *low) {
 #pragma unroll
-            for (int u = 0; u < HALF; ++u) {
-                // k ascending like every other kernel; the first term stands for 0 + itself (no table holds -0)
-                float d = T[rec[u][0] & 0xffu];
-#pragma unroll
-                for (int w = 0; w < WORDS; ++w) {
-#pragma unroll
-                    for (int b = w == 0 ? 1 : 0; b < 4; ++b)
-                        d += T[(w * 4 + b) * ICQ_LUT_W + ((rec[u][w] >> (8 * b)) & 0xffu)];
+                for (int u = 0; u < HALF; ++u) {
+                    uint32_t pos = 0;
+                    if (r + u < rend) pos = locate(r + u);          // wavefront-uniform
+                    const uint32_t *p = reinterpret_cast<const uint32_t *>(items_grouped + (size_t)pos * (WORDS * 4));
+                    if (WORDS == 1) {
+                        rec[u][0] = p[0];
+                    } else if (WORDS == 2) {
+                        const uint2 v = *reinterpret_cast<const uint2 *>(p);
+                        rec[u][0] = v.x;
+                        rec[u][1 % WORDS] = v.y;
+                    } else {
+                        const uint4 v = *reinterpret_cast<const uint4 *>(p);
+                        rec[u][0] = v.x;
+                        rec[u][1 % WORDS] = v.y;
+                        rec[u][2 % WORDS] = v.z;
+                        rec[u][3 % WORDS] = v.w;
+                    }
+                    low[u] = FUSED ? pos : perm[pos];
                 }
-                const uint32_t ob = icq_order_bits(d);
-                key[slot0 + u] = ((unsigned long long)ob << 32) | low[u];
-                // survivors of this row that exist (wavefront-uniform count: the last row of a pass is ragged)
-                // (one signed comparison against a wavefront-uniform bound: rows at or past `lim` give <= 0)
-                const uint32_t first = (r + u) * 64;
-                const bool exists = (int)lane < (int)(lim - first);
+            };
+            unsigned long long key[GD_ROWS];
+            bool take[GD_ROWS];
+            uint64_t mk[GD_ROWS];                  // FUSED: ballot of take (wavefront-uniform)
+            // distances and keys of rows r, r + 1 from their records
+            auto finish = [&](uint32_t r, const uint32_t (*rec)[WORDS], const uint32_t *low, int slot0) {
+#pragma unroll
+                for (int u = 0; u < HALF; ++u) {
+                    // k ascending like every other kernel; the first term stands for 0 + itself (no table holds -0)
+                    float d = T[rec[u][0] & 0xffu];
+#pragma unroll
+                    for (int w = 0; w < WORDS; ++w) {
+#pragma unroll
+                        for (int b = w == 0 ? 1 : 0; b < 4; ++b)
+                            d += T[(w * 4 + b) * ICQ_LUT_W + ((rec[u][w] >> (8 * b)) & 0xffu)];
+                    }
+                    const uint32_t ob = icq_order_bits(d);
+                    key[slot0 + u] = ((unsigned long long)ob << 32) | low[u];
+                    // survivors of this row that exist (wavefront-uniform count: the last row of a pass is ragged)
+                    // (one signed comparison against a wavefront-uniform bound: rows at or past `lim` give <= 0)
+                    const uint32_t first = (r + u) * 64;
+                    const bool exists = (int)lane < (int)(lim - first);
+                    if (FUSED) {
+                        // the comparisons feed the ballots directly (one instruction each, no select)
+                        const bool near = ob <= bound;
+                        mk[slot0 + u] = __builtin_amdgcn_ballot_w64(near) & __builtin_amdgcn_ballot_w64(exists);
+                        take[slot0 + u] = near && exists;
+                    } else {
+                        take[slot0 + u] = exists;
+                        const uint64_t slot = (uint64_t)base + first + lane;
+                        if (exists && slot < (uint64_t)cap) my_out[slot] = key[slot0 + u];
+                    }
+                }
+            };
+            // Two half steps in flight: the records of one half are fetched while the other half's
+            // distances are formed, each into registers of its own (no copies, so no wait on the
+            // loads that were just sent).
+            uint32_t recA[HALF][WORDS], recB[HALF][WORDS], lowA[HALF], lowB[HALF];
+            fetch(r0, recA, lowA);
+            for (uint32_t it = 0; it < steps; ++it) {
+                const uint32_t r = r0 + it * GD_ROWS;
+                fetch(r + HALF, recB, lowB);
+                finish(r, recA, lowA, 0);
+                fetch(r + GD_ROWS, recA, lowA);
+                finish(r + HALF, recB, lowB, HALF);
                 if (FUSED) {
-                    // the comparisons feed the ballots directly (one instruction each, no select)
-                    const bool near = ob <= bound;
-                    mk[slot0 + u] = __builtin_amdgcn_ballot_w64(near) & __builtin_amdgcn_ballot_w64(exists);
-                    take[slot0 + u] = near && exists;
-                } else {
-                    take[slot0 + u] = exists;
-                    const uint64_t slot = (uint64_t)base + first + lane;
-                    if (exists && slot < (uint64_t)cap) my_out[slot] = key[slot0 + u];
+                    uint32_t pre[GD_ROWS], mycnt = 0;
+#pragma unroll
+                    for (int u = 0; u < GD_ROWS; ++u) {
+                        pre[u] = mycnt;
+                        mycnt += (uint32_t)__builtin_popcountll(mk[u]);
+                    }
+                    if (lane == 0) sh.wtot[it & 1][wave] = mycnt;
+                    __syncthreads();
+                    uint32_t mybase = cnt, all = 0;              // scalar registers: the counts are read once per wavefront
+#pragma unroll
+                    for (int w = 0; w < GS_THREADS / 64; ++w) {
+                        const uint32_t tw = (uint32_t)__builtin_amdgcn_readfirstlane((int)sh.wtot[it & 1][w]);
+                        if (w < wave) mybase += tw;
+                        all += tw;
+                    }
+#pragma unroll
+                    for (int u = 0; u < GD_ROWS; ++u)
+                        if (take[u])
+                            list[__builtin_amdgcn_mbcnt_hi((uint32_t)(mk[u] >> 32),
+                                                           __builtin_amdgcn_mbcnt_lo((uint32_t)mk[u], mybase + pre[u]))] = key[u];
+                    cnt += all;
+                    // block-uniform: cut while the next step might not fit -- one counting pass, then
+                    // (fat bin) exactly, then (many equal distances) by id
+                    for (int lvl = 0; lvl < 3 && cnt > (uint32_t)(GD_LIST - GD_STEP); ++lvl) {
+                        if (lvl < 2) cnt = block_cut(sh, list, cnt, (uint32_t)topk, &bound, lvl == 1, tid, lane, wave);
+                        else cnt = block_tie_cut(sh, list, cnt, (uint32_t)topk, bound, perm, tid, lane, wave);
+                    }
                 }
             }
-        };
-        // Two half steps in flight: the records of one half are fetched while the other half's
-        // distances are formed, each into registers of its own (no copies, so no wait on the
-        // loads that were just sent).
-        uint32_t recA[HALF][WORDS], recB[HALF][WORDS], lowA[HALF], lowB[HALF];
-        fetch(r0, recA, lowA);
-        for (uint32_t it = 0; it < steps; ++it) {
-            const uint32_t r = r0 + it * GD_ROWS;
-            fetch(r + HALF, recB, lowB);
-            finish(r, recA, lowA, 0);
-            fetch(r + GD_ROWS, recA, lowA);
-            finish(r + HALF, recB, lowB, HALF);
-            if (FUSED) {
-                uint32_t pre[GD_ROWS], mycnt = 0;
-#pragma unroll
-                for (int u = 0; u < GD_ROWS; ++u) {
-                    pre[u] = mycnt;
-                    mycnt += (uint32_t)__builtin_popcountll(mk[u]);
-                }
-                if (lane == 0) sh.wtot[it & 1][wave] = mycnt;
-                __syncthreads();
-                uint32_t mybase = cnt, all = 0;              // scalar registers: the counts are read once per wavefront
-#pragma unroll
-                for (int w = 0; w < GS_THREADS / 64; ++w) {
-                    const uint32_t tw = (uint32_t)__builtin_amdgcn_readfirstlane((int)sh.wtot[it & 1][w]);
-                    if (w < wave) mybase += tw;
-                    all += tw;
-                }
-#pragma unroll
-                for (int u = 0; u < GD_ROWS; ++u)
-                    if (take[u])
-                        list[__builtin_amdgcn_mbcnt_hi((uint32_t)(mk[u] >> 32),
-                                                       __builtin_amdgcn_mbcnt_lo((uint32_t)mk[u], mybase + pre[u]))] = key[u];
-                cnt += all;
-                // block-uniform: cut while the next step might not fit -- one counting pass, then
-                // (fat bin) exactly, then (many equal distances) by id
-                for (int lvl = 0; lvl < 3 && cnt > (uint32_t)(GD_LIST - GD_STEP); ++lvl) {
-                    if (lvl < 2) cnt = block_cut(sh, list, cnt, (uint32_t)topk, &bound, lvl == 1, tid, lane, wave);
-                    else cnt = block_tie_cut(sh, list, cnt, (uint32_t)topk, bound, perm, tid, lane, wave);
-                }
-            }
-        }
-        __syncthreads();                       // hbuf / hx are rewritten by the next part or pass
-        // the first part's topk-th distance (upper end of its histogram bin) becomes the bound
-        if (FUSED && nsp == 2 && sp == 0 && cnt > (uint32_t)topk)
-            cnt = block_cut(sh, list, cnt, (uint32_t)topk, &bound, false, tid, lane, wave);
+            __syncthreads();                       // hbuf / hx are rewritten by the next part or pass
+            // the first part's topk-th distance (upper end of its histogram bin) becomes the bound
+            if (FUSED && nsp == 2 && sp == 0 && cnt > (uint32_t)topk)
+                cnt = block_cut(sh, list, cnt, (uint32_t)topk, &bound, false, tid, lane, wave);
         }
     }
 
