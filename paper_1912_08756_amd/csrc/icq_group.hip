@@ -335,8 +335,9 @@ __device__ __forceinline__ uint32_t prune_above(uint32_t bound, float smin) {
 // result and the survivor count (tuple sizes) are those of visiting everything.  At the end
 // positions become item ids and the keys are ranked by (D, id) -- after one counting cut if the
 // list is longer than a block's worth of keys.  No candidate list ever reaches memory.  One block per query writes the result rows; with
-// several (few queries) every block evaluates all tuples, takes an equal share of the surviving
-// ones and leaves its topk best as ascending keys in keys_out[q][part][topk] for the merge.
+// several (few queries) every block evaluates and lists all tuples, takes its slice of every
+// surviving tuple's items and leaves its topk best as ascending keys in keys_out[q][part][topk]
+// for the merge.
 //
 // !FUSED (topk above GD_TOPK): the blocks of a query split the tuple rows; every survivor's key
 // (bits of D, item id) is written to slot base + number of the query's key list for the select
@@ -473,11 +474,11 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     uint32_t cnt = 0;                          // FUSED: keys in the list (block-uniform)
     uint32_t bound = 0xFFFFFFFFu;              // FUSED: keys with distance bits above it cannot reach the result
 
-    // this block's share of the surviving tuples (all of them unless the lists stay on chip)
-    const uint32_t hit_lo = FUSED ? (uint32_t)((uint64_t)total_hits * blockIdx.x / gridDim.x) : 0u;
-    const uint32_t hit_hi = FUSED ? (uint32_t)((uint64_t)total_hits * (blockIdx.x + 1) / gridDim.x) : total_hits;
-    for (uint32_t pass_lo = hit_lo; pass_lo < hit_hi; pass_lo += GD_HITS) {
-        const uint32_t nh = hit_hi - pass_lo < (uint32_t)GD_HITS ? hit_hi - pass_lo : (uint32_t)GD_HITS;
+    // Every block of a query lists all its surviving tuples; with several blocks (lists on chip, few
+    // queries) each takes its slice of every tuple's items (see below), so the blocks are balanced
+    // whatever the tuple sizes.
+    for (uint32_t pass_lo = 0; pass_lo < total_hits; pass_lo += GD_HITS) {
+        const uint32_t nh = total_hits - pass_lo < (uint32_t)GD_HITS ? total_hits - pass_lo : (uint32_t)GD_HITS;
         // ---- tuples number pass_lo .. pass_lo + nh - 1 -> hbuf
         // A thread lists its own hits one by one -- unless it has many: the column of the query's
         // nearest second-codebook codeword can hold a hundred, and one lane walking them alone
@@ -538,6 +539,12 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
         for (int u = 0; u < GD_PER; ++u) {
             const uint32_t h = (uint32_t)u * GS_THREADS + tid;
             n[u] = h < nh ? n[u] - s[u] : 0u;
+            if (FUSED && gridDim.x > 1) {
+                // this block's slice of the tuple's items: part b of p takes n / p of them (+1 for b < n % p)
+                const uint32_t per = n[u] / gridDim.x, rem = n[u] % gridDim.x;
+                s[u] += blockIdx.x * per + (blockIdx.x < rem ? blockIdx.x : rem);
+                n[u] = per + (blockIdx.x < rem ? 1u : 0u);
+            }
         }
         // FUSED: the pass runs in two parts while the list has no bound yet -- first the tuples
         // with the smallest crude distances, about GD_SEED * topk survivors, whose topk-th distance
@@ -752,7 +759,7 @@ __global__ __launch_bounds__(GS_THREADS) __attribute__((amdgpu_waves_per_eu(WORD
     }
 
     if (!FUSED) return;                        // the atomics have counted the survivors
-    // Several blocks per query (few queries): each keeps the list of its share of the tuple rows
+    // Several blocks per query (few queries): each keeps the list of its slices of the tuples
     // and leaves its topk best as keys (bits of D, id) for the merge kernel.
     unsigned long long *part = keys_out ? keys_out + ((int64_t)q * gridDim.x + blockIdx.x) * topk : nullptr;
     if (tid == 0) {
@@ -902,12 +909,14 @@ bool icq_group_fused(const icq_index *ix, int Q, int topk) {
 }
 
 // Blocks per query in the fused form: one when the queries alone fill the chip; else each block
-// takes an equal share of the surviving tuples and a merge kernel joins the parts' lists (at most
-// 8 parts of at most 256 keys; more parts measured slower: every block evaluates all tuples and
-// starts with an open bound).
+// takes its slice of every surviving tuple's items and a merge kernel joins the parts' lists (at
+// most 8 parts of at most 256 keys).  Every block evaluates and lists all tuples, so more blocks
+// pay only where the items weigh more than that: two blocks per CU with about 16 items per tuple
+// (N = 1e6), four with 150 (N = 1e7) measured best.
 int icq_group_fused_parts(const icq_index *ix, int Q) {
     if (ix->Kf != 2 || Q <= 0) return 1;
-    int parts = (2 * ix->num_cu + Q - 1) / Q;
+    const int per_cu = ix->N >= (int64_t)64 * ix->groups ? 4 : 2;
+    int parts = (per_cu * ix->num_cu + Q - 1) / Q;
     if (parts > 8) parts = 8;
     if (parts < 1) parts = 1;
     return parts;
