@@ -36,7 +36,7 @@ constexpr int E_THREADS = 256;
 // src: x (row stride d, level 0) or the residuals (row stride d_pad); dst: residuals.
 __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
     const float *src, int src_stride, int d, const float *__restrict__ cb_k, int d_pad,
-    const float *__restrict__ cnorm_k, int64_t N, uint8_t *__restrict__ codes_k, float *res) {
+    const float *__restrict__ cnorm_k, int64_t N, uint8_t *__restrict__ codes_k, float *res, int vec_ok) {
     __shared__ float As[EK][EM + 1];
     __shared__ float Bs[EK][EN + 1];
     __shared__ u64 best[E_THREADS / 64][EM];
@@ -52,14 +52,21 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
         for (int j = 0; j < 2; ++j)
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
+    // Rows past N read the last row instead (their codes and residuals are never stored) and
+    // columns past d read column d - 1 (the codebook copy is zero there, the product vanishes):
+    // no load depends on a condition, so a slice's twenty are in flight together.
+    const float *arow[EM / 16];
+#pragma unroll
+    for (int p = 0; p < EM / 16; ++p) {
+        const int64_t row = i0 + lr + 16 * p;
+        arow[p] = src + (row < N ? row : N - 1) * src_stride;
+    }
     for (int k0 = 0; k0 < d_pad; k0 += EK) {
         float a[EM / 16], b[EN / 16];
         const int e = k0 + le;
+        const int ec = e < d ? e : d - 1;
 #pragma unroll
-        for (int p = 0; p < EM / 16; ++p) {
-            const int64_t row = i0 + lr + 16 * p;
-            a[p] = (row < N && e < d) ? src[row * src_stride + e] : 0.0f;
-        }
+        for (int p = 0; p < EM / 16; ++p) a[p] = arow[p][ec];
 #pragma unroll
         for (int p = 0; p < EN / 16; ++p) b[p] = cb_k[(int64_t)(lr + 16 * p) * d_pad + e];
         __syncthreads();   // previous slice fully consumed
@@ -120,6 +127,35 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
     }
     __syncthreads();
     // residual update of the block's rows (zero beyond d, so later levels can read whole slices)
+    if (vec_ok && i0 + EM <= N) {
+        // whole block, d == d_pad, 16-byte aligned rows: 128-bit accesses, two of a thread's in flight
+        // together (one by one, each store would be waited for before the next load: stores count
+        // with the loads)
+        const int row4 = d_pad / 4;                       // 128-bit pieces per row; EM * row4 = 256 * (d_pad / 16)
+        const int nit = d_pad / 16;
+        const float4 *src4 = reinterpret_cast<const float4 *>(src);
+        const float4 *cb4 = reinterpret_cast<const float4 *>(cb_k);
+        float4 *res4 = reinterpret_cast<float4 *>(res);
+        const int src_row4 = src_stride / 4;
+        for (int it = 0; it < nit; it += 2) {
+            float4 xa[2], ca[2];
+            int64_t off[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int idx = (it + u < nit ? it + u : it) * E_THREADS + tid;
+                const int r = idx / row4, e4 = idx % row4;
+                xa[u] = src4[(i0 + r) * src_row4 + e4];
+                ca[u] = cb4[(int64_t)s_code[r] * row4 + e4];
+                off[u] = (i0 + r) * row4 + e4;
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                if (it + u < nit)                         // block-uniform
+                    res4[off[u]] = make_float4(xa[u].x - ca[u].x, xa[u].y - ca[u].y, xa[u].z - ca[u].z, xa[u].w - ca[u].w);
+            }
+        }
+        return;
+    }
     for (int idx = tid; idx < EM * d_pad; idx += E_THREADS) {
         const int r = idx / d_pad, e = idx % d_pad;
         const int64_t row = i0 + r;
@@ -155,9 +191,11 @@ ICQ_EXPORT int icq_encode(const icq_index *ix, const float *x, int64_t N, uint8_
         const int stride = k == 0 ? ix->d : ix->d_pad;
         // in place for k > 0: a block reads and writes only its own rows, and every read of a row
         // (slices, then the update) precedes its write in program order behind a barrier
-        encode_level_kernel<<<blocks, E_THREADS, 0, s>>>(src, stride, ix->d, ix->cb + (size_t)k * ICQ_LUT_W * ix->d_pad,
-                                                         ix->d_pad, ix->cnorm + (size_t)k * ICQ_LUT_W, N,
-                                                         codes_out + (size_t)k * N, res);
+        const float *cbk = ix->cb + (size_t)k * ICQ_LUT_W * ix->d_pad;
+        const int vec_ok = ix->d == ix->d_pad && stride % 4 == 0 && (uintptr_t)src % 16 == 0 && (uintptr_t)cbk % 16 == 0;
+        encode_level_kernel<<<blocks, E_THREADS, 0, s>>>(src, stride, ix->d, cbk, ix->d_pad,
+                                                         ix->cnorm + (size_t)k * ICQ_LUT_W, N,
+                                                         codes_out + (size_t)k * N, res, vec_ok);
     }
     return icq_check_launch();
 }
