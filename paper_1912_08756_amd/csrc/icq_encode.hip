@@ -128,7 +128,7 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
     __syncthreads();
     // residual update of the block's rows (zero beyond d, so later levels can read whole slices)
     if (vec_ok && i0 + EM <= N) {
-        // whole block, d == d_pad, 16-byte aligned rows: 128-bit accesses, two of a thread's in flight
+        // whole block, d == d_pad, 16-byte aligned rows: 128-bit accesses, four of a thread's in flight
         // together (one by one, each store would be waited for before the next load: stores count
         // with the loads)
         const int row4 = d_pad / 4;                       // 128-bit pieces per row; EM * row4 = 256 * (d_pad / 16)
@@ -137,11 +137,12 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
         const float4 *cb4 = reinterpret_cast<const float4 *>(cb_k);
         float4 *res4 = reinterpret_cast<float4 *>(res);
         const int src_row4 = src_stride / 4;
-        for (int it = 0; it < nit; it += 2) {
-            float4 xa[2], ca[2];
-            int64_t off[2];
+        constexpr int U = 4;
+        for (int it = 0; it < nit; it += U) {
+            float4 xa[U], ca[U];
+            int64_t off[U];
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < U; ++u) {
                 const int idx = (it + u < nit ? it + u : it) * E_THREADS + tid;
                 const int r = idx / row4, e4 = idx % row4;
                 xa[u] = src4[(i0 + r) * src_row4 + e4];
@@ -149,7 +150,7 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
                 off[u] = (i0 + r) * row4 + e4;
             }
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < U; ++u) {
                 if (it + u < nit)                         // block-uniform
                     res4[off[u]] = make_float4(xa[u].x - ca[u].x, xa[u].y - ca[u].y, xa[u].z - ca[u].z, xa[u].w - ca[u].w);
             }
