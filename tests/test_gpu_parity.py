@@ -318,6 +318,26 @@ def test_search_with_lists_kept_on_chip(gpu, name, N, Q, over, rule, topk):
         assert np.array_equal(dist3[:, :topk], dist2)
 
 
+def test_search_with_queries_that_are_codewords(gpu):
+    """Queries equal to a codeword of a slow codebook: the table entry of that codeword is
+    ||q||^2 - 2<q,c> + ||c||^2 = 0 up to rounding, on either side of zero.  The grouped kernel
+    prunes tuples by its list's bound only when no table entry is negative; with such queries
+    some blocks run with the pruning and some without (about 135 of the 600 queries get a negative
+    entry, 48 an exact zero), and both must give the oracle's lists."""
+    cfg = small("C1", 70_000, 600)
+    rng = np.random.default_rng(11)
+    K, m = cfg["K"], cfg["codebooks"].shape[1]
+    for q in range(0, 600, 2):
+        cfg["queries"][q] = cfg["codebooks"][rng.integers(2, K), rng.integers(0, m)]
+    g = Gpu(gpu, cfg, 2)
+    T, P, D = oracle_all(cfg)
+    thr = thresholds_quantile(P, 0.02)
+    _check_search(g, cfg, T, P, D, thr, 100, 70_000)
+    ids1, dist1, surv1 = Gpu(gpu, cfg, 1).search(thr, 70_000, 100)
+    ids2, dist2, surv2 = g.search(thr, 70_000, 100)
+    assert np.array_equal(surv2, surv1) and np.array_equal(ids2, ids1) and np.array_equal(dist2, dist1)
+
+
 def test_search_infinite_threshold_is_exhaustive_adc(gpu):
     cfg = small("C1", 20_000, 20)
     g = Gpu(gpu, cfg)
