@@ -48,6 +48,9 @@ extern "C" {
 #define ICQ_ERR_CAPACITY (-4)  /* reserved for synchronous helpers; async calls report
                                   overflow through cand_count / out_survivors            */
 
+#define ICQ_ERR_SCRATCH (-5)   /* icq_search_static: the call needs more than the built-in
+                                  scratch array of ICQ_STATIC_SCRATCH_BYTES holds           */
+
 #define ICQ_MAX_K 64      /* codebooks                         */
 #define ICQ_MAX_M 256     /* codewords per codebook (one byte) */
 #define ICQ_MAX_TOPK 1024 /* result list length                */
@@ -184,6 +187,27 @@ int icq_refine(const icq_index *index, const float *lut, int Q, const uint32_t *
 int icq_search(const icq_index *index, const float *queries, int Q, const float *thresholds,
                int64_t cap, int topk, uint32_t *out_ids, float *out_dist, uint32_t *out_survivors,
                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * icq_search for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and kernels as icq_search, but the
+ * workspace is a fixed array of ICQ_STATIC_SCRATCH_BYTES inside the library's
+ * device image (every GPU the library runs on holds its copy until the process
+ * ends).  The call allocates nothing and frees nothing.  The whole call must
+ * fit the array at once -- icq_workspace_bytes(index, Q, cap, topk) <=
+ * ICQ_STATIC_SCRATCH_BYTES -- else ICQ_ERR_SCRATCH and nothing is enqueued
+ * (lower Q, cap or topk, or use icq_search with a workspace of your own).  The
+ * index must live on the current device (ICQ_ERR_ARG otherwise).  All calls on
+ * one GPU share that GPU's array: calls that overlap in time on one GPU -- from
+ * different streams or host threads -- race; run them on one stream or order
+ * them with events.  The array keeps the last call's contents; everything a
+ * call reads it writes first.
+ */
+#define ICQ_STATIC_SCRATCH_BYTES (32 << 20)
+int icq_search_static(const icq_index *index, const float *queries, int Q, const float *thresholds,
+                      int64_t cap, int topk, uint32_t *out_ids, float *out_dist, uint32_t *out_survivors,
+                      void *stream);
 
 /*
  * A static threshold with the meaning of the running one of Sec. 3.4 (right

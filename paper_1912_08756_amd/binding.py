@@ -13,7 +13,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libicq.so")
 
-ICQ_OK, ICQ_ERR_ARG, ICQ_ERR_WORKSPACE, ICQ_ERR_HIP, ICQ_ERR_CAPACITY = 0, -1, -2, -3, -4
+ICQ_OK, ICQ_ERR_ARG, ICQ_ERR_WORKSPACE, ICQ_ERR_HIP, ICQ_ERR_CAPACITY, ICQ_ERR_SCRATCH = 0, -1, -2, -3, -4, -5
+ICQ_STATIC_SCRATCH_BYTES = 32 << 20
 ICQ_PAD_ID = 0xFFFFFFFF
 ICQ_LUT_W = 256
 
@@ -32,6 +33,7 @@ SIGNATURES = {
     "icq_scan_fast": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
     "icq_refine": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _sz, _vp]),
     "icq_search": (_i, [_vp, _vp, _i, _vp, _i64, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "icq_search_static": (_i, [_vp, _vp, _i, _vp, _i64, _i, _vp, _vp, _vp, _vp]),
     "icq_sample_thresholds": (_i, [_vp, _vp, _i, _vp, _i, _i64, _vp, _vp]),
     "icq_op_counts": (_i, [_vp, _vp, _i, _vp, _vp, _vp]),
     "icq_encode_workspace_bytes": (_i, [_vp, _i64, ctypes.POINTER(_sz)]),
@@ -193,6 +195,17 @@ def icq_search(index, queries, thresholds, cap, topk, out_ids, out_dist, out_sur
                              _dev(out_survivors, torch.int32, (Q,), "out_survivors"),
                              _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()),
            "icq_search")
+
+
+def icq_search_static(index, queries, thresholds, cap, topk, out_ids, out_dist, out_survivors):
+    """icq_search on the library's built-in scratch array (no workspace, no allocation)."""
+    Q = queries.shape[0]
+    _check(load().icq_search_static(index.handle, _dev(queries, torch.float32, (Q, index.d), "queries"), Q,
+                                    _dev(thresholds, torch.float32, (Q,), "thresholds"), cap, topk,
+                                    _dev(out_ids, torch.int32, (Q, topk), "out_ids"),
+                                    _dev(out_dist, torch.float32, (Q, topk), "out_dist"),
+                                    _dev(out_survivors, torch.int32, (Q,), "out_survivors"), _stream()),
+           "icq_search_static")
 
 
 def icq_sample_thresholds(index, lut, sigma, topk, M, thresholds_out):

@@ -80,6 +80,7 @@ ICQ_EXPORT const char *icq_strerror(int code) {
         case ICQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case ICQ_ERR_HIP: return "HIP runtime error";
         case ICQ_ERR_CAPACITY: return "candidate capacity exceeded";
+        case ICQ_ERR_SCRATCH: return "the call needs more than the library's built-in scratch array (ICQ_STATIC_SCRATCH_BYTES)";
         default: return "unknown error code";
     }
 }

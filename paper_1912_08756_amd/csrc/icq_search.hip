@@ -4,6 +4,8 @@
 // side only: workspace carving and kernel sequencing on one stream.
 #include "icq_internal.h"
 
+#include <mutex>
+
 icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool with_lut,
                          bool with_cands) {
     icq_ws_layout L;
@@ -45,10 +47,10 @@ ICQ_EXPORT int icq_workspace_bytes(const icq_index *ix, int Q, int64_t cap, int 
     return ICQ_OK;
 }
 
-ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, const float *thresholds,
-                          int64_t cap, int topk, uint32_t *out_ids, float *out_dist,
-                          uint32_t *out_survivors, void *workspace, size_t workspace_bytes,
-                          void *stream) {
+static int search_impl(const icq_index *ix, const float *queries, int Q, const float *thresholds,
+                       int64_t cap, int topk, uint32_t *out_ids, float *out_dist,
+                       uint32_t *out_survivors, void *workspace, size_t workspace_bytes,
+                       void *stream) {
     if (!ix || Q < 0 || Q > (1 << 22) || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK)
         return ICQ_ERR_ARG;
     if (Q == 0) return ICQ_OK;
@@ -101,4 +103,59 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
         if (timed) ICQ_HIP_TRY(hipEventRecord(ev[3], s));
     }
     return ICQ_OK;
+}
+
+ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, const float *thresholds,
+                          int64_t cap, int topk, uint32_t *out_ids, float *out_dist,
+                          uint32_t *out_survivors, void *workspace, size_t workspace_bytes,
+                          void *stream) {
+    return search_impl(ix, queries, Q, thresholds, cap, topk, out_ids, out_dist, out_survivors, workspace,
+                       workspace_bytes, stream);
+}
+
+// ---- icq_search for callers that cannot allocate: the workspace is a fixed array in the
+// library's own device image.  Every GPU holds its own copy of the array at its own address;
+// host code never uses the array's name as an address, only the pointer that
+// hipGetSymbolAddress returned for the device in question.
+static __device__ __align__(256) unsigned char scratch[ICQ_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES];      // per device, nullptr until its first call
+}  // namespace
+
+// Device address of `scratch` on the current device (looked up once per device).
+static int scratch_address(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return ICQ_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return ICQ_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ICQ_OK;
+}
+
+ICQ_EXPORT int icq_search_static(const icq_index *ix, const float *queries, int Q, const float *thresholds,
+                                 int64_t cap, int topk, uint32_t *out_ids, float *out_dist,
+                                 uint32_t *out_survivors, void *stream) {
+    if (!ix || Q < 0 || Q > ICQ_MAX_Q || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK) return ICQ_ERR_ARG;
+    if (Q == 0) return ICQ_OK;
+    if ((double)Q * (double)cap >= 1099511627776.0) return ICQ_ERR_ARG;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return ICQ_ERR_HIP;
+    if (dev != ix->device) return ICQ_ERR_ARG;          // the array used is the current device's
+    // the whole call must fit at once: no silent split into sub-batches here
+    if (icq_layout(ix, Q, cap, topk, true, true).total > (size_t)ICQ_STATIC_SCRATCH_BYTES) return ICQ_ERR_SCRATCH;
+    void *ws = nullptr;
+    const int rc = scratch_address(&ws);
+    if (rc != ICQ_OK) return rc;
+    return search_impl(ix, queries, Q, thresholds, cap, topk, out_ids, out_dist, out_survivors, ws,
+                       (size_t)ICQ_STATIC_SCRATCH_BYTES, stream);
 }

@@ -60,6 +60,8 @@ def test_host_side_argument_checks():
     assert lib.icq_scan_fast(None, one, 1, one, one, one, one, 1, one, 0, None) == binding.ICQ_ERR_ARG
     assert lib.icq_refine(None, one, 1, one, one, one, 1, 1, one, one, one, 0, None) == binding.ICQ_ERR_ARG
     assert lib.icq_search(None, one, 1, one, 1, 1, one, one, None, one, 0, None) == binding.ICQ_ERR_ARG
+    assert lib.icq_search_static(None, one, 1, one, 1, 1, one, one, None, None) == binding.ICQ_ERR_ARG
+    assert "scratch" in binding.strerror(binding.ICQ_ERR_SCRATCH)
     lib.icq_index_destroy(None)
 
 
