@@ -186,10 +186,7 @@ __global__ __launch_bounds__(GS_THREADS) void group_scan_kernel(
 // ---- grouped stage 1 fused with stage 2
 constexpr int GD_HITS = 768;      // tuples below the threshold handled per pass
 constexpr int GD_PER = GD_HITS / GS_THREADS;
-#ifndef GD_SEED_V
-#define GD_SEED_V 4
-#endif
-constexpr int GD_SEED = GD_SEED_V;         // survivors of a pass's first part, in result lengths
+constexpr int GD_SEED = 4;        // survivors of a pass's first part, in result lengths
 constexpr int GD_ROWS = 2;        // rows of 64 survivors per wavefront and step
 constexpr int GD_STEP = GD_ROWS * GS_THREADS;            // most keys one step can add to the list
 constexpr int GD_LIST = 1024;     // keys of the block's nearest-neighbour list

@@ -4,7 +4,10 @@
 #include "icq_internal.h"
 
 #include <math.h>
+#include <mutex>
 #include <new>
+#include <set>
+#include <utility>
 
 namespace {
 
@@ -73,6 +76,19 @@ int item_stride_for(int K) {
 
 }  // namespace
 
+hipError_t icq_allow_lds(const void *fn, int bytes) {
+    static std::mutex mu;
+    static std::set<std::pair<int, const void *>> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count({dev, fn})) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.insert({dev, fn});
+    return e;
+}
+
 ICQ_EXPORT const char *icq_strerror(int code) {
     switch (code) {
         case ICQ_OK: return "ok";
@@ -95,6 +111,8 @@ ICQ_EXPORT void icq_index_destroy(icq_index *ix) {
     (void)hipFree(ix->group_cursor);
     (void)hipFree(ix->perm);
     (void)hipFree(ix->items_grouped);
+    (void)hipFree(ix->g2_rows);
+    (void)hipFree(ix->g2_info);
     if (ix->timer) {
         for (int i = 0; i < ICQ_TIMED_CALLS * 4; ++i) (void)hipEventDestroy(ix->timer->ev[i / 4][i % 4]);
         delete ix->timer;
@@ -121,6 +139,7 @@ ICQ_EXPORT int icq_index_create(icq_index **out, const float *codebooks, const u
     ix->cb = nullptr; ix->cnorm = nullptr; ix->fast = nullptr; ix->items = nullptr;
     ix->groups = 0; ix->scan_mode = ICQ_SCAN_AUTO; ix->timer = nullptr;
     ix->group_start = nullptr; ix->group_cursor = nullptr; ix->perm = nullptr; ix->items_grouped = nullptr;
+    ix->g2 = 0; ix->g2_npos = 0; ix->g2_npad = 0; ix->g2_rows = nullptr; ix->g2_info = nullptr;
     hipDeviceProp_t prop;
     if (hipGetDevice(&ix->device) != hipSuccess ||
         hipGetDeviceProperties(&prop, ix->device) != hipSuccess) {
@@ -149,7 +168,7 @@ ICQ_EXPORT int icq_index_create(icq_index **out, const float *codebooks, const u
     if (N > 0)
         copy_items_kernel<<<(unsigned)((N + T - 1) / T), T, 0, s>>>(codes, N, K, ix->item_stride,
                                                                      ix->items);
-    if (icq_check_launch() != ICQ_OK || icq_group_build(ix, s) != ICQ_OK) {
+    if (icq_check_launch() != ICQ_OK || icq_group_build(ix, s) != ICQ_OK || icq_group2_build(ix, s) != ICQ_OK) {
         icq_index_destroy(ix);
         return ICQ_ERR_HIP;
     }
@@ -164,6 +183,7 @@ ICQ_EXPORT int icq_index_export_codes(const icq_index *ix, int from_items, uint8
     const int T = 256;
     dim3 g((unsigned)((ix->N + T - 1) / T), (unsigned)ix->K);
     if (from_items == 2) {
+        if (ix->g2) return icq_group2_export(ix, codes_out, (hipStream_t)stream);
         if (!ix->groups) return ICQ_ERR_ARG;
         export_grouped_kernel<<<g, T, 0, (hipStream_t)stream>>>(ix->items_grouped, ix->perm, ix->N,
                                                                 ix->item_stride, codes_out);

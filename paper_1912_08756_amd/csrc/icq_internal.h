@@ -37,8 +37,36 @@ struct icq_index {
     uint32_t *group_cursor;    // [groups] scratch of the build
     uint32_t *perm;            // [N] grouped position -> item id
     uint8_t *items_grouped;    // [N][item_stride] the item records in grouped order
+    // Grouping by the first two fast sub-codes (Kf = 3, 4 and N large enough, icq_group2.hip): the
+    // items ordered by that pair -- the pairs themselves in a scattered order, so that any stretch of
+    // positions holds unrelated pairs -- every pair's run padded to whole 16 positions.  Stage 1 then
+    // streams only the remaining Kf - 2 fast rows and forms the pair's table sum once per 16
+    // positions.  Uses group_start [65537], perm [g2_npad] (ICQ_PAD_ID in the padding) and
+    // items_grouped [g2_npad][item_stride] as the Kf <= 2 grouping does.
+    int g2;                    // 1 when this grouping exists
+    int64_t g2_npos;           // positions stage 1 walks: an upper bound of the padded total, whole block steps
+    int64_t g2_npad;           // row stride of g2_rows = length of perm / items_grouped (g2_npos + read-ahead spare)
+    uint8_t *g2_rows;          // [Kf - 2][g2_npad] the remaining fast sub-codes in grouped order
+    uint32_t *g2_info;         // [g2_npad / 16] c0 | c1 << 8 | valid positions << 16 of each 16 positions
     icq_stage_timer *timer;    // nullptr unless stage timing is on
 };
+
+// Position of pair (c0, c1) in the grouped order and back: multiplication by an odd constant is a
+// bijection on 16 bits that sends neighbouring pairs far apart.
+#define ICQ_G2_MUL 0x9E37u
+#define ICQ_G2_INV 0x7787u     // ICQ_G2_MUL * ICQ_G2_INV == 1 (mod 65536)
+static inline __host__ __device__ uint32_t icq_g2_slot_of_pair(uint32_t pair) { return (pair * ICQ_G2_INV) & 0xFFFFu; }
+static inline __host__ __device__ uint32_t icq_g2_pair_of_slot(uint32_t slot) { return (slot * ICQ_G2_MUL) & 0xFFFFu; }
+// automatic: when a pair's run averages 64 items or more, so that the padding to 16 weighs little
+static inline bool icq_g2_usable(const icq_index *ix) {
+    if (!ix->g2 || ix->scan_mode == ICQ_SCAN_STREAMED) return false;
+    return ix->scan_mode == ICQ_SCAN_GROUPED || ix->N >= 64ll * 65536;
+}
+int icq_group2_build(icq_index *ix, hipStream_t s);
+int icq_group2_export(const icq_index *ix, uint8_t *codes_out, hipStream_t s);
+
+// hipFuncSetAttribute(fn, MaxDynamicSharedMemorySize, bytes), once per (device, kernel); thread-safe.
+hipError_t icq_allow_lds(const void *fn, int bytes);
 
 // What a candidate list holds.
 enum icq_list_kind {
@@ -68,6 +96,11 @@ __device__ __forceinline__ uint32_t icq_order_bits(float x) {
 struct icq_ws_layout {
     size_t lut_off, ids_off, count_off, keys_off, total;
     int splits;                // stage-2 blocks per query
+    // icq_search with the item-by-item stage 1: hit bits instead of candidate lists (ids_off holds them)
+    bool masked;
+    size_t keycount_off;       // [Q] keys written per query
+    size_t mask_stride;        // 16-bit words of hit bits per query
+    int64_t scan_end;          // scan positions the hit bits cover (whole chunks)
 };
 
 static inline size_t icq_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -78,6 +111,19 @@ static inline size_t icq_align_up(size_t x, size_t a) { return (x + a - 1) / a *
 icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool with_lut,
                          bool with_cands);
 int icq_refine_splits(const icq_index *ix, int Q, int64_t cap, int topk);
+// icq_search with the item-by-item stage 1 hands the survivors to stage 2 as one hit bit per scan
+// position and query instead of lists.
+bool icq_masks_usable(const icq_index *ix, int Q, int topk);
+int64_t icq_mask_scan_end(const icq_index *ix);              // positions the hit bits cover: whole stage-2 chunks
+// Stage 1 into hit bits (zeroes cand_count and key_count first; after_fill as in icq_launch_scan).
+int icq_launch_scan_masks(const icq_index *ix, const float *lut, int Q, const float *thr, uint16_t *masks,
+                          size_t mask_stride, int64_t scan_end, uint32_t *cand_count, uint32_t *key_count,
+                          hipEvent_t after_fill, hipStream_t s);
+// Stage 2 from hit bits; keys [Q][cap] (+ slice lists in front, see icq_cand_keys); adds the survivors to cand_count.
+int icq_launch_refine_masks(const icq_index *ix, const float *lut, int Q, const uint16_t *masks, size_t mask_stride,
+                            int64_t scan_end, int64_t cap, int topk, int splits, unsigned long long *keys,
+                            uint32_t *key_count, uint32_t *cand_count, uint32_t *out_ids, float *out_dist,
+                            hipStream_t s);
 
 // Kernel launchers (each checks nothing; the extern "C" entry points validate).
 int icq_launch_build_lut(const icq_index *ix, const float *queries, int Q, float *lut,

@@ -237,12 +237,7 @@ ICQ_EXPORT int icq_sample_thresholds(const icq_index *ix, const float *lut, int 
         return icq_check_launch();
     }
     const size_t lds = sizeof(float) * (size_t)ix->K * ICQ_LUT_W;
-    static bool attr_set = false;
-    if (!attr_set) {
-        ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&sample_threshold_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 65536));
-        attr_set = true;
-    }
+    ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&sample_threshold_kernel), 65536));
     sample_threshold_kernel<<<Q, SP_THREADS, lds, s>>>(ix->items, ix->item_stride, ix->K, ix->Kf, lut, sigma,
                                                        topk, n, thresholds_out);
     return icq_check_launch();

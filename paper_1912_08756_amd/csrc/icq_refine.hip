@@ -518,6 +518,198 @@ __global__ __launch_bounds__(SK_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8
     }
 }
 
+// ------------------------------------------------------------------ stage 2 from hit bits
+// icq_search with the item-by-item stage 1: stage 1 leaves one hit bit per scan position and query,
+// and this kernel turns them into distances and keys.  The positions are cut into chunks of 32768
+// (4 KB of hit bits per query, 512 KB of 16-byte item records).  A block belongs to ONE query --
+// its tables stay in LDS for the block's whole life -- and walks a window of a few chunks, its
+// four wavefronts a chunk at a time each and each on its own (no barrier after the tables are
+// in place).  Workgroups go round the 8 XCDs in turn, each XCD has a cache of its own (block x of
+// the grid is on XCD x % 8), and they start in the order of their numbers: the blocks are
+// numbered window by window, within a window query by query, then XCD -- so the blocks of ALL
+// queries of the batch that walk the same window run on the same XCD at about the same time,
+// the chip holds the blocks of two windows at once, and that XCD has a few chunks' records in its
+// cache at a time.  An item that survives for several queries of the batch -- or shares its cache
+// line with one that does -- is then fetched from memory once: with 1 % survivors and 128
+// queries that is ten uses per 128-byte line.  Per chunk and wavefront: the query's 256 words of hit
+// bits (one 128-bit load per lane, two chunks ahead), a prefix of their popcounts, the set bits
+// expanded into a position list in the wavefront's part of LDS, then per position the record
+// gather, the K table reads and the key, as in refine_dist_kernel.
+// Every 33rd chunk is done in a first launch, unfiltered (!FILTER); the select kernel's topk-th
+// distance of those keys then bounds what the other chunks add in a second launch (FILTER: keys
+// above it are dropped; ties at it are kept, the final select decides).  The final lists are
+// unchanged -- at least topk keys at or below the bound are already there -- and the key lists
+// shrink to a few per cent.  Survivors are counted from the popcounts.
+constexpr int RM_THREADS = 256;
+constexpr int RM_WAVES = RM_THREADS / 64;
+constexpr uint32_t RM_CHUNK = 32768;                  // positions per chunk; a multiple of the scan kernel's block step
+constexpr int RM_WORDS = RM_CHUNK / 32 / 64;          // 32-bit words of hit bits per lane and chunk
+constexpr int RM_PER = 4;                             // records a lane gathers together
+constexpr int RM_LIST = 512;                          // positions a wavefront expands per round
+constexpr int RM_SEED_EVERY = 33;                     // odd: the first launch's chunks are spread over all XCDs
+static_assert(RM_LIST % (64 * RM_PER) == 0, "a round of the list is whole steps of gathers");
+
+template <int WORDS, bool FILTER>
+__global__ __launch_bounds__(RM_THREADS) __attribute__((amdgpu_waves_per_eu(5, 8))) void refine_mask_kernel(
+    const uint8_t *__restrict__ items, int K, const float *__restrict__ lut, const uint32_t *__restrict__ masks,
+    size_t mask_words, const uint32_t *__restrict__ perm, uint32_t nsel, int window, int Q,
+    const float *__restrict__ kth_dist, int topk, u64 *__restrict__ keys, uint32_t *__restrict__ key_count,
+    int64_t cap, uint32_t *__restrict__ cand_count) {
+    __shared__ __attribute__((aligned(16))) float T[4 * WORDS * ICQ_LUT_W];
+    __shared__ uint32_t cand_all[RM_WAVES][RM_LIST];
+    constexpr int RW = WORDS;
+    const int tid = threadIdx.x;
+    const uint32_t lane = (uint32_t)tid & 63u;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    uint32_t *cand = cand_all[wave];
+    // block -> (window, query, XCD): chunks i = (win * window + j) * 8 + xcd, j = 0 .. window - 1, of this
+    // launch's; wavefront w takes j = w, w + 4, ..
+    const uint32_t xcd = blockIdx.x & 7u, rest = blockIdx.x >> 3;
+    const uint32_t q = rest % (uint32_t)Q, win = rest / (uint32_t)Q;
+    auto chunk_of = [&](uint32_t j) -> uint32_t {
+        const uint32_t i = (win * (uint32_t)window + j) * 8u + xcd;
+        if (j >= (uint32_t)window || i >= nsel) return 0xFFFFFFFFu;
+        return FILTER ? i + i / (RM_SEED_EVERY - 1) + 1u : i * RM_SEED_EVERY;
+    };
+    if (chunk_of(0) == 0xFFFFFFFFu) return;           // block-uniform: nothing for this block
+    // Word r of this lane covers the 32 positions from c * RM_CHUNK + (r * 64 + lane) * 32: neighbouring
+    // words sit in neighbouring lanes, so a dense stretch of hits is shared out among many lanes.
+    const uint32_t *mq = masks + (size_t)q * mask_words + lane;
+    uint32_t c = chunk_of((uint32_t)wave);
+    uint32_t nxt[RM_WORDS];
+    {
+        const uint32_t c0 = c != 0xFFFFFFFFu ? c : 0u;
+#pragma unroll
+        for (int r = 0; r < RM_WORDS; ++r) nxt[r] = mq[(size_t)c0 * (RM_CHUNK / 32) + r * 64];
+    }
+    {   // the query's tables -> LDS, one table per record byte, zero beyond K
+        const float4 *src = reinterpret_cast<const float4 *>(lut + (int64_t)q * K * ICQ_LUT_W);
+        float4 *dst = reinterpret_cast<float4 *>(T);
+        constexpr int N4 = 4 * WORDS * (ICQ_LUT_W / 4);
+        float4 v[N4 / RM_THREADS];
+#pragma unroll
+        for (int j = 0; j < N4 / RM_THREADS; ++j) {
+            const int i = j * RM_THREADS + tid;
+            v[j] = i / (ICQ_LUT_W / 4) < K ? src[i] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        }
+#pragma unroll
+        for (int j = 0; j < N4 / RM_THREADS; ++j) dst[j * RM_THREADS + tid] = v[j];
+    }
+    uint32_t bound = 0xFFFFFFFFu;
+    if (FILTER) {
+        const uint32_t ob = icq_order_bits(kth_dist[(int64_t)q * topk + topk - 1]);
+        if (ob < 0xFF800000u) bound = ob;             // a finite topk-th distance; else the list is still open
+    }
+    __syncthreads();                                  // the only barrier: from here on every wavefront is on its own
+    u64 *kout = keys + (int64_t)q * cap;
+    uint32_t survivors = 0;                           // of this wavefront's chunks (wavefront-uniform)
+    for (uint32_t j = (uint32_t)wave; c != 0xFFFFFFFFu; j += RM_WAVES) {
+        uint32_t w[RM_WORDS];
+#pragma unroll
+        for (int r = 0; r < RM_WORDS; ++r) w[r] = nxt[r];
+        const uint32_t cn = chunk_of(j + RM_WAVES);
+        if (cn != 0xFFFFFFFFu) {                      // the wavefront's next chunk: its hit bits travel while this one is worked on
+#pragma unroll
+            for (int r = 0; r < RM_WORDS; ++r) nxt[r] = mq[(size_t)cn * (RM_CHUNK / 32) + r * 64];
+        }
+        uint32_t mine = 0;
+#pragma unroll
+        for (int r = 0; r < RM_WORDS; ++r) mine += (uint32_t)__builtin_popcount(w[r]);
+        const uint32_t incl = wave_scan_add(mine);
+        const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        const uint32_t off = incl - mine;
+        survivors += total;
+        // unfiltered: every survivor of the chunk gets a key, so their slots are reserved at once (the atomic's
+        // answer travels while the positions are expanded)
+        uint32_t chunk_slot = 0;
+        if (!FILTER && total != 0) {
+            if (lane == 0) chunk_slot = atomicAdd(&key_count[q], total);
+        }
+        const uint32_t p0 = c * RM_CHUNK + lane * 32u;
+        for (uint32_t lo = 0; lo < total; lo += RM_LIST) {      // wavefront-uniform; one round unless the chunk is dense
+            __builtin_amdgcn_wave_barrier();          // LDS runs a wavefront's accesses in order: the last round's reads are done
+            if (off + mine > lo && off < lo + RM_LIST) {
+                uint32_t idx = off - lo;              // wraps below the window: fails the test until it is inside
+#pragma unroll
+                for (int r = 0; r < RM_WORDS; ++r) {
+                    uint32_t m = w[r];
+                    while (m != 0) {
+                        const uint32_t bit = (uint32_t)__builtin_ctz(m);
+                        m &= m - 1;
+                        if (idx < (uint32_t)RM_LIST) cand[idx] = p0 + (uint32_t)r * 2048u + bit;
+                        ++idx;
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            const uint32_t n = total - lo < (uint32_t)RM_LIST ? total - lo : (uint32_t)RM_LIST;
+            for (uint32_t base = 0; base < n; base += 64 * RM_PER) {
+                uint32_t id[RM_PER], rec[RM_PER][RW];
+#pragma unroll
+                for (int u = 0; u < RM_PER; ++u) {
+                    const uint32_t i = base + (uint32_t)u * 64u + lane;
+                    id[u] = cand[i < n ? i : n - 1];
+                }
+#pragma unroll
+                for (int u = 0; u < RM_PER; ++u) {
+                    const uint32_t *p = reinterpret_cast<const uint32_t *>(items + (size_t)id[u] * (RW * 4));
+                    if (RW == 1) {
+                        rec[u][0] = p[0];
+                    } else if (RW == 2) {
+                        const uint2 v = *reinterpret_cast<const uint2 *>(p);
+                        rec[u][0] = v.x;
+                        rec[u][1 % RW] = v.y;
+                    } else {
+                        const uint4 v = *reinterpret_cast<const uint4 *>(p);
+                        rec[u][0] = v.x;
+                        rec[u][1 % RW] = v.y;
+                        rec[u][2 % RW] = v.z;
+                        rec[u][3 % RW] = v.w;
+                    }
+                }
+                u64 key[RM_PER];
+                uint64_t mk[RM_PER];
+                uint32_t mycnt = 0;
+#pragma unroll
+                for (int u = 0; u < RM_PER; ++u) {
+                    // k ascending like every other kernel; the first term stands for 0 + itself (no table holds -0)
+                    float d = T[rec[u][0] & 0xffu];
+#pragma unroll
+                    for (int x = 0; x < WORDS; ++x) {
+#pragma unroll
+                        for (int b = x == 0 ? 1 : 0; b < 4; ++b)
+                            d += T[(x * 4 + b) * ICQ_LUT_W + ((rec[u][x] >> (8 * b)) & 0xffu)];
+                    }
+                    const uint32_t ob = icq_order_bits(d);
+                    const bool keep = base + (uint32_t)u * 64u + lane < n && ob <= bound;
+                    mk[u] = __builtin_amdgcn_ballot_w64(keep);
+                    mycnt += (uint32_t)__builtin_popcountll(mk[u]);
+                    key[u] = (u64)ob << 32;
+                }
+                if (mycnt == 0) continue;             // wavefront-uniform
+                uint32_t slot0 = 0;
+                if (FILTER) {
+                    if (lane == 0) slot0 = atomicAdd(&key_count[q], mycnt);
+                    slot0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)slot0);
+                } else {
+                    slot0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)chunk_slot) + lo + base;
+                }
+#pragma unroll
+                for (int u = 0; u < RM_PER; ++u) {
+                    if ((mk[u] >> lane) & 1ull) {
+                        const uint64_t slot = (uint64_t)__builtin_amdgcn_mbcnt_hi(
+                            (uint32_t)(mk[u] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mk[u], slot0));
+                        if (slot < (uint64_t)cap) kout[slot] = key[u] | (perm ? perm[id[u]] : id[u]);
+                    }
+                    slot0 += (uint32_t)__builtin_popcountll(mk[u]);
+                }
+            }
+        }
+        c = cn;
+    }
+    if (lane == 0 && survivors != 0) atomicAdd(&cand_count[q], survivors);
+}
+
 }  // namespace
 
 // Item records of at most 16 bytes take the bounded-stream kernel; wider records
@@ -583,12 +775,7 @@ int icq_launch_refine(const icq_index *ix, const float *lut, int Q, const uint32
     } else {
         const int bufn = bufn_for(topk);
         const size_t lds = sizeof(u64) * bufn + tab;
-        static bool attr_set = false;
-        if (!attr_set) {
-            ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&refine_kernel),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 98304));
-            attr_set = true;
-        }
+        ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&refine_kernel), 98304));
         refine_kernel<<<grid, RF_THREADS, lds, s>>>(items, ix->item_stride, ix->K, ix->Kf, lut,
                                                     cand_ids, cand_part, perm, cand_count, cap, topk,
                                                     bufn, splits, keys, out_ids, out_dist);
@@ -614,4 +801,69 @@ ICQ_EXPORT int icq_refine(const icq_index *ix, const float *lut, int Q, const ui
     u64 *keys = reinterpret_cast<u64 *>(static_cast<char *>(workspace) + L.keys_off);
     return icq_launch_refine(ix, lut, Q, cand_ids, cand_part, ICQ_LIST_IDS, cand_count, cap, topk,
                              L.splits, keys, out_ids, out_dist, (hipStream_t)stream);
+}
+
+bool icq_masks_usable(const icq_index *ix, int Q, int topk) {
+    return ix->Kf <= 4 && !icq_group_usable(ix, Q) && use_select(ix, topk) && ix->N > 0 &&
+           ix->N + 16ll * 65536 < (1ll << 31);
+}
+
+int64_t icq_mask_scan_end(const icq_index *ix) {
+    const int64_t npos = icq_g2_usable(ix) ? ix->g2_npos : ix->N;
+    return (npos + RM_CHUNK - 1) / RM_CHUNK * RM_CHUNK;
+}
+
+int icq_launch_refine_masks(const icq_index *ix, const float *lut, int Q, const uint16_t *masks, size_t mask_stride,
+                            int64_t scan_end, int64_t cap, int topk, int splits, u64 *keys, uint32_t *key_count,
+                            uint32_t *cand_count, uint32_t *out_ids, float *out_dist, hipStream_t s) {
+    if (Q == 0) return ICQ_OK;
+    const bool g2 = icq_g2_usable(ix);
+    const uint8_t *items = g2 ? ix->items_grouped : ix->items;
+    const uint32_t *perm = g2 ? ix->perm : nullptr;
+    u64 *cand_keys = icq_cand_keys(keys, Q, splits, topk);     // [Q][cap], behind the slice lists
+    const uint32_t chunks = (uint32_t)(scan_end / RM_CHUNK);
+    const uint32_t nseed = (chunks + RM_SEED_EVERY - 1) / RM_SEED_EVERY, nmain = chunks - nseed;
+    const unsigned grid_sel = (unsigned)Q * (unsigned)splits;
+    const int listcap = 1024;
+    auto select = [&]() -> int {
+        select_keys_kernel<<<grid_sel, SK_THREADS, (sizeof(u64) + sizeof(uint32_t)) * listcap, s>>>(
+            cand_keys, key_count, cap, topk, listcap, splits, keys, out_ids, out_dist);
+        if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;
+        if (splits > 1) return icq_launch_merge(keys, Q, splits, topk, false, out_ids, out_dist, s);
+        return ICQ_OK;
+    };
+    // Chunks per block: few, so that the blocks in flight (two windows' worth when the queries fill the
+    // chip) keep to a few chunks per XCD; more when there are so few queries that the table load would weigh.
+    auto window_for = [&](uint32_t nsel) -> int {
+        int w = Q >= 8 && !g2 ? 8 : 16;               // grouped order: a query's survivors sit in runs, the walk depends less on the cache
+        const int most = (int)((nsel + 7) / 8);
+        return w < most ? w : (most > 0 ? most : 1);
+    };
+    const size_t mask_words = mask_stride / 2;
+    const uint32_t *m32 = reinterpret_cast<const uint32_t *>(masks);
+#define ICQ_RM_LAUNCH(W, FILTER, NSEL)                                                                       \
+    do {                                                                                                     \
+        const int window = window_for(NSEL);                                                                 \
+        const unsigned nwin = ((NSEL) + 8u * window - 1) / (8u * window);                                    \
+        refine_mask_kernel<W, FILTER><<<nwin * (unsigned)Q * 8u, RM_THREADS, 0, s>>>(                         \
+            items, ix->K, lut, m32, mask_words, perm, (NSEL), window, Q, out_dist, topk, cand_keys,           \
+            key_count, cap, cand_count);                                                                     \
+    } while (0)
+    switch (ix->item_stride) {
+        case 4: ICQ_RM_LAUNCH(1, false, nseed); break;
+        case 8: ICQ_RM_LAUNCH(2, false, nseed); break;
+        default: ICQ_RM_LAUNCH(4, false, nseed); break;
+    }
+    if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;
+    if (nmain == 0) return select();
+    int rc = select();
+    if (rc != ICQ_OK) return rc;
+    switch (ix->item_stride) {
+        case 4: ICQ_RM_LAUNCH(1, true, nmain); break;
+        case 8: ICQ_RM_LAUNCH(2, true, nmain); break;
+        default: ICQ_RM_LAUNCH(4, true, nmain); break;
+    }
+#undef ICQ_RM_LAUNCH
+    if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;
+    return select();
 }

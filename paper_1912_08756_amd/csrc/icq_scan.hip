@@ -85,16 +85,32 @@ constexpr int SS_WAVES = SS_THREADS / 64;
 // NT: the code stream is loaded with the non-temporal hint -- for an array far beyond the 256 MB
 // last-level cache that is read once per pass anyway, 400 MB then read in 60 instead of 67 us
 // (a plain read kernel in this launch shape); an array that fits is better kept.
-template <int KF, int B, bool NT>
+//
+// G2 (index grouped by the first two fast sub-codes, see icq_group2.hip): the scan walks grouped
+// positions; `fast` holds the KF = Kf - 2 remaining fast rows in grouped order and info[p / 16]
+// names the tuple that positions p .. p + 15 belong to (c0 | c1 << 8 | valid positions << 16).  The
+// sum of the tuple's two table entries is formed once per 16 positions from unreplicated copies of
+// the first two tables and the streamed rows' entries are added to it in codebook order -- the same
+// additions as item by item.  Listed are grouped positions (ids through `perm` when it is given).
+//
+// MASK (icq_search): no lists at all.  The kernel stores the hit bits themselves, one bit per
+// scan position and query (masks[q * mask_stride + p / 16] holds positions p .. p + 15, bit j =
+// position p + j), for every position of the block's range -- zeros beyond N -- and stage 2 walks
+// those words.  No staging, no compaction, no atomics; whatever the survivors' number or order.
+template <int KF, int B, bool NT, bool G2, bool MASK>
 __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     const uint8_t *fast, int64_t Npad, uint32_t N, const float *__restrict__ lut, int K,
     const float *__restrict__ thr, int Q, uint32_t *__restrict__ cand_ids,
-    uint32_t *__restrict__ cand_count, int64_t cap, uint32_t items_per_block, uint32_t wave_cap) {
+    uint32_t *__restrict__ cand_count, int64_t cap, uint32_t items_per_block, uint32_t wave_cap,
+    const uint32_t *__restrict__ info, const uint32_t *__restrict__ perm, uint16_t *__restrict__ masks,
+    size_t mask_stride, uint32_t scan_end) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     __shared__ uint32_t s_wcnt[B][SS_WAVES], s_base[B];
     constexpr int C = ss_copies(KF, B);
     constexpr int SS_HALF = ss_half(B);
     constexpr int TAB_FLOATS = KF * ICQ_LUT_W * C * B;
+    constexpr int T01_FLOATS = G2 ? 2 * ICQ_LUT_W * B : 0;
+    constexpr int K0 = G2 ? 2 : 0;                    // codebook of the first streamed row
     const int tid = threadIdx.x;
     const uint32_t lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -111,7 +127,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
 #pragma unroll
         for (int b = 0; b < B; ++b) {
             const int qb = (qbase + b) < Q ? qbase + b : Q - 1;       // clamped; replaced by +inf below
-            row[b] = lut + (int64_t)qb * K * ICQ_LUT_W;
+            row[b] = lut + ((int64_t)qb * K + K0) * ICQ_LUT_W;
         }
         float x[NV][B];
 #pragma unroll
@@ -132,13 +148,25 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
             v.w = x[j][3 % B];
             reinterpret_cast<float4 *>(smem)[j * SS_THREADS + tid] = v;
         }
+        if (G2 && tid < T01_FLOATS / 4) {
+            // the first two tables, one copy, the B values of an entry adjacent
+            float4 v;
+            float *vv = reinterpret_cast<float *>(&v);
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                const int idx = tid * 4 + f, e = idx / B, b = idx % B;
+                vv[f] = (qbase + b) < Q ? lut[(int64_t)(qbase + b) * K * ICQ_LUT_W + e] : INFINITY;
+            }
+            reinterpret_cast<float4 *>(smem + TAB_FLOATS)[tid] = v;
+        }
         __syncthreads();
     };
     float t[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) t[b] = (qbase + b) < Q ? thr[qbase + b] : -INFINITY;
     // staging: [B][SS_WAVES][wave_cap] ids
-    uint32_t *stage = reinterpret_cast<uint32_t *>(smem + TAB_FLOATS);
+    uint32_t *stage = reinterpret_cast<uint32_t *>(smem + TAB_FLOATS + T01_FLOATS);
+    const float *t01 = smem + TAB_FLOATS;
     uint32_t wc[B];               // ids staged by this wavefront (wavefront-uniform)
 #pragma unroll
     for (int b = 0; b < B; ++b) wc[b] = 0;
@@ -146,6 +174,13 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     const uint32_t begin = blockIdx.x * items_per_block;
     uint32_t end = begin + items_per_block;
     if (end > N || end < begin) end = N;
+    // MASK: the steps run to the end of the block's range even past the last item (scan_end is a whole
+    // number of block steps and the mask words reach that far)
+    uint32_t walk_end = end;
+    if (MASK) {
+        walk_end = begin + items_per_block;
+        if (walk_end > scan_end || walk_end < begin) walk_end = scan_end;
+    }
     // byte offset of this lane's copy inside an entry; an entry is C copies of B floats
     constexpr int ENTRY_BYTES = C * 4 * B;
     constexpr int ENTRY_SHIFT = ENTRY_BYTES == 64 ? 6 : ENTRY_BYTES == 128 ? 7 : 8;
@@ -153,15 +188,17 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     const uint32_t copy_off = (lane & (C - 1)) * (4 * B);
     const char *tab_bytes = reinterpret_cast<const char *>(smem);
     constexpr uint32_t step = (uint32_t)SS_WAVES * 1024u;
-    const uint32_t nsteps = end > begin ? (end - begin + step - 1) / step : 0;   // same for every wavefront
+    const uint32_t nsteps = walk_end > begin ? (walk_end - begin + step - 1) / step : 0;   // same for every wavefront
 
     // 1024 items at g into w; past the block's range the block's first items are read instead
     // (unused, but in bounds: g < end <= N and the rows are padded by more than 1024 bytes)
     constexpr int R = B == 1 ? 3 : 2;
     static_assert(B == 1 || B == 2 || B == 4, "one 32/64/128-bit table read per lookup");
     uint4 w[R][KF];
-    auto load = [&](uint32_t g, uint4 (&w)[KF]) {
+    uint32_t ci[R];               // G2: the tuple and valid count of this lane's 16 positions
+    auto load = [&](uint32_t g, uint4 (&w)[KF], uint32_t &ci) {
         const uint32_t gs = (g < end && g >= begin) ? g : begin;
+        if (G2) ci = info[(gs >> 4) + lane];
 #pragma unroll
         for (int k = 0; k < KF; ++k) {
             typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -175,13 +212,31 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
         uint32_t *dst = cand_ids + (int64_t)(qbase + b) * cap;
         for (uint32_t i = lane; i < n; i += 64) {
             const uint64_t slot = first + i;
-            if (slot < (uint64_t)cap) dst[slot] = src[i];
+            if (slot < (uint64_t)cap) dst[slot] = (G2 && perm) ? perm[src[i]] : src[i];
         }
     };
     // the 1024 items at g held in w: table sums and hit bits.  hm[b] (zero on entry) receives the hit
     // bits of this lane's 16 items for query b, item j in bit 15 - j.
-    auto hits = [&](uint32_t g, const uint4 (&w)[KF], uint32_t (&hm)[B]) {
+    auto hits = [&](uint32_t g, const uint4 (&w)[KF], uint32_t ci, uint32_t (&hm)[B]) {
         const uint32_t id0 = g + lane * 16;
+        float p01[B];
+        if (G2) {
+            // the tuple's two entries, summed once for the 16 positions
+            const float *e0 = t01 + (ci & 0xffu) * B, *e1 = t01 + (ICQ_LUT_W + ((ci >> 8) & 0xffu)) * B;
+            if (B == 1) {
+                p01[0] = e0[0] + e1[0];
+            } else if (B == 2) {
+                const float2 a = *reinterpret_cast<const float2 *>(e0), c = *reinterpret_cast<const float2 *>(e1);
+                p01[0] = a.x + c.x;
+                p01[1 % B] = a.y + c.y;
+            } else {
+                const float4 a = *reinterpret_cast<const float4 *>(e0), c = *reinterpret_cast<const float4 *>(e1);
+                p01[0] = a.x + c.x;
+                p01[1 % B] = a.y + c.y;
+                p01[2 % B] = a.z + c.z;
+                p01[3 % B] = a.w + c.w;
+            }
+        }
 #pragma unroll
         for (int h = 0; h < 16; h += SS_HALF) {
             // phase 1: every table address of the half step
@@ -229,7 +284,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
             for (int jj = 0; jj < SS_HALF; ++jj) {
 #pragma unroll
                 for (int b = 0; b < B; ++b) {
-                    float P = v[jj][0][b];
+                    float P = G2 ? p01[b] + v[jj][0][b] : v[jj][0][b];
 #pragma unroll
                     for (int k = 1; k < KF; ++k) P += v[jj][k][b];
                     icq_hit_shift_in(hm[b], P, t[b]);
@@ -238,6 +293,11 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
         }
         if (id0 + 16 > end || id0 + 16 < id0) {   // ragged tail: drop bits of items at or beyond `end`
             const uint32_t valid = id0 < end ? 0xFFFFu & ~((1u << (16 - (end - id0))) - 1u) : 0u;
+#pragma unroll
+            for (int b = 0; b < B; ++b) hm[b] &= valid;
+        }
+        if (G2) {   // the padding behind a tuple's last item
+            const uint32_t valid = (0xFFFF0000u >> (ci >> 16)) & 0xFFFFu;
 #pragma unroll
             for (int b = 0; b < B; ++b) hm[b] &= valid;
         }
@@ -311,7 +371,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     // R register sets of 1024 items per wavefront: R - 1 steps are always in flight
     uint32_t g = begin + wave * 1024u;
 #pragma unroll
-    for (int r = 0; r < R - 1; ++r) load(g + (uint32_t)r * step, w[r]);
+    for (int r = 0; r < R - 1; ++r) load(g + (uint32_t)r * step, w[r], ci[r]);
     fill_tables();
     static_assert(SS_CHECK % 2 == 0, "a pair of steps never straddles a periodic check");
     uint32_t held[B];        // PAIR: the even step's hit bits, waiting for the odd step's
@@ -321,14 +381,24 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     for (uint32_t it = 0; it < nsteps; it += R, g += R * step) {
 #pragma unroll
         for (int u = 0; u < R; ++u) {
-            load(g + (uint32_t)(u + R - 1) * step, w[(u + R - 1) % R]);     // never conditional
+            load(g + (uint32_t)(u + R - 1) * step, w[(u + R - 1) % R], ci[(u + R - 1) % R]);     // never conditional
             const uint32_t gu = g + (uint32_t)u * step, itu = it + u;
             const uint32_t idu = gu + lane * 16;
             const bool check = itu < nsteps && ((itu % SS_CHECK) == SS_CHECK - 1 || itu == nsteps - 1);   // block-uniform
             uint32_t hm[B];
 #pragma unroll
             for (int b = 0; b < B; ++b) hm[b] = 0;
-            if (gu < end && gu >= begin) hits(gu, w[u], hm);
+            if (gu < end && gu >= begin) hits(gu, w[u], ci[u], hm);
+            if (MASK) {
+                // the 16 hit bits of this lane's positions, first position in bit 0
+                if (itu < nsteps) {
+#pragma unroll
+                    for (int b = 0; b < B; ++b)
+                        if (qbase + b < Q)
+                            masks[(size_t)(qbase + b) * mask_stride + (gu >> 4) + lane] = (uint16_t)(__builtin_bitreverse32(hm[b]) >> 16);
+                }
+                continue;
+            }
             if (PAIR && u % 2 == 0) {
 #pragma unroll
                 for (int b = 0; b < B; ++b) held[b] = hm[b] << 16;
@@ -346,49 +416,95 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     }
 }
 
-template <int KF, int B, bool NT>
+// masks == nullptr: the queries' lists cand_ids [Q][cap] (item ids); else one hit bit per scan position
+// and query, mask_stride 16-bit words per query, for the positions below scan_end (whole block steps).
+template <int KF, int B, bool NT, bool G2, bool MASK>
 int launch_stream_as(const icq_index *ix, const float *lut, int Q, const float *thr, uint32_t *cand_ids,
-                  uint32_t *cand_count, int64_t cap, hipStream_t s) {
-    const size_t tab = sizeof(float) * KF * ICQ_LUT_W * ss_copies(KF, B) * B;
+                     uint32_t *cand_count, int64_t cap, uint16_t *masks, size_t mask_stride, int64_t scan_end,
+                     hipStream_t s) {
+    const size_t tab = sizeof(float) * (KF * ICQ_LUT_W * ss_copies(KF, B) * B + (G2 ? 2 * ICQ_LUT_W * B : 0));
     const int threads = SS_THREADS;
     // ids one wavefront stages per query: 512 (32 KB per query) when the tables leave that much LDS
     uint32_t wave_cap = 512;
     while (tab + sizeof(uint32_t) * B * SS_WAVES * wave_cap > 163840 - 512) wave_cap -= 8;   // 512: the static arrays
-    const size_t lds = tab + sizeof(uint32_t) * B * SS_WAVES * wave_cap;
-    static bool attr_set = false;
-    if (!attr_set) {
-        ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_stream_kernel<KF, B, NT>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 163840 - 512));
-        attr_set = true;
-    }
+    const size_t lds = MASK ? tab : tab + sizeof(uint32_t) * B * SS_WAVES * wave_cap;
+    ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&scan_stream_kernel<KF, B, NT, G2, MASK>), 163840 - 512));
     const int groups = (Q + B - 1) / B;
     const uint32_t step = (uint32_t)(threads / 64) * 1024u;
+    const int64_t nitems = G2 ? ix->g2_npos : ix->N;          // scan positions that can hold an item
+    const int64_t npos = MASK ? scan_end : nitems;            // positions to walk
     // one wave of equally loaded blocks: the chip is filled once and every block streams a long run
     int64_t chunks = ((int64_t)ix->num_cu + groups - 1) / groups;
-    int64_t max_chunks = (ix->N + step - 1) / step;
+    int64_t max_chunks = (npos + step - 1) / step;
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks < 1) chunks = 1;
-    uint32_t per = (uint32_t)(((ix->N + chunks - 1) / chunks + step - 1) / step * step);
-    chunks = (ix->N + per - 1) / per;
-    dim3 grid((unsigned)chunks, (unsigned)groups);
-    scan_stream_kernel<KF, B, NT><<<grid, threads, lds, s>>>(ix->fast, ix->Npad, (uint32_t)ix->N, lut,
-                                                         ix->K, thr, Q, cand_ids, cand_count, cap, per,
-                                                         wave_cap);
+    uint32_t per = (uint32_t)(((npos + chunks - 1) / chunks + step - 1) / step * step);
+    chunks = (npos + per - 1) / per;
+    // query groups along grid.y, at most 65535 per launch
+    for (int g0 = 0; g0 < groups; g0 += 65535) {
+        const int ng = groups - g0 < 65535 ? groups - g0 : 65535;
+        const int q0 = g0 * B, nq = (Q - q0) < ng * B ? (Q - q0) : ng * B;
+        dim3 grid((unsigned)chunks, (unsigned)ng);
+        scan_stream_kernel<KF, B, NT, G2, MASK><<<grid, threads, lds, s>>>(
+            G2 ? ix->g2_rows : ix->fast, G2 ? ix->g2_npad : ix->Npad, (uint32_t)nitems,
+            lut + (int64_t)q0 * ix->K * ICQ_LUT_W, ix->K, thr + q0, nq, MASK ? nullptr : cand_ids + (int64_t)q0 * cap,
+            cand_count + q0, cap, per, wave_cap, G2 ? ix->g2_info : nullptr, G2 ? ix->perm : nullptr,
+            MASK ? masks + (size_t)q0 * mask_stride : nullptr, mask_stride, (uint32_t)scan_end);
+    }
     return icq_check_launch();
 }
 
 // One or two queries per pass over a code array that cannot stay in the 256 MB last-level cache:
 // the memory-bound case, where the non-temporal stream pays.  (Four queries per pass are bound by
 // the table lookups, and a smaller array is re-read from the cache by the next pass or call.)
-template <int KF, int B>
+template <int KF, int B, bool G2>
 int launch_stream(const icq_index *ix, const float *lut, int Q, const float *thr, uint32_t *cand_ids,
-                  uint32_t *cand_count, int64_t cap, hipStream_t s) {
-#ifndef ICQ_NT_BYTES
-#define ICQ_NT_BYTES (256ll << 20)
-#endif
-    if (B <= 2 && (int64_t)KF * ix->Npad > ICQ_NT_BYTES)
-        return launch_stream_as<KF, B, (B <= 2)>(ix, lut, Q, thr, cand_ids, cand_count, cap, s);
-    return launch_stream_as<KF, B, false>(ix, lut, Q, thr, cand_ids, cand_count, cap, s);
+                  uint32_t *cand_count, int64_t cap, uint16_t *masks, size_t mask_stride, int64_t scan_end,
+                  hipStream_t s) {
+    constexpr int64_t NT_BYTES = 256ll << 20;
+    const int64_t bytes = G2 ? (int64_t)KF * ix->g2_npad : (int64_t)KF * ix->Npad;
+    const bool nt = B <= 2 && bytes > NT_BYTES;
+    if (masks) {
+        if (nt) return launch_stream_as<KF, B, (B <= 2), G2, true>(ix, lut, Q, thr, cand_ids, cand_count, cap, masks, mask_stride, scan_end, s);
+        return launch_stream_as<KF, B, false, G2, true>(ix, lut, Q, thr, cand_ids, cand_count, cap, masks, mask_stride, scan_end, s);
+    }
+    if (nt) return launch_stream_as<KF, B, (B <= 2), G2, false>(ix, lut, Q, thr, cand_ids, cand_count, cap, masks, mask_stride, scan_end, s);
+    return launch_stream_as<KF, B, false, G2, false>(ix, lut, Q, thr, cand_ids, cand_count, cap, masks, mask_stride, scan_end, s);
+}
+
+// Item-by-item stage 1 for Kf <= 4: one pass over the fast sub-codes per group of B queries, B = 1 or 2
+// for one or two queries, else 4.  An index that also keeps the items grouped by their first two
+// fast sub-codes streams only the remaining Kf - 2 rows.
+int launch_stream_any(const icq_index *ix, const float *lut, int Q, const float *thr, uint32_t *cand_ids,
+                      uint32_t *cand_count, int64_t cap, uint16_t *masks, size_t mask_stride, int64_t scan_end,
+                      hipStream_t s) {
+    const int bsel = Q >= 3 ? 2 : Q >= 2 ? 1 : 0;
+#define ICQ_SS(KF, B, G2) launch_stream<KF, B, G2>(ix, lut, Q, thr, cand_ids, cand_count, cap, masks, mask_stride, scan_end, s)
+    if (icq_g2_usable(ix)) {
+        switch ((ix->Kf - 2) * 3 + bsel) {
+            case 3: return ICQ_SS(1, 1, true);
+            case 4: return ICQ_SS(1, 2, true);
+            case 5: return ICQ_SS(1, 4, true);
+            case 6: return ICQ_SS(2, 1, true);
+            case 7: return ICQ_SS(2, 2, true);
+            default: return ICQ_SS(2, 4, true);
+        }
+    }
+    switch (ix->Kf * 3 + bsel) {
+        case 3: return ICQ_SS(1, 1, false);
+        case 4: return ICQ_SS(1, 2, false);
+        case 5: return ICQ_SS(1, 4, false);
+        case 6: return ICQ_SS(2, 1, false);
+        case 7: return ICQ_SS(2, 2, false);
+        case 8: return ICQ_SS(2, 4, false);
+        case 9: return ICQ_SS(3, 1, false);
+        case 10: return ICQ_SS(3, 2, false);
+        case 11: return ICQ_SS(3, 4, false);
+        case 12: return ICQ_SS(4, 1, false);
+        case 13: return ICQ_SS(4, 2, false);
+        default: return ICQ_SS(4, 4, false);
+    }
+#undef ICQ_SS
 }
 
 // ------------------------------------------------------------------ lanes = items
@@ -490,21 +606,7 @@ int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *t
     if (ix->Kf <= 4) {
         // lanes = items, one pass over the fast sub-codes per group of B queries: B = 1 or 2 for one or
         // two queries, B = 4 for every larger call that has neither grouping nor transposed tables
-        int rc;
-        switch (ix->Kf * 3 + (Q >= 3 ? 2 : Q >= 2 ? 1 : 0)) {
-            case 3: rc = launch_stream<1, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 4: rc = launch_stream<1, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 5: rc = launch_stream<1, 4>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 6: rc = launch_stream<2, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 7: rc = launch_stream<2, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 8: rc = launch_stream<2, 4>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 9: rc = launch_stream<3, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 10: rc = launch_stream<3, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 11: rc = launch_stream<3, 4>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 12: rc = launch_stream<4, 1>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            case 13: rc = launch_stream<4, 2>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-            default: rc = launch_stream<4, 4>(ix, lut, Q, thr, cand_ids, cand_count, cap, s); break;
-        }
+        const int rc = launch_stream_any(ix, lut, Q, thr, cand_ids, cand_count, cap, nullptr, 0, 0, s);
         if (rc != ICQ_OK || !cand_part) return rc;
         const int bpq = (int)((cap + 255) / 256 < 256 ? (cap + 255) / 256 : 256);
         fill_partials_kernel<<<(unsigned)Q * (unsigned)bpq, 256, 0, s>>>(
@@ -529,12 +631,7 @@ int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *t
     dim3 grid((unsigned)groups, (unsigned)chunks);
 #define ICQ_SI_LAUNCH(KFM)                                                                          \
     do {                                                                                            \
-        static bool attr_set = false;                                                               \
-        if (!attr_set) {                                                                            \
-            ICQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_items_kernel<KFM>),\
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 65536));    \
-            attr_set = true;                                                                        \
-        }                                                                                           \
+        ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&scan_items_kernel<KFM>), 65536)); \
         scan_items_kernel<KFM><<<grid, SI_THREADS, lds, s>>>(ix->fast, ix->Npad, (uint32_t)ix->N,   \
                                                              lut, ix->K, ix->Kf, thr, Q, nb,        \
                                                              cand_ids, cand_part, cand_count, cap,  \
@@ -545,6 +642,16 @@ int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *t
     else ICQ_SI_LAUNCH(64);
 #undef ICQ_SI_LAUNCH
     return icq_check_launch();
+}
+
+int icq_launch_scan_masks(const icq_index *ix, const float *lut, int Q, const float *thr, uint16_t *masks,
+                          size_t mask_stride, int64_t scan_end, uint32_t *cand_count, uint32_t *key_count,
+                          hipEvent_t after_fill, hipStream_t s) {
+    if (Q == 0) return ICQ_OK;
+    zero_counts_kernel<<<(Q + 255) / 256, 256, 0, s>>>(cand_count, Q);
+    zero_counts_kernel<<<(Q + 255) / 256, 256, 0, s>>>(key_count, Q);
+    if (after_fill) ICQ_HIP_TRY(hipEventRecord(after_fill, s));
+    return launch_stream_any(ix, lut, Q, thr, nullptr, cand_count, 0, masks, mask_stride, scan_end, s);
 }
 
 ICQ_EXPORT int icq_scan_fast(const icq_index *ix, const float *lut, int Q, const float *thresholds,

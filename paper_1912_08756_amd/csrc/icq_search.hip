@@ -8,18 +8,27 @@
 
 icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool with_lut,
                          bool with_cands) {
-    icq_ws_layout L;
+    icq_ws_layout L = {};
     size_t off = 0;
     L.lut_off = off;
     if (with_lut) off = icq_align_up(off + sizeof(float) * (size_t)Q * ix->K * ICQ_LUT_W, ICQ_ALIGN);
     // icq_search with the grouped stage 1 keeping the lists on chip: no candidate lists in the
     // workspace, only (few queries, several blocks per query) the parts' lists for the merge
     const bool on_chip = with_cands && icq_group_fused(ix, Q, topk);
+    L.masked = with_cands && !on_chip && icq_masks_usable(ix, Q, topk);
+    L.splits = icq_refine_splits(ix, Q, cap, topk);
     L.ids_off = off;
-    if (with_cands && !on_chip) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
+    if (L.masked) {
+        L.scan_end = icq_mask_scan_end(ix);
+        L.mask_stride = (size_t)(L.scan_end / 16);
+        off = icq_align_up(off + sizeof(uint16_t) * (size_t)Q * L.mask_stride, ICQ_ALIGN);
+        L.keycount_off = off;
+        off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q, ICQ_ALIGN);
+    } else if (with_cands && !on_chip) {
+        off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q * (size_t)cap, ICQ_ALIGN);
+    }
     L.count_off = off;
     if (with_cands) off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q, ICQ_ALIGN);
-    L.splits = icq_refine_splits(ix, Q, cap, topk);
     L.keys_off = off;
     // slice lists [Q][splits][topk] (when sliced), then one 64-bit key per candidate [Q][cap]
     if (on_chip) {
@@ -35,15 +44,26 @@ icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool
     return L;
 }
 
+// Most queries icq_search takes through the kernels at once.
+constexpr int SEARCH_MAX_BATCH = 32768;
+
 ICQ_EXPORT int icq_workspace_bytes(const icq_index *ix, int Q, int64_t cap, int topk, size_t *out) {
-    if (!ix || !out || Q < 0 || Q > (1 << 22) || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK)
+    if (!ix || !out || Q < 0 || Q > ICQ_MAX_Q || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK)
         return ICQ_ERR_ARG;
     if ((double)Q * (double)cap >= 1099511627776.0) return ICQ_ERR_ARG;
-    // the largest of what icq_search and the staged calls (which take lists from the caller) carve out
-    const size_t a = icq_layout(ix, Q, cap, topk, true, true).total;
-    const size_t b = icq_layout(ix, Q, cap, topk, false, false).total;
-    const size_t need = a > b ? a : b;
-    *out = need > ICQ_ALIGN ? need : ICQ_ALIGN;
+    // the largest of what icq_search and the staged calls (which take lists from the caller) carve
+    // out, whichever stage-1 strategy is selected when they run
+    size_t need = ICQ_ALIGN;
+    const int Qs = Q < SEARCH_MAX_BATCH ? Q : SEARCH_MAX_BATCH;
+    for (int mode = ICQ_SCAN_AUTO; mode <= ICQ_SCAN_GROUPED; ++mode) {
+        icq_index view = *ix;
+        view.scan_mode = mode;
+        const size_t a = icq_layout(&view, Qs, cap, topk, true, true).total;
+        const size_t b = icq_layout(&view, Q, cap, topk, false, false).total;
+        if (a > need) need = a;
+        if (b > need) need = b;
+    }
+    *out = need;
     return ICQ_OK;
 }
 
@@ -51,7 +71,7 @@ static int search_impl(const icq_index *ix, const float *queries, int Q, const f
                        int64_t cap, int topk, uint32_t *out_ids, float *out_dist,
                        uint32_t *out_survivors, void *workspace, size_t workspace_bytes,
                        void *stream) {
-    if (!ix || Q < 0 || Q > (1 << 22) || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK)
+    if (!ix || Q < 0 || Q > ICQ_MAX_Q || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK)
         return ICQ_ERR_ARG;
     if (Q == 0) return ICQ_OK;
     if (!queries || !thresholds || !out_ids || !out_dist) return ICQ_ERR_ARG;
@@ -59,7 +79,7 @@ static int search_impl(const icq_index *ix, const float *queries, int Q, const f
     if (!workspace || ((uintptr_t)workspace % ICQ_ALIGN) != 0) return ICQ_ERR_WORKSPACE;
 
     // Largest sub-batch (all of Q, else a multiple of 64 queries) that fits the workspace.
-    int Qb = Q;
+    int Qb = Q < SEARCH_MAX_BATCH ? Q : SEARCH_MAX_BATCH;
     while (icq_layout(ix, Qb, cap, topk, true, true).total > workspace_bytes) {
         if (Qb <= 64) return ICQ_ERR_WORKSPACE;
         Qb = ((Qb / 2) + 63) / 64 * 64;
@@ -87,6 +107,20 @@ static int search_impl(const icq_index *ix, const float *queries, int Q, const f
         if (timed) ICQ_HIP_TRY(hipEventRecord(ev[0], s));
         int rc = icq_launch_build_lut(ix, queries + (int64_t)q0 * ix->d, nq, lut, s);
         if (rc != ICQ_OK) return rc;
+        if (L.masked) {
+            // item-by-item stage 1 into hit bits, stage 2 chunk by chunk from them
+            uint16_t *masks = reinterpret_cast<uint16_t *>(ws + L.ids_off);
+            uint32_t *key_count = reinterpret_cast<uint32_t *>(ws + L.keycount_off);
+            rc = icq_launch_scan_masks(ix, lut, nq, thresholds + q0, masks, L.mask_stride, L.scan_end, cnt, key_count,
+                                       timed ? ev[1] : nullptr, s);
+            if (rc != ICQ_OK) return rc;
+            if (timed) ICQ_HIP_TRY(hipEventRecord(ev[2], s));
+            rc = icq_launch_refine_masks(ix, lut, nq, masks, L.mask_stride, L.scan_end, cap, topk, L.splits, keys,
+                                         key_count, cnt, out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
+            if (rc != ICQ_OK) return rc;
+            if (timed) ICQ_HIP_TRY(hipEventRecord(ev[3], s));
+            continue;
+        }
         int list_kind = ICQ_LIST_IDS;
         // keys of the survivors behind the slice lists, or (on-chip lists) the parts' lists
         unsigned long long *cand_keys = icq_group_fused(ix, nq, topk) ? keys
