@@ -511,18 +511,25 @@ def test_search_grouped_by_the_first_two_fast_codes(gpu, name, N, Q, over, frac,
         check_candidates(P[q], thr[q], ids[q], part[q], cnt[q], cap)
 
 
-@pytest.mark.parametrize("mode", [1, 2], ids=["streamed", "grouped"])
-def test_search_over_many_chunks_of_hit_bits(gpu, mode):
-    """Enough items for several dozen stage-2 chunks (32768 scan positions each), so that both
-    launches of the chunk walk run -- the unfiltered first part over more than one chunk, then the
-    rest bounded by its topk-th distance -- with a ragged last chunk."""
-    cfg = small("C4", 2_300_017, 24, K=12)
+@pytest.mark.parametrize("mode,over,Q", [(1, dict(K=12), 16), (2, dict(K=12), 16), (2, dict(K=8, Kf=3), 3),
+                                         (1, dict(K=4, Kf=1), 1), (1, dict(K=6, Kf=2), 9), (2, dict(K=4), 5)],
+                         ids=["streamed-K12", "grouped-K12", "grouped-Kf3-K8", "streamed-Kf1", "streamed-Kf2", "grouped-K4"])
+def test_search_over_many_chunks_of_hit_bits(gpu, mode, over, Q):
+    """From 2^22 items on icq_search hands the survivors of the item-by-item stage 1 to stage 2 as
+    hit bits.  Enough items for more than a hundred stage-2 chunks (32768 scan positions each), so
+    that both launches of the chunk walk run -- the unfiltered first part over several chunks, then
+    the rest bounded by its topk-th distance -- with a ragged last chunk; 4-, 8- and 16-byte records,
+    one, two and four queries per pass of stage 1."""
+    cfg = small("C4", 4_300_017, Q, **over)
     T, P, D = oracle_all(cfg)
     thr = thresholds_quantile(P, 0.01)
-    thr[3] = np.inf                                          # every position a survivor: dense rounds
+    thr[Q - 1] = np.inf                                      # every position a survivor: dense rounds
     g = Gpu(gpu, cfg, mode)
-    out_ids, out_dist, surv = _check_search(g, cfg, T, P, D, thr, 100, cfg["N"])
-    assert surv[3] == cfg["N"]
+    out_ids, out_dist, surv = _check_search(g, cfg, T, P, D, thr, 100, cfg["N"], min_equal=0.8 if Q > 4 else 0.0)
+    assert surv[Q - 1] == cfg["N"]
+    if mode == 2:       # the grouped and the item-by-item order must agree bit for bit
+        ref = Gpu(gpu, cfg, 1).search(thr, cfg["N"], 100)
+        assert np.array_equal(ref[0], out_ids) and np.array_equal(ref[1], out_dist) and np.array_equal(ref[2], surv)
 
 # ------------------------------------------------------------------ full size, as benchmarked
 @pytest.mark.parametrize("mode", [0, 1], ids=["auto", "streamed"])
