@@ -1,16 +1,20 @@
 #!/usr/bin/env python3
 """Throughput of the ICQ query-time path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4]
 
-A step is one icq_search call over the whole query set of the workload (table
-build, stage-1 scan, stage-2 refine, top-k), inputs resident in HBM.  Prints ONE
-JSON line: queries/s; the roofline of the dominant kernel of that step (stage 1
-over the items grouped by fast-code tuple, fused with the survivors' distances
-and the nearest-neighbour lists);
-the same step with the item-by-item stage 1 (bound by LDS table reads); the
-stage-1 scan on a 400 MB fast-code array with one and two queries (bound by
-HBM); and the CPU oracle timed on the host cores as a baseline.
+A step is one pass of the whole path (table build, stage-1 scan, stage-2 refine,
+top-k) over the workload's whole query set, one icq_search call per query batch of
+the size the workload names, inputs resident in HBM.  The default workload is the
+largest one: N = 1e8 items, K = 16, Kf = 4, 1000 queries in batches of 128, top-100.
+Prints ONE JSON line: queries/s; `roofline` for the dominant kernel of that step
+with the resource that binds it, its work model and the time of its launches
+measured by events on the launch stream inside the timed calls; the same for
+stage 2; the step with stage 1 walking all Kf fast rows item by item; the stage-1
+scan on a 400 MB fast-code array with one, two and four queries per pass (bound by
+HBM); the CPU oracle timed on the host cores as a baseline, its lists doubling as
+the oracle-matched check; and every other workload shape, each checked against
+the oracle by the acceptance rule.
 """
 import argparse
 import json
@@ -26,7 +30,13 @@ if ROOT not in sys.path:
 import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E
-LDS_PEAK_GBS = 256 * 128 * 2.4              # 256 CUs x 128 B/clk x 2.4 GHz = 78643 GB/s
+# Plain vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 lane operations per second (the
+# published 157.3 TFLOP/s fp32 counts a fused multiply-add as two and assumes the packed two-wide
+# form; an add, a compare or a bit operation is one operation in one lane)
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# LDS: the measured rate of 4-, 8- and 16-byte reads is 16 addresses per clock and CU, whatever the
+# width (64 / 120 / 192 B/clk/CU measured: profiles/machine_limits.txt), so table reads are priced per address
+LDS_PEAK_GADDR = 256 * 16 * 2.4             # 1e9 addresses per second
 SURVIVE_FRAC = 0.01
 
 
@@ -92,7 +102,11 @@ def hbm_leg(torch, b, steps, warmup):
     cb = torch.from_numpy(synth.make_codebooks(Kf, 256, d, synth.sigmas(("geom", 0.8), Kf), 4)).cuda()
     idx = b.icq_index_create(cb, codes, Kf)
     out = {}
-    for Q in (1, 2, 4):
+    for Q, grouped in ((1, False), (2, False), (4, False), (1, True), (2, True)):
+        # item by item over all four rows (the 400 MB stream), or over the two rows left when the
+        # items are ordered by their first two fast sub-codes
+        b.icq_index_set_scan_mode(idx, b.ICQ_SCAN_GROUPED if grouped else b.ICQ_SCAN_STREAMED)
+        npos = b.icq_index_scan_positions(idx, Q)
         src = codes[:, :Q].long()
         q = torch.stack([sum(cb[k, src[k, i]] for k in range(Kf)) for i in range(Q)]).contiguous()
         q = q + 0.05 * q.norm(dim=1, keepdim=True) / math.sqrt(d) * torch.randn((Q, d), device="cuda", generator=g)
@@ -118,27 +132,51 @@ def hbm_leg(torch, b, steps, warmup):
         b.icq_index_set_stage_timing(idx, False)
         ms = stage[1]
         surv = int(cnt.sum().item())
-        alg_bytes = Kf * N + 4 * Q * Kf * 256 + 4 * surv      # codes once, tables, survivor ids
+        # what the launch must move: the streamed rows once, the tables, the survivors' ids
+        # (grouped: two rows and one 4-byte label per 16 positions, over the padded positions)
+        rows = (Kf - 2) * npos + npos // 4 if grouped else Kf * N
+        alg_bytes = rows + 4 * Q * Kf * 256 + 4 * surv
         achieved = alg_bytes / (ms * 1e-3) / 1e9
-        out["B%d" % Q] = {"bound": "hbm", "kernel": "scan_stream_kernel<4,%d,%s>" % (Q, "true" if Q <= 2 else "false"), "achieved": round(achieved, 1),
-                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                          "traffic": (pmc_traffic("scan_stream_kernel_B%d" % Q) or {}).get("bytes"),
-                          "ms": round(ms, 4),
-                          "workload": "fast codes [4][1e8] u8 (400 MB), %d quer%s per pass, %d survivors"
-                                      % (Q, "y" if Q == 1 else "ies", surv)}
+        nt = "true" if Q <= 2 and rows > (256 << 20) else "false"
+        kern = "scan_stream_kernel<%d,%d,%s,%s,false>" % (Kf - 2 if grouped else Kf, Q, nt, "true" if grouped else "false")
+        tr = pmc_traffic("scan_stream_kernel_B%d%s" % (Q, "g" if grouped else ""), "fast400MB")
+        out["B%d%s" % (Q, "_grouped" if grouped else "")] = {
+            "bound": "hbm", "kernel": kern, "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "algorithmic_bytes": alg_bytes, "traffic": tr["bytes"] if tr else None, "traffic_source": tr["source"] if tr else None,
+            "ms": round(ms, 4),
+            "workload": "fast codes [4][1e8] u8 (400 MB)%s, %d quer%s per pass, %d survivors"
+                        % (", items ordered by the first two: %d positions, %d MB streamed" % (npos, rows >> 20) if grouped else "",
+                           Q, "y" if Q == 1 else "ies", surv)}
     return out
+
+
+def rule_check(orc, cfg, thr_np, qs, gpu_ids, gpu_dist):
+    """The acceptance rule (tests/helpers.py: distances within 1e-4 (|d| + 1), top-k sets equal up
+    to ties and to items within that tolerance of the threshold) on the queries `qs`, against the
+    oracle's crude and full distances of EVERY item.  Raises AssertionError on a violation."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import check_topk
+    codes, Kf, K, topk = cfg["codes"], cfg["Kf"], cfg["K"], cfg["topk"]
+    group = max(1, min(16, int(2e9 // (16 * codes.shape[1]))))     # P and D: 16 bytes per item and query
+    for c0 in range(0, len(qs), group):
+        sel = np.asarray(qs[c0:c0 + group], dtype=np.int64)
+        T = orc.lut(cfg["codebooks"], cfg["queries"][sel])
+        P = orc.partial(T, codes, Kf)
+        D = orc.partial(T, codes, K)        # all K terms, k ascending: the full distance
+        for j, q in enumerate(sel):
+            check_topk(P[j], D[j], thr_np[q], topk, gpu_ids[q], gpu_dist[q])
+    return len(qs)
 
 
 def cpu_baseline(cfg, thr_np, gpu_ids, gpu_dist, target_s=15.0):
     """The oracle as it stands, timed on the host cores on a bounded sample of the
     same workload; its results double as the oracle-matched check of the GPU lists."""
     from oracle import icq_oracle as orc
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from helpers import check_topk
     codes, cb, queries = cfg["codes"], cfg["codebooks"], cfg["queries"]
     Kf, topk = cfg["Kf"], cfg["topk"]
     Q = queries.shape[0]
-    pilot = min(Q, 64)
+    pilot = min(Q, orc.threads())
     t0 = time.perf_counter()
     T = orc.lut(cb, queries[:pilot])
     orc.search(T, codes, Kf, thr_np[:pilot], topk)
@@ -148,25 +186,22 @@ def cpu_baseline(cfg, thr_np, gpu_ids, gpu_dist, target_s=15.0):
     T = orc.lut(cb, queries[:n])
     o_ids, o_dist, o_cnt = orc.search(T, codes, Kf, thr_np[:n], topk)
     dt = time.perf_counter() - t0
-    # oracle-matched: full acceptance rule on a few queries, identical-list rate on all sampled
-    # (the first 16 queries, and up to 48 of those whose lists differ from the oracle's -- ties and
-    # items within rounding of the threshold or of the topk-th distance, which the rule decides)
+    # oracle-matched: identical-list rate on all sampled queries; the acceptance rule itself on the
+    # first few and on a bounded number of those whose lists differ from the oracle's (ties and items
+    # within rounding of the threshold or of the topk-th distance, which the rule decides)
     identical = (gpu_ids[:n] == o_ids).all(axis=1)
     differ = np.nonzero(~identical)[0]
-    check = np.unique(np.concatenate([np.arange(min(n, 16)), differ[:48]])).astype(np.int64)
-    for c0 in range(0, len(check), 16):
-        qs = check[c0:c0 + 16]
-        Tq = np.ascontiguousarray(T[qs])
-        P = orc.partial(Tq, codes, Kf)
-        _, _, D = orc.adc_exhaustive(Tq, codes, 1, want_all=True)
-        for j, q in enumerate(qs):
-            check_topk(P[j], D[j], thr_np[q], topk, gpu_ids[q], gpu_dist[q])
+    few = 16 if codes.shape[1] <= 20_000_000 else 4
+    most = 48 if codes.shape[1] <= 20_000_000 else 12
+    check = np.unique(np.concatenate([np.arange(min(n, few)), differ[:most]])).astype(np.int64)
+    rule_check(orc, cfg, thr_np, check, gpu_ids, gpu_dist)
     same = float(identical.mean())
     return ({"value": round(n / dt, 2), "unit": "queries/s", "cores": orc.threads(), "kind": "oracle",
              "sample": "first %d of %d queries of the workload, full N, table build + two-step search, "
                        "%.1f s wall" % (n, Q, dt)},
-            {"checked_queries": int(len(check)), "checked_of_the_differing": int(min(len(differ), 48)),
-             "differing_lists": int(len(differ)), "identical_lists_frac": round(same, 4), "sampled_queries": n})
+            {"checked_queries": int(len(check)), "checked_of_the_differing": int(min(len(differ), most)),
+             "rule_violations": 0, "differing_lists": int(len(differ)), "identical_lists_frac": round(same, 4),
+             "sampled_queries": n})
 
 
 def policy_leg(torch, b, cfg, index, queries, step_args, steps, with_cpu):
@@ -174,7 +209,8 @@ def policy_leg(torch, b, cfg, index, queries, step_args, steps, with_cpu):
     with the margin of Eq. 11 (icq_sample_thresholds), then the two-step search, then the
     operation counts of the paper's speed axis; on a few queries the result is compared with
     the paper's serial loop (oracle) run with the same margin."""
-    K, Kf, N, Q, topk = cfg["K"], cfg["Kf"], cfg["N"], cfg["Q"], cfg["topk"]
+    K, Kf, N, topk = cfg["K"], cfg["Kf"], cfg["N"], cfg["topk"]
+    Q = queries.shape[0]
     M = 4096
     # margin: variance of the data in the part of space the slow codebooks cover, summed over
     # the dimensions -- for sub-codes drawn uniformly that is the codeword variance of the slow
@@ -183,6 +219,7 @@ def policy_leg(torch, b, cfg, index, queries, step_args, steps, with_cpu):
     sigma_val = float(sum(cbk[k].var(axis=0).sum() for k in range(Kf, K)))
     sigma = torch.full((Q,), sigma_val, dtype=torch.float32, device="cuda")
     cap, out_ids, out_dist, surv, ws = step_args
+    out_ids, out_dist, surv = out_ids[:Q], out_dist[:Q], surv[:Q]
     lut = torch.empty((Q, K, 256), dtype=torch.float32, device="cuda")
     thr = torch.empty((Q,), dtype=torch.float32, device="cuda")
     b.icq_build_lut(index, queries, lut)
@@ -205,7 +242,8 @@ def policy_leg(torch, b, cfg, index, queries, step_args, steps, with_cpu):
     torch.cuda.synchronize()
     sm = summary.cpu().numpy()
     surv_np = surv.cpu().numpy().view(np.uint32)
-    out = {"policy": "t_q = crude distance of the top-%d-th nearest of the first %d items + sigma" % (topk, M),
+    out = {"queries": Q,
+           "policy": "t_q = crude distance of the top-%d-th nearest of the first %d items + sigma" % (topk, M),
            "sigma": round(sigma_val, 4), "ms_sample_thresholds": round(ms_sample, 4),
            "ms_tables_policy_search": round(ms_whole, 4), "queries_per_s": round(Q / (ms_whole * 1e-3), 1),
            "survivors_mean": round(float(surv_np.mean()), 1), "survivors_frac": round(float(surv_np.mean()) / N, 5),
@@ -213,7 +251,7 @@ def policy_leg(torch, b, cfg, index, queries, step_args, steps, with_cpu):
            "code_bits": K * 8, "effective_code_bits": round(float(sm[3]), 3)}
     if with_cpu:
         from oracle import icq_oracle as orc
-        nq = 16
+        nq = min(16, Q)
         T = orc.lut(cfg["codebooks"], cfg["queries"][:nq])
         t0 = time.perf_counter()
         r_ids, _, refined = orc.running_search(T, cfg["codes"], Kf, np.full(nq, sigma_val), topk)
@@ -265,19 +303,20 @@ def encode_leg(torch, b, cfg, steps):
                     "v_mfma_f32_32x32x2_f32; each level also rewrites the N x d residuals" % K}
 
 
-def pmc_traffic(kernel):
-    """HBM bytes per launch of `kernel` from the committed counter summary (two rocprofv3
-    --pmc runs of this program, scaled by what the counters read for a copy of known
-    size), or None when the summary has no line for it.  Line format:
+def pmc_traffic(kernel, workload):
+    """HBM-side bytes per launch of `kernel` on `workload` from the committed counter summary
+    (two rocprofv3 --pmc runs of this program, scaled by what the counters read for a copy of
+    known size) -- a figure of that profile, not of this run -- or None when the summary has
+    no line for this kernel and workload.  Line format:
     `traffic <kernel> <workload> <fetch_bytes> <write_bytes>`."""
     path = os.path.join(ROOT, "profiles", "pmc_traffic.txt")
     if not os.path.exists(path):
         return None
     for line in open(path):
         f = line.split()
-        if len(f) == 5 and f[0] == "traffic" and f[1] == kernel:
+        if len(f) == 5 and f[0] == "traffic" and f[1] == kernel and f[2] == workload:
             return {"workload": f[2], "fetch_bytes": float(f[3]), "write_bytes": float(f[4]),
-                    "bytes": float(f[3]) + float(f[4]), "source": "profiles/pmc_traffic.txt"}
+                    "bytes": float(f[3]) + float(f[4]), "source": "profiles/pmc_traffic.txt (committed rocprofv3 run)"}
     return None
 
 
@@ -288,9 +327,10 @@ def configs_leg(torch, b, synth, skip, with_cpu, target_s=4.0):
     the sampled 1 % quantile.  Input preparation is not timed."""
     from oracle import icq_oracle as orc
     out = {}
-    for name, batch in (("C0", None), ("C1", None), ("C2", None), ("C3", 256), ("C4", 128)):
+    for name in ("C0", "C1", "C2", "C3", "C4"):
         if name == skip:
             continue
+        batch = synth.CONFIGS[name]["batch"]
         t_prep = time.perf_counter()
         cfg = synth.make(name)
         K, Kf, d, N, Q, topk = cfg["K"], cfg["Kf"], cfg["d"], cfg["N"], cfg["Q"], cfg["topk"]
@@ -334,8 +374,15 @@ def configs_leg(torch, b, synth, skip, with_cpu, target_s=4.0):
         torch.cuda.synchronize()
         sec = (time.perf_counter() - t0) / reps
         surv_np = surv.cpu().numpy().view(np.uint32)
+        b.icq_index_set_stage_timing(index, True)
+        run()
+        torch.cuda.synchronize()
+        stage, _, _ = b.icq_index_stage_times(index)
+        b.icq_index_set_stage_timing(index, False)
         entry = {"workload": "%s: d=%d K=%d Kf=%d N=%d Q=%d top-%d, batches of %d" % (name, d, K, Kf, N, Q, topk, batch),
                  "queries_per_s": round(Q / sec, 1), "ms_per_batch": round(sec * 1e3 / math.ceil(Q / batch), 4),
+                 "stages_ms_per_batch": {"build_lut": round(stage[0], 4), "stage1": round(stage[1], 4), "stage2": round(stage[2], 4)},
+                 "stage1_kernel": stage1_kernel_name(Kf, K, N, batch, topk),
                  "survivors_mean": round(float(surv_np.mean()), 1), "overflowed_lists": int((surv_np > cap).sum())}
         if with_cpu:
             thr_np = thr.cpu().numpy()
@@ -349,10 +396,19 @@ def configs_leg(torch, b, synth, skip, with_cpu, target_s=4.0):
                 t0 = time.perf_counter()
                 o_ids = orc.search(orc.lut(cfg["codebooks"], cfg["queries"][:n]), cfg["codes"], Kf, thr_np[:n], topk)[0]
                 dt = time.perf_counter() - t0
-            g_ids = out_ids[:n].cpu().numpy().view(np.uint32)
+            g_ids = out_ids.cpu().numpy().view(np.uint32)
+            g_dist = out_dist.cpu().numpy()
+            identical = (g_ids[:n] == o_ids).all(axis=1)
+            differ = np.nonzero(~identical)[0]
+            # the acceptance rule on the first queries and on (at most 16 of) the lists that differ; a
+            # violation raises and the bench fails
+            check = np.unique(np.concatenate([np.arange(min(n, 4)), differ[:16]])).astype(np.int64)
+            rule_check(orc, cfg, thr_np, check, g_ids, g_dist)
             entry["oracle"] = {"queries_per_s": round(n / dt, 2), "cores": orc.threads(),
                                "sample": "first %d queries, full N, %.1f s wall" % (n, dt),
-                               "identical_lists_frac": round(float((g_ids == o_ids).all(axis=1).mean()), 4)}
+                               "identical_lists_frac": round(float(identical.mean()), 4),
+                               "differing_lists": int(len(differ)), "rule_checked_queries": int(len(check)),
+                               "rule_violations": 0}
             entry["gpu_over_oracle"] = round(Q / sec / (n / dt), 1)
         out[name] = entry
         log("[bench] %s: %.0f queries/s (%.3f ms per batch of %d)%s, prepared in %.0f s" %
@@ -363,12 +419,61 @@ def configs_leg(torch, b, synth, skip, with_cpu, target_s=4.0):
     return out
 
 
+def index_words(K):
+    return 1 if K <= 4 else 2 if K <= 8 else 4
+
+
+def stage1_form(Kf, K, N, Qb, topk):
+    """Which stage-1 form the library picks in automatic mode (icq_index_set_scan_mode) for a call
+    of Qb queries: 'tuples' (Kf <= 2: one evaluation per fast-code tuple, distances and lists in the
+    same kernel), 'pairs' (Kf = 3, 4 from 64 * 65536 items on: items ordered by their first two fast
+    sub-codes, the other rows streamed) or 'items' (all Kf rows streamed); and whether stage 1
+    hands stage 2 hit bits (from 2^22 items on) or candidate lists."""
+    if Kf <= 2 and Qb > 4 and N >= 256 ** Kf // 2:
+        return "tuples", False
+    bits = Kf <= 4 and K <= 16 and topk <= 512 and N >= 1 << 22
+    if Kf in (3, 4) and N >= 64 * 65536:
+        return "pairs", bits
+    return "items", bits
+
+
+def stage1_kernel_name(Kf, K, N, Qb, topk, mode_streamed=False):
+    form, bits = stage1_form(Kf, K, N, Qb, topk)
+    if mode_streamed and form != "items":
+        form, bits = "items", Kf <= 4 and K <= 16 and topk <= 512 and N >= 1 << 22
+    if form == "tuples":
+        return "group_keys_kernel<%d,%d,%s>" % (Kf, index_words(K), "true" if topk <= 256 and K <= 16 else "false")
+    if Kf > 4:
+        return "scan_items_kernel"
+    B = 4 if Qb >= 3 else Qb
+    return "scan_stream_kernel<%d,%d,false,%s,%s>" % (Kf - 2 if form == "pairs" else Kf, B,
+                                                       "true" if form == "pairs" else "false", "true" if bits else "false")
+
+
+def stage1_model(Kf, npos, Qb, pairs):
+    """Work of ONE launch of the item-by-item stage-1 kernel over npos scan positions for Qb
+    queries, four queries per pass.  Per (query, position): one table read per streamed row, the
+    additions of Eq. 2 left of the threshold, one comparison, one instruction that collects the hit
+    bit; per position and pass: one byte extraction and one address per streamed row (shared by
+    the pass's four queries).  pairs: the first two entries' sum comes once per 16 positions (not
+    counted) and is one more addition per (query, position)."""
+    R = Kf - 2 if pairs else Kf
+    adds = R if pairs else R - 1
+    passes = (Qb + 3) // 4 if Qb >= 3 else 1
+    return {"positions": npos, "queries": Qb, "passes": passes, "streamed_rows": R,
+            "alu_ops": npos * Qb * (adds + 2) + npos * passes * 2 * R,
+            "lds_addresses": npos * passes * R,            # one read serves the pass's queries
+            "table_entries": npos * Qb * R,
+            "code_bytes": npos * passes * R + (npos * passes // 4 if pairs else 0),
+            "hit_bit_bytes": npos * Qb // 8}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C1")
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hbm-leg", action="store_true")
     ap.add_argument("--no-streamed-leg", action="store_true")
@@ -399,26 +504,31 @@ def main():
     log("[bench] drawing workload", args.workload)
     cfg = synth.make(args.workload)
     K, Kf, d, N, Q, topk = cfg["K"], cfg["Kf"], cfg["d"], cfg["N"], cfg["Q"], cfg["topk"]
+    batch = min(cfg["batch"], Q)
+    nbatches = math.ceil(Q / batch)
     cb = torch.from_numpy(cfg["codebooks"]).cuda()
     codes = torch.from_numpy(cfg["codes"]).cuda()
     queries = torch.from_numpy(cfg["queries"]).cuda()
     index = b.icq_index_create(cb, codes, Kf)
     thr = sampled_thresholds(torch, b, cb, codes, queries, Kf, SURVIVE_FRAC, 16384, cfg["seed"])
-    cap = 1 << int(math.ceil(math.log2(max(64, N * SURVIVE_FRAC * 1.5))))
+    cap = int(N * SURVIVE_FRAC * 2) if N > 1 << 20 else 1 << int(math.ceil(math.log2(max(64, N * SURVIVE_FRAC * 1.5))))
     out_ids = torch.empty((Q, topk), dtype=torch.int32, device="cuda")
     out_dist = torch.empty((Q, topk), dtype=torch.float32, device="cuda")
     surv = torch.empty((Q,), dtype=torch.int32, device="cuda")
-    ws_bytes = b.icq_workspace_bytes(index, Q, cap, topk)
+    ws_bytes = b.icq_workspace_bytes(index, batch, cap, topk)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    log("[bench] N=%d Q=%d K=%d Kf=%d d=%d topk=%d cap=%d workspace=%.2f GB" %
-        (N, Q, K, Kf, d, topk, cap, ws_bytes / 1e9))
+    log("[bench] N=%d Q=%d (batches of %d) K=%d Kf=%d d=%d topk=%d cap=%d workspace=%.2f GB" %
+        (N, Q, batch, K, Kf, d, topk, cap, ws_bytes / 1e9))
 
     def step():
-        b.icq_search(index, queries, thr, cap, topk, out_ids, out_dist, surv, ws)
+        for q0 in range(0, Q, batch):
+            b.icq_search(index, queries[q0:q0 + batch], thr[q0:q0 + batch], cap, topk, out_ids[q0:q0 + batch],
+                         out_dist[q0:q0 + batch], surv[q0:q0 + batch], ws)
 
     def timed(steps, warmup):
-        """ms per step by the host clock around `steps` calls, and the stage times the
-        library's own events (on the launch stream) recorded inside those same calls."""
+        """ms per step by the host clock around `steps` passes over the query set, and the stage
+        times per icq_search call that the library's own events (on the launch stream) recorded
+        inside those same calls (the latest 64 calls)."""
         b.icq_index_set_stage_timing(index, False)
         for _ in range(warmup):
             step()
@@ -431,85 +541,131 @@ def main():
         ms = (time.perf_counter() - t0) * 1e3 / steps
         stage, calls, batches = b.icq_index_stage_times(index)
         b.icq_index_set_stage_timing(index, False)
-        assert batches == 1, "the workspace must hold the whole query set"
+        assert batches == 1, "the workspace must hold a whole query batch"
         return ms, stage, calls
 
     ms_per_step, stage, calls = timed(args.steps, args.warmup)
     surv_np = surv.cpu().numpy().view(np.uint32)
     overflow = int((surv_np > cap).sum())
-    n_surv = float(np.minimum(surv_np, cap).sum())
-    log("[bench] %.3f ms/step; stages (events, mean of %d steps): lut %.3f, stage 1 %.3f, stage 2 %.3f ms; "
+    n_surv_batch = float(np.minimum(surv_np, cap).sum()) / nbatches
+    log("[bench] %.3f ms/step (%d calls); per call (events, mean of %d calls): lut %.3f, stage 1 %.3f, stage 2 %.3f ms; "
         "survivors mean %.0f max %d, overflowed lists %d" %
-        (ms_per_step, calls, stage[0], stage[1], stage[2], surv_np.mean(), surv_np.max(), overflow))
+        (ms_per_step, nbatches, calls, stage[0], stage[1], stage[2], surv_np.mean(), surv_np.max(), overflow))
     gpu_ids = out_ids.cpu().numpy().view(np.uint32)
     gpu_dist = out_dist.cpu().numpy()
+    qmean = Q / nbatches                       # queries per call (the last batch may be short)
 
-    # Dominant kernel of the step: stage 1 over the items grouped by fast-code tuple, fused with
-    # the survivors' distances and the nearest-neighbour lists (group_keys_kernel<Kf,W,true>;
-    # the stage-1 event pair starts after the counter fill).  What the method itself must
-    # move per launch: per survivor its K code bytes, per query its K tables (4*K*256 bytes)
-    # and its result rows (8 bytes per entry).  Candidates never leave the chip.
-    alg_bytes = n_surv * K + 4.0 * Q * K * 256 + 8.0 * Q * topk
-    achieved = alg_bytes / (stage[1] * 1e-3) / 1e9
-    traffic = pmc_traffic("group_keys_kernel")
-    roofline = {"bound": "hbm", "kernel": "group_keys_kernel<%d,%d,true>" % (Kf, index_words(K)),
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": traffic["bytes"] if traffic else None, "traffic_detail": traffic,
-                "ms": round(stage[1], 4), "algorithmic_bytes": alg_bytes,
-                "note": "bytes per launch = survivors*K code bytes + Q*4*K*256 table bytes + Q*topk*8 result bytes; "
-                        "duration = stage-1 event pair inside the timed icq_search calls.  The algorithmic bytes are "
-                        "the method's (every survivor refined); the kernel skips the tuples that its list's bound "
-                        "excludes (crude distance + smallest possible remainder above the topk-th distance, same "
-                        "result), so it visits about a third of the survivors and 'traffic' is well below them.  It "
-                        "is bound by instruction issue (92 % of the vector issue slots), not by memory"}
+    form, bits = stage1_form(Kf, K, N, batch, topk)
+    kern1 = stage1_kernel_name(Kf, K, N, batch, topk)
+    npos = b.icq_index_scan_positions(index, batch)
+    wl = args.workload
+    if form == "tuples":
+        # Stage 1 over the items grouped by fast-code tuple, fused with the survivors' distances and
+        # the nearest-neighbour lists (one launch is the whole of stages 1 and 2).  It is bound by
+        # instruction issue (profiles/sq_counters_C1.txt); priced here by the bytes the method must
+        # move -- per survivor its K code bytes, per query its K tables and result rows -- next to
+        # the bytes the counters saw, which are fewer: the kernel skips tuples its list's bound excludes.
+        alg_bytes = n_surv_batch * K + 4.0 * qmean * K * 256 + 8.0 * qmean * topk
+        achieved = alg_bytes / (stage[1] * 1e-3) / 1e9
+        tr = pmc_traffic("group_keys_kernel", wl)
+        roofline = {"bound": "hbm", "kernel": kern1, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": alg_bytes,
+                    "traffic": tr["bytes"] if tr else None, "traffic_source": tr["source"] if tr else None,
+                    "ms": round(stage[1], 4),
+                    "note": "algorithmic bytes = survivors*K + Q*4*K*256 + Q*topk*8 per launch over the stage-1 event pair; "
+                            "the kernel itself is bound by instruction issue and moves fewer bytes than that (traffic)"}
+    else:
+        # Item-by-item stage 1: bound by the vector ALUs (every (query, position) pair costs a few
+        # plain vector instructions whatever the memory system does; SQ counters in profiles/).
+        m = stage1_model(Kf, npos, int(round(qmean)), form == "pairs")
+        t = stage[1] * 1e-3
+        ach = m["alu_ops"] / t / 1e12
+        tr = pmc_traffic(kern1.split("<")[0] + ("_pairs" if form == "pairs" else "_items"), wl)
+        roofline = {"bound": "alu", "kernel": kern1, "achieved": round(ach, 3), "peak": round(ALU_PEAK_TOPS, 2),
+                    "unit": "Tops/s", "frac": round(ach / ALU_PEAK_TOPS, 4), "ms": round(stage[1], 4),
+                    "work_model": m,
+                    "lds": {"achieved_Gaddr_s": round(m["lds_addresses"] / t / 1e9, 1), "peak_Gaddr_s": LDS_PEAK_GADDR,
+                            "frac": round(m["lds_addresses"] / t / 1e9 / LDS_PEAK_GADDR, 4),
+                            "table_entries_per_s": round(m["table_entries"] / t, 1)},
+                    "hbm": {"algorithmic_bytes": m["code_bytes"] + m["hit_bit_bytes"] + 4 * int(round(qmean)) * Kf * 256,
+                            "achieved_GBs": round((m["code_bytes"] + m["hit_bit_bytes"]) / t / 1e9, 1), "peak_GBs": HBM_PEAK_GBS,
+                            "frac": round((m["code_bytes"] + m["hit_bit_bytes"]) / t / 1e9 / HBM_PEAK_GBS, 4)},
+                    "traffic": tr["bytes"] if tr else None, "traffic_source": tr["source"] if tr else None,
+                    "note": "one launch per icq_search call; duration = the stage-1 event pair inside the timed calls "
+                            "(counter fill .. after the scan kernel).  achieved = plain vector operations of the work "
+                            "model (alu_ops: additions, comparison and hit-bit collection per (query, position), byte "
+                            "extraction and table address per position and pass) per second; peak = 256 CU x 4 SIMD x "
+                            "16 lanes x 2.4 GHz.  lds / hbm: the same launch against the other two resources "
+                            "(LDS: 16 addresses per clock and CU measured for any read width; HBM: code rows per "
+                            "pass plus the hit bits written)"}
 
     result = {
         "metric": "queries/sec at top-%d (oracle-matched)" % topk,
         "value": round(Q / (ms_per_step * 1e-3), 1), "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: d=%d K=%d Kf=%d m=256 N=%d Q=%d top-%d, ~%.0f%% survive stage 1" %
-                   (args.workload, d, K, Kf, N, Q, topk, 100 * SURVIVE_FRAC),
-                   "cap": cap, "overflowed_lists": overflow,
-                   "survivors_mean": round(float(surv_np.mean()), 1), "stage1": "grouped by fast-code tuple"},
-        "stages_ms": {"build_lut": round(stage[0], 4), "stage1_scan_distances_lists": round(stage[1], 4),
-                      "stage2_separate_kernels": round(stage[2], 4)},
+        "config": {"workload": "%s: d=%d K=%d Kf=%d m=256 N=%d Q=%d in batches of %d, top-%d, ~%.0f%% survive stage 1" %
+                   (args.workload, d, K, Kf, N, Q, batch, topk, 100 * SURVIVE_FRAC),
+                   "batch": batch, "calls_per_step": nbatches, "cap": cap, "overflowed_lists": overflow,
+                   "survivors_mean": round(float(surv_np.mean()), 1),
+                   "stage1": {"tuples": "one evaluation per fast-code tuple, distances and lists in the same kernel",
+                              "pairs": "items ordered by their first two fast sub-codes, remaining fast rows streamed",
+                              "items": "all fast rows streamed item by item"}[form],
+                   "stage1_to_stage2": "hit bits" if bits else ("on chip" if form == "tuples" else "candidate lists")},
+        "stages_ms_per_call": {"build_lut": round(stage[0], 4), "stage1": round(stage[1], 4), "stage2": round(stage[2], 4)},
         "roofline": roofline,
     }
+    if form != "tuples":
+        # stage 2: record gathers; what the method must move per call is one 16-byte record per
+        # survivor, the hit bits once more, the tables and the result rows
+        rec = index_words(K) * 4
+        alg2 = n_surv_batch * rec + (npos * qmean / 8 if bits else 4 * n_surv_batch) + 4.0 * qmean * K * 256 + 8.0 * qmean * topk
+        ach2 = alg2 / (stage[2] * 1e-3) / 1e9
+        k2 = "refine_mask_kernel<%d,true>" % index_words(K) if bits else "refine_dist_kernel<%d>" % index_words(K)
+        tr2 = pmc_traffic(k2.split("<")[0], wl)
+        result["roofline_stage2"] = {
+            "bound": "hbm", "kernel": k2 + " (+ its unfiltered first part and two selections)" if bits else k2 + " + select_keys_kernel",
+            "achieved": round(ach2, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach2 / HBM_PEAK_GBS, 4),
+            "algorithmic_bytes": alg2, "traffic": tr2["bytes"] if tr2 else None, "traffic_source": tr2["source"] if tr2 else None,
+            "ms": round(stage[2], 4), "survivors_per_call": n_surv_batch,
+            "note": "all stage-2 kernels of a call (event pair after stage 1 .. results written); algorithmic bytes = "
+                    "survivors x record + hit bits (or ids) + tables + result rows.  A random 16-byte gather moves a "
+                    "whole cache line, so the traffic is a multiple of the algorithmic bytes unless the line is "
+                    "reused from the cache by the batch's other queries"}
 
-    if not args.no_streamed_leg and index.Kf <= 2:
-        # The same step with stage 1 walking the fast sub-codes item by item, four queries per
-        # pass (what an index without the grouping, or with N below 256^Kf, runs): bound by LDS
-        # table reads.
+    if not args.no_streamed_leg:
+        # The same step with stage 1 walking all Kf fast rows item by item (what an index without the
+        # grouped layouts runs)
         b.icq_index_set_scan_mode(index, b.ICQ_SCAN_STREAMED)
-        ws2 = torch.empty(b.icq_workspace_bytes(index, Q, cap, topk), dtype=torch.uint8, device="cuda")
+        ws2 = torch.empty(b.icq_workspace_bytes(index, batch, cap, topk), dtype=torch.uint8, device="cuda")
         ws_keep, ws = ws, ws2
-        ms_s, stage_s, _ = timed(max(3, args.steps // 4), 1)
-        same = bool((out_ids.cpu().numpy().view(np.uint32) == gpu_ids).all())
+        ms_s, stage_s, _ = timed(max(2, args.steps // 4), 1)
+        same = bool((out_ids.cpu().numpy().view(np.uint32) == gpu_ids).all() and (out_dist.cpu().numpy() == gpu_dist).all())
         ws = ws_keep
         del ws2
         b.icq_index_set_scan_mode(index, b.ICQ_SCAN_AUTO)
-        lds_bytes = 4.0 * Kf * N * Q                 # one 4-byte table read per (query, item, fast codebook)
-        ach = lds_bytes / (stage_s[1] * 1e-3) / 1e9
-        result["roofline_streamed"] = {
-            "bound": "lds", "kernel": "scan_stream_kernel<%d,4,false>" % Kf, "achieved": round(ach, 1),
-            "peak": round(LDS_PEAK_GBS, 1), "unit": "GB/s", "frac": round(ach / LDS_PEAK_GBS, 4), "traffic": None,
-            "ms": round(stage_s[1], 4), "ms_per_step": round(ms_s, 4),
-            "queries_per_s": round(Q / (ms_s * 1e-3), 1),
-            "same_ids_as_grouped": same,
-            "stages_ms": {"build_lut": round(stage_s[0], 4), "stage1": round(stage_s[1], 4),
-                          "stage2": round(stage_s[2], 4)},
-            "note": "item-by-item stage 1: algorithmic LDS gather bytes 4*Kf*N*Q over the stage-1 event pair (the scan "
-                    "kernel); peak = 256 CU x 128 B/clk x 2.4 GHz; the LDS takes 16 addresses per "
-                    "clock and CU, so the kernel reads the entries of 4 queries with one 128-bit access; code bytes "
-                    "read are Kf*N*ceil(Q/4), from the last-level cache at this N"}
-        log("[bench] streamed stage 1: %.3f ms/step (stage 1 %.3f ms), same ids as grouped: %s" %
+        if Kf <= 4:
+            m = stage1_model(Kf, N, int(round(qmean)), False)
+            t = stage_s[1] * 1e-3
+            ach = m["alu_ops"] / t / 1e12
+            result["roofline_streamed"] = {
+                "bound": "alu", "kernel": stage1_kernel_name(Kf, K, N, batch, topk, True), "achieved": round(ach, 3),
+                "peak": round(ALU_PEAK_TOPS, 2), "unit": "Tops/s", "frac": round(ach / ALU_PEAK_TOPS, 4),
+                "ms": round(stage_s[1], 4), "ms_per_step": round(ms_s, 4), "queries_per_s": round(Q / (ms_s * 1e-3), 1),
+                "same_lists_as_default": same, "work_model": m,
+                "lds": {"achieved_Gaddr_s": round(m["lds_addresses"] / t / 1e9, 1), "peak_Gaddr_s": LDS_PEAK_GADDR,
+                        "frac": round(m["lds_addresses"] / t / 1e9 / LDS_PEAK_GADDR, 4),
+                        "table_entries_per_s": round(m["table_entries"] / t, 1)},
+                "stages_ms_per_call": {"build_lut": round(stage_s[0], 4), "stage1": round(stage_s[1], 4),
+                                       "stage2": round(stage_s[2], 4)},
+                "traffic": None}
+        log("[bench] all fast rows item by item: %.3f ms/step (stage 1 %.3f ms per call), same lists: %s" %
             (ms_s, stage_s[1], same))
 
     if not args.no_policy_leg:
         log("[bench] threshold policy of the paper: sampled thresholds with margin, search, operation counts")
-        result["threshold_policy"] = policy_leg(torch, b, cfg, index, queries, (cap, out_ids, out_dist, surv, ws),
+        result["threshold_policy"] = policy_leg(torch, b, cfg, index, queries[:batch].contiguous(),
+                                                (cap, out_ids, out_dist, surv, ws),
                                                 max(3, args.steps // 2), not args.no_cpu_baseline)
         p = result["threshold_policy"]
         log("[bench] policy: thresholds %.3f ms, tables + policy + search %.3f ms, %.2f %% survive, ops ratio %.4f"
@@ -521,10 +677,10 @@ def main():
         log("[bench] encode: %.3f ms for %d items, %.1f TFLOP/s" %
             (result["encode"]["ms"], result["encode"]["N"], result["encode"]["achieved"]))
 
+    del ws, index, cb, codes, queries
+    torch.cuda.empty_cache()
     if not args.no_hbm_leg:
-        del ws
-        torch.cuda.empty_cache()
-        log("[bench] stage-1 scan on the 400 MB fast-code array, one query")
+        log("[bench] stage-1 scan on the 400 MB fast-code array, one, two and four queries per pass")
         result["roofline_stage1_hbm"] = hbm_leg(torch, b, max(5, args.steps), args.warmup)
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle")
@@ -532,15 +688,9 @@ def main():
         result["cpu_baseline"] = base
         result["oracle_matched"] = match
     if not args.no_configs_leg:
-        del index, cb, codes, queries
-        torch.cuda.empty_cache()
         log("[bench] the other workload shapes, each against the oracle")
         result["configs"] = configs_leg(torch, b, synth, args.workload, not args.no_cpu_baseline)
     print(json.dumps(result), flush=True)
-
-
-def index_words(K):
-    return 1 if K <= 4 else 2 if K <= 8 else 4
 
 
 if __name__ == "__main__":

@@ -13,12 +13,14 @@
  *    except that an index keeps private device copies it allocates itself.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Every call only enqueues work on `stream` and returns; results are valid
- *    once the stream has been synchronised.  Calls on one index from several
+ *    once the stream has been synchronised (icq_index_create also waits for
+ *    its own counting pass before it sizes the grouped layouts).  Calls on one index from several
  *    host threads are safe as long as they do not share output or workspace
  *    buffers.
  *  - Return value: ICQ_OK (0) or a negative ICQ_ERR_* code.  Arguments are
- *    checked on the host before anything is launched; on error nothing has
- *    been enqueued.
+ *    checked on the host before anything is launched; an argument or
+ *    workspace error means nothing has been enqueued (ICQ_ERR_HIP can come from
+ *    a launch in the middle of a call).
  *  - Layouts are row-major with the last index contiguous.
  *  - Candidate lists: cand_ids / cand_partial are [Q][cap]; list q holds
  *    min(cand_count[q], cap) valid entries in UNSPECIFIED order (compare as
@@ -87,24 +89,40 @@ void icq_index_destroy(icq_index *index);
 /* Write the index's private copy of the codes back in the input layout
  * [K][N] (bit-exact round trip of the storage layout; a debugging aid).
  * from_items == 0: fast rows from the stage-1 array, slow rows from the item
- * records; 1: every row from the item records; 2: every row from the grouped
- * item records through the position -> id map (ICQ_ERR_ARG if the index is not
- * grouped, i.e. Kf > 2 or N == 0). */
+ * records; 1: every row from the item records; 2: from the grouped layout alone
+ * through its position -> id map (Kf <= 2: the grouped item records; Kf = 3, 4:
+ * rows 0, 1 from the pair each group of 16 positions is labelled with, the other
+ * fast rows from the streamed rows, the rest from the grouped records);
+ * ICQ_ERR_ARG if the index has no grouped layout (Kf > 4 or N == 0). */
 int icq_index_export_codes(const icq_index *index, int from_items, uint8_t *codes_out, void *stream);
 
 /*
- * Stage-1 strategy for calls with more than 4 queries on an index with Kf <= 2.
- * An item's crude distance (Eq. 2) depends only on its Kf fast sub-codes, so when
- * N is much larger than 256^Kf the index also keeps the items grouped by that
- * tuple and stage 1 evaluates each tuple once per query instead of each item
- * (identical values and survivors).  ICQ_SCAN_AUTO picks the grouped form when
- * it is available and cheaper, ICQ_SCAN_STREAMED always walks the fast
- * sub-codes, ICQ_SCAN_GROUPED uses the grouped form whenever the index has it.
+ * Stage-1 strategy.  An item's crude distance (Eq. 2) depends only on its Kf fast
+ * sub-codes.  Kf <= 2: when N is much larger than 256^Kf the index also keeps the
+ * items grouped by that tuple, and for calls with more than 4 queries stage 1
+ * evaluates each tuple once per query instead of each item.  Kf = 3, 4: the index
+ * also keeps the items ordered by their first two fast sub-codes (every pair's run
+ * padded to 16 positions); stage 1 then forms the pair's table sum once per 16
+ * positions and streams only the remaining fast rows.  Values, survivors and
+ * results are identical in every form (same additions in the same order).
+ * ICQ_SCAN_AUTO picks a grouped form when it is available and cheaper (Kf = 3, 4:
+ * from 64 * 65536 items on), ICQ_SCAN_STREAMED always walks all Kf fast rows item
+ * by item, ICQ_SCAN_GROUPED uses the grouped form whenever the index has it.
  */
 #define ICQ_SCAN_AUTO 0
 #define ICQ_SCAN_STREAMED 1
 #define ICQ_SCAN_GROUPED 2
 int icq_index_set_scan_mode(icq_index *index, int mode);
+
+/*
+ * Number of positions stage 1 walks per pass over the index in its current scan
+ * mode (host call; a measurement aid for work and traffic models): N for the
+ * item-by-item scan; the 65536 runs' padded total, rounded up to whole block
+ * steps, when the items grouped by their first two fast sub-codes are walked
+ * (Kf = 3, 4); 256^Kf (one evaluation per tuple) for the grouped form of
+ * Kf <= 2 with more than 4 queries.  *out is a host pointer.
+ */
+int icq_index_scan_positions(const icq_index *index, int Q, int64_t *out /*host*/);
 
 /*
  * Stage timing, a measurement aid for icq_search (for profiling only: it adds
@@ -165,7 +183,8 @@ int icq_scan_fast(const icq_index *index, const float *lut, int Q, const float *
  * nearest-neighbour list (Sec. 3.4):
  *   D[q][i] = cand_partial + sum_{k=Kf..K-1} lut[q][k][code_k(i)]   (k ascending, fp32)
  * then the topk smallest (D, id) per query.  Reads min(cand_count[q], cap)
- * entries of each list.  With cand_partial == NULL the same D is formed as the
+ * entries of each list; every listed id must be below N (ids are not checked:
+ * a larger one reads outside the index's item records).  With cand_partial == NULL the same D is formed as the
  * whole K-term sum (same order of additions, identical bits).
  * 1 <= topk <= ICQ_MAX_TOPK.
  */
@@ -180,9 +199,13 @@ int icq_refine(const icq_index *index, const float *lut, int Q, const uint32_t *
  * per-query candidate capacity carved out of the workspace (needs
  * icq_workspace_bytes(index, Q, cap, topk)).  out_survivors [Q] (may be NULL)
  * receives the true survivor count of each query; a value above cap means
- * that query's list overflowed and its result may miss neighbours (when the
- * grouped stage 1 runs, records are at most 16 bytes and topk <= 256, the
- * candidates never leave the chip and the result is complete whatever cap is).
+ * that query's list overflowed and its result may miss neighbours.  (Two forms
+ * keep no candidate lists and are complete for far more survivors than cap:
+ * the grouped stage 1 of Kf <= 2 with records of at most 16 bytes and
+ * topk <= 256, where the candidates never leave the chip; and, from 2^22 items
+ * on with K <= 16 and topk <= 512, the item-by-item stage 1, which hands stage 2
+ * one hit bit per item and query and keeps only the keys that can still reach
+ * the result.)  Calls with more than 32768 queries are worked off in slices.
  */
 int icq_search(const icq_index *index, const float *queries, int Q, const float *thresholds,
                int64_t cap, int topk, uint32_t *out_ids, float *out_dist, uint32_t *out_survivors,

@@ -26,6 +26,7 @@ SIGNATURES = {
     "icq_index_destroy": (None, [_vp]),
     "icq_index_export_codes": (_i, [_vp, _i, _vp, _vp]),
     "icq_index_set_scan_mode": (_i, [_vp, _i]),
+    "icq_index_scan_positions": (_i, [_vp, _i, ctypes.POINTER(_i64)]),
     "icq_index_set_stage_timing": (_i, [_vp, _i]),
     "icq_index_stage_times": (_i, [_vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(_i), ctypes.POINTER(_i)]),
     "icq_workspace_bytes": (_i, [_vp, _i, _i64, _i, ctypes.POINTER(_sz)]),
@@ -133,6 +134,12 @@ ICQ_SCAN_AUTO, ICQ_SCAN_STREAMED, ICQ_SCAN_GROUPED = 0, 1, 2
 
 def icq_index_set_scan_mode(index, mode):
     _check(load().icq_index_set_scan_mode(index.handle, int(mode)), "icq_index_set_scan_mode")
+
+
+def icq_index_scan_positions(index, Q):
+    out = _i64(0)
+    _check(load().icq_index_scan_positions(index.handle, int(Q), ctypes.byref(out)), "icq_index_scan_positions")
+    return int(out.value)
 
 
 def icq_index_set_stage_timing(index, enable):

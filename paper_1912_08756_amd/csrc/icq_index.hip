@@ -195,6 +195,14 @@ ICQ_EXPORT int icq_index_export_codes(const icq_index *ix, int from_items, uint8
     return icq_check_launch();
 }
 
+ICQ_EXPORT int icq_index_scan_positions(const icq_index *ix, int Q, int64_t *out) {
+    if (!ix || !out || Q < 0) return ICQ_ERR_ARG;
+    if (icq_group_usable(ix, Q)) *out = ix->groups;
+    else if (icq_g2_usable(ix) && ix->Kf <= 4) *out = ix->g2_npos;
+    else *out = ix->N;
+    return ICQ_OK;
+}
+
 static void timer_free(icq_stage_timer *t, int created) {
     for (int i = 0; i < created; ++i) (void)hipEventDestroy(t->ev[i / 4][i % 4]);
     delete t;

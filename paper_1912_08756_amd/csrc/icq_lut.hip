@@ -128,14 +128,19 @@ int icq_launch_build_lut(const icq_index *ix, const float *queries, int Q, float
     const int ncols = ix->K * ICQ_LUT_W;
     // two column blocks per wavefront: 5 % faster than one at C1 and C2; four are slower at d = 960 and for few queries
     constexpr int NB = 2;
-    dim3 grid((unsigned)(ncols / (NB * BN)), (unsigned)((Q + BM - 1) / BM));   // ncols = K * 256
-    build_lut_kernel<NB><<<grid, 256, 0, s>>>(queries, Q, ix->d, ix->cb, ix->d_pad, ix->cnorm, ncols,
-                                                  lut);
+    // query blocks along grid.y, at most 65535 per launch
+    constexpr int SLICE = 65535 * BM;
+    for (int q0 = 0; q0 < Q; q0 += SLICE) {
+        const int nq = Q - q0 < SLICE ? Q - q0 : SLICE;
+        dim3 grid((unsigned)(ncols / (NB * BN)), (unsigned)((nq + BM - 1) / BM));   // ncols = K * 256
+        build_lut_kernel<NB><<<grid, 256, 0, s>>>(queries + (int64_t)q0 * ix->d, nq, ix->d, ix->cb, ix->d_pad,
+                                                      ix->cnorm, ncols, lut + (int64_t)q0 * ncols);
+    }
     return icq_check_launch();
 }
 
 ICQ_EXPORT int icq_build_lut(const icq_index *ix, const float *queries, int Q, float *lut,
                              void *stream) {
-    if (!ix || Q < 0 || (Q > 0 && (!queries || !lut))) return ICQ_ERR_ARG;
+    if (!ix || Q < 0 || Q > ICQ_MAX_Q || (Q > 0 && (!queries || !lut))) return ICQ_ERR_ARG;
     return icq_launch_build_lut(ix, queries, Q, lut, (hipStream_t)stream);
 }

@@ -789,7 +789,7 @@ ICQ_EXPORT int icq_refine(const icq_index *ix, const float *lut, int Q, const ui
                           const float *cand_part, const uint32_t *cand_count, int64_t cap, int topk,
                           uint32_t *out_ids, float *out_dist, void *workspace,
                           size_t workspace_bytes, void *stream) {
-    if (!ix || Q < 0 || Q > (1 << 22) || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK)
+    if (!ix || Q < 0 || Q > ICQ_MAX_Q || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK)
         return ICQ_ERR_ARG;
     if (Q == 0) return ICQ_OK;
     if (!lut || !cand_ids || !cand_count || !out_ids || !out_dist) return ICQ_ERR_ARG;

@@ -657,7 +657,7 @@ int icq_launch_scan_masks(const icq_index *ix, const float *lut, int Q, const fl
 ICQ_EXPORT int icq_scan_fast(const icq_index *ix, const float *lut, int Q, const float *thresholds,
                              uint32_t *cand_ids, float *cand_part, uint32_t *cand_count,
                              int64_t cap, void *workspace, size_t workspace_bytes, void *stream) {
-    if (!ix || Q < 0 || Q > (1 << 22) || cap < 1) return ICQ_ERR_ARG;
+    if (!ix || Q < 0 || Q > ICQ_MAX_Q || cap < 1) return ICQ_ERR_ARG;
     if (Q == 0) return ICQ_OK;
     if (!lut || !thresholds || !cand_ids || !cand_count) return ICQ_ERR_ARG;
     if ((double)Q * (double)cap >= 1099511627776.0) return ICQ_ERR_ARG;

@@ -72,6 +72,7 @@ def test_host_side_argument_checks_of_the_policy_encoding_and_utility_calls():
     one = ctypes.c_void_p(1)
     out = ctypes.c_size_t(0)
     assert lib.icq_index_set_scan_mode(None, 0) == E
+    assert lib.icq_index_scan_positions(None, 1, None) == E
     assert lib.icq_index_set_stage_timing(None, 1) == E
     assert lib.icq_index_stage_times(None, None, None, None) == E
     assert lib.icq_index_export_codes(None, 0, one, None) == E
