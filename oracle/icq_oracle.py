@@ -30,6 +30,19 @@ def build(force=False):
     return _LIB
 
 
+def build_sanitize_check(sanitize, out_dir=None):
+    """Compile oracle/sanitize_check.c -- the oracle plus a driver that calls every function on
+    small awkward inputs and prints the results -- plainly or with the address and
+    undefined-behaviour sanitizers (host code only).  Returns the executable's path."""
+    out_dir = out_dir or _HERE
+    exe = os.path.join(out_dir, "sanitize_check_san" if sanitize else "sanitize_check_plain")
+    flags = (["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"]
+             if sanitize else ["-O2"])
+    subprocess.check_call(["gcc", "-std=c11", "-fopenmp", "-Wall", "-Wextra"] + flags +
+                          ["-o", exe, os.path.join(_HERE, "sanitize_check.c"), "-lm"])
+    return exe
+
+
 def _load():
     global _lib
     if _lib is None:

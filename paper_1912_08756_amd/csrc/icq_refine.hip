@@ -550,7 +550,7 @@ constexpr int RM_SEED_EVERY = 33;                     // odd: the first launch's
 static_assert(RM_LIST % (64 * RM_PER) == 0, "a round of the list is whole steps of gathers");
 
 template <int WORDS, bool FILTER>
-__global__ __launch_bounds__(RM_THREADS) __attribute__((amdgpu_waves_per_eu(5, 8))) void refine_mask_kernel(
+__global__ __launch_bounds__(RM_THREADS) __attribute__((amdgpu_waves_per_eu(8, 8))) void refine_mask_kernel(
     const uint8_t *__restrict__ items, int K, const float *__restrict__ lut, const uint32_t *__restrict__ masks,
     size_t mask_words, const uint32_t *__restrict__ perm, uint32_t nsel, uint32_t seed_every, int window, int Q,
     const float *__restrict__ kth_dist, int topk, u64 *__restrict__ keys, uint32_t *__restrict__ key_count,

@@ -106,8 +106,9 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     size_t mask_stride, uint32_t scan_end) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     __shared__ uint32_t s_wcnt[B][SS_WAVES], s_base[B];
+    __shared__ float s_tmin[KF][B][4];                // G2: smallest entry of each streamed table, per wavefront of entries
     constexpr int C = ss_copies(KF, B);
-    constexpr int SS_HALF = ss_half(B);
+    constexpr int SS_HALF = G2 && B == 4 ? 4 : ss_half(B);
     constexpr int TAB_FLOATS = KF * ICQ_LUT_W * C * B;
     constexpr int T01_FLOATS = G2 ? 2 * ICQ_LUT_W * B : 0;
     constexpr int K0 = G2 ? 2 : 0;                    // codebook of the first streamed row
@@ -120,6 +121,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     // Consecutive threads write consecutive 16-byte pieces (conflict-free; writing an entry's C
     // copies from one thread instead puts 16 lanes on the same banks and took 7 us per block);
     // a piece holds 4 / B copies of the entry's B values.  All loads go out before the writes.
+    float tmin[KF][B];
     auto fill_tables = [&]() {
         constexpr int NV = TAB_FLOATS / 4 / SS_THREADS;              // 16-byte pieces per thread
         static_assert(TAB_FLOATS % (4 * SS_THREADS) == 0 && C % 4 == 0, "whole pieces, inside one entry");
@@ -160,6 +162,26 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
             reinterpret_cast<float4 *>(smem + TAB_FLOATS)[tid] = v;
         }
         __syncthreads();
+        if (G2) {
+            // smallest entry of every streamed table (from its first copy): what the streamed rows add at least
+            if (tid < ICQ_LUT_W) {
+#pragma unroll
+                for (int k = 0; k < KF; ++k) {
+#pragma unroll
+                    for (int b = 0; b < B; ++b) {
+                        const float m = wave_min_f32(smem[((k * ICQ_LUT_W + tid) * C) * B + b]);
+                        if (lane == 0) s_tmin[k][b][tid >> 6] = m;
+                    }
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < KF; ++k) {
+#pragma unroll
+                for (int b = 0; b < B; ++b)
+                    tmin[k][b] = fminf(fminf(s_tmin[k][b][0], s_tmin[k][b][1]), fminf(s_tmin[k][b][2], s_tmin[k][b][3]));
+            }
+        }
     };
     float t[B];
 #pragma unroll
@@ -237,6 +259,26 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
                 p01[3 % B] = a.w + c.w;
             }
         }
+        // G2: a query none of whose 64 x 16 positions can be a hit is left out of this step.  Every
+        // position's sum is its pair's sum plus one entry of each streamed table, added in this order;
+        // rounding is monotone, so the same additions with the tables' smallest entries bound it from below
+        // exactly -- a lane whose bound is not below the threshold has no hit.  (A pair's run is some
+        // 1500 positions at N = 1e8, so the wavefront's 1024 positions belong to one or two pairs, and for
+        // most queries most pairs are out of reach.)
+        bool live[B];
+        bool any_live = !G2;
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            live[b] = true;
+            if (G2) {
+                float lb = p01[b] + tmin[0][b];
+#pragma unroll
+                for (int k = 1; k < KF; ++k) lb += tmin[k][b];
+                live[b] = __builtin_amdgcn_ballot_w64(lb < t[b]) != 0;      // wavefront-uniform
+                any_live |= live[b];
+            }
+        }
+        if (!any_live) return;
 #pragma unroll
         for (int h = 0; h < 16; h += SS_HALF) {
             // phase 1: every table address of the half step
@@ -281,9 +323,10 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
             __builtin_amdgcn_sched_barrier(0);
             // phase 3: sums (k ascending) and hit bits
 #pragma unroll
-            for (int jj = 0; jj < SS_HALF; ++jj) {
+            for (int b = 0; b < B; ++b) {
+                if (G2 && !live[b]) continue;             // wavefront-uniform; hm[b] stays zero for the whole step
 #pragma unroll
-                for (int b = 0; b < B; ++b) {
+                for (int jj = 0; jj < SS_HALF; ++jj) {
                     float P = G2 ? p01[b] + v[jj][0][b] : v[jj][0][b];
 #pragma unroll
                     for (int k = 1; k < KF; ++k) P += v[jj][k][b];
