@@ -419,6 +419,34 @@ def configs_leg(torch, b, synth, skip, with_cpu, target_s=4.0):
     return out
 
 
+def machine_limits(torch, b):
+    """What this GPU delivers for the access patterns the kernels are made of (icq_machine_probe):
+    the figures behind the peaks the rooflines use."""
+    buf = torch.zeros(400_000_000, dtype=torch.uint8, device="cuda")
+    out = {}
+    for name, kind, reps in (("stream_read_400MB", b.ICQ_PROBE_READ, 20), ("stream_read_400MB_nontemporal", b.ICQ_PROBE_READ_NT, 20),
+                             ("lds_read_b32", b.ICQ_PROBE_LDS_B32, 3), ("lds_read_b64", b.ICQ_PROBE_LDS_B64, 3),
+                             ("lds_read_b128", b.ICQ_PROBE_LDS_B128, 3), ("valu_add_f32", b.ICQ_PROBE_VALU, 3),
+                             ("atomic_add_one_word", b.ICQ_PROBE_ATOMIC, 5)):
+        ms, units = b.icq_machine_probe(kind, buf, reps)
+        rate = units / (ms * 1e-3)
+        e = {"ms": round(ms, 4)}
+        if "stream" in name:
+            e.update(GBs=round(rate / 1e9, 1), frac_of_8TBs=round(rate / 8e12, 4))
+        elif "lds" in name:
+            width = {"b32": 4, "b64": 8, "b128": 16}[name.split("_")[-1]]
+            e.update(Gaddr_s=round(rate / 1e9, 1), addr_per_clk_per_cu_at_2p4GHz=round(rate / 256 / 2.4e9, 2),
+                     bytes_per_clk_per_cu_at_2p4GHz=round(rate * width / 256 / 2.4e9, 1))
+        elif "valu" in name:
+            e.update(Tops_s=round(rate / 1e12, 2), lanes_per_clk_per_cu_at_2p4GHz=round(rate / 256 / 2.4e9, 1))
+        else:
+            e.update(Matomics_s=round(rate / 1e6, 1))
+        out[name] = e
+    del buf
+    torch.cuda.empty_cache()
+    return out
+
+
 def index_words(K):
     return 1 if K <= 4 else 2 if K <= 8 else 4
 
@@ -480,6 +508,8 @@ def main():
     ap.add_argument("--no-policy-leg", action="store_true")
     ap.add_argument("--no-encode-leg", action="store_true")
     ap.add_argument("--no-configs-leg", action="store_true")
+    ap.add_argument("--machine-limits-only", action="store_true",
+                    help="print only the machine-limit probes (one JSON line) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB): the scale for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
@@ -492,6 +522,10 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     b.load()
+
+    if args.machine_limits_only:
+        print(json.dumps({"machine_limits": machine_limits(torch, b)}), flush=True)
+        return
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
@@ -679,6 +713,7 @@ def main():
 
     del ws, index, cb, codes, queries
     torch.cuda.empty_cache()
+    result["machine_limits"] = machine_limits(torch, b)
     if not args.no_hbm_leg:
         log("[bench] stage-1 scan on the 400 MB fast-code array, one, two and four queries per pass")
         result["roofline_stage1_hbm"] = hbm_leg(torch, b, max(5, args.steps), args.warmup)

@@ -310,6 +310,26 @@ int icq_subspace_mask(const double *lambda, int d, double pi1, double sigma1, do
 int icq_fast_set(const icq_index *index, const uint8_t *xi, uint8_t *fast_out, void *stream);
 int icq_margin(const double *lambda, const uint8_t *xi, int d, double *sigma_out, void *stream);
 
+/*
+ * Machine-limit probe, a measurement aid (nothing on the search path uses it): runs one of a few
+ * plain kernels `reps` times on `stream`, WAITS for them, and reports the mean launch time in
+ * milliseconds (*ms_out, host) and the work one launch did (*units_out, host): bytes read
+ * (ICQ_PROBE_READ: 128-bit loads over `buffer`, one block per CU; ICQ_PROBE_READ_NT: the same with
+ * the non-temporal hint), lane reads of a conflict-free 128 KB LDS table in 4-, 8- or 16-byte
+ * accesses (ICQ_PROBE_LDS_B32/B64/B128), plain single-precision vector additions
+ * (ICQ_PROBE_VALU), or atomic additions on one word (ICQ_PROBE_ATOMIC).  buffer: device memory
+ * of `bytes` >= 4 MiB, 16-byte aligned; every kind may overwrite its first 4 MiB.
+ */
+#define ICQ_PROBE_READ 0
+#define ICQ_PROBE_READ_NT 1
+#define ICQ_PROBE_LDS_B32 2
+#define ICQ_PROBE_LDS_B64 3
+#define ICQ_PROBE_LDS_B128 4
+#define ICQ_PROBE_VALU 5
+#define ICQ_PROBE_ATOMIC 6
+int icq_machine_probe(int kind, void *buffer, size_t bytes, int reps, double *ms_out /*host*/,
+                      double *units_out /*host*/, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -44,6 +44,7 @@ SIGNATURES = {
     "icq_subspace_mask": (_i, [_vp, _i] + [ctypes.c_double] * 6 + [_vp, _vp]),
     "icq_fast_set": (_i, [_vp, _vp, _vp, _vp]),
     "icq_margin": (_i, [_vp, _vp, _i, _vp, _vp]),
+    "icq_machine_probe": (_i, [_i, _vp, _sz, _i, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), _vp]),
 }
 _lib = None
 
@@ -275,3 +276,15 @@ def icq_margin(lam, xi, sigma_out):
     d = lam.shape[0]
     _check(load().icq_margin(_dev(lam, torch.float64, (d,)), _dev(xi, torch.uint8, (d,)), d,
                              _dev(sigma_out, torch.float64, (1,)), _stream()), "icq_margin")
+
+
+ICQ_PROBE_READ, ICQ_PROBE_READ_NT, ICQ_PROBE_LDS_B32, ICQ_PROBE_LDS_B64, ICQ_PROBE_LDS_B128, ICQ_PROBE_VALU, \
+    ICQ_PROBE_ATOMIC = range(7)
+
+
+def icq_machine_probe(kind, buffer, reps):
+    """(ms per launch, work units per launch) of one probe kernel; buffer: uint8 device tensor >= 4 MiB."""
+    ms, units = ctypes.c_double(0), ctypes.c_double(0)
+    _check(load().icq_machine_probe(int(kind), _dev(buffer, torch.uint8, name="buffer"), buffer.numel(), int(reps),
+                                    ctypes.byref(ms), ctypes.byref(units), _stream()), "icq_machine_probe")
+    return float(ms.value), float(units.value)

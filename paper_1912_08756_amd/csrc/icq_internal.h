@@ -78,6 +78,9 @@ enum icq_list_kind {
 
 // hm = 2 * hm + (P < t): the comparison's carry shifted in with one add (the compiler's own
 // form is a select and an or per item).  After n calls the first comparison sits in bit n - 1, the last in bit 0.
+// (Tried: the sign of P - t funnel-shifted in -- v_sub_f32 + v_alignbit_b32 issue in 6.3 clocks per item
+// against 10.2 for this pair in isolation -- and the table address as shift + v_and_or_b32; both exact,
+// neither shortened the scans, which wait on the LDS and on each other's phases rather than on issue slots.)
 __device__ __forceinline__ void icq_hit_shift_in(uint32_t &hm, float P, float t) {
     // the two wait states are the ones the compiler itself puts between a vector instruction that
     // writes VCC and one that reads it (it does not look inside an asm statement)

@@ -106,7 +106,7 @@ __global__ __launch_bounds__(SS_THREADS) void scan_stream_kernel(
     size_t mask_stride, uint32_t scan_end) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     __shared__ uint32_t s_wcnt[B][SS_WAVES], s_base[B];
-    __shared__ float s_tmin[KF][B][4];                // G2: smallest entry of each streamed table, per wavefront of entries
+    __shared__ float s_tmin[G2 ? KF : 1][G2 ? B : 1][4];   // G2: smallest entry of each streamed table, per wavefront of entries
     constexpr int C = ss_copies(KF, B);
     constexpr int SS_HALF = G2 && B == 4 ? 4 : ss_half(B);
     constexpr int TAB_FLOATS = KF * ICQ_LUT_W * C * B;
@@ -469,9 +469,9 @@ int launch_stream_as(const icq_index *ix, const float *lut, int Q, const float *
     const int threads = SS_THREADS;
     // ids one wavefront stages per query: 512 (32 KB per query) when the tables leave that much LDS
     uint32_t wave_cap = 512;
-    while (tab + sizeof(uint32_t) * B * SS_WAVES * wave_cap > 163840 - 512) wave_cap -= 8;   // 512: the static arrays
+    while (tab + sizeof(uint32_t) * B * SS_WAVES * wave_cap > 163840 - 1024) wave_cap -= 8;   // 1024: the static arrays
     const size_t lds = MASK ? tab : tab + sizeof(uint32_t) * B * SS_WAVES * wave_cap;
-    ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&scan_stream_kernel<KF, B, NT, G2, MASK>), 163840 - 512));
+    ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&scan_stream_kernel<KF, B, NT, G2, MASK>), 163840 - 1024));
     const int groups = (Q + B - 1) / B;
     const uint32_t step = (uint32_t)(threads / 64) * 1024u;
     const int64_t nitems = G2 ? ix->g2_npos : ix->N;          // scan positions that can hold an item

@@ -73,6 +73,8 @@ def test_host_side_argument_checks_of_the_policy_encoding_and_utility_calls():
     out = ctypes.c_size_t(0)
     assert lib.icq_index_set_scan_mode(None, 0) == E
     assert lib.icq_index_scan_positions(None, 1, None) == E
+    assert lib.icq_machine_probe(0, None, 1 << 22, 1, None, None, None) == E
+    assert lib.icq_machine_probe(99, one, 1 << 22, 1, None, None, None) == E
     assert lib.icq_index_set_stage_timing(None, 1) == E
     assert lib.icq_index_stage_times(None, None, None, None) == E
     assert lib.icq_index_export_codes(None, 0, one, None) == E
