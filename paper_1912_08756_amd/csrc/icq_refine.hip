@@ -535,7 +535,7 @@ __global__ __launch_bounds__(SK_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8
 // bits (one 128-bit load per lane, two chunks ahead), a prefix of their popcounts, the set bits
 // expanded into a position list in the wavefront's part of LDS, then per position the record
 // gather, the K table reads and the key, as in refine_dist_kernel.
-// Every 33rd chunk is done in a first launch, unfiltered (!FILTER); the select kernel's topk-th
+// Every 65th chunk is done in a first launch, unfiltered (!FILTER); the select kernel's topk-th
 // distance of those keys then bounds what the other chunks add in a second launch (FILTER: keys
 // above it are dropped; ties at it are kept, the final select decides).  The final lists are
 // unchanged -- at least topk keys at or below the bound are already there -- and the key lists
@@ -546,26 +546,31 @@ constexpr uint32_t RM_CHUNK = 32768;                  // positions per chunk; a 
 constexpr int RM_WORDS = RM_CHUNK / 32 / 64;          // 32-bit words of hit bits per lane and chunk
 constexpr int RM_PER = 4;                             // records a lane gathers together
 constexpr int RM_LIST = 512;                          // positions a wavefront expands per round
-constexpr int RM_SEED_EVERY = 33;                     // odd: the first launch's chunks are spread over all XCDs
+constexpr int RM_QPB = 1;                             // queries per block (two: 1.39 against 1.25 ms at N = 1e8, 128 queries)
+constexpr int RM_SEED_EVERY = 65;                     // odd: the first launch's chunks are spread over all XCDs
 static_assert(RM_LIST % (64 * RM_PER) == 0, "a round of the list is whole steps of gathers");
 
-template <int WORDS, bool FILTER>
-__global__ __launch_bounds__(RM_THREADS) __attribute__((amdgpu_waves_per_eu(8, 8))) void refine_mask_kernel(
+// QPB queries per block: their tables sit in LDS side by side and every chunk is worked through for one
+// query after the other, so the later ones find the chunk's records in the cache for certain.
+template <int WORDS, bool FILTER, int QPB>
+__global__ __launch_bounds__(RM_THREADS) void refine_mask_kernel(
     const uint8_t *__restrict__ items, int K, const float *__restrict__ lut, const uint32_t *__restrict__ masks,
     size_t mask_words, const uint32_t *__restrict__ perm, uint32_t nsel, uint32_t seed_every, int window, int Q,
     const float *__restrict__ kth_dist, int topk, u64 *__restrict__ keys, uint32_t *__restrict__ key_count,
     int64_t cap, uint32_t *__restrict__ cand_count) {
-    __shared__ __attribute__((aligned(16))) float T[4 * WORDS * ICQ_LUT_W];
+    __shared__ __attribute__((aligned(16))) float T_all[QPB][4 * WORDS * ICQ_LUT_W];
     __shared__ uint32_t cand_all[RM_WAVES][RM_LIST];
     constexpr int RW = WORDS;
     const int tid = threadIdx.x;
     const uint32_t lane = (uint32_t)tid & 63u;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     uint32_t *cand = cand_all[wave];
-    // block -> (window, query, XCD): chunks i = (win * window + j) * 8 + xcd, j = 0 .. window - 1, of this
+    // block -> (window, query group, XCD): chunks i = (win * window + j) * 8 + xcd, j = 0 .. window - 1, of this
     // launch's; wavefront w takes j = w, w + 4, ..
+    const uint32_t ngroups = ((uint32_t)Q + QPB - 1) / QPB;
     const uint32_t xcd = blockIdx.x & 7u, rest = blockIdx.x >> 3;
-    const uint32_t q = rest % (uint32_t)Q, win = rest / (uint32_t)Q;
+    const uint32_t q0 = (rest % ngroups) * QPB, win = rest / ngroups;
+    const uint32_t nq = (uint32_t)Q - q0 < (uint32_t)QPB ? (uint32_t)Q - q0 : (uint32_t)QPB;
     auto chunk_of = [&](uint32_t j) -> uint32_t {
         const uint32_t i = (win * (uint32_t)window + j) * 8u + xcd;
         if (j >= (uint32_t)window || i >= nsel) return 0xFFFFFFFFu;
@@ -574,51 +579,77 @@ __global__ __launch_bounds__(RM_THREADS) __attribute__((amdgpu_waves_per_eu(8, 8
     if (chunk_of(0) == 0xFFFFFFFFu) return;           // block-uniform: nothing for this block
     // Word r of this lane covers the 32 positions from c * RM_CHUNK + (r * 64 + lane) * 32: neighbouring
     // words sit in neighbouring lanes, so a dense stretch of hits is shared out among many lanes.
-    const uint32_t *mq = masks + (size_t)q * mask_words + lane;
-    uint32_t c = chunk_of((uint32_t)wave);
+    // The wavefront's work is the sequence (chunk j, query qq), qq fastest; the next one's hit bits travel
+    // while the current one is worked on.
+    const uint32_t *mq = masks + (size_t)q0 * mask_words + lane;
+    uint32_t j = (uint32_t)wave, qq = 0;
+    uint32_t c = chunk_of(j);
     uint32_t nxt[RM_WORDS];
     {
         const uint32_t c0 = c != 0xFFFFFFFFu ? c : 0u;
 #pragma unroll
         for (int r = 0; r < RM_WORDS; ++r) nxt[r] = mq[(size_t)c0 * (RM_CHUNK / 32) + r * 64];
     }
-    {   // the query's tables -> LDS, one table per record byte, zero beyond K
-        const float4 *src = reinterpret_cast<const float4 *>(lut + (int64_t)q * K * ICQ_LUT_W);
-        float4 *dst = reinterpret_cast<float4 *>(T);
+    // the queries' tables -> LDS, one table per record byte, zero beyond K
+#pragma unroll
+    for (int g = 0; g < QPB; ++g) {
+        const uint32_t qg = q0 + ((uint32_t)g < nq ? (uint32_t)g : 0u);
+        const float4 *src = reinterpret_cast<const float4 *>(lut + (int64_t)qg * K * ICQ_LUT_W);
+        float4 *dst = reinterpret_cast<float4 *>(T_all[g]);
         constexpr int N4 = 4 * WORDS * (ICQ_LUT_W / 4);
         float4 v[N4 / RM_THREADS];
 #pragma unroll
-        for (int j = 0; j < N4 / RM_THREADS; ++j) {
-            const int i = j * RM_THREADS + tid;
-            v[j] = i / (ICQ_LUT_W / 4) < K ? src[i] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        for (int u = 0; u < N4 / RM_THREADS; ++u) {
+            const int i = u * RM_THREADS + tid;
+            v[u] = i / (ICQ_LUT_W / 4) < K ? src[i] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         }
 #pragma unroll
-        for (int j = 0; j < N4 / RM_THREADS; ++j) dst[j * RM_THREADS + tid] = v[j];
+        for (int u = 0; u < N4 / RM_THREADS; ++u) dst[u * RM_THREADS + tid] = v[u];
     }
-    uint32_t bound = 0xFFFFFFFFu;
-    if (FILTER) {
-        const uint32_t ob = icq_order_bits(kth_dist[(int64_t)q * topk + topk - 1]);
-        if (ob < 0xFF800000u) bound = ob;             // a finite topk-th distance; else the list is still open
+    uint32_t bound_all[QPB];
+#pragma unroll
+    for (int g = 0; g < QPB; ++g) {
+        bound_all[g] = 0xFFFFFFFFu;
+        if (FILTER) {
+            const uint32_t qg = q0 + ((uint32_t)g < nq ? (uint32_t)g : 0u);
+            const uint32_t ob = icq_order_bits(kth_dist[(int64_t)qg * topk + topk - 1]);
+            if (ob < 0xFF800000u) bound_all[g] = ob;  // a finite topk-th distance; else the list is still open
+        }
     }
     __syncthreads();                                  // the only barrier: from here on every wavefront is on its own
-    u64 *kout = keys + (int64_t)q * cap;
-    uint32_t survivors = 0;                           // of this wavefront's chunks (wavefront-uniform)
-    for (uint32_t j = (uint32_t)wave; c != 0xFFFFFFFFu; j += RM_WAVES) {
+    uint32_t survivors[QPB];                          // of this wavefront's chunks (wavefront-uniform)
+#pragma unroll
+    for (int g = 0; g < QPB; ++g) survivors[g] = 0;
+    while (c != 0xFFFFFFFFu) {
         uint32_t w[RM_WORDS];
 #pragma unroll
         for (int r = 0; r < RM_WORDS; ++r) w[r] = nxt[r];
-        const uint32_t cn = chunk_of(j + RM_WAVES);
-        if (cn != 0xFFFFFFFFu) {                      // the wavefront's next chunk: its hit bits travel while this one is worked on
-#pragma unroll
-            for (int r = 0; r < RM_WORDS; ++r) nxt[r] = mq[(size_t)cn * (RM_CHUNK / 32) + r * 64];
+        // next piece of work: the next query of this chunk, else the wavefront's next chunk
+        uint32_t qn = qq + 1, jn = j, cn = c;
+        if (qn >= nq) {
+            qn = 0;
+            jn = j + RM_WAVES;
+            cn = chunk_of(jn);
         }
+        if (cn != 0xFFFFFFFFu) {
+            const uint32_t *mn = mq + (size_t)qn * mask_words + (size_t)cn * (RM_CHUNK / 32);
+#pragma unroll
+            for (int r = 0; r < RM_WORDS; ++r) nxt[r] = mn[r * 64];
+        }
+        const uint32_t q = q0 + qq;
+        const float *T = T_all[QPB == 1 ? 0 : qq];
+        uint32_t bound = bound_all[0];
+#pragma unroll
+        for (int g = 1; g < QPB; ++g) bound = qq == (uint32_t)g ? bound_all[g] : bound;
+        u64 *kout = keys + (int64_t)q * cap;
         uint32_t mine = 0;
 #pragma unroll
         for (int r = 0; r < RM_WORDS; ++r) mine += (uint32_t)__builtin_popcount(w[r]);
         const uint32_t incl = wave_scan_add(mine);
         const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
         const uint32_t off = incl - mine;
-        survivors += total;
+#pragma unroll
+        for (int g = 0; g < QPB; ++g) survivors[g] += qq == (uint32_t)g ? total : 0u;
         // unfiltered: every survivor of the chunk gets a key, so their slots are reserved at once (the atomic's
         // answer travels while the positions are expanded)
         uint32_t chunk_slot = 0;
@@ -705,9 +736,13 @@ __global__ __launch_bounds__(RM_THREADS) __attribute__((amdgpu_waves_per_eu(8, 8
                 }
             }
         }
+        qq = qn;
+        j = jn;
         c = cn;
     }
-    if (lane == 0 && survivors != 0) atomicAdd(&cand_count[q], survivors);
+#pragma unroll
+    for (int g = 0; g < QPB; ++g)
+        if (lane == 0 && (uint32_t)g < nq && survivors[g] != 0) atomicAdd(&cand_count[q0 + g], survivors[g]);
 }
 
 }  // namespace
@@ -839,8 +874,9 @@ int icq_launch_refine_masks(const icq_index *ix, const float *lut, int Q, const 
     };
     // Chunks per block: few, so that the blocks in flight (two windows' worth when the queries fill the
     // chip) keep to a few chunks per XCD; more when there are so few queries that the table load would weigh.
-    auto window_for = [&](uint32_t nsel) -> int {
-        int w = Q >= 8 && !g2 ? 8 : 16;               // grouped order: a query's survivors sit in runs, the walk depends less on the cache
+    auto window_for = [&](uint32_t nsel, bool filtered) -> int {
+        int w = Q >= 8 && !g2 ? 8 : 16;
+        if (!filtered && Q >= 8) w = 4;               // the unfiltered part is short: spread it over more blocks               // grouped order: a query's survivors sit in runs, the walk depends less on the cache
         const int most = (int)((nsel + 7) / 8);
         return w < most ? w : (most > 0 ? most : 1);
     };
@@ -848,9 +884,10 @@ int icq_launch_refine_masks(const icq_index *ix, const float *lut, int Q, const 
     const uint32_t *m32 = reinterpret_cast<const uint32_t *>(masks);
 #define ICQ_RM_LAUNCH(W, FILTER, NSEL)                                                                       \
     do {                                                                                                     \
-        const int window = window_for(NSEL);                                                                 \
+        const int window = window_for(NSEL, FILTER);                                                               \
         const unsigned nwin = ((NSEL) + 8u * window - 1) / (8u * window);                                    \
-        refine_mask_kernel<W, FILTER><<<nwin * (unsigned)Q * 8u, RM_THREADS, 0, s>>>(                         \
+        const unsigned ngroups = ((unsigned)Q + RM_QPB - 1) / RM_QPB;                                        \
+        refine_mask_kernel<W, FILTER, RM_QPB><<<nwin * ngroups * 8u, RM_THREADS, 0, s>>>(                     \
             items, ix->K, lut, m32, mask_words, perm, (NSEL), seed_every, window, Q, out_dist, topk, cand_keys, \
             key_count, cap, cand_count);                                                                     \
     } while (0)
