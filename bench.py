@@ -34,9 +34,11 @@ HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E
 # published 157.3 TFLOP/s fp32 counts a fused multiply-add as two and assumes the packed two-wide
 # form; an add, a compare or a bit operation is one operation in one lane)
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-# LDS: the measured rate of 4-, 8- and 16-byte reads is 16 addresses per clock and CU, whatever the
-# width (64 / 120 / 192 B/clk/CU measured: profiles/machine_limits.txt), so table reads are priced per address
-LDS_PEAK_GADDR = 256 * 16 * 2.4             # 1e9 addresses per second
+# LDS: table reads are priced per lane address against the rate measured for 16-byte reads of a
+# conflict-free table (profiles/machine_limits.txt: 9.3e12, 11.4e12 and 7.7e12 addresses per second for
+# 4-, 8- and 16-byte reads -- about 16 per clock and CU whatever the width); the four-queries-per-pass
+# kernels read 16 bytes (the four queries' entries) per address
+LDS_PEAK_GADDR = 7720.0                     # 1e9 addresses per second, 16-byte reads
 SURVIVE_FRAC = 0.01
 
 
@@ -630,8 +632,11 @@ def main():
                             "model (alu_ops: additions, comparison and hit-bit collection per (query, position), byte "
                             "extraction and table address per position and pass) per second; peak = 256 CU x 4 SIMD x "
                             "16 lanes x 2.4 GHz.  lds / hbm: the same launch against the other two resources "
-                            "(LDS: 16 addresses per clock and CU measured for any read width; HBM: code rows per "
-                            "pass plus the hit bits written)"}
+                            "(LDS: lane addresses against the 7.72e12 per second measured for 16-byte reads; HBM: code "
+                            "rows per pass plus the hit bits written -- all passes but the first are served by the caches, "
+                            "see traffic).  The vector peak is the rate of three-operand and compare instructions; "
+                            "two-operand additions can issue at almost twice that (profiles/machine_limits.txt), so the "
+                            "fraction is an upper estimate; SQ counters of the same launch: profiles/sq_counters_C4.txt"}
 
     result = {
         "metric": "queries/sec at top-%d (oracle-matched)" % topk,
@@ -692,7 +697,8 @@ def main():
                         "table_entries_per_s": round(m["table_entries"] / t, 1)},
                 "stages_ms_per_call": {"build_lut": round(stage_s[0], 4), "stage1": round(stage_s[1], 4),
                                        "stage2": round(stage_s[2], 4)},
-                "traffic": None}
+                "traffic": (pmc_traffic("scan_stream_kernel_items", wl) or {}).get("bytes"),
+                "traffic_source": (pmc_traffic("scan_stream_kernel_items", wl) or {}).get("source")}
         log("[bench] all fast rows item by item: %.3f ms/step (stage 1 %.3f ms per call), same lists: %s" %
             (ms_s, stage_s[1], same))
 
