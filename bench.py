@@ -429,7 +429,8 @@ def machine_limits(torch, b):
     for name, kind, reps in (("stream_read_400MB", b.ICQ_PROBE_READ, 20), ("stream_read_400MB_nontemporal", b.ICQ_PROBE_READ_NT, 20),
                              ("lds_read_b32", b.ICQ_PROBE_LDS_B32, 3), ("lds_read_b64", b.ICQ_PROBE_LDS_B64, 3),
                              ("lds_read_b128", b.ICQ_PROBE_LDS_B128, 3), ("valu_add_f32", b.ICQ_PROBE_VALU, 3),
-                             ("atomic_add_one_word", b.ICQ_PROBE_ATOMIC, 5)):
+                             ("atomic_add_one_word", b.ICQ_PROBE_ATOMIC, 5), ("mfma_f32_32x32x2", b.ICQ_PROBE_MFMA_F32, 3),
+                             ("mfma_f32_32x32x2_random_operands", b.ICQ_PROBE_MFMA_F32_RANDOM, 3)):
         ms, units = b.icq_machine_probe(kind, buf, reps)
         rate = units / (ms * 1e-3)
         e = {"ms": round(ms, 4)}
@@ -439,6 +440,8 @@ def machine_limits(torch, b):
             width = {"b32": 4, "b64": 8, "b128": 16}[name.split("_")[-1]]
             e.update(Gaddr_s=round(rate / 1e9, 1), addr_per_clk_per_cu_at_2p4GHz=round(rate / 256 / 2.4e9, 2),
                      bytes_per_clk_per_cu_at_2p4GHz=round(rate * width / 256 / 2.4e9, 1))
+        elif "mfma" in name:
+            e.update(TFLOPs=round(rate / 1e12, 1), frac_of_157p3=round(rate / 157.3e12, 4))
         elif "valu" in name:
             e.update(Tops_s=round(rate / 1e12, 2), lanes_per_clk_per_cu_at_2p4GHz=round(rate / 256 / 2.4e9, 1))
         else:

@@ -157,8 +157,9 @@ int icq_workspace_bytes(const icq_index *index, int Q, int64_t cap, int topk, si
  * Lookup-table precompute (Sec. 1, text after Eq. 1: all ||q - c_{k,j}||^2 are
  * computed once per query so that a distance costs K additions):
  *   lut[q][k][j] = ||q||^2 - 2<q, c_{k,j}> + ||c_{k,j}||^2,   fp32, [Q][K][256]
- * (rows are always 256 wide; entries j >= m are +inf).  queries [Q][d] fp32.
- * The inner products run on the fp32 matrix cores.  Q >= 0.
+ * (rows are always 256 wide; entries j >= m are +inf).  queries [Q][d] fp32;
+ * lut 16-byte aligned (ICQ_ERR_ARG otherwise).  The inner products run on the
+ * fp32 matrix cores.  Q >= 0.
  */
 int icq_build_lut(const icq_index *index, const float *queries, int Q, float *lut, void *stream);
 
@@ -317,7 +318,10 @@ int icq_margin(const double *lambda, const uint8_t *xi, int d, double *sigma_out
  * (ICQ_PROBE_READ: 128-bit loads over `buffer`, one block per CU; ICQ_PROBE_READ_NT: the same with
  * the non-temporal hint), lane reads of a conflict-free 128 KB LDS table in 4-, 8- or 16-byte
  * accesses (ICQ_PROBE_LDS_B32/B64/B128), plain single-precision vector additions
- * (ICQ_PROBE_VALU), or atomic additions on one word (ICQ_PROBE_ATOMIC).  buffer: device memory
+ * (ICQ_PROBE_VALU), atomic additions on one word (ICQ_PROBE_ATOMIC), or the single-precision
+ * 32x32x2 matrix instruction on register operands (ICQ_PROBE_MFMA_F32: two small integers as
+ * operands; ICQ_PROBE_MFMA_F32_RANDOM: pseudo-random values with full mantissas; units =
+ * floating-point operations).  buffer: device memory
  * of `bytes` >= 4 MiB, 16-byte aligned; every kind may overwrite its first 4 MiB.
  */
 #define ICQ_PROBE_READ 0
@@ -327,6 +331,8 @@ int icq_margin(const double *lambda, const uint8_t *xi, int d, double *sigma_out
 #define ICQ_PROBE_LDS_B128 4
 #define ICQ_PROBE_VALU 5
 #define ICQ_PROBE_ATOMIC 6
+#define ICQ_PROBE_MFMA_F32 7
+#define ICQ_PROBE_MFMA_F32_RANDOM 8
 int icq_machine_probe(int kind, void *buffer, size_t bytes, int reps, double *ms_out /*host*/,
                       double *units_out /*host*/, void *stream);
 

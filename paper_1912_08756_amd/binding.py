@@ -279,7 +279,7 @@ def icq_margin(lam, xi, sigma_out):
 
 
 ICQ_PROBE_READ, ICQ_PROBE_READ_NT, ICQ_PROBE_LDS_B32, ICQ_PROBE_LDS_B64, ICQ_PROBE_LDS_B128, ICQ_PROBE_VALU, \
-    ICQ_PROBE_ATOMIC = range(7)
+    ICQ_PROBE_ATOMIC, ICQ_PROBE_MFMA_F32, ICQ_PROBE_MFMA_F32_RANDOM = range(9)
 
 
 def icq_machine_probe(kind, buffer, reps):

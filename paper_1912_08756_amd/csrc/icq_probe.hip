@@ -1,6 +1,6 @@
 // Machine-limit probes: a few plain kernels that show what one MI355X delivers for the access
 // patterns the search kernels are made of -- a streaming read, LDS table reads of 4, 8 and 16
-// bytes, plain vector arithmetic, atomics on one address.  The rooflines of the search kernels are
+// bytes, plain vector arithmetic, the single-precision matrix instruction, atomics on one address.  The rooflines of the search kernels are
 // judged against these figures next to the published peaks.  A measurement aid; nothing on the
 // search path calls it.
 #include "icq_internal.h"
@@ -81,6 +81,46 @@ __global__ __launch_bounds__(PB_THREADS, 1) void probe_valu_kernel(float *out, i
     out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// Four independent accumulators of the single-precision 32x32x2 matrix instruction per wavefront,
+// operands in registers: the rate the matrix cores sustain for the table build's instruction.
+// RANDOM: the operands are 32 different pseudo-random values per lane, full mantissas (what real
+// data looks like to the multipliers); otherwise two small integers.
+template <bool RANDOM>
+__global__ __launch_bounds__(256) void probe_mfma_kernel(float *out, int iters) {
+    typedef float float16v __attribute__((ext_vector_type(16)));
+    float16v acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+    float a[16], b[16];
+    uint32_t r = (blockIdx.x * blockDim.x + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        if (RANDOM) {
+            r = r * 1664525u + 1013904223u;
+            a[u] = __uint_as_float(0x3F800000u | (r >> 9)) - 1.5f;      // uniform in [-0.5, 0.5)
+            r = r * 1664525u + 1013904223u;
+            b[u] = __uint_as_float(0x3F800000u | (r >> 9)) - 1.5f;
+        } else {
+            a[u] = (float)(threadIdx.x & 7);
+            b[u] = (float)(threadIdx.x & 3);
+        }
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[4 * u + j], b[4 * u + j], acc[j], 0, 0, 0);
+        }
+    }
+    float s = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        for (int v = 0; v < 16; ++v) s += acc[j][v];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 // One atomic per wavefront and iteration, all on the same word.
 __global__ __launch_bounds__(PB_THREADS) void probe_atomic_kernel(uint32_t *counter, int iters) {
     if ((threadIdx.x & 63) != 0) return;
@@ -91,7 +131,7 @@ __global__ __launch_bounds__(PB_THREADS) void probe_atomic_kernel(uint32_t *coun
 
 ICQ_EXPORT int icq_machine_probe(int kind, void *buffer, size_t bytes, int reps, double *ms_out, double *units_out,
                                  void *stream) {
-    if (kind < ICQ_PROBE_READ || kind > ICQ_PROBE_ATOMIC || !buffer || bytes < (1u << 22) || reps < 1 || !ms_out ||
+    if (kind < ICQ_PROBE_READ || kind > ICQ_PROBE_MFMA_F32_RANDOM || !buffer || bytes < (1u << 22) || reps < 1 || !ms_out ||
         !units_out || ((uintptr_t)buffer % 16) != 0)
         return ICQ_ERR_ARG;
     hipStream_t s = (hipStream_t)stream;
@@ -130,6 +170,15 @@ ICQ_EXPORT int icq_machine_probe(int kind, void *buffer, size_t bytes, int reps,
             case ICQ_PROBE_VALU:
                 probe_valu_kernel<<<cus, PB_THREADS, 0, s>>>(static_cast<float *>(buffer), iters);
                 units = (double)cus * PB_THREADS * iters * 16.0 * 8.0;  // lane operations
+                break;
+            case ICQ_PROBE_MFMA_F32:
+                // 8 blocks of 4 wavefronts per CU; 32*32*2 multiply-adds per instruction
+                probe_mfma_kernel<false><<<cus * 8, 256, 0, s>>>(static_cast<float *>(buffer), iters);
+                units = (double)cus * 8 * 4 * iters * 16.0 * 4096.0;   // floating-point operations
+                break;
+            case ICQ_PROBE_MFMA_F32_RANDOM:
+                probe_mfma_kernel<true><<<cus * 8, 256, 0, s>>>(static_cast<float *>(buffer), iters);
+                units = (double)cus * 8 * 4 * iters * 16.0 * 4096.0;
                 break;
             default:
                 probe_atomic_kernel<<<cus, PB_THREADS, 0, s>>>(static_cast<uint32_t *>(buffer), 64);

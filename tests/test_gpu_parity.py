@@ -118,7 +118,9 @@ def test_storage_round_trip_is_bit_exact(gpu, K, Kf, N):
 # ------------------------------------------------------------------ lookup tables
 @pytest.mark.parametrize("name,Q,over", [
     ("C0", 100, {}), ("C1", 130, {}), ("C2", 70, {}), ("C3", 65, {}),
-    ("C0", 5, dict(d=7)), ("C0", 64, dict(d=33, m=100)), ("C1", 1, dict(d=200, K=3, Kf=1, sigma=("geom", 0.5)))])
+    ("C0", 5, dict(d=7)), ("C0", 64, dict(d=33, m=100)), ("C1", 1, dict(d=200, K=3, Kf=1, sigma=("geom", 0.5))),
+    # more than four blocks per compute unit: the kernel form without read-ahead, with and without 16-byte query loads
+    ("C1", 4100, {}), ("C0", 8200, dict(d=33))])
 def test_build_lut_matches_oracle(gpu, name, Q, over):
     cfg = synth.make(name, N=1000, Q=Q, **over)
     g = Gpu(gpu, cfg)
