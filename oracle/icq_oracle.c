@@ -237,6 +237,71 @@ void icq_oracle_running_search(const double *T, int K, int m, const uint8_t *cod
     }
 }
 
+/* The loop of Sec. 3.4 with the right side of its crude comparison refreshed per
+ * tile of items instead of per item (what a machine that scans a tile of items
+ * in parallel can do): tile r covers the items bounds[r] .. bounds[r+1]-1
+ * (bounds[0] = 0, ascending, bounds[R] = N).  At the start of a tile let f be the
+ * furthest element of the list as it stands; every item of the tile meets the
+ * crude comparison P(i) < P(f) + sigma_q with THAT f (no comparison while the
+ * list was not full at the start of the tile: every item of the tile then gets
+ * the exact comparison).  The exact comparison D(i) < D(furthest now) and the
+ * replacement run item by item as in the loop.  Tiles of one item each are the
+ * paper's loop itself; one tile over everything is the exhaustive search.
+ * Outputs as icq_oracle_running_search. */
+void icq_oracle_running_search_tiled(const double *T, int K, int m, const uint8_t *codes,
+                                     int64_t N, int Kf, int Q, const double *sigma, int topk,
+                                     const int64_t *bounds, int R,
+                                     uint32_t *out_ids, double *out_dist, int64_t *out_refined)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int q = 0; q < Q; ++q) {
+        const double *Tq = T + (size_t)q * K * m;
+        pair_t *list = (pair_t *)malloc(sizeof(pair_t) * (size_t)topk);
+        double *listP = (double *)malloc(sizeof(double) * (size_t)topk);
+        int len = 0;
+        int64_t refined = 0;
+        for (int r = 0; r < R; ++r) {
+            const int full_at_start = len == topk;
+            double t = INFINITY;
+            if (full_at_start) {
+                int f = 0;
+                for (int e = 1; e < len; ++e)
+                    if (pair_cmp(&list[e], &list[f]) > 0) f = e;
+                t = listP[f] + sigma[q];
+            }
+            for (int64_t i = bounds[r]; i < bounds[r + 1]; ++i) {
+                double p = 0.0;
+                for (int k = 0; k < Kf; ++k)
+                    p += Tq[(size_t)k * m + codes[(size_t)k * N + i]];
+                if (full_at_start && !(p < t)) continue;
+                double dfull = p;
+                for (int k = Kf; k < K; ++k)
+                    dfull += Tq[(size_t)k * m + codes[(size_t)k * N + i]];
+                ++refined;
+                if (len < topk) {
+                    list[len].dist = dfull; list[len].id = (uint32_t)i; listP[len] = p;
+                    ++len;
+                } else {
+                    int f = 0;
+                    for (int e = 1; e < len; ++e)
+                        if (pair_cmp(&list[e], &list[f]) > 0) f = e;
+                    if (dfull < list[f].dist) {
+                        list[f].dist = dfull; list[f].id = (uint32_t)i; listP[f] = p;
+                    }
+                }
+            }
+        }
+        qsort(list, (size_t)len, sizeof(pair_t), pair_cmp);
+        for (int r = 0; r < topk; ++r) {
+            out_ids[(size_t)q * topk + r] = r < len ? list[r].id : 0xFFFFFFFFu;
+            out_dist[(size_t)q * topk + r] = r < len ? list[r].dist : INFINITY;
+        }
+        out_refined[q] = refined;
+        free(list);
+        free(listP);
+    }
+}
+
 /* A static threshold with the meaning of Sec. 3.4's running one: look at the
  * first M items only, give every one of them the exact comparison, let f be
  * the topk-th nearest of them by (D, id), and set

@@ -62,6 +62,7 @@ def _load():
         lib.icq_oracle_reconstruct.argtypes = [c_f, i, i, i, c_u8, i64, c_i64, i64, c_d]
         lib.icq_oracle_bruteforce_knn.argtypes = [c_f, i, i, i, c_u8, i64, c_f, i, i, c_u32, c_d]
         lib.icq_oracle_running_search.argtypes = [c_d, i, i, c_u8, i64, i, i, c_d, i, c_u32, c_d, c_i64]
+        lib.icq_oracle_running_search_tiled.argtypes = [c_d, i, i, c_u8, i64, i, i, c_d, i, c_i64, i, c_u32, c_d, c_i64]
         lib.icq_oracle_sample_thresholds.argtypes = [c_d, i, i, c_u8, i64, i, i, c_d, i, i64, c_d]
         lib.icq_oracle_op_counts.argtypes = [i64, i, i, i, c_i64, ctypes.c_double, c_d, c_d]
         dbl = ctypes.c_double
@@ -74,7 +75,7 @@ def _load():
         lib.icq_oracle_encode.argtypes = [c_f, i, i, i, c_f, i64, c_u8, c_d]
         lib.icq_oracle_threads.restype = i
         for name in ("lut", "partial", "search", "adc_exhaustive", "reconstruct", "bruteforce_knn",
-                     "running_search", "sample_thresholds", "op_counts", "encode",
+                     "running_search", "running_search_tiled", "sample_thresholds", "op_counts", "encode",
                      "batch_moments", "online_variance", "subspace_mask", "fast_set"):
             getattr(lib, "icq_oracle_" + name).restype = None
         _lib = lib
@@ -169,6 +170,27 @@ def running_search(T, codes, Kf, sigma, topk):
     _load().icq_oracle_running_search(_p(T, ctypes.c_double), K, m, _p(cd, ctypes.c_uint8), N, Kf, Q,
                                       _p(sg, ctypes.c_double), topk, _p(ids, ctypes.c_uint32),
                                       _p(dist, ctypes.c_double), _p(refined, ctypes.c_int64))
+    return ids, dist, refined
+
+
+def running_search_tiled(T, codes, Kf, sigma, topk, bounds):
+    """The serial loop with the crude comparison's right side refreshed per tile of items;
+    bounds [R+1] ascending from 0 to N.  Returns as running_search."""
+    Q, K, m = T.shape
+    N = codes.shape[1]
+    T = _chk(T, np.float64, (Q, K, m))
+    cd = _chk(codes, np.uint8, (K, N))
+    sg = _chk(sigma, np.float64, (Q,))
+    bd = np.ascontiguousarray(bounds, dtype=np.int64)
+    if bd.ndim != 1 or bd.size < 2 or bd[0] != 0 or bd[-1] != N or (np.diff(bd) < 0).any():
+        raise ValueError("bounds must ascend from 0 to N")
+    ids = np.empty((Q, topk), dtype=np.uint32)
+    dist = np.empty((Q, topk), dtype=np.float64)
+    refined = np.empty((Q,), dtype=np.int64)
+    _load().icq_oracle_running_search_tiled(_p(T, ctypes.c_double), K, m, _p(cd, ctypes.c_uint8), N, Kf, Q,
+                                            _p(sg, ctypes.c_double), topk, _p(bd, ctypes.c_int64), bd.size - 1,
+                                            _p(ids, ctypes.c_uint32), _p(dist, ctypes.c_double),
+                                            _p(refined, ctypes.c_int64))
     return ids, dist, refined
 
 

@@ -90,6 +90,15 @@ static void one_case(int K, int Kf, int m, int d, int64_t N, int Q, int topk, in
     icq_oracle_running_search(T, K, m, codes, N, Kf, Q, sigma, topk, ids, dist, refined);
     print_u32("running ids", ids, (size_t)Q * topk);
     print_i64("running refined", refined, (size_t)Q);
+    {
+        /* an empty tile, a tile shorter than the list, ragged ones, the rest */
+        int64_t bounds[6];
+        bounds[0] = 0; bounds[1] = 0; bounds[2] = topk / 2 < N ? topk / 2 : N; bounds[3] = N / 3 > bounds[2] ? N / 3 : bounds[2];
+        bounds[4] = N / 3 * 2 + 1 > bounds[3] && N / 3 * 2 + 1 <= N ? N / 3 * 2 + 1 : bounds[3]; bounds[5] = N;
+        icq_oracle_running_search_tiled(T, K, m, codes, N, Kf, Q, sigma, topk, bounds, 5, ids, dist, refined);
+        print_u32("tiled running ids", ids, (size_t)Q * topk);
+        print_i64("tiled running refined", refined, (size_t)Q);
+    }
 
     double *thr_out = (double *)malloc(sizeof(double) * (size_t)Q);
     icq_oracle_sample_thresholds(T, K, m, codes, N, Kf, Q, sigma, topk, N / 2 + 3, thr_out);

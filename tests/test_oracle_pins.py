@@ -348,6 +348,19 @@ def test_running_search_matches_hand_worked_trace():
     assert np.array_equal(ids9[0, :7], [4, 2, 6, 1, 3, 5, 0])
 
 
+def test_tiled_running_search_matches_hand_worked_traces():
+    gold = _golden_file("running_example.txt")
+    T = _micro_tables()
+    codes = np.stack([gold["codes0"], gold["codes1"]]).astype(np.uint8)
+    topk = int(gold["topk"][0])
+    sigma = np.array([gold["sigma"][0]])
+    for tag in ("a", "b"):
+        ids, dist, refined = orc.running_search_tiled(T, codes, 1, sigma, topk, gold["tiles_" + tag].astype(np.int64))
+        assert np.array_equal(ids[0], gold["ids"].astype(np.uint32))
+        assert np.array_equal(dist[0], gold["dist"])
+        assert refined[0] == int(gold["refined_" + tag][0]), tag
+
+
 def _random_case(seed, K=6, Kf=2, N=4000, Q=7, d=12):
     g = _rng(seed)
     cb = (g.standard_normal((K, 256, d)) * (0.7 ** np.arange(K))[:, None, None]).astype(np.float32)
@@ -385,6 +398,41 @@ def test_running_search_loses_nothing_when_the_margin_exceeds_the_spread_of_the_
     ids0, _, refined0 = orc.running_search(T, codes, Kf, np.zeros(Q), topk)
     assert (refined0 < refined).all()
     assert (ids0 != e_ids).any()
+
+
+def test_tiled_running_search_special_cases():
+    """Tiles of one item are the serial loop; one tile is the exhaustive search; the two tiles
+    [0, M) and [M, N) are the static threshold of the first M items applied to the rest."""
+    T, codes = _random_case(23, N=3000)
+    Q, N, Kf, topk = T.shape[0], codes.shape[1], 2, 10
+    sigma = np.linspace(0.0, 3.0, Q)
+    ids, dist, refined = orc.running_search(T, codes, Kf, sigma, topk)
+    ids1, dist1, refined1 = orc.running_search_tiled(T, codes, Kf, sigma, topk, np.arange(N + 1))
+    assert np.array_equal(ids, ids1) and np.array_equal(dist, dist1) and np.array_equal(refined, refined1)
+    # empty tiles change nothing
+    b = np.sort(np.concatenate([np.arange(N + 1), [0, 5, 5, N]]))
+    ids2, dist2, refined2 = orc.running_search_tiled(T, codes, Kf, sigma, topk, b)
+    assert np.array_equal(ids, ids2) and np.array_equal(refined, refined2)
+    # one tile: no crude comparison at all
+    e_ids, e_dist = orc.adc_exhaustive(T, codes, topk)
+    idsw, distw, refinedw = orc.running_search_tiled(T, codes, Kf, sigma, topk, np.array([0, N]))
+    assert np.array_equal(idsw, e_ids) and np.array_equal(distw, e_dist) and (refinedw == N).all()
+    # two tiles against the composition of two other oracle functions
+    M = 400
+    thr = orc.sample_thresholds(T, codes, Kf, sigma, topk, M)
+    P = orc.partial(T, codes, Kf)
+    D = orc.adc_exhaustive(T, codes, topk, want_all=True)[2]
+    ids3, dist3, refined3 = orc.running_search_tiled(T, codes, Kf, sigma, topk, np.array([0, M, N]))
+    for q in range(Q):
+        keep = np.concatenate([np.arange(M), M + np.nonzero(P[q, M:] < thr[q])[0]])
+        assert refined3[q] == keep.size
+        order = keep[np.lexsort((keep, D[q, keep]))][:topk]
+        assert np.array_equal(ids3[q], order.astype(np.uint32))
+        assert np.array_equal(dist3[q], D[q, order])
+    # an infinite margin makes every crude comparison hold, whatever the tiles
+    b4 = np.unique(np.concatenate([[0], np.arange(M, N + 1, 100), [N]]))
+    ids4, dist4, refined4 = orc.running_search_tiled(T, codes, Kf, np.full(Q, np.inf), topk, b4)
+    assert np.array_equal(ids4, e_ids) and np.array_equal(dist4, e_dist) and (refined4 == N).all()
 
 
 def test_running_search_with_margin_minus_infinity_keeps_the_first_items():
