@@ -206,7 +206,17 @@ def cpu_baseline(cfg, thr_np, gpu_ids, gpu_dist, target_s=15.0):
              "sampled_queries": n})
 
 
-def policy_leg(torch, b, cfg, index, queries, step_args, steps, with_cpu):
+def tile_bounds(N, first=16384):
+    """Tiles of doubling size: the threshold of Sec. 3.4's loop tightens fastest over the first items."""
+    bounds, size = [0], first
+    while bounds[-1] + size < N:
+        bounds.append(bounds[-1] + size)
+        size *= 2
+    bounds.append(N)
+    return bounds
+
+
+def policy_leg(torch, b, cfg, index, queries, step_args, steps, with_cpu, cb=None, codes=None):
     """The paper's threshold policy on the same workload: thresholds from the first M items
     with the margin of Eq. 11 (icq_sample_thresholds), then the two-step search, then the
     operation counts of the paper's speed axis; on a few queries the result is compared with
@@ -251,6 +261,37 @@ def policy_leg(torch, b, cfg, index, queries, step_args, steps, with_cpu):
            "survivors_mean": round(float(surv_np.mean()), 1), "survivors_frac": round(float(surv_np.mean()) / N, 5),
            "ops_two_step_mean": float(sm[0]), "ops_one_step": float(sm[1]), "ops_ratio": round(float(sm[2]), 5),
            "code_bits": K * 8, "effective_code_bits": round(float(sm[3]), 3)}
+    tiled_ids = None
+    if cb is not None and codes is not None:
+        # the loop's threshold refreshed per tile (icq_search_running): tiles of doubling size
+        bounds = tile_bounds(N)
+        tiles = [b.icq_index_create(cb, codes[:, a:e].contiguous(), Kf) for a, e in zip(bounds[:-1], bounds[1:])]
+        tcap = max(bounds[1], cap)
+        t_ids = torch.empty((Q, topk), dtype=torch.int32, device="cuda")
+        t_dist = torch.empty((Q, topk), dtype=torch.float32, device="cuda")
+        t_ref = torch.empty((Q,), dtype=torch.int32, device="cuda")
+        tws = torch.empty(b.icq_running_workspace_bytes(tiles, Q, tcap, topk), dtype=torch.uint8, device="cuda")
+
+        def tiled():
+            b.icq_search_running(tiles, bounds[:-1], queries, sigma, tcap, topk, t_ids, t_dist, t_ref, tws)
+        tiled()
+        torch.cuda.synchronize()
+        ms_tiled = event_time_ms(torch, tiled, max(3, steps))
+        b.icq_op_counts(index, t_ref, ops, summary)
+        torch.cuda.synchronize()
+        st = summary.cpu().numpy()
+        ref_np = t_ref.cpu().numpy().view(np.uint32)
+        tiled_ids = t_ids.cpu().numpy().view(np.uint32)
+        out["tiled_running"] = {
+            "policy": "threshold of the loop refreshed per tile: %d tiles of doubling size from %d items" % (len(tiles), bounds[1]),
+            "ms_tables_search": round(ms_tiled, 4), "queries_per_s": round(Q / (ms_tiled * 1e-3), 1),
+            "refined_mean": round(float(ref_np.mean()), 1), "refined_frac": round(float(ref_np.mean()) / N, 6),
+            "ops_two_step_mean": float(st[0]), "ops_ratio": round(float(st[2]), 5),
+            "effective_code_bits": round(float(st[3]), 3)}
+        for t in tiles:
+            b.icq_index_destroy(t)
+        del tws, tiles
+        torch.cuda.empty_cache()
     if with_cpu:
         from oracle import icq_oracle as orc
         nq = min(16, Q)
@@ -261,6 +302,11 @@ def policy_leg(torch, b, cfg, index, queries, step_args, steps, with_cpu):
         e_ids, _ = orc.adc_exhaustive(T, cfg["codes"], topk)
         g_ids = out_ids[:nq].cpu().numpy().view(np.uint32)
         inter = lambda a, c: float(np.mean([np.intersect1d(a[q], c[q]).size / topk for q in range(nq)]))
+        if tiled_ids is not None:
+            out["tiled_running"].update(
+                recall_of_exhaustive_lists=round(inter(tiled_ids[:nq], e_ids), 4),
+                recall_of_serial_loop_lists=round(inter(tiled_ids[:nq], r_ids), 4),
+                refined_mean_of_these_queries=float(ref_np[:nq].mean()))
         out["vs_serial_loop"] = {
             "queries": nq, "recall_of_serial_loop_lists": round(inter(g_ids, r_ids), 4),
             "recall_of_exhaustive_lists": round(inter(g_ids, e_ids), 4),
@@ -709,8 +755,12 @@ def main():
         log("[bench] threshold policy of the paper: sampled thresholds with margin, search, operation counts")
         result["threshold_policy"] = policy_leg(torch, b, cfg, index, queries[:batch].contiguous(),
                                                 (cap, out_ids, out_dist, surv, ws),
-                                                max(3, args.steps // 2), not args.no_cpu_baseline)
+                                                max(3, args.steps // 2), not args.no_cpu_baseline, cb, codes)
         p = result["threshold_policy"]
+        if "tiled_running" in p:
+            t = p["tiled_running"]
+            log("[bench] loop threshold per tile: tables + search %.3f ms, %.4f %% refined, ops ratio %.4f"
+                % (t["ms_tables_search"], 100 * t["refined_frac"], t["ops_ratio"]))
         log("[bench] policy: thresholds %.3f ms, tables + policy + search %.3f ms, %.2f %% survive, ops ratio %.4f"
             % (p["ms_sample_thresholds"], p["ms_tables_policy_search"], 100 * p["survivors_frac"], p["ops_ratio"]))
 

@@ -251,6 +251,43 @@ int icq_sample_thresholds(const icq_index *index, const float *lut, int Q, const
                           int64_t M, float *thresholds_out, void *stream);
 
 /*
+ * The search loop of Sec. 3.4 with its running threshold refreshed per tile of
+ * items.  The paper visits the items one by one and lets an item through to the
+ * exact comparison when its crude distance is below that of the furthest
+ * element f of the nearest-neighbour list plus the margin (right side of Eq. 2,
+ * sigma as in Eq. 11).  Here the database is given as R tiles -- indexes over
+ * consecutive ranges of item ids, created by the caller from the same codebooks
+ * with the same Kf (ICQ_ERR_ARG when K, Kf, d or m differ), tile r holding the
+ * items id_base[r] .. id_base[r] + N_r - 1 -- and tile r is searched like
+ * icq_search with
+ *     t_q = P[q][f] + sigma[q],   f = furthest element (largest (D, id)) of the
+ *                                 list after tiles 0 .. r-1,
+ * or t_q = +inf while that list holds fewer than topk items (every item of the
+ * tile then gets the exact comparison); the tile's survivors are merged into
+ * the list by (D, id) and the threshold is refreshed.  Tiles of one item each
+ * would be the paper's loop itself; one tile is the exhaustive search.
+ *   out_ids/out_dist [Q][topk]: the list after the last tile, ids global, as
+ *                    icq_search writes them (padding included);
+ *   out_refined [Q]: items that got the exact comparison, summed over the tiles
+ *                    (the `refined` of icq_op_counts, which takes N from the
+ *                    index it is given: one over the whole database);
+ *   sigma [Q] fp32, may be NULL (zero margin); id_base is a HOST array [R];
+ *   cap: candidate capacity per query and tile as in icq_search (a tile never
+ *        needs more than its own item count; tiles searched while the list is
+ *        not full need all of it);
+ *   workspace: icq_running_workspace_bytes(tiles, R, Q, cap, topk) bytes, 256-byte
+ *        aligned; tiles is a HOST array of R index handles.
+ * Work is enqueued on `stream`: one table build, then per tile the two-step
+ * search and one merge kernel.
+ */
+int icq_running_workspace_bytes(const icq_index *const *tiles /*host [R]*/, int R, int Q, int64_t cap, int topk,
+                                size_t *out /*host*/);
+int icq_search_running(const icq_index *const *tiles /*host [R]*/, const uint32_t *id_base /*host [R]*/, int R,
+                       const float *queries, int Q, const float *sigma, int64_t cap, int topk, uint32_t *out_ids,
+                       float *out_dist, uint32_t *out_refined, void *workspace, size_t workspace_bytes,
+                       void *stream);
+
+/*
  * Operation counts of the two-step search (Sec. 1: Kf table additions for every
  * item, K - Kf more for each item that gets the exact comparison, against K per
  * item for the one-step search) and the effective code length of Sec. 4.2.

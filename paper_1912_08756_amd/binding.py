@@ -35,6 +35,9 @@ SIGNATURES = {
     "icq_refine": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _sz, _vp]),
     "icq_search": (_i, [_vp, _vp, _i, _vp, _i64, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "icq_search_static": (_i, [_vp, _vp, _i, _vp, _i64, _i, _vp, _vp, _vp, _vp]),
+    "icq_running_workspace_bytes": (_i, [ctypes.POINTER(_vp), _i, _i, _i64, _i, ctypes.POINTER(_sz)]),
+    "icq_search_running": (_i, [ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_uint32), _i, _vp, _i, _vp, _i64, _i, _vp, _vp,
+                                _vp, _vp, _sz, _vp]),
     "icq_sample_thresholds": (_i, [_vp, _vp, _i, _vp, _i, _i64, _vp, _vp]),
     "icq_op_counts": (_i, [_vp, _vp, _i, _vp, _vp, _vp]),
     "icq_encode_workspace_bytes": (_i, [_vp, _i64, ctypes.POINTER(_sz)]),
@@ -214,6 +217,30 @@ def icq_search_static(index, queries, thresholds, cap, topk, out_ids, out_dist, 
                                     _dev(out_dist, torch.float32, (Q, topk), "out_dist"),
                                     _dev(out_survivors, torch.int32, (Q,), "out_survivors"), _stream()),
            "icq_search_static")
+
+
+def _tile_handles(tiles):
+    return (_vp * len(tiles))(*[t.handle for t in tiles])
+
+
+def icq_running_workspace_bytes(tiles, Q, cap, topk):
+    out = ctypes.c_size_t(0)
+    _check(load().icq_running_workspace_bytes(_tile_handles(tiles), len(tiles), Q, cap, topk, ctypes.byref(out)),
+           "icq_running_workspace_bytes")
+    return int(out.value)
+
+
+def icq_search_running(tiles, id_base, queries, sigma, cap, topk, out_ids, out_dist, out_refined, workspace):
+    """tiles: indexes over consecutive id ranges (same codebooks); id_base: first item id of each (host ints);
+    sigma: [Q] f32 device tensor or None."""
+    Q = queries.shape[0]
+    bases = (ctypes.c_uint32 * len(tiles))(*[int(x) for x in id_base])
+    _check(load().icq_search_running(
+        _tile_handles(tiles), bases, len(tiles), _dev(queries, torch.float32, (Q, tiles[0].d), "queries"), Q,
+        _dev(sigma, torch.float32, (Q,), "sigma") if sigma is not None else None, cap, topk,
+        _dev(out_ids, torch.int32, (Q, topk), "out_ids"), _dev(out_dist, torch.float32, (Q, topk), "out_dist"),
+        _dev(out_refined, torch.int32, (Q,), "out_refined"),
+        _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()), "icq_search_running")
 
 
 def icq_sample_thresholds(index, lut, sigma, topk, M, thresholds_out):

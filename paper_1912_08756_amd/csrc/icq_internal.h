@@ -119,6 +119,10 @@ int icq_refine_splits(const icq_index *ix, int Q, int64_t cap, int topk);
 bool icq_masks_usable(const icq_index *ix, int Q, int topk);
 int64_t icq_mask_scan_end(const icq_index *ix);              // positions the hit bits cover: whole stage-2 chunks
 // Stage 1 into hit bits (zeroes cand_count and key_count first; after_fill as in icq_launch_scan).
+// icq_search's body; lut_ext (device, [Q][K][256]) replaces the table build when not null.
+int icq_search_impl(const icq_index *ix, const float *queries, const float *lut_ext, int Q, const float *thresholds,
+                    int64_t cap, int topk, uint32_t *out_ids, float *out_dist, uint32_t *out_survivors,
+                    void *workspace, size_t workspace_bytes, void *stream);
 int icq_launch_scan_masks(const icq_index *ix, const float *lut, int Q, const float *thr, uint16_t *masks,
                           size_t mask_stride, int64_t scan_end, uint32_t *cand_count, uint32_t *key_count,
                           hipEvent_t after_fill, hipStream_t s);

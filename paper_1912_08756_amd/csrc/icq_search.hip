@@ -67,24 +67,26 @@ ICQ_EXPORT int icq_workspace_bytes(const icq_index *ix, int Q, int64_t cap, int 
     return ICQ_OK;
 }
 
-static int search_impl(const icq_index *ix, const float *queries, int Q, const float *thresholds,
-                       int64_t cap, int topk, uint32_t *out_ids, float *out_dist,
-                       uint32_t *out_survivors, void *workspace, size_t workspace_bytes,
-                       void *stream) {
+// lut_ext: the queries' tables when the caller has built them already (queries is not read then).
+int icq_search_impl(const icq_index *ix, const float *queries, const float *lut_ext, int Q, const float *thresholds,
+                    int64_t cap, int topk, uint32_t *out_ids, float *out_dist,
+                    uint32_t *out_survivors, void *workspace, size_t workspace_bytes,
+                    void *stream) {
     if (!ix || Q < 0 || Q > ICQ_MAX_Q || cap < 1 || topk < 1 || topk > ICQ_MAX_TOPK)
         return ICQ_ERR_ARG;
     if (Q == 0) return ICQ_OK;
-    if (!queries || !thresholds || !out_ids || !out_dist) return ICQ_ERR_ARG;
+    if ((!queries && !lut_ext) || !thresholds || !out_ids || !out_dist) return ICQ_ERR_ARG;
+    const bool own_lut = lut_ext == nullptr;
     if ((double)Q * (double)cap >= 1099511627776.0) return ICQ_ERR_ARG;
     if (!workspace || ((uintptr_t)workspace % ICQ_ALIGN) != 0) return ICQ_ERR_WORKSPACE;
 
     // Largest sub-batch (all of Q, else a multiple of 64 queries) that fits the workspace.
     int Qb = Q < SEARCH_MAX_BATCH ? Q : SEARCH_MAX_BATCH;
-    while (icq_layout(ix, Qb, cap, topk, true, true).total > workspace_bytes) {
+    while (icq_layout(ix, Qb, cap, topk, own_lut, true).total > workspace_bytes) {
         if (Qb <= 64) return ICQ_ERR_WORKSPACE;
         Qb = ((Qb / 2) + 63) / 64 * 64;
     }
-    if (Q % Qb != 0 && icq_layout(ix, Q % Qb, cap, topk, true, true).total > workspace_bytes)
+    if (Q % Qb != 0 && icq_layout(ix, Q % Qb, cap, topk, own_lut, true).total > workspace_bytes)
         return ICQ_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     char *ws = static_cast<char *>(workspace);
@@ -99,13 +101,15 @@ static int search_impl(const icq_index *ix, const float *queries, int Q, const f
     for (int q0 = 0; q0 < Q; q0 += Qb) {
         const bool timed = tm && q0 == 0;
         const int nq = (Q - q0) < Qb ? (Q - q0) : Qb;
-        const icq_ws_layout L = icq_layout(ix, nq, cap, topk, true, true);
-        float *lut = reinterpret_cast<float *>(ws + L.lut_off);
+        const icq_ws_layout L = icq_layout(ix, nq, cap, topk, own_lut, true);
+        const float *lut = own_lut ? reinterpret_cast<float *>(ws + L.lut_off)
+                                   : lut_ext + (int64_t)q0 * ix->K * ICQ_LUT_W;
         uint32_t *ids = reinterpret_cast<uint32_t *>(ws + L.ids_off);
         uint32_t *cnt = out_survivors ? out_survivors + q0 : reinterpret_cast<uint32_t *>(ws + L.count_off);
         unsigned long long *keys = reinterpret_cast<unsigned long long *>(ws + L.keys_off);
         if (timed) ICQ_HIP_TRY(hipEventRecord(ev[0], s));
-        int rc = icq_launch_build_lut(ix, queries + (int64_t)q0 * ix->d, nq, lut, s);
+        int rc = ICQ_OK;
+        if (own_lut) rc = icq_launch_build_lut(ix, queries + (int64_t)q0 * ix->d, nq, reinterpret_cast<float *>(ws + L.lut_off), s);
         if (rc != ICQ_OK) return rc;
         if (L.masked) {
             // item-by-item stage 1 into hit bits, stage 2 chunk by chunk from them
@@ -143,8 +147,8 @@ ICQ_EXPORT int icq_search(const icq_index *ix, const float *queries, int Q, cons
                           int64_t cap, int topk, uint32_t *out_ids, float *out_dist,
                           uint32_t *out_survivors, void *workspace, size_t workspace_bytes,
                           void *stream) {
-    return search_impl(ix, queries, Q, thresholds, cap, topk, out_ids, out_dist, out_survivors, workspace,
-                       workspace_bytes, stream);
+    return icq_search_impl(ix, queries, nullptr, Q, thresholds, cap, topk, out_ids, out_dist, out_survivors, workspace,
+                           workspace_bytes, stream);
 }
 
 // ---- icq_search for callers that cannot allocate: the workspace is a fixed array in the
@@ -190,6 +194,6 @@ ICQ_EXPORT int icq_search_static(const icq_index *ix, const float *queries, int 
     void *ws = nullptr;
     const int rc = scratch_address(&ws);
     if (rc != ICQ_OK) return rc;
-    return search_impl(ix, queries, Q, thresholds, cap, topk, out_ids, out_dist, out_survivors, ws,
+    return icq_search_impl(ix, queries, nullptr, Q, thresholds, cap, topk, out_ids, out_dist, out_survivors, ws,
                        (size_t)ICQ_STATIC_SCRATCH_BYTES, stream);
 }

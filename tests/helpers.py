@@ -83,3 +83,43 @@ def check_topk(P_q, D_q, t, topk, out_ids, out_dist):
     else:
         missing = np.setdiff1d(sure, ids)
         assert missing.size == 0, "survivor missing from a short result"
+
+
+def tiled_loop_analysis(P_q, D_q, sigma, topk, bounds, band):
+    """Follows the oracle's tiled search loop (crude comparison against the list as it stands at the
+    start of a tile) for one query on the oracle's own crude distances P_q and distances D_q, and
+    reports which of its decisions a computation with rounding errors up to band(x) could take
+    differently.  Returns (list ids ascending by (D, id), least and most exact comparisons, clean);
+    clean: no item within the band of a tile's threshold could enter the list, and neither the cut
+    of the list nor its furthest element (whose crude distance is the next threshold) hangs on
+    distances closer than the band.  With band = 0 this is the oracle's loop itself."""
+    ids = np.empty(0, dtype=np.int64)
+    lo = hi = 0
+    clean = True
+    for r in range(len(bounds) - 1):
+        a, b = int(bounds[r]), int(bounds[r + 1])
+        tile = np.arange(a, b, dtype=np.int64)
+        maybe = np.empty(0, dtype=np.int64)
+        if ids.size == topk:
+            t = P_q[ids[-1]] + sigma
+            w = band(t)
+            sure = tile[P_q[a:b] < t - w]
+            if w > 0:
+                maybe = tile[np.abs(P_q[a:b] - t) <= w]
+        else:
+            sure = tile
+        lo += sure.size
+        hi += sure.size + maybe.size
+        cand = np.concatenate([ids, sure])
+        order = cand[np.lexsort((cand, D_q[cand]))]
+        ids = order[:topk]
+        if ids.size == topk:
+            Dk = D_q[ids[-1]]
+            w = band(Dk)
+            if maybe.size and (D_q[maybe] <= Dk + w).any():
+                clean = False
+            if w > 0 and order.size > topk and D_q[order[topk]] - Dk <= w:
+                clean = False
+            if w > 0 and topk > 1 and Dk - D_q[ids[-2]] <= w:
+                clean = False
+    return ids, lo, hi, clean

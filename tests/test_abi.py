@@ -79,6 +79,8 @@ def test_host_side_argument_checks_of_the_policy_encoding_and_utility_calls():
     assert lib.icq_index_stage_times(None, None, None, None) == E
     assert lib.icq_index_export_codes(None, 0, one, None) == E
     assert lib.icq_sample_thresholds(None, one, 1, None, 10, 100, one, None) == E
+    assert lib.icq_running_workspace_bytes(None, 1, 1, 10, 10, ctypes.byref(out)) == E
+    assert lib.icq_search_running(None, None, 1, one, 1, None, 10, 10, one, one, one, one, 1 << 20, None) == E
     assert lib.icq_op_counts(None, one, 1, one, one, None) == E
     assert lib.icq_encode_workspace_bytes(None, 10, ctypes.byref(out)) == E
     assert lib.icq_encode(None, one, 10, one, one, 1 << 20, None) == E

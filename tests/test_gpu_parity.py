@@ -6,7 +6,7 @@ storage round trip bit-exact."""
 import numpy as np
 import pytest
 
-from helpers import check_candidates, check_topk, thresholds_kth, thresholds_quantile, tol
+from helpers import check_candidates, check_topk, thresholds_kth, thresholds_quantile, tiled_loop_analysis, tol
 from oracle import icq_oracle as orc
 from paper_1912_08756_amd import synth
 
@@ -725,6 +725,85 @@ def test_two_pass_search_with_sampled_thresholds(gpu):
         worst = out_dist[q][-1]
         need = inside[D[q, inside] < worst - tol(worst)]
         assert np.isin(need, out_ids[q]).all()
+
+
+RUNNING_CASES = [
+    # name, N, Q, overrides, topk, tile bounds, scan mode
+    ("C1", 60_000, 48, {}, 100, [0, 300, 2_000, 9_000, 30_000, 60_000], 0),      # Kf = 2: tuples, lists on chip
+    ("C1", 60_000, 48, {}, 10, [0, 300, 2_000, 9_000, 30_000, 60_000], 1),       # item by item
+    ("C4", 70_001, 32, dict(K=16), 20, [0, 1_000, 8_000, 40_000, 70_001], 0),     # Kf = 4, ragged last tile
+    ("C4", 70_001, 32, dict(K=16), 20, [0, 1_000, 8_000, 40_000, 70_001], 2),     # pair ordering forced
+    ("C0", 5_000, 20, {}, 7, [0, 3, 9, 100, 101, 2_500, 5_000], 0),               # tiles shorter than the list, one item
+    ("C1", 9_000, 5, {}, 1, [0, 9_000], 0),                                       # one tile: exhaustive
+]
+
+
+@pytest.mark.parametrize("name,N,Q,over,topk,bounds,mode", RUNNING_CASES)
+def test_running_search_in_tiles_matches_oracle(gpu, name, N, Q, over, topk, bounds, mode):
+    """The loop of Sec. 3.4 with the threshold refreshed per tile, against the oracle's statement of
+    it.  Both sides decide P < t and D < D(f) in their own precision and a decision taken
+    differently feeds back into the later thresholds, so the lists are compared exactly for the
+    queries none of whose decisions lies within 1e-5 * (|x| + 1) of its threshold (five times the
+    largest error measured between the two sides' distances), and every list is checked to be
+    made of true distances in ascending order; the counts of exact comparisons must lie between
+    the fewest and the most the band allows."""
+    torch, b = gpu
+    cfg = small(name, N, Q, **over)
+    K, Kf = cfg["K"], cfg["Kf"]
+    T, P, D = oracle_all(cfg)
+    cbv = cfg["codebooks"].astype(np.float64)
+    sig = float(sum(cbv[k].var(axis=0).sum() for k in range(Kf, K)))       # spread of the slow terms
+    rng = np.random.default_rng(17)
+    sigma = (sig * rng.uniform(0.0, 1.5, size=Q)).astype(np.float32)
+    want_ids, want_dist, want_refined = orc.running_search_tiled(T, cfg["codes"], Kf, sigma.astype(np.float64), topk,
+                                                                  np.array(bounds))
+    cb = _dev(torch, cfg["codebooks"])
+    tiles = []
+    for a, e in zip(bounds[:-1], bounds[1:]):
+        t = b.icq_index_create(cb, _dev(torch, cfg["codes"][:, a:e]), Kf)
+        b.icq_index_set_scan_mode(t, mode)
+        tiles.append(t)
+    cap = max(e - a for a, e in zip(bounds[:-1], bounds[1:]))
+    out_ids = torch.empty((Q, topk), dtype=torch.int32, device="cuda")
+    out_dist = torch.empty((Q, topk), dtype=torch.float32, device="cuda")
+    refined = torch.empty((Q,), dtype=torch.int32, device="cuda")
+    ws = torch.empty(b.icq_running_workspace_bytes(tiles, Q, cap, topk), dtype=torch.uint8, device="cuda")
+    for _ in range(2):          # a second call on the same workspace and outputs: nothing carried over
+        b.icq_search_running(tiles, bounds[:-1], _dev(torch, cfg["queries"]), _dev(torch, sigma), cap, topk, out_ids,
+                             out_dist, refined, ws)
+    torch.cuda.synchronize()
+    ids, dist, ref = _u32(out_ids), out_dist.cpu().numpy().astype(np.float64), _u32(refined)
+    nclean = 0
+    for q in range(Q):
+        valid = ids[q] != 0xFFFFFFFF
+        nv = int(valid.sum())
+        assert valid[:nv].all() and nv == min(topk, N)
+        got = ids[q, :nv].astype(np.int64)
+        assert len(np.unique(got)) == nv and got.max() < N
+        assert (np.abs(dist[q, :nv] - D[q, got]) <= tol(D[q, got])).all()
+        assert (np.diff(dist[q, :nv]) >= 0).all()
+        lst, lo, hi, clean = tiled_loop_analysis(P[q], D[q], float(sigma[q]), topk, bounds, lambda x: 1e-5 * (abs(x) + 1.0))
+        if not clean:
+            continue
+        nclean += 1
+        assert np.array_equal(lst.astype(np.uint32), want_ids[q])          # the analysis agrees with the oracle
+        assert np.array_equal(ids[q], want_ids[q]), q
+        assert lo <= ref[q] <= hi and lo <= want_refined[q] <= hi, (q, lo, ref[q], hi)
+    assert nclean >= Q // 2, nclean
+    if len(bounds) == 2:
+        assert (ref == N).all()
+    # argument errors: tiles from different codebook shapes, a workspace too small
+    other = b.icq_index_create(_dev(torch, cfg["codebooks"][: K - 1]), _dev(torch, cfg["codes"][: K - 1, :64]), min(Kf, K - 1)) \
+        if K > 1 else None
+    if other is not None:
+        with pytest.raises(b.IcqError):
+            b.icq_running_workspace_bytes(tiles + [other], Q, cap, topk)
+        b.icq_index_destroy(other)
+    with pytest.raises(b.IcqError):
+        b.icq_search_running(tiles, bounds[:-1], _dev(torch, cfg["queries"]), None, cap, topk, out_ids, out_dist, refined,
+                             ws[: ws.numel() // 2 // 256 * 256])
+    for t in tiles:
+        b.icq_index_destroy(t)
 
 
 def test_op_counts_match_oracle(gpu):

@@ -594,3 +594,19 @@ def test_fast_set_and_margin_on_codebooks_built_inside_and_outside_psi():
         abs(orc.margin(lam, xi) - lam[outside].sum()) < 1e-15
     assert orc.margin(lam, np.ones(d, dtype=np.uint8)) == 0.0
     assert abs(orc.margin(lam, np.zeros(d, dtype=np.uint8)) - lam.sum()) < 1e-15
+
+
+def test_tiled_loop_analysis_without_a_band_is_the_oracles_tiled_loop():
+    """The helper the GPU parity test judges rounding-sensitive decisions with follows the same loop."""
+    from helpers import tiled_loop_analysis
+    T, codes = _random_case(31, N=5000)
+    Q, N, Kf, topk = T.shape[0], codes.shape[1], 2, 12
+    sigma = np.linspace(0.0, 2.0, Q)
+    bounds = np.array([0, 5, 40, 41, 700, 2500, N])
+    ids, dist, refined = orc.running_search_tiled(T, codes, Kf, sigma, topk, bounds)
+    P = orc.partial(T, codes, Kf)
+    D = orc.adc_exhaustive(T, codes, topk, want_all=True)[2]
+    for q in range(Q):
+        got, lo, hi, clean = tiled_loop_analysis(P[q], D[q], sigma[q], topk, bounds, lambda x: 0.0)
+        assert clean and lo == hi == refined[q]
+        assert np.array_equal(got.astype(np.uint32), ids[q])
