@@ -404,6 +404,78 @@ void icq_oracle_encode(const float *codebooks, int K, int m, int d, const float 
     }
 }
 
+/* ||x_i - xbar_i||^2 of given codes (Sec. 1: xbar_i = sum_k c_{k,code_k(i)}; the quantity
+ * the quantizers of Sec. 2 minimise).  codes [K][N]; err_out [N]. */
+void icq_oracle_quantization_error(const float *codebooks, int K, int m, int d, const float *x,
+                                   int64_t N, const uint8_t *codes, double *err_out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i) {
+        double s = 0.0;
+        for (int e = 0; e < d; ++e) {
+            double xb = 0.0;
+            for (int k = 0; k < K; ++k)
+                xb += (double)codebooks[((size_t)k * m + codes[(size_t)k * N + i]) * d + e];
+            const double diff = (double)x[(size_t)i * d + e] - xb;
+            s += diff * diff;
+        }
+        err_out[i] = s;
+    }
+}
+
+/* Refinement of given codes by coordinate descent over the codebooks (iterated
+ * conditional modes; the paper gives no assignment algorithm, and the greedy
+ * assignment above never revisits a choice).  One sweep takes the codebooks in
+ * order k = 0 .. K-1; with all other sub-codes of the item fixed,
+ *     r = x_i - sum_{l != k} c_{l,code_l(i)},
+ *     j* = argmin_j || r - c_{k,j} ||^2   (smallest j among exact minima),
+ * and code_k(i) becomes j* only if that is strictly nearer than the current
+ * codeword (so ||x_i - xbar_i||^2 never grows, and equal choices keep what is
+ * there).  r is formed from scratch for every step.  codes [K][N] in and out;
+ * changed_out [sweeps] (may be NULL) = sub-codes changed in each sweep. */
+void icq_oracle_encode_icm(const float *codebooks, int K, int m, int d, const float *x,
+                           int64_t N, uint8_t *codes, int sweeps, int64_t *changed_out)
+{
+    for (int sw = 0; sw < sweeps; ++sw) {
+        int64_t changed = 0;
+#pragma omp parallel
+        {
+            double *r = (double *)malloc(sizeof(double) * (size_t)d);
+#pragma omp for schedule(static) reduction(+ : changed)
+            for (int64_t i = 0; i < N; ++i) {
+                for (int k = 0; k < K; ++k) {
+                    for (int e = 0; e < d; ++e) {
+                        double others = 0.0;
+                        for (int l = 0; l < K; ++l)
+                            if (l != k)
+                                others += (double)codebooks[((size_t)l * m + codes[(size_t)l * N + i]) * d + e];
+                        r[e] = (double)x[(size_t)i * d + e] - others;
+                    }
+                    const int old = codes[(size_t)k * N + i];
+                    int best = 0;
+                    double best_s = INFINITY, old_s = INFINITY;
+                    for (int j = 0; j < m; ++j) {
+                        const float *c = codebooks + ((size_t)k * m + j) * d;
+                        double sq = 0.0;
+                        for (int e = 0; e < d; ++e) {
+                            const double diff = r[e] - (double)c[e];
+                            sq += diff * diff;
+                        }
+                        if (sq < best_s) { best_s = sq; best = j; }
+                        if (j == old) old_s = sq;
+                    }
+                    if (best_s < old_s) {
+                        codes[(size_t)k * N + i] = (uint8_t)best;
+                        ++changed;
+                    }
+                }
+            }
+            free(r);
+        }
+        if (changed_out) changed_out[sw] = changed;
+    }
+}
+
 /* ---- quantities around the fast set (Sec. 3.1 - 3.4); none is on the search path ---- */
 
 /* Population mean and variance of a batch per dimension (what Sec. 3.2 calls the

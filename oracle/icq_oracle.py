@@ -73,9 +73,11 @@ def _load():
         lib.icq_oracle_margin.argtypes = [c_d, c_u8, i]
         lib.icq_oracle_margin.restype = dbl
         lib.icq_oracle_encode.argtypes = [c_f, i, i, i, c_f, i64, c_u8, c_d]
+        lib.icq_oracle_quantization_error.argtypes = [c_f, i, i, i, c_f, i64, c_u8, c_d]
+        lib.icq_oracle_encode_icm.argtypes = [c_f, i, i, i, c_f, i64, c_u8, i, c_i64]
         lib.icq_oracle_threads.restype = i
         for name in ("lut", "partial", "search", "adc_exhaustive", "reconstruct", "bruteforce_knn",
-                     "running_search", "running_search_tiled", "sample_thresholds", "op_counts", "encode",
+                     "running_search", "running_search_tiled", "sample_thresholds", "op_counts", "encode", "quantization_error", "encode_icm",
                      "batch_moments", "online_variance", "subspace_mask", "fast_set"):
             getattr(lib, "icq_oracle_" + name).restype = None
         _lib = lib
@@ -229,6 +231,32 @@ def encode(codebooks, x, want_err=False):
     _load().icq_oracle_encode(_p(cb, ctypes.c_float), K, m, d, _p(xs, ctypes.c_float), N,
                               _p(codes, ctypes.c_uint8), _p(err, ctypes.c_double))
     return (codes, err) if want_err else codes
+
+
+def quantization_error(codebooks, x, codes):
+    """||x_i - xbar_i||^2 [N] f64 of codes [K][N]."""
+    K, m, d = codebooks.shape
+    cb = _chk(codebooks, np.float32, (K, m, d))
+    N = x.shape[0]
+    xs = _chk(x, np.float32, (N, d))
+    cd = _chk(codes, np.uint8, (K, N))
+    err = np.empty((N,), dtype=np.float64)
+    _load().icq_oracle_quantization_error(_p(cb, ctypes.c_float), K, m, d, _p(xs, ctypes.c_float), N,
+                                          _p(cd, ctypes.c_uint8), _p(err, ctypes.c_double))
+    return err
+
+
+def encode_icm(codebooks, x, codes, sweeps):
+    """Coordinate descent over the codebooks from the given codes [K][N]; returns (codes, changed [sweeps])."""
+    K, m, d = codebooks.shape
+    cb = _chk(codebooks, np.float32, (K, m, d))
+    N = x.shape[0]
+    xs = _chk(x, np.float32, (N, d))
+    cd = _chk(codes, np.uint8, (K, N)).copy()
+    changed = np.zeros((max(sweeps, 0),), dtype=np.int64)
+    _load().icq_oracle_encode_icm(_p(cb, ctypes.c_float), K, m, d, _p(xs, ctypes.c_float), N,
+                                  _p(cd, ctypes.c_uint8), sweeps, _p(changed, ctypes.c_int64))
+    return cd, changed
 
 
 def batch_moments(x):

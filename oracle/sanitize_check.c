@@ -130,6 +130,17 @@ static void one_case(int K, int Kf, int m, int d, int64_t N, int Q, int topk, in
         printf("\n");
         print_f64("encode err", err, (size_t)(n_items + 3));
         icq_oracle_encode(cb, K, m, d, x, n_items + 3, enc, NULL);
+        {
+            int64_t changed[3];
+            for (size_t i = 0; i < (size_t)K * (size_t)(n_items + 3); ++i) enc[i] = (uint8_t)(rnd() % (uint32_t)m);
+            icq_oracle_quantization_error(cb, K, m, d, x, n_items + 3, enc, err);
+            print_f64("error of random codes", err, (size_t)(n_items + 3));
+            icq_oracle_encode_icm(cb, K, m, d, x, n_items + 3, enc, 3, changed);
+            print_i64("icm changed", changed, 3);
+            icq_oracle_encode_icm(cb, K, m, d, x, n_items + 3, enc, 0, NULL);
+            icq_oracle_quantization_error(cb, K, m, d, x, n_items + 3, enc, err);
+            print_f64("error after icm", err, (size_t)(n_items + 3));
+        }
         free(xbar); free(x); free(enc); free(err);
     }
     icq_oracle_bruteforce_knn(cb, K, m, d, codes, N, queries, Q, topk, ids, dist);

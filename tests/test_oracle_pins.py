@@ -534,6 +534,104 @@ def test_encode_returns_the_codes_of_a_reconstruction():
     assert (err == 0).all()
 
 
+def _errors_numpy(cb, x, codes):
+    rec = np.zeros((x.shape[0], x.shape[1]))
+    for k in range(cb.shape[0]):
+        rec += cb[k].astype(np.float64)[codes[k]]
+    return ((x.astype(np.float64) - rec) ** 2).sum(axis=1)
+
+
+def test_quantization_error_is_the_squared_distance_to_the_reconstruction():
+    g = _rng(34)
+    K, m, d, N = 4, 50, 13, 200
+    cb = g.standard_normal((K, m, d)).astype(np.float32)
+    x = g.standard_normal((N, d)).astype(np.float32)
+    codes = g.integers(0, m, size=(K, N), dtype=np.uint8)
+    err = orc.quantization_error(cb, x, codes)
+    assert np.allclose(err, _errors_numpy(cb, x, codes), rtol=1e-12, atol=1e-15)
+    rec = orc.reconstruct(cb, codes, np.arange(N))
+    assert np.allclose(err, ((x.astype(np.float64) - rec) ** 2).sum(axis=1), rtol=1e-12, atol=1e-15)
+    # the greedy encoder's own error output is the same quantity
+    codes_g, err_g = orc.encode(cb, x, want_err=True)
+    assert np.allclose(orc.quantization_error(cb, x, codes_g), err_g, rtol=1e-10, atol=1e-13)
+
+
+def test_icm_never_increases_the_error_and_ends_where_no_single_change_helps():
+    g = _rng(35)
+    K, m, d, N = 4, 16, 10, 120
+    cb = (g.standard_normal((K, m, d)) * (0.8 ** np.arange(K))[:, None, None]).astype(np.float32)
+    x = (g.standard_normal((N, d)) * 1.5).astype(np.float32)
+    for start in (orc.encode(cb, x), g.integers(0, m, size=(K, N), dtype=np.uint8)):
+        codes, prev = start.copy(), orc.quantization_error(cb, x, start)
+        same0, ch0 = orc.encode_icm(cb, x, codes, 0)
+        assert np.array_equal(same0, codes) and ch0.size == 0
+        for sweep in range(30):
+            nxt, changed = orc.encode_icm(cb, x, codes, 1)
+            err = orc.quantization_error(cb, x, nxt)
+            assert (err <= prev * (1 + 1e-12) + 1e-15).all()              # never worse, item by item
+            assert changed[0] == (nxt != codes).sum()
+            strictly = err < prev * (1 - 1e-12)
+            assert ((nxt != codes).any(axis=0) <= strictly).all()       # a change always pays
+            codes, prev = nxt, err
+            if changed[0] == 0:
+                break
+        assert changed[0] == 0, "no fixed point after 30 sweeps"
+        # several sweeps in one call = the same sweeps one by one
+        multi, ch = orc.encode_icm(cb, x, start, sweep + 1)
+        assert np.array_equal(multi, codes) and ch[-1] == 0
+        # fixed point: brute force over every single sub-code change finds nothing strictly better
+        cb64 = cb.astype(np.float64)
+        for k in range(K):
+            rest = x.astype(np.float64) - sum(cb64[l][codes[l]] for l in range(K) if l != k)
+            d2 = ((rest[:, None, :] - cb64[k][None, :, :]) ** 2).sum(axis=2)
+            assert (d2.min(axis=1) >= prev * (1 - 1e-12) - 1e-15).all()
+
+
+def test_icm_against_brute_force_on_a_tiny_codebook_set():
+    """m^K = 125 combinations: the optimum is a fixed point, and refinement started from the greedy
+    codes ends between the optimum and the greedy error."""
+    g = _rng(36)
+    K, m, d, N = 3, 5, 4, 300
+    cb = g.standard_normal((K, m, d)).astype(np.float32)
+    x = g.standard_normal((N, d)).astype(np.float32)
+    cb64, x64 = cb.astype(np.float64), x.astype(np.float64)
+    best = np.full(N, np.inf)
+    arg = np.zeros((K, N), dtype=np.uint8)
+    for j0 in range(m):
+        for j1 in range(m):
+            for j2 in range(m):
+                e = ((x64 - (cb64[0, j0] + cb64[1, j1] + cb64[2, j2])) ** 2).sum(axis=1)
+                better = e < best
+                best[better] = e[better]
+                arg[:, better] = np.array([[j0], [j1], [j2]], dtype=np.uint8)
+    stay, changed = orc.encode_icm(cb, x, arg, 2)
+    assert np.array_equal(stay, arg) and (changed == 0).all()
+    greedy, err_g = orc.encode(cb, x, want_err=True)
+    refined, _ = orc.encode_icm(cb, x, greedy, 20)
+    err_r = orc.quantization_error(cb, x, refined)
+    assert (err_r >= best - 1e-12).all() and (err_r <= err_g + 1e-12).all()
+    assert err_r.mean() < err_g.mean() and (err_r < err_g - 1e-9).sum() > N // 10    # and it does help
+    assert (np.abs(err_r - best) < 1e-12).mean() > 0.5                                # often all the way
+
+
+def test_icm_on_disjoint_supports_reaches_the_optimum_in_one_sweep_from_anywhere():
+    g = _rng(37)
+    K, m, d, N = 3, 4, 7, 60
+    cb, groups = disjoint_support_codebooks(g, K, m, d)
+    x = g.standard_normal((N, d)).astype(np.float32)
+    optimum = orc.encode(cb, x)                    # pinned above as the brute-force optimum
+    start = g.integers(0, m, size=(K, N), dtype=np.uint8)
+    one, _ = orc.encode_icm(cb, x, start, 1)
+    e1, e0 = orc.quantization_error(cb, x, one), orc.quantization_error(cb, x, optimum)
+    assert np.allclose(e1, e0, rtol=1e-12, atol=1e-15)
+    # with one codebook a sweep is the nearest codeword whatever the start
+    cb1 = g.standard_normal((1, 30, 5)).astype(np.float32)
+    x1 = g.standard_normal((80, 5)).astype(np.float32)
+    c1, _ = orc.encode_icm(cb1, x1, g.integers(0, 30, size=(1, 80), dtype=np.uint8), 1)
+    assert np.allclose(orc.quantization_error(cb1, x1, c1), orc.quantization_error(cb1, x1, orc.encode(cb1, x1)),
+                       rtol=1e-12, atol=1e-15)
+
+
 # ================================================================ quantities around the fast set
 def test_online_variance_equals_the_variance_of_the_concatenated_batches():
     g = _rng(41)
