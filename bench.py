@@ -344,9 +344,37 @@ def encode_leg(torch, b, cfg, steps):
     d_pad = (d + 15) // 16 * 16
     flops = 2.0 * N * K * 256 * d_pad
     ach = flops / (ms * 1e-3) / 1e12
+    # quality: mean ||x - xbar||^2 of the planted codes (the noise), of the greedy codes, and of the
+    # greedy codes after sweeps of coordinate descent over the codebooks (icq_encode_refine)
+    err = torch.empty((N,), dtype=torch.float64, device="cuda")
+
+    def mean_err(c):
+        b.icq_quantization_error(index, x, c, err)
+        return float(err.mean().item())
+    e_planted = mean_err(src.to(torch.uint8).contiguous())
+    e_greedy = mean_err(codes)
+    sweeps = 4
+    changed = torch.zeros((sweeps,), dtype=torch.int32, device="cuda")
+    greedy = codes.clone()
+    refined = codes.clone()
+
+    def refine():
+        refined.copy_(greedy)
+        b.icq_encode_refine(index, x, refined, sweeps, changed, ws)
+    refine()
+    torch.cuda.synchronize()
+    ms_refine = event_time_ms(torch, refine, max(3, steps))
+    e_refined = mean_err(refined)
+    same_r = float((refined == src.to(torch.uint8)).all(dim=0).float().mean().item())
+    x_norm2 = float((x.double() ** 2).sum(dim=1).mean().item())
     return {"bound": "mfma", "kernel": "encode_level_kernel", "achieved": round(ach, 2), "peak": 157.3,
             "unit": "TFLOP/s", "frac": round(ach / 157.3, 4), "traffic": None, "ms": round(ms, 4),
             "items_per_s": round(N / (ms * 1e-3), 1), "N": N, "codes_recovered_frac": round(same, 4),
+            "mean_sq_error": {"planted_codes": round(e_planted, 4), "greedy": round(e_greedy, 4),
+                              "greedy_then_%d_sweeps" % sweeps: round(e_refined, 4), "mean_sq_norm_of_x": round(x_norm2, 2)},
+            "refine": {"sweeps": sweeps, "ms": round(ms_refine, 4), "subcodes_changed_per_sweep": changed.cpu().tolist(),
+                       "codes_recovered_frac": round(same_r, 4),
+                       "TFLOPs": round(flops * sweeps / (ms_refine * 1e-3) / 1e12, 2)},
             "note": "%d launches (one per codebook); flops = 2*N*K*256*d_pad; fp32 inputs on "
                     "v_mfma_f32_32x32x2_f32; each level also rewrites the N x d residuals" % K}
 
@@ -767,8 +795,9 @@ def main():
     if not args.no_encode_leg:
         log("[bench] greedy encoding of vectors of the workload's shape")
         result["encode"] = encode_leg(torch, b, cfg, max(3, args.steps // 4))
-        log("[bench] encode: %.3f ms for %d items, %.1f TFLOP/s" %
-            (result["encode"]["ms"], result["encode"]["N"], result["encode"]["achieved"]))
+        log("[bench] encode: %.3f ms for %d items, %.1f TFLOP/s; mean squared error %s; %d refinement sweeps %.3f ms" %
+            (result["encode"]["ms"], result["encode"]["N"], result["encode"]["achieved"],
+             result["encode"]["mean_sq_error"], result["encode"]["refine"]["sweeps"], result["encode"]["refine"]["ms"]))
 
     del ws, index, cb, codes, queries
     torch.cuda.empty_cache()

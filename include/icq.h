@@ -319,6 +319,27 @@ int icq_encode(const icq_index *index, const float *x, int64_t N, uint8_t *codes
                size_t workspace_bytes, void *stream);
 
 /*
+ * Refinement of given codes by coordinate descent over the codebooks (iterated
+ * conditional modes; the greedy assignment above never revisits a choice).  One
+ * sweep takes the codebooks in order; with the item's other sub-codes fixed,
+ *     r = x_i - sum_{l != k} c_{l,code_l(i)},   j* = argmin_j ||r - c_{k,j}||^2,
+ * and code_k(i) becomes j* only if it is strictly nearer than the current
+ * codeword (equal scores keep what is there), so ||x_i - xbar_i||^2 does not
+ * grow beyond the rounding of the fp32 scores.  codes [K][N] in and out;
+ * 0 <= sweeps <= ICQ_MAX_SWEEPS; changed_out: device [sweeps] or NULL, the
+ * number of sub-codes replaced in each sweep (a sweep that replaces none has
+ * reached a point no single change improves); workspace as icq_encode.
+ *
+ * icq_quantization_error: err_out[i] = ||x_i - xbar_i||^2 of given codes,
+ * accumulated in double (device [N]).
+ */
+#define ICQ_MAX_SWEEPS 64
+int icq_encode_refine(const icq_index *index, const float *x, int64_t N, uint8_t *codes, int sweeps,
+                      uint32_t *changed_out, void *workspace, size_t workspace_bytes, void *stream);
+int icq_quantization_error(const icq_index *index, const float *x, int64_t N, const uint8_t *codes,
+                           double *err_out, void *stream);
+
+/*
  * Quantities around the fast set (Sec. 3.1 - 3.4).  Small utilities, none on
  * the search path; all arrays are device memory, variances and the prior are
  * handled in double.

@@ -42,6 +42,8 @@ SIGNATURES = {
     "icq_op_counts": (_i, [_vp, _vp, _i, _vp, _vp, _vp]),
     "icq_encode_workspace_bytes": (_i, [_vp, _i64, ctypes.POINTER(_sz)]),
     "icq_encode": (_i, [_vp, _vp, _i64, _vp, _vp, _sz, _vp]),
+    "icq_encode_refine": (_i, [_vp, _vp, _i64, _vp, _i, _vp, _vp, _sz, _vp]),
+    "icq_quantization_error": (_i, [_vp, _vp, _i64, _vp, _vp, _vp]),
     "icq_batch_moments": (_i, [_vp, _i64, _i, _vp, _vp, _vp]),
     "icq_online_variance_update": (_i, [_vp, _vp, _vp, _vp, _i, _i64, _vp]),
     "icq_subspace_mask": (_i, [_vp, _i] + [ctypes.c_double] * 6 + [_vp, _vp]),
@@ -273,6 +275,25 @@ def icq_encode(index, x, codes_out, workspace):
                              _dev(codes_out, torch.uint8, (index.K, N), "codes_out"),
                              _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()),
            "icq_encode")
+
+
+def icq_encode_refine(index, x, codes, sweeps, changed_out, workspace):
+    """codes [K][N] u8 in/out; changed_out: [sweeps] int32 device tensor or None."""
+    N = x.shape[0]
+    _check(load().icq_encode_refine(index.handle, _dev(x, torch.float32, (N, index.d), "x"), N,
+                                    _dev(codes, torch.uint8, (index.K, N), "codes"), int(sweeps),
+                                    _dev(changed_out, torch.int32, (sweeps,), "changed_out") if changed_out is not None else None,
+                                    _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream()),
+           "icq_encode_refine")
+
+
+def icq_quantization_error(index, x, codes, err_out):
+    """err_out [N] float64 (device) = ||x - reconstruction||^2 of codes [K][N]."""
+    N = x.shape[0]
+    _check(load().icq_quantization_error(index.handle, _dev(x, torch.float32, (N, index.d), "x"), N,
+                                         _dev(codes, torch.uint8, (index.K, N), "codes"),
+                                         _dev(err_out, torch.float64, (N,), "err_out"), _stream()),
+           "icq_quantization_error")
 
 
 def icq_batch_moments(x, mean_out, var_out):

@@ -8,6 +8,13 @@
 // is one [N x d].[d x 256] contraction on the fp32 matrix cores with the epilogue
 // argmin_j (||c_j||^2 - 2<r,c_j>), followed by the residual update of the block's own
 // rows.
+//
+// icq_encode_refine revisits given codes by coordinate descent over the codebooks (iterated
+// conditional modes): with the other sub-codes of an item fixed, codebook k's codeword becomes the
+// nearest one to r = x - sum_{l != k} c_l, and only if that is strictly nearer than the current
+// one.  The kernel is the same contraction: the residual array holds x - xbar, a level adds the
+// current codeword back while staging its rows, the argmin prefers the current codeword among equal
+// scores, and only rows whose sub-code changed are rewritten.
 #include "icq_internal.h"
 #include "icq_sort.h"
 
@@ -34,16 +41,21 @@ constexpr int E_THREADS = 256;
 // 2x2 accumulators of 32x32 (MFMA 32x32x2 layout: lane l supplies A[l%32][l/32] and
 // B[l/32][l%32]; accumulator register v of lane l is C[(v%4) + 4*(l/32) + 8*(v/4)][l%32]).
 // src: x (row stride d, level 0) or the residuals (row stride d_pad); dst: residuals.
+// ICM: src = res holds x - xbar, codes_k holds the current sub-codes (in and out), *changed counts
+// the sub-codes replaced.
+template <bool ICM>
 __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
     const float *src, int src_stride, int d, const float *__restrict__ cb_k, int d_pad,
-    const float *__restrict__ cnorm_k, int64_t N, uint8_t *__restrict__ codes_k, float *res, int vec_ok) {
+    const float *__restrict__ cnorm_k, int64_t N, uint8_t *codes_k, float *res, int vec_ok, uint32_t *changed) {
     __shared__ float As[EK][EM + 1];
     __shared__ float Bs[EK][EN + 1];
     __shared__ u64 best[E_THREADS / 64][EM];
     __shared__ uint32_t s_code[EM];
+    __shared__ uint32_t s_old[EM];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t i0 = (int64_t)blockIdx.x * EM;
     const int le = tid & 15, lr = tid >> 4;       // reduction position and row (+16 per pass) of the staging loads
+    if (ICM && tid < EM) s_old[tid] = codes_k[i0 + tid < N ? i0 + tid : N - 1];     // visible after the first slice's barrier
 
     float16v acc[2][2];
 #pragma unroll
@@ -56,17 +68,20 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
     // columns past d read column d - 1 (the codebook copy is zero there, the product vanishes):
     // no load depends on a condition, so a slice's twenty are in flight together.
     const float *arow[EM / 16];
+    const float *orow[EM / 16];                   // ICM: the row's current codeword, added back while staging
 #pragma unroll
     for (int p = 0; p < EM / 16; ++p) {
         const int64_t row = i0 + lr + 16 * p;
-        arow[p] = src + (row < N ? row : N - 1) * src_stride;
+        const int64_t rc = row < N ? row : N - 1;
+        arow[p] = src + rc * src_stride;
+        orow[p] = ICM ? cb_k + (int64_t)codes_k[rc] * d_pad : cb_k;
     }
     for (int k0 = 0; k0 < d_pad; k0 += EK) {
         float a[EM / 16], b[EN / 16];
         const int e = k0 + le;
         const int ec = e < d ? e : d - 1;
 #pragma unroll
-        for (int p = 0; p < EM / 16; ++p) a[p] = arow[p][ec];
+        for (int p = 0; p < EM / 16; ++p) a[p] = ICM ? arow[p][ec] + orow[p][e] : arow[p][ec];
 #pragma unroll
         for (int p = 0; p < EN / 16; ++p) b[p] = cb_k[(int64_t)(lr + 16 * p) * d_pad + e];
         __syncthreads();   // previous slice fully consumed
@@ -92,6 +107,7 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
     }
     // argmin over the wavefront's 64 codewords for each of the 64 rows: key = (order-preserving bits
     // of ||c||^2 - 2<r,c>, codeword index), the smaller key wins, so equal scores go to the smaller index
+    // (ICM: index + 1, and 0 for the row's current codeword, which so wins among equal scores)
     float cn[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) cn[j] = cnorm_k[wave * 64 + j * 32 + (lane & 31)];
@@ -100,10 +116,13 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             u64 key = ~0ull;
+            const uint32_t cur = ICM ? s_old[i * 32 + (v & 3) + 4 * (lane >> 5) + 8 * (v >> 2)] : 0u;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const float score = cn[j] - 2.0f * acc[i][j][v];
-                const u64 kj = ((u64)icq_order_bits(score) << 32) | (uint32_t)(wave * 64 + j * 32 + (lane & 31));
+                const uint32_t col = (uint32_t)(wave * 64 + j * 32 + (lane & 31));
+                const uint32_t field = ICM ? (col == cur ? 0u : col + 1u) : col;
+                const u64 kj = ((u64)icq_order_bits(score) << 32) | field;
                 key = kj < key ? kj : key;
             }
             // minimum over each half of 32 lanes on the DPP path (row shifts, then lane 15 of rows 0 and 2
@@ -121,9 +140,15 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
         u64 key = best[0][tid];
 #pragma unroll
         for (int w = 1; w < E_THREADS / 64; ++w) key = best[w][tid] < key ? best[w][tid] : key;
-        const uint32_t code = (uint32_t)key;
+        const uint32_t field = (uint32_t)key;
+        const uint32_t code = ICM ? (field == 0u ? s_old[tid] : field - 1u) : field;
         s_code[tid] = code;
-        if (i0 + tid < N) codes_k[i0 + tid] = (uint8_t)code;
+        const bool store = i0 + tid < N && (!ICM || code != s_old[tid]);
+        if (store) codes_k[i0 + tid] = (uint8_t)code;
+        if (ICM && changed) {                      // tid < 64: the first wavefront, whole
+            const int n = __builtin_popcountll(__ballot(store));
+            if (tid == 0 && n > 0) atomicAdd(changed, (uint32_t)n);
+        }
     }
     __syncthreads();
     // residual update of the block's rows (zero beyond d, so later levels can read whole slices)
@@ -141,6 +166,7 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
         for (int it = 0; it < nit; it += U) {
             float4 xa[U], ca[U];
             int64_t off[U];
+            bool keep[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int idx = (it + u < nit ? it + u : it) * E_THREADS + tid;
@@ -148,10 +174,15 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
                 xa[u] = src4[(i0 + r) * src_row4 + e4];
                 ca[u] = cb4[(int64_t)s_code[r] * row4 + e4];
                 off[u] = (i0 + r) * row4 + e4;
+                keep[u] = ICM && s_code[r] == s_old[r];
+                if (ICM) {
+                    const float4 co = cb4[(int64_t)s_old[r] * row4 + e4];
+                    xa[u] = make_float4(xa[u].x + co.x, xa[u].y + co.y, xa[u].z + co.z, xa[u].w + co.w);
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (it + u < nit)                         // block-uniform
+                if (it + u < nit && !keep[u])             // the first condition is block-uniform
                     res4[off[u]] = make_float4(xa[u].x - ca[u].x, xa[u].y - ca[u].y, xa[u].z - ca[u].z, xa[u].w - ca[u].w);
             }
         }
@@ -160,11 +191,48 @@ __global__ __launch_bounds__(E_THREADS) void encode_level_kernel(
     for (int idx = tid; idx < EM * d_pad; idx += E_THREADS) {
         const int r = idx / d_pad, e = idx % d_pad;
         const int64_t row = i0 + r;
-        if (row < N) {
-            const float xv = e < d ? src[row * src_stride + e] : 0.0f;
+        if (row < N && !(ICM && s_code[r] == s_old[r])) {
+            float xv = e < d ? src[row * src_stride + e] : 0.0f;
+            if (ICM) xv += cb_k[(int64_t)s_old[r] * d_pad + e];
             res[row * d_pad + e] = xv - cb_k[(int64_t)s_code[r] * d_pad + e];
         }
     }
+}
+
+// res[n][e] = x[n][e] - sum_k c_{k,code_k(n)}[e] (k ascending), zero beyond d: what the refinement starts from.
+__global__ void residual_kernel(const float *__restrict__ x, int d, int d_pad, const float *__restrict__ cb, int K,
+                                const uint8_t *__restrict__ codes, int64_t N, float *__restrict__ res) {
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= N * d_pad) return;
+    const int64_t n = idx / d_pad;
+    const int e = (int)(idx % d_pad);
+    float r = e < d ? x[n * d + e] : 0.0f;
+    for (int k = 0; k < K; ++k) r -= cb[((int64_t)k * ICQ_LUT_W + codes[(int64_t)k * N + n]) * d_pad + e];
+    res[idx] = r;
+}
+
+__global__ void zero_words_kernel(uint32_t *p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// One wavefront per item: ||x - sum_k c_{k,code_k}||^2 accumulated in double.
+__global__ __launch_bounds__(256) void quantization_error_kernel(const float *__restrict__ x, int d, int d_pad,
+                                                                 const float *__restrict__ cb, int K,
+                                                                 const uint8_t *__restrict__ codes, int64_t N,
+                                                                 double *__restrict__ err) {
+    const int64_t n = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= N) return;                            // whole wavefronts leave together
+    const int lane = threadIdx.x & 63;
+    double s = 0.0;
+    for (int e = lane; e < d; e += 64) {
+        double xb = 0.0;
+        for (int k = 0; k < K; ++k) xb += (double)cb[((int64_t)k * ICQ_LUT_W + codes[(int64_t)k * N + n]) * d_pad + e];
+        const double diff = (double)x[n * d + e] - xb;
+        s += diff * diff;
+    }
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) err[n] = s;
 }
 
 }  // namespace
@@ -194,9 +262,47 @@ ICQ_EXPORT int icq_encode(const icq_index *ix, const float *x, int64_t N, uint8_
         // (slices, then the update) precedes its write in program order behind a barrier
         const float *cbk = ix->cb + (size_t)k * ICQ_LUT_W * ix->d_pad;
         const int vec_ok = ix->d == ix->d_pad && stride % 4 == 0 && (uintptr_t)src % 16 == 0 && (uintptr_t)cbk % 16 == 0;
-        encode_level_kernel<<<blocks, E_THREADS, 0, s>>>(src, stride, ix->d, cbk, ix->d_pad,
-                                                         ix->cnorm + (size_t)k * ICQ_LUT_W, N,
-                                                         codes_out + (size_t)k * N, res, vec_ok);
+        encode_level_kernel<false><<<blocks, E_THREADS, 0, s>>>(src, stride, ix->d, cbk, ix->d_pad,
+                                                                ix->cnorm + (size_t)k * ICQ_LUT_W, N,
+                                                                codes_out + (size_t)k * N, res, vec_ok, nullptr);
     }
+    return icq_check_launch();
+}
+
+ICQ_EXPORT int icq_encode_refine(const icq_index *ix, const float *x, int64_t N, uint8_t *codes, int sweeps,
+                                 uint32_t *changed_out, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!ix || N < 0 || N > ICQ_MAX_N || sweeps < 0 || sweeps > ICQ_MAX_SWEEPS) return ICQ_ERR_ARG;
+    if (N == 0 || sweeps == 0) return ICQ_OK;
+    if (!x || !codes) return ICQ_ERR_ARG;
+    size_t need = 0;
+    (void)icq_encode_workspace_bytes(ix, N, &need);
+    if (!workspace || ((uintptr_t)workspace % ICQ_ALIGN) != 0 || workspace_bytes < need) return ICQ_ERR_WORKSPACE;
+    float *res = static_cast<float *>(workspace);
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t total = N * ix->d_pad;
+    residual_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(x, ix->d, ix->d_pad, ix->cb, ix->K, codes, N, res);
+    if (changed_out) zero_words_kernel<<<(sweeps + 255) / 256, 256, 0, s>>>(changed_out, sweeps);
+    const unsigned blocks = (unsigned)((N + EM - 1) / EM);
+    for (int sw = 0; sw < sweeps; ++sw) {
+        for (int k = 0; k < ix->K; ++k) {
+            // in place: a block reads and writes only its own rows and sub-codes, reads first
+            const float *cbk = ix->cb + (size_t)k * ICQ_LUT_W * ix->d_pad;
+            const int vec_ok = ix->d == ix->d_pad && (uintptr_t)cbk % 16 == 0;
+            encode_level_kernel<true><<<blocks, E_THREADS, 0, s>>>(res, ix->d_pad, ix->d, cbk, ix->d_pad,
+                                                                   ix->cnorm + (size_t)k * ICQ_LUT_W, N,
+                                                                   codes + (size_t)k * N, res, vec_ok,
+                                                                   changed_out ? changed_out + sw : nullptr);
+        }
+    }
+    return icq_check_launch();
+}
+
+ICQ_EXPORT int icq_quantization_error(const icq_index *ix, const float *x, int64_t N, const uint8_t *codes,
+                                      double *err_out, void *stream) {
+    if (!ix || N < 0 || N > ICQ_MAX_N) return ICQ_ERR_ARG;
+    if (N == 0) return ICQ_OK;
+    if (!x || !codes || !err_out) return ICQ_ERR_ARG;
+    quantization_error_kernel<<<(unsigned)((N + 3) / 4), 256, 0, (hipStream_t)stream>>>(x, ix->d, ix->d_pad, ix->cb, ix->K,
+                                                                                         codes, N, err_out);
     return icq_check_launch();
 }

@@ -84,6 +84,8 @@ def test_host_side_argument_checks_of_the_policy_encoding_and_utility_calls():
     assert lib.icq_op_counts(None, one, 1, one, one, None) == E
     assert lib.icq_encode_workspace_bytes(None, 10, ctypes.byref(out)) == E
     assert lib.icq_encode(None, one, 10, one, one, 1 << 20, None) == E
+    assert lib.icq_encode_refine(None, one, 10, one, 1, None, one, 1 << 20, None) == E
+    assert lib.icq_quantization_error(None, one, 10, one, one, None) == E
     # the utilities take no index: bad sizes and null pointers
     assert lib.icq_batch_moments(one, -1, 4, one, one, None) == E
     assert lib.icq_batch_moments(one, 10, 0, one, one, None) == E

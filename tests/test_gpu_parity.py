@@ -887,6 +887,93 @@ def test_encode_on_disjoint_supports_recovers_the_codes(gpu):
     assert np.array_equal(back.cpu().numpy(), codes)
 
 
+@pytest.mark.parametrize("K,m,d,N,sweeps,start", [
+    (8, 256, 128, 5_000, 3, "greedy"), (4, 256, 32, 1_000, 2, "random"), (16, 256, 96, 777, 2, "greedy"),
+    (3, 100, 17, 130, 4, "random"), (1, 256, 8, 64, 1, "random"), (2, 7, 5, 1, 2, "greedy")])
+def test_encode_refine_matches_oracle(gpu, K, m, d, N, sweeps, start):
+    """Coordinate descent over the codebooks from the same starting codes on both sides.  fp32 scores
+    may order near-ties differently and a different choice changes every later step, so each GPU
+    sweep is judged given the GPU's own codes before it: level by level the chosen codeword must be
+    a nearest one up to the tolerance and a replaced one must not have been clearly nearer; the
+    error never grows beyond the tolerance; the counts of replaced sub-codes are exact; and the
+    end result is as good as the oracle's, mostly identical."""
+    torch, b = gpu
+    rng = np.random.default_rng(K * 1000 + d + 1)
+    cb = (rng.standard_normal((K, m, d)) * (0.8 ** np.arange(K))[:, None, None]).astype(np.float32)
+    src = rng.integers(0, m, size=(K, N))
+    x = np.ascontiguousarray(sum(cb[k][src[k]] for k in range(K)) + 0.3 * rng.standard_normal((N, d)), dtype=np.float32)
+    first = orc.encode(cb, x) if start == "greedy" else rng.integers(0, m, size=(K, N)).astype(np.uint8)
+    index = b.icq_index_create(_dev(torch, cb), torch.empty((K, 0), dtype=torch.uint8, device="cuda"), min(2, K))
+    ws = torch.empty(b.icq_encode_workspace_bytes(index, N), dtype=torch.uint8, device="cuda")
+    xd = _dev(torch, x)
+    # the error call against the oracle's
+    err = torch.empty((N,), dtype=torch.float64, device="cuda")
+    b.icq_quantization_error(index, xd, _dev(torch, first), err)
+    torch.cuda.synchronize()
+    err0 = orc.quantization_error(cb, x, first)
+    assert np.allclose(err.cpu().numpy(), err0, rtol=1e-10, atol=1e-12)
+    # all sweeps in one call, and one by one
+    codes_all = _dev(torch, first)
+    changed_all = torch.full((sweeps,), -1, dtype=torch.int32, device="cuda")
+    b.icq_encode_refine(index, xd, codes_all, sweeps, changed_all, ws)
+    cur = _dev(torch, first)
+    one = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    cb64, x64, n = cb.astype(np.float64), x.astype(np.float64), np.arange(N)
+    before, prev_err = first.copy(), err0
+    for sw in range(sweeps):
+        b.icq_encode_refine(index, xd, cur, 1, one, ws)
+        torch.cuda.synchronize()
+        after = cur.cpu().numpy()
+        assert (after < m).all()
+        assert int(one.cpu()[0]) == int((after != before).sum()) == int(changed_all.cpu()[sw])
+        for k in range(K):
+            state = np.concatenate([after[:k], before[k:]])          # the codes this level saw
+            r = x64 - sum(cb64[l][state[l]] for l in range(K) if l != k)
+            d2 = ((r[:, None, :] - cb64[k][None, :, :]) ** 2).sum(axis=2) if N * m * d < 4e7 else \
+                (r * r).sum(axis=1)[:, None] - 2.0 * r @ cb64[k].T + (cb64[k] ** 2).sum(axis=1)[None, :]
+            chosen, old, best = d2[n, after[k]], d2[n, before[k]], d2.min(axis=1)
+            assert (chosen <= best + tol(best)).all(), "sweep %d level %d: a clearly nearer codeword exists" % (sw, k)
+            moved = after[k] != before[k]
+            assert (chosen[moved] <= old[moved] + tol(old[moved])).all(), "replaced a clearly nearer codeword"
+        e = orc.quantization_error(cb, x, after)
+        assert (e <= prev_err + tol(prev_err)).all()
+        before, prev_err = after, e
+    assert np.array_equal(codes_all.cpu().numpy(), before)            # one call = the same sweeps one by one
+    want, want_changed = orc.encode_icm(cb, x, first, sweeps)
+    e_want = orc.quantization_error(cb, x, want)
+    assert abs(prev_err.mean() - e_want.mean()) <= 0.01 * e_want.mean() + 1e-12
+    assert (before == want).all(axis=0).mean() >= 0.9
+    assert prev_err.mean() <= err0.mean()
+    # no sweeps: untouched; too many: refused
+    b.icq_encode_refine(index, xd, cur, 0, None, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(cur.cpu().numpy(), before)
+    with pytest.raises(b.IcqError):
+        b.icq_encode_refine(index, xd, cur, 65, None, ws)
+    with pytest.raises(b.IcqError):
+        b.icq_encode_refine(index, xd, cur, 1, None, ws[:128])
+
+
+def test_encode_refine_on_disjoint_supports_finds_the_planted_codes_in_one_sweep(gpu):
+    torch, b = gpu
+    rng = np.random.default_rng(78)
+    K, m, d, N = 8, 256, 64, 20_000
+    cb = np.zeros((K, m, d), dtype=np.float32)
+    groups = np.array_split(rng.permutation(d), K)
+    for k in range(K):
+        cb[k][:, groups[k]] = rng.standard_normal((m, len(groups[k]))).astype(np.float32)
+    codes = rng.integers(0, m, size=(K, N)).astype(np.uint8)
+    x = orc.reconstruct(cb, codes, np.arange(N)).astype(np.float32)
+    index = b.icq_index_create(_dev(torch, cb), torch.empty((K, 0), dtype=torch.uint8, device="cuda"), 2)
+    cur = _dev(torch, rng.integers(0, m, size=(K, N)).astype(np.uint8))
+    changed = torch.zeros((2,), dtype=torch.int32, device="cuda")
+    ws = torch.empty(b.icq_encode_workspace_bytes(index, N), dtype=torch.uint8, device="cuda")
+    b.icq_encode_refine(index, _dev(torch, x), cur, 2, changed, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(cur.cpu().numpy(), codes)
+    assert int(changed.cpu()[1]) == 0 and int(changed.cpu()[0]) > 0
+
+
 # ------------------------------------------------------------------ quantities around the fast set
 def test_moments_online_variance_mask_fast_set_and_margin_match_oracle(gpu):
     torch, b = gpu
