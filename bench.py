@@ -1,15 +1,18 @@
 #!/usr/bin/env python3
 """Throughput of the ICQ query-time path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--streams 2]
 
 A step is one pass of the whole path (table build, stage-1 scan, stage-2 refine,
 top-k) over the workload's whole query set, one icq_search call per query batch of
 the size the workload names, inputs resident in HBM.  The default workload is the
 largest one: N = 1e8 items, K = 16, Kf = 4, 1000 queries in batches of 128, top-100.
+The calls of a step alternate between two HIP streams (one workspace each), so one
+batch's stage 2 runs beside the next batch's stage 1; the same steps are timed on
+one stream first, and the stage times and rooflines come from that pass.
 Prints ONE JSON line: queries/s; `roofline` for the dominant kernel of that step
 with the resource that binds it, its work model and the time of its launches
-measured by events on the launch stream inside the timed calls; the same for
+measured by events on the launch stream inside the one-stream calls; the same for
 stage 2; the step with stage 1 walking all Kf fast rows item by item; the stage-1
 scan on a 400 MB fast-code array with one, two and four queries per pass (bound by
 HBM); the CPU oracle timed on the host cores as a baseline, its lists doubling as
@@ -379,6 +382,19 @@ def encode_leg(torch, b, cfg, steps):
                     "v_mfma_f32_32x32x2_f32; each level also rewrites the N x d residuals" % K}
 
 
+def counted_vector_instructions(kernel, workload):
+    """Wavefront vector instructions per launch of `kernel` on `workload` from the committed SQ
+    counter summary (line `issue <kernel> <workload> <count>` in profiles/sq_counters_<workload>.txt)."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "sq_counters_%s.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 4 and f[0] == "issue" and f[1] == kernel and f[2] == workload:
+            return float(f[3])
+    return None
+
+
 def pmc_traffic(kernel, workload):
     """HBM-side bytes per launch of `kernel` on `workload` from the committed counter summary
     (two rocprofv3 --pmc runs of this program, scaled by what the counters read for a copy of
@@ -581,6 +597,9 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C4")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="HIP streams the step's icq_search calls alternate between (each with a workspace of its "
+                         "own); 1 = all calls on one stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hbm-leg", action="store_true")
     ap.add_argument("--no-streamed-leg", action="store_true")
@@ -657,13 +676,46 @@ def main():
         assert batches == 1, "the workspace must hold a whole query batch"
         return ms, stage, calls
 
-    ms_per_step, stage, calls = timed(args.steps, args.warmup)
+    # One stream first: the library's stage events are recorded inside these calls, undisturbed by
+    # other work on the GPU; the rooflines below use them.
+    ms_one_stream, stage, calls = timed(args.steps, args.warmup)
+    ms_per_step = ms_one_stream
+    nstreams = max(1, min(args.streams, nbatches))
+    if nstreams > 1:
+        # The timed region of record: the same calls alternating between streams, so that one batch's
+        # stage 2 (bound by record gathers) runs beside the next batch's stage 1 (bound by vector issue).
+        wss = [ws] + [torch.empty(ws_bytes, dtype=torch.uint8, device="cuda") for _ in range(nstreams - 1)]
+        streams = [torch.cuda.Stream() for _ in range(nstreams)]          # default priority
+
+        def step_streams():
+            cur = torch.cuda.current_stream()
+            for st in streams:
+                st.wait_stream(cur)
+            for i, q0 in enumerate(range(0, Q, batch)):
+                with torch.cuda.stream(streams[i % nstreams]):
+                    b.icq_search(index, queries[q0:q0 + batch], thr[q0:q0 + batch], cap, topk, out_ids[q0:q0 + batch],
+                                 out_dist[q0:q0 + batch], surv[q0:q0 + batch], wss[i % nstreams])
+            for st in streams:
+                cur.wait_stream(st)
+        ids_one = out_ids.clone()
+        for _ in range(args.warmup):
+            step_streams()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_streams()
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+        assert bool((out_ids == ids_one).all()), "the calls on several streams gave other lists"
+        del wss, streams, ids_one
+        torch.cuda.empty_cache()
+        log("[bench] %d streams: %.3f ms/step (one stream: %.3f)" % (nstreams, ms_per_step, ms_one_stream))
     surv_np = surv.cpu().numpy().view(np.uint32)
     overflow = int((surv_np > cap).sum())
     n_surv_batch = float(np.minimum(surv_np, cap).sum()) / nbatches
-    log("[bench] %.3f ms/step (%d calls); per call (events, mean of %d calls): lut %.3f, stage 1 %.3f, stage 2 %.3f ms; "
+    log("[bench] one stream: %.3f ms/step (%d calls); per call (events, mean of %d calls): lut %.3f, stage 1 %.3f, stage 2 %.3f ms; "
         "survivors mean %.0f max %d, overflowed lists %d" %
-        (ms_per_step, nbatches, calls, stage[0], stage[1], stage[2], surv_np.mean(), surv_np.max(), overflow))
+        (ms_one_stream, nbatches, calls, stage[0], stage[1], stage[2], surv_np.mean(), surv_np.max(), overflow))
     gpu_ids = out_ids.cpu().numpy().view(np.uint32)
     gpu_dist = out_dist.cpu().numpy()
     qmean = Q / nbatches                       # queries per call (the last batch may be short)
@@ -679,14 +731,23 @@ def main():
         # move -- per survivor its K code bytes, per query its K tables and result rows -- next to
         # the bytes the counters saw, which are fewer: the kernel skips tuples its list's bound excludes.
         alg_bytes = n_surv_batch * K + 4.0 * qmean * K * 256 + 8.0 * qmean * topk
-        achieved = alg_bytes / (stage[1] * 1e-3) / 1e9
         tr = pmc_traffic("group_keys_kernel", wl)
-        roofline = {"bound": "hbm", "kernel": kern1, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": alg_bytes,
+        insts = counted_vector_instructions("group_keys_kernel", wl)
+        issue_peak = 256 * 4 * 2.4e9 / 4.0 / 1e9          # G wavefront instructions/s: one per SIMD every 4 clocks
+        ach = insts / (stage[1] * 1e-3) / 1e9 if insts else None
+        roofline = {"bound": "issue", "kernel": kern1, "achieved": round(ach, 1) if ach else None, "peak": issue_peak,
+                    "unit": "G wavefront vector instructions/s", "frac": round(ach / issue_peak, 4) if ach else None,
+                    "ms": round(stage[1], 4), "vector_instructions_per_launch": insts,
+                    "instructions_source": "profiles/sq_counters_%s.txt (committed rocprofv3 run)" % wl if insts else None,
+                    "hbm": {"algorithmic_bytes": alg_bytes, "achieved_GBs": round(alg_bytes / (stage[1] * 1e-3) / 1e9, 1),
+                            "peak_GBs": HBM_PEAK_GBS, "frac": round(alg_bytes / (stage[1] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
                     "traffic": tr["bytes"] if tr else None, "traffic_source": tr["source"] if tr else None,
-                    "ms": round(stage[1], 4),
-                    "note": "algorithmic bytes = survivors*K + Q*4*K*256 + Q*topk*8 per launch over the stage-1 event pair; "
-                            "the kernel itself is bound by instruction issue and moves fewer bytes than that (traffic)"}
+                    "note": "bound by instruction issue: achieved = the wavefront vector instructions one launch issues "
+                            "(SQ_INSTS_VALU of the committed counter run; the work depends on the data -- which tuples the "
+                            "list's bound excludes -- so it is counted, not modelled) over the stage-1 event time of this "
+                            "run; peak = 256 CU x 4 SIMD x 2.4 GHz / 4 clocks.  hbm: the bytes the method must move "
+                            "(survivors*K + Q*4*K*256 + Q*topk*8) against 8 TB/s, for reference only: the kernel skips the "
+                            "tuples its bound excludes and moves fewer bytes than that (traffic)"}
     else:
         # Item-by-item stage 1: bound by the vector ALUs (every (query, position) pair costs a few
         # plain vector instructions whatever the memory system does; SQ counters in profiles/).
@@ -722,13 +783,17 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: d=%d K=%d Kf=%d m=256 N=%d Q=%d in batches of %d, top-%d, ~%.0f%% survive stage 1" %
                    (args.workload, d, K, Kf, N, Q, batch, topk, 100 * SURVIVE_FRAC),
-                   "batch": batch, "calls_per_step": nbatches, "cap": cap, "overflowed_lists": overflow,
+                   "batch": batch, "calls_per_step": nbatches, "streams": nstreams, "cap": cap, "overflowed_lists": overflow,
                    "survivors_mean": round(float(surv_np.mean()), 1),
                    "stage1": {"tuples": "one evaluation per fast-code tuple, distances and lists in the same kernel",
                               "pairs": "items ordered by their first two fast sub-codes, remaining fast rows streamed",
                               "items": "all fast rows streamed item by item"}[form],
                    "stage1_to_stage2": "hit bits" if bits else ("on chip" if form == "tuples" else "candidate lists")},
-        "stages_ms_per_call": {"build_lut": round(stage[0], 4), "stage1": round(stage[1], 4), "stage2": round(stage[2], 4)},
+        "ms_per_step_one_stream": round(ms_one_stream, 4),
+        "stages_ms_per_call": {"build_lut": round(stage[0], 4), "stage1": round(stage[1], 4), "stage2": round(stage[2], 4),
+                               "measured": "the library's events inside the calls of the one-stream pass (%d steps, timed "
+                                           "before the pass of record); with %d streams the calls of a step overlap, so "
+                                           "calls_per_step x their sum exceeds ms_per_step" % (args.steps, nstreams)},
         "roofline": roofline,
     }
     if form != "tuples":

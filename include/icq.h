@@ -14,9 +14,11 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Every call only enqueues work on `stream` and returns; results are valid
  *    once the stream has been synchronised (icq_index_create also waits for
- *    its own counting pass before it sizes the grouped layouts).  Calls on one index from several
- *    host threads are safe as long as they do not share output or workspace
- *    buffers.
+ *    its own counting pass before it sizes the grouped layouts).  Calls on one
+ *    index from several host threads, or on several streams, are safe as long
+ *    as they do not share output or workspace buffers (with stage timing off):
+ *    searches of different query batches on two streams overlap, one batch's
+ *    exact comparisons running beside the next batch's crude ones.
  *  - Return value: ICQ_OK (0) or a negative ICQ_ERR_* code.  Arguments are
  *    checked on the host before anything is launched; an argument or
  *    workspace error means nothing has been enqueued (ICQ_ERR_HIP can come from
