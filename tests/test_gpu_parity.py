@@ -806,6 +806,64 @@ def test_running_search_in_tiles_matches_oracle(gpu, name, N, Q, over, topk, bou
         b.icq_index_destroy(t)
 
 
+def test_running_search_at_full_size_sampled_against_oracle(gpu):
+    """The largest workload (N = 1e8, K = 16, Kf = 4) in the launch configuration bench.py times: 13 tiles
+    of doubling size, one batch of 128 queries; four of them against the oracle's tiled loop, the rest by
+    properties."""
+    import bench
+    torch, b = gpu
+    cfg = synth.make("C4", Q=128)
+    N, Q, K, Kf, topk = cfg["N"], 128, cfg["K"], cfg["Kf"], cfg["topk"]
+    bounds = bench.tile_bounds(N)
+    cb = _dev(torch, cfg["codebooks"])
+    codes = _dev(torch, cfg["codes"])
+    tiles = [b.icq_index_create(cb, codes[:, a:e].contiguous(), Kf) for a, e in zip(bounds[:-1], bounds[1:])]
+    del codes
+    cbv = cfg["codebooks"].astype(np.float64)
+    sig = float(sum(cbv[k].var(axis=0).sum() for k in range(Kf, K)))
+    sigma = torch.full((Q,), sig, dtype=torch.float32, device="cuda")
+    cap = max(bounds[1], int(N * 0.02))
+    out_ids = torch.empty((Q, topk), dtype=torch.int32, device="cuda")
+    out_dist = torch.empty((Q, topk), dtype=torch.float32, device="cuda")
+    refined = torch.empty((Q,), dtype=torch.int32, device="cuda")
+    ws = torch.empty(b.icq_running_workspace_bytes(tiles, Q, cap, topk), dtype=torch.uint8, device="cuda")
+    b.icq_search_running(tiles, bounds[:-1], _dev(torch, cfg["queries"]), sigma, cap, topk, out_ids, out_dist, refined, ws)
+    torch.cuda.synchronize()
+    ids, dist, ref = _u32(out_ids), out_dist.cpu().numpy().astype(np.float64), _u32(refined)
+    for t in tiles:
+        b.icq_index_destroy(t)
+    del ws
+    torch.cuda.empty_cache()
+    assert (ids < N).all() and (np.diff(dist, axis=1) >= 0).all()
+    assert (np.diff(np.sort(ids, axis=1).astype(np.int64), axis=1) > 0).all(), "duplicate ids in a result"
+    assert (ref >= bounds[1]).all() and ref.mean() < 0.01 * N          # the first tile whole, then a tightening threshold
+    sample = np.array([0, 41, 86, 127])
+    T = orc.lut(cfg["codebooks"], cfg["queries"][sample])
+    want_ids, _, want_refined = orc.running_search_tiled(T, cfg["codes"], Kf, np.full(sample.size, float(np.float32(sig))),
+                                                         topk, np.array(bounds))
+    nclean = 0
+    for r, q in enumerate(sample):
+        P = orc.partial(T[r:r + 1], cfg["codes"], Kf)[0]
+        D = orc.partial(T[r:r + 1], cfg["codes"], K)[0]
+        got = ids[q].astype(np.int64)
+        assert (np.abs(dist[q] - D[got]) <= tol(D[got])).all()
+        lst, lo, hi, clean = tiled_loop_analysis(P, D, float(np.float32(sig)), topk, bounds, lambda x: 1e-5 * (abs(x) + 1.0))
+        if clean:
+            nclean += 1
+            assert np.array_equal(lst.astype(np.uint32), want_ids[r])
+            assert np.array_equal(ids[q], want_ids[r])
+            assert lo <= ref[q] <= hi and lo <= want_refined[r] <= hi
+        else:
+            # At this size some decision of every query hangs on rounding (the 100 nearest of 1e8 items lie
+            # closer together than the band); the two runs then part ways by a few items, no more
+            same = np.intersect1d(ids[q], want_ids[r]).size
+            print("query %d: %d of %d ids as the oracle's, exact comparisons %d (oracle %d, band %d..%d)"
+                  % (q, same, topk, ref[q], want_refined[r], lo, hi))
+            assert same >= 0.95 * topk
+            assert abs(int(ref[q]) - int(want_refined[r])) <= 0.05 * want_refined[r]
+        del P, D
+
+
 def test_op_counts_match_oracle(gpu):
     torch, b = gpu
     cfg = small("C1", 5_000, 300)
