@@ -568,19 +568,35 @@ def stage1_kernel_name(Kf, K, N, Qb, topk, mode_streamed=False):
         return "group_keys_kernel<%d,%d,%s>" % (Kf, index_words(K), "true" if topk <= 256 and K <= 16 else "false")
     if Kf > 4:
         return "scan_items_kernel"
+    if form == "pairs" and bits and Qb >= 6:
+        return "scan_pairs_q16_kernel<%d>" % (Kf - 2)
     B = 4 if Qb >= 3 else Qb
     return "scan_stream_kernel<%d,%d,false,%s,%s>" % (Kf - 2 if form == "pairs" else Kf, B,
                                                        "true" if form == "pairs" else "false", "true" if bits else "false")
 
 
-def stage1_model(Kf, npos, Qb, pairs):
+def stage1_model(Kf, npos, Qb, pairs, q16=False):
     """Work of ONE launch of the item-by-item stage-1 kernel over npos scan positions for Qb
-    queries, four queries per pass.  Per (query, position): one table read per streamed row, the
-    additions of Eq. 2 left of the threshold, one comparison, one instruction that collects the hit
-    bit; per position and pass: one byte extraction and one address per streamed row (shared by
-    the pass's four queries).  pairs: the first two entries' sum comes once per 16 positions (not
-    counted) and is one more addition per (query, position)."""
+    queries.  fp32 form, four queries per pass -- per (query, position): one table read per
+    streamed row, the additions of Eq. 2 left of the threshold, one comparison, one instruction
+    that collects the hit bit; per position and pass: one byte extraction and one address per
+    streamed row (shared by the pass's four queries).  pairs: the first two entries' sum comes once
+    per 16 positions (not counted) and is one more addition per (query, position).
+    q16 (the 16-bit pre-filter over the pair ordering, eight queries per pass): a packed
+    instruction serves two queries, so per position and pass there are one address per streamed
+    row, and per PAIR of queries one saturating addition per streamed row, one sign extraction and
+    one instruction that collects the two hit bits; per 16 positions and pass about 40 more (the
+    pair's part of the sum, the tests that let a pair of queries sit a step out, masks, stores).
+    alu_ops counts lanes of wavefront instructions either way."""
     R = Kf - 2 if pairs else Kf
+    if q16:
+        passes = (Qb + 7) // 8
+        return {"positions": npos, "queries": Qb, "passes": passes, "streamed_rows": R,
+                "alu_ops": npos * passes * (R + 4 * (R + 2)) + npos // 16 * passes * 40,
+                "lds_addresses": npos * passes * R,
+                "table_entries": npos * Qb * R,
+                "code_bytes": npos * passes * R + npos * passes // 4,
+                "hit_bit_bytes": npos * Qb // 8}
     adds = R if pairs else R - 1
     passes = (Qb + 3) // 4 if Qb >= 3 else 1
     return {"positions": npos, "queries": Qb, "passes": passes, "streamed_rows": R,
@@ -751,10 +767,11 @@ def main():
     else:
         # Item-by-item stage 1: bound by the vector ALUs (every (query, position) pair costs a few
         # plain vector instructions whatever the memory system does; SQ counters in profiles/).
-        m = stage1_model(Kf, npos, int(round(qmean)), form == "pairs")
+        q16 = kern1.startswith("scan_pairs_q16")
+        m = stage1_model(Kf, npos, int(round(qmean)), form == "pairs", q16)
         t = stage[1] * 1e-3
         ach = m["alu_ops"] / t / 1e12
-        tr = pmc_traffic(kern1.split("<")[0] + ("_pairs" if form == "pairs" else "_items"), wl)
+        tr = pmc_traffic("scan_pairs_q16_kernel" if q16 else kern1.split("<")[0] + ("_pairs" if form == "pairs" else "_items"), wl)
         roofline = {"bound": "alu", "kernel": kern1, "achieved": round(ach, 3), "peak": round(ALU_PEAK_TOPS, 2),
                     "unit": "Tops/s", "frac": round(ach / ALU_PEAK_TOPS, 4), "ms": round(stage[1], 4),
                     "work_model": m,
@@ -765,11 +782,11 @@ def main():
                             "achieved_GBs": round((m["code_bytes"] + m["hit_bit_bytes"]) / t / 1e9, 1), "peak_GBs": HBM_PEAK_GBS,
                             "frac": round((m["code_bytes"] + m["hit_bit_bytes"]) / t / 1e9 / HBM_PEAK_GBS, 4)},
                     "traffic": tr["bytes"] if tr else None, "traffic_source": tr["source"] if tr else None,
-                    "note": "one launch per icq_search call; duration = the stage-1 event pair inside the timed calls "
-                            "(counter fill .. after the scan kernel).  achieved = plain vector operations of the work "
-                            "model (alu_ops: additions, comparison and hit-bit collection per (query, position), byte "
-                            "extraction and table address per position and pass) per second; peak = 256 CU x 4 SIMD x "
-                            "16 lanes x 2.4 GHz.  lds / hbm: the same launch against the other two resources "
+                    "note": "one launch per icq_search call; duration = the stage-1 event pair inside the one-stream calls "
+                            "(counter fill .. after the scan kernel).  achieved = lanes of the vector instructions of the "
+                            "work model (alu_ops; see stage1_model in bench.py: additions, comparison or sign, hit-bit "
+                            "collection, table addresses -- packed 16-bit instructions serve two queries each in the "
+                            "16-bit pre-filter) per second; peak = 256 CU x 4 SIMD x 16 lanes x 2.4 GHz.  lds / hbm: the same launch against the other two resources "
                             "(LDS: lane addresses against the 7.72e12 per second measured for 16-byte reads; HBM: code "
                             "rows per pass plus the hit bits written -- all passes but the first are served by the caches, "
                             "see traffic).  The vector peak is the rate of three-operand and compare instructions; "
@@ -786,7 +803,9 @@ def main():
                    "batch": batch, "calls_per_step": nbatches, "streams": nstreams, "cap": cap, "overflowed_lists": overflow,
                    "survivors_mean": round(float(surv_np.mean()), 1),
                    "stage1": {"tuples": "one evaluation per fast-code tuple, distances and lists in the same kernel",
-                              "pairs": "items ordered by their first two fast sub-codes, remaining fast rows streamed",
+                              "pairs": "items ordered by their first two fast sub-codes, remaining fast rows streamed"
+                                       + (" through a conservative 16-bit pre-filter, eight queries per pass; stage 2 "
+                                          "applies the exact comparison" if kern1.startswith("scan_pairs_q16") else ""),
                               "items": "all fast rows streamed item by item"}[form],
                    "stage1_to_stage2": "hit bits" if bits else ("on chip" if form == "tuples" else "candidate lists")},
         "ms_per_step_one_stream": round(ms_one_stream, 4),

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libicq.so")
 BUILD_DIR = os.path.join(ROOT, "_build")
-SOURCES = ["icq_index.hip", "icq_lut.hip", "icq_scan.hip", "icq_group.hip", "icq_group2.hip", "icq_refine.hip", "icq_search.hip", "icq_running.hip", "icq_policy.hip", "icq_encode.hip", "icq_probe.hip"]
+SOURCES = ["icq_index.hip", "icq_lut.hip", "icq_scan.hip", "icq_scan16.hip", "icq_group.hip", "icq_group2.hip", "icq_refine.hip", "icq_search.hip", "icq_running.hip", "icq_policy.hip", "icq_encode.hip", "icq_probe.hip"]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
     "-Wall", "-Wno-unused-command-line-argument",

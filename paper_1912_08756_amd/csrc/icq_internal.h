@@ -125,12 +125,18 @@ int icq_search_impl(const icq_index *ix, const float *queries, const float *lut_
                     void *workspace, size_t workspace_bytes, void *stream);
 int icq_launch_scan_masks(const icq_index *ix, const float *lut, int Q, const float *thr, uint16_t *masks,
                           size_t mask_stride, int64_t scan_end, uint32_t *cand_count, uint32_t *key_count,
-                          hipEvent_t after_fill, hipStream_t s);
+                          hipEvent_t after_fill, bool *superset, hipStream_t s);
+// The 16-bit pre-filter over the pair ordering (icq_scan16.hip): hit bits of a superset of the survivors.
+bool icq_scan_q16_usable(const icq_index *ix, int Q);
+int icq_launch_scan_masks_q16(const icq_index *ix, const float *lut, int Q, const float *thr, uint16_t *masks,
+                              size_t mask_stride, int64_t scan_end, hipStream_t s);
 // Stage 2 from hit bits; keys [Q][cap] (+ slice lists in front, see icq_cand_keys); adds the survivors to cand_count.
+// thr != nullptr: the bits mark a superset of the survivors, and an item counts only if its crude distance
+// (the first Kf terms of the sum, the additions of Eq. 2) is below thr[q].
 int icq_launch_refine_masks(const icq_index *ix, const float *lut, int Q, const uint16_t *masks, size_t mask_stride,
                             int64_t scan_end, int64_t cap, int topk, int splits, unsigned long long *keys,
-                            uint32_t *key_count, uint32_t *cand_count, uint32_t *out_ids, float *out_dist,
-                            hipStream_t s);
+                            uint32_t *key_count, uint32_t *cand_count, const float *thr, uint32_t *out_ids,
+                            float *out_dist, hipStream_t s);
 
 // Kernel launchers (each checks nothing; the extern "C" entry points validate).
 int icq_launch_build_lut(const icq_index *ix, const float *queries, int Q, float *lut,

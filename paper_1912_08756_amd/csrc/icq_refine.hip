@@ -552,12 +552,17 @@ static_assert(RM_LIST % (64 * RM_PER) == 0, "a round of the list is whole steps 
 
 // QPB queries per block: their tables sit in LDS side by side and every chunk is worked through for one
 // query after the other, so the later ones find the chunk's records in the cache for certain.
-template <int WORDS, bool FILTER, int QPB>
-__global__ __launch_bounds__(RM_THREADS) void refine_mask_kernel(
+// EXACT: the hit bits mark a superset of the survivors (the 16-bit pre-filter of stage 1); an item is a
+// survivor when the first Kf terms of its sum -- the crude distance of Eq. 2, the same fp32 additions
+// stage 1 makes item by item -- are below thr[q].  Only survivors are counted and get keys.
+// The filtered launch is held to the registers of five wavefronts per SIMD (the exact comparison's few
+// more would cost the fifth: 1.17 -> 1.29 ms for the stage at N = 1e8).
+template <int WORDS, bool FILTER, int QPB, bool EXACT>
+__global__ __launch_bounds__(RM_THREADS, FILTER ? 5 : 1) void refine_mask_kernel(
     const uint8_t *__restrict__ items, int K, const float *__restrict__ lut, const uint32_t *__restrict__ masks,
     size_t mask_words, const uint32_t *__restrict__ perm, uint32_t nsel, uint32_t seed_every, int window, int Q,
     const float *__restrict__ kth_dist, int topk, u64 *__restrict__ keys, uint32_t *__restrict__ key_count,
-    int64_t cap, uint32_t *__restrict__ cand_count) {
+    int64_t cap, uint32_t *__restrict__ cand_count, const float *__restrict__ thr, int Kf) {
     __shared__ __attribute__((aligned(16))) float T_all[QPB][4 * WORDS * ICQ_LUT_W];
     __shared__ uint32_t cand_all[RM_WAVES][RM_LIST];
     constexpr int RW = WORDS;
@@ -618,8 +623,9 @@ __global__ __launch_bounds__(RM_THREADS) void refine_mask_kernel(
     }
     __syncthreads();                                  // the only barrier: from here on every wavefront is on its own
     uint32_t survivors[QPB];                          // of this wavefront's chunks (wavefront-uniform)
+    uint32_t lane_survivors[QPB];                     // EXACT: counted per lane, summed at the end
 #pragma unroll
-    for (int g = 0; g < QPB; ++g) survivors[g] = 0;
+    for (int g = 0; g < QPB; ++g) survivors[g] = lane_survivors[g] = 0;
     while (c != 0xFFFFFFFFu) {
         uint32_t w[RM_WORDS];
 #pragma unroll
@@ -637,6 +643,7 @@ __global__ __launch_bounds__(RM_THREADS) void refine_mask_kernel(
             for (int r = 0; r < RM_WORDS; ++r) nxt[r] = mn[r * 64];
         }
         const uint32_t q = q0 + qq;
+        const float tq = EXACT ? thr[q] : 0.0f;
         const float *T = T_all[QPB == 1 ? 0 : qq];
         uint32_t bound = bound_all[0];
 #pragma unroll
@@ -648,12 +655,14 @@ __global__ __launch_bounds__(RM_THREADS) void refine_mask_kernel(
         const uint32_t incl = wave_scan_add(mine);
         const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
         const uint32_t off = incl - mine;
+        if (!EXACT) {
 #pragma unroll
-        for (int g = 0; g < QPB; ++g) survivors[g] += qq == (uint32_t)g ? total : 0u;
+            for (int g = 0; g < QPB; ++g) survivors[g] += qq == (uint32_t)g ? total : 0u;
+        }
         // unfiltered: every survivor of the chunk gets a key, so their slots are reserved at once (the atomic's
         // answer travels while the positions are expanded)
         uint32_t chunk_slot = 0;
-        if (!FILTER && total != 0) {
+        if (!FILTER && !EXACT && total != 0) {
             if (lane == 0) chunk_slot = atomicAdd(&key_count[q], total);
         }
         const uint32_t p0 = c * RM_CHUNK + lane * 32u;
@@ -705,21 +714,30 @@ __global__ __launch_bounds__(RM_THREADS) void refine_mask_kernel(
                 for (int u = 0; u < RM_PER; ++u) {
                     // k ascending like every other kernel; the first term stands for 0 + itself (no table holds -0)
                     float d = T[rec[u][0] & 0xffu];
+                    float crude = d;                  // the sum after its first Kf terms (Kf <= 4: inside the first word)
 #pragma unroll
                     for (int x = 0; x < WORDS; ++x) {
 #pragma unroll
-                        for (int b = x == 0 ? 1 : 0; b < 4; ++b)
+                        for (int b = x == 0 ? 1 : 0; b < 4; ++b) {
                             d += T[(x * 4 + b) * ICQ_LUT_W + ((rec[u][x] >> (8 * b)) & 0xffu)];
+                            if (EXACT && x == 0) crude = b < Kf ? d : crude;
+                        }
                     }
                     const uint32_t ob = icq_order_bits(d);
-                    const bool keep = base + (uint32_t)u * 64u + lane < n && ob <= bound;
+                    bool keep = base + (uint32_t)u * 64u + lane < n;
+                    if (EXACT) {
+                        keep = keep && crude < tq;
+#pragma unroll
+                        for (int g = 0; g < QPB; ++g) lane_survivors[g] += (qq == (uint32_t)g && keep) ? 1u : 0u;
+                    }
+                    keep = keep && ob <= bound;
                     mk[u] = __builtin_amdgcn_ballot_w64(keep);
                     mycnt += (uint32_t)__builtin_popcountll(mk[u]);
                     key[u] = (u64)ob << 32;
                 }
                 if (mycnt == 0) continue;             // wavefront-uniform
                 uint32_t slot0 = 0;
-                if (FILTER) {
+                if (FILTER || EXACT) {
                     if (lane == 0) slot0 = atomicAdd(&key_count[q], mycnt);
                     slot0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)slot0);
                 } else {
@@ -739,6 +757,11 @@ __global__ __launch_bounds__(RM_THREADS) void refine_mask_kernel(
         qq = qn;
         j = jn;
         c = cn;
+    }
+    if (EXACT) {
+#pragma unroll
+        for (int g = 0; g < QPB; ++g)
+            survivors[g] = (uint32_t)__builtin_amdgcn_readlane((int)wave_scan_add(lane_survivors[g]), 63);
     }
 #pragma unroll
     for (int g = 0; g < QPB; ++g)
@@ -853,7 +876,7 @@ int64_t icq_mask_scan_end(const icq_index *ix) {
 
 int icq_launch_refine_masks(const icq_index *ix, const float *lut, int Q, const uint16_t *masks, size_t mask_stride,
                             int64_t scan_end, int64_t cap, int topk, int splits, u64 *keys, uint32_t *key_count,
-                            uint32_t *cand_count, uint32_t *out_ids, float *out_dist, hipStream_t s) {
+                            uint32_t *cand_count, const float *thr, uint32_t *out_ids, float *out_dist, hipStream_t s) {
     if (Q == 0) return ICQ_OK;
     const bool g2 = icq_g2_usable(ix);
     const uint8_t *items = g2 ? ix->items_grouped : ix->items;
@@ -887,9 +910,14 @@ int icq_launch_refine_masks(const icq_index *ix, const float *lut, int Q, const 
         const int window = window_for(NSEL, FILTER);                                                               \
         const unsigned nwin = ((NSEL) + 8u * window - 1) / (8u * window);                                    \
         const unsigned ngroups = ((unsigned)Q + RM_QPB - 1) / RM_QPB;                                        \
-        refine_mask_kernel<W, FILTER, RM_QPB><<<nwin * ngroups * 8u, RM_THREADS, 0, s>>>(                     \
-            items, ix->K, lut, m32, mask_words, perm, (NSEL), seed_every, window, Q, out_dist, topk, cand_keys, \
-            key_count, cap, cand_count);                                                                     \
+        if (thr)                                                                                             \
+            refine_mask_kernel<W, FILTER, RM_QPB, true><<<nwin * ngroups * 8u, RM_THREADS, 0, s>>>(           \
+                items, ix->K, lut, m32, mask_words, perm, (NSEL), seed_every, window, Q, out_dist, topk,     \
+                cand_keys, key_count, cap, cand_count, thr, ix->Kf);                                         \
+        else                                                                                                 \
+            refine_mask_kernel<W, FILTER, RM_QPB, false><<<nwin * ngroups * 8u, RM_THREADS, 0, s>>>(          \
+                items, ix->K, lut, m32, mask_words, perm, (NSEL), seed_every, window, Q, out_dist, topk,     \
+                cand_keys, key_count, cap, cand_count, nullptr, ix->Kf);                                     \
     } while (0)
     switch (ix->item_stride) {
         case 4: ICQ_RM_LAUNCH(1, false, nseed); break;

@@ -687,13 +687,20 @@ int icq_launch_scan(const icq_index *ix, const float *lut, int Q, const float *t
     return icq_check_launch();
 }
 
+// *superset: the bits written mark a superset of the survivors (the 16-bit pre-filter); stage 2 then
+// applies the exact comparison itself.
 int icq_launch_scan_masks(const icq_index *ix, const float *lut, int Q, const float *thr, uint16_t *masks,
                           size_t mask_stride, int64_t scan_end, uint32_t *cand_count, uint32_t *key_count,
-                          hipEvent_t after_fill, hipStream_t s) {
+                          hipEvent_t after_fill, bool *superset, hipStream_t s) {
+    *superset = false;
     if (Q == 0) return ICQ_OK;
     zero_counts_kernel<<<(Q + 255) / 256, 256, 0, s>>>(cand_count, Q);
     zero_counts_kernel<<<(Q + 255) / 256, 256, 0, s>>>(key_count, Q);
     if (after_fill) ICQ_HIP_TRY(hipEventRecord(after_fill, s));
+    if (icq_scan_q16_usable(ix, Q)) {
+        *superset = true;
+        return icq_launch_scan_masks_q16(ix, lut, Q, thr, masks, mask_stride, scan_end, s);
+    }
     return launch_stream_any(ix, lut, Q, thr, nullptr, cand_count, 0, masks, mask_stride, scan_end, s);
 }
 

@@ -1,0 +1,276 @@
+// Stage 1 of the two-step search (arxiv 1912.08756, Eq. 2) as a conservative pre-filter in 16-bit
+// integers, for the index ordered by the first two fast sub-codes when icq_search keeps hit bits.
+//
+// The crude comparison P = sum_{k<Kf} T_k[code_k] < t is decided exactly where the item's record
+// is in hand anyway -- by the kernel that forms the exact distance, from the same fp32 additions.
+// What this kernel leaves is a SUPERSET of the survivors, found with a quarter of the work per
+// (query, position): every fast table is replaced by
+//     q_k[c] = max(0, floor((T_k[c] - min T_k) / s) - 1)        (16-bit, never above the true quotient)
+// with one scale s per query chosen so that the threshold falls at 30000 units, and an item passes
+// when  q_0 + q_1 + q_2 (+ q_3) <= floor((t - sum_k min T_k) / s) + 1.  Rounding down every term
+// and up the right side cannot lose a survivor (the slack of one unit per term also covers the
+// rounding of the fp32 sum the exact test uses, which s >= |t| * 2^-18 keeps below a sixteenth of a
+// unit); what it lets through beyond the survivors are items within a few units -- a ten-thousandth
+// of the threshold's distance from the tables' minimum -- of the threshold.
+// Eight queries' 16-bit entries make one 16-byte LDS read, two queries share every packed
+// instruction (saturating adds, the sign of  sum - threshold - 1  is the hit bit), and the byte
+// extraction and table address of a position serve eight queries instead of four.
+#include "icq_internal.h"
+#include "icq_sort.h"
+
+#include <math.h>
+
+namespace {
+
+typedef short short2v __attribute__((ext_vector_type(2)));
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+
+constexpr int QS_THREADS = 1024;
+constexpr int QS_WAVES = QS_THREADS / 64;
+constexpr int QS_B = 8;                  // queries per pass
+constexpr int QS_C = 16;                 // copies of a streamed table's entry: lane l reads copy l % 16
+constexpr int QS_HALF = 4;               // positions whose table reads are issued together
+constexpr float QS_UNITS = 30000.0f;     // where the threshold falls on the 16-bit scale
+
+__device__ __forceinline__ uint32_t lane_id() {
+    return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+__device__ __forceinline__ uint32_t pk_add_sat(uint32_t a, uint32_t b) {
+    const short2v r = __builtin_elementwise_add_sat(__builtin_bit_cast(short2v, a), __builtin_bit_cast(short2v, b));
+    return __builtin_bit_cast(uint32_t, r);
+}
+// 1 in each half whose 16-bit value is negative
+__device__ __forceinline__ uint32_t pk_sign(uint32_t x) {
+    const ushort2v r = __builtin_bit_cast(ushort2v, x) >> (ushort2v){15, 15};
+    return __builtin_bit_cast(uint32_t, r);
+}
+// never above the true quotient (x - base) / s: floor, minus one unit for the rounding of the product
+__device__ __forceinline__ int quantise(float x, float base, float inv_s) {
+    const float v = floorf((x - base) * inv_s) - 1.0f;
+    return (int)fminf(fmaxf(v, 0.0f), 32000.0f);          // a NaN (inf * 0) ends as 0
+}
+
+// KF = Kf - 2 streamed rows.  Grid: x = ranges of scan positions, y = groups of eight queries.
+// masks[q * mask_stride + p / 16] receives the hit bits of positions p .. p + 15 (bit j = position
+// p + j) for every position of the block's range below scan_end, zeros beyond the last item.
+template <int KF>
+__global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
+    const uint8_t *rows, int64_t npad, uint32_t N, const float *__restrict__ lut, int K, const float *__restrict__ thr,
+    int Q, uint32_t items_per_block, const uint32_t *__restrict__ info, uint16_t *__restrict__ masks, size_t mask_stride,
+    uint32_t scan_end) {
+    extern __shared__ __attribute__((aligned(16))) uint4 qs_smem[];
+    __shared__ float s_min[KF + 2][QS_B];
+    __shared__ float s_inv[QS_B];
+    __shared__ int s_thr[QS_B];
+    uint4 *tab = qs_smem;                                   // [KF][256][QS_C]
+    uint4 *t01 = qs_smem + KF * ICQ_LUT_W * QS_C;           // [2][256]
+    const int tid = threadIdx.x;
+    const uint32_t lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int qbase = blockIdx.y * QS_B;
+    constexpr int KFAST = KF + 2;
+
+    const uint32_t begin = blockIdx.x * items_per_block;
+    uint32_t end = begin + items_per_block;
+    if (end > N || end < begin) end = N;
+    uint32_t walk_end = begin + items_per_block;
+    if (walk_end > scan_end || walk_end < begin) walk_end = scan_end;
+    constexpr uint32_t step = (uint32_t)QS_WAVES * 1024u;
+    const uint32_t nsteps = walk_end > begin ? (walk_end - begin + step - 1) / step : 0;
+
+    uint4 w[2][KF];
+    uint32_t ci[2];
+    // 1024 positions at g; past the block's range the block's first positions are read instead
+    // (unused, in bounds: the rows are padded by more than a block step)
+    auto load = [&](uint32_t g, uint4 (&w)[KF], uint32_t &ci) {
+        const uint32_t gs = (g < end && g >= begin) ? g : begin;
+        ci = info[(gs >> 4) + lane];
+#pragma unroll
+        for (int k = 0; k < KF; ++k) w[k] = *reinterpret_cast<const uint4 *>(rows + (int64_t)k * npad + gs + lane * 16);
+    };
+    uint32_t g = begin + wave * 1024u;
+    load(g, w[0], ci[0]);                                   // in flight while the tables are prepared
+
+    auto row_of = [&](int b, int k) -> const float * {
+        const int qb = qbase + b < Q ? qbase + b : Q - 1;   // a slot past the last query: clamped, and never stored
+        return lut + ((int64_t)qb * K + k) * ICQ_LUT_W;
+    };
+    // smallest entry of every fast table of every query: 8 * Kf combinations over 16 wavefronts
+    for (int combo = wave; combo < QS_B * KFAST; combo += QS_WAVES) {
+        const int b = combo % QS_B, k = combo / QS_B;
+        const float *r = row_of(b, k);
+        float m = fminf(fminf(r[lane], r[lane + 64]), fminf(r[lane + 128], r[lane + 192]));
+        m = wave_min_f32(m);
+        if (lane == 0) s_min[k][b] = m;
+    }
+    __syncthreads();
+    if (tid < QS_B) {
+        const float t = qbase + tid < Q ? thr[qbase + tid] : -INFINITY;
+        float L = s_min[0][tid] + s_min[1][tid];            // the order of the additions of Eq. 2
+#pragma unroll
+        for (int k = 2; k < KFAST; ++k) L += s_min[k][tid];
+        float inv = 0.0f;
+        int units = -2;                                     // nothing can pass: t <= L, t = -inf or NaN
+        if (t == INFINITY) {
+            units = (int)QS_UNITS;                          // everything passes (all quotients are 0)
+        } else if (t > L) {
+            const float s = fmaxf(fmaxf((t - L) / QS_UNITS, fabsf(t) * 3.814697265625e-6f), 1e-30f);
+            inv = 1.0f / s;
+            units = (int)fminf(floorf((t - L) * inv) + 1.0f, QS_UNITS);
+        }
+        s_inv[tid] = inv;
+        s_thr[tid] = units;
+    }
+    __syncthreads();
+    // the streamed tables, 16 copies of every entry, eight queries' values side by side; consecutive
+    // threads write consecutive 16-byte pieces
+    auto entry = [&](int k, int c, bool first) -> uint4 {
+        uint32_t h[QS_B];
+#pragma unroll
+        for (int b = 0; b < QS_B; ++b) {
+            int v = quantise(row_of(b, k)[c], s_min[k][b], s_inv[b]);
+            if (first) v -= s_thr[b] + 1;                   // the threshold rides on the first table: a sum below 0 passes
+            h[b] = (uint32_t)v & 0xFFFFu;
+        }
+        return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    };
+#pragma unroll
+    for (int j = 0; j < KF * ICQ_LUT_W * QS_C / QS_THREADS; ++j) {
+        const int p = j * QS_THREADS + tid, e = p / QS_C;
+        tab[p] = entry(2 + e / ICQ_LUT_W, e % ICQ_LUT_W, false);
+    }
+    if (tid < 2 * ICQ_LUT_W) t01[tid] = entry(tid / ICQ_LUT_W, tid % ICQ_LUT_W, tid < ICQ_LUT_W);
+    __syncthreads();
+
+    // A table address is assembled from bytes by one instruction: byte 0 = this lane's copy (times 16),
+    // byte 1 = the sub-code (an entry is 16 copies of 16 bytes), byte 2 = the streamed table.
+    const uint32_t lane_bytes = (lane & (QS_C - 1)) * 16u | 0x100u;      // byte 1 = 1: the source of "table 1"
+    const char *tab_bytes = reinterpret_cast<const char *>(tab);
+    // hit bits of the 1024 positions at g: hm[d] = queries 2d (low half) and 2d + 1, position j in bit 15 - j
+    auto hits = [&](uint32_t g, const uint4 (&w)[KF], uint32_t ci, uint32_t (&hm)[QS_B / 2]) {
+        const uint4 a = t01[ci & 0xffu], c = t01[ICQ_LUT_W + ((ci >> 8) & 0xffu)];
+        uint32_t p01[QS_B / 2];
+        p01[0] = pk_add_sat(a.x, c.x);
+        p01[1] = pk_add_sat(a.y, c.y);
+        p01[2] = pk_add_sat(a.z, c.z);
+        p01[3] = pk_add_sat(a.w, c.w);
+        // the streamed tables add at least 0: a pair of queries whose two sums are not below 0 in any
+        // lane has no hit among the wavefront's 1024 positions
+        bool live[QS_B / 2], any_live = false;
+#pragma unroll
+        for (int d = 0; d < QS_B / 2; ++d) {
+            live[d] = __builtin_amdgcn_ballot_w64((p01[d] & 0x80008000u) != 0u) != 0;   // wavefront-uniform
+            any_live |= live[d];
+        }
+        if (!any_live) return;
+        uint32_t acc[2][QS_B / 2];                           // positions 0 .. 7 and 8 .. 15: eight bits per half
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+            for (int d = 0; d < QS_B / 2; ++d) acc[x][d] = 0;
+#pragma unroll
+        for (int h = 0; h < 16; h += QS_HALF) {
+            uint32_t off[QS_HALF][KF];
+#pragma unroll
+            for (int jj = 0; jj < QS_HALF; ++jj) {
+                const int j = h + jj;
+#pragma unroll
+                for (int k = 0; k < KF; ++k) {
+                    const uint32_t word = j < 4 ? w[k].x : j < 8 ? w[k].y : j < 12 ? w[k].z : w[k].w;
+                    // selector bytes: 0 = lane_bytes byte 0, 4 + n = byte n of the code word, 1 = lane_bytes byte 1, 0x0c = zero
+                    const uint32_t sel = 0x0c000000u | (k == 0 ? 0x000c0000u : 0x00010000u) | ((4u + (j & 3)) << 8);
+                    off[jj][k] = __builtin_amdgcn_perm(word, lane_bytes, sel);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            uint4 v[QS_HALF][KF];
+#pragma unroll
+            for (int jj = 0; jj < QS_HALF; ++jj)
+#pragma unroll
+                for (int k = 0; k < KF; ++k)
+                    v[jj][k] = *reinterpret_cast<const uint4 *>(tab_bytes + off[jj][k]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int d = 0; d < QS_B / 2; ++d) {
+                if (!live[d]) continue;                      // wavefront-uniform
+#pragma unroll
+                for (int jj = 0; jj < QS_HALF; ++jj) {
+                    uint32_t x = p01[d];
+#pragma unroll
+                    for (int k = 0; k < KF; ++k) {
+                        const uint32_t e = d == 0 ? v[jj][k].x : d == 1 ? v[jj][k].y : d == 2 ? v[jj][k].z : v[jj][k].w;
+                        x = pk_add_sat(x, e);
+                    }
+                    // one instruction per step (left to itself the compiler regroups the chain into more)
+                    uint32_t &m = acc[(h + jj) >> 3][d];
+                    asm("v_lshl_or_b32 %0, %1, 1, %2" : "=v"(m) : "v"(m), "v"(pk_sign(x)));
+                }
+            }
+        }
+        // the padding behind a pair's last item, and positions at or beyond the end
+        uint32_t valid = (0xFFFF0000u >> (ci >> 16)) & 0xFFFFu;
+        const uint32_t id0 = g + lane * 16;
+        if (id0 + 16 > end || id0 + 16 < id0) valid &= id0 < end ? 0xFFFFu & ~((1u << (16 - (end - id0))) - 1u) : 0u;
+        valid |= valid << 16;
+#pragma unroll
+        for (int d = 0; d < QS_B / 2; ++d) hm[d] = ((acc[0][d] << 8) | acc[1][d]) & valid;
+    };
+
+    for (uint32_t it = 0; it < nsteps; it += 2, g += 2 * step) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            load(g + (uint32_t)(u + 1) * step, w[(u + 1) % 2], ci[(u + 1) % 2]);        // never conditional
+            const uint32_t gu = g + (uint32_t)u * step;
+            uint32_t hm[QS_B / 2];
+#pragma unroll
+            for (int d = 0; d < QS_B / 2; ++d) hm[d] = 0;
+            if (gu < end && gu >= begin) hits(gu, w[u], ci[u], hm);
+            if (it + u < nsteps) {
+#pragma unroll
+                for (int d = 0; d < QS_B / 2; ++d) {
+                    const uint32_t r = __builtin_bitreverse32(hm[d]);      // first position in bit 0; the halves change places
+                    uint16_t *dst = masks + (size_t)(qbase + 2 * d) * mask_stride + (gu >> 4) + lane;
+                    if (qbase + 2 * d < Q) dst[0] = (uint16_t)(r >> 16);
+                    if (qbase + 2 * d + 1 < Q) dst[mask_stride] = (uint16_t)r;
+                }
+            }
+        }
+    }
+}
+
+template <int KF>
+int launch_q16(const icq_index *ix, const float *lut, int Q, const float *thr, uint16_t *masks, size_t mask_stride,
+               int64_t scan_end, hipStream_t s) {
+    const size_t lds = sizeof(uint4) * (size_t)(KF * ICQ_LUT_W * QS_C + 2 * ICQ_LUT_W);
+    ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&scan_pairs_q16_kernel<KF>), lds));
+    const int groups = (Q + QS_B - 1) / QS_B;
+    const uint32_t step = (uint32_t)QS_WAVES * 1024u;
+    // one wave of equally loaded blocks: the chip is filled once and every block streams a long run
+    int64_t chunks = ((int64_t)ix->num_cu + groups - 1) / groups;
+    const int64_t max_chunks = (scan_end + step - 1) / step;
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (chunks < 1) chunks = 1;
+    const uint32_t per = (uint32_t)(((scan_end + chunks - 1) / chunks + step - 1) / step * step);
+    chunks = (scan_end + per - 1) / per;
+    for (int g0 = 0; g0 < groups; g0 += 65535) {
+        const int ng = groups - g0 < 65535 ? groups - g0 : 65535;
+        const int q0 = g0 * QS_B, nq = (Q - q0) < ng * QS_B ? (Q - q0) : ng * QS_B;
+        dim3 grid((unsigned)chunks, (unsigned)ng);
+        scan_pairs_q16_kernel<KF><<<grid, QS_THREADS, lds, s>>>(
+            ix->g2_rows, ix->g2_npad, (uint32_t)ix->g2_npos, lut + (int64_t)q0 * ix->K * ICQ_LUT_W, ix->K, thr + q0, nq,
+            per, ix->g2_info, masks + (size_t)q0 * mask_stride, mask_stride, (uint32_t)scan_end);
+    }
+    return icq_check_launch();
+}
+
+}  // namespace
+
+// Calls with at least this many queries take the 16-bit pre-filter (below, a pass of eight would be mostly empty slots).
+bool icq_scan_q16_usable(const icq_index *ix, int Q) { return icq_g2_usable(ix) && Q >= 6; }
+
+// Hit bits of a superset of the survivors; the caller's stage 2 applies the exact comparison.
+int icq_launch_scan_masks_q16(const icq_index *ix, const float *lut, int Q, const float *thr, uint16_t *masks,
+                              size_t mask_stride, int64_t scan_end, hipStream_t s) {
+    if (ix->Kf == 3) return launch_q16<1>(ix, lut, Q, thr, masks, mask_stride, scan_end, s);
+    return launch_q16<2>(ix, lut, Q, thr, masks, mask_stride, scan_end, s);
+}

@@ -115,12 +115,14 @@ int icq_search_impl(const icq_index *ix, const float *queries, const float *lut_
             // item-by-item stage 1 into hit bits, stage 2 chunk by chunk from them
             uint16_t *masks = reinterpret_cast<uint16_t *>(ws + L.ids_off);
             uint32_t *key_count = reinterpret_cast<uint32_t *>(ws + L.keycount_off);
+            bool superset = false;
             rc = icq_launch_scan_masks(ix, lut, nq, thresholds + q0, masks, L.mask_stride, L.scan_end, cnt, key_count,
-                                       timed ? ev[1] : nullptr, s);
+                                       timed ? ev[1] : nullptr, &superset, s);
             if (rc != ICQ_OK) return rc;
             if (timed) ICQ_HIP_TRY(hipEventRecord(ev[2], s));
             rc = icq_launch_refine_masks(ix, lut, nq, masks, L.mask_stride, L.scan_end, cap, topk, L.splits, keys,
-                                         key_count, cnt, out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
+                                         key_count, cnt, superset ? thresholds + q0 : nullptr,
+                                         out_ids + (int64_t)q0 * topk, out_dist + (int64_t)q0 * topk, s);
             if (rc != ICQ_OK) return rc;
             if (timed) ICQ_HIP_TRY(hipEventRecord(ev[3], s));
             continue;

@@ -514,18 +514,29 @@ def test_search_grouped_by_the_first_two_fast_codes(gpu, name, N, Q, over, frac,
 
 
 @pytest.mark.parametrize("mode,over,Q", [(1, dict(K=12), 16), (2, dict(K=12), 16), (2, dict(K=8, Kf=3), 3),
-                                         (1, dict(K=4, Kf=1), 1), (1, dict(K=6, Kf=2), 9), (2, dict(K=4), 5)],
-                         ids=["streamed-K12", "grouped-K12", "grouped-Kf3-K8", "streamed-Kf1", "streamed-Kf2", "grouped-K4"])
+                                         (1, dict(K=4, Kf=1), 1), (1, dict(K=6, Kf=2), 9), (2, dict(K=4), 5),
+                                         (2, dict(K=8, Kf=3), 13), (2, dict(K=16), 21)],
+                         ids=["streamed-K12", "grouped-K12", "grouped-Kf3-K8", "streamed-Kf1", "streamed-Kf2", "grouped-K4",
+                              "grouped-Kf3-13-queries", "grouped-K16-21-queries"])
 def test_search_over_many_chunks_of_hit_bits(gpu, mode, over, Q):
     """From 2^22 items on icq_search hands the survivors of the item-by-item stage 1 to stage 2 as
     hit bits.  Enough items for more than a hundred stage-2 chunks (32768 scan positions each), so
     that both launches of the chunk walk run -- the unfiltered first part over several chunks, then
     the rest bounded by its topk-th distance -- with a ragged last chunk; 4-, 8- and 16-byte records,
-    one, two and four queries per pass of stage 1."""
+    one, two and four queries per pass of stage 1, and from six queries on over the pair ordering the
+    16-bit pre-filter with eight queries per pass (ragged last pass), whose superset stage 2 cuts back
+    by the exact comparison: thresholds that let everything, nothing, or only the items at the very
+    smallest crude distance through."""
     cfg = small("C4", 4_300_017, Q, **over)
     T, P, D = oracle_all(cfg)
     thr = thresholds_quantile(P, 0.01)
     thr[Q - 1] = np.inf                                      # every position a survivor: dense rounds
+    if Q >= 6:
+        thr[0] = -np.inf
+        thr[1] = np.nan
+        thr[2] = np.nextafter(np.float32(P[2].min()), np.float32(np.inf))     # just above the smallest crude distance
+        thr[3] = np.float32(P[3].min())                      # at it: P < t fails for every item (up to rounding)
+        thr[4] = np.float32(np.quantile(P[4], 0.3))          # a third of the items survive
     g = Gpu(gpu, cfg, mode)
     out_ids, out_dist, surv = _check_search(g, cfg, T, P, D, thr, 100, cfg["N"], min_equal=0.8 if Q > 4 else 0.0)
     assert surv[Q - 1] == cfg["N"]
