@@ -712,16 +712,22 @@ __global__ __launch_bounds__(RM_THREADS, FILTER ? 5 : 1) void refine_mask_kernel
                 uint32_t mycnt = 0;
 #pragma unroll
                 for (int u = 0; u < RM_PER; ++u) {
-                    // k ascending like every other kernel; the first term stands for 0 + itself (no table holds -0)
-                    float d = T[rec[u][0] & 0xffu];
-                    float crude = d;                  // the sum after its first Kf terms (Kf <= 4: inside the first word)
+                    // all table reads of the record first (a read waited for before the next is asked for is a
+                    // chain of 4 * WORDS LDS round trips), then the sum: k ascending like every other kernel, the
+                    // first term standing for 0 + itself (no table holds -0)
+                    float tv[4 * WORDS];
 #pragma unroll
                     for (int x = 0; x < WORDS; ++x) {
 #pragma unroll
-                        for (int b = x == 0 ? 1 : 0; b < 4; ++b) {
-                            d += T[(x * 4 + b) * ICQ_LUT_W + ((rec[u][x] >> (8 * b)) & 0xffu)];
-                            if (EXACT && x == 0) crude = b < Kf ? d : crude;
-                        }
+                        for (int b = 0; b < 4; ++b) tv[x * 4 + b] = T[(x * 4 + b) * ICQ_LUT_W + ((rec[u][x] >> (8 * b)) & 0xffu)];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    float d = tv[0];
+                    float crude = d;                  // the sum after its first Kf terms (Kf <= 4: inside the first word)
+#pragma unroll
+                    for (int i = 1; i < 4 * WORDS; ++i) {
+                        d += tv[i];
+                        if (EXACT && i < 4) crude = i < Kf ? d : crude;
                     }
                     const uint32_t ob = icq_order_bits(d);
                     bool keep = base + (uint32_t)u * 64u + lane < n;
