@@ -810,9 +810,10 @@ def main():
                    "stage1_to_stage2": "hit bits" if bits else ("on chip" if form == "tuples" else "candidate lists")},
         "ms_per_step_one_stream": round(ms_one_stream, 4),
         "stages_ms_per_call": {"build_lut": round(stage[0], 4), "stage1": round(stage[1], 4), "stage2": round(stage[2], 4),
-                               "measured": "the library's events inside the calls of the one-stream pass (%d steps, timed "
-                                           "before the pass of record); with %d streams the calls of a step overlap, so "
-                                           "calls_per_step x their sum exceeds ms_per_step" % (args.steps, nstreams)},
+                               "measured": "the library's events inside the calls of the one-stream pass (%d steps)%s"
+                                           % (args.steps, ", timed before the pass of record; with %d streams the calls of a "
+                                              "step overlap, so calls_per_step x their sum exceeds ms_per_step" % nstreams
+                                              if nstreams > 1 else "")},
         "roofline": roofline,
     }
     if form != "tuples":
