@@ -29,7 +29,7 @@ constexpr int QS_THREADS = 1024;
 constexpr int QS_WAVES = QS_THREADS / 64;
 constexpr int QS_B = 8;                  // queries per pass
 constexpr int QS_C = 16;                 // copies of a streamed table's entry: lane l reads copy l % 16
-constexpr int QS_HALF = 4;               // positions whose table reads are issued together
+constexpr int QS_HALF = 8;               // positions whose table reads are issued together (4: 3 % slower; 16 spills)
 constexpr float QS_UNITS = 30000.0f;     // where the threshold falls on the 16-bit scale
 
 __device__ __forceinline__ uint32_t lane_id() {
@@ -58,12 +58,14 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
     const uint8_t *rows, int64_t npad, uint32_t N, const float *__restrict__ lut, int K, const float *__restrict__ thr,
     int Q, uint32_t items_per_block, const uint32_t *__restrict__ info, uint16_t *__restrict__ masks, size_t mask_stride,
     uint32_t scan_end) {
+    // The streamed tables sit at LDS address 0 (no static arrays in this kernel): the table addresses the
+    // inner loop assembles from bytes are then the LDS addresses themselves, with nothing to add.
     extern __shared__ __attribute__((aligned(16))) uint4 qs_smem[];
-    __shared__ float s_min[KF + 2][QS_B];
-    __shared__ float s_inv[QS_B];
-    __shared__ int s_thr[QS_B];
     uint4 *tab = qs_smem;                                   // [KF][256][QS_C]
     uint4 *t01 = qs_smem + KF * ICQ_LUT_W * QS_C;           // [2][256]
+    float (*s_min)[QS_B] = reinterpret_cast<float (*)[QS_B]>(t01 + 2 * ICQ_LUT_W);     // [KF + 2][QS_B]
+    float *s_inv = &s_min[KF + 2][0];                       // [QS_B]
+    int *s_thr = reinterpret_cast<int *>(s_inv + QS_B);     // [QS_B]
     const int tid = threadIdx.x;
     const uint32_t lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -241,7 +243,7 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
 template <int KF>
 int launch_q16(const icq_index *ix, const float *lut, int Q, const float *thr, uint16_t *masks, size_t mask_stride,
                int64_t scan_end, hipStream_t s) {
-    const size_t lds = sizeof(uint4) * (size_t)(KF * ICQ_LUT_W * QS_C + 2 * ICQ_LUT_W);
+    const size_t lds = sizeof(uint4) * (size_t)(KF * ICQ_LUT_W * QS_C + 2 * ICQ_LUT_W) + sizeof(float) * (KF + 4) * QS_B;
     ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&scan_pairs_q16_kernel<KF>), lds));
     const int groups = (Q + QS_B - 1) / QS_B;
     const uint32_t step = (uint32_t)QS_WAVES * 1024u;
