@@ -593,7 +593,7 @@ __global__ __launch_bounds__(RM_THREADS, FILTER ? 5 : 1) void refine_mask_kernel
     {
         const uint32_t c0 = c != 0xFFFFFFFFu ? c : 0u;
 #pragma unroll
-        for (int r = 0; r < RM_WORDS; ++r) nxt[r] = mq[(size_t)c0 * (RM_CHUNK / 32) + r * 64];
+        for (int r = 0; r < RM_WORDS; ++r) nxt[r] = __builtin_nontemporal_load(mq + (size_t)c0 * (RM_CHUNK / 32) + r * 64);
     }
     // the queries' tables -> LDS, one table per record byte, zero beyond K
 #pragma unroll
@@ -640,7 +640,7 @@ __global__ __launch_bounds__(RM_THREADS, FILTER ? 5 : 1) void refine_mask_kernel
         if (cn != 0xFFFFFFFFu) {
             const uint32_t *mn = mq + (size_t)qn * mask_words + (size_t)cn * (RM_CHUNK / 32);
 #pragma unroll
-            for (int r = 0; r < RM_WORDS; ++r) nxt[r] = mn[r * 64];
+            for (int r = 0; r < RM_WORDS; ++r) nxt[r] = __builtin_nontemporal_load(mn + r * 64);
         }
         const uint32_t q = q0 + qq;
         const float tq = EXACT ? thr[q] : 0.0f;

@@ -232,8 +232,9 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
                 for (int d = 0; d < QS_B / 2; ++d) {
                     const uint32_t r = __builtin_bitreverse32(hm[d]);      // first position in bit 0; the halves change places
                     uint16_t *dst = masks + (size_t)(qbase + 2 * d) * mask_stride + (gu >> 4) + lane;
-                    if (qbase + 2 * d < Q) dst[0] = (uint16_t)(r >> 16);
-                    if (qbase + 2 * d + 1 < Q) dst[mask_stride] = (uint16_t)r;
+                    // written once, read once by stage 2: kept out of the caches the code rows are re-read from
+                    if (qbase + 2 * d < Q) __builtin_nontemporal_store((uint16_t)(r >> 16), dst);
+                    if (qbase + 2 * d + 1 < Q) __builtin_nontemporal_store((uint16_t)r, dst + mask_stride);
                 }
             }
         }
