@@ -721,7 +721,6 @@ ICQ_EXPORT int icq_scan_fast(const icq_index *ix, const float *lut, int Q, const
     if (tm) {
         if (tm->batches < 1) tm->batches = 1;
         ev = tm->ev[tm->calls % ICQ_TIMED_CALLS];
-        tm->calls += 1;
         ICQ_HIP_TRY(hipEventRecord(ev[0], s));
     }
     const int rc = icq_launch_scan(ix, lut, Q, thresholds, cand_ids, cand_part, nullptr, nullptr, cand_count, cap,
@@ -730,6 +729,7 @@ ICQ_EXPORT int icq_scan_fast(const icq_index *ix, const float *lut, int Q, const
     if (ev) {
         ICQ_HIP_TRY(hipEventRecord(ev[2], s));
         ICQ_HIP_TRY(hipEventRecord(ev[3], s));
+        tm->calls += 1;           // counted once all four events of the call are recorded
     }
     return ICQ_OK;
 }

@@ -96,7 +96,6 @@ int icq_search_impl(const icq_index *ix, const float *queries, const float *lut_
         const int nb = (Q + Qb - 1) / Qb;
         if (nb > tm->batches) tm->batches = nb;
         ev = tm->ev[tm->calls % ICQ_TIMED_CALLS];
-        tm->calls += 1;
     }
     for (int q0 = 0; q0 < Q; q0 += Qb) {
         const bool timed = tm && q0 == 0;
@@ -142,6 +141,7 @@ int icq_search_impl(const icq_index *ix, const float *queries, const float *lut_
         if (rc != ICQ_OK) return rc;
         if (timed) ICQ_HIP_TRY(hipEventRecord(ev[3], s));
     }
+    if (tm) tm->calls += 1;       // counted once every launch and event of the call is enqueued
     return ICQ_OK;
 }
 
