@@ -1137,3 +1137,50 @@ def test_search_sweep_against_oracle(gpu, case):
     else:
         thr = np.quantile(P, frac, axis=1).astype(np.float32)
     _check_search(g, cfg, T, P, D, thr, topk, N + 1)
+
+
+# ------------------------------------------------------------------ HIP graphs
+@pytest.mark.parametrize("name,N,Q,over", [("C0", 10_000, 100, {}), ("C1", 200_003, 130, {}), ("C4", 4_300_017, 16, dict(K=12))],
+                         ids=["tuples-Kf1", "tuples-Kf2", "pairs-hit-bits"])
+def test_search_replayed_from_a_captured_graph(gpu, name, N, Q, over):
+    """icq_search only launches kernels on the caller's stream (counters are cleared by fill kernels,
+    not memset nodes), so a call can be captured into a HIP graph and replayed: three replays, with
+    eager work and synchronisations in between and the outputs scrubbed before each, give the eager
+    call's lists bit for bit -- also after the queries and thresholds behind the captured pointers
+    have been replaced."""
+    torch, b = gpu
+    cfg = small(name, N, Q, **over)
+    g = Gpu(gpu, cfg)
+    topk = cfg["topk"]
+    rng = np.random.default_rng(5)
+    P = orc.partial(orc.lut(cfg["codebooks"], cfg["queries"]), cfg["codes"], cfg["Kf"])
+    thr_np = thresholds_quantile(P, 0.01)
+    cap = int(N * 0.03) + 64
+    queries = g.queries.clone()
+    thr = _dev(torch, thr_np)
+    out_ids = torch.empty((Q, topk), dtype=torch.int32, device="cuda")
+    out_dist = torch.empty((Q, topk), dtype=torch.float32, device="cuda")
+    surv = torch.empty((Q,), dtype=torch.int32, device="cuda")
+    ws = g.workspace(Q, cap, topk)
+    b.icq_search(g.index, queries, thr, cap, topk, out_ids, out_dist, surv, ws)      # eager: also sets kernel attributes
+    torch.cuda.synchronize()
+    want = (out_ids.clone(), out_dist.clone(), surv.clone())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        b.icq_search(g.index, queries, thr, cap, topk, out_ids, out_dist, surv, ws)
+    for rep in range(3):
+        out_ids.fill_(-7); out_dist.fill_(float("nan")); surv.fill_(-7)
+        ws.fill_(rep + 1)                                   # whatever an earlier call left must not matter
+        junk = torch.randn(1 << 20, device="cuda").sum()    # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_ids, want[0]) and torch.equal(out_dist, want[1]) and torch.equal(surv, want[2]), rep
+        del junk
+    # other queries behind the same pointers: the graph follows the data, not the values it was captured with
+    perm = torch.from_numpy(rng.permutation(Q)).cuda()
+    queries.copy_(g.queries[perm])
+    thr.copy_(thr[perm])
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out_ids, want[0][perm]) and torch.equal(out_dist, want[1][perm]) and torch.equal(surv, want[2][perm])
