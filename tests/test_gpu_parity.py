@@ -818,8 +818,8 @@ def test_running_search_in_tiles_matches_oracle(gpu, name, N, Q, over, topk, bou
 
 
 def test_running_search_at_full_size_sampled_against_oracle(gpu):
-    """The largest workload (N = 1e8, K = 16, Kf = 4) in the launch configuration bench.py times: 13 tiles
-    of doubling size, one batch of 128 queries; four of them against the oracle's tiled loop, the rest by
+    """The largest workload (N = 1e8, K = 16, Kf = 4) in the launch configuration bench.py times: 8 tiles
+    growing fourfold from 8192 items, one batch of 128 queries; four of them against the oracle's tiled loop, the rest by
     properties."""
     import bench
     torch, b = gpu
