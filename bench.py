@@ -556,7 +556,7 @@ def stage1_form(Kf, K, N, Qb, topk):
     hands stage 2 hit bits (from 2^22 items on) or candidate lists."""
     if Kf <= 2 and Qb > 4 and N >= 256 ** Kf // 2:
         return "tuples", False
-    bits = Kf <= 4 and K <= 16 and topk <= 512 and N >= 1 << 22
+    bits = Kf <= 4 and K <= 16 and topk <= 512 and (N >= 1 << 22 or (N >= 1 << 19 and Qb >= 32))
     if Kf in (3, 4) and N >= 64 * 65536:
         return "pairs", bits
     return "items", bits
@@ -565,13 +565,13 @@ def stage1_form(Kf, K, N, Qb, topk):
 def stage1_kernel_name(Kf, K, N, Qb, topk, mode_streamed=False):
     form, bits = stage1_form(Kf, K, N, Qb, topk)
     if mode_streamed and form != "items":
-        form, bits = "items", Kf <= 4 and K <= 16 and topk <= 512 and N >= 1 << 22
+        form, bits = "items", Kf <= 4 and K <= 16 and topk <= 512 and (N >= 1 << 22 or (N >= 1 << 19 and Qb >= 32))
     if form == "tuples":
         return "group_keys_kernel<%d,%d,%s>" % (Kf, index_words(K), "true" if topk <= 256 and K <= 16 else "false")
     if Kf > 4:
         return "scan_items_kernel"
-    if form == "pairs" and bits and Qb >= 6:
-        return "scan_pairs_q16_kernel<%d>" % (Kf - 2)
+    if bits and Qb >= 6:
+        return "scan_pairs_q16_kernel<%d,%s>" % ((Kf - 2, "true") if form == "pairs" else (Kf, "false"))
     B = 4 if Qb >= 3 else Qb
     return "scan_stream_kernel<%d,%d,false,%s,%s>" % (Kf - 2 if form == "pairs" else Kf, B,
                                                        "true" if form == "pairs" else "false", "true" if bits else "false")
@@ -593,8 +593,10 @@ def stage1_model(Kf, npos, Qb, pairs, q16=False):
     R = Kf - 2 if pairs else Kf
     if q16:
         passes = (Qb + 7) // 8
+        addr = R if R <= 2 else 2 * R          # one byte permute per address with 16 table copies, extract + shift-add with 8
+        per_pair = (R if pairs else R - 1) + 2  # saturating additions, sign, collection
         return {"positions": npos, "queries": Qb, "passes": passes, "streamed_rows": R,
-                "alu_ops": npos * passes * (R + 4 * (R + 2)) + npos // 16 * passes * 40,
+                "alu_ops": npos * passes * (addr + 4 * per_pair) + npos // 16 * passes * (40 if pairs else 24),
                 "lds_addresses": npos * passes * R,
                 "table_entries": npos * Qb * R,
                 "code_bytes": npos * passes * R + npos * passes // 4,
@@ -848,11 +850,12 @@ def main():
         del ws2
         b.icq_index_set_scan_mode(index, b.ICQ_SCAN_AUTO)
         if Kf <= 4:
-            m = stage1_model(Kf, N, int(round(qmean)), False)
+            kern_s = stage1_kernel_name(Kf, K, N, batch, topk, True)
+            m = stage1_model(Kf, N, int(round(qmean)), False, kern_s.startswith("scan_pairs_q16"))
             t = stage_s[1] * 1e-3
             ach = m["alu_ops"] / t / 1e12
             result["roofline_streamed"] = {
-                "bound": "alu", "kernel": stage1_kernel_name(Kf, K, N, batch, topk, True), "achieved": round(ach, 3),
+                "bound": "alu", "kernel": kern_s, "achieved": round(ach, 3),
                 "peak": round(ALU_PEAK_TOPS, 2), "unit": "Tops/s", "frac": round(ach / ALU_PEAK_TOPS, 4),
                 "ms": round(stage_s[1], 4), "ms_per_step": round(ms_s, 4), "queries_per_s": round(Q / (ms_s * 1e-3), 1),
                 "same_lists_as_default": same, "work_model": m,
@@ -861,8 +864,8 @@ def main():
                         "table_entries_per_s": round(m["table_entries"] / t, 1)},
                 "stages_ms_per_call": {"build_lut": round(stage_s[0], 4), "stage1": round(stage_s[1], 4),
                                        "stage2": round(stage_s[2], 4)},
-                "traffic": (pmc_traffic("scan_stream_kernel_items", wl) or {}).get("bytes"),
-                "traffic_source": (pmc_traffic("scan_stream_kernel_items", wl) or {}).get("source")}
+                "traffic": (pmc_traffic(kern_s.split("<")[0] + "_items", wl) or {}).get("bytes"),
+                "traffic_source": (pmc_traffic(kern_s.split("<")[0] + "_items", wl) or {}).get("source")}
         log("[bench] all fast rows item by item: %.3f ms/step (stage 1 %.3f ms per call), same lists: %s" %
             (ms_s, stage_s[1], same))
 

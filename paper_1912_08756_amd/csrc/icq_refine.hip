@@ -871,7 +871,10 @@ ICQ_EXPORT int icq_refine(const icq_index *ix, const float *lut, int Q, const ui
 // order of the gathers, and candidate lists with the flat distance kernel are quicker (N = 1e6,
 // K = 16, 1000 queries: 0.15 against 0.24 ms for stage 2).
 bool icq_masks_usable(const icq_index *ix, int Q, int topk) {
-    return ix->Kf <= 4 && !icq_group_usable(ix, Q) && use_select(ix, topk) && ix->N >= (1ll << 22) &&
+    // from 2^22 items on; with the 16-bit pre-filter (eight queries per pass of stage 1) and enough queries to
+    // fill the chunk walk already from 2^19 (1000 queries, K = 16: lists are ahead up to 3e5 items, hit bits from 6e5)
+    const bool large = ix->N >= (1ll << 22) || (ix->N >= (1ll << 19) && Q >= 32 && icq_scan_q16_usable(ix, Q));
+    return ix->Kf <= 4 && !icq_group_usable(ix, Q) && use_select(ix, topk) && large &&
            ix->N + 16ll * 65536 < (1ll << 31);
 }
 

@@ -1,5 +1,7 @@
 // Stage 1 of the two-step search (arxiv 1912.08756, Eq. 2) as a conservative pre-filter in 16-bit
-// integers, for the index ordered by the first two fast sub-codes when icq_search keeps hit bits.
+// integers, for icq_search when it keeps hit bits: over the index ordered by the first two fast
+// sub-codes (G2: the pair's part of the sum once per 16 positions, Kf - 2 rows streamed) or over the
+// items in id order (all Kf rows streamed).
 //
 // The crude comparison P = sum_{k<Kf} T_k[code_k] < t is decided exactly where the item's record
 // is in hand anyway -- by the kernel that forms the exact distance, from the same fp32 additions.
@@ -28,8 +30,12 @@ typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
 constexpr int QS_THREADS = 1024;
 constexpr int QS_WAVES = QS_THREADS / 64;
 constexpr int QS_B = 8;                  // queries per pass
-constexpr int QS_C = 16;                 // copies of a streamed table's entry: lane l reads copy l % 16
-constexpr int QS_HALF = 8;               // positions whose table reads are issued together (4: 3 % slower; 16 spills)
+// copies of a streamed table's entry (lane l reads copy l % C): 16 while the tables fit, else 8 -- two
+// lanes of a 16-lane group then share a copy and collide when their sub-codes have the same parity
+constexpr int qs_copies(int KF) { return KF <= 2 ? 16 : 8; }
+// positions whose table reads are issued together: 8 with one or two streamed rows (4: 3 % slower; 16 spills),
+// fewer with more rows -- the reads of a phase are 16 bytes per row and position, all held in registers
+constexpr int qs_half(int KF) { return KF <= 2 ? 8 : KF == 3 ? 4 : 2; }
 constexpr float QS_UNITS = 30000.0f;     // where the threshold falls on the 16-bit scale
 
 __device__ __forceinline__ uint32_t lane_id() {
@@ -50,10 +56,11 @@ __device__ __forceinline__ int quantise(float x, float base, float inv_s) {
     return (int)fminf(fmaxf(v, 0.0f), 32000.0f);          // a NaN (inf * 0) ends as 0
 }
 
-// KF = Kf - 2 streamed rows.  Grid: x = ranges of scan positions, y = groups of eight queries.
+// KF streamed rows: Kf - 2 (G2: `rows` = the grouped rows, `info` the pairs' labels) or Kf (`rows` =
+// the fast rows in id order).  Grid: x = ranges of scan positions, y = groups of eight queries.
 // masks[q * mask_stride + p / 16] receives the hit bits of positions p .. p + 15 (bit j = position
 // p + j) for every position of the block's range below scan_end, zeros beyond the last item.
-template <int KF>
+template <int KF, bool G2>
 __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
     const uint8_t *rows, int64_t npad, uint32_t N, const float *__restrict__ lut, int K, const float *__restrict__ thr,
     int Q, uint32_t items_per_block, const uint32_t *__restrict__ info, uint16_t *__restrict__ masks, size_t mask_stride,
@@ -61,16 +68,19 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
     // The streamed tables sit at LDS address 0 (no static arrays in this kernel): the table addresses the
     // inner loop assembles from bytes are then the LDS addresses themselves, with nothing to add.
     extern __shared__ __attribute__((aligned(16))) uint4 qs_smem[];
+    constexpr int QS_C = qs_copies(KF);
+    constexpr int QS_HALF = qs_half(KF);
+    constexpr int KFAST = G2 ? KF + 2 : KF;                 // fast codebooks
+    constexpr int K0 = G2 ? 2 : 0;                          // codebook of the first streamed row
     uint4 *tab = qs_smem;                                   // [KF][256][QS_C]
-    uint4 *t01 = qs_smem + KF * ICQ_LUT_W * QS_C;           // [2][256]
-    float (*s_min)[QS_B] = reinterpret_cast<float (*)[QS_B]>(t01 + 2 * ICQ_LUT_W);     // [KF + 2][QS_B]
-    float *s_inv = &s_min[KF + 2][0];                       // [QS_B]
+    uint4 *t01 = qs_smem + KF * ICQ_LUT_W * QS_C;           // G2: [2][256]
+    float (*s_min)[QS_B] = reinterpret_cast<float (*)[QS_B]>(t01 + (G2 ? 2 * ICQ_LUT_W : 0));     // [KFAST][QS_B]
+    float *s_inv = &s_min[KFAST][0];                        // [QS_B]
     int *s_thr = reinterpret_cast<int *>(s_inv + QS_B);     // [QS_B]
     const int tid = threadIdx.x;
     const uint32_t lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qbase = blockIdx.y * QS_B;
-    constexpr int KFAST = KF + 2;
 
     const uint32_t begin = blockIdx.x * items_per_block;
     uint32_t end = begin + items_per_block;
@@ -86,7 +96,7 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
     // (unused, in bounds: the rows are padded by more than a block step)
     auto load = [&](uint32_t g, uint4 (&w)[KF], uint32_t &ci) {
         const uint32_t gs = (g < end && g >= begin) ? g : begin;
-        ci = info[(gs >> 4) + lane];
+        ci = G2 ? info[(gs >> 4) + lane] : 0u;
 #pragma unroll
         for (int k = 0; k < KF; ++k) w[k] = *reinterpret_cast<const uint4 *>(rows + (int64_t)k * npad + gs + lane * 16);
     };
@@ -108,9 +118,9 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
     __syncthreads();
     if (tid < QS_B) {
         const float t = qbase + tid < Q ? thr[qbase + tid] : -INFINITY;
-        float L = s_min[0][tid] + s_min[1][tid];            // the order of the additions of Eq. 2
+        float L = s_min[0][tid];                            // the order of the additions of Eq. 2
 #pragma unroll
-        for (int k = 2; k < KFAST; ++k) L += s_min[k][tid];
+        for (int k = 1; k < KFAST; ++k) L += s_min[k][tid];
         float inv = 0.0f;
         int units = -2;                                     // nothing can pass: t <= L, t = -inf or NaN
         if (t == INFINITY) {
@@ -139,30 +149,42 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
 #pragma unroll
     for (int j = 0; j < KF * ICQ_LUT_W * QS_C / QS_THREADS; ++j) {
         const int p = j * QS_THREADS + tid, e = p / QS_C;
-        tab[p] = entry(2 + e / ICQ_LUT_W, e % ICQ_LUT_W, false);
+        const int k = K0 + e / ICQ_LUT_W;
+        tab[p] = entry(k, e % ICQ_LUT_W, k == 0);
     }
-    if (tid < 2 * ICQ_LUT_W) t01[tid] = entry(tid / ICQ_LUT_W, tid % ICQ_LUT_W, tid < ICQ_LUT_W);
+    if (G2 && tid < 2 * ICQ_LUT_W) t01[tid] = entry(tid / ICQ_LUT_W, tid % ICQ_LUT_W, tid < ICQ_LUT_W);
     __syncthreads();
 
-    // A table address is assembled from bytes by one instruction: byte 0 = this lane's copy (times 16),
-    // byte 1 = the sub-code (an entry is 16 copies of 16 bytes), byte 2 = the streamed table.
+    // 16 copies: a table address is assembled from bytes by one instruction: byte 0 = this lane's copy
+    // (times 16), byte 1 = the sub-code (an entry is 16 copies of 16 bytes), byte 2 = the streamed table.
+    // 8 copies (entries of 128 bytes): sub-code * 128 + (copy * 16 + table * 32768), the bracket per lane.
     const uint32_t lane_bytes = (lane & (QS_C - 1)) * 16u | 0x100u;      // byte 1 = 1: the source of "table 1"
+    uint32_t lane_off[KF];
+#pragma unroll
+    for (int k = 0; k < KF; ++k) lane_off[k] = (lane & (QS_C - 1)) * 16u + (uint32_t)k * (ICQ_LUT_W * QS_C * 16);
     const char *tab_bytes = reinterpret_cast<const char *>(tab);
     // hit bits of the 1024 positions at g: hm[d] = queries 2d (low half) and 2d + 1, position j in bit 15 - j
     auto hits = [&](uint32_t g, const uint4 (&w)[KF], uint32_t ci, uint32_t (&hm)[QS_B / 2]) {
-        const uint4 a = t01[ci & 0xffu], c = t01[ICQ_LUT_W + ((ci >> 8) & 0xffu)];
         uint32_t p01[QS_B / 2];
-        p01[0] = pk_add_sat(a.x, c.x);
-        p01[1] = pk_add_sat(a.y, c.y);
-        p01[2] = pk_add_sat(a.z, c.z);
-        p01[3] = pk_add_sat(a.w, c.w);
-        // the streamed tables add at least 0: a pair of queries whose two sums are not below 0 in any
-        // lane has no hit among the wavefront's 1024 positions
-        bool live[QS_B / 2], any_live = false;
+        bool live[QS_B / 2], any_live = !G2;
 #pragma unroll
         for (int d = 0; d < QS_B / 2; ++d) {
-            live[d] = __builtin_amdgcn_ballot_w64((p01[d] & 0x80008000u) != 0u) != 0;   // wavefront-uniform
-            any_live |= live[d];
+            p01[d] = 0;
+            live[d] = true;
+        }
+        if (G2) {
+            const uint4 a = t01[ci & 0xffu], c = t01[ICQ_LUT_W + ((ci >> 8) & 0xffu)];
+            p01[0] = pk_add_sat(a.x, c.x);
+            p01[1] = pk_add_sat(a.y, c.y);
+            p01[2] = pk_add_sat(a.z, c.z);
+            p01[3] = pk_add_sat(a.w, c.w);
+            // the streamed tables add at least 0: a pair of queries whose two sums are not below 0 in any
+            // lane has no hit among the wavefront's 1024 positions
+#pragma unroll
+            for (int d = 0; d < QS_B / 2; ++d) {
+                live[d] = __builtin_amdgcn_ballot_w64((p01[d] & 0x80008000u) != 0u) != 0;   // wavefront-uniform
+                any_live |= live[d];
+            }
         }
         if (!any_live) return;
         uint32_t acc[2][QS_B / 2];                           // positions 0 .. 7 and 8 .. 15: eight bits per half
@@ -179,9 +201,16 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
 #pragma unroll
                 for (int k = 0; k < KF; ++k) {
                     const uint32_t word = j < 4 ? w[k].x : j < 8 ? w[k].y : j < 12 ? w[k].z : w[k].w;
-                    // selector bytes: 0 = lane_bytes byte 0, 4 + n = byte n of the code word, 1 = lane_bytes byte 1, 0x0c = zero
-                    const uint32_t sel = 0x0c000000u | (k == 0 ? 0x000c0000u : 0x00010000u) | ((4u + (j & 3)) << 8);
-                    off[jj][k] = __builtin_amdgcn_perm(word, lane_bytes, sel);
+                    if (QS_C == 16) {
+                        // selector bytes: 0 = lane_bytes byte 0, 4 + n = byte n of the code word, 1 = lane_bytes byte 1, 0x0c = zero
+                        const uint32_t sel = 0x0c000000u | (k == 0 ? 0x000c0000u : 0x00010000u) | ((4u + (j & 3)) << 8);
+                        off[jj][k] = __builtin_amdgcn_perm(word, lane_bytes, sel);
+                    } else {
+                        uint32_t code;
+                        if ((j & 3) == 0) asm("v_bfe_u32 %0, %1, 0, 8" : "=v"(code) : "v"(word));
+                        else code = (word >> (8 * (j & 3))) & 0xffu;
+                        off[jj][k] = (code << 7) + lane_off[k];
+                    }
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -201,7 +230,7 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
 #pragma unroll
                     for (int k = 0; k < KF; ++k) {
                         const uint32_t e = d == 0 ? v[jj][k].x : d == 1 ? v[jj][k].y : d == 2 ? v[jj][k].z : v[jj][k].w;
-                        x = pk_add_sat(x, e);
+                        x = (!G2 && k == 0) ? e : pk_add_sat(x, e);      // id order: the first table carries the threshold
                     }
                     // one instruction per step (left to itself the compiler regroups the chain into more)
                     uint32_t &m = acc[(h + jj) >> 3][d];
@@ -210,7 +239,7 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
             }
         }
         // the padding behind a pair's last item, and positions at or beyond the end
-        uint32_t valid = (0xFFFF0000u >> (ci >> 16)) & 0xFFFFu;
+        uint32_t valid = G2 ? (0xFFFF0000u >> (ci >> 16)) & 0xFFFFu : 0xFFFFu;
         const uint32_t id0 = g + lane * 16;
         if (id0 + 16 > end || id0 + 16 < id0) valid &= id0 < end ? 0xFFFFu & ~((1u << (16 - (end - id0))) - 1u) : 0u;
         valid |= valid << 16;
@@ -241,11 +270,12 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
     }
 }
 
-template <int KF>
+template <int KF, bool G2>
 int launch_q16(const icq_index *ix, const float *lut, int Q, const float *thr, uint16_t *masks, size_t mask_stride,
                int64_t scan_end, hipStream_t s) {
-    const size_t lds = sizeof(uint4) * (size_t)(KF * ICQ_LUT_W * QS_C + 2 * ICQ_LUT_W) + sizeof(float) * (KF + 4) * QS_B;
-    ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&scan_pairs_q16_kernel<KF>), lds));
+    const size_t lds = sizeof(uint4) * (size_t)(KF * ICQ_LUT_W * qs_copies(KF) + (G2 ? 2 * ICQ_LUT_W : 0)) +
+                       sizeof(float) * ((G2 ? KF + 2 : KF) + 2) * QS_B;
+    ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&scan_pairs_q16_kernel<KF, G2>), lds));
     const int groups = (Q + QS_B - 1) / QS_B;
     const uint32_t step = (uint32_t)QS_WAVES * 1024u;
     // one wave of equally loaded blocks: the chip is filled once and every block streams a long run
@@ -259,21 +289,31 @@ int launch_q16(const icq_index *ix, const float *lut, int Q, const float *thr, u
         const int ng = groups - g0 < 65535 ? groups - g0 : 65535;
         const int q0 = g0 * QS_B, nq = (Q - q0) < ng * QS_B ? (Q - q0) : ng * QS_B;
         dim3 grid((unsigned)chunks, (unsigned)ng);
-        scan_pairs_q16_kernel<KF><<<grid, QS_THREADS, lds, s>>>(
-            ix->g2_rows, ix->g2_npad, (uint32_t)ix->g2_npos, lut + (int64_t)q0 * ix->K * ICQ_LUT_W, ix->K, thr + q0, nq,
-            per, ix->g2_info, masks + (size_t)q0 * mask_stride, mask_stride, (uint32_t)scan_end);
+        scan_pairs_q16_kernel<KF, G2><<<grid, QS_THREADS, lds, s>>>(
+            G2 ? ix->g2_rows : ix->fast, G2 ? ix->g2_npad : ix->Npad, (uint32_t)(G2 ? ix->g2_npos : ix->N),
+            lut + (int64_t)q0 * ix->K * ICQ_LUT_W, ix->K, thr + q0, nq, per, G2 ? ix->g2_info : nullptr,
+            masks + (size_t)q0 * mask_stride, mask_stride, (uint32_t)scan_end);
     }
     return icq_check_launch();
 }
 
 }  // namespace
 
-// Calls with at least this many queries take the 16-bit pre-filter (below, a pass of eight would be mostly empty slots).
-bool icq_scan_q16_usable(const icq_index *ix, int Q) { return icq_g2_usable(ix) && Q >= 6; }
+// Calls with at least this many queries take the 16-bit pre-filter (below, a pass of eight would be mostly empty
+// slots); Kf <= 4 (the caller keeps hit bits only then).
+bool icq_scan_q16_usable(const icq_index *ix, int Q) { return ix->Kf <= 4 && Q >= 6; }
 
 // Hit bits of a superset of the survivors; the caller's stage 2 applies the exact comparison.
 int icq_launch_scan_masks_q16(const icq_index *ix, const float *lut, int Q, const float *thr, uint16_t *masks,
                               size_t mask_stride, int64_t scan_end, hipStream_t s) {
-    if (ix->Kf == 3) return launch_q16<1>(ix, lut, Q, thr, masks, mask_stride, scan_end, s);
-    return launch_q16<2>(ix, lut, Q, thr, masks, mask_stride, scan_end, s);
+    if (icq_g2_usable(ix)) {
+        if (ix->Kf == 3) return launch_q16<1, true>(ix, lut, Q, thr, masks, mask_stride, scan_end, s);
+        return launch_q16<2, true>(ix, lut, Q, thr, masks, mask_stride, scan_end, s);
+    }
+    switch (ix->Kf) {
+        case 1: return launch_q16<1, false>(ix, lut, Q, thr, masks, mask_stride, scan_end, s);
+        case 2: return launch_q16<2, false>(ix, lut, Q, thr, masks, mask_stride, scan_end, s);
+        case 3: return launch_q16<3, false>(ix, lut, Q, thr, masks, mask_stride, scan_end, s);
+        default: return launch_q16<4, false>(ix, lut, Q, thr, masks, mask_stride, scan_end, s);
+    }
 }
