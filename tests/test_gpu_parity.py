@@ -515,9 +515,11 @@ def test_search_grouped_by_the_first_two_fast_codes(gpu, name, N, Q, over, frac,
 
 @pytest.mark.parametrize("mode,over,Q", [(1, dict(K=12), 16), (2, dict(K=12), 16), (2, dict(K=8, Kf=3), 3),
                                          (1, dict(K=4, Kf=1), 1), (1, dict(K=6, Kf=2), 9), (2, dict(K=4), 5),
-                                         (2, dict(K=8, Kf=3), 13), (2, dict(K=16), 21)],
+                                         (2, dict(K=8, Kf=3), 13), (2, dict(K=16), 21),
+                                         (1, dict(K=4, Kf=1), 8), (1, dict(K=8, Kf=3), 12)],
                          ids=["streamed-K12", "grouped-K12", "grouped-Kf3-K8", "streamed-Kf1", "streamed-Kf2", "grouped-K4",
-                              "grouped-Kf3-13-queries", "grouped-K16-21-queries"])
+                              "grouped-Kf3-13-queries", "grouped-K16-21-queries", "streamed-Kf1-8-queries",
+                              "streamed-Kf3-12-queries"])
 def test_search_over_many_chunks_of_hit_bits(gpu, mode, over, Q):
     """From 2^22 items on icq_search hands the survivors of the item-by-item stage 1 to stage 2 as
     hit bits.  Enough items for more than a hundred stage-2 chunks (32768 scan positions each), so
