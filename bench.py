@@ -513,6 +513,140 @@ def configs_leg(torch, b, synth, skip, with_cpu, target_s=4.0):
     return out
 
 
+def encoded_index_leg(torch, b, synth, with_cpu, sweeps=2):
+    """C3's shape with codes that come from the encoder instead of a generator: 1e7 Gaussian-mixture
+    vectors (synth.make_vectors) are encoded on the GPU (greedy assignment, then `sweeps` sweeps of
+    coordinate descent), indexed and searched like C3.  The oracle beside it encodes a sample of the
+    vectors itself -- the GPU's returned neighbours, cluster mates of the queries' sources and random
+    items -- and judges codes, distances and completeness of the lists on that sample."""
+    from oracle import icq_oracle as orc
+    t_prep = time.perf_counter()
+    cfg = synth.make_vectors("C3")
+    K, Kf, d, N, Q, topk, batch = cfg["K"], cfg["Kf"], cfg["d"], cfg["N"], cfg["Q"], cfg["topk"], cfg["batch"]
+    cb = torch.from_numpy(cfg["codebooks"]).cuda()
+    x = torch.from_numpy(cfg["x"]).cuda()
+    queries = torch.from_numpy(cfg["queries"]).cuda()
+    enc = b.icq_index_create(cb, torch.empty((K, 0), dtype=torch.uint8, device="cuda"), Kf)
+    ws_e = torch.empty(b.icq_encode_workspace_bytes(enc, N), dtype=torch.uint8, device="cuda")
+    codes = torch.empty((K, N), dtype=torch.uint8, device="cuda")
+    changed = torch.zeros((sweeps,), dtype=torch.int32, device="cuda")
+    err = torch.empty((N,), dtype=torch.float64, device="cuda")
+
+    def mean_err():
+        b.icq_quantization_error(enc, x, codes, err)
+        return float(err.mean().item())
+    b.icq_encode(enc, x, codes, ws_e)
+    torch.cuda.synchronize()
+    ms_greedy = event_time_ms(torch, lambda: b.icq_encode(enc, x, codes, ws_e), 2)
+    e_greedy = mean_err()
+    greedy = codes.clone()
+    b.icq_encode_refine(enc, x, codes, sweeps, changed, ws_e)
+    torch.cuda.synchronize()
+    codes.copy_(greedy)
+    ms_refine = event_time_ms(torch, lambda: b.icq_encode_refine(enc, x, codes, sweeps, changed, ws_e), 1)
+    e_refined = mean_err()
+    x_norm2 = float((x[:1 << 20].double() ** 2).sum(dim=1).mean().item())
+    del greedy, err, ws_e, x
+    torch.cuda.empty_cache()
+    t0 = time.perf_counter()
+    index = b.icq_index_create(cb, codes, Kf)
+    torch.cuda.synchronize()
+    ms_index = (time.perf_counter() - t0) * 1e3
+    pairs = codes[0].to(torch.int32) * 256 + codes[1].to(torch.int32)
+    runs = torch.bincount(pairs, minlength=65536)
+    thr = sampled_thresholds(torch, b, cb, codes, queries, Kf, SURVIVE_FRAC, 16384, cfg["seed"])
+    cap = int(N * SURVIVE_FRAC * 4)
+    out_ids = torch.empty((Q, topk), dtype=torch.int32, device="cuda")
+    out_dist = torch.empty((Q, topk), dtype=torch.float32, device="cuda")
+    surv = torch.empty((Q,), dtype=torch.int32, device="cuda")
+    ws = torch.empty(b.icq_workspace_bytes(index, batch, cap, topk), dtype=torch.uint8, device="cuda")
+
+    def run():
+        for q0 in range(0, Q, batch):
+            b.icq_search(index, queries[q0:q0 + batch], thr[q0:q0 + batch], cap, topk, out_ids[q0:q0 + batch],
+                         out_dist[q0:q0 + batch], surv[q0:q0 + batch], ws)
+    run()
+    torch.cuda.synchronize()
+    reps = 5
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        run()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / reps
+    b.icq_index_set_stage_timing(index, True)
+    run()
+    torch.cuda.synchronize()
+    stage, _, _ = b.icq_index_stage_times(index)
+    b.icq_index_set_stage_timing(index, False)
+    surv_np = surv.cpu().numpy().view(np.uint32)
+    flops = 2.0 * N * K * 256 * ((d + 15) // 16 * 16)
+    entry = {"workload": "C3's shape over encoded vectors: d=%d K=%d Kf=%d N=%d Q=%d top-%d, batches of %d; "
+                         "%d-cluster Gaussian mixture, spread %.1f" % (d, K, Kf, N, Q, topk, batch, cfg["n_centres"], cfg["spread"]),
+             "encode": {"greedy_ms": round(ms_greedy, 2), "greedy_TFLOPs": round(flops / (ms_greedy * 1e-3) / 1e12, 1),
+                        "refine_sweeps": sweeps, "refine_ms": round(ms_refine, 2),
+                        "subcodes_changed_per_sweep": changed.cpu().tolist(),
+                        "mean_sq_error": {"greedy": round(e_greedy, 4), "refined": round(e_refined, 4),
+                                          "mean_sq_norm_of_x": round(x_norm2, 2)}},
+             "index_build_ms": round(ms_index, 1),
+             "fast_pairs_in_use": int((runs > 0).sum().item()), "largest_pair_run": int(runs.max().item()),
+             "queries_per_s": round(Q / sec, 1), "ms_per_batch": round(sec * 1e3 / math.ceil(Q / batch), 4),
+             "stages_ms_per_batch": {"build_lut": round(stage[0], 4), "stage1": round(stage[1], 4), "stage2": round(stage[2], 4)},
+             "stage1_kernel": stage1_kernel_name(Kf, K, N, batch, topk),
+             "survivors_mean": round(float(surv_np.mean()), 1), "overflowed_lists": int((surv_np > cap).sum())}
+    if with_cpu:
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from helpers import tol
+        n = 8
+        g_ids = out_ids[:n].cpu().numpy().view(np.uint32)
+        g_dist = out_dist[:n].cpu().numpy()
+        thr_np = thr[:n].cpu().numpy()
+        rng = np.random.default_rng(cfg["seed"])
+        parts = [g_ids[g_ids != 0xFFFFFFFF].astype(np.int64), rng.integers(0, N, size=4000)]
+        for q in range(n):
+            mates = np.nonzero(cfg["cluster"] == cfg["cluster"][cfg["query_sources"][q]])[0]
+            parts.append(rng.choice(mates, size=min(1500, len(mates)), replace=False))
+        S = np.unique(np.concatenate(parts))
+        t0 = time.perf_counter()
+        xs = np.ascontiguousarray(cfg["x"][S])
+        want, _ = orc.encode_icm(cfg["codebooks"], xs, orc.encode(cfg["codebooks"], xs), sweeps)
+        got = codes[:, torch.from_numpy(S).cuda()].cpu().numpy()
+        same = (want == got).all(axis=0)
+        if same.mean() < 0.95:
+            raise AssertionError("encoded index: only %.3f of the sampled items carry the oracle's codes" % same.mean())
+        S_ok, c_ok = S[same], np.ascontiguousarray(want[:, same])
+        T = orc.lut(cfg["codebooks"], cfg["queries"][:n])
+        P, D = orc.partial(T, c_ok, Kf), orc.partial(T, c_ok, K)
+        checked = skipped = 0
+        for q in range(n):
+            t = float(thr_np[q])
+            valid = g_ids[q] != 0xFFFFFFFF
+            pos = np.searchsorted(S_ok, g_ids[q][valid])
+            pos[pos >= len(S_ok)] = 0
+            known = S_ok[pos] == g_ids[q][valid]
+            skipped += int((~known).sum())
+            dq = g_dist[q][valid][known]
+            if not (np.abs(dq - D[q][pos[known]]) <= tol(D[q][pos[known]])).all():
+                raise AssertionError("encoded index, query %d: a returned distance is off" % q)
+            if not (P[q][pos[known]] <= t + tol(t)).all():
+                raise AssertionError("encoded index, query %d: a returned item is clearly above the threshold" % q)
+            dk = float(g_dist[q][-1]) if valid.all() else np.inf
+            must = np.nonzero((P[q] < t - tol(t)) & (D[q] < dk - tol(dk)))[0] if np.isfinite(dk) else \
+                np.nonzero(P[q] < t - tol(t))[0]
+            if not np.isin(S_ok[must], g_ids[q][valid]).all():
+                raise AssertionError("encoded index, query %d: a clearly nearer survivor is missing from the list" % q)
+            checked += int(known.sum()) + len(must)
+        entry["oracle"] = {"sample_items": int(len(S)), "codes_identical_frac": round(float(same.mean()), 4),
+                           "queries": n, "checks": checked, "returned_items_with_differing_codes_skipped": skipped,
+                           "violations": 0, "cores": orc.threads(), "wall_s": round(time.perf_counter() - t0, 1),
+                           "what": "the oracle encodes the sampled vectors itself (greedy + %d sweeps) and judges, on the "
+                                   "items whose codes agree, returned distances, the threshold and that no clearly "
+                                   "nearer survivor of the sample is missing" % sweeps}
+    log("[bench] C3 over encoded vectors: encode %.1f + %.1f ms, index %.0f ms, %.0f queries/s (%.3f ms per batch), "
+        "%.0f survivors/query, prepared in %.0f s" % (ms_greedy, ms_refine, ms_index, Q / sec, entry["ms_per_batch"],
+                                                      surv_np.mean(), time.perf_counter() - t_prep))
+    return entry
+
+
 def machine_limits(torch, b):
     """What this GPU delivers for the access patterns the kernels are made of (icq_machine_probe):
     the figures behind the peaks the rooflines use."""
@@ -903,6 +1037,8 @@ def main():
     if not args.no_configs_leg:
         log("[bench] the other workload shapes, each against the oracle")
         result["configs"] = configs_leg(torch, b, synth, args.workload, not args.no_cpu_baseline)
+        log("[bench] C3's shape over vectors encoded on the GPU")
+        result["configs"]["C3_encoded"] = encoded_index_leg(torch, b, synth, not args.no_cpu_baseline)
     print(json.dumps(result), flush=True)
 
 

@@ -24,6 +24,18 @@ Recipe (all draws from numpy's counter-based Philox generator, keyed by
 
 Database vectors themselves are never materialised (the path consumes codes
 only); reconstructions are formed for the Q query sources alone.
+
+A second recipe draws database VECTORS instead of codes (`make_vectors`), for
+indexes whose codes come from the encoder rather than from a generator:
+
+* vectors     1000 centres, each the reconstruction of a uniformly drawn code;
+              x_i = centre of a uniformly drawn cluster + N(0, spread^2 I_d),
+              float32, spread = 1 (the per-component deviation of the first
+              codebook: with sigma_k = 2^-k the nearest first codeword is then
+              the centre's for practically every vector of a cluster, the
+              second for about 94 %, the third for about 30 %).
+* queries     Q vectors drawn uniformly with replacement plus per-component
+              noise of std 0.05 * rms(||x||) / sqrt(d).
 """
 import numpy as np
 
@@ -42,7 +54,7 @@ CONFIGS = {
     "C4": dict(d=96, K=16, Kf=4, m=256, N=100_000_000, Q=1_000, topk=100,
                sigma=("geom", 0.8), codes="uniform", noise="rel", batch=128),
 }
-_STREAM_CODEBOOKS, _STREAM_CODES, _STREAM_QUERIES, _STREAM_CENTRES = 1, 2, 3, 4
+_STREAM_CODEBOOKS, _STREAM_CODES, _STREAM_QUERIES, _STREAM_CENTRES, _STREAM_VECTORS = 1, 2, 3, 4, 5
 
 
 def _rng(seed, stream):
@@ -113,4 +125,62 @@ def make(name, N=None, Q=None, seed=None, **override):
     codes = make_codes(K, Kf, m, cfg["N"], cfg["codes"], seed)
     queries, src = make_queries(cb, codes, cfg["Q"], cfg["noise"], seed)
     cfg.update(name=name, seed=seed, codebooks=cb, codes=codes, queries=queries, query_sources=src)
+    return cfg
+
+
+_VECTOR_CHUNK = 1 << 16        # rows per independently keyed block of the vector stream (part of the recipe)
+
+
+def make_mixture_vectors(codebooks, N, n_centres, spread, seed, workers=None):
+    """[N][d] float32 vectors of a Gaussian mixture whose centres are reconstructions of
+    uniformly drawn codes; returns (x, cluster index of every vector).  Rows come in blocks of
+    65536, block j from the Philox stream (seed, vector stream) at counter word 3 = j, so blocks
+    are independent of each other and of N and can be drawn by several threads."""
+    from concurrent.futures import ThreadPoolExecutor
+    import os
+    K, m, d = codebooks.shape
+    gc = _rng(seed, _STREAM_CENTRES)
+    centre_codes = gc.integers(0, m, size=(K, n_centres))
+    centres = np.zeros((n_centres, d), dtype=np.float32)
+    for k in range(K):
+        centres += codebooks[k][centre_codes[k]]
+    pick = gc.integers(0, n_centres, size=N)
+    x = np.empty((N, d), dtype=np.float32)
+
+    def block(j):
+        lo, hi = j * _VECTOR_CHUNK, min(N, (j + 1) * _VECTOR_CHUNK)
+        g = np.random.Generator(np.random.Philox(key=[int(seed), _STREAM_VECTORS], counter=[0, 0, 0, j]))
+        part = x[lo:hi]
+        g.standard_normal(out=part, dtype=np.float32)
+        part *= np.float32(spread)
+        part += centres[pick[lo:hi]]
+
+    blocks = range((N + _VECTOR_CHUNK - 1) // _VECTOR_CHUNK)
+    workers = workers or min(16, os.cpu_count() or 1)
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        list(pool.map(block, blocks))
+    return x, pick
+
+
+def make_vectors(name, N=None, Q=None, seed=None, n_centres=1000, spread=1.0):
+    """A workload's shape with database vectors in place of codes: codebooks [K][m][d],
+    x [N][d] f32 (Gaussian mixture), queries [Q][d] f32 (noisy copies of drawn vectors)."""
+    cfg = dict(CONFIGS[name])
+    if N is not None:
+        cfg["N"] = int(N)
+    if Q is not None:
+        cfg["Q"] = int(Q)
+    if seed is None:
+        seed = BASE_SEED + 100 + sorted(CONFIGS).index(name)
+    del cfg["codes"]                      # the generator kind of `make`: here the codes come from an encoder
+    K, m, d = cfg["K"], cfg["m"], cfg["d"]
+    cb = make_codebooks(K, m, d, sigmas(cfg["sigma"], K), seed)
+    x, pick = make_mixture_vectors(cb, cfg["N"], n_centres, spread, seed)
+    g = _rng(seed, _STREAM_QUERIES)
+    src = g.integers(0, cfg["N"], size=cfg["Q"])
+    xs = x[src].astype(np.float64)
+    rms = np.sqrt(np.mean(np.sum(xs * xs, axis=1))) if cfg["Q"] > 0 else 0.0
+    q = xs + (0.05 * rms / np.sqrt(d)) * g.standard_normal((cfg["Q"], d))
+    cfg.update(name=name, seed=seed, codebooks=cb, x=x, cluster=pick, n_centres=n_centres, spread=spread,
+               queries=np.ascontiguousarray(q, dtype=np.float32), query_sources=src)
     return cfg

@@ -1046,6 +1046,41 @@ def test_encode_refine_on_disjoint_supports_finds_the_planted_codes_in_one_sweep
 
 
 # ------------------------------------------------------------------ quantities around the fast set
+@pytest.mark.parametrize("mode", [1, 2], ids=["streamed", "grouped"])
+def test_search_over_an_index_encoded_from_mixture_vectors(gpu, mode):
+    """The clustered shape with codes that come from the encoder: Gaussian-mixture vectors, greedy
+    assignment plus two sweeps of coordinate descent.  Both sides encode the vectors themselves;
+    the index the search runs over is built from the ORACLE's codes on both sides."""
+    torch, b = gpu
+    cfg = synth.make_vectors("C3", N=20_000, Q=64)
+    cb, x, K, Kf = cfg["codebooks"], cfg["x"], cfg["K"], cfg["Kf"]
+    N = x.shape[0]
+    want, _ = orc.encode_icm(cb, x, orc.encode(cb, x), 2)
+    enc = b.icq_index_create(_dev(torch, cb), torch.empty((K, 0), dtype=torch.uint8, device="cuda"), Kf)
+    ws = torch.empty(b.icq_encode_workspace_bytes(enc, N), dtype=torch.uint8, device="cuda")
+    got = torch.empty((K, N), dtype=torch.uint8, device="cuda")
+    xd = _dev(torch, x)
+    b.icq_encode(enc, xd, got, ws)
+    b.icq_encode_refine(enc, xd, got, 2, None, ws)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    assert (got == want).all(axis=0).mean() >= 0.95
+    e_got, e_want = orc.quantization_error(cb, x, got).mean(), orc.quantization_error(cb, x, want).mean()
+    assert abs(e_got - e_want) <= 1e-3 * e_want
+    # the structure the encoder gives the fast sub-codes: a cluster's vectors share the first, mostly the second
+    pairs = want[0].astype(np.int64) * 256 + want[1]
+    share = np.mean([(pairs[cfg["cluster"] == c] == np.bincount(pairs[cfg["cluster"] == c]).argmax()).mean()
+                     for c in range(0, cfg["n_centres"], 10) if (cfg["cluster"] == c).any()])
+    assert 0.8 <= share <= 0.999
+    cfg["codes"] = want
+    g = Gpu(gpu, cfg, mode)
+    T, P, D = oracle_all(cfg)
+    for rule in (("q", 0.01), ("q", 0.05)):
+        thr = _thr(P, rule)
+        exact = (P < thr[:, None].astype(np.float64)).sum(axis=1)
+        _check_search(g, cfg, T, P, D, thr, cfg["topk"], int(exact.max() * 1.2) + 64)
+
+
 def test_moments_online_variance_mask_fast_set_and_margin_match_oracle(gpu):
     torch, b = gpu
     rng = np.random.default_rng(12)
