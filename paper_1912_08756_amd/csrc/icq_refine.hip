@@ -549,6 +549,7 @@ constexpr int RM_LIST = 512;                          // positions a wavefront e
 constexpr int RM_QPB = 1;                             // queries per block (two: 1.39 against 1.25 ms at N = 1e8, 128 queries)
 constexpr int RM_SEED_EVERY = 65;                     // odd: the first launch's chunks are spread over all XCDs
 static_assert(RM_LIST % (64 * RM_PER) == 0, "a round of the list is whole steps of gathers");
+static_assert(RM_CHUNK <= 65536, "the position lists hold 16-bit offsets into the chunk");
 
 // QPB queries per block: their tables sit in LDS side by side and every chunk is worked through for one
 // query after the other, so the later ones find the chunk's records in the cache for certain.
@@ -564,12 +565,12 @@ __global__ __launch_bounds__(RM_THREADS, FILTER ? 5 : 1) void refine_mask_kernel
     const float *__restrict__ kth_dist, int topk, u64 *__restrict__ keys, uint32_t *__restrict__ key_count,
     int64_t cap, uint32_t *__restrict__ cand_count, const float *__restrict__ thr, int Kf) {
     __shared__ __attribute__((aligned(16))) float T_all[QPB][4 * WORDS * ICQ_LUT_W];
-    __shared__ uint32_t cand_all[RM_WAVES][RM_LIST];
+    __shared__ uint16_t cand_all[RM_WAVES][RM_LIST];  // positions inside the chunk (RM_CHUNK <= 65536)
     constexpr int RW = WORDS;
     const int tid = threadIdx.x;
     const uint32_t lane = (uint32_t)tid & 63u;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    uint32_t *cand = cand_all[wave];
+    uint16_t *cand = cand_all[wave];
     // block -> (window, query group, XCD): chunks i = (win * window + j) * 8 + xcd, j = 0 .. window - 1, of this
     // launch's; wavefront w takes j = w, w + 4, ..
     const uint32_t ngroups = ((uint32_t)Q + QPB - 1) / QPB;
@@ -665,7 +666,7 @@ __global__ __launch_bounds__(RM_THREADS, FILTER ? 5 : 1) void refine_mask_kernel
         if (!FILTER && !EXACT && total != 0) {
             if (lane == 0) chunk_slot = atomicAdd(&key_count[q], total);
         }
-        const uint32_t p0 = c * RM_CHUNK + lane * 32u;
+        const uint32_t cbase = c * RM_CHUNK, p0 = lane * 32u;
         for (uint32_t lo = 0; lo < total; lo += RM_LIST) {      // wavefront-uniform; one round unless the chunk is dense
             __builtin_amdgcn_wave_barrier();          // LDS runs a wavefront's accesses in order: the last round's reads are done
             if (off + mine > lo && off < lo + RM_LIST) {
@@ -676,7 +677,7 @@ __global__ __launch_bounds__(RM_THREADS, FILTER ? 5 : 1) void refine_mask_kernel
                     while (m != 0) {
                         const uint32_t bit = (uint32_t)__builtin_ctz(m);
                         m &= m - 1;
-                        if (idx < (uint32_t)RM_LIST) cand[idx] = p0 + (uint32_t)r * 2048u + bit;
+                        if (idx < (uint32_t)RM_LIST) cand[idx] = (uint16_t)(p0 + (uint32_t)r * 2048u + bit);
                         ++idx;
                     }
                 }
@@ -688,7 +689,7 @@ __global__ __launch_bounds__(RM_THREADS, FILTER ? 5 : 1) void refine_mask_kernel
 #pragma unroll
                 for (int u = 0; u < RM_PER; ++u) {
                     const uint32_t i = base + (uint32_t)u * 64u + lane;
-                    id[u] = cand[i < n ? i : n - 1];
+                    id[u] = cbase + cand[i < n ? i : n - 1];
                 }
 #pragma unroll
                 for (int u = 0; u < RM_PER; ++u) {
