@@ -8,15 +8,19 @@
 // What this kernel leaves is a SUPERSET of the survivors, found with a quarter of the work per
 // (query, position): every fast table is replaced by
 //     q_k[c] = max(0, floor((T_k[c] - min T_k) / s) - 1)        (16-bit, never above the true quotient)
-// with one scale s per query chosen so that the threshold falls at 30000 units, and an item passes
+// with one scale s per query chosen so that the threshold falls at 7500 units, and an item passes
 // when  q_0 + q_1 + q_2 (+ q_3) <= floor((t - sum_k min T_k) / s) + 1.  Rounding down every term
 // and up the right side cannot lose a survivor (the slack of one unit per term also covers the
 // rounding of the fp32 sum the exact test uses, which s >= |t| * 2^-18 keeps below a sixteenth of a
-// unit); what it lets through beyond the survivors are items within a few units -- a ten-thousandth
-// of the threshold's distance from the tables' minimum -- of the threshold.
-// Eight queries' 16-bit entries make one 16-byte LDS read, two queries share every packed
-// instruction (saturating adds, the sign of  sum - threshold - 1  is the hit bit), and the byte
-// extraction and table address of a position serve eight queries instead of four.
+// unit); what it lets through beyond the survivors are items within a few units -- a few
+// ten-thousandths of the threshold's distance from the tables' minimum -- of the threshold.
+// Eight queries' 16-bit entries make one 16-byte LDS read, and two queries share every 32-bit
+// instruction: entries stop at 8000 units and the first table carries 32768 - (threshold units + 1),
+// so a sum of up to four entries stays inside its 16 bits -- the two halves of a word are added by
+// ONE plain 32-bit addition with no carry between them -- and bit 15 of a half is clear exactly when
+// the sum is at or below the threshold's units.  Plain two-operand additions issue almost twice as
+// often as the packed 16-bit forms.  The byte extraction and table address of a position serve
+// eight queries instead of four.
 #include "icq_internal.h"
 #include "icq_sort.h"
 
@@ -24,8 +28,8 @@
 
 namespace {
 
-typedef short short2v __attribute__((ext_vector_type(2)));
-typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int QS_THREADS = 1024;
 constexpr int QS_WAVES = QS_THREADS / 64;
@@ -36,24 +40,18 @@ constexpr int qs_copies(int KF) { return KF <= 2 ? 16 : 8; }
 // positions whose table reads are issued together: 8 with one or two streamed rows (4: 3 % slower; 16 spills),
 // fewer with more rows -- the reads of a phase are 16 bytes per row and position, all held in registers
 constexpr int qs_half(int KF) { return KF <= 2 ? 8 : KF == 3 ? 4 : 2; }
-constexpr float QS_UNITS = 30000.0f;     // where the threshold falls on the 16-bit scale
+constexpr float QS_UNITS = 7500.0f;      // where the threshold falls on the 16-bit scale
+constexpr float QS_CAP = 8000.0f;        // entries stop here (above the threshold): bias + four entries < 65536
+constexpr int QS_BIAS = 32768;           // the first table carries QS_BIAS - (threshold units + 1): bit 15 clear = passes
+static_assert(QS_UNITS + 1.0f < QS_CAP && QS_BIAS + 1 + 4 * (int)QS_CAP < 65536, "sums stay inside 16 bits");
 
 __device__ __forceinline__ uint32_t lane_id() {
     return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
 }
-__device__ __forceinline__ uint32_t pk_add_sat(uint32_t a, uint32_t b) {
-    const short2v r = __builtin_elementwise_add_sat(__builtin_bit_cast(short2v, a), __builtin_bit_cast(short2v, b));
-    return __builtin_bit_cast(uint32_t, r);
-}
-// 1 in each half whose 16-bit value is negative
-__device__ __forceinline__ uint32_t pk_sign(uint32_t x) {
-    const ushort2v r = __builtin_bit_cast(ushort2v, x) >> (ushort2v){15, 15};
-    return __builtin_bit_cast(uint32_t, r);
-}
 // never above the true quotient (x - base) / s: floor, minus one unit for the rounding of the product
 __device__ __forceinline__ int quantise(float x, float base, float inv_s) {
     const float v = floorf((x - base) * inv_s) - 1.0f;
-    return (int)fminf(fmaxf(v, 0.0f), 32000.0f);          // a NaN (inf * 0) ends as 0
+    return (int)fminf(fmaxf(v, 0.0f), QS_CAP);            // a NaN (inf * 0) ends as 0
 }
 
 // KF streamed rows: Kf - 2 (G2: `rows` = the grouped rows, `info` the pairs' labels) or Kf (`rows` =
@@ -65,8 +63,9 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
     const uint8_t *rows, int64_t npad, uint32_t N, const float *__restrict__ lut, int K, const float *__restrict__ thr,
     int Q, uint32_t items_per_block, const uint32_t *__restrict__ info, uint16_t *__restrict__ masks, size_t mask_stride,
     uint32_t scan_end) {
-    // The streamed tables sit at LDS address 0 (no static arrays in this kernel): the table addresses the
-    // inner loop assembles from bytes are then the LDS addresses themselves, with nothing to add.
+    // The streamed tables sit at LDS address 0 (no static arrays in this kernel; the launcher checks that the
+    // kernel's static LDS size is zero): the table addresses the inner loop assembles from bytes are then the
+    // LDS addresses themselves, and the reads take them as such -- nothing to add, not even a zero.
     extern __shared__ __attribute__((aligned(16))) uint4 qs_smem[];
     constexpr int QS_C = qs_copies(KF);
     constexpr int QS_HALF = qs_half(KF);
@@ -141,7 +140,7 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
 #pragma unroll
         for (int b = 0; b < QS_B; ++b) {
             int v = quantise(row_of(b, k)[c], s_min[k][b], s_inv[b]);
-            if (first) v -= s_thr[b] + 1;                   // the threshold rides on the first table: a sum below 0 passes
+            if (first) v += QS_BIAS - (s_thr[b] + 1);       // the threshold rides on the first table: a sum below 32768 passes
             h[b] = (uint32_t)v & 0xFFFFu;
         }
         return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
@@ -162,8 +161,7 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
     uint32_t lane_off[KF];
 #pragma unroll
     for (int k = 0; k < KF; ++k) lane_off[k] = (lane & (QS_C - 1)) * 16u + (uint32_t)k * (ICQ_LUT_W * QS_C * 16);
-    const char *tab_bytes = reinterpret_cast<const char *>(tab);
-    // hit bits of the 1024 positions at g: hm[d] = queries 2d (low half) and 2d + 1, position j in bit 15 - j
+    // hit bits of the 1024 positions at g: hm[d] = queries 2d (low half) and 2d + 1, position j in bit j
     auto hits = [&](uint32_t g, const uint4 (&w)[KF], uint32_t ci, uint32_t (&hm)[QS_B / 2]) {
         uint32_t p01[QS_B / 2];
         bool live[QS_B / 2], any_live = !G2;
@@ -174,24 +172,27 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
         }
         if (G2) {
             const uint4 a = t01[ci & 0xffu], c = t01[ICQ_LUT_W + ((ci >> 8) & 0xffu)];
-            p01[0] = pk_add_sat(a.x, c.x);
-            p01[1] = pk_add_sat(a.y, c.y);
-            p01[2] = pk_add_sat(a.z, c.z);
-            p01[3] = pk_add_sat(a.w, c.w);
-            // the streamed tables add at least 0: a pair of queries whose two sums are not below 0 in any
+            p01[0] = a.x + c.x;
+            p01[1] = a.y + c.y;
+            p01[2] = a.z + c.z;
+            p01[3] = a.w + c.w;
+            // the streamed tables add at least 0: a pair of queries whose two sums have reached 32768 in every
             // lane has no hit among the wavefront's 1024 positions
 #pragma unroll
             for (int d = 0; d < QS_B / 2; ++d) {
-                live[d] = __builtin_amdgcn_ballot_w64((p01[d] & 0x80008000u) != 0u) != 0;   // wavefront-uniform
+                live[d] = __builtin_amdgcn_ballot_w64((~p01[d] & 0x80008000u) != 0u) != 0;  // wavefront-uniform
                 any_live |= live[d];
             }
         }
         if (!any_live) return;
-        uint32_t acc[2][QS_B / 2];                           // positions 0 .. 7 and 8 .. 15: eight bits per half
+        // MISS bits: every position shifts the word right and takes bits 15 and 31 from the two sums (a bit-field
+        // insert: what the shift moved from bit 16 to bit 15 is replaced), so after 16 positions position j sits in
+        // bit j (and 16 + j); a pair that is skipped keeps all ones
+        uint32_t acc[QS_B / 2];
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
-#pragma unroll
-            for (int d = 0; d < QS_B / 2; ++d) acc[x][d] = 0;
+        for (int d = 0; d < QS_B / 2; ++d) acc[d] = 0xFFFFFFFFu;
+        uint32_t top_bits;                                   // in a register: an instruction with a literal issues slower
+        asm volatile("v_mov_b32 %0, 0x80008000" : "=v"(top_bits));
 #pragma unroll
         for (int h = 0; h < 16; h += QS_HALF) {
             uint32_t off[QS_HALF][KF];
@@ -219,7 +220,10 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
             for (int jj = 0; jj < QS_HALF; ++jj)
 #pragma unroll
                 for (int k = 0; k < KF; ++k)
-                    v[jj][k] = *reinterpret_cast<const uint4 *>(tab_bytes + off[jj][k]);
+                {
+                    const u32x4 e = *(const __attribute__((address_space(3))) u32x4 *)(uintptr_t)off[jj][k];   // LDS address = table offset
+                    v[jj][k] = make_uint4(e.x, e.y, e.z, e.w);
+                }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int d = 0; d < QS_B / 2; ++d) {
@@ -230,21 +234,20 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
 #pragma unroll
                     for (int k = 0; k < KF; ++k) {
                         const uint32_t e = d == 0 ? v[jj][k].x : d == 1 ? v[jj][k].y : d == 2 ? v[jj][k].z : v[jj][k].w;
-                        x = (!G2 && k == 0) ? e : pk_add_sat(x, e);      // id order: the first table carries the threshold
+                        x = (!G2 && k == 0) ? e : x + e;                 // id order: the first table carries the threshold
                     }
-                    // one instruction per step (left to itself the compiler regroups the chain into more)
-                    uint32_t &m = acc[(h + jj) >> 3][d];
-                    asm("v_lshl_or_b32 %0, %1, 1, %2" : "=v"(m) : "v"(m), "v"(pk_sign(x)));
+                    // two instructions per step (left to itself the compiler regroups the chain into more)
+                    asm("v_lshrrev_b32 %0, 1, %0\n\tv_bfi_b32 %0, %2, %1, %0" : "+v"(acc[d]) : "v"(x), "v"(top_bits));
                 }
             }
         }
         // the padding behind a pair's last item, and positions at or beyond the end
-        uint32_t valid = G2 ? (0xFFFF0000u >> (ci >> 16)) & 0xFFFFu : 0xFFFFu;
+        uint32_t valid = G2 ? (1u << (ci >> 16)) - 1u : 0xFFFFu;      // the label's count is at most 16
         const uint32_t id0 = g + lane * 16;
-        if (id0 + 16 > end || id0 + 16 < id0) valid &= id0 < end ? 0xFFFFu & ~((1u << (16 - (end - id0))) - 1u) : 0u;
+        if (id0 + 16 > end || id0 + 16 < id0) valid &= id0 < end ? (1u << (end - id0)) - 1u : 0u;
         valid |= valid << 16;
 #pragma unroll
-        for (int d = 0; d < QS_B / 2; ++d) hm[d] = ((acc[0][d] << 8) | acc[1][d]) & valid;
+        for (int d = 0; d < QS_B / 2; ++d) hm[d] = ~acc[d] & valid;
     };
 
     for (uint32_t it = 0; it < nsteps; it += 2, g += 2 * step) {
@@ -259,11 +262,10 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
             if (it + u < nsteps) {
 #pragma unroll
                 for (int d = 0; d < QS_B / 2; ++d) {
-                    const uint32_t r = __builtin_bitreverse32(hm[d]);      // first position in bit 0; the halves change places
                     uint16_t *dst = masks + (size_t)(qbase + 2 * d) * mask_stride + (gu >> 4) + lane;
                     // written once, read once by stage 2: kept out of the caches the code rows are re-read from
-                    if (qbase + 2 * d < Q) __builtin_nontemporal_store((uint16_t)(r >> 16), dst);
-                    if (qbase + 2 * d + 1 < Q) __builtin_nontemporal_store((uint16_t)r, dst + mask_stride);
+                    if (qbase + 2 * d < Q) __builtin_nontemporal_store((uint16_t)hm[d], dst);
+                    if (qbase + 2 * d + 1 < Q) __builtin_nontemporal_store((uint16_t)(hm[d] >> 16), dst + mask_stride);
                 }
             }
         }
@@ -276,6 +278,15 @@ int launch_q16(const icq_index *ix, const float *lut, int Q, const float *thr, u
     const size_t lds = sizeof(uint4) * (size_t)(KF * ICQ_LUT_W * qs_copies(KF) + (G2 ? 2 * ICQ_LUT_W : 0)) +
                        sizeof(float) * ((G2 ? KF + 2 : KF) + 2) * QS_B;
     ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&scan_pairs_q16_kernel<KF, G2>), lds));
+    {   // the kernel reads its tables at absolute LDS addresses: its dynamic LDS must start at 0
+        static int static_lds = -1;                         // same value whoever writes it first
+        if (static_lds < 0) {
+            hipFuncAttributes attr;
+            ICQ_HIP_TRY(hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&scan_pairs_q16_kernel<KF, G2>)));
+            static_lds = (int)attr.sharedSizeBytes;
+        }
+        if (static_lds != 0) return ICQ_ERR_HIP;
+    }
     const int groups = (Q + QS_B - 1) / QS_B;
     const uint32_t step = (uint32_t)QS_WAVES * 1024u;
     // one wave of equally loaded blocks: the chip is filled once and every block streams a long run
