@@ -922,8 +922,8 @@ def main():
                     "traffic": tr["bytes"] if tr else None, "traffic_source": tr["source"] if tr else None,
                     "note": "one launch per icq_search call; duration = the stage-1 event pair inside the one-stream calls "
                             "(counter fill .. after the scan kernel).  achieved = lanes of the vector instructions of the "
-                            "work model (alu_ops; see stage1_model in bench.py: additions, comparison or sign, hit-bit "
-                            "collection, table addresses -- packed 16-bit instructions serve two queries each in the "
+                            "work model (alu_ops; see stage1_model in bench.py: additions, comparison, hit-bit "
+                            "collection, table addresses -- a 32-bit instruction serves two queries' 16-bit sums in the "
                             "16-bit pre-filter) per second; peak = 256 CU x 4 SIMD x 16 lanes x 2.4 GHz.  lds / hbm: the same launch against the other two resources "
                             "(LDS: lane addresses against the 7.72e12 per second measured for 16-byte reads; HBM: code "
                             "rows per pass plus the hit bits written -- all passes but the first are served by the caches, "
