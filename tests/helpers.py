@@ -80,9 +80,16 @@ def check_topk(P_q, D_q, t, topk, out_ids, out_dist):
         need = sure[D_q[sure] < Dk_all - tol(Dk_all)]
         missing = np.setdiff1d(need, ids)
         assert missing.size == 0, "clearly-closer survivor missing: %s" % missing[:8]
-    else:
+    elif maybe.size <= topk:
         missing = np.setdiff1d(sure, ids)
         assert missing.size == 0, "survivor missing from a short result"
+    else:
+        # fewer certain survivors than topk, but with the band items more than topk: the band items that
+        # survive can fill the list and push the farthest certain survivors out
+        Dk_all = np.partition(D_q[maybe], topk - 1)[topk - 1]
+        need = sure[D_q[sure] < Dk_all - tol(Dk_all)]
+        missing = np.setdiff1d(need, ids)
+        assert missing.size == 0, "clearly-closer survivor missing: %s" % missing[:8]
 
 
 def tiled_loop_analysis(P_q, D_q, sigma, topk, bounds, band):

@@ -1176,6 +1176,51 @@ def test_search_sweep_against_oracle(gpu, case):
     _check_search(g, cfg, T, P, D, thr, topk, N + 1)
 
 
+def _hit_bit_cases():
+    rng = np.random.default_rng(20241)
+    cases = []
+    for i in range(14):
+        K = int(rng.choice([4, 5, 8, 12, 16]))
+        Kf = int(rng.integers(1, 5))
+        m = int(rng.choice([256, 256, 100]))
+        big = i % 3 == 0                      # from 2^22 items on: also the pair ordering (Kf = 3, 4), any six queries
+        N = int(rng.choice([4_200_000, 4_456_449]) if big else rng.choice([524_288, 530_001, 1_048_577, 1_300_000]))
+        Q = int(rng.choice([6, 9, 16, 33]) if big else rng.choice([32, 40, 65]))
+        topk = int(rng.choice([1, 10, 100, 257]))
+        fracs = [float(f) for f in rng.choice([0.0005, 0.002, 0.01, 0.1, 0.5], size=2, replace=False)]
+        # Kf <= 2: the tuple walk would take the call otherwise; large and Kf = 3, 4: mostly the pair ordering
+        mode = 1 if Kf <= 2 else (int(i % 12 != 6) ^ 1 if big else int(rng.choice([0, 1])))
+        cases.append((i, K, Kf, m, N, Q, topk, fracs, mode))
+    return cases
+
+
+@pytest.mark.parametrize("case", _hit_bit_cases(), ids=lambda c: "h%02d-K%d-Kf%d-m%d-N%d-Q%d-k%d-mode%d" % (
+    c[0], c[1], c[2], c[3], c[4], c[5], c[6], c[8]))
+def test_search_sweep_over_hit_bits(gpu, case):
+    """Shapes drawn from a fixed seed at sizes where icq_search keeps hit bits and stage 1 is the 16-bit
+    pre-filter: every Kf from 1 to 4 in id order, Kf = 3, 4 over the pair ordering, short codebooks (table
+    entries at +inf), ragged N, query counts around the pass width of eight, and per query a threshold
+    from a mix of quantiles (a sparse and a dense one per case), +inf and -inf."""
+    i, K, Kf, m, N, Q, topk, fracs, mode = case
+    rng = np.random.default_rng(3000 + i)
+    d = 16
+    cb = (rng.standard_normal((K, m, d)) * (0.8 ** np.arange(K))[:, None, None]).astype(np.float32)
+    codes = rng.integers(0, m, size=(K, N), dtype=np.uint8)
+    src = rng.integers(0, N, size=Q)
+    queries = sum(cb[k][codes[k, src]] for k in range(K)) + 0.2 * rng.standard_normal((Q, d))
+    cfg = dict(codebooks=cb, codes=codes, queries=np.ascontiguousarray(queries, dtype=np.float32),
+               K=K, Kf=Kf, d=d, N=N, Q=Q, topk=topk)
+    g = Gpu(gpu, cfg, mode)
+    T, P, D = oracle_all(cfg)
+    thr = np.empty(Q, dtype=np.float32)
+    for q in range(Q):
+        thr[q] = np.quantile(P[q], fracs[q % 2])
+    thr[Q - 1] = np.inf
+    thr[Q - 2] = -np.inf
+    exact = (P < thr[:, None].astype(np.float64)).sum(axis=1)
+    _check_search(g, cfg, T, P, D, thr, topk, int(exact.max()) + 64, min_equal=0.8)
+
+
 # ------------------------------------------------------------------ HIP graphs
 @pytest.mark.parametrize("name,N,Q,over", [("C0", 10_000, 100, {}), ("C1", 200_003, 130, {}), ("C4", 4_300_017, 16, dict(K=12))],
                          ids=["tuples-Kf1", "tuples-Kf2", "pairs-hit-bits"])
