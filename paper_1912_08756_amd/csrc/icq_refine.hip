@@ -902,7 +902,8 @@ int icq_launch_refine_masks(const icq_index *ix, const float *lut, int Q, const 
         select_keys_kernel<<<grid_sel, SK_THREADS, (sizeof(u64) + sizeof(uint32_t)) * listcap, s>>>(
             cand_keys, key_count, cap, topk, listcap, splits, keys, out_ids, out_dist);
         if (icq_check_launch() != ICQ_OK) return ICQ_ERR_HIP;
-        if (splits > 1) return icq_launch_merge(keys, Q, splits, topk, false, out_ids, out_dist, s);
+        // every slice comes out of the selection ascending, and a position -- hence an id -- has one key
+        if (splits > 1) return icq_launch_merge(keys, Q, splits, topk, true, out_ids, out_dist, s);
         return ICQ_OK;
     };
     // Chunks per block: few, so that the blocks in flight (two windows' worth when the queries fill the
