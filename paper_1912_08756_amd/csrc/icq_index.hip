@@ -76,7 +76,7 @@ int item_stride_for(int K) {
 
 }  // namespace
 
-hipError_t icq_allow_lds(const void *fn, int bytes) {
+hipError_t icq_allow_lds(const void *fn, int bytes, bool no_static_lds) {
     static std::mutex mu;
     static std::set<std::pair<int, const void *>> done;
     int dev = 0;
@@ -84,6 +84,12 @@ hipError_t icq_allow_lds(const void *fn, int bytes) {
     if (e != hipSuccess) return e;
     std::lock_guard<std::mutex> lock(mu);
     if (done.count({dev, fn})) return hipSuccess;
+    if (no_static_lds) {
+        hipFuncAttributes attr;
+        e = hipFuncGetAttributes(&attr, fn);
+        if (e != hipSuccess) return e;
+        if (attr.sharedSizeBytes != 0) return hipErrorInvalidValue;
+    }
     e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e == hipSuccess) done.insert({dev, fn});
     return e;

@@ -66,7 +66,8 @@ int icq_group2_build(icq_index *ix, hipStream_t s);
 int icq_group2_export(const icq_index *ix, uint8_t *codes_out, hipStream_t s);
 
 // hipFuncSetAttribute(fn, MaxDynamicSharedMemorySize, bytes), once per (device, kernel); thread-safe.
-hipError_t icq_allow_lds(const void *fn, int bytes);
+// no_static_lds: also refuse (hipErrorInvalidValue) a kernel whose code object holds static LDS.
+hipError_t icq_allow_lds(const void *fn, int bytes, bool no_static_lds = false);
 
 // What a candidate list holds.
 enum icq_list_kind {

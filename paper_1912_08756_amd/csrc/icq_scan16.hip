@@ -277,16 +277,8 @@ int launch_q16(const icq_index *ix, const float *lut, int Q, const float *thr, u
                int64_t scan_end, hipStream_t s) {
     const size_t lds = sizeof(uint4) * (size_t)(KF * ICQ_LUT_W * qs_copies(KF) + (G2 ? 2 * ICQ_LUT_W : 0)) +
                        sizeof(float) * ((G2 ? KF + 2 : KF) + 2) * QS_B;
-    ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&scan_pairs_q16_kernel<KF, G2>), lds));
-    {   // the kernel reads its tables at absolute LDS addresses: its dynamic LDS must start at 0
-        static int static_lds = -1;                         // same value whoever writes it first
-        if (static_lds < 0) {
-            hipFuncAttributes attr;
-            ICQ_HIP_TRY(hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&scan_pairs_q16_kernel<KF, G2>)));
-            static_lds = (int)attr.sharedSizeBytes;
-        }
-        if (static_lds != 0) return ICQ_ERR_HIP;
-    }
+    // the kernel reads its tables at absolute LDS addresses: its dynamic LDS must start at 0 (no static LDS)
+    ICQ_HIP_TRY(icq_allow_lds(reinterpret_cast<const void *>(&scan_pairs_q16_kernel<KF, G2>), lds, true));
     const int groups = (Q + QS_B - 1) / QS_B;
     const uint32_t step = (uint32_t)QS_WAVES * 1024u;
     // one wave of equally loaded blocks: the chip is filled once and every block streams a long run
