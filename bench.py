@@ -720,17 +720,19 @@ def stage1_model(Kf, npos, Qb, pairs, q16=False):
     per 16 positions (not counted) and is one more addition per (query, position).
     q16 (the 16-bit pre-filter, eight queries per pass): a 32-bit instruction serves two queries,
     so per position and pass there are one address per streamed row, and per PAIR of queries the
-    additions (two of them fold into one three-operand instruction), one shift and one bit-field
-    insert that collect the two miss bits; per 16 positions and pass about 40 more (the pair's
-    part of the sum, the tests that let a pair of queries sit a step out, masks, stores).
+    additions (two of them fold into one three-operand instruction) and, per TWO positions, one
+    byte permute, one shift and one bit-field insert that collect the four miss bits; per 16
+    positions and pass about 40 more (the pair's part of the sum, the tests that let a pair of
+    queries sit a step out, masks, stores).
     alu_ops counts lanes of wavefront instructions either way."""
     R = Kf - 2 if pairs else Kf
     if q16:
         passes = (Qb + 7) // 8
         addr = R if R <= 2 else 2 * R          # one byte permute per address with 16 table copies, extract + shift-add with 8
-        per_pair = ((R if pairs else R - 1) + 1) // 2 + 2  # additions (two per instruction), shift, bit-field insert
+        # per query pair and TWO positions: the additions of both (two per instruction), permute, shift, insert
+        per_pair2 = 2 * (((R if pairs else R - 1) + 1) // 2) + 3
         return {"positions": npos, "queries": Qb, "passes": passes, "streamed_rows": R,
-                "alu_ops": npos * passes * (addr + 4 * per_pair) + npos // 16 * passes * (40 if pairs else 24),
+                "alu_ops": npos * passes * addr + npos // 2 * passes * 4 * per_pair2 + npos // 16 * passes * (40 if pairs else 24),
                 "lds_addresses": npos * passes * R,
                 "table_entries": npos * Qb * R,
                 "code_bytes": npos * passes * R + npos * passes // 4,

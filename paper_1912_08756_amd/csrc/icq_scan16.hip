@@ -39,7 +39,7 @@ constexpr int QS_B = 8;                  // queries per pass
 constexpr int qs_copies(int KF) { return KF <= 2 ? 16 : 8; }
 // positions whose table reads are issued together: 8 with one or two streamed rows (4: 3 % slower; 16 spills),
 // fewer with more rows -- the reads of a phase are 16 bytes per row and position, all held in registers
-constexpr int qs_half(int KF) { return KF <= 2 ? 8 : KF == 3 ? 4 : 2; }
+constexpr int qs_half(int KF) { return KF <= 2 ? 8 : KF == 3 ? 4 : 2; }   // even: positions come in pairs (j, j + 8)
 constexpr float QS_UNITS = 7500.0f;      // where the threshold falls on the 16-bit scale
 constexpr float QS_CAP = 8000.0f;        // entries stop here (above the threshold): bias + four entries < 65536
 constexpr int QS_BIAS = 32768;           // the first table carries QS_BIAS - (threshold units + 1): bit 15 clear = passes
@@ -185,20 +185,23 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
             }
         }
         if (!any_live) return;
-        // MISS bits: every position shifts the word right and takes bits 15 and 31 from the two sums (a bit-field
-        // insert: what the shift moved from bit 16 to bit 15 is replaced), so after 16 positions position j sits in
-        // bit j (and 16 + j); a pair that is skipped keeps all ones
+        // MISS bits, positions j and j + 8 together: one byte permute brings the top bytes of their two sums (two
+        // queries each) side by side -- low query: bytes 0 (j) and 1 (j + 8), high query: bytes 2 and 3 -- and every
+        // such step shifts the collecting word right and takes bit 7 of each byte from them (a bit-field insert:
+        // what the shift moved into those bits from the byte above is replaced).  After the eight steps j = 0 .. 7
+        // position p sits in bit p (and 16 + p).  A pair of queries that is skipped keeps all ones.
         uint32_t acc[QS_B / 2];
 #pragma unroll
         for (int d = 0; d < QS_B / 2; ++d) acc[d] = 0xFFFFFFFFu;
         uint32_t top_bits;                                   // in a register: an instruction with a literal issues slower
-        asm volatile("v_mov_b32 %0, 0x80008000" : "=v"(top_bits));
+        asm volatile("v_mov_b32 %0, 0x80808080" : "=v"(top_bits));
 #pragma unroll
         for (int h = 0; h < 16; h += QS_HALF) {
+            // the phase's positions: j = h / 2 .. h / 2 + QS_HALF / 2 - 1 (even jj) and their partners j + 8 (odd jj)
             uint32_t off[QS_HALF][KF];
 #pragma unroll
             for (int jj = 0; jj < QS_HALF; ++jj) {
-                const int j = h + jj;
+                const int j = h / 2 + (jj >> 1) + 8 * (jj & 1);
 #pragma unroll
                 for (int k = 0; k < KF; ++k) {
                     const uint32_t word = j < 4 ? w[k].x : j < 8 ? w[k].y : j < 12 ? w[k].z : w[k].w;
@@ -229,15 +232,22 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
             for (int d = 0; d < QS_B / 2; ++d) {
                 if (!live[d]) continue;                      // wavefront-uniform
 #pragma unroll
-                for (int jj = 0; jj < QS_HALF; ++jj) {
-                    uint32_t x = p01[d];
+                for (int jj = 0; jj < QS_HALF; jj += 2) {
+                    uint32_t x[2];
 #pragma unroll
-                    for (int k = 0; k < KF; ++k) {
-                        const uint32_t e = d == 0 ? v[jj][k].x : d == 1 ? v[jj][k].y : d == 2 ? v[jj][k].z : v[jj][k].w;
-                        x = (!G2 && k == 0) ? e : x + e;                 // id order: the first table carries the threshold
+                    for (int u = 0; u < 2; ++u) {
+                        x[u] = p01[d];
+#pragma unroll
+                        for (int k = 0; k < KF; ++k) {
+                            const uint4 &t = v[jj + u][k];
+                            const uint32_t e = d == 0 ? t.x : d == 1 ? t.y : d == 2 ? t.z : t.w;
+                            x[u] = (!G2 && k == 0) ? e : x[u] + e;       // id order: the first table carries the threshold
+                        }
                     }
+                    // bytes 1 and 3 of both sums: x[0] (position j) to bytes 0 and 2, x[1] (position j + 8) to bytes 1 and 3
+                    const uint32_t tops = __builtin_amdgcn_perm(x[1], x[0], 0x07030501u);
                     // two instructions per step (left to itself the compiler regroups the chain into more)
-                    asm("v_lshrrev_b32 %0, 1, %0\n\tv_bfi_b32 %0, %2, %1, %0" : "+v"(acc[d]) : "v"(x), "v"(top_bits));
+                    asm("v_lshrrev_b32 %0, 1, %0\n\tv_bfi_b32 %0, %2, %1, %0" : "+v"(acc[d]) : "v"(tops), "v"(top_bits));
                 }
             }
         }
