@@ -915,6 +915,12 @@ def main():
         roofline = {"bound": "alu", "kernel": kern1, "achieved": round(ach, 3), "peak": round(ALU_PEAK_TOPS, 2),
                     "unit": "Tops/s", "frac": round(ach / ALU_PEAK_TOPS, 4), "ms": round(stage[1], 4),
                     "work_model": m,
+                    # Eq. 2 as written: Kf - 1 additions and one comparison per (query, item).  The kernel needs fewer
+                    # instructions than that (two queries per 32-bit instruction, the first two terms once per run of
+                    # items), so this rate can exceed the vector peak; it does not depend on how the kernel is written.
+                    "eq2": {"ops_per_launch": int(N) * int(round(qmean)) * Kf,
+                            "Tops_per_s": round(N * qmean * Kf / t / 1e12, 2),
+                            "vs_vector_peak": round(N * qmean * Kf / t / 1e12 / ALU_PEAK_TOPS, 3)},
                     "lds": {"achieved_Gaddr_s": round(m["lds_addresses"] / t / 1e9, 1), "peak_Gaddr_s": LDS_PEAK_GADDR,
                             "frac": round(m["lds_addresses"] / t / 1e9 / LDS_PEAK_GADDR, 4),
                             "table_entries_per_s": round(m["table_entries"] / t, 1)},
