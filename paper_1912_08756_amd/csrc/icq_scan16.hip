@@ -7,7 +7,7 @@
 // is in hand anyway -- by the kernel that forms the exact distance, from the same fp32 additions.
 // What this kernel leaves is a SUPERSET of the survivors, found with a quarter of the work per
 // (query, position): every fast table is replaced by
-//     q_k[c] = max(0, floor((T_k[c] - min T_k) / s) - 1)        (16-bit, never above the true quotient)
+//     q_k[c] = min(8000, max(0, floor((T_k[c] - min T_k) / s) - 1))   (16-bit, never above the true quotient)
 // with one scale s per query chosen so that the threshold falls at 7500 units, and an item passes
 // when  q_0 + q_1 + q_2 (+ q_3) <= floor((t - sum_k min T_k) / s) + 1.  Rounding down every term
 // and up the right side cannot lose a survivor (the slack of one unit per term also covers the
@@ -18,9 +18,9 @@
 // instruction: entries stop at 8000 units and the first table carries 32768 - (threshold units + 1),
 // so a sum of up to four entries stays inside its 16 bits -- the two halves of a word are added by
 // ONE plain 32-bit addition with no carry between them -- and bit 15 of a half is clear exactly when
-// the sum is at or below the threshold's units.  Plain two-operand additions issue almost twice as
-// often as the packed 16-bit forms.  The byte extraction and table address of a position serve
-// eight queries instead of four.
+// the sum is at or below the threshold's units (an entry stopped at 8000 units is beyond the threshold
+// by itself).  The miss bits of two positions are collected by one byte permute, one shift and one
+// bit-field insert.  The byte extraction and table address of a position serve eight queries.
 #include "icq_internal.h"
 #include "icq_sort.h"
 
