@@ -561,7 +561,7 @@ static_assert(RM_CHUNK <= 65536, "the position lists hold 16-bit offsets into th
 template <int WORDS, bool FILTER, int QPB, bool EXACT>
 __global__ __launch_bounds__(RM_THREADS, FILTER ? 5 : 1) void refine_mask_kernel(
     const uint8_t *__restrict__ items, int K, const float *__restrict__ lut, const uint32_t *__restrict__ masks,
-    size_t mask_words, const uint32_t *__restrict__ perm, uint32_t nsel, uint32_t seed_every, int window, int Q,
+    size_t mask_words, const uint32_t *__restrict__ perm, uint32_t nsel, uint32_t seed_every, int window, int xs_shift, int Q,
     const float *__restrict__ kth_dist, int topk, u64 *__restrict__ keys, uint32_t *__restrict__ key_count,
     int64_t cap, uint32_t *__restrict__ cand_count, const float *__restrict__ thr, int Kf) {
     __shared__ __attribute__((aligned(16))) float T_all[QPB][4 * WORDS * ICQ_LUT_W];
@@ -572,13 +572,14 @@ __global__ __launch_bounds__(RM_THREADS, FILTER ? 5 : 1) void refine_mask_kernel
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     uint16_t *cand = cand_all[wave];
     // block -> (window, query group, XCD): chunks i = (win * window + j) * 8 + xcd, j = 0 .. window - 1, of this
-    // launch's; wavefront w takes j = w, w + 4, ..
+    // launch's; wavefront w takes j = w, w + 4, ..  (An index of few chunks is cut 2^xs_shift < 8 ways instead, so
+    // that a block still has a window's worth of chunks for the tables it loads.)
     const uint32_t ngroups = ((uint32_t)Q + QPB - 1) / QPB;
-    const uint32_t xcd = blockIdx.x & 7u, rest = blockIdx.x >> 3;
+    const uint32_t xcd = blockIdx.x & ((1u << xs_shift) - 1u), rest = blockIdx.x >> xs_shift;
     const uint32_t q0 = (rest % ngroups) * QPB, win = rest / ngroups;
     const uint32_t nq = (uint32_t)Q - q0 < (uint32_t)QPB ? (uint32_t)Q - q0 : (uint32_t)QPB;
     auto chunk_of = [&](uint32_t j) -> uint32_t {
-        const uint32_t i = (win * (uint32_t)window + j) * 8u + xcd;
+        const uint32_t i = ((win * (uint32_t)window + j) << xs_shift) + xcd;
         if (j >= (uint32_t)window || i >= nsel) return 0xFFFFFFFFu;
         return FILTER ? i + i / (seed_every - 1u) + 1u : i * seed_every;   // the others : every seed_every-th
     };
@@ -908,26 +909,35 @@ int icq_launch_refine_masks(const icq_index *ix, const float *lut, int Q, const 
     };
     // Chunks per block: few, so that the blocks in flight (two windows' worth when the queries fill the
     // chip) keep to a few chunks per XCD; more when there are so few queries that the table load would weigh.
-    auto window_for = [&](uint32_t nsel, bool filtered) -> int {
+    // An unfiltered launch with little work for the chip (the first part of a large index: one chunk per
+    // wavefront is all the parallelism there is) is spread over as many blocks as possible; one that is the
+    // whole stage (a small index, many queries) takes full windows, and the chunks are cut fewer than 8
+    // ways when 8 windows' worth do not exist: 16 MB of records stay in the caches wherever the blocks run.
+    auto plan_for = [&](uint32_t nsel, bool filtered, int *xs_shift) -> int {
         int w = Q >= 8 && !g2 ? 8 : 16;
-        if (!filtered && Q >= 8) w = 4;               // the unfiltered part is short: spread it over more blocks               // grouped order: a query's survivors sit in runs, the walk depends less on the cache
-        const int most = (int)((nsel + 7) / 8);
+        if (!filtered && Q >= 8) w = (uint64_t)nsel * (uint64_t)Q <= 16384u ? 4 : 16;
+        int shift = 3;
+        while (shift > 0 && ((uint32_t)w << shift) > nsel) --shift;
+        *xs_shift = shift;
+        const int most = (int)((nsel + (1u << shift) - 1) >> shift);
         return w < most ? w : (most > 0 ? most : 1);
     };
     const size_t mask_words = mask_stride / 2;
     const uint32_t *m32 = reinterpret_cast<const uint32_t *>(masks);
 #define ICQ_RM_LAUNCH(W, FILTER, NSEL)                                                                       \
     do {                                                                                                     \
-        const int window = window_for(NSEL, FILTER);                                                               \
-        const unsigned nwin = ((NSEL) + 8u * window - 1) / (8u * window);                                    \
+        int xs_shift = 3;                                                                                    \
+        const int window = plan_for(NSEL, FILTER, &xs_shift);                                                \
+        const unsigned per_win = (unsigned)window << xs_shift;                                               \
+        const unsigned nwin = ((NSEL) + per_win - 1) / per_win;                                              \
         const unsigned ngroups = ((unsigned)Q + RM_QPB - 1) / RM_QPB;                                        \
         if (thr)                                                                                             \
-            refine_mask_kernel<W, FILTER, RM_QPB, true><<<nwin * ngroups * 8u, RM_THREADS, 0, s>>>(           \
-                items, ix->K, lut, m32, mask_words, perm, (NSEL), seed_every, window, Q, out_dist, topk,     \
+            refine_mask_kernel<W, FILTER, RM_QPB, true><<<(nwin * ngroups) << xs_shift, RM_THREADS, 0, s>>>(           \
+                items, ix->K, lut, m32, mask_words, perm, (NSEL), seed_every, window, xs_shift, Q, out_dist, topk,     \
                 cand_keys, key_count, cap, cand_count, thr, ix->Kf);                                         \
         else                                                                                                 \
-            refine_mask_kernel<W, FILTER, RM_QPB, false><<<nwin * ngroups * 8u, RM_THREADS, 0, s>>>(          \
-                items, ix->K, lut, m32, mask_words, perm, (NSEL), seed_every, window, Q, out_dist, topk,     \
+            refine_mask_kernel<W, FILTER, RM_QPB, false><<<(nwin * ngroups) << xs_shift, RM_THREADS, 0, s>>>(          \
+                items, ix->K, lut, m32, mask_words, perm, (NSEL), seed_every, window, xs_shift, Q, out_dist, topk,     \
                 cand_keys, key_count, cap, cand_count, nullptr, ix->Kf);                                     \
     } while (0)
     switch (ix->item_stride) {
