@@ -979,6 +979,12 @@ def main():
                     "survivors x record + hit bits (or ids) + tables + result rows.  A random 16-byte gather moves a "
                     "whole cache line, so the traffic is a multiple of the algorithmic bytes unless the line is "
                     "reused from the cache by the batch's other queries"}
+        # `roofline` is the stage that takes longer between the library's events; the other keeps its own key
+        result["roofline_stage1"] = roofline
+        if stage[2] > stage[1]:
+            result["roofline"] = dict(result["roofline_stage2"])
+            result["roofline"]["why_this_one"] = ("stage 2 takes %.3f ms of the call, stage 1 %.3f (roofline_stage1: bound "
+                                                  "by the vector ALUs)" % (stage[2], stage[1]))
 
     if not args.no_streamed_leg:
         # The same step with stage 1 walking all Kf fast rows item by item (what an index without the
