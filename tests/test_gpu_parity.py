@@ -1221,6 +1221,46 @@ def test_search_sweep_over_hit_bits(gpu, case):
     _check_search(g, cfg, T, P, D, thr, topk, int(exact.max()) + 64, min_equal=0.8)
 
 
+def test_search_calls_overlapping_on_two_streams(gpu):
+    """The configuration the benchmark times: the batches of a query set alternate between two streams, each with
+    a workspace of its own, on ONE index, so that one batch's stage 2 runs beside the next batch's stage 1.  The
+    lists must be those of the same calls made one after the other, and those the oracle accepts."""
+    torch, b = gpu
+    cfg = small("C4", 4_300_017, 96, K=12)
+    Q, topk, batch = 96, 100, 16
+    T, P, D = oracle_all(cfg)
+    thr = thresholds_quantile(P, 0.01)
+    g = Gpu(gpu, cfg, 0)
+    cap = int((P < thr[:, None].astype(np.float64)).sum(axis=1).max() * 1.2) + 64
+    thr_dev = _dev(torch, thr)
+    one = g.search(thr, cap, topk)
+    out_ids = torch.full((Q, topk), -1, dtype=torch.int32, device="cuda")
+    out_dist = torch.full((Q, topk), float("nan"), dtype=torch.float32, device="cuda")
+    surv = torch.full((Q,), 12345, dtype=torch.int32, device="cuda")
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    wss = [g.workspace(batch, cap, topk), g.workspace(batch, cap, topk)]
+    torch.cuda.synchronize()
+    for rep in range(3):                                   # the same overlap three times over: no state carried along
+        cur = torch.cuda.current_stream()
+        for st in streams:
+            st.wait_stream(cur)
+        for i, q0 in enumerate(range(0, Q, batch)):
+            with torch.cuda.stream(streams[i % 2]):
+                b.icq_search(g.index, g.queries[q0:q0 + batch], thr_dev[q0:q0 + batch], cap, topk,
+                             out_ids[q0:q0 + batch], out_dist[q0:q0 + batch], surv[q0:q0 + batch], wss[i % 2])
+        for st in streams:
+            cur.wait_stream(st)
+        torch.cuda.synchronize()
+        assert np.array_equal(_u32(out_ids), one[0]) and np.array_equal(out_dist.cpu().numpy(), one[1])
+        assert np.array_equal(_u32(surv), one[2])
+        out_ids.fill_(-1)
+        out_dist.fill_(float("nan"))
+    o_ids = orc.search(T, cfg["codes"], cfg["Kf"], thr, topk)[0]
+    for q in range(Q):
+        check_topk(P[q], D[q], thr[q], topk, one[0][q], one[1][q])
+    assert (one[0] == o_ids).all(axis=1).mean() >= 0.9
+
+
 # ------------------------------------------------------------------ HIP graphs
 @pytest.mark.parametrize("name,N,Q,over", [("C0", 10_000, 100, {}), ("C1", 200_003, 130, {}), ("C4", 4_300_017, 16, dict(K=12))],
                          ids=["tuples-Kf1", "tuples-Kf2", "pairs-hit-bits"])
