@@ -17,8 +17,8 @@
  *    its own counting pass before it sizes the grouped layouts).  Calls on one
  *    index from several host threads, or on several streams, are safe as long
  *    as they do not share output or workspace buffers (with stage timing off):
- *    searches of different query batches on two streams overlap, one batch's
- *    exact comparisons running beside the next batch's crude ones.
+ *    searches of different query batches on two streams overlap -- the short
+ *    kernels of one call run behind the long ones of the other.
  *  - Return value: ICQ_OK (0) or a negative ICQ_ERR_* code.  Arguments are
  *    checked on the host before anything is launched; an argument or
  *    workspace error means nothing has been enqueued (ICQ_ERR_HIP can come from
