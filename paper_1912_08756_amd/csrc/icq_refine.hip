@@ -914,7 +914,7 @@ int icq_launch_refine_masks(const icq_index *ix, const float *lut, int Q, const 
     // whole stage (a small index, many queries) takes full windows, and the chunks are cut fewer than 8
     // ways when 8 windows' worth do not exist: 16 MB of records stay in the caches wherever the blocks run.
     auto plan_for = [&](uint32_t nsel, bool filtered, int *xs_shift) -> int {
-        int w = Q >= 8 && !g2 ? 8 : 16;
+        int w = Q >= 8 ? (g2 ? 12 : 8) : 16;          // at N = 1e8, 128 queries, pair ordering: 16 / 12 / 8 / 6 / 4: 1.105 / 1.090 / 1.109 / 1.18 / 1.31 ms
         if (!filtered && Q >= 8) w = (uint64_t)nsel * (uint64_t)Q <= 16384u ? 4 : 16;
         // (with thousands of queries a window's blocks no longer run at the same time, and the 8-way cut that
         // keeps a chunk's records in ONE L2 is worth more than the longer windows: 1e4 queries, 1e6 items,
