@@ -56,7 +56,7 @@ __device__ __forceinline__ int quantise(float x, float base, float inv_s) {
 
 // KF streamed rows: Kf - 2 (G2: `rows` = the grouped rows, `info` the pairs' labels) or Kf (`rows` =
 // the fast rows in id order).  Grid: x = ranges of scan positions, y = groups of eight queries.
-// masks[q * mask_stride + p / 16] receives the hit bits of positions p .. p + 15 (bit j = position
+// masks (rows for ceil(Q / 8) * 8 queries) [q * mask_stride + p / 16] receives the hit bits of positions p .. p + 15 (bit j = position
 // p + j) for every position of the block's range below scan_end, zeros beyond the last item.
 template <int KF, bool G2>
 __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
@@ -272,10 +272,12 @@ __global__ __launch_bounds__(QS_THREADS) void scan_pairs_q16_kernel(
             if (it + u < nsteps) {
 #pragma unroll
                 for (int d = 0; d < QS_B / 2; ++d) {
-                    uint16_t *dst = masks + (size_t)(qbase + 2 * d) * mask_stride + (gu >> 4) + lane;
+                    // the wavefront's row piece (uniform), lane l's word behind it.  Slots past the last query have
+                    // rows too (the caller sizes the bits for whole groups of eight) and get zeros: no conditions.
+                    uint16_t *row = masks + (size_t)(qbase + 2 * d) * mask_stride + (gu >> 4);
                     // written once, read once by stage 2: kept out of the caches the code rows are re-read from
-                    if (qbase + 2 * d < Q) __builtin_nontemporal_store((uint16_t)hm[d], dst);
-                    if (qbase + 2 * d + 1 < Q) __builtin_nontemporal_store((uint16_t)(hm[d] >> 16), dst + mask_stride);
+                    __builtin_nontemporal_store((uint16_t)hm[d], row + lane);
+                    __builtin_nontemporal_store((uint16_t)(hm[d] >> 16), row + mask_stride + lane);
                 }
             }
         }

@@ -21,7 +21,8 @@ icq_ws_layout icq_layout(const icq_index *ix, int Q, int64_t cap, int topk, bool
     if (L.masked) {
         L.scan_end = icq_mask_scan_end(ix);
         L.mask_stride = (size_t)(L.scan_end / 16);
-        off = icq_align_up(off + sizeof(uint16_t) * (size_t)Q * L.mask_stride, ICQ_ALIGN);
+        // rows for whole groups of eight queries: the pre-filter kernel stores all eight slots of its last group
+        off = icq_align_up(off + sizeof(uint16_t) * (size_t)((Q + 7) / 8 * 8) * L.mask_stride, ICQ_ALIGN);
         L.keycount_off = off;
         off = icq_align_up(off + sizeof(uint32_t) * (size_t)Q, ICQ_ALIGN);
     } else if (with_cands && !on_chip) {
