@@ -722,7 +722,7 @@ def stage1_model(Kf, npos, Qb, pairs, q16=False):
     so per position and pass there are one address per streamed row, and per PAIR of queries the
     additions (two of them fold into one three-operand instruction) and, per TWO positions, one
     byte permute, one shift and one bit-field insert that collect the four miss bits; per 16
-    positions and pass about 40 more (the pair's part of the sum, the tests that let a pair of
+    positions and pass about 26 more (the pair's part of the sum, the tests that let a pair of
     queries sit a step out, masks, stores).
     alu_ops counts lanes of wavefront instructions either way."""
     R = Kf - 2 if pairs else Kf
@@ -732,7 +732,7 @@ def stage1_model(Kf, npos, Qb, pairs, q16=False):
         # per query pair and TWO positions: the additions of both (two per instruction), permute, shift, insert
         per_pair2 = 2 * (((R if pairs else R - 1) + 1) // 2) + 3
         return {"positions": npos, "queries": Qb, "passes": passes, "streamed_rows": R,
-                "alu_ops": npos * passes * addr + npos // 2 * passes * 4 * per_pair2 + npos // 16 * passes * (40 if pairs else 24),
+                "alu_ops": npos * passes * addr + npos // 2 * passes * 4 * per_pair2 + npos // 16 * passes * (26 if pairs else 24),
                 "lds_addresses": npos * passes * R,
                 "table_entries": npos * Qb * R,
                 "code_bytes": npos * passes * R + npos * passes // 4,
